@@ -1,0 +1,273 @@
+/*
+ * sar_mi355x.h -- C ABI of the SAR aggregation hot path for AMD MI355X (gfx950).
+ *
+ * What the library computes (arXiv 2111.06483): one worker p's sequential
+ * aggregation of its destination partition V_p over P source-partition edge
+ * blocks G_{p,q} (Sec. 3.2, Alg. 1), the per-block backward of Alg. 2, with
+ *   - sum / mean aggregation of neighbour features (Eq. 2),
+ *   - the fused, rematerialising attention kernels of Sec. 3.3 for GAT
+ *     (Eq. 3) using the running-maximum incremental softmax of Sec. 3.4,
+ *   - the node-wise transform z = W h of Eq. 1, written row-major as Z = X W.
+ *
+ * Conventions that hold for every call
+ *   - Every function returns 0 (SAR_OK) or a negative sar_status.  The text of
+ *     the most recent failure on the calling thread: sar_last_error().
+ *     No C++ exception crosses this boundary.
+ *   - Unless a parameter says "host", every pointer is a DEVICE pointer on the
+ *     current HIP device, allocated and owned by the caller.  The library keeps
+ *     no reference to caller memory after a call returns, except that a handle
+ *     made by sar_blocks_wrap() borrows the CSR arrays it was given.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Compute calls only enqueue work on it and return; they do not
+ *     synchronise.  sar_blocks_build / sar_blocks_wrap allocate device memory
+ *     and synchronise the stream before returning.
+ *   - An edge j->i carries a message from source j to destination i.  Rows of
+ *     a block are destinations (ids local to V_p), columns are sources (ids
+ *     local to V_q).  Local id = rank of the global id among the nodes of the
+ *     same partition, ascending.
+ *   - Feature tensors are row-major [n, H, D] (F = H*D contiguous values per
+ *     node; heads are independent and concatenated).  `dtype` selects their
+ *     storage: SAR_F32 or SAR_BF16 (round-to-nearest-even on store).  All
+ *     running state, scores, log-sum-exps and parameter gradients are fp32 and
+ *     all accumulation is fp32.
+ *   - a_r multiplies the destination's z_i and a_l the source's z_j: the vector
+ *     a of Eq. 3 is [a_r ; a_l] in the order the equation writes z_i || z_j.
+ *   - Supported shapes for the gather kernels: F*sizeof(element) <= 1024 bytes
+ *     per row, D a multiple of 4 (fp32) or 8 (bf16).  Anything else returns
+ *     SAR_ERR_UNSUPPORTED.
+ *   - A destination with no in-edge at all has out = 0 and L = -inf, and
+ *     contributes nothing to any gradient; the mean of an empty set is 0.
+ *   - A repeated edge counts with its multiplicity (one softmax term / one
+ *     summand / one unit of degree per copy).
+ */
+#ifndef SAR_MI355X_H
+#define SAR_MI355X_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SAR_OK = 0,
+    SAR_ERR_INVALID_ARG = -1, /* null pointer, negative size, id out of range ... */
+    SAR_ERR_UNSUPPORTED = -2, /* dtype / H / D / P combination the kernels do not cover */
+    SAR_ERR_HIP = -3,         /* a HIP runtime call failed (text has hipGetErrorString) */
+    SAR_ERR_STATE = -4        /* handle lacks what the call needs (e.g. no transpose) */
+} sar_status;
+
+typedef enum { SAR_F32 = 0, SAR_BF16 = 1 } sar_dtype;
+
+/* Most blocks one batched (..._all) call or one handle can hold. */
+#define SAR_MAX_BLOCKS 64
+
+/* flags of sar_blocks_build / sar_blocks_wrap */
+#define SAR_BUILD_TRANSPOSE 1 /* also build the source-major index (needed by every *_bwd_*) */
+#define SAR_BUILD_FUSED 2     /* also build the all-blocks row index (needed by every *_all) */
+
+typedef struct sar_blocks sar_blocks_t; /* opaque, library-owned */
+
+/* One block G_{p,q} = (V_{p,q}, E_{p,q}) (Sec. 3.2) as seen by the caller.
+ * All pointers are device pointers borrowed from the handle; they die with it.
+ *   indptr/indices      destination-major CSR: sources of row i are
+ *                       indices[indptr[i] .. indptr[i+1]), ascending, local to V_q
+ *   t_indptr/t_indices  the same edges source-major: destinations of source j,
+ *                       ascending, local to V_p          (NULL without TRANSPOSE)
+ *   rows / t_rows       the rows (resp. sources) that have at least one edge in
+ *                       this block, ordered longest-first by degree class: the
+ *                       launch order of the kernels.  The first n_long (resp.
+ *                       n_t_long) of them are longer than the long-row threshold.
+ *                       The order inside a degree class is unspecified.
+ *   touched             = t_rows sorted ascending: V_{p,q} intersected with V_q,
+ *                       the rows of Z_q a remote fetch would have to carry
+ *                       (Alg. 1, "Fetch Z_{q->p}")        (NULL without TRANSPOSE)
+ */
+typedef struct {
+    int64_t n_dst, n_src, nnz;
+    const int32_t* indptr;
+    const int32_t* indices;
+    const int32_t* t_indptr;
+    const int32_t* t_indices;
+    const int32_t* rows;
+    int64_t n_rows, n_long;
+    const int32_t* t_rows;
+    int64_t n_t_rows, n_t_long;
+    const int32_t* touched;
+} sar_block_view;
+
+/* Text of the last error on this thread ("" if none).  Host pointer, valid until
+ * the next failing call on the same thread. */
+const char* sar_last_error(void);
+
+/* ABI version of this header (currently 1). */
+int sar_version(void);
+
+/* ------------------------------------------------------------------ blocks
+ * Sec. 3.2: "for each worker p, SAR constructs N subgraphs G_{p,1..N}; E_{p,q}
+ * are all the edges from the vertices in partition q to the vertices in
+ * partition p".
+ */
+
+/* Build worker p's P blocks from a global edge list.
+ *   src,dst    [E] global node ids of the edges j->i (src = j, dst = i);
+ *              idx_bytes = 4 (int32) or 8 (int64).  Edges whose destination is
+ *              not in partition p are ignored.  Ids must lie in [0,N).
+ *   part       [N] partition of every node, each in [0,P)
+ *   P <= SAR_MAX_BLOCKS, every block must hold fewer than 2^31 edges and every
+ *   partition fewer than 2^31 nodes.
+ * The result is integer work and bit-exact: it does not depend on thread
+ * scheduling.  *out is a new handle the caller frees with sar_blocks_free. */
+int sar_blocks_build(const void* src, const void* dst, int idx_bytes, int64_t E,
+                     const int32_t* part, int64_t N, int P, int p, int flags, void* stream,
+                     sar_blocks_t** out);
+
+/* Wrap P caller-built destination-major CSR blocks (device arrays, borrowed
+ * until sar_blocks_free) and build the derived indexes `flags` asks for.
+ *   n_src      host [P], indptr host [P] of device int32 [n_dst+1],
+ *   indices    host [P] of device int32 [nnz_q]; columns must be < n_src[q].
+ * Rows need not be sorted for the kernels to be correct. */
+int sar_blocks_wrap(int P, int64_t n_dst, const int64_t* n_src, const int32_t* const* indptr,
+                    const int32_t* const* indices, int flags, void* stream, sar_blocks_t** out);
+
+/* *P = number of blocks, *n_dst = |V_p|. */
+int sar_blocks_info(const sar_blocks_t* b, int* P, int64_t* n_dst);
+
+/* Fill *v (host struct) with block q's device pointers and sizes. */
+int sar_blocks_get(const sar_blocks_t* b, int q, sar_block_view* v);
+
+/* *deg = device int32 [n_dst]: total in-degree |N(i)| over all blocks (Eq. 2). */
+int sar_blocks_degree(const sar_blocks_t* b, const int32_t** deg);
+
+/* Free the handle and everything the library allocated for it. */
+int sar_blocks_free(sar_blocks_t* b);
+
+/* ------------------------------------------------------- Eq. 2: sum / mean
+ * Alg. 1 with m_{j->i} = z_j:  Acc_i += sum over the block's edges of z_j.
+ */
+
+/* acc[i,:] += sum_{(j->i) in block q} Zq[j,:].   acc fp32 [n_dst,F] in/out
+ * (zero it before the first block); Zq [n_src_q,F] of `dtype`. */
+int sar_spmm_block(const sar_blocks_t* b, int q, const void* Zq, int dtype, int F, float* acc,
+                   void* stream);
+
+/* After the last block: out = acc (mean == 0) or acc / |N(i)| (Eq. 2; 0 when
+ * |N(i)| = 0).  out [n_dst,F] of `dtype`; deg from sar_blocks_degree. */
+int sar_spmm_end(const int32_t* deg, int mean, const float* acc, void* out, int dtype,
+                 int64_t n_dst, int F, void* stream);
+
+/* All P blocks in one launch, the accumulator never leaving registers; same
+ * result as P sar_spmm_block calls in block order followed by sar_spmm_end.
+ * Zq: host array [P] of device pointers.  Needs SAR_BUILD_FUSED. */
+int sar_spmm_all(const sar_blocks_t* b, const void* const* Zq, int dtype, int F, int mean,
+                 void* out, void* stream);
+
+/* Case 1 of Sec. 3.2 (the gradient of a sum does not need the features):
+ * dZq[j,:] = sum_{(j->i) in block q} G[i,:] / (mean ? |N(i)| : 1).
+ * dZq [n_src_q,F] of `dtype` is OVERWRITTEN (it is the error E_{p->q} of
+ * Alg. 2).  G [n_dst,F] of `dtype`.  Needs SAR_BUILD_TRANSPOSE. */
+int sar_spmm_bwd_block(const sar_blocks_t* b, int q, const void* G, int mean, int dtype, int F,
+                       void* dZq, void* stream);
+
+/* ------------------------------------------------------ Eq. 3: attention
+ * e_{j->i} = LeakyReLU(a^T (z_i || z_j)) = LeakyReLU(s_i + t_j) per head with
+ * s = <a_r, z_i>, t = <a_l, z_j>;  out_i = sum_j softmax_j(e_{j->i}) z_j.
+ */
+
+/* score[v,h] = <a[h,:], Z[v,h,:]>.  Z [n,H,D] of `dtype`, a fp32 [H,D],
+ * score fp32 [n,H].  Used for s (a = a_r, Z = Z_dst) and t_q (a = a_l, Z = Z_q). */
+int sar_gat_scores(const void* Z, int dtype, int64_t n, int H, int D, const float* a,
+                   float* score, void* stream);
+
+/* Start of Alg. 1's loop: running state of Sec. 3.4, m = -inf, l = 0, acc = 0.
+ * m,l fp32 [n_dst,H]; acc fp32 [n_dst,H,D]. */
+int sar_gat_fwd_begin(float* m, float* l, float* acc, int64_t n_dst, int H, int D, void* stream);
+
+/* One block of Alg. 1 with the fused kernel of Sec. 3.3: for every destination
+ * with an edge in block q, per head: new running maximum m' = max(m, max_j e),
+ * l = l exp(m-m') + sum_j exp(e-m'), acc = acc exp(m-m') + sum_j exp(e-m') z_j.
+ * No per-edge value is written to memory.  Destinations without an edge in the
+ * block are not touched.  s fp32 [n_dst,H]; tq fp32 [n_src_q,H]. */
+int sar_gat_fwd_block(const sar_blocks_t* b, int q, const void* Zq, const float* s,
+                      const float* tq, int dtype, int H, int D, float slope, float* m, float* l,
+                      float* acc, void* stream);
+
+/* After the last block: out = acc / l (the division of Sec. 3.2), and the
+ * log-sum-exp L = m + log l that the backward pass reads.  out [n_dst,H,D] of
+ * `dtype`, L fp32 [n_dst,H]. */
+int sar_gat_fwd_end(const float* m, const float* l, const float* acc, void* out, float* L,
+                    int dtype, int64_t n_dst, int H, int D, void* stream);
+
+/* All P blocks in one launch: each destination walks its blocks in order
+ * q = 0..P-1 with the same running-maximum updates, state in registers.
+ * Zq, tq: host arrays [P] of device pointers.  Needs SAR_BUILD_FUSED. */
+int sar_gat_fwd_all(const sar_blocks_t* b, const void* const* Zq, const float* s,
+                    const float* const* tq, int dtype, int H, int D, float slope, void* out,
+                    float* L, void* stream);
+
+/* Bytes of scratch the backward calls below need for these sizes. */
+int sar_gat_workspace_bytes(int64_t n_dst, int64_t n_src_max, int H, int D, size_t* bytes);
+
+/* Start of Alg. 2's loop.  Packs what the backward kernel needs per destination
+ * and head into one 16-byte record rec[i,h] = (s log2(e), L log2(e), delta, 0)
+ * with delta[i,h] = <G[i,h,:], out[i,h,:]>, and sets ds = 0.
+ * G (the error e_Acc) and out [n_dst,H,D] of `dtype`; s, L fp32 [n_dst,H] (from
+ * the forward pass); rec fp32 [n_dst,H,4] (16-byte aligned); ds fp32 [n_dst,H]. */
+int sar_gat_bwd_begin(const void* G, const void* out, const float* s, const float* L, int dtype,
+                      float* rec, float* ds, int64_t n_dst, int H, int D, void* stream);
+
+/* One block of Alg. 2 with the rematerialising kernel of Sec. 3.3.  For every
+ * edge the coefficient alpha = exp(e - L_i) is recomputed from s_i, t_j, L_i:
+ *   de = alpha (<G_i, z_j> - delta_i),  du = de * (1 if s_i+t_j > 0 else slope)
+ *   dZq[j] = sum_i alpha G_i + dtq[j] a_l     (OVERWRITTEN: the error E_{p->q})
+ *   dtq[j] = sum_i du                          (OVERWRITTEN, fp32 [n_src_q,H])
+ *   ds[i] += du                                (accumulates over blocks; atomic,
+ *                                               so its rounding order may vary)
+ *   da_l  += sum_j dtq[j] Zq[j]                (accumulates over blocks, fp32 [H,D])
+ * The kernel walks the source-major index (needs SAR_BUILD_TRANSPOSE): every
+ * source gathers its destinations' G rows, so dZq is written once, without
+ * atomics.  rec from sar_gat_bwd_begin; work: scratch of at least
+ * sar_gat_workspace_bytes, 16-byte aligned. */
+int sar_gat_bwd_block(const sar_blocks_t* b, int q, const void* Zq, const void* G, const float* tq,
+                      const float* rec, const float* a_l, int dtype, int H, int D, float slope,
+                      void* dZq, float* dtq, float* ds, float* da_l, void* work, size_t work_bytes,
+                      void* stream);
+
+/* All P blocks of Alg. 2's loop in one launch (same results as P
+ * sar_gat_bwd_block calls).  Zq, tq, dZq, dtq: host arrays [P] of device
+ * pointers.  Needs SAR_BUILD_TRANSPOSE. */
+int sar_gat_bwd_all(const sar_blocks_t* b, const void* const* Zq, const void* G,
+                    const float* const* tq, const float* rec, const float* a_l, int dtype, int H,
+                    int D, float slope, void* const* dZq, float* const* dtq, float* ds, float* da_l,
+                    void* work, size_t work_bytes, void* stream);
+
+/* After the last block, the destination side of the score:
+ * dZdst[i] = ds[i] a_r (OVERWRITTEN, `dtype`), da_r += sum_i ds[i] Zdst[i]. */
+int sar_gat_bwd_end(const void* Zdst, const float* ds, const float* a_r, void* dZdst, float* da_r,
+                    int dtype, int64_t n_dst, int H, int D, void* work, size_t work_bytes,
+                    void* stream);
+
+/* ------------------------------------------------- Eq. 1: Z = X W on MFMA */
+
+/* Z[n,F] = X[n,K] W[K,F]; X, Z of `dtype`, W fp32 row-major.  When a_score is
+ * non-null (fp32 [H,D], F = H*D) also writes score[v,h] = <a_score[h], Z[v,h]>
+ * from the fp32 accumulators (fp32 [n,H]); a second pair (a_score2, score2)
+ * may be given as well.  Pass H = D = 0 and null pointers for no scores. */
+int sar_linear_fwd(const void* X, const float* W, void* Z, int dtype, int64_t n, int K, int F,
+                   int H, int D, const float* a_score, float* score, const float* a_score2,
+                   float* score2, void* stream);
+
+/* What Z.backward(E) of Alg. 2 does for the transform: dW += X^T dZ (fp32
+ * [K,F], accumulates so that several blocks can add up), dX = dZ W^T
+ * (OVERWRITTEN, `dtype`, may be NULL to skip).  work: scratch of at least
+ * sar_linear_workspace_bytes. */
+int sar_linear_bwd(const void* X, const void* dZ, const float* W, float* dW, void* dX, int dtype,
+                   int64_t n, int K, int F, void* work, size_t work_bytes, void* stream);
+
+int sar_linear_workspace_bytes(int64_t n, int K, int F, size_t* bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SAR_MI355X_H */

@@ -1,0 +1,994 @@
+// Partition-block builder: worker p's P destination-major CSR blocks
+// G_{p,q} (Sec. 3.2 of the paper), plus the derived indexes the aggregation
+// kernels launch from: the source-major transpose of every block, degree-class
+// ordered row lists, the sorted touched-source list and the all-blocks row
+// index.  Integer work only.  Every array whose content is part of the
+// contract (indptr, indices, t_indptr, t_indices, deg, touched) is bit-exact
+// and independent of scheduling: rows are filled through atomic cursors and
+// then sorted.  Only the order inside a degree class of the launch lists is
+// left to the scheduler.
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "sar_internal.h"
+
+namespace sar {
+
+static thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+void clear_error() { g_err[0] = 0; }
+
+}  // namespace sar
+
+extern "C" const char* sar_last_error(void) { return sar::g_err; }
+extern "C" int sar_version(void) { return 1; }
+
+namespace {
+
+using sar::Block;
+
+constexpr int kThreads = 256;
+constexpr int kScanTile = 2048;   // 256 threads x 8 values
+constexpr int kPartTile = 1024;   // nodes per workgroup when ranking nodes in partitions
+constexpr int kShortSort = 32;    // rows up to this length are insertion-sorted by one thread
+constexpr int kLdsSort = 8192;    // longer rows up to this length are sorted in LDS
+
+// ---------------------------------------------------------------- scan
+
+__device__ inline int block_exclusive_scan(int v, int* lds4, int* total)
+{
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    int incl = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        int t = __shfl_up(incl, o);
+        if (lane >= o) incl += t;
+    }
+    if (lane == 63) lds4[w] = incl;
+    __syncthreads();
+    int woff = 0;
+    for (int k = 0; k < w; ++k) woff += lds4[k];
+    *total = lds4[0] + lds4[1] + lds4[2] + lds4[3];
+    __syncthreads();
+    return woff + incl - v;
+}
+
+__global__ __launch_bounds__(kThreads) void k_tile_reduce(const int32_t* __restrict__ in, int64_t n,
+                                                          int32_t* __restrict__ tile_sums)
+{
+    __shared__ int lds4[4];
+    const int64_t base = (int64_t)blockIdx.x * kScanTile + threadIdx.x * 8;
+    int s = 0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+        if (base + k < n) s += in[base + k];
+    int total;
+    block_exclusive_scan(s, lds4, &total);
+    if (threadIdx.x == 0) tile_sums[blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(kThreads) void k_tile_scan(const int32_t* in, int64_t n,
+                                                        const int32_t* __restrict__ tile_offsets,
+                                                        int32_t* out)
+{
+    __shared__ int lds4[4];
+    const int64_t base = (int64_t)blockIdx.x * kScanTile + threadIdx.x * 8;
+    int v[8], s = 0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        v[k] = (base + k < n) ? in[base + k] : 0;
+        s += v[k];
+    }
+    int total;
+    int run = block_exclusive_scan(s, lds4, &total) + (tile_offsets ? tile_offsets[blockIdx.x] : 0);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        if (base + k < n) out[base + k] = run;
+        run += v[k];
+    }
+}
+
+struct DeviceTemps {
+    std::vector<void*> ptrs;
+    ~DeviceTemps()
+    {
+        for (void* p : ptrs) (void)hipFree(p);
+    }
+    template <typename T>
+    int alloc(T** out, int64_t count)
+    {
+        void* p = nullptr;
+        SAR_HIP(hipMalloc(&p, std::max<int64_t>(count, 1) * sizeof(T)));
+        ptrs.push_back(p);
+        *out = static_cast<T*>(p);
+        return SAR_OK;
+    }
+};
+
+// out[k] = sum of in[0..k) for k in [0,n); in may equal out.
+int exclusive_scan(const int32_t* in, int32_t* out, int64_t n, hipStream_t st, DeviceTemps& tmp)
+{
+    if (n <= 0) return SAR_OK;
+    const int64_t tiles = (n + kScanTile - 1) / kScanTile;
+    if (tiles == 1) {
+        k_tile_scan<<<1, kThreads, 0, st>>>(in, n, nullptr, out);
+        SAR_LAUNCH_CHECK();
+        return SAR_OK;
+    }
+    int32_t* sums = nullptr;
+    SAR_TRY(tmp.alloc(&sums, tiles));
+    k_tile_reduce<<<(unsigned)tiles, kThreads, 0, st>>>(in, n, sums);
+    SAR_LAUNCH_CHECK();
+    SAR_TRY(exclusive_scan(sums, sums, tiles, st, tmp));
+    k_tile_scan<<<(unsigned)tiles, kThreads, 0, st>>>(in, n, sums, out);
+    SAR_LAUNCH_CHECK();
+    return SAR_OK;
+}
+
+// ------------------------------------------------- local ids of all nodes
+
+__global__ __launch_bounds__(kThreads) void k_part_tile_count(const int32_t* __restrict__ part,
+                                                              int64_t N, int P, int64_t n_tiles,
+                                                              int32_t* __restrict__ tile_counts,
+                                                              int* __restrict__ err)
+{
+    __shared__ int hist[SAR_MAX_BLOCKS];
+    if (threadIdx.x < SAR_MAX_BLOCKS) hist[threadIdx.x] = 0;
+    __syncthreads();
+    for (int r = 0; r < kPartTile / kThreads; ++r) {
+        const int64_t v = (int64_t)blockIdx.x * kPartTile + r * kThreads + threadIdx.x;
+        if (v < N) {
+            const int pv = part[v];
+            if (pv < 0 || pv >= P)
+                atomicOr(err, 1);
+            else
+                atomicAdd(&hist[pv], 1);
+        }
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < P) tile_counts[(int64_t)threadIdx.x * n_tiles + blockIdx.x] = hist[threadIdx.x];
+}
+
+// lid[v] = number of nodes u < v in the same partition as v.
+__global__ __launch_bounds__(kThreads) void k_local_ids(const int32_t* __restrict__ part, int64_t N,
+                                                        int P, int64_t n_tiles,
+                                                        const int32_t* __restrict__ tile_base,
+                                                        int32_t* __restrict__ lid)
+{
+    constexpr int kRounds = kPartTile / kThreads;
+    constexpr int kChunks = kPartTile / 64;
+    __shared__ int cnt[kChunks][SAR_MAX_BLOCKS];
+    for (int k = threadIdx.x; k < kChunks * SAR_MAX_BLOCKS; k += kThreads) (&cnt[0][0])[k] = 0;
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int pv[kRounds], rank[kRounds];
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+        const int64_t v = (int64_t)blockIdx.x * kPartTile + r * kThreads + threadIdx.x;
+        int x = (v < N) ? part[v] : -1;
+        if (x < 0 || x >= P) x = -1;
+        pv[r] = x;
+        // lanes holding the same partition id find each other
+        unsigned long long mine = 0;
+        bool pending = x >= 0;
+        unsigned long long todo = __ballot(pending);
+        while (todo) {
+            const int first = __ffsll((long long)todo) - 1;
+            const int val = __shfl(x, first);
+            const unsigned long long same = __ballot(pending && x == val);
+            if (pending && x == val) {
+                mine = same;
+                pending = false;
+            }
+            todo = __ballot(pending);
+        }
+        const unsigned long long below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+        rank[r] = __popcll(mine & below);
+        if (x >= 0 && rank[r] == 0) cnt[r * (kThreads / 64) + wave][x] = __popcll(mine);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+        const int64_t v = (int64_t)blockIdx.x * kPartTile + r * kThreads + threadIdx.x;
+        if (pv[r] < 0) continue;
+        const int chunk = r * (kThreads / 64) + wave;
+        int pre = 0;
+        for (int c = 0; c < chunk; ++c) pre += cnt[c][pv[r]];
+        const int64_t col = (int64_t)pv[r] * n_tiles;
+        lid[v] = tile_base[col + blockIdx.x] - tile_base[col] + pre + rank[r];
+    }
+}
+
+// ------------------------------------------------------ edges -> blocks
+
+template <typename IdxT>
+__global__ __launch_bounds__(kThreads) void k_edge_count(const IdxT* __restrict__ src,
+                                                         const IdxT* __restrict__ dst, int64_t E,
+                                                         const int32_t* __restrict__ part, int64_t N,
+                                                         int p, const int32_t* __restrict__ lid,
+                                                         int64_t n_dst, int32_t* __restrict__ row_cnt,
+                                                         int* __restrict__ err)
+{
+    for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < E;
+         e += (int64_t)gridDim.x * kThreads) {
+        const int64_t d = (int64_t)dst[e], s = (int64_t)src[e];
+        if (d < 0 || d >= N || s < 0 || s >= N) {
+            atomicOr(err, 2);
+            continue;
+        }
+        if (part[d] != p) continue;
+        atomicAdd(&row_cnt[(int64_t)part[s] * n_dst + lid[d]], 1);
+    }
+}
+
+// Uses row_cnt as a countdown cursor: slot order inside a row is arbitrary
+// here and fixed by the sort that follows.
+template <typename IdxT>
+__global__ __launch_bounds__(kThreads) void k_edge_scatter(const IdxT* __restrict__ src,
+                                                           const IdxT* __restrict__ dst, int64_t E,
+                                                           const int32_t* __restrict__ part,
+                                                           int64_t N, int p,
+                                                           const int32_t* __restrict__ lid,
+                                                           int64_t n_dst, int32_t* __restrict__ row_cnt,
+                                                           const int32_t* __restrict__ row_off,
+                                                           int32_t* __restrict__ indices_all)
+{
+    for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < E;
+         e += (int64_t)gridDim.x * kThreads) {
+        const int64_t d = (int64_t)dst[e], s = (int64_t)src[e];
+        if (d < 0 || d >= N || s < 0 || s >= N) continue;
+        if (part[d] != p) continue;
+        const int64_t r = (int64_t)part[s] * n_dst + lid[d];
+        const int pos = atomicSub(&row_cnt[r], 1) - 1;
+        indices_all[(int64_t)row_off[r] + pos] = lid[s];
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void k_make_indptr(const int32_t* __restrict__ row_off,
+                                                          int64_t n_dst, int P,
+                                                          int32_t* __restrict__ indptr_all)
+{
+    const int64_t total = (int64_t)P * (n_dst + 1);
+    for (int64_t k = (int64_t)blockIdx.x * kThreads + threadIdx.x; k < total;
+         k += (int64_t)gridDim.x * kThreads) {
+        const int64_t q = k / (n_dst + 1), i = k - q * (n_dst + 1);
+        indptr_all[k] = row_off[q * n_dst + i] - row_off[q * n_dst];
+    }
+}
+
+// ------------------------------------------------------------ row sorting
+
+__global__ __launch_bounds__(kThreads) void k_sort_short(const int32_t* __restrict__ off,
+                                                         int64_t n_rows, int32_t* __restrict__ data,
+                                                         int32_t* __restrict__ long_list,
+                                                         int* __restrict__ long_count)
+{
+    for (int64_t r = (int64_t)blockIdx.x * kThreads + threadIdx.x; r < n_rows;
+         r += (int64_t)gridDim.x * kThreads) {
+        const int beg = off[r], len = off[r + 1] - beg;
+        if (len <= 1) continue;
+        if (len > kShortSort) {
+            long_list[atomicAdd(long_count, 1)] = (int32_t)r;
+            continue;
+        }
+        int32_t* a = data + beg;
+        for (int k = 1; k < len; ++k) {
+            const int32_t x = a[k];
+            int m = k - 1;
+            while (m >= 0 && a[m] > x) {
+                a[m + 1] = a[m];
+                --m;
+            }
+            a[m + 1] = x;
+        }
+    }
+}
+
+// One workgroup per listed row: bitonic network in which every comparator is
+// ascending, so the virtual +inf padding behind the row never moves.
+__global__ __launch_bounds__(kThreads) void k_sort_long(const int32_t* __restrict__ off,
+                                                        int32_t* __restrict__ data,
+                                                        const int32_t* __restrict__ long_list,
+                                                        const int* __restrict__ long_count)
+{
+    __shared__ int32_t buf[kLdsSort];
+    const int n_list = *long_count;
+    for (int w = blockIdx.x; w < n_list; w += gridDim.x) {
+        const int64_t r = long_list[w];
+        const int beg = off[r], len = off[r + 1] - beg;
+        int32_t* g = data + beg;
+        const bool in_lds = len <= kLdsSort;
+        int32_t* a = in_lds ? buf : g;
+        if (in_lds) {
+            for (int t = threadIdx.x; t < len; t += kThreads) buf[t] = g[t];
+        }
+        __syncthreads();
+        int n2 = 1;
+        while (n2 < len) n2 <<= 1;
+        for (int k = 2; k <= n2; k <<= 1) {
+            for (int j = k >> 1; j > 0; j >>= 1) {
+                const bool flip = (j == (k >> 1));
+                for (int t = threadIdx.x; t < n2; t += kThreads) {
+                    const int partner = flip ? (t ^ (k - 1)) : (t ^ j);
+                    if (partner > t && partner < len) {
+                        const int32_t x = a[t], y = a[partner];
+                        if (x > y) {
+                            a[t] = y;
+                            a[partner] = x;
+                        }
+                    }
+                }
+                __syncthreads();
+            }
+        }
+        if (in_lds) {
+            for (int t = threadIdx.x; t < len; t += kThreads) g[t] = buf[t];
+        }
+        __syncthreads();
+    }
+}
+
+int sort_rows(const int32_t* off, int64_t n_rows, int32_t* data, int64_t nnz, hipStream_t st,
+              DeviceTemps& tmp)
+{
+    if (n_rows <= 0 || nnz <= 1) return SAR_OK;
+    const int64_t cap = nnz / (kShortSort + 1) + 1;
+    int32_t* list = nullptr;
+    int* count = nullptr;
+    SAR_TRY(tmp.alloc(&list, cap));
+    SAR_TRY(tmp.alloc(&count, 1));
+    SAR_HIP(hipMemsetAsync(count, 0, sizeof(int), st));
+    const unsigned g1 = (unsigned)std::min<int64_t>((n_rows + kThreads - 1) / kThreads, 1 << 20);
+    k_sort_short<<<g1, kThreads, 0, st>>>(off, n_rows, data, list, count);
+    SAR_LAUNCH_CHECK();
+    const unsigned g2 = (unsigned)std::min<int64_t>(cap, 16384);
+    k_sort_long<<<g2, kThreads, 0, st>>>(off, data, list, count);
+    SAR_LAUNCH_CHECK();
+    return SAR_OK;
+}
+
+// ------------------------------------------------- degree-class row lists
+
+__device__ inline int degree_class(int len) { return len <= 0 ? 0 : 32 - __clz(len); }
+
+__global__ __launch_bounds__(kThreads) void k_class_hist(const int32_t* __restrict__ off, int64_t n,
+                                                         int* __restrict__ hist)
+{
+    __shared__ int h[sar::kNumClasses];
+    if (threadIdx.x < sar::kNumClasses) h[threadIdx.x] = 0;
+    __syncthreads();
+    for (int64_t r = (int64_t)blockIdx.x * kThreads + threadIdx.x; r < n;
+         r += (int64_t)gridDim.x * kThreads) {
+        const int c = degree_class(off[r + 1] - off[r]);
+        if (c > 0) atomicAdd(&h[c], 1);
+    }
+    __syncthreads();
+    if (threadIdx.x < sar::kNumClasses && h[threadIdx.x]) atomicAdd(&hist[threadIdx.x], h[threadIdx.x]);
+}
+
+// cursor[c] starts at the first slot of class c; value written = r | tag.
+__global__ __launch_bounds__(kThreads) void k_class_place(const int32_t* __restrict__ off, int64_t n,
+                                                          int* __restrict__ cursor, uint32_t tag,
+                                                          uint32_t* __restrict__ out)
+{
+    __shared__ int h[sar::kNumClasses];
+    __shared__ int base[sar::kNumClasses];
+    const int64_t r = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (threadIdx.x < sar::kNumClasses) h[threadIdx.x] = 0;
+    __syncthreads();
+    int c = 0, local = 0;
+    if (r < n) {
+        c = degree_class(off[r + 1] - off[r]);
+        if (c > 0) local = atomicAdd(&h[c], 1);
+    }
+    __syncthreads();
+    if (threadIdx.x < sar::kNumClasses && h[threadIdx.x])
+        base[threadIdx.x] = atomicAdd(&cursor[threadIdx.x], h[threadIdx.x]);
+    __syncthreads();
+    if (c > 0) out[base[c] + local] = (uint32_t)r | tag;
+}
+
+struct ClassLayout {
+    int64_t n_rows = 0, n_long = 0;
+    int start[sar::kNumClasses];
+};
+
+ClassLayout layout_from_hist(const int* hist, int64_t offset)
+{
+    ClassLayout L;
+    int64_t run = offset;
+    for (int c = sar::kNumClasses - 1; c >= 1; --c) {
+        L.start[c] = (int)run;
+        run += hist[c];
+        L.n_rows += hist[c];
+        if (c >= sar::kLongClass) L.n_long += hist[c];
+    }
+    L.start[0] = (int)run;
+    return L;
+}
+
+// --------------------------------------------------- transpose of a block
+
+// One wavefront per listed destination row.
+__global__ __launch_bounds__(kThreads) void k_t_count(const int32_t* __restrict__ indptr,
+                                                      const int32_t* __restrict__ indices,
+                                                      const uint32_t* __restrict__ rows,
+                                                      int64_t n_rows, int32_t* __restrict__ col_cnt)
+{
+    const int lane = threadIdx.x & 63;
+    for (int64_t w = ((int64_t)blockIdx.x * kThreads + threadIdx.x) >> 6; w < n_rows;
+         w += ((int64_t)gridDim.x * kThreads) >> 6) {
+        const int i = (int)rows[w];
+        const int beg = indptr[i], end = indptr[i + 1];
+        for (int e = beg + lane; e < end; e += 64) atomicAdd(&col_cnt[indices[e]], 1);
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void k_t_scatter(const int32_t* __restrict__ indptr,
+                                                        const int32_t* __restrict__ indices,
+                                                        const uint32_t* __restrict__ rows,
+                                                        int64_t n_rows, int32_t* __restrict__ col_cnt,
+                                                        const int32_t* __restrict__ col_off,
+                                                        int32_t* __restrict__ t_indices_all)
+{
+    const int lane = threadIdx.x & 63;
+    for (int64_t w = ((int64_t)blockIdx.x * kThreads + threadIdx.x) >> 6; w < n_rows;
+         w += ((int64_t)gridDim.x * kThreads) >> 6) {
+        const int i = (int)rows[w];
+        const int beg = indptr[i], end = indptr[i + 1];
+        for (int e = beg + lane; e < end; e += 64) {
+            const int j = indices[e];
+            const int pos = atomicSub(&col_cnt[j], 1) - 1;
+            t_indices_all[(int64_t)col_off[j] + pos] = i;
+        }
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void k_rebase(const int32_t* __restrict__ off, int64_t n_plus_1,
+                                                     int32_t* __restrict__ out)
+{
+    const int32_t base = off[0];
+    for (int64_t k = (int64_t)blockIdx.x * kThreads + threadIdx.x; k < n_plus_1;
+         k += (int64_t)gridDim.x * kThreads)
+        out[k] = off[k] - base;
+}
+
+// flags[j] = 1 if source j has an edge (from global offsets)
+__global__ __launch_bounds__(kThreads) void k_nonempty_flags(const int32_t* __restrict__ off, int64_t n,
+                                                             int32_t* __restrict__ flags)
+{
+    for (int64_t k = (int64_t)blockIdx.x * kThreads + threadIdx.x; k < n;
+         k += (int64_t)gridDim.x * kThreads)
+        flags[k] = off[k + 1] > off[k] ? 1 : 0;
+}
+
+__global__ __launch_bounds__(kThreads) void k_compact(const int32_t* __restrict__ off,
+                                                      const int32_t* __restrict__ pos, int64_t n,
+                                                      int32_t base_pos, int32_t* __restrict__ out)
+{
+    for (int64_t k = (int64_t)blockIdx.x * kThreads + threadIdx.x; k < n;
+         k += (int64_t)gridDim.x * kThreads)
+        if (off[k + 1] > off[k]) out[pos[k] - base_pos] = (int32_t)k;
+}
+
+// ------------------------------------------------- all-blocks (fused) index
+
+struct PtrTable {
+    const int32_t* indptr[SAR_MAX_BLOCKS];
+};
+
+__global__ __launch_bounds__(kThreads) void k_total_degree(PtrTable t, int P, int64_t n_dst,
+                                                           int32_t* __restrict__ deg)
+{
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i <= n_dst;
+         i += (int64_t)gridDim.x * kThreads) {
+        int d = 0;
+        if (i < n_dst)
+            for (int q = 0; q < P; ++q) d += t.indptr[q][i + 1] - t.indptr[q][i];
+        deg[i] = d;   // deg[n_dst] = 0 closes the scan
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void k_fused_copy(PtrTable t, int q,
+                                                         const int32_t* __restrict__ indices,
+                                                         const uint32_t* __restrict__ rows,
+                                                         int64_t n_rows,
+                                                         const int32_t* __restrict__ f_indptr,
+                                                         uint32_t tag, uint32_t* __restrict__ f_indices)
+{
+    const int lane = threadIdx.x & 63;
+    for (int64_t w = ((int64_t)blockIdx.x * kThreads + threadIdx.x) >> 6; w < n_rows;
+         w += ((int64_t)gridDim.x * kThreads) >> 6) {
+        const int i = (int)rows[w];
+        int64_t dstpos = f_indptr[i];
+        for (int k = 0; k < q; ++k) dstpos += t.indptr[k][i + 1] - t.indptr[k][i];
+        const int beg = t.indptr[q][i], end = t.indptr[q][i + 1];
+        for (int e = beg + lane; e < end; e += 64)
+            f_indices[dstpos + (e - beg)] = (uint32_t)indices[e] | tag;
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void k_check_columns(const int32_t* __restrict__ indptr,
+                                                            const int32_t* __restrict__ indices,
+                                                            int64_t n_dst, int64_t nnz, int64_t n_src,
+                                                            int* __restrict__ err)
+{
+    for (int64_t k = (int64_t)blockIdx.x * kThreads + threadIdx.x; k < nnz;
+         k += (int64_t)gridDim.x * kThreads)
+        if (indices[k] < 0 || indices[k] >= n_src) atomicOr(err, 4);
+    for (int64_t k = (int64_t)blockIdx.x * kThreads + threadIdx.x; k < n_dst;
+         k += (int64_t)gridDim.x * kThreads)
+        if (indptr[k + 1] < indptr[k]) atomicOr(err, 8);
+}
+
+unsigned grid_for(int64_t items, int per_block = kThreads, int64_t cap = 1 << 20)
+{
+    return (unsigned)std::max<int64_t>(1, std::min<int64_t>((items + per_block - 1) / per_block, cap));
+}
+
+template <typename T>
+int own(sar_blocks* h, T** out, int64_t count)
+{
+    void* p = nullptr;
+    SAR_HIP(hipMalloc(&p, std::max<int64_t>(count, 1) * sizeof(T)));
+    h->owned.push_back(p);
+    *out = static_cast<T*>(p);
+    return SAR_OK;
+}
+
+int bits_for(int64_t n)
+{
+    int b = 0;
+    while (((int64_t)1 << b) < n) ++b;
+    return b;
+}
+
+// Builds what `flags` asks for on top of per-block CSR arrays already in h->blk.
+int derive(sar_blocks* h, hipStream_t st)
+{
+    const int P = h->P;
+    const int64_t n_dst = h->n_dst;
+    DeviceTemps tmp;
+
+    int64_t nnz_total = 0, n_src_total = 0, n_src_max = 0;
+    for (auto& b : h->blk) {
+        nnz_total += b.nnz;
+        n_src_total += b.n_src;
+        n_src_max = std::max(n_src_max, b.n_src);
+    }
+    h->tag_shift = std::max(1, bits_for(std::max<int64_t>(n_src_max, 2)));
+    if (h->tag_shift + bits_for(P) > 32)
+        return sar::fail(SAR_ERR_UNSUPPORTED, "P=%d blocks of up to %lld sources do not fit a 32-bit tagged index",
+                         P, (long long)n_src_max);
+
+    PtrTable tab;
+    memset(&tab, 0, sizeof(tab));
+    for (int q = 0; q < P; ++q) tab.indptr[q] = h->blk[q].indptr;
+
+    // total in-degree |N(i)|
+    SAR_TRY(own(h, &h->deg, n_dst + 1));
+    k_total_degree<<<grid_for(n_dst + 1), kThreads, 0, st>>>(tab, P, n_dst, h->deg);
+    SAR_LAUNCH_CHECK();
+
+    // ---- destination-row launch lists, one per block, longest class first
+    int* hist_d = nullptr;
+    const int n_hist = (P + 2) * sar::kNumClasses;
+    SAR_TRY(tmp.alloc(&hist_d, n_hist));
+    SAR_HIP(hipMemsetAsync(hist_d, 0, n_hist * sizeof(int), st));
+    for (int q = 0; q < P; ++q) {
+        k_class_hist<<<grid_for(n_dst, kThreads, 4096), kThreads, 0, st>>>(h->blk[q].indptr, n_dst,
+                                                                           hist_d + q * sar::kNumClasses);
+        SAR_LAUNCH_CHECK();
+    }
+    std::vector<int> hist(n_hist);
+    SAR_HIP(hipMemcpyAsync(hist.data(), hist_d, n_hist * sizeof(int), hipMemcpyDeviceToHost, st));
+    SAR_HIP(hipStreamSynchronize(st));
+    std::vector<int> cursors(n_hist, 0);
+    int64_t rows_total = 0;
+    std::vector<int64_t> rows_base(P);
+    for (int q = 0; q < P; ++q) {
+        ClassLayout L = layout_from_hist(&hist[q * sar::kNumClasses], 0);
+        h->blk[q].n_rows = L.n_rows;
+        h->blk[q].n_long = L.n_long;
+        memcpy(&cursors[q * sar::kNumClasses], L.start, sizeof(L.start));
+        rows_base[q] = rows_total;
+        rows_total += L.n_rows;
+    }
+    int32_t* rows_all = nullptr;
+    SAR_TRY(own(h, &rows_all, rows_total));
+    SAR_HIP(hipMemcpyAsync(hist_d, cursors.data(), n_hist * sizeof(int), hipMemcpyHostToDevice, st));
+    for (int q = 0; q < P; ++q) {
+        h->blk[q].rows = rows_all + rows_base[q];
+        k_class_place<<<grid_for(n_dst, kThreads, 1 << 23), kThreads, 0, st>>>(h->blk[q].indptr, n_dst,
+                                                            hist_d + q * sar::kNumClasses, 0u,
+                                                            reinterpret_cast<uint32_t*>(h->blk[q].rows));
+        SAR_LAUNCH_CHECK();
+    }
+    SAR_HIP(hipStreamSynchronize(st));   // cursors (host vector) must outlive the copy
+
+    // ---- all-blocks destination-major index
+    if (h->flags & SAR_BUILD_FUSED) {
+        if (nnz_total >= ((int64_t)1 << 31))
+            return sar::fail(SAR_ERR_UNSUPPORTED, "all-blocks index needs fewer than 2^31 edges, got %lld",
+                             (long long)nnz_total);
+        SAR_TRY(own(h, &h->f_indptr, n_dst + 1));
+        SAR_TRY(exclusive_scan(h->deg, h->f_indptr, n_dst + 1, st, tmp));
+        SAR_TRY(own(h, &h->f_indices, nnz_total));
+        for (int q = 0; q < P; ++q) {
+            if (h->blk[q].n_rows == 0) continue;
+            k_fused_copy<<<grid_for(h->blk[q].n_rows * 64), kThreads, 0, st>>>(
+                tab, q, h->blk[q].indices, reinterpret_cast<const uint32_t*>(h->blk[q].rows),
+                h->blk[q].n_rows, h->f_indptr, (uint32_t)q << h->tag_shift, h->f_indices);
+            SAR_LAUNCH_CHECK();
+        }
+        int* fh = hist_d + P * sar::kNumClasses;
+        SAR_HIP(hipMemsetAsync(fh, 0, sar::kNumClasses * sizeof(int), st));
+        k_class_hist<<<grid_for(n_dst, kThreads, 4096), kThreads, 0, st>>>(h->f_indptr, n_dst, fh);
+        SAR_LAUNCH_CHECK();
+        int fhist[sar::kNumClasses];
+        SAR_HIP(hipMemcpyAsync(fhist, fh, sizeof(fhist), hipMemcpyDeviceToHost, st));
+        SAR_HIP(hipStreamSynchronize(st));
+        ClassLayout L = layout_from_hist(fhist, 0);
+        h->n_f_rows = L.n_rows;
+        h->n_f_long = L.n_long;
+        SAR_TRY(own(h, &h->f_rows, L.n_rows));
+        SAR_HIP(hipMemcpyAsync(fh, L.start, sizeof(L.start), hipMemcpyHostToDevice, st));
+        k_class_place<<<grid_for(n_dst, kThreads, 1 << 23), kThreads, 0, st>>>(h->f_indptr, n_dst, fh, 0u,
+                                                            reinterpret_cast<uint32_t*>(h->f_rows));
+        SAR_LAUNCH_CHECK();
+        SAR_HIP(hipStreamSynchronize(st));
+    }
+
+    // ---- source-major transpose of every block
+    if (h->flags & SAR_BUILD_TRANSPOSE) {
+        if (nnz_total >= ((int64_t)1 << 31))
+            return sar::fail(SAR_ERR_UNSUPPORTED, "transpose needs fewer than 2^31 edges in total, got %lld",
+                             (long long)nnz_total);
+        // counts of all blocks in one array [sum n_src + 1], block q at coff[q]
+        std::vector<int64_t> coff(P + 1, 0);
+        for (int q = 0; q < P; ++q) coff[q + 1] = coff[q] + h->blk[q].n_src;
+        int32_t *col_cnt = nullptr, *col_off = nullptr, *t_indices_all = nullptr, *t_indptr_all = nullptr;
+        SAR_TRY(tmp.alloc(&col_cnt, n_src_total + 1));
+        SAR_TRY(tmp.alloc(&col_off, n_src_total + 1));
+        SAR_HIP(hipMemsetAsync(col_cnt, 0, (n_src_total + 1) * sizeof(int32_t), st));
+        for (int q = 0; q < P; ++q) {
+            const Block& b = h->blk[q];
+            if (b.n_rows == 0) continue;
+            k_t_count<<<grid_for(b.n_rows * 64), kThreads, 0, st>>>(
+                b.indptr, b.indices, reinterpret_cast<const uint32_t*>(b.rows), b.n_rows, col_cnt + coff[q]);
+            SAR_LAUNCH_CHECK();
+        }
+        SAR_TRY(exclusive_scan(col_cnt, col_off, n_src_total + 1, st, tmp));
+        SAR_TRY(own(h, &t_indices_all, nnz_total));
+        for (int q = 0; q < P; ++q) {
+            const Block& b = h->blk[q];
+            if (b.n_rows == 0) continue;
+            k_t_scatter<<<grid_for(b.n_rows * 64), kThreads, 0, st>>>(
+                b.indptr, b.indices, reinterpret_cast<const uint32_t*>(b.rows), b.n_rows, col_cnt + coff[q],
+                col_off + coff[q], t_indices_all);
+            SAR_LAUNCH_CHECK();
+        }
+        SAR_TRY(sort_rows(col_off, n_src_total, t_indices_all, nnz_total, st, tmp));
+
+        // per-block views: own indptr (rebased to the block) and a slice of the indices
+        SAR_TRY(own(h, &t_indptr_all, n_src_total + P));
+        std::vector<int32_t> block_first(P + 1, 0);
+        for (int q = 0; q <= P; ++q)
+            SAR_HIP(hipMemcpyAsync(&block_first[q], col_off + coff[q], sizeof(int32_t),
+                                   hipMemcpyDeviceToHost, st));
+        SAR_HIP(hipStreamSynchronize(st));
+        for (int q = 0; q < P; ++q) {
+            Block& b = h->blk[q];
+            b.t_indptr = t_indptr_all + coff[q] + q;
+            b.t_indices = t_indices_all + block_first[q];
+            k_rebase<<<grid_for(b.n_src + 1), kThreads, 0, st>>>(col_off + coff[q], b.n_src + 1, b.t_indptr);
+            SAR_LAUNCH_CHECK();
+        }
+
+        // source launch lists per block + one for all blocks, and the touched lists
+        SAR_HIP(hipMemsetAsync(hist_d, 0, n_hist * sizeof(int), st));
+        for (int q = 0; q < P; ++q) {
+            k_class_hist<<<grid_for(h->blk[q].n_src, kThreads, 4096), kThreads, 0, st>>>(
+                h->blk[q].t_indptr, h->blk[q].n_src, hist_d + q * sar::kNumClasses);
+            SAR_LAUNCH_CHECK();
+        }
+        SAR_HIP(hipMemcpyAsync(hist.data(), hist_d, n_hist * sizeof(int), hipMemcpyDeviceToHost, st));
+        SAR_HIP(hipStreamSynchronize(st));
+        int all_hist[sar::kNumClasses] = {0};
+        int64_t t_rows_total = 0;
+        std::vector<int64_t> t_base(P);
+        for (int q = 0; q < P; ++q) {
+            ClassLayout L = layout_from_hist(&hist[q * sar::kNumClasses], 0);
+            h->blk[q].n_t_rows = L.n_rows;
+            h->blk[q].n_t_long = L.n_long;
+            memcpy(&cursors[q * sar::kNumClasses], L.start, sizeof(L.start));
+            t_base[q] = t_rows_total;
+            t_rows_total += L.n_rows;
+            for (int c = 0; c < sar::kNumClasses; ++c) all_hist[c] += hist[q * sar::kNumClasses + c];
+        }
+        ClassLayout LA = layout_from_hist(all_hist, 0);
+        h->n_ft_rows = LA.n_rows;
+        h->n_ft_long = LA.n_long;
+        memcpy(&cursors[P * sar::kNumClasses], LA.start, sizeof(LA.start));
+        int32_t *t_rows_all = nullptr, *touched_all = nullptr;
+        SAR_TRY(own(h, &t_rows_all, t_rows_total));
+        SAR_TRY(own(h, &touched_all, t_rows_total));
+        SAR_TRY(own(h, &h->ft_rows, t_rows_total));
+        SAR_HIP(hipMemcpyAsync(hist_d, cursors.data(), n_hist * sizeof(int), hipMemcpyHostToDevice, st));
+        for (int q = 0; q < P; ++q) {
+            Block& b = h->blk[q];
+            b.t_rows = t_rows_all + t_base[q];
+            b.touched = touched_all + t_base[q];
+            k_class_place<<<grid_for(b.n_src, kThreads, 1 << 23), kThreads, 0, st>>>(b.t_indptr, b.n_src,
+                                                                  hist_d + q * sar::kNumClasses, 0u,
+                                                                  reinterpret_cast<uint32_t*>(b.t_rows));
+            SAR_LAUNCH_CHECK();
+            k_class_place<<<grid_for(b.n_src, kThreads, 1 << 23), kThreads, 0, st>>>(b.t_indptr, b.n_src,
+                                                                  hist_d + P * sar::kNumClasses,
+                                                                  (uint32_t)q << h->tag_shift, h->ft_rows);
+            SAR_LAUNCH_CHECK();
+        }
+        // touched = ascending ids of the sources with an edge: compaction by scan
+        int32_t* pos = nullptr;
+        SAR_TRY(tmp.alloc(&pos, n_src_total + 1));
+        k_nonempty_flags<<<grid_for(n_src_total), kThreads, 0, st>>>(col_off, n_src_total, pos);
+        SAR_LAUNCH_CHECK();
+        SAR_HIP(hipMemsetAsync(pos + n_src_total, 0, sizeof(int32_t), st));
+        SAR_TRY(exclusive_scan(pos, pos, n_src_total + 1, st, tmp));
+        for (int q = 0; q < P; ++q) {
+            Block& b = h->blk[q];
+            if (b.n_t_rows == 0) continue;
+            k_compact<<<grid_for(b.n_src), kThreads, 0, st>>>(b.t_indptr, pos + coff[q], b.n_src,
+                                                              (int32_t)t_base[q], b.touched);
+            SAR_LAUNCH_CHECK();
+        }
+        SAR_HIP(hipStreamSynchronize(st));
+    }
+    SAR_HIP(hipStreamSynchronize(st));
+    return SAR_OK;
+}
+
+int check_err_flag(int* err_d, hipStream_t st)
+{
+    int err = 0;
+    SAR_HIP(hipMemcpyAsync(&err, err_d, sizeof(int), hipMemcpyDeviceToHost, st));
+    SAR_HIP(hipStreamSynchronize(st));
+    if (err & 1) return sar::fail(SAR_ERR_INVALID_ARG, "part[] holds a value outside [0,P)");
+    if (err & 2) return sar::fail(SAR_ERR_INVALID_ARG, "edge list holds a node id outside [0,N)");
+    if (err & 4) return sar::fail(SAR_ERR_INVALID_ARG, "indices[] holds a column outside [0,n_src)");
+    if (err & 8) return sar::fail(SAR_ERR_INVALID_ARG, "indptr[] is not non-decreasing");
+    return SAR_OK;
+}
+
+int build_from_edges(sar_blocks* h, const void* src, const void* dst, int idx_bytes, int64_t E,
+                     const int32_t* part, int64_t N, int P, int p, hipStream_t st)
+{
+    DeviceTemps tmp;
+    int* err_d = nullptr;
+    SAR_TRY(tmp.alloc(&err_d, 1));
+    SAR_HIP(hipMemsetAsync(err_d, 0, sizeof(int), st));
+
+    // 1. rank of every node inside its partition
+    const int64_t n_tiles = std::max<int64_t>(1, (N + kPartTile - 1) / kPartTile);
+    int32_t *tile_counts = nullptr, *lid = nullptr;
+    SAR_TRY(tmp.alloc(&tile_counts, (int64_t)P * n_tiles + 1));
+    SAR_TRY(tmp.alloc(&lid, N));
+    SAR_HIP(hipMemsetAsync(tile_counts, 0, ((int64_t)P * n_tiles + 1) * sizeof(int32_t), st));
+    k_part_tile_count<<<(unsigned)n_tiles, kThreads, 0, st>>>(part, N, P, n_tiles, tile_counts, err_d);
+    SAR_LAUNCH_CHECK();
+    SAR_TRY(check_err_flag(err_d, st));
+    SAR_TRY(exclusive_scan(tile_counts, tile_counts, (int64_t)P * n_tiles + 1, st, tmp));
+    std::vector<int32_t> part_first(P + 1);
+    for (int q = 0; q <= P; ++q)
+        SAR_HIP(hipMemcpyAsync(&part_first[q], tile_counts + (int64_t)q * n_tiles, sizeof(int32_t),
+                               hipMemcpyDeviceToHost, st));
+    SAR_HIP(hipStreamSynchronize(st));
+    k_local_ids<<<(unsigned)n_tiles, kThreads, 0, st>>>(part, N, P, n_tiles, tile_counts, lid);
+    SAR_LAUNCH_CHECK();
+    const int64_t n_dst = part_first[p + 1] - part_first[p];
+    h->n_dst = n_dst;
+    h->blk.resize(P);
+    for (int q = 0; q < P; ++q) {
+        h->blk[q].n_dst = n_dst;
+        h->blk[q].n_src = part_first[q + 1] - part_first[q];
+    }
+
+    // 2. count, scan, scatter, sort
+    const int64_t n_rows_all = (int64_t)P * n_dst;
+    int32_t *row_cnt = nullptr, *row_off = nullptr;
+    SAR_TRY(tmp.alloc(&row_cnt, n_rows_all + 1));
+    SAR_TRY(tmp.alloc(&row_off, n_rows_all + 1));
+    SAR_HIP(hipMemsetAsync(row_cnt, 0, (n_rows_all + 1) * sizeof(int32_t), st));
+    const unsigned ge = grid_for(E, kThreads, 1 << 16);
+    if (E > 0) {
+        if (idx_bytes == 4)
+            k_edge_count<int32_t><<<ge, kThreads, 0, st>>>((const int32_t*)src, (const int32_t*)dst, E, part,
+                                                           N, p, lid, n_dst, row_cnt, err_d);
+        else
+            k_edge_count<int64_t><<<ge, kThreads, 0, st>>>((const int64_t*)src, (const int64_t*)dst, E, part,
+                                                           N, p, lid, n_dst, row_cnt, err_d);
+        SAR_LAUNCH_CHECK();
+        SAR_TRY(check_err_flag(err_d, st));
+    }
+    SAR_TRY(exclusive_scan(row_cnt, row_off, n_rows_all + 1, st, tmp));
+    std::vector<int32_t> block_first(P + 1);
+    for (int q = 0; q <= P; ++q)
+        SAR_HIP(hipMemcpyAsync(&block_first[q], row_off + (int64_t)q * n_dst, sizeof(int32_t),
+                               hipMemcpyDeviceToHost, st));
+    SAR_HIP(hipStreamSynchronize(st));
+    const int64_t nnz_total = block_first[P];
+    int32_t *indices_all = nullptr, *indptr_all = nullptr;
+    SAR_TRY(own(h, &indices_all, nnz_total));
+    SAR_TRY(own(h, &indptr_all, (int64_t)P * (n_dst + 1)));
+    if (E > 0) {
+        if (idx_bytes == 4)
+            k_edge_scatter<int32_t><<<ge, kThreads, 0, st>>>((const int32_t*)src, (const int32_t*)dst, E,
+                                                             part, N, p, lid, n_dst, row_cnt, row_off,
+                                                             indices_all);
+        else
+            k_edge_scatter<int64_t><<<ge, kThreads, 0, st>>>((const int64_t*)src, (const int64_t*)dst, E,
+                                                             part, N, p, lid, n_dst, row_cnt, row_off,
+                                                             indices_all);
+        SAR_LAUNCH_CHECK();
+    }
+    SAR_TRY(sort_rows(row_off, n_rows_all, indices_all, nnz_total, st, tmp));
+    k_make_indptr<<<grid_for((int64_t)P * (n_dst + 1)), kThreads, 0, st>>>(row_off, n_dst, P, indptr_all);
+    SAR_LAUNCH_CHECK();
+    for (int q = 0; q < P; ++q) {
+        h->blk[q].nnz = block_first[q + 1] - block_first[q];
+        h->blk[q].indptr = indptr_all + (int64_t)q * (n_dst + 1);
+        h->blk[q].indices = indices_all + block_first[q];
+    }
+    SAR_HIP(hipStreamSynchronize(st));
+    return SAR_OK;
+}
+
+void destroy(sar_blocks* h)
+{
+    if (!h) return;
+    for (void* p : h->owned) (void)hipFree(p);
+    delete h;
+}
+
+}  // namespace
+
+extern "C" int sar_blocks_build(const void* src, const void* dst, int idx_bytes, int64_t E,
+                                const int32_t* part, int64_t N, int P, int p, int flags, void* stream,
+                                sar_blocks_t** out)
+{
+    SAR_CHECK_ARG(out != nullptr, "out is null");
+    *out = nullptr;
+    SAR_CHECK_ARG(idx_bytes == 4 || idx_bytes == 8, "idx_bytes must be 4 or 8, got %d", idx_bytes);
+    SAR_CHECK_ARG(E >= 0 && N > 0, "need E >= 0 and N > 0 (E=%lld, N=%lld)", (long long)E, (long long)N);
+    SAR_CHECK_ARG(E == 0 || (src && dst), "src/dst is null");
+    SAR_CHECK_ARG(part != nullptr, "part is null");
+    SAR_CHECK_ARG(P >= 1 && p >= 0 && p < P, "need 0 <= p < P, got p=%d P=%d", p, P);
+    SAR_CHECK_ARG((flags & ~(SAR_BUILD_TRANSPOSE | SAR_BUILD_FUSED)) == 0, "unknown flags 0x%x", flags);
+    if (P > SAR_MAX_BLOCKS)
+        return sar::fail(SAR_ERR_UNSUPPORTED, "P=%d exceeds SAR_MAX_BLOCKS=%d", P, SAR_MAX_BLOCKS);
+    if (E >= ((int64_t)1 << 31) || N >= ((int64_t)1 << 31))
+        return sar::fail(SAR_ERR_UNSUPPORTED, "E and N must be below 2^31 (32-bit offsets)");
+    sar_blocks* h = new (std::nothrow) sar_blocks();
+    if (!h) return sar::fail(SAR_ERR_HIP, "out of host memory");
+    h->P = P;
+    h->flags = flags;
+    hipStream_t st = sar::as_stream(stream);
+    int rc = build_from_edges(h, src, dst, idx_bytes, E, part, N, P, p, st);
+    if (rc == SAR_OK) rc = derive(h, st);
+    if (rc != SAR_OK) {
+        destroy(h);
+        return rc;
+    }
+    *out = h;
+    return SAR_OK;
+}
+
+extern "C" int sar_blocks_wrap(int P, int64_t n_dst, const int64_t* n_src, const int32_t* const* indptr,
+                               const int32_t* const* indices, int flags, void* stream, sar_blocks_t** out)
+{
+    SAR_CHECK_ARG(out != nullptr, "out is null");
+    *out = nullptr;
+    SAR_CHECK_ARG(P >= 1 && n_dst >= 0, "need P >= 1 and n_dst >= 0");
+    SAR_CHECK_ARG(n_src && indptr && indices, "n_src/indptr/indices is null");
+    SAR_CHECK_ARG((flags & ~(SAR_BUILD_TRANSPOSE | SAR_BUILD_FUSED)) == 0, "unknown flags 0x%x", flags);
+    if (P > SAR_MAX_BLOCKS)
+        return sar::fail(SAR_ERR_UNSUPPORTED, "P=%d exceeds SAR_MAX_BLOCKS=%d", P, SAR_MAX_BLOCKS);
+    for (int q = 0; q < P; ++q) {
+        SAR_CHECK_ARG(indptr[q] != nullptr, "indptr[%d] is null", q);
+        SAR_CHECK_ARG(n_src[q] >= 0 && n_src[q] < ((int64_t)1 << 31), "n_src[%d] out of range", q);
+    }
+    SAR_CHECK_ARG(n_dst < ((int64_t)1 << 31), "n_dst must be below 2^31");
+    hipStream_t st = sar::as_stream(stream);
+    sar_blocks* h = new (std::nothrow) sar_blocks();
+    if (!h) return sar::fail(SAR_ERR_HIP, "out of host memory");
+    h->P = P;
+    h->n_dst = n_dst;
+    h->flags = flags;
+    h->blk.resize(P);
+    auto body = [&]() -> int {
+        DeviceTemps tmp;
+        int* err_d = nullptr;
+        SAR_TRY(tmp.alloc(&err_d, 1));
+        SAR_HIP(hipMemsetAsync(err_d, 0, sizeof(int), st));
+        for (int q = 0; q < P; ++q) {
+            Block& b = h->blk[q];
+            b.n_dst = n_dst;
+            b.n_src = n_src[q];
+            b.indptr = indptr[q];
+            b.indices = indices[q];
+            int32_t ends[2] = {0, 0};
+            SAR_HIP(hipMemcpyAsync(&ends[0], indptr[q], sizeof(int32_t), hipMemcpyDeviceToHost, st));
+            SAR_HIP(hipMemcpyAsync(&ends[1], indptr[q] + n_dst, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+            SAR_HIP(hipStreamSynchronize(st));
+            SAR_CHECK_ARG(ends[0] == 0 && ends[1] >= 0, "indptr[%d] must start at 0 and end >= 0", q);
+            b.nnz = ends[1];
+            SAR_CHECK_ARG(b.nnz == 0 || indices[q] != nullptr, "indices[%d] is null", q);
+            k_check_columns<<<grid_for(std::max(b.nnz, n_dst), kThreads, 4096), kThreads, 0, st>>>(
+                b.indptr, b.indices, n_dst, b.nnz, b.n_src, err_d);
+            SAR_LAUNCH_CHECK();
+        }
+        SAR_TRY(check_err_flag(err_d, st));
+        return derive(h, st);
+    };
+    int rc = body();
+    if (rc != SAR_OK) {
+        destroy(h);
+        return rc;
+    }
+    *out = h;
+    return SAR_OK;
+}
+
+extern "C" int sar_blocks_info(const sar_blocks_t* b, int* P, int64_t* n_dst)
+{
+    SAR_CHECK_ARG(b != nullptr, "handle is null");
+    if (P) *P = b->P;
+    if (n_dst) *n_dst = b->n_dst;
+    return SAR_OK;
+}
+
+extern "C" int sar_blocks_get(const sar_blocks_t* b, int q, sar_block_view* v)
+{
+    SAR_CHECK_ARG(b != nullptr && v != nullptr, "handle or view is null");
+    SAR_CHECK_ARG(q >= 0 && q < b->P, "block %d out of range [0,%d)", q, b->P);
+    const Block& k = b->blk[q];
+    v->n_dst = k.n_dst;
+    v->n_src = k.n_src;
+    v->nnz = k.nnz;
+    v->indptr = k.indptr;
+    v->indices = k.indices;
+    v->t_indptr = k.t_indptr;
+    v->t_indices = k.t_indices;
+    v->rows = k.rows;
+    v->n_rows = k.n_rows;
+    v->n_long = k.n_long;
+    v->t_rows = k.t_rows;
+    v->n_t_rows = k.n_t_rows;
+    v->n_t_long = k.n_t_long;
+    v->touched = k.touched;
+    return SAR_OK;
+}
+
+extern "C" int sar_blocks_degree(const sar_blocks_t* b, const int32_t** deg)
+{
+    SAR_CHECK_ARG(b != nullptr && deg != nullptr, "handle or deg is null");
+    *deg = b->deg;
+    return SAR_OK;
+}
+
+extern "C" int sar_blocks_free(sar_blocks_t* b)
+{
+    destroy(b);
+    return SAR_OK;
+}

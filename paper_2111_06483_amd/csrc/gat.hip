@@ -1,0 +1,1006 @@
+// Fused, rematerialising attention kernels for GAT (Eq. 3; Sec. 3.3) with the
+// running-maximum incremental softmax of Sec. 3.4, as row gathers on gfx950.
+//
+// Forward: one wavefront owns one destination row.  Per edge it reads the
+// source's score half t_j and the source row z_j (16 bytes per lane, a 1 KiB
+// row is one wave-wide load, several in flight), forms e = LeakyReLU(s_i+t_j)
+// and folds exp(e - m) z_j into fp32 registers, rescaling when the running
+// maximum m grows.  Nothing per edge is written to memory.
+//
+// Backward: the same gather, run over the source-major index: one wavefront
+// owns one SOURCE row j, keeps z_j and t_j in registers, and for every
+// destination i of j reads G_i and the per-destination record (s_i, L_i,
+// delta_i), recomputes alpha = exp(e - L_i) and accumulates
+// dZ_j += alpha G_i, dt_j += du in registers.  dZ_q is written once per row,
+// coalesced, with no atomics; only the tiny ds[i,h] += du uses atomics.
+//
+// All exponentials are taken in base 2: scores are pre-multiplied by log2(e)
+// (LeakyReLU commutes with a positive scale), so e2 = LeakyReLU(s2 + t2) and
+// exp(e - m) = exp2(e2 - m2).
+#include <algorithm>
+
+#include "gather_common.h"
+#include "sar_internal.h"
+
+namespace {
+
+using namespace sar;
+
+constexpr int kU = 4;   // edges in flight per lane group
+
+struct PtrTab {
+    const void* p[SAR_MAX_BLOCKS];
+};
+
+__device__ inline float leaky(float u, float slope) { return u > 0.f ? u : slope * u; }
+
+// ------------------------------------------------------------------ forward
+
+struct FwdArgs {
+    const int32_t* indptr;
+    const uint32_t* indices;
+    const uint32_t* rows;
+    int64_t n_rows, n_long;
+    const void* Z;       // per-block call: this block's source rows
+    const float* t;      //                 and their score halves [n_src,H]
+    const float* s;      // destination score halves [n_dst,H]
+    float* m;            // running state (per-block calls), natural-log units
+    float* l;
+    float* acc;
+    void* out;           // batched call: normalised output rows
+    float* L;            //               and log-sum-exp [n_dst,H]
+    int H, D, F;
+    int tag_shift;
+    float slope;
+};
+
+template <int VEC>
+struct SoftState {
+    float m2;          // running maximum of e, in log2 units
+    float l;           // running sum of exp(e - m)
+    float acc[VEC];    // running sum of exp(e - m) z
+};
+
+template <int VEC>
+__device__ inline void state_reset(SoftState<VEC>& st)
+{
+    st.m2 = -INFINITY;
+    st.l = 0.f;
+#pragma unroll
+    for (int x = 0; x < VEC; ++x) st.acc[x] = 0.f;
+}
+
+// st <- st (+) other : the recursive aggregation property of Sec. 3.2 for the
+// (max, denominator, numerator) triple.
+template <int VEC>
+__device__ inline void state_merge(SoftState<VEC>& st, float om2, float ol, const float (&oacc)[VEC])
+{
+    const float mn = fmaxf(st.m2, om2);
+    const float ref = (mn == -INFINITY) ? 0.f : mn;
+    const float ca = fast_exp2(st.m2 - ref), cb = fast_exp2(om2 - ref);
+    st.l = st.l * ca + ol * cb;
+#pragma unroll
+    for (int x = 0; x < VEC; ++x) st.acc[x] = st.acc[x] * ca + oacc[x] * cb;
+    st.m2 = mn;
+}
+
+// Folds the edges idx[beg,end) into st; this wavefront takes the 64-edge
+// chunks chunk0, chunk0+stride, ...  s2 is the destination score half of this
+// lane's head in log2 units.
+template <typename T, int G, bool ALL>
+__device__ inline void fwd_edges(SoftState<Vec<T>::N>& st, const FwdArgs& a, const void* const* ztab,
+                                 const float* const* ttab, int beg, int end, int chunk0, int stride,
+                                 const LaneMap<T, G>& lm, float s2)
+{
+    constexpr int VEC = Vec<T>::N;
+    constexpr int SLOTS = kWave / G;
+    const uint32_t mask = ALL ? ((1u << a.tag_shift) - 1u) : 0xffffffffu;
+    for (int cb = beg + chunk0 * kWave; cb < end; cb += stride * kWave) {
+        const int cnt = min(kWave, end - cb);
+        const uint32_t mine = (lm.lane < cnt) ? a.indices[cb + lm.lane] : 0u;
+        for (int k0 = 0; k0 < cnt; k0 += SLOTS * kU) {
+            typename Vec<T>::Raw raw[kU];
+            float e2[kU];
+#pragma unroll
+            for (int k = 0; k < kU; ++k) {
+                const int ek = k0 + k * SLOTS + lm.slot;
+                const uint32_t id = __shfl(mine, ek & (kWave - 1));
+                raw[k] = Vec<T>::zero();
+                e2[k] = -INFINITY;
+                if (ek < cnt) {
+                    const uint32_t j = id & mask;
+                    const T* zb;
+                    const float* tb;
+                    if constexpr (ALL) {
+                        zb = static_cast<const T*>(ztab[id >> a.tag_shift]);
+                        tb = ttab[id >> a.tag_shift];
+                    } else {
+                        zb = static_cast<const T*>(a.Z);
+                        tb = a.t;
+                    }
+                    e2[k] = tb[(int64_t)j * a.H + lm.h];
+                    if (lm.on) raw[k] = Vec<T>::load(zb + (int64_t)j * a.F + lm.gl * VEC);
+                }
+            }
+            float mx = st.m2;
+#pragma unroll
+            for (int k = 0; k < kU; ++k) {
+                // -inf marks an absent edge and survives both operations
+                e2[k] = leaky(fmaf(e2[k], kLog2e, s2), a.slope);
+                mx = fmaxf(mx, e2[k]);
+            }
+            if (mx > st.m2) {
+                const float c = fast_exp2(st.m2 - mx);   // st.m2 = -inf gives 0
+                st.l *= c;
+#pragma unroll
+                for (int x = 0; x < VEC; ++x) st.acc[x] *= c;
+                st.m2 = mx;
+            }
+            const float ref = (st.m2 == -INFINITY) ? 0.f : st.m2;
+#pragma unroll
+            for (int k = 0; k < kU; ++k) {
+                const float p = fast_exp2(e2[k] - ref);
+                float v[VEC];
+                Vec<T>::unpack(raw[k], v);
+                st.l += p;
+#pragma unroll
+                for (int x = 0; x < VEC; ++x) st.acc[x] = fmaf(p, v[x], st.acc[x]);
+            }
+        }
+    }
+}
+
+template <typename T, int G>
+__device__ inline void fwd_merge_slots(SoftState<Vec<T>::N>& st)
+{
+    constexpr int VEC = Vec<T>::N;
+#pragma unroll
+    for (int o = G; o < kWave; o <<= 1) {
+        const float om2 = __shfl_xor(st.m2, o), ol = __shfl_xor(st.l, o);
+        float oacc[VEC];
+#pragma unroll
+        for (int x = 0; x < VEC; ++x) oacc[x] = __shfl_xor(st.acc[x], o);
+        state_merge<VEC>(st, om2, ol, oacc);
+    }
+}
+
+template <typename T, int G, bool ALL>
+__device__ inline void fwd_finish_row(SoftState<Vec<T>::N>& st, const FwdArgs& a, int i,
+                                      const LaneMap<T, G>& lm)
+{
+    constexpr int VEC = Vec<T>::N;
+    if (lm.slot != 0 || !lm.on) return;
+    const int64_t o = (int64_t)i * a.F + lm.gl * VEC;
+    if constexpr (ALL) {
+        // the division by the normaliser (Sec. 3.2), and L = m + log l for the backward pass
+        const float inv = st.l > 0.f ? 1.f / st.l : 0.f;
+        float v[VEC];
+#pragma unroll
+        for (int x = 0; x < VEC; ++x) v[x] = st.acc[x] * inv;
+        Vec<T>::store(static_cast<T*>(a.out) + o, v);
+        if ((lm.gl % lm.lph) == 0)
+            a.L[(int64_t)i * a.H + lm.h] = st.l > 0.f ? (st.m2 + fast_log2(st.l)) * kLn2 : -INFINITY;
+    } else {
+        store_f32<VEC>(a.acc + o, st.acc);
+        if ((lm.gl % lm.lph) == 0) {
+            a.m[(int64_t)i * a.H + lm.h] = st.m2 * kLn2;
+            a.l[(int64_t)i * a.H + lm.h] = st.l;
+        }
+    }
+}
+
+template <typename T, int G, bool ALL>
+__global__ __launch_bounds__(kGatherThreads) void k_gat_fwd(FwdArgs a, PtrTab ztab_arg, PtrTab ttab_arg,
+                                                            int P)
+{
+    constexpr int VEC = Vec<T>::N;
+    __shared__ const void* ztab[SAR_MAX_BLOCKS];
+    __shared__ const float* ttab[SAR_MAX_BLOCKS];
+    __shared__ float part_acc[kWavesPerWG][G][VEC];
+    __shared__ float part_ml[kWavesPerWG][G][2];
+    if constexpr (ALL) {
+        if ((int)threadIdx.x < P) {
+            ztab[threadIdx.x] = ztab_arg.p[threadIdx.x];
+            ttab[threadIdx.x] = static_cast<const float*>(ttab_arg.p[threadIdx.x]);
+        }
+        __syncthreads();
+    }
+    const LaneMap<T, G> lm(a.F, a.H, a.D);
+    const int wave = threadIdx.x / kWave;
+
+    auto load_state = [&](SoftState<VEC>& st, int i) {
+        state_reset<VEC>(st);
+        if constexpr (!ALL) {
+            // the state carried from the previous blocks enters through lane group 0
+            if (lm.slot == 0) {
+                st.m2 = a.m[(int64_t)i * a.H + lm.h] * kLog2e;
+                st.l = a.l[(int64_t)i * a.H + lm.h];
+                if (lm.on) load_f32<VEC>(a.acc + (int64_t)i * a.F + lm.gl * VEC, st.acc);
+            }
+        }
+    };
+
+    for (int64_t r = blockIdx.x; r < a.n_long; r += gridDim.x) {
+        const int i = (int)a.rows[r];
+        const float s2 = a.s[(int64_t)i * a.H + lm.h] * kLog2e;
+        SoftState<VEC> st;
+        if (wave == 0)
+            load_state(st, i);
+        else
+            state_reset<VEC>(st);
+        fwd_edges<T, G, ALL>(st, a, ztab, ttab, a.indptr[i], a.indptr[i + 1], wave, kWavesPerWG, lm, s2);
+        fwd_merge_slots<T, G>(st);
+        if (lm.slot == 0) {
+#pragma unroll
+            for (int x = 0; x < VEC; ++x) part_acc[wave][lm.gl][x] = st.acc[x];
+            part_ml[wave][lm.gl][0] = st.m2;
+            part_ml[wave][lm.gl][1] = st.l;
+        }
+        __syncthreads();
+        if (wave == 0) {
+            for (int w = 1; w < kWavesPerWG; ++w) {
+                float oacc[VEC];
+#pragma unroll
+                for (int x = 0; x < VEC; ++x) oacc[x] = part_acc[w][lm.gl][x];
+                state_merge<VEC>(st, part_ml[w][lm.gl][0], part_ml[w][lm.gl][1], oacc);
+            }
+            fwd_finish_row<T, G, ALL>(st, a, i, lm);
+        }
+        __syncthreads();
+    }
+    const int64_t n_waves = (int64_t)gridDim.x * kWavesPerWG;
+    for (int64_t r = a.n_long + (int64_t)blockIdx.x * kWavesPerWG + wave; r < a.n_rows; r += n_waves) {
+        const int i = (int)a.rows[r];
+        const float s2 = a.s[(int64_t)i * a.H + lm.h] * kLog2e;
+        SoftState<VEC> st;
+        load_state(st, i);
+        fwd_edges<T, G, ALL>(st, a, ztab, ttab, a.indptr[i], a.indptr[i + 1], 0, 1, lm, s2);
+        fwd_merge_slots<T, G>(st);
+        fwd_finish_row<T, G, ALL>(st, a, i, lm);
+    }
+}
+
+// ----------------------------------------------------------------- backward
+
+struct BwdArgs {
+    const int32_t* t_indptr[SAR_MAX_BLOCKS];   // per block (one entry for per-block calls)
+    const int32_t* t_indices[SAR_MAX_BLOCKS];
+    const void* Z[SAR_MAX_BLOCKS];
+    const float* t[SAR_MAX_BLOCKS];
+    void* dZ[SAR_MAX_BLOCKS];
+    float* dt[SAR_MAX_BLOCKS];
+};
+
+struct BwdScalars {
+    const uint32_t* rows;       // source work list; tagged with the block when ALL
+    int64_t n_rows, n_long;
+    const void* G;              // [n_dst,H,D]
+    const float4* rec;          // [n_dst,H]: (s*log2e, L*log2e, delta, unused)
+    const float* a_l;           // [H,D]
+    float* ds;                  // [n_dst,H], atomically accumulated
+    float* partial;             // [gridDim.x][F] per-workgroup da_l partial sums
+    int H, D, F;
+    int tag_shift;
+    float slope;
+};
+
+template <int VEC>
+struct BwdAcc {
+    float dz[VEC];   // sum_i alpha G_i
+    float dt;        // sum_i du   (this lane's head)
+};
+
+// Edges (destinations) idx[beg,end) of one source row.
+template <typename T, int G>
+__device__ inline void bwd_edges(BwdAcc<Vec<T>::N>& ac, const BwdScalars& a, const int32_t* idx, int beg,
+                                 int end, int chunk0, int stride, const LaneMap<T, G>& lm,
+                                 const float (&zj)[Vec<T>::N], float t2, bool pow2)
+{
+    constexpr int VEC = Vec<T>::N;
+    constexpr int SLOTS = kWave / G;
+    const T* Gp = static_cast<const T*>(a.G);
+    for (int cb = beg + chunk0 * kWave; cb < end; cb += stride * kWave) {
+        const int cnt = min(kWave, end - cb);
+        const int mine = (lm.lane < cnt) ? idx[cb + lm.lane] : 0;
+        for (int k0 = 0; k0 < cnt; k0 += SLOTS * kU) {
+            typename Vec<T>::Raw raw[kU];
+            float4 rec[kU];
+            int dst[kU];
+#pragma unroll
+            for (int k = 0; k < kU; ++k) {
+                const int ek = k0 + k * SLOTS + lm.slot;
+                const int i = __shfl(mine, ek & (kWave - 1));
+                dst[k] = (ek < cnt) ? i : -1;
+                raw[k] = Vec<T>::zero();
+                rec[k] = make_float4(0.f, INFINITY, 0.f, 0.f);   // L = +inf gives alpha = 0
+                if (ek < cnt) {
+                    rec[k] = a.rec[(int64_t)i * a.H + lm.h];
+                    if (lm.on) raw[k] = Vec<T>::load(Gp + (int64_t)i * a.F + lm.gl * VEC);
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < kU; ++k) {
+                float g[VEC];
+                Vec<T>::unpack(raw[k], g);
+                float c = 0.f;
+#pragma unroll
+                for (int x = 0; x < VEC; ++x) c = fmaf(g[x], zj[x], c);
+                c = pow2 ? group_sum_pow2(c, lm.lph) : group_sum_any(c, lm.head_first, lm.lph);
+                const float u2 = rec[k].x + t2;
+                const float alpha = fast_exp2(leaky(u2, a.slope) - rec[k].y);
+                const float de = alpha * (c - rec[k].z);
+                const float du = u2 > 0.f ? de : a.slope * de;
+#pragma unroll
+                for (int x = 0; x < VEC; ++x) ac.dz[x] = fmaf(alpha, g[x], ac.dz[x]);
+                ac.dt += du;
+                if (dst[k] >= 0 && lm.on && (lm.gl % lm.lph) == 0)
+                    unsafeAtomicAdd(a.ds + (int64_t)dst[k] * a.H + lm.h, du);
+            }
+        }
+    }
+}
+
+template <typename T, int G>
+__device__ inline void bwd_merge_slots(BwdAcc<Vec<T>::N>& ac)
+{
+#pragma unroll
+    for (int o = G; o < kWave; o <<= 1) {
+#pragma unroll
+        for (int x = 0; x < Vec<T>::N; ++x) ac.dz[x] += __shfl_xor(ac.dz[x], o);
+        ac.dt += __shfl_xor(ac.dt, o);
+    }
+}
+
+template <typename T, int G, bool ALL>
+__global__ __launch_bounds__(kGatherThreads) void k_gat_bwd(BwdArgs tabs, BwdScalars a)
+{
+    constexpr int VEC = Vec<T>::N;
+    __shared__ float part[kWavesPerWG][G][VEC + 1];
+    const LaneMap<T, G> lm(a.F, a.H, a.D);
+    const int wave = threadIdx.x / kWave;
+    const bool pow2 = is_pow2(lm.lph);
+    const uint32_t mask = ALL ? ((1u << a.tag_shift) - 1u) : 0xffffffffu;
+
+    float al[VEC], dal[VEC];
+#pragma unroll
+    for (int x = 0; x < VEC; ++x) {
+        al[x] = lm.on ? a.a_l[lm.gl * VEC + x] : 0.f;
+        dal[x] = 0.f;
+    }
+
+    // Source row j of block q: z_j and t_j stay in registers for all its edges.
+    auto row_inputs = [&](uint32_t id, int& q, int& j, float (&zj)[VEC], float& t2) {
+        q = ALL ? (int)(id >> a.tag_shift) : 0;
+        j = (int)(id & mask);
+        typename Vec<T>::Raw r = Vec<T>::zero();
+        if (lm.on) r = Vec<T>::load(static_cast<const T*>(tabs.Z[q]) + (int64_t)j * a.F + lm.gl * VEC);
+        Vec<T>::unpack(r, zj);
+        t2 = tabs.t[q][(int64_t)j * a.H + lm.h] * kLog2e;
+    };
+    // dZ_q[j] = sum alpha G + dt a_l ; dt_q[j] = dt ; da_l += dt z_j
+    auto row_outputs = [&](const BwdAcc<VEC>& ac, int q, int j, const float (&zj)[VEC]) {
+        if (lm.slot != 0 || !lm.on) return;
+        float v[VEC];
+#pragma unroll
+        for (int x = 0; x < VEC; ++x) {
+            v[x] = fmaf(ac.dt, al[x], ac.dz[x]);
+            dal[x] = fmaf(ac.dt, zj[x], dal[x]);
+        }
+        Vec<T>::store(static_cast<T*>(tabs.dZ[q]) + (int64_t)j * a.F + lm.gl * VEC, v);
+        if ((lm.gl % lm.lph) == 0) tabs.dt[q][(int64_t)j * a.H + lm.h] = ac.dt;
+    };
+
+    for (int64_t r = blockIdx.x; r < a.n_long; r += gridDim.x) {
+        int q, j;
+        float zj[VEC], t2;
+        row_inputs(a.rows[r], q, j, zj, t2);
+        BwdAcc<VEC> ac = {};
+        bwd_edges<T, G>(ac, a, tabs.t_indices[q], tabs.t_indptr[q][j], tabs.t_indptr[q][j + 1], wave,
+                        kWavesPerWG, lm, zj, t2, pow2);
+        bwd_merge_slots<T, G>(ac);
+        if (lm.slot == 0) {
+#pragma unroll
+            for (int x = 0; x < VEC; ++x) part[wave][lm.gl][x] = ac.dz[x];
+            part[wave][lm.gl][VEC] = ac.dt;
+        }
+        __syncthreads();
+        if (wave == 0) {
+#pragma unroll
+            for (int x = 0; x <= VEC; ++x) {
+                float s = 0.f;
+                for (int w = 0; w < kWavesPerWG; ++w) s += part[w][lm.gl][x];
+                if (x < VEC)
+                    ac.dz[x] = s;
+                else
+                    ac.dt = s;
+            }
+            row_outputs(ac, q, j, zj);
+        }
+        __syncthreads();
+    }
+    const int64_t n_waves = (int64_t)gridDim.x * kWavesPerWG;
+    for (int64_t r = a.n_long + (int64_t)blockIdx.x * kWavesPerWG + wave; r < a.n_rows; r += n_waves) {
+        int q, j;
+        float zj[VEC], t2;
+        row_inputs(a.rows[r], q, j, zj, t2);
+        BwdAcc<VEC> ac = {};
+        bwd_edges<T, G>(ac, a, tabs.t_indices[q], tabs.t_indptr[q][j], tabs.t_indptr[q][j + 1], 0, 1, lm,
+                        zj, t2, pow2);
+        bwd_merge_slots<T, G>(ac);
+        row_outputs(ac, q, j, zj);
+    }
+
+    // this workgroup's share of da_l = sum_j dt_j z_j
+    __syncthreads();
+    if (lm.slot == 0)
+#pragma unroll
+        for (int x = 0; x < VEC; ++x) part[wave][lm.gl][x] = dal[x];
+    __syncthreads();
+    if (wave == 0 && lm.slot == 0 && lm.on) {
+        float v[VEC];
+#pragma unroll
+        for (int x = 0; x < VEC; ++x) {
+            float s = 0.f;
+            for (int w = 0; w < kWavesPerWG; ++w) s += part[w][lm.gl][x];
+            v[x] = s;
+        }
+        store_f32<VEC>(a.partial + (int64_t)blockIdx.x * a.F + lm.gl * VEC, v);
+    }
+}
+
+// out[f] += sum_w partial[w][f]
+__global__ __launch_bounds__(256) void k_reduce_partials(const float* __restrict__ partial, int n_part,
+                                                         int F, float* __restrict__ out)
+{
+    __shared__ float red[256];
+    const int f = blockIdx.x;
+    float s = 0.f;
+    for (int w = threadIdx.x; w < n_part; w += 256) s += partial[(int64_t)w * F + f];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) out[f] += red[0];
+}
+
+// ---------------------------------------------------------------- node-wise
+
+// score[v,h] = <a[h], Z[v,h]>; one lane group per node.
+template <typename T, int G>
+__global__ __launch_bounds__(kGatherThreads) void k_scores(const T* __restrict__ Z, int64_t n, int H, int D,
+                                                           int F, const float* __restrict__ avec,
+                                                           float* __restrict__ score)
+{
+    constexpr int VEC = Vec<T>::N;
+    constexpr int SLOTS = kWave / G;
+    const LaneMap<T, G> lm(F, H, D);
+    const bool pow2 = is_pow2(lm.lph);
+    float av[VEC];
+#pragma unroll
+    for (int x = 0; x < VEC; ++x) av[x] = lm.on ? avec[lm.gl * VEC + x] : 0.f;
+    const int64_t wave_id = ((int64_t)blockIdx.x * kGatherThreads + threadIdx.x) / kWave;
+    const int64_t n_waves = (int64_t)gridDim.x * kWavesPerWG;
+    for (int64_t v0 = wave_id * SLOTS; v0 < n; v0 += n_waves * SLOTS) {
+        const int64_t v = v0 + lm.slot;
+        float z[VEC] = {};
+        if (v < n && lm.on) Vec<T>::unpack(Vec<T>::load(Z + v * F + lm.gl * VEC), z);
+        float c = 0.f;
+#pragma unroll
+        for (int x = 0; x < VEC; ++x) c = fmaf(av[x], z[x], c);
+        c = pow2 ? group_sum_pow2(c, lm.lph) : group_sum_any(c, lm.head_first, lm.lph);
+        if (v < n && lm.on && (lm.gl % lm.lph) == 0) score[v * H + lm.h] = c;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_fwd_begin(float* __restrict__ m, float* __restrict__ l,
+                                                   float* __restrict__ acc, int64_t n_h, int64_t n_f)
+{
+    for (int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x; k < n_f; k += (int64_t)gridDim.x * 256) {
+        acc[k] = 0.f;
+        if (k < n_h) {
+            m[k] = -INFINITY;
+            l[k] = 0.f;
+        }
+    }
+}
+
+template <typename T, int G>
+__global__ __launch_bounds__(kGatherThreads) void k_fwd_end(const float* __restrict__ m,
+                                                            const float* __restrict__ l,
+                                                            const float* __restrict__ acc, T* __restrict__ out,
+                                                            float* __restrict__ L, int64_t n, int H, int D, int F)
+{
+    constexpr int VEC = Vec<T>::N;
+    constexpr int SLOTS = kWave / G;
+    const LaneMap<T, G> lm(F, H, D);
+    const int64_t wave_id = ((int64_t)blockIdx.x * kGatherThreads + threadIdx.x) / kWave;
+    const int64_t n_waves = (int64_t)gridDim.x * kWavesPerWG;
+    for (int64_t v0 = wave_id * SLOTS; v0 < n; v0 += n_waves * SLOTS) {
+        const int64_t v = v0 + lm.slot;
+        if (v >= n || !lm.on) continue;
+        const float lv = l[v * H + lm.h];
+        const float inv = lv > 0.f ? 1.f / lv : 0.f;
+        float a[VEC];
+        load_f32<VEC>(acc + v * F + lm.gl * VEC, a);
+#pragma unroll
+        for (int x = 0; x < VEC; ++x) a[x] *= inv;
+        Vec<T>::store(out + v * F + lm.gl * VEC, a);
+        if ((lm.gl % lm.lph) == 0) L[v * H + lm.h] = lv > 0.f ? m[v * H + lm.h] + fast_log2(lv) * kLn2 : -INFINITY;
+    }
+}
+
+// rec[i,h] = (s log2e, L log2e, <G_i, out_i>, 0) and ds = 0
+template <typename T, int G>
+__global__ __launch_bounds__(kGatherThreads) void k_bwd_begin(const T* __restrict__ Gr, const T* __restrict__ out,
+                                                              const float* __restrict__ s,
+                                                              const float* __restrict__ L, float4* __restrict__ rec,
+                                                              float* __restrict__ ds, int64_t n, int H, int D, int F)
+{
+    constexpr int VEC = Vec<T>::N;
+    constexpr int SLOTS = kWave / G;
+    const LaneMap<T, G> lm(F, H, D);
+    const bool pow2 = is_pow2(lm.lph);
+    const int64_t wave_id = ((int64_t)blockIdx.x * kGatherThreads + threadIdx.x) / kWave;
+    const int64_t n_waves = (int64_t)gridDim.x * kWavesPerWG;
+    for (int64_t v0 = wave_id * SLOTS; v0 < n; v0 += n_waves * SLOTS) {
+        const int64_t v = v0 + lm.slot;
+        float g[VEC] = {}, o[VEC] = {};
+        if (v < n && lm.on) {
+            Vec<T>::unpack(Vec<T>::load(Gr + v * F + lm.gl * VEC), g);
+            Vec<T>::unpack(Vec<T>::load(out + v * F + lm.gl * VEC), o);
+        }
+        float c = 0.f;
+#pragma unroll
+        for (int x = 0; x < VEC; ++x) c = fmaf(g[x], o[x], c);
+        c = pow2 ? group_sum_pow2(c, lm.lph) : group_sum_any(c, lm.head_first, lm.lph);
+        if (v < n && lm.on && (lm.gl % lm.lph) == 0) {
+            const int64_t k = v * H + lm.h;
+            rec[k] = make_float4(s[k] * kLog2e, L[k] * kLog2e, c, 0.f);
+            ds[k] = 0.f;
+        }
+    }
+}
+
+// dZdst[i] = ds[i] a_r ; per-workgroup partial of da_r = sum_i ds[i] Zdst[i]
+template <typename T, int G>
+__global__ __launch_bounds__(kGatherThreads) void k_bwd_end(const T* __restrict__ Zdst, const float* __restrict__ ds,
+                                                            const float* __restrict__ a_r, T* __restrict__ dZdst,
+                                                            float* __restrict__ partial, int64_t n, int H, int D,
+                                                            int F)
+{
+    constexpr int VEC = Vec<T>::N;
+    constexpr int SLOTS = kWave / G;
+    __shared__ float part[kWavesPerWG][kWave][VEC];
+    const LaneMap<T, G> lm(F, H, D);
+    const int wave = threadIdx.x / kWave;
+    float ar[VEC], dar[VEC];
+#pragma unroll
+    for (int x = 0; x < VEC; ++x) {
+        ar[x] = lm.on ? a_r[lm.gl * VEC + x] : 0.f;
+        dar[x] = 0.f;
+    }
+    const int64_t wave_id = (int64_t)blockIdx.x * kWavesPerWG + wave;
+    const int64_t n_waves = (int64_t)gridDim.x * kWavesPerWG;
+    for (int64_t v0 = wave_id * SLOTS; v0 < n; v0 += n_waves * SLOTS) {
+        const int64_t v = v0 + lm.slot;
+        if (v >= n || !lm.on) continue;
+        const float d = ds[v * H + lm.h];
+        float z[VEC], o[VEC];
+        Vec<T>::unpack(Vec<T>::load(Zdst + v * F + lm.gl * VEC), z);
+#pragma unroll
+        for (int x = 0; x < VEC; ++x) {
+            o[x] = d * ar[x];
+            dar[x] = fmaf(d, z[x], dar[x]);
+        }
+        Vec<T>::store(dZdst + v * F + lm.gl * VEC, o);
+    }
+#pragma unroll
+    for (int x = 0; x < VEC; ++x) part[wave][lm.lane][x] = dar[x];
+    __syncthreads();
+    if (wave == 0 && lm.slot == 0 && lm.on) {
+        float v[VEC];
+#pragma unroll
+        for (int x = 0; x < VEC; ++x) {
+            float s = 0.f;
+            for (int w = 0; w < kWavesPerWG; ++w)
+                for (int sl = 0; sl < SLOTS; ++sl) s += part[w][sl * G + lm.gl][x];
+            v[x] = s;
+        }
+        store_f32<VEC>(partial + (int64_t)blockIdx.x * F + lm.gl * VEC, v);
+    }
+}
+
+// Rows the launch lists skip (no edge): typed row = 0, per-head scalar = fill.
+template <typename T>
+__global__ __launch_bounds__(256) void k_fill_rows_without_edges(const int32_t* __restrict__ indptr, int64_t n,
+                                                                 int H, int F, T* __restrict__ rows_out,
+                                                                 float* __restrict__ per_head, float fill)
+{
+    const int64_t total = n * F;
+    for (int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x; k < total; k += (int64_t)gridDim.x * 256) {
+        const int64_t i = k / F;
+        if (indptr[i + 1] != indptr[i]) continue;
+        rows_out[k] = T{};
+        const int f = (int)(k - i * F);
+        if (per_head && f < H) per_head[i * H + f] = fill;
+    }
+}
+
+// --------------------------------------------------------------- host side
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_shape(int dtype, int H, int D)
+{
+    if (dtype != SAR_F32 && dtype != SAR_BF16)
+        return sar::fail(SAR_ERR_UNSUPPORTED, "dtype %d is neither SAR_F32 nor SAR_BF16", dtype);
+    const int vec = dtype == SAR_F32 ? 4 : 8;
+    if (H <= 0 || D <= 0) return sar::fail(SAR_ERR_INVALID_ARG, "H and D must be positive (H=%d, D=%d)", H, D);
+    if (D % vec != 0)
+        return sar::fail(SAR_ERR_UNSUPPORTED, "D=%d must be a multiple of %d for this dtype", D, vec);
+    if ((int64_t)H * D / vec > 64)
+        return sar::fail(SAR_ERR_UNSUPPORTED, "row of H*D=%d values is wider than 1024 bytes", H * D);
+    return SAR_OK;
+}
+
+unsigned persistent_grid(int64_t n_rows, int64_t n_long)
+{
+    const int64_t want = n_long + (n_rows - n_long + kWavesPerWG - 1) / kWavesPerWG;
+    return (unsigned)std::max<int64_t>(1, std::min<int64_t>(want, kMaxPersistentWGs));
+}
+
+unsigned nodewise_grid(int64_t n, int slots)
+{
+    const int64_t waves = (n + slots - 1) / slots;
+    return (unsigned)std::max<int64_t>(1, std::min<int64_t>((waves + kWavesPerWG - 1) / kWavesPerWG, kMaxPersistentWGs));
+}
+
+#define SAR_DISPATCH_G(T, F, CALL)                                                   \
+    switch (lanes_for((F), Vec<T>::N)) {                                             \
+        case 4: { constexpr int kG = 4; CALL; } break;                                \
+        case 8: { constexpr int kG = 8; CALL; } break;                                \
+        case 16: { constexpr int kG = 16; CALL; } break;                              \
+        case 32: { constexpr int kG = 32; CALL; } break;                              \
+        default: { constexpr int kG = 64; CALL; } break;                              \
+    }
+
+template <typename T, bool ALL>
+int launch_fwd(const FwdArgs& a, const PtrTab& zt, const PtrTab& tt, int P, hipStream_t st)
+{
+    if (a.n_rows == 0) return SAR_OK;
+    const unsigned grid = persistent_grid(a.n_rows, a.n_long);
+    SAR_DISPATCH_G(T, a.F, (k_gat_fwd<T, kG, ALL><<<grid, kGatherThreads, 0, st>>>(a, zt, tt, P)));
+    SAR_LAUNCH_CHECK();
+    return SAR_OK;
+}
+
+template <typename T, bool ALL>
+int launch_bwd(const BwdArgs& tabs, BwdScalars& a, float* da_l, hipStream_t st)
+{
+    if (a.n_rows == 0) return SAR_OK;
+    const unsigned grid = persistent_grid(a.n_rows, a.n_long);
+    SAR_DISPATCH_G(T, a.F, (k_gat_bwd<T, kG, ALL><<<grid, kGatherThreads, 0, st>>>(tabs, a)));
+    SAR_LAUNCH_CHECK();
+    k_reduce_partials<<<a.F, 256, 0, st>>>(a.partial, (int)grid, a.F, da_l);
+    SAR_LAUNCH_CHECK();
+    return SAR_OK;
+}
+
+size_t workspace_bytes(int F) { return (size_t)kMaxPersistentWGs * F * sizeof(float); }
+
+}  // namespace
+
+extern "C" int sar_gat_scores(const void* Z, int dtype, int64_t n, int H, int D, const float* a,
+                              float* score, void* stream)
+{
+    SAR_TRY(check_shape(dtype, H, D));
+    SAR_CHECK_ARG(n >= 0, "n is negative");
+    if (n == 0) return SAR_OK;
+    SAR_CHECK_ARG(Z && a && score, "Z, a or score is null");
+    SAR_CHECK_ARG(aligned16(Z), "Z must be 16-byte aligned");
+    const int F = H * D;
+    hipStream_t st = sar::as_stream(stream);
+    if (dtype == SAR_F32) {
+        SAR_DISPATCH_G(float, F, (k_scores<float, kG><<<nodewise_grid(n, kWave / kG), kGatherThreads, 0, st>>>(
+                                     static_cast<const float*>(Z), n, H, D, F, a, score)));
+    } else {
+        SAR_DISPATCH_G(bf16_t, F, (k_scores<bf16_t, kG><<<nodewise_grid(n, kWave / kG), kGatherThreads, 0, st>>>(
+                                      static_cast<const bf16_t*>(Z), n, H, D, F, a, score)));
+    }
+    SAR_LAUNCH_CHECK();
+    return SAR_OK;
+}
+
+extern "C" int sar_gat_fwd_begin(float* m, float* l, float* acc, int64_t n_dst, int H, int D, void* stream)
+{
+    SAR_CHECK_ARG(n_dst >= 0 && H > 0 && D > 0, "need n_dst >= 0, H > 0, D > 0");
+    if (n_dst == 0) return SAR_OK;
+    SAR_CHECK_ARG(m && l && acc, "m, l or acc is null");
+    const int64_t n_f = n_dst * H * D;
+    const unsigned grid = (unsigned)std::min<int64_t>((n_f + 255) / 256, 1 << 20);
+    k_fwd_begin<<<grid, 256, 0, sar::as_stream(stream)>>>(m, l, acc, n_dst * H, n_f);
+    SAR_LAUNCH_CHECK();
+    return SAR_OK;
+}
+
+extern "C" int sar_gat_fwd_block(const sar_blocks_t* b, int q, const void* Zq, const float* s,
+                                 const float* tq, int dtype, int H, int D, float slope, float* m, float* l,
+                                 float* acc, void* stream)
+{
+    SAR_CHECK_ARG(b != nullptr, "handle is null");
+    SAR_CHECK_ARG(q >= 0 && q < b->P, "block %d out of range [0,%d)", q, b->P);
+    SAR_TRY(check_shape(dtype, H, D));
+    const sar::Block& k = b->blk[q];
+    if (k.n_rows == 0) return SAR_OK;
+    SAR_CHECK_ARG(Zq && s && tq && m && l && acc, "a tensor argument is null");
+    SAR_CHECK_ARG(aligned16(Zq) && aligned16(acc), "Zq and acc must be 16-byte aligned");
+    FwdArgs a{};
+    a.indptr = k.indptr;
+    a.indices = reinterpret_cast<const uint32_t*>(k.indices);
+    a.rows = reinterpret_cast<const uint32_t*>(k.rows);
+    a.n_rows = k.n_rows;
+    a.n_long = k.n_long;
+    a.Z = Zq;
+    a.t = tq;
+    a.s = s;
+    a.m = m;
+    a.l = l;
+    a.acc = acc;
+    a.H = H;
+    a.D = D;
+    a.F = H * D;
+    a.slope = slope;
+    PtrTab none{};
+    if (dtype == SAR_F32) return launch_fwd<float, false>(a, none, none, 0, sar::as_stream(stream));
+    return launch_fwd<bf16_t, false>(a, none, none, 0, sar::as_stream(stream));
+}
+
+extern "C" int sar_gat_fwd_end(const float* m, const float* l, const float* acc, void* out, float* L,
+                               int dtype, int64_t n_dst, int H, int D, void* stream)
+{
+    SAR_TRY(check_shape(dtype, H, D));
+    SAR_CHECK_ARG(n_dst >= 0, "n_dst is negative");
+    if (n_dst == 0) return SAR_OK;
+    SAR_CHECK_ARG(m && l && acc && out && L, "a tensor argument is null");
+    SAR_CHECK_ARG(aligned16(acc) && aligned16(out), "acc and out must be 16-byte aligned");
+    const int F = H * D;
+    hipStream_t st = sar::as_stream(stream);
+    if (dtype == SAR_F32) {
+        SAR_DISPATCH_G(float, F, (k_fwd_end<float, kG><<<nodewise_grid(n_dst, kWave / kG), kGatherThreads, 0, st>>>(
+                                     m, l, acc, static_cast<float*>(out), L, n_dst, H, D, F)));
+    } else {
+        SAR_DISPATCH_G(bf16_t, F, (k_fwd_end<bf16_t, kG><<<nodewise_grid(n_dst, kWave / kG), kGatherThreads, 0, st>>>(
+                                      m, l, acc, static_cast<bf16_t*>(out), L, n_dst, H, D, F)));
+    }
+    SAR_LAUNCH_CHECK();
+    return SAR_OK;
+}
+
+extern "C" int sar_gat_fwd_all(const sar_blocks_t* b, const void* const* Zq, const float* s,
+                               const float* const* tq, int dtype, int H, int D, float slope, void* out,
+                               float* L, void* stream)
+{
+    SAR_CHECK_ARG(b != nullptr, "handle is null");
+    SAR_TRY(check_shape(dtype, H, D));
+    if (!b->f_indptr) return sar::fail(SAR_ERR_STATE, "handle was built without SAR_BUILD_FUSED");
+    if (b->n_dst == 0) return SAR_OK;
+    SAR_CHECK_ARG(Zq && tq && s && out && L, "a tensor argument is null");
+    SAR_CHECK_ARG(aligned16(out), "out must be 16-byte aligned");
+    PtrTab zt{}, tt{};
+    for (int q = 0; q < b->P; ++q) {
+        SAR_CHECK_ARG((Zq[q] && tq[q]) || b->blk[q].nnz == 0, "Zq[%d] or tq[%d] is null", q, q);
+        SAR_CHECK_ARG(aligned16(Zq[q]), "Zq[%d] must be 16-byte aligned", q);
+        zt.p[q] = Zq[q];
+        tt.p[q] = tq[q];
+    }
+    hipStream_t st = sar::as_stream(stream);
+    FwdArgs a{};
+    a.indptr = b->f_indptr;
+    a.indices = b->f_indices;
+    a.rows = reinterpret_cast<const uint32_t*>(b->f_rows);
+    a.n_rows = b->n_f_rows;
+    a.n_long = b->n_f_long;
+    a.s = s;
+    a.out = out;
+    a.L = L;
+    a.H = H;
+    a.D = D;
+    a.F = H * D;
+    a.tag_shift = b->tag_shift;
+    a.slope = slope;
+    if (b->n_f_rows < b->n_dst) {
+        // destinations without any in-edge: out = 0, L = -inf
+        const unsigned gz = (unsigned)std::min<int64_t>((b->n_dst * a.F + 255) / 256, 1 << 16);
+        if (dtype == SAR_F32)
+            k_fill_rows_without_edges<float><<<gz, 256, 0, st>>>(b->f_indptr, b->n_dst, H, a.F,
+                                                                 static_cast<float*>(out), L, -INFINITY);
+        else
+            k_fill_rows_without_edges<bf16_t><<<gz, 256, 0, st>>>(b->f_indptr, b->n_dst, H, a.F,
+                                                                  static_cast<bf16_t*>(out), L, -INFINITY);
+        SAR_LAUNCH_CHECK();
+    }
+    int rc;
+    if (dtype == SAR_F32)
+        rc = launch_fwd<float, true>(a, zt, tt, b->P, st);
+    else
+        rc = launch_fwd<bf16_t, true>(a, zt, tt, b->P, st);
+    return rc;
+}
+
+extern "C" int sar_gat_workspace_bytes(int64_t n_dst, int64_t n_src_max, int H, int D, size_t* bytes)
+{
+    SAR_CHECK_ARG(bytes != nullptr, "bytes is null");
+    SAR_CHECK_ARG(n_dst >= 0 && n_src_max >= 0 && H > 0 && D > 0, "sizes must be non-negative, H and D positive");
+    *bytes = workspace_bytes(H * D);
+    return SAR_OK;
+}
+
+extern "C" int sar_gat_bwd_begin(const void* G, const void* out, const float* s, const float* L, int dtype,
+                                 float* rec, float* ds, int64_t n_dst, int H, int D, void* stream)
+{
+    SAR_TRY(check_shape(dtype, H, D));
+    SAR_CHECK_ARG(n_dst >= 0, "n_dst is negative");
+    if (n_dst == 0) return SAR_OK;
+    SAR_CHECK_ARG(G && out && s && L && rec && ds, "a tensor argument is null");
+    SAR_CHECK_ARG(aligned16(G) && aligned16(out) && aligned16(rec), "G, out and rec must be 16-byte aligned");
+    const int F = H * D;
+    hipStream_t st = sar::as_stream(stream);
+    if (dtype == SAR_F32) {
+        SAR_DISPATCH_G(float, F, (k_bwd_begin<float, kG><<<nodewise_grid(n_dst, kWave / kG), kGatherThreads, 0, st>>>(
+                                     static_cast<const float*>(G), static_cast<const float*>(out), s, L,
+                                     reinterpret_cast<float4*>(rec), ds, n_dst, H, D, F)));
+    } else {
+        SAR_DISPATCH_G(bf16_t, F, (k_bwd_begin<bf16_t, kG><<<nodewise_grid(n_dst, kWave / kG), kGatherThreads, 0, st>>>(
+                                      static_cast<const bf16_t*>(G), static_cast<const bf16_t*>(out), s, L,
+                                      reinterpret_cast<float4*>(rec), ds, n_dst, H, D, F)));
+    }
+    SAR_LAUNCH_CHECK();
+    return SAR_OK;
+}
+
+namespace {
+
+template <typename T>
+int zero_untouched_sources(const sar::Block& k, int H, int F, void* dZq, float* dtq, hipStream_t st)
+{
+    if (k.n_t_rows == k.n_src) return SAR_OK;
+    const unsigned gz = (unsigned)std::min<int64_t>((k.n_src * F + 255) / 256, 1 << 16);
+    k_fill_rows_without_edges<T><<<gz, 256, 0, st>>>(k.t_indptr, k.n_src, H, F, static_cast<T*>(dZq), dtq, 0.f);
+    SAR_LAUNCH_CHECK();
+    return SAR_OK;
+}
+
+int bwd_common_checks(const sar_blocks_t* b, int dtype, int H, int D, const void* G, const float* rec,
+                      const float* a_l, const float* ds, const float* da_l, const void* work, size_t work_bytes)
+{
+    SAR_CHECK_ARG(b != nullptr, "handle is null");
+    SAR_TRY(check_shape(dtype, H, D));
+    if (!(b->flags & SAR_BUILD_TRANSPOSE))
+        return sar::fail(SAR_ERR_STATE, "handle was built without SAR_BUILD_TRANSPOSE");
+    SAR_CHECK_ARG(G && rec && a_l && ds && da_l, "a tensor argument is null");
+    SAR_CHECK_ARG(aligned16(G) && aligned16(rec), "G and rec must be 16-byte aligned");
+    SAR_CHECK_ARG(work != nullptr && aligned16(work), "work is null or not 16-byte aligned");
+    SAR_CHECK_ARG(work_bytes >= workspace_bytes(H * D), "work_bytes=%zu is below the %zu bytes required",
+                  work_bytes, workspace_bytes(H * D));
+    return SAR_OK;
+}
+
+}  // namespace
+
+extern "C" int sar_gat_bwd_block(const sar_blocks_t* b, int q, const void* Zq, const void* G, const float* tq,
+                                 const float* rec, const float* a_l, int dtype, int H, int D, float slope,
+                                 void* dZq, float* dtq, float* ds, float* da_l, void* work, size_t work_bytes,
+                                 void* stream)
+{
+    SAR_TRY(bwd_common_checks(b, dtype, H, D, G, rec, a_l, ds, da_l, work, work_bytes));
+    SAR_CHECK_ARG(q >= 0 && q < b->P, "block %d out of range [0,%d)", q, b->P);
+    const sar::Block& k = b->blk[q];
+    if (k.n_src == 0) return SAR_OK;
+    SAR_CHECK_ARG(Zq && tq && dZq && dtq, "a tensor argument is null");
+    SAR_CHECK_ARG(aligned16(Zq) && aligned16(dZq), "Zq and dZq must be 16-byte aligned");
+    hipStream_t st = sar::as_stream(stream);
+    BwdArgs tabs{};
+    tabs.t_indptr[0] = k.t_indptr;
+    tabs.t_indices[0] = k.t_indices;
+    tabs.Z[0] = Zq;
+    tabs.t[0] = tq;
+    tabs.dZ[0] = dZq;
+    tabs.dt[0] = dtq;
+    BwdScalars a{};
+    a.rows = reinterpret_cast<const uint32_t*>(k.t_rows);
+    a.n_rows = k.n_t_rows;
+    a.n_long = k.n_t_long;
+    a.G = G;
+    a.rec = reinterpret_cast<const float4*>(rec);
+    a.a_l = a_l;
+    a.ds = ds;
+    a.partial = static_cast<float*>(work);
+    a.H = H;
+    a.D = D;
+    a.F = H * D;
+    a.slope = slope;
+    if (dtype == SAR_F32) {
+        SAR_TRY(zero_untouched_sources<float>(k, H, a.F, dZq, dtq, st));
+        return launch_bwd<float, false>(tabs, a, da_l, st);
+    }
+    SAR_TRY(zero_untouched_sources<bf16_t>(k, H, a.F, dZq, dtq, st));
+    return launch_bwd<bf16_t, false>(tabs, a, da_l, st);
+}
+
+extern "C" int sar_gat_bwd_all(const sar_blocks_t* b, const void* const* Zq, const void* G,
+                               const float* const* tq, const float* rec, const float* a_l, int dtype, int H,
+                               int D, float slope, void* const* dZq, float* const* dtq, float* ds, float* da_l,
+                               void* work, size_t work_bytes, void* stream)
+{
+    SAR_TRY(bwd_common_checks(b, dtype, H, D, G, rec, a_l, ds, da_l, work, work_bytes));
+    SAR_CHECK_ARG(Zq && tq && dZq && dtq, "a pointer table is null");
+    hipStream_t st = sar::as_stream(stream);
+    BwdArgs tabs{};
+    const int F = H * D;
+    for (int q = 0; q < b->P; ++q) {
+        const sar::Block& k = b->blk[q];
+        if (k.n_src == 0) continue;
+        SAR_CHECK_ARG(Zq[q] && tq[q] && dZq[q] && dtq[q], "a tensor of block %d is null", q);
+        SAR_CHECK_ARG(aligned16(Zq[q]) && aligned16(dZq[q]), "Zq[%d] and dZq[%d] must be 16-byte aligned", q, q);
+        tabs.t_indptr[q] = k.t_indptr;
+        tabs.t_indices[q] = k.t_indices;
+        tabs.Z[q] = Zq[q];
+        tabs.t[q] = tq[q];
+        tabs.dZ[q] = dZq[q];
+        tabs.dt[q] = dtq[q];
+        if (dtype == SAR_F32)
+            SAR_TRY(zero_untouched_sources<float>(k, H, F, dZq[q], dtq[q], st));
+        else
+            SAR_TRY(zero_untouched_sources<bf16_t>(k, H, F, dZq[q], dtq[q], st));
+    }
+    BwdScalars a{};
+    a.rows = b->ft_rows;
+    a.n_rows = b->n_ft_rows;
+    a.n_long = b->n_ft_long;
+    a.G = G;
+    a.rec = reinterpret_cast<const float4*>(rec);
+    a.a_l = a_l;
+    a.ds = ds;
+    a.partial = static_cast<float*>(work);
+    a.H = H;
+    a.D = D;
+    a.F = F;
+    a.tag_shift = b->tag_shift;
+    a.slope = slope;
+    if (dtype == SAR_F32) return launch_bwd<float, true>(tabs, a, da_l, st);
+    return launch_bwd<bf16_t, true>(tabs, a, da_l, st);
+}
+
+extern "C" int sar_gat_bwd_end(const void* Zdst, const float* ds, const float* a_r, void* dZdst, float* da_r,
+                               int dtype, int64_t n_dst, int H, int D, void* work, size_t work_bytes,
+                               void* stream)
+{
+    SAR_TRY(check_shape(dtype, H, D));
+    SAR_CHECK_ARG(n_dst >= 0, "n_dst is negative");
+    if (n_dst == 0) return SAR_OK;
+    SAR_CHECK_ARG(Zdst && ds && a_r && dZdst && da_r, "a tensor argument is null");
+    SAR_CHECK_ARG(aligned16(Zdst) && aligned16(dZdst), "Zdst and dZdst must be 16-byte aligned");
+    SAR_CHECK_ARG(work != nullptr && aligned16(work), "work is null or not 16-byte aligned");
+    const int F = H * D;
+    SAR_CHECK_ARG(work_bytes >= workspace_bytes(F), "work_bytes=%zu is below the %zu bytes required", work_bytes,
+                  workspace_bytes(F));
+    hipStream_t st = sar::as_stream(stream);
+    unsigned grid = 1;
+    if (dtype == SAR_F32) {
+        SAR_DISPATCH_G(float, F, (grid = nodewise_grid(n_dst, kWave / kG),
+                                  k_bwd_end<float, kG><<<grid, kGatherThreads, 0, st>>>(
+                                      static_cast<const float*>(Zdst), ds, a_r, static_cast<float*>(dZdst),
+                                      static_cast<float*>(work), n_dst, H, D, F)));
+    } else {
+        SAR_DISPATCH_G(bf16_t, F, (grid = nodewise_grid(n_dst, kWave / kG),
+                                   k_bwd_end<bf16_t, kG><<<grid, kGatherThreads, 0, st>>>(
+                                       static_cast<const bf16_t*>(Zdst), ds, a_r, static_cast<bf16_t*>(dZdst),
+                                       static_cast<float*>(work), n_dst, H, D, F)));
+    }
+    SAR_LAUNCH_CHECK();
+    k_reduce_partials<<<F, 256, 0, st>>>(static_cast<const float*>(work), (int)grid, F, da_r);
+    SAR_LAUNCH_CHECK();
+    return SAR_OK;
+}

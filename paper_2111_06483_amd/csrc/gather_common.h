@@ -1,0 +1,159 @@
+// Device helpers shared by the row-gather kernels (sum/mean aggregation and
+// the fused attention kernels).
+//
+// Mapping used throughout: a feature row of F values is covered by G lanes of
+// a 64-wide wavefront, each lane owning VEC consecutive values moved with one
+// 16-byte access (4 fp32 or 8 bf16).  G is the power of two >= F/VEC, so a
+// 1 KiB fp32 row (F = 256) is one fully coalesced wave-wide load.  When G < 64
+// the wavefront is cut into SLOTS = 64/G lane groups that work on different
+// edges of the same row and are merged at the end.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sar {
+
+struct bf16_t {
+    uint16_t bits;
+};
+
+constexpr int kWave = 64;
+constexpr int kGatherThreads = 256;          // 4 wavefronts per workgroup
+constexpr int kWavesPerWG = kGatherThreads / kWave;
+constexpr int kMaxPersistentWGs = 256 * 8;   // 256 CUs x 8 resident workgroups
+
+template <typename T>
+struct Vec;
+
+template <>
+struct Vec<float> {
+    static constexpr int N = 4;
+    using Raw = float4;
+    static __device__ inline Raw load(const float* p) { return *reinterpret_cast<const float4*>(p); }
+    static __device__ inline Raw zero() { return make_float4(0.f, 0.f, 0.f, 0.f); }
+    static __device__ inline void unpack(const Raw& r, float (&v)[4])
+    {
+        v[0] = r.x;
+        v[1] = r.y;
+        v[2] = r.z;
+        v[3] = r.w;
+    }
+    static __device__ inline void store(float* p, const float (&v)[4])
+    {
+        *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    }
+};
+
+__device__ inline uint32_t f32_to_bf16_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;   // keep NaN a NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+template <>
+struct Vec<bf16_t> {
+    static constexpr int N = 8;
+    using Raw = uint4;
+    static __device__ inline Raw load(const bf16_t* p) { return *reinterpret_cast<const uint4*>(p); }
+    static __device__ inline Raw zero() { return make_uint4(0u, 0u, 0u, 0u); }
+    static __device__ inline void unpack(const Raw& r, float (&v)[8])
+    {
+        v[0] = __uint_as_float(r.x << 16);
+        v[1] = __uint_as_float(r.x & 0xffff0000u);
+        v[2] = __uint_as_float(r.y << 16);
+        v[3] = __uint_as_float(r.y & 0xffff0000u);
+        v[4] = __uint_as_float(r.z << 16);
+        v[5] = __uint_as_float(r.z & 0xffff0000u);
+        v[6] = __uint_as_float(r.w << 16);
+        v[7] = __uint_as_float(r.w & 0xffff0000u);
+    }
+    static __device__ inline void store(bf16_t* p, const float (&v)[8])
+    {
+        uint4 r;
+        r.x = f32_to_bf16_rne(v[0]) | (f32_to_bf16_rne(v[1]) << 16);
+        r.y = f32_to_bf16_rne(v[2]) | (f32_to_bf16_rne(v[3]) << 16);
+        r.z = f32_to_bf16_rne(v[4]) | (f32_to_bf16_rne(v[5]) << 16);
+        r.w = f32_to_bf16_rne(v[6]) | (f32_to_bf16_rne(v[7]) << 16);
+        *reinterpret_cast<uint4*>(p) = r;
+    }
+};
+
+// fp32 rows of VEC values (the accumulator rows), 16 bytes at a time
+template <int N>
+__device__ inline void load_f32(const float* p, float (&v)[N])
+{
+#pragma unroll
+    for (int k = 0; k < N; k += 4) {
+        const float4 x = *reinterpret_cast<const float4*>(p + k);
+        v[k] = x.x;
+        v[k + 1] = x.y;
+        v[k + 2] = x.z;
+        v[k + 3] = x.w;
+    }
+}
+template <int N>
+__device__ inline void store_f32(float* p, const float (&v)[N])
+{
+#pragma unroll
+    for (int k = 0; k < N; k += 4)
+        *reinterpret_cast<float4*>(p + k) = make_float4(v[k], v[k + 1], v[k + 2], v[k + 3]);
+}
+
+__device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ inline float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// Sum over the `width` (power of two, <= 64) consecutive lanes that hold one
+// head; every lane of the group receives the total.
+__device__ inline float group_sum_pow2(float v, int width)
+{
+    for (int o = 1; o < width; o <<= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+// Sum over `width` consecutive lanes starting at lane `first` for any width.
+__device__ inline float group_sum_any(float v, int first, int width)
+{
+    float s = 0.f;
+    for (int k = 0; k < width; ++k) s += __shfl(v, first + k);
+    return s;
+}
+
+__device__ inline bool is_pow2(int x) { return (x & (x - 1)) == 0; }
+
+// Geometry of one lane inside the row mapping.
+template <typename T, int G>
+struct LaneMap {
+    static constexpr int VEC = Vec<T>::N;
+    static constexpr int SLOTS = kWave / G;
+    int lane, gl, slot;   // lane in wave, lane in group, group index
+    int h;                // head owned by this lane (clamped for idle lanes)
+    int lph;              // lanes per head = D / VEC
+    int head_first;       // first lane (in wave) of this lane's head group
+    bool on;              // lane covers real features
+    __device__ inline LaneMap(int F, int H, int D)
+    {
+        lane = threadIdx.x & (kWave - 1);
+        gl = lane & (G - 1);
+        slot = lane / G;
+        on = gl * VEC < F;
+        lph = D / VEC;
+        const int hh = (gl * VEC) / D;
+        h = hh < H ? hh : H - 1;
+        head_first = slot * G + h * lph;
+    }
+};
+
+inline int lanes_for(int F, int vec)
+{
+    int need = (F + vec - 1) / vec, g = 4;
+    while (g < need) g <<= 1;
+    return g;
+}
+
+}  // namespace sar

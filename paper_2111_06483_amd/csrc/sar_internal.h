@@ -1,0 +1,80 @@
+// Internal declarations shared by the translation units of libsar_mi355x.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "../../include/sar_mi355x.h"
+
+namespace sar {
+
+// Records the message for sar_last_error() and returns `code`.
+int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+void clear_error();
+
+#define SAR_HIP(expr)                                                                   \
+    do {                                                                                \
+        hipError_t sar_e_ = (expr);                                                     \
+        if (sar_e_ != hipSuccess)                                                       \
+            return ::sar::fail(SAR_ERR_HIP, "%s failed: %s", #expr,                     \
+                               hipGetErrorString(sar_e_));                              \
+    } while (0)
+
+#define SAR_CHECK_ARG(cond, ...)                                                        \
+    do {                                                                                \
+        if (!(cond)) return ::sar::fail(SAR_ERR_INVALID_ARG, __VA_ARGS__);              \
+    } while (0)
+
+#define SAR_TRY(expr)                                                                   \
+    do {                                                                                \
+        int sar_rc_ = (expr);                                                           \
+        if (sar_rc_ != SAR_OK) return sar_rc_;                                          \
+    } while (0)
+
+#define SAR_LAUNCH_CHECK() SAR_HIP(hipGetLastError())
+
+// Rows (or sources) with at least this many edges in a block are "long": they
+// are handled by a whole workgroup instead of one wavefront.  A power of two
+// so that it coincides with a degree-class boundary.
+constexpr int kLongRow = 512;
+constexpr int kLongClass = 10;  // 1 + log2(kLongRow)
+constexpr int kNumClasses = 32;
+
+struct Block {
+    int64_t n_dst = 0, n_src = 0, nnz = 0;
+    const int32_t* indptr = nullptr;
+    const int32_t* indices = nullptr;
+    int32_t* t_indptr = nullptr;
+    int32_t* t_indices = nullptr;
+    int32_t* rows = nullptr;
+    int64_t n_rows = 0, n_long = 0;
+    int32_t* t_rows = nullptr;
+    int64_t n_t_rows = 0, n_t_long = 0;
+    int32_t* touched = nullptr;
+};
+
+inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+
+}  // namespace sar
+
+struct sar_blocks {
+    int P = 0;
+    int64_t n_dst = 0;
+    int flags = 0;
+    std::vector<sar::Block> blk;
+    int32_t* deg = nullptr;
+    // All-blocks destination-major index: row i lists its sources block after
+    // block (q ascending), each entry (q << tag_shift) | local source id.
+    int32_t* f_indptr = nullptr;   // [n_dst+1]
+    uint32_t* f_indices = nullptr; // [sum nnz]
+    int32_t* f_rows = nullptr;     // destinations with deg > 0, longest class first
+    int64_t n_f_rows = 0, n_f_long = 0;
+    int tag_shift = 0;
+    // All-blocks source-side work list: (q << tag_shift) | local source id of
+    // every source with an edge, longest class first.
+    uint32_t* ft_rows = nullptr;
+    int64_t n_ft_rows = 0, n_ft_long = 0;
+    std::vector<void*> owned;      // device allocations freed with the handle
+};

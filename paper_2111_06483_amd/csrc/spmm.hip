@@ -1,0 +1,367 @@
+// Sum / mean aggregation of neighbour features over partition blocks
+// (Eq. 2 and the accumulation loop of Alg. 1), and its case-1 backward
+// (Sec. 3.2: the gradient of a sum needs no features).
+//
+// All kernels are row gathers bound by HBM/L2 bandwidth: one wavefront owns one
+// output row, reads the listed input rows with 16-byte lane accesses (a 1 KiB
+// row is one wave-wide load), keeps several of them in flight, and adds them
+// in fp32 registers.  Rows at least kLongRow long are shared by the four
+// wavefronts of a workgroup and merged through LDS.  The grid is persistent:
+// workgroups stride over the degree-ordered row list, longest rows first.
+#include <algorithm>
+
+#include "gather_common.h"
+#include "sar_internal.h"
+
+namespace {
+
+using namespace sar;
+
+constexpr int kU = 4;   // rows in flight per lane group
+
+struct PtrTab {
+    const void* p[SAR_MAX_BLOCKS];
+};
+
+struct SpmmArgs {
+    const int32_t* indptr;    // row offsets ([n+1]); per-block, all-blocks or transposed
+    const uint32_t* indices;  // column ids (tagged with the block in the all-blocks index)
+    const uint32_t* rows;     // launch list, longest class first
+    int64_t n_rows, n_long;
+    const void* Z;            // single input (per-block calls)
+    float* acc;               // fp32 accumulator rows, read-modify-write (forward per block)
+    void* out;                // typed output rows (batched forward, backward)
+    const int32_t* deg;       // |N(i)| for the mean, or null
+    int F;
+    int tag_shift;            // all-blocks index: block = id >> tag_shift
+    int mean;
+};
+
+enum class Mode { kBlock, kAll, kBackward };
+
+// Adds the rows listed in idx[beg,end) into acc.  The wavefront takes the
+// 64-edge chunks chunk0, chunk0+stride, ...
+template <typename T, int G, Mode M>
+__device__ inline void add_rows(float (&acc)[Vec<T>::N], const SpmmArgs& a, const void* const* ztab,
+                                int beg, int end, int chunk0, int stride, const LaneMap<T, G>& lm,
+                                float inv_scale_unused)
+{
+    constexpr int VEC = Vec<T>::N;
+    constexpr int SLOTS = kWave / G;
+    const uint32_t mask = (M == Mode::kAll) ? ((1u << a.tag_shift) - 1u) : 0xffffffffu;
+    for (int cb = beg + chunk0 * kWave; cb < end; cb += stride * kWave) {
+        const int cnt = min(kWave, end - cb);
+        const uint32_t mine = (lm.lane < cnt) ? a.indices[cb + lm.lane] : 0u;
+        for (int k0 = 0; k0 < cnt; k0 += SLOTS * kU) {
+            typename Vec<T>::Raw raw[kU];
+            float w[kU];
+#pragma unroll
+            for (int k = 0; k < kU; ++k) {
+                const int ek = k0 + k * SLOTS + lm.slot;
+                const uint32_t id = __shfl(mine, ek & (kWave - 1));
+                const bool ok = (ek < cnt) && lm.on;
+                raw[k] = Vec<T>::zero();
+                w[k] = 1.f;
+                if (ok) {
+                    const uint32_t j = id & mask;
+                    const T* base;
+                    if constexpr (M == Mode::kAll)
+                        base = static_cast<const T*>(ztab[id >> a.tag_shift]);
+                    else
+                        base = static_cast<const T*>(a.Z);
+                    raw[k] = Vec<T>::load(base + (int64_t)j * a.F + lm.gl * VEC);
+                    if constexpr (M == Mode::kBackward) {
+                        if (a.mean) w[k] = 1.f / (float)max(a.deg[j], 1);
+                    }
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < kU; ++k) {
+                float v[VEC];
+                Vec<T>::unpack(raw[k], v);
+#pragma unroll
+                for (int x = 0; x < VEC; ++x) {
+                    if constexpr (M == Mode::kBackward)
+                        acc[x] = fmaf(w[k], v[x], acc[x]);
+                    else
+                        acc[x] += v[x];
+                }
+            }
+        }
+    }
+}
+
+template <typename T, int G>
+__device__ inline void merge_slots(float (&acc)[Vec<T>::N])
+{
+#pragma unroll
+    for (int o = G; o < kWave; o <<= 1)
+#pragma unroll
+        for (int x = 0; x < Vec<T>::N; ++x) acc[x] += __shfl_xor(acc[x], o);
+}
+
+template <typename T, int G, Mode M>
+__device__ inline void finish_row(const float (&acc)[Vec<T>::N], const SpmmArgs& a, int i,
+                                  const LaneMap<T, G>& lm)
+{
+    constexpr int VEC = Vec<T>::N;
+    if (lm.slot != 0 || !lm.on) return;
+    const int64_t o = (int64_t)i * a.F + lm.gl * VEC;
+    if constexpr (M == Mode::kBlock) {
+        float cur[VEC];
+        load_f32<VEC>(a.acc + o, cur);
+#pragma unroll
+        for (int x = 0; x < VEC; ++x) cur[x] += acc[x];
+        store_f32<VEC>(a.acc + o, cur);
+    } else {
+        float v[VEC];
+        float sc = 1.f;
+        if constexpr (M == Mode::kAll) {
+            if (a.mean) sc = 1.f / (float)max(a.deg[i], 1);
+        }
+#pragma unroll
+        for (int x = 0; x < VEC; ++x) v[x] = acc[x] * sc;
+        Vec<T>::store(static_cast<T*>(a.out) + o, v);
+    }
+}
+
+template <typename T, int G, Mode M>
+__global__ __launch_bounds__(kGatherThreads) void k_spmm(SpmmArgs a, PtrTab tab, int P)
+{
+    constexpr int VEC = Vec<T>::N;
+    __shared__ const void* ztab[SAR_MAX_BLOCKS];
+    __shared__ float part[kWavesPerWG][G][VEC];
+    if constexpr (M == Mode::kAll) {
+        if ((int)threadIdx.x < P) ztab[threadIdx.x] = tab.p[threadIdx.x];
+        __syncthreads();
+    }
+    const LaneMap<T, G> lm(a.F, 1, a.F);
+    const int wave = threadIdx.x / kWave;
+
+    // long rows: one workgroup each
+    for (int64_t r = blockIdx.x; r < a.n_long; r += gridDim.x) {
+        const int i = (int)a.rows[r];
+        float acc[VEC] = {};
+        add_rows<T, G, M>(acc, a, ztab, a.indptr[i], a.indptr[i + 1], wave, kWavesPerWG, lm, 1.f);
+        merge_slots<T, G>(acc);
+        if (lm.slot == 0)
+#pragma unroll
+            for (int x = 0; x < VEC; ++x) part[wave][lm.gl][x] = acc[x];
+        __syncthreads();
+        if (wave == 0) {
+#pragma unroll
+            for (int x = 0; x < VEC; ++x) {
+                float t = 0.f;
+                for (int w = 0; w < kWavesPerWG; ++w) t += part[w][lm.gl][x];
+                acc[x] = t;
+            }
+            finish_row<T, G, M>(acc, a, i, lm);
+        }
+        __syncthreads();
+    }
+    // remaining rows: one wavefront each
+    const int64_t n_waves = (int64_t)gridDim.x * kWavesPerWG;
+    for (int64_t r = a.n_long + (int64_t)blockIdx.x * kWavesPerWG + wave; r < a.n_rows; r += n_waves) {
+        const int i = (int)a.rows[r];
+        float acc[VEC] = {};
+        add_rows<T, G, M>(acc, a, ztab, a.indptr[i], a.indptr[i + 1], 0, 1, lm, 1.f);
+        merge_slots<T, G>(acc);
+        finish_row<T, G, M>(acc, a, i, lm);
+    }
+}
+
+// Typed rows of destinations that the launch lists skip (no edge at all): 0.
+template <typename T>
+__global__ __launch_bounds__(256) void k_zero_rows_without_edges(const int32_t* __restrict__ indptr,
+                                                                 int64_t n, int F, T* __restrict__ out)
+{
+    const int64_t total = n * F;
+    for (int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x; k < total; k += (int64_t)gridDim.x * 256) {
+        const int64_t i = k / F;
+        if (indptr[i + 1] == indptr[i]) out[k] = T{};
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_spmm_end(const int32_t* __restrict__ deg, int mean,
+                                                  const float* __restrict__ acc, T* __restrict__ out,
+                                                  int64_t n, int F)
+{
+    constexpr int VEC = Vec<T>::N;
+    const int64_t total = n * (F / VEC);
+    for (int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x; k < total; k += (int64_t)gridDim.x * 256) {
+        const int64_t i = k / (F / VEC);
+        float v[VEC];
+        load_f32<VEC>(acc + k * VEC, v);
+        float sc = 1.f;
+        if (mean) {
+            const int d = deg[i];
+            sc = d > 0 ? 1.f / (float)d : 0.f;
+        }
+#pragma unroll
+        for (int x = 0; x < VEC; ++x) v[x] *= sc;
+        Vec<T>::store(out + k * VEC, v);
+    }
+}
+
+unsigned persistent_grid(int64_t n_rows, int64_t n_long)
+{
+    const int64_t want = n_long + (n_rows - n_long + kWavesPerWG - 1) / kWavesPerWG;
+    return (unsigned)std::max<int64_t>(1, std::min<int64_t>(want, kMaxPersistentWGs));
+}
+
+template <typename T, Mode M>
+int launch_spmm(const SpmmArgs& a, const PtrTab& tab, int P, hipStream_t st)
+{
+    if (a.n_rows == 0) return SAR_OK;
+    const unsigned grid = persistent_grid(a.n_rows, a.n_long);
+    switch (lanes_for(a.F, Vec<T>::N)) {
+        case 4: k_spmm<T, 4, M><<<grid, kGatherThreads, 0, st>>>(a, tab, P); break;
+        case 8: k_spmm<T, 8, M><<<grid, kGatherThreads, 0, st>>>(a, tab, P); break;
+        case 16: k_spmm<T, 16, M><<<grid, kGatherThreads, 0, st>>>(a, tab, P); break;
+        case 32: k_spmm<T, 32, M><<<grid, kGatherThreads, 0, st>>>(a, tab, P); break;
+        case 64: k_spmm<T, 64, M><<<grid, kGatherThreads, 0, st>>>(a, tab, P); break;
+        default: return sar::fail(SAR_ERR_UNSUPPORTED, "row of F=%d values is wider than 1024 bytes", a.F);
+    }
+    SAR_LAUNCH_CHECK();
+    return SAR_OK;
+}
+
+int check_row_shape(int dtype, int F)
+{
+    if (dtype != SAR_F32 && dtype != SAR_BF16)
+        return sar::fail(SAR_ERR_UNSUPPORTED, "dtype %d is neither SAR_F32 nor SAR_BF16", dtype);
+    const int vec = dtype == SAR_F32 ? 4 : 8;
+    if (F <= 0 || F % vec != 0)
+        return sar::fail(SAR_ERR_UNSUPPORTED, "F=%d must be a positive multiple of %d for this dtype", F, vec);
+    if (F / vec > 64)
+        return sar::fail(SAR_ERR_UNSUPPORTED, "row of F=%d values is wider than 1024 bytes", F);
+    return SAR_OK;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+
+extern "C" int sar_spmm_block(const sar_blocks_t* b, int q, const void* Zq, int dtype, int F, float* acc,
+                              void* stream)
+{
+    SAR_CHECK_ARG(b != nullptr, "handle is null");
+    SAR_CHECK_ARG(q >= 0 && q < b->P, "block %d out of range [0,%d)", q, b->P);
+    SAR_TRY(check_row_shape(dtype, F));
+    const sar::Block& k = b->blk[q];
+    if (k.n_rows == 0) return SAR_OK;
+    SAR_CHECK_ARG(Zq && acc, "Zq or acc is null");
+    SAR_CHECK_ARG(aligned16(Zq) && aligned16(acc), "Zq and acc must be 16-byte aligned");
+    SpmmArgs a{};
+    a.indptr = k.indptr;
+    a.indices = reinterpret_cast<const uint32_t*>(k.indices);
+    a.rows = reinterpret_cast<const uint32_t*>(k.rows);
+    a.n_rows = k.n_rows;
+    a.n_long = k.n_long;
+    a.Z = Zq;
+    a.acc = acc;
+    a.F = F;
+    PtrTab tab{};
+    if (dtype == SAR_F32) return launch_spmm<float, Mode::kBlock>(a, tab, 0, sar::as_stream(stream));
+    return launch_spmm<bf16_t, Mode::kBlock>(a, tab, 0, sar::as_stream(stream));
+}
+
+extern "C" int sar_spmm_end(const int32_t* deg, int mean, const float* acc, void* out, int dtype,
+                            int64_t n_dst, int F, void* stream)
+{
+    SAR_TRY(check_row_shape(dtype, F));
+    SAR_CHECK_ARG(n_dst >= 0, "n_dst is negative");
+    if (n_dst == 0) return SAR_OK;
+    SAR_CHECK_ARG(acc && out && (!mean || deg), "acc, out or deg is null");
+    SAR_CHECK_ARG(aligned16(acc) && aligned16(out), "acc and out must be 16-byte aligned");
+    const int vec = dtype == SAR_F32 ? 4 : 8;
+    const unsigned grid = (unsigned)std::min<int64_t>((n_dst * (F / vec) + 255) / 256, 1 << 20);
+    if (dtype == SAR_F32)
+        k_spmm_end<float><<<grid, 256, 0, sar::as_stream(stream)>>>(deg, mean, acc, static_cast<float*>(out), n_dst, F);
+    else
+        k_spmm_end<bf16_t><<<grid, 256, 0, sar::as_stream(stream)>>>(deg, mean, acc, static_cast<bf16_t*>(out), n_dst, F);
+    SAR_LAUNCH_CHECK();
+    return SAR_OK;
+}
+
+extern "C" int sar_spmm_all(const sar_blocks_t* b, const void* const* Zq, int dtype, int F, int mean,
+                            void* out, void* stream)
+{
+    SAR_CHECK_ARG(b != nullptr, "handle is null");
+    SAR_TRY(check_row_shape(dtype, F));
+    if (!b->f_indptr) return sar::fail(SAR_ERR_STATE, "handle was built without SAR_BUILD_FUSED");
+    if (b->n_dst == 0) return SAR_OK;
+    SAR_CHECK_ARG(Zq && out, "Zq or out is null");
+    SAR_CHECK_ARG(aligned16(out), "out must be 16-byte aligned");
+    PtrTab tab{};
+    for (int q = 0; q < b->P; ++q) {
+        SAR_CHECK_ARG(Zq[q] != nullptr || b->blk[q].nnz == 0, "Zq[%d] is null", q);
+        SAR_CHECK_ARG(aligned16(Zq[q]), "Zq[%d] must be 16-byte aligned", q);
+        tab.p[q] = Zq[q];
+    }
+    hipStream_t st = sar::as_stream(stream);
+    const unsigned gz = (unsigned)std::min<int64_t>((b->n_dst * F + 255) / 256, 1 << 16);
+    SpmmArgs a{};
+    a.indptr = b->f_indptr;
+    a.indices = b->f_indices;
+    a.rows = reinterpret_cast<const uint32_t*>(b->f_rows);
+    a.n_rows = b->n_f_rows;
+    a.n_long = b->n_f_long;
+    a.out = out;
+    a.deg = b->deg;
+    a.F = F;
+    a.tag_shift = b->tag_shift;
+    a.mean = mean;
+    if (dtype == SAR_F32) {
+        if (b->n_f_rows < b->n_dst) {
+            k_zero_rows_without_edges<float><<<gz, 256, 0, st>>>(b->f_indptr, b->n_dst, F, static_cast<float*>(out));
+            SAR_LAUNCH_CHECK();
+        }
+        return launch_spmm<float, Mode::kAll>(a, tab, b->P, st);
+    }
+    if (b->n_f_rows < b->n_dst) {
+        k_zero_rows_without_edges<bf16_t><<<gz, 256, 0, st>>>(b->f_indptr, b->n_dst, F, static_cast<bf16_t*>(out));
+        SAR_LAUNCH_CHECK();
+    }
+    return launch_spmm<bf16_t, Mode::kAll>(a, tab, b->P, st);
+}
+
+extern "C" int sar_spmm_bwd_block(const sar_blocks_t* b, int q, const void* G, int mean, int dtype, int F,
+                                  void* dZq, void* stream)
+{
+    SAR_CHECK_ARG(b != nullptr, "handle is null");
+    SAR_CHECK_ARG(q >= 0 && q < b->P, "block %d out of range [0,%d)", q, b->P);
+    SAR_TRY(check_row_shape(dtype, F));
+    const sar::Block& k = b->blk[q];
+    if (!k.t_indptr) return sar::fail(SAR_ERR_STATE, "handle was built without SAR_BUILD_TRANSPOSE");
+    if (k.n_src == 0) return SAR_OK;
+    SAR_CHECK_ARG(G && dZq, "G or dZq is null");
+    SAR_CHECK_ARG(aligned16(G) && aligned16(dZq), "G and dZq must be 16-byte aligned");
+    hipStream_t st = sar::as_stream(stream);
+    SpmmArgs a{};
+    a.indptr = k.t_indptr;
+    a.indices = reinterpret_cast<const uint32_t*>(k.t_indices);
+    a.rows = reinterpret_cast<const uint32_t*>(k.t_rows);
+    a.n_rows = k.n_t_rows;
+    a.n_long = k.n_t_long;
+    a.Z = G;
+    a.out = dZq;
+    a.deg = b->deg;
+    a.F = F;
+    a.mean = mean;
+    PtrTab tab{};
+    const unsigned gz = (unsigned)std::min<int64_t>((k.n_src * F + 255) / 256, 1 << 16);
+    if (dtype == SAR_F32) {
+        if (k.n_t_rows < k.n_src) {
+            k_zero_rows_without_edges<float><<<gz, 256, 0, st>>>(k.t_indptr, k.n_src, F, static_cast<float*>(dZq));
+            SAR_LAUNCH_CHECK();
+        }
+        return launch_spmm<float, Mode::kBackward>(a, tab, 0, st);
+    }
+    if (k.n_t_rows < k.n_src) {
+        k_zero_rows_without_edges<bf16_t><<<gz, 256, 0, st>>>(k.t_indptr, k.n_src, F, static_cast<bf16_t*>(dZq));
+        SAR_LAUNCH_CHECK();
+    }
+    return launch_spmm<bf16_t, Mode::kBackward>(a, tab, 0, st);
+}

@@ -1,0 +1,362 @@
+"""Thin ctypes binding over libsar_mi355x.so: same names as include/sar_mi355x.h.
+
+Argument marshalling only -- every step of the path runs in the library's HIP
+kernels.  torch is used for device memory (``tensor.data_ptr()``) and for the
+current stream.  If the shared library is missing the import of any function
+here raises; there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsar_mi355x.so")
+
+SAR_OK = 0
+SAR_ERR_INVALID_ARG = -1
+SAR_ERR_UNSUPPORTED = -2
+SAR_ERR_HIP = -3
+SAR_ERR_STATE = -4
+SAR_F32 = 0
+SAR_BF16 = 1
+SAR_MAX_BLOCKS = 64
+SAR_BUILD_TRANSPOSE = 1
+SAR_BUILD_FUSED = 2
+
+_c_i64 = ctypes.c_int64
+_c_int = ctypes.c_int
+_vp = ctypes.c_void_p
+
+
+class SarError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__("sar error %d: %s" % (code, text))
+        self.code = code
+
+
+class BlockView(ctypes.Structure):
+    _fields_ = [
+        ("n_dst", _c_i64), ("n_src", _c_i64), ("nnz", _c_i64),
+        ("indptr", _vp), ("indices", _vp), ("t_indptr", _vp), ("t_indices", _vp),
+        ("rows", _vp), ("n_rows", _c_i64), ("n_long", _c_i64),
+        ("t_rows", _vp), ("n_t_rows", _c_i64), ("n_t_long", _c_i64),
+        ("touched", _vp),
+    ]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                "%s is missing: build it with `python -m paper_2111_06483_amd.build` "
+                "(there is no fallback path)" % LIB_PATH)
+        _lib = ctypes.CDLL(LIB_PATH)
+        _lib.sar_last_error.restype = ctypes.c_char_p
+        for name in EXPORTS:
+            getattr(_lib, name)   # fail early if a symbol is missing
+    return _lib
+
+
+EXPORTS = [
+    "sar_last_error", "sar_version",
+    "sar_blocks_build", "sar_blocks_wrap", "sar_blocks_info", "sar_blocks_get", "sar_blocks_degree",
+    "sar_blocks_free",
+    "sar_spmm_block", "sar_spmm_end", "sar_spmm_all", "sar_spmm_bwd_block",
+    "sar_gat_scores", "sar_gat_fwd_begin", "sar_gat_fwd_block", "sar_gat_fwd_end", "sar_gat_fwd_all",
+    "sar_gat_workspace_bytes", "sar_gat_bwd_begin", "sar_gat_bwd_block", "sar_gat_bwd_all", "sar_gat_bwd_end",
+    "sar_linear_fwd", "sar_linear_bwd", "sar_linear_workspace_bytes",
+]
+
+
+def _check(rc: int) -> None:
+    if rc != SAR_OK:
+        raise SarError(rc, lib().sar_last_error().decode())
+
+
+def _ptr(t: Optional[torch.Tensor]) -> _vp:
+    if t is None:
+        return _vp(None)
+    assert t.is_contiguous(), "tensors passed to the library must be contiguous"
+    return _vp(t.data_ptr())
+
+
+def _stream() -> _vp:
+    if torch.cuda.is_available():
+        return _vp(torch.cuda.current_stream().cuda_stream)
+    return _vp(None)
+
+
+def dtype_code(dt: torch.dtype) -> int:
+    if dt == torch.float32:
+        return SAR_F32
+    if dt == torch.bfloat16:
+        return SAR_BF16
+    raise SarError(SAR_ERR_UNSUPPORTED, "dtype %s" % dt)
+
+
+def _ptr_array(ts: Sequence[Optional[torch.Tensor]]):
+    arr = (_vp * len(ts))()
+    for k, t in enumerate(ts):
+        arr[k] = None if t is None else t.data_ptr()
+    return arr
+
+
+class Blocks:
+    """Owner of a sar_blocks_t handle (freed on ``close`` / garbage collection)."""
+
+    def __init__(self, handle: _vp, keep=()):
+        self._h = handle
+        self._keep = keep   # tensors borrowed by a wrapped handle
+        self._n_src = {}
+        P, n = _c_int(0), _c_i64(0)
+        _check(lib().sar_blocks_info(self._h, ctypes.byref(P), ctypes.byref(n)))
+        self.P, self.n_dst = P.value, n.value
+
+    @property
+    def handle(self) -> _vp:
+        if self._h is None:
+            raise SarError(SAR_ERR_STATE, "blocks handle already freed")
+        return self._h
+
+    def view(self, q: int) -> BlockView:
+        v = BlockView()
+        _check(lib().sar_blocks_get(self.handle, _c_int(q), ctypes.byref(v)))
+        return v
+
+    def n_src(self, q: int) -> int:
+        if q not in self._n_src:
+            self._n_src[q] = int(self.view(q).n_src)
+        return self._n_src[q]
+
+    def check_rows(self, q: int, *tensors) -> None:
+        """Host-side guard: per-source tensors of block q must have n_src rows."""
+        for t in tensors:
+            if t is not None and t.shape[0] != self.n_src(q):
+                raise SarError(SAR_ERR_INVALID_ARG, "block %d has %d sources, tensor has %d rows"
+                               % (q, self.n_src(q), t.shape[0]))
+
+    def check_dst(self, *tensors) -> None:
+        for t in tensors:
+            if t is not None and t.shape[0] != self.n_dst:
+                raise SarError(SAR_ERR_INVALID_ARG, "handle has %d destinations, tensor has %d rows"
+                               % (self.n_dst, t.shape[0]))
+
+    def close(self) -> None:
+        if self._h is not None:
+            lib().sar_blocks_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def device_array(ptr: Optional[int], count: int, dtype=torch.int32, device="cuda") -> torch.Tensor:
+    """Copy of `count` elements at device address `ptr` (for inspection in tests)."""
+    out = torch.empty(count, dtype=dtype, device=device)
+    if count:
+        nbytes = count * out.element_size()
+        rc = _hip().hipMemcpy(_vp(out.data_ptr()), _vp(ptr), ctypes.c_size_t(nbytes), _c_int(3))
+        if rc != 0:
+            raise RuntimeError("hipMemcpy failed: %d" % rc)
+    return out
+
+
+_hiprt = None
+
+
+def _hip():
+    global _hiprt
+    if _hiprt is None:
+        _hiprt = ctypes.CDLL("libamdhip64.so")
+    return _hiprt
+
+
+# ------------------------------------------------------------------ blocks
+
+def sar_blocks_build(src: torch.Tensor, dst: torch.Tensor, part: torch.Tensor, P: int, p: int,
+                     flags: int = SAR_BUILD_TRANSPOSE | SAR_BUILD_FUSED) -> Blocks:
+    assert src.dtype == dst.dtype and src.dtype in (torch.int32, torch.int64)
+    assert part.dtype == torch.int32
+    h = _vp(None)
+    _check(lib().sar_blocks_build(_ptr(src), _ptr(dst), _c_int(src.element_size()), _c_i64(src.numel()),
+                                  _ptr(part), _c_i64(part.numel()), _c_int(P), _c_int(p), _c_int(flags),
+                                  _stream(), ctypes.byref(h)))
+    return Blocks(h)
+
+
+def sar_blocks_wrap(n_dst: int, n_src: Sequence[int], indptr: Sequence[torch.Tensor],
+                    indices: Sequence[torch.Tensor],
+                    flags: int = SAR_BUILD_TRANSPOSE | SAR_BUILD_FUSED) -> Blocks:
+    P = len(indptr)
+    ns = (_c_i64 * P)(*[int(x) for x in n_src])
+    h = _vp(None)
+    _check(lib().sar_blocks_wrap(_c_int(P), _c_i64(n_dst), ns, _ptr_array(indptr), _ptr_array(indices),
+                                 _c_int(flags), _stream(), ctypes.byref(h)))
+    return Blocks(h, keep=(list(indptr), list(indices)))
+
+
+def sar_blocks_degree(b: Blocks) -> torch.Tensor:
+    p = _vp(None)
+    _check(lib().sar_blocks_degree(b.handle, ctypes.byref(p)))
+    return device_array(p.value, b.n_dst)
+
+
+# -------------------------------------------------------------------- spmm
+
+def sar_spmm_block(b: Blocks, q: int, Zq: torch.Tensor, acc: torch.Tensor) -> None:
+    b.check_rows(q, Zq)
+    b.check_dst(acc)
+    _check(lib().sar_spmm_block(b.handle, _c_int(q), _ptr(Zq), _c_int(dtype_code(Zq.dtype)),
+                                _c_int(Zq.shape[-1]), _ptr(acc), _stream()))
+
+
+def sar_spmm_end(deg: torch.Tensor, mean: bool, acc: torch.Tensor, out: torch.Tensor) -> None:
+    _check(lib().sar_spmm_end(_ptr(deg), _c_int(int(mean)), _ptr(acc), _ptr(out),
+                              _c_int(dtype_code(out.dtype)), _c_i64(acc.shape[0]), _c_int(acc.shape[1]),
+                              _stream()))
+
+
+def sar_spmm_all(b: Blocks, Zq: Sequence[torch.Tensor], mean: bool, out: torch.Tensor) -> None:
+    for q in range(b.P):
+        b.check_rows(q, Zq[q])
+    b.check_dst(out)
+    _check(lib().sar_spmm_all(b.handle, _ptr_array(Zq), _c_int(dtype_code(out.dtype)),
+                              _c_int(out.shape[-1]), _c_int(int(mean)), _ptr(out), _stream()))
+
+
+def sar_spmm_bwd_block(b: Blocks, q: int, G: torch.Tensor, mean: bool, dZq: torch.Tensor) -> None:
+    b.check_rows(q, dZq)
+    b.check_dst(G)
+    _check(lib().sar_spmm_bwd_block(b.handle, _c_int(q), _ptr(G), _c_int(int(mean)),
+                                    _c_int(dtype_code(G.dtype)), _c_int(G.shape[-1]), _ptr(dZq), _stream()))
+
+
+# --------------------------------------------------------------------- GAT
+
+def sar_gat_scores(Z: torch.Tensor, a: torch.Tensor, score: torch.Tensor) -> None:
+    H, D = a.shape
+    _check(lib().sar_gat_scores(_ptr(Z), _c_int(dtype_code(Z.dtype)), _c_i64(Z.shape[0]), _c_int(H), _c_int(D),
+                                _ptr(a), _ptr(score), _stream()))
+
+
+def sar_gat_fwd_begin(m: torch.Tensor, l: torch.Tensor, acc: torch.Tensor) -> None:
+    n, H, D = acc.shape
+    _check(lib().sar_gat_fwd_begin(_ptr(m), _ptr(l), _ptr(acc), _c_i64(n), _c_int(H), _c_int(D), _stream()))
+
+
+def sar_gat_fwd_block(b: Blocks, q: int, Zq: torch.Tensor, s: torch.Tensor, tq: torch.Tensor, slope: float,
+                      m: torch.Tensor, l: torch.Tensor, acc: torch.Tensor) -> None:
+    _, H, D = acc.shape
+    b.check_rows(q, Zq, tq)
+    b.check_dst(s, m, l, acc)
+    _check(lib().sar_gat_fwd_block(b.handle, _c_int(q), _ptr(Zq), _ptr(s), _ptr(tq),
+                                   _c_int(dtype_code(Zq.dtype)), _c_int(H), _c_int(D), ctypes.c_float(slope),
+                                   _ptr(m), _ptr(l), _ptr(acc), _stream()))
+
+
+def sar_gat_fwd_end(m: torch.Tensor, l: torch.Tensor, acc: torch.Tensor, out: torch.Tensor,
+                    L: torch.Tensor) -> None:
+    n, H, D = acc.shape
+    _check(lib().sar_gat_fwd_end(_ptr(m), _ptr(l), _ptr(acc), _ptr(out), _ptr(L),
+                                 _c_int(dtype_code(out.dtype)), _c_i64(n), _c_int(H), _c_int(D), _stream()))
+
+
+def sar_gat_fwd_all(b: Blocks, Zq: Sequence[torch.Tensor], s: torch.Tensor, tq: Sequence[torch.Tensor],
+                    slope: float, out: torch.Tensor, L: torch.Tensor) -> None:
+    _, H, D = out.shape
+    for q in range(b.P):
+        b.check_rows(q, Zq[q], tq[q])
+    b.check_dst(s, out, L)
+    _check(lib().sar_gat_fwd_all(b.handle, _ptr_array(Zq), _ptr(s), _ptr_array(tq),
+                                 _c_int(dtype_code(out.dtype)), _c_int(H), _c_int(D), ctypes.c_float(slope),
+                                 _ptr(out), _ptr(L), _stream()))
+
+
+def sar_gat_workspace_bytes(n_dst: int, n_src_max: int, H: int, D: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().sar_gat_workspace_bytes(_c_i64(n_dst), _c_i64(n_src_max), _c_int(H), _c_int(D),
+                                         ctypes.byref(out)))
+    return out.value
+
+
+def sar_gat_bwd_begin(G: torch.Tensor, out: torch.Tensor, s: torch.Tensor, L: torch.Tensor,
+                      rec: torch.Tensor, ds: torch.Tensor) -> None:
+    n, H, D = G.shape
+    _check(lib().sar_gat_bwd_begin(_ptr(G), _ptr(out), _ptr(s), _ptr(L), _c_int(dtype_code(G.dtype)),
+                                   _ptr(rec), _ptr(ds), _c_i64(n), _c_int(H), _c_int(D), _stream()))
+
+
+def sar_gat_bwd_block(b: Blocks, q: int, Zq: torch.Tensor, G: torch.Tensor, tq: torch.Tensor,
+                      rec: torch.Tensor, a_l: torch.Tensor, slope: float, dZq: torch.Tensor,
+                      dtq: torch.Tensor, ds: torch.Tensor, da_l: torch.Tensor, work: torch.Tensor) -> None:
+    H, D = a_l.shape
+    b.check_rows(q, Zq, tq, dZq, dtq)
+    b.check_dst(G, rec, ds)
+    _check(lib().sar_gat_bwd_block(b.handle, _c_int(q), _ptr(Zq), _ptr(G), _ptr(tq), _ptr(rec), _ptr(a_l),
+                                   _c_int(dtype_code(G.dtype)), _c_int(H), _c_int(D), ctypes.c_float(slope),
+                                   _ptr(dZq), _ptr(dtq), _ptr(ds), _ptr(da_l), _ptr(work),
+                                   ctypes.c_size_t(work.numel() * work.element_size()), _stream()))
+
+
+def sar_gat_bwd_all(b: Blocks, Zq: Sequence[torch.Tensor], G: torch.Tensor, tq: Sequence[torch.Tensor],
+                    rec: torch.Tensor, a_l: torch.Tensor, slope: float, dZq: Sequence[torch.Tensor],
+                    dtq: Sequence[torch.Tensor], ds: torch.Tensor, da_l: torch.Tensor,
+                    work: torch.Tensor) -> None:
+    H, D = a_l.shape
+    for q in range(b.P):
+        b.check_rows(q, Zq[q], tq[q], dZq[q], dtq[q])
+    b.check_dst(G, rec, ds)
+    _check(lib().sar_gat_bwd_all(b.handle, _ptr_array(Zq), _ptr(G), _ptr_array(tq), _ptr(rec), _ptr(a_l),
+                                 _c_int(dtype_code(G.dtype)), _c_int(H), _c_int(D), ctypes.c_float(slope),
+                                 _ptr_array(dZq), _ptr_array(dtq), _ptr(ds), _ptr(da_l), _ptr(work),
+                                 ctypes.c_size_t(work.numel() * work.element_size()), _stream()))
+
+
+def sar_gat_bwd_end(Zdst: torch.Tensor, ds: torch.Tensor, a_r: torch.Tensor, dZdst: torch.Tensor,
+                    da_r: torch.Tensor, work: torch.Tensor) -> None:
+    H, D = a_r.shape
+    _check(lib().sar_gat_bwd_end(_ptr(Zdst), _ptr(ds), _ptr(a_r), _ptr(dZdst), _ptr(da_r),
+                                 _c_int(dtype_code(Zdst.dtype)), _c_i64(Zdst.shape[0]), _c_int(H), _c_int(D),
+                                 _ptr(work), ctypes.c_size_t(work.numel() * work.element_size()), _stream()))
+
+
+# ------------------------------------------------------------------ linear
+
+def sar_linear_workspace_bytes(n: int, K: int, F: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().sar_linear_workspace_bytes(_c_i64(n), _c_int(K), _c_int(F), ctypes.byref(out)))
+    return out.value
+
+
+def sar_linear_fwd(X: torch.Tensor, W: torch.Tensor, Z: torch.Tensor,
+                   a_score: Optional[torch.Tensor] = None, score: Optional[torch.Tensor] = None,
+                   a_score2: Optional[torch.Tensor] = None, score2: Optional[torch.Tensor] = None) -> None:
+    n, K = X.shape
+    F = W.shape[1]
+    H, D = (a_score.shape if a_score is not None else (0, 0))
+    _check(lib().sar_linear_fwd(_ptr(X), _ptr(W), _ptr(Z), _c_int(dtype_code(X.dtype)), _c_i64(n), _c_int(K),
+                                _c_int(F), _c_int(H), _c_int(D), _ptr(a_score), _ptr(score), _ptr(a_score2),
+                                _ptr(score2), _stream()))
+
+
+def sar_linear_bwd(X: Optional[torch.Tensor], dZ: torch.Tensor, W: Optional[torch.Tensor],
+                   dW: Optional[torch.Tensor], dX: Optional[torch.Tensor],
+                   work: Optional[torch.Tensor]) -> None:
+    n = dZ.shape[0]
+    F = dZ.numel() // max(n, 1)
+    K = X.shape[1] if X is not None else W.shape[0]
+    wb = 0 if work is None else work.numel() * work.element_size()
+    _check(lib().sar_linear_bwd(_ptr(X), _ptr(dZ), _ptr(W), _ptr(dW), _ptr(dX), _c_int(dtype_code(dZ.dtype)),
+                                _c_i64(n), _c_int(K), _c_int(F), _ptr(work), ctypes.c_size_t(wb), _stream()))

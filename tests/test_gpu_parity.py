@@ -1,0 +1,327 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, element by element.
+
+Tolerances (the benchmark spec): bit-exact for the block index; tensor-scale relative
+error max|a-b|/max|b| <= 1e-4 for fp32 tensors; <= 2e-2 for bf16-stored
+tensors with fp32 accumulation.  The oracle always runs in fp64 on the same
+(already rounded) inputs.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import sar_oracle as orc
+from tests.helpers import rel_err
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    from paper_2111_06483_amd import sar
+    from tests import gpu_util as gu
+
+TOL = {torch.float32: 1e-4, torch.bfloat16: 2e-2}
+SLOPE = 0.2
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU in this process")
+    sar.lib()   # raises if the HIP library is missing: no fallback
+
+
+def make_graph(seed, N, E, P, hubs=True, simple=True, empty_block=None):
+    """Random directed graph with a heavy destination, a heavy source and ragged sizes."""
+    rng = np.random.default_rng(seed)
+    src = rng.integers(0, N, size=E)
+    dst = rng.integers(0, N, size=E)
+    part = rng.integers(0, P, size=N).astype(np.int32)
+    part[:P] = np.arange(P)
+    if hubs:
+        k = min(N, 1500)
+        hub_dst = int(np.flatnonzero(part == 0)[0])
+        hub_src = int(np.flatnonzero(part == P - 1)[-1])
+        src = np.concatenate([src, rng.choice(N, k, replace=False), np.full(k, hub_src)])
+        dst = np.concatenate([dst, np.full(k, hub_dst), rng.choice(N, k, replace=False)])
+    if empty_block is not None:
+        keep = part[src] != empty_block
+        src, dst = src[keep], dst[keep]
+    if simple:
+        key = np.unique(dst.astype(np.int64) * N + src)
+        dst, src = key // N, key % N
+    return src.astype(np.int64), dst.astype(np.int64), part, rng
+
+
+def feats(rng, n, F, dtype, scale=1.0):
+    x = torch.from_numpy((rng.standard_normal((n, F)) * scale).astype(np.float32)).to(dtype)
+    return x
+
+
+def f64(t):
+    return t.to(torch.float64).cpu().numpy()
+
+
+# ------------------------------------------------------------------ builder
+
+@pytest.mark.parametrize("idx_dtype", [torch.int32, torch.int64])
+@pytest.mark.parametrize("N,E,P,p,simple", [(3000, 40000, 3, 0, True), (5000, 30000, 7, 6, False),
+                                            (257, 900, 1, 0, False), (70000, 150000, 16, 3, True)])
+def test_builder_bit_exact(N, E, P, p, simple, idx_dtype):
+    src, dst, part, _ = make_graph(1, N, E, P, simple=simple, empty_block=(1 if P > 2 else None))
+    want, want_deg = orc.build_blocks(src, dst, part, P, p)
+    b = gu.build_blocks(src, dst, part, P, p, idx_dtype=idx_dtype)
+    assert b.P == P and b.n_dst == want[0].n_dst
+    assert np.array_equal(sar.sar_blocks_degree(b).cpu().numpy(), want_deg)
+    for q in range(P):
+        v = gu.view_arrays(b, q)
+        w = want[q]
+        assert (v["n_dst"], v["n_src"], v["nnz"]) == (w.n_dst, w.n_src, w.nnz)
+        assert np.array_equal(v["indptr"], w.indptr.astype(np.int32))
+        assert np.array_equal(v["indices"], w.indices)
+        assert np.array_equal(v["t_indptr"], w.t_indptr.astype(np.int32))
+        assert np.array_equal(v["t_indices"], w.t_indices)
+        # launch lists: exactly the non-empty rows, longest degree class first
+        deg_q = np.diff(w.indptr)
+        assert sorted(v["rows"].tolist()) == np.flatnonzero(deg_q > 0).tolist()
+        cls = np.floor(np.log2(np.maximum(deg_q[v["rows"]], 1))).astype(int)
+        assert np.all(np.diff(cls) <= 0)
+        assert v["n_long"] == int(np.sum(deg_q >= 512))
+        tdeg = np.diff(w.t_indptr)
+        assert sorted(v["t_rows"].tolist()) == np.flatnonzero(tdeg > 0).tolist()
+        assert np.array_equal(v["touched"], np.flatnonzero(tdeg > 0).astype(np.int32))
+        assert v["n_t_long"] == int(np.sum(tdeg >= 512))
+    b.close()
+
+
+def test_builder_rejects_bad_input():
+    src, dst, part, _ = make_graph(2, 500, 2000, 2, hubs=False)
+    bad = src.copy()
+    bad[7] = 500
+    with pytest.raises(sar.SarError) as e:
+        gu.build_blocks(bad, dst, part, 2, 0)
+    assert e.value.code == sar.SAR_ERR_INVALID_ARG
+    badp = part.copy()
+    badp[3] = 2
+    with pytest.raises(sar.SarError):
+        gu.build_blocks(src, dst, badp, 2, 0)
+    with pytest.raises(sar.SarError):
+        gu.build_blocks(src, dst, part, 2, 2)
+
+
+def test_wrap_equals_build():
+    src, dst, part, rng = make_graph(3, 2000, 20000, 3)
+    want, _ = orc.build_blocks(src, dst, part, 3, 1)
+    indptr = [gu.dev(w.indptr, torch.int32) for w in want]
+    indices = [gu.dev(w.indices, torch.int32) for w in want]
+    b = sar.sar_blocks_wrap(want[0].n_dst, [w.n_src for w in want], indptr, indices)
+    for q in range(3):
+        v = gu.view_arrays(b, q)
+        assert np.array_equal(v["t_indptr"], want[q].t_indptr.astype(np.int32))
+        assert np.array_equal(v["t_indices"], want[q].t_indices)
+    Zs = [feats(rng, w.n_src, 32, torch.float32).cuda() for w in want]
+    got = gu.spmm_all(b, Zs, True)
+    assert rel_err(f64(got), orc.spmm(want, [f64(z) for z in Zs], True)) < 1e-4
+    b.close()
+
+
+# --------------------------------------------------------------------- spmm
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("F", [8, 64, 200, 256])
+@pytest.mark.parametrize("mean", [False, True])
+def test_spmm_parity(dtype, F, mean):
+    if dtype == torch.bfloat16 and F % 8:
+        pytest.skip("bf16 rows move 8 values per lane")
+    src, dst, part, rng = make_graph(4, 3000, 40000, 3, simple=False)
+    want_b, deg = orc.build_blocks(src, dst, part, 3, 0)
+    b = gu.build_blocks(src, dst, part, 3, 0)
+    Zs = [feats(rng, w.n_src, F, dtype).cuda() for w in want_b]
+    want = orc.spmm(want_b, [f64(z) for z in Zs], mean)
+    assert rel_err(f64(gu.spmm_stream(b, Zs, mean)), want) < TOL[dtype]
+    assert rel_err(f64(gu.spmm_all(b, Zs, mean)), want) < TOL[dtype]
+    # case 1 backward
+    G = feats(rng, b.n_dst, F, dtype).cuda()
+    want_d = orc.spmm_bwd(want_b, f64(G), mean)
+    for q in range(3):
+        dZ = torch.full(Zs[q].shape, float("nan"), dtype=dtype, device="cuda")
+        sar.sar_spmm_bwd_block(b, q, G, mean, dZ)
+        assert rel_err(f64(dZ), want_d[q]) < TOL[dtype]
+    b.close()
+
+
+def test_spmm_all_ones_gives_degree_exactly():
+    src, dst, part, rng = make_graph(5, 3000, 40000, 4, simple=False)
+    b = gu.build_blocks(src, dst, part, 4, 2)
+    _, deg = orc.build_blocks(src, dst, part, 4, 2)
+    Zs = [torch.ones((b.view(q).n_src, 16), device="cuda") for q in range(4)]
+    out = gu.spmm_all(b, Zs, False).cpu().numpy()
+    assert np.array_equal(out, np.repeat(deg[:, None], 16, 1).astype(np.float32))
+    b.close()
+
+
+# ---------------------------------------------------------------------- GAT
+
+def gat_case(seed, N, E, P, p, H, D, dtype, scale=1.0, simple=True, empty_block=None):
+    src, dst, part, rng = make_graph(seed, N, E, P, simple=simple, empty_block=empty_block)
+    want_b, deg = orc.build_blocks(src, dst, part, P, p)
+    b = gu.build_blocks(src, dst, part, P, p)
+    F = H * D
+    Zs = [feats(rng, w.n_src, F, dtype, scale).cuda().reshape(-1, H, D) for w in want_b]
+    Zdst = feats(rng, b.n_dst, F, dtype, scale).cuda().reshape(-1, H, D)
+    a_l = torch.from_numpy(rng.uniform(-0.5, 0.5, (H, D)).astype(np.float32)).cuda()
+    a_r = torch.from_numpy(rng.uniform(-0.5, 0.5, (H, D)).astype(np.float32)).cuda()
+    G = feats(rng, b.n_dst, F, dtype).cuda().reshape(-1, H, D)
+    return b, want_b, deg, Zdst, Zs, a_l, a_r, G
+
+
+def check_fwd(got, want, deg, dtype):
+    tol = TOL[dtype]
+    assert rel_err(f64(got.out), want.out) < tol
+    Lg = f64(got.L)
+    has = deg > 0
+    assert np.all(np.isneginf(Lg[~has])) and np.all(f64(got.out)[~has] == 0)
+    assert rel_err(Lg[has], want.L[has]) < 1e-4          # L is fp32 state in both dtypes
+    assert rel_err(f64(got.s), want.s) < 1e-4
+    for tg, tw in zip(got.t, want.t):
+        assert rel_err(f64(tg), tw) < 1e-4
+
+
+SHAPES = [(4, 16), (1, 4), (4, 64), (8, 32), (2, 100), (3, 12)]
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("H,D", SHAPES)
+def test_gat_forward_parity(dtype, H, D):
+    if dtype == torch.bfloat16 and D % 8:
+        pytest.skip("bf16 rows move 8 values per lane")
+    b, want_b, deg, Zdst, Zs, a_l, a_r, G = gat_case(6, 3000, 40000, 3, 0, H, D, dtype, simple=False)
+    want = orc.gat_fwd(want_b, f64(Zdst), [f64(z) for z in Zs], f64(a_l), f64(a_r), SLOPE)
+    states = []
+    check_fwd(gu.gat_fwd_stream(b, Zdst, Zs, a_l, a_r, SLOPE, states=states), want, deg, dtype)
+    check_fwd(gu.gat_fwd_all(b, Zdst, Zs, a_l, a_r, SLOPE), want, deg, dtype)
+    # the carried state after block k represents Eq. 3 restricted to blocks 0..k
+    for k, (m, l, acc) in enumerate(states[:-1]):
+        part = orc.gat_fwd(want_b[:k + 1], f64(Zdst), [f64(z) for z in Zs[:k + 1]], f64(a_l), f64(a_r), SLOPE)
+        seen = l > 0
+        assert np.array_equal(seen, np.isfinite(part.L))
+        got = np.where(seen[:, :, None], acc / np.where(seen, l, 1)[:, :, None], 0)
+        assert rel_err(got, part.out) < 1e-4
+        assert rel_err((m + np.log(np.where(seen, l, 1)))[seen], part.L[seen]) < 1e-4
+    b.close()
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("H,D", SHAPES)
+@pytest.mark.parametrize("batched", [False, True])
+def test_gat_backward_parity(dtype, H, D, batched):
+    if dtype == torch.bfloat16 and D % 8:
+        pytest.skip("bf16 rows move 8 values per lane")
+    b, want_b, deg, Zdst, Zs, a_l, a_r, G = gat_case(7, 3000, 40000, 3, 1, H, D, dtype)
+    wf = orc.gat_fwd(want_b, f64(Zdst), [f64(z) for z in Zs], f64(a_l), f64(a_r), SLOPE)
+    wb = orc.gat_bwd(want_b, f64(Zdst), [f64(z) for z in Zs], f64(G), f64(a_l), f64(a_r), SLOPE, wf)
+    fw = gu.gat_fwd_all(b, Zdst, Zs, a_l, a_r, SLOPE)
+    g = gu.gat_bwd(b, Zdst, Zs, G, a_l, a_r, SLOPE, fw, batched)
+    tol = TOL[dtype]
+    for q in range(b.P):
+        assert rel_err(f64(g.dZs[q]), wb.dZs[q]) < tol, q
+        assert rel_err(f64(g.dts[q]), wb.dt[q]) < tol, q
+    assert rel_err(f64(g.ds), wb.ds) < tol
+    assert rel_err(f64(g.dZdst), wb.dZdst) < tol
+    assert rel_err(f64(g.da_l), wb.da_l) < tol
+    assert rel_err(f64(g.da_r), wb.da_r) < tol
+    b.close()
+
+
+def test_gat_edge_cases():
+    """Empty block, single block, destinations without edges, block order, big scores."""
+    H, D = 4, 16
+    b, want_b, deg, Zdst, Zs, a_l, a_r, G = gat_case(8, 2000, 6000, 4, 2, H, D, torch.float32,
+                                                     scale=40.0, empty_block=1)
+    assert want_b[1].nnz == 0 and (deg == 0).any()
+    want = orc.gat_fwd(want_b, f64(Zdst), [f64(z) for z in Zs], f64(a_l), f64(a_r), SLOPE)
+    assert np.abs(want.s).max() > 100          # exp() of these overflows fp32 without the running max
+    got = gu.gat_fwd_stream(b, Zdst, Zs, a_l, a_r, SLOPE)
+    check_fwd(got, want, deg, torch.float32)
+    assert torch.isfinite(got.out).all()
+    perm = gu.gat_fwd_stream(b, Zdst, Zs, a_l, a_r, SLOPE, order=[3, 1, 0, 2])
+    assert rel_err(f64(perm.out), want.out) < 1e-4
+    allb = gu.gat_fwd_all(b, Zdst, Zs, a_l, a_r, SLOPE)
+    check_fwd(allb, want, deg, torch.float32)
+    wb = orc.gat_bwd(want_b, f64(Zdst), [f64(z) for z in Zs], f64(G), f64(a_l), f64(a_r), SLOPE, want)
+    for batched in (False, True):
+        g = gu.gat_bwd(b, Zdst, Zs, G, a_l, a_r, SLOPE, allb, batched)
+        for q in range(4):
+            assert rel_err(f64(g.dZs[q]), wb.dZs[q]) < 1e-4
+        assert torch.all(g.dZs[1] == 0)
+        assert rel_err(f64(g.da_l), wb.da_l) < 1e-4 and rel_err(f64(g.da_r), wb.da_r) < 1e-4
+        assert rel_err(f64(g.dZdst), wb.dZdst) < 1e-4
+    b.close()
+
+
+def test_gat_zero_attention_equals_mean_kernel():
+    """a = 0 makes attention uniform: the GAT kernels must agree with the SpMM-mean kernel."""
+    H, D = 2, 32
+    b, want_b, deg, Zdst, Zs, a_l, a_r, G = gat_case(9, 3000, 30000, 3, 0, H, D, torch.float32)
+    zero = torch.zeros_like(a_l)
+    got = gu.gat_fwd_all(b, Zdst, Zs, zero, zero, SLOPE)
+    mean = gu.spmm_all(b, [z.reshape(-1, H * D) for z in Zs], True)
+    assert rel_err(f64(got.out).reshape(-1, H * D), f64(mean)) < 1e-5
+    b.close()
+
+
+def test_config1_full():
+    """BASELINE config 1: 4096-node Chung-Lu graph, self-loops, 1 block, 64 -> 4 x 16, fp32."""
+    from paper_2111_06483_amd import synth
+    w = synth.make_workload("cfg1")
+    members = w.members(0)
+    X = synth.normal_rows(2, members, w.f_in)
+    W, a_l, a_r = synth.gat_params(3, w.f_in, w.H, w.D)
+    G = synth.normal_rows(4, members, w.H * w.D).reshape(-1, w.H, w.D)
+    want_b, deg = orc.build_blocks(w.src.numpy(), w.dst.numpy(), w.part.numpy(), 1, 0)
+    res = orc.gat_layer(want_b, f64(X), [f64(X)], f64(W), f64(a_l), f64(a_r), w.slope, f64(G))
+
+    b = sar.sar_blocks_build(w.src.cuda(), w.dst.cuda(), w.part.cuda(), 1, 0)
+    v = gu.view_arrays(b, 0)
+    assert np.array_equal(v["indptr"], want_b[0].indptr.astype(np.int32))
+    assert np.array_equal(v["indices"], want_b[0].indices)
+    Xd, Wd, ald, ard, Gd = X.cuda(), W.cuda(), a_l.cuda(), a_r.cuda(), G.cuda()
+    Z, s, t = gu.linear_fwd(Xd, Wd, ard, ald)
+    assert rel_err(f64(Z), res.Zdst.reshape(Z.shape)) < 1e-4
+    Z3 = Z.reshape(-1, w.H, w.D)
+    for fwd in (gu.gat_fwd_stream, gu.gat_fwd_all):
+        fw = fwd(b, Z3, [Z3], ald, ard, w.slope)
+        check_fwd(fw, res.fwd, deg, torch.float32)
+    for batched in (False, True):
+        g = gu.gat_bwd(b, Z3, [Z3], Gd, ald, ard, w.slope, fw, batched)
+        assert rel_err(f64(g.dZs[0]), res.bwd.dZs[0]) < 1e-4
+        assert rel_err(f64(g.dZdst), res.bwd.dZdst) < 1e-4
+        assert rel_err(f64(g.da_l), res.bwd.da_l) < 1e-4
+        assert rel_err(f64(g.da_r), res.bwd.da_r) < 1e-4
+    # the transform's backward: destination rows and the (local) source block add up in dW
+    dW = torch.zeros_like(Wd)
+    dXd = gu.linear_bwd(Xd, g.dZdst, Wd, dW)
+    dXs = gu.linear_bwd(Xd, g.dZs[0], Wd, dW)
+    assert rel_err(f64(dW), res.dW) < 1e-4
+    assert rel_err(f64(dXd), res.dXdst) < 1e-4
+    assert rel_err(f64(dXs), res.dXs[0]) < 1e-4
+    b.close()
+
+
+# ------------------------------------------------------------------- linear
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("n,K,F", [(1000, 100, 256), (333, 64, 64), (4097, 128, 256), (130, 256, 40)])
+def test_linear_parity(dtype, n, K, F):
+    rng = np.random.default_rng(10)
+    X = feats(rng, n, K, dtype).cuda()
+    W = torch.from_numpy((rng.standard_normal((K, F)) * 0.1).astype(np.float32)).cuda()
+    dZ = feats(rng, n, F, dtype).cuda()
+    Z, _, _ = gu.linear_fwd(X, W)
+    assert rel_err(f64(Z), orc.linear_fwd(f64(X), f64(W))) < (1e-4 if dtype == torch.float32 else 2e-2)
+    dW = torch.zeros_like(W)
+    dX = gu.linear_bwd(X, dZ, W, dW)
+    want_dW, want_dX = orc.linear_bwd(f64(X), f64(dZ), f64(W))
+    assert rel_err(f64(dW), want_dW) < 1e-4      # dW is fp32 in both storage types
+    assert rel_err(f64(dX), want_dX) < TOL[dtype]
+    # accumulates
+    gu.linear_bwd(X, dZ, W, dW)
+    assert rel_err(f64(dW), 2 * want_dW) < 1e-4
