@@ -1,0 +1,252 @@
+#!/usr/bin/env python3
+"""Benchmark of the SAR aggregation hot path on one MI355X.
+
+One "step" is one pass of worker p's GAT layer over all P resident source
+blocks, forward and rematerialising backward:
+
+    Z_p = X_p W (+ score halves s, t_p)                     MFMA
+    t_q = <a_l, Z_q> for every fetched block                 node-wise
+    fused attention forward over the P blocks               (dominant gather)
+    backward begin, fused attention backward over P blocks, backward end
+    dW, dX for the worker's own rows                         MFMA
+
+Inputs are synthetic and already resident in HBM when the timed region starts
+(the feature blocks Z_q of the other partitions stand for what a worker would
+have fetched; they are produced before timing).  The metric is the worker's
+in-edges processed per second of forward+backward.
+
+Prints ONE JSON line.  --gpus above 1 is refused: this build is single-GPU.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink the graph (debugging only)")
+    ap.add_argument("--mode", default="all", choices=["all", "stream"],
+                    help="all: one launch over the P blocks; stream: one launch per block")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-blocks", type=int, default=1, help="blocks in the oracle's timed sample")
+    return ap.parse_args()
+
+
+class Layer:
+    """Device state of one worker's GAT layer; methods only call the C ABI."""
+
+    def __init__(self, w, torch, sar, synth):
+        self.torch, self.sar, self.w = torch, sar, w
+        dev = "cuda"
+        H, D, P, p = w.H, w.D, w.P, w.p
+        self.H, self.D, self.F, self.P, self.p = H, D, H * D, P, p
+        t0 = time.perf_counter()
+        self.blocks = sar.sar_blocks_build(w.src, w.dst, w.part, P, p)
+        torch.cuda.synchronize()
+        self.builder_s = time.perf_counter() - t0
+        self.views = [self.blocks.view(q) for q in range(P)]
+        self.E = sum(v.nnz for v in self.views)
+        n = self.blocks.n_dst
+        self.n = n
+        self.W, self.a_l, self.a_r = synth.gat_params(3, w.f_in, H, D, device=dev)
+        members = [w.members(q) for q in range(P)]
+        self.members = members
+        self.X = synth.normal_rows(2, members[p], w.f_in, dtype=w.dtype)
+        self.G = synth.normal_rows(4, members[p], self.F, dtype=w.dtype).reshape(n, H, D)
+        # features of the other partitions, as fetched: Z_q = X_q W produced before timing
+        self.Zs, self.ts = [], []
+        for q in range(P):
+            Xq = synth.normal_rows(2, members[q], w.f_in, dtype=w.dtype)
+            Zq = torch.empty((Xq.shape[0], self.F), dtype=w.dtype, device=dev)
+            sar.sar_linear_fwd(Xq, self.W, Zq)
+            self.Zs.append(Zq.reshape(-1, H, D))
+            self.ts.append(torch.empty((Xq.shape[0], H), dtype=torch.float32, device=dev))
+            del Xq
+        f32 = dict(dtype=torch.float32, device=dev)
+        self.Zp = torch.empty((n, H, D), dtype=w.dtype, device=dev)
+        self.s = torch.empty((n, H), **f32)
+        self.tp = torch.empty((n, H), **f32)
+        self.m = torch.empty((n, H), **f32)
+        self.l = torch.empty((n, H), **f32)
+        self.acc = torch.empty((n, H, D), **f32)
+        self.out = torch.empty((n, H, D), dtype=w.dtype, device=dev)
+        self.L = torch.empty((n, H), **f32)
+        self.rec = torch.empty((n, H, 4), **f32)
+        self.ds = torch.empty((n, H), **f32)
+        self.dZs = [torch.empty_like(z) for z in self.Zs]
+        self.dts = [torch.empty((z.shape[0], H), **f32) for z in self.Zs]
+        self.dZdst = torch.empty((n, H, D), dtype=w.dtype, device=dev)
+        self.da_l = torch.zeros((H, D), **f32)
+        self.da_r = torch.zeros((H, D), **f32)
+        self.dW = torch.zeros_like(self.W)
+        self.dX_dst = torch.empty_like(self.X)
+        self.dX_src = torch.empty_like(self.X)
+        n_src_max = max(v.n_src for v in self.views)
+        self.work = torch.empty(sar.sar_gat_workspace_bytes(n, n_src_max, H, D) // 4, **f32)
+        self.lwork = torch.empty(max(1, sar.sar_linear_workspace_bytes(n, w.f_in, self.F) // 4), **f32)
+        torch.cuda.synchronize()
+
+    def step(self, mode, ev=None):
+        sar, P, p, w = self.sar, self.P, self.p, self.w
+        mark = (lambda k: ev[k].record()) if ev is not None else (lambda k: None)
+        mark("t0")
+        # Eq. 1 for the worker's own rows, with both score halves
+        sar.sar_linear_fwd(self.X, self.W, self.Zp.reshape(self.n, self.F), self.a_r, self.s, self.a_l, self.tp)
+        Zs = list(self.Zs)
+        Zs[p] = self.Zp                      # the local block reads the rows just produced
+        for q in range(P):
+            sar.sar_gat_scores(Zs[q], self.a_l, self.ts[q])
+        mark("fwd0")
+        if mode == "all":
+            sar.sar_gat_fwd_all(self.blocks, Zs, self.s, self.ts, w.slope, self.out, self.L)
+        else:
+            sar.sar_gat_fwd_begin(self.m, self.l, self.acc)
+            for q in range(P):
+                sar.sar_gat_fwd_block(self.blocks, q, Zs[q], self.s, self.ts[q], w.slope, self.m, self.l, self.acc)
+            sar.sar_gat_fwd_end(self.m, self.l, self.acc, self.out, self.L)
+        mark("fwd1")
+        sar.sar_gat_bwd_begin(self.G, self.out, self.s, self.L, self.rec, self.ds)
+        self.da_l.zero_()
+        self.da_r.zero_()
+        self.dW.zero_()
+        mark("bwd0")
+        if mode == "all":
+            sar.sar_gat_bwd_all(self.blocks, Zs, self.G, self.ts, self.rec, self.a_l, w.slope, self.dZs, self.dts,
+                                self.ds, self.da_l, self.work)
+        else:
+            for q in range(P):
+                sar.sar_gat_bwd_block(self.blocks, q, Zs[q], self.G, self.ts[q], self.rec, self.a_l, w.slope,
+                                      self.dZs[q], self.dts[q], self.ds, self.da_l, self.work)
+        mark("bwd1")
+        sar.sar_gat_bwd_end(self.Zp, self.ds, self.a_r, self.dZdst, self.da_r, self.work)
+        # Z_p.backward(E_p) with the errors this worker itself produced for its rows
+        sar.sar_linear_bwd(self.X, self.dZdst, self.W, self.dW, self.dX_dst, self.lwork)
+        sar.sar_linear_bwd(self.X, self.dZs[p], self.W, self.dW, self.dX_src, self.lwork)
+        mark("t1")
+
+    # ---- algorithmic bytes of the two gather launches (what the method must move)
+    def alg_bytes(self):
+        fb = 2 if self.w.dtype == self.torch.bfloat16 else 4
+        F, H, n, E = self.F, self.H, self.n, self.E
+        touched = sum(v.n_t_rows for v in self.views)
+        n_src = sum(v.n_src for v in self.views)
+        fwd = (4 * E + 4 * (n + 1) + 4 * n            # tagged index, row offsets, launch list
+               + touched * (F * fb + H * 4)           # each touched source row and its t once
+               + n * (H * 4 + F * fb + H * 4))        # s read, out and L written
+        bwd = (4 * E + 4 * (n_src + self.P) + 4 * touched   # transposed index, offsets, launch list
+               + touched * (F * fb + H * 4)           # z_j, t_j read once (the rematerialisation)
+               + n_src * (F * fb + H * 4)             # dZ_q, dt_q written once
+               + n * (F * fb + H * 16 + 2 * H * 4))   # G and the record read once, ds read-modify-write
+        return fwd, bwd
+
+
+def cpu_baseline(layer, n_blocks):
+    """The oracle, as it stands, on the first n_blocks blocks of the same workload."""
+    import numpy as np
+    from oracle import sar_oracle as orc
+    torch, w = layer.torch, layer.w
+    f64 = lambda t: t.to(torch.float64).cpu().numpy()
+    src, dst, part = w.src.cpu().numpy(), w.dst.cpu().numpy(), w.part.cpu().numpy()
+    keep = np.isin(part[src], np.arange(n_blocks))
+    blocks, _ = orc.build_blocks(src[keep], dst[keep], part, w.P, w.p)
+    blocks = blocks[:n_blocks]
+    W = f64(layer.W)
+    Xp = f64(layer.X)
+    from paper_2111_06483_amd import synth
+    Xs = [f64(synth.normal_rows(2, layer.members[q].cpu(), w.f_in, dtype=w.dtype)) for q in range(n_blocks)]
+    a_l, a_r, G = f64(layer.a_l), f64(layer.a_r), f64(layer.G)
+    t0 = time.perf_counter()
+    Zdst = orc.linear_fwd(Xp, W)
+    Zs = [orc.linear_fwd(X, W) for X in Xs]
+    fwd = orc.gat_fwd(blocks, Zdst, Zs, a_l, a_r, w.slope)
+    bwd = orc.gat_bwd(blocks, Zdst, Zs, G, a_l, a_r, w.slope, fwd)
+    orc.linear_bwd(Xp, bwd.dZdst, W)
+    dt = time.perf_counter() - t0
+    edges = sum(b.nnz for b in blocks)
+    return {"value": edges / dt, "unit": "edges/s", "cores": 1, "kind": "oracle",
+            "sample": "%d of %d source blocks of the same workload (%d edges), forward+backward, fp64, %.1f s"
+                      % (n_blocks, w.P, edges, dt)}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported"
+              % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2111_06483_amd import sar, synth
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    sar.lib()
+    torch.cuda.set_device(0)
+    w = synth.make_workload(args.workload, device="cuda", scale=args.scale)
+    layer = Layer(w, torch, sar, synth)
+
+    for _ in range(args.warmup):
+        layer.step(args.mode)
+    torch.cuda.synchronize()
+    names = ["t0", "fwd0", "fwd1", "bwd0", "bwd1", "t1"]
+    evs = [{k: torch.cuda.Event(enable_timing=True) for k in names} for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        layer.step(args.mode, evs[k])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_step = wall * 1e3 / args.steps
+    avg = lambda a, b: sum(e[a].elapsed_time(e[b]) for e in evs) / len(evs)
+    fwd_ms, bwd_ms, all_ms = avg("fwd0", "fwd1"), avg("bwd0", "bwd1"), avg("t0", "t1")
+
+    fwd_b, bwd_b = layer.alg_bytes()
+    if bwd_ms >= fwd_ms:
+        dom, dom_b, dom_ms = "gat_bwd", bwd_b, bwd_ms
+    else:
+        dom, dom_b, dom_ms = "gat_fwd", fwd_b, fwd_ms
+    achieved = dom_b / (dom_ms * 1e-3) / 1e9
+    fb = 2 if w.dtype == torch.bfloat16 else 4
+    res = {
+        "metric": "fused GAT fwd+bwd edges/sec per GPU",
+        "value": layer.E / (ms_step * 1e-3),
+        "unit": "edges/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if w.dtype == torch.float32 else "bf16 storage, f32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": "%s: one worker's share of a %d-node power-law graph, %d-way split, %d destinations, "
+                               "%d in-edges over %d resident source blocks, GAT %d heads x %d, in_dim %d"
+                               % (args.workload, w.N, w.P, layer.n, layer.E, w.P, w.H, w.D, w.f_in),
+                   "mode": args.mode, "scale": args.scale},
+        "phases_ms": {"step_events": all_ms, "gat_fwd": fwd_ms, "gat_bwd": bwd_ms,
+                      "other (XW fwd+bwd, scores, begin/end)": all_ms - fwd_ms - bwd_ms},
+        "aggregation_only_edges_per_s": layer.E / ((fwd_ms + bwd_ms) * 1e-3),
+        "builder_s": layer.builder_s,
+        "roofline": {"bound": "hbm", "kernel": "k_%s (all blocks)" % dom if args.mode == "all" else "k_%s" % dom,
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None,
+                     "alg_bytes_per_launch": dom_b, "avg_launch_ms": dom_ms,
+                     "gather_volume_GBs": layer.E * layer.F * fb / (dom_ms * 1e-3) / 1e9,
+                     "fwd": {"alg_bytes": fwd_b, "ms": fwd_ms, "GBs": fwd_b / (fwd_ms * 1e-3) / 1e9},
+                     "bwd": {"alg_bytes": bwd_b, "ms": bwd_ms, "GBs": bwd_b / (bwd_ms * 1e-3) / 1e9}},
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(layer, args.cpu_blocks)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()
