@@ -37,7 +37,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the graph (debugging only)")
     ap.add_argument("--mode", default="all", choices=["all", "stream"],
                     help="all: one launch over the P blocks; stream: one launch per block")
@@ -182,6 +182,47 @@ def cpu_baseline(layer, n_blocks):
                       % (n_blocks, w.P, edges, dt)}
 
 
+def spmm_bench(args, w, torch, sar, synth):
+    """Config 2: GraphSage mean aggregation only (Eq. 2) over the P resident blocks."""
+    P, p, F = w.P, w.p, w.H * w.D
+    blocks = sar.sar_blocks_build(w.src, w.dst, w.part, P, p)
+    views = [blocks.view(q) for q in range(P)]
+    E = sum(v.nnz for v in views)
+    n = blocks.n_dst
+    Zs = [synth.normal_rows(2, w.members(q), F, dtype=w.dtype) for q in range(P)]
+    acc = torch.zeros((n, F), dtype=torch.float32, device="cuda")
+    out = torch.empty((n, F), dtype=w.dtype, device="cuda")
+    deg = sar.sar_blocks_degree(blocks)
+
+    def step():
+        if args.mode == "all":
+            sar.sar_spmm_all(blocks, Zs, True, out)
+        else:
+            acc.zero_()
+            for q in range(P):
+                sar.sar_spmm_block(blocks, q, Zs[q], acc)
+            sar.sar_spmm_end(deg, True, acc, out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    fb = 4
+    touched = sum(v.n_t_rows for v in views)
+    alg = 4 * E + 8 * n + touched * F * fb + n * F * fb
+    print(json.dumps({"metric": "SpMM mean aggregation edges/sec per GPU", "value": E / (ms * 1e-3), "unit": "edges/s",
+                      "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+                      "config": {"workload": "cfg2: %d destinations, %d in-edges, %d blocks, F=%d fp32" % (n, E, P, F),
+                                 "mode": args.mode},
+                      "roofline": {"bound": "hbm", "achieved": alg / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                                   "unit": "GB/s", "frac": alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                   "alg_bytes_per_launch": alg, "gather_volume_GBs": E * F * fb / (ms * 1e-3) / 1e9}}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -194,6 +235,9 @@ def main():
     sar.lib()
     torch.cuda.set_device(0)
     w = synth.make_workload(args.workload, device="cuda", scale=args.scale)
+    if args.workload == "cfg2":
+        spmm_bench(args, w, torch, sar, synth)
+        return
     layer = Layer(w, torch, sar, synth)
 
     for _ in range(args.warmup):

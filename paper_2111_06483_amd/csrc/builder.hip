@@ -370,33 +370,34 @@ __global__ __launch_bounds__(kThreads) void k_class_hist(const int32_t* __restri
     __syncthreads();
     for (int64_t r = (int64_t)blockIdx.x * kThreads + threadIdx.x; r < n;
          r += (int64_t)gridDim.x * kThreads) {
-        const int c = degree_class(off[r + 1] - off[r]);
-        if (c > 0) atomicAdd(&h[c], 1);
+        atomicAdd(&h[degree_class(off[r + 1] - off[r])], 1);
     }
     __syncthreads();
     if (threadIdx.x < sar::kNumClasses && h[threadIdx.x]) atomicAdd(&hist[threadIdx.x], h[threadIdx.x]);
 }
 
 // cursor[c] starts at the first slot of class c; value written = r | tag.
+// Rows without edges (class 0) are listed last, and only if with_empty.
 __global__ __launch_bounds__(kThreads) void k_class_place(const int32_t* __restrict__ off, int64_t n,
                                                           int* __restrict__ cursor, uint32_t tag,
-                                                          uint32_t* __restrict__ out)
+                                                          bool with_empty, uint32_t* __restrict__ out)
 {
     __shared__ int h[sar::kNumClasses];
     __shared__ int base[sar::kNumClasses];
     const int64_t r = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (threadIdx.x < sar::kNumClasses) h[threadIdx.x] = 0;
     __syncthreads();
-    int c = 0, local = 0;
+    int c = -1, local = 0;
     if (r < n) {
         c = degree_class(off[r + 1] - off[r]);
-        if (c > 0) local = atomicAdd(&h[c], 1);
+        if (c == 0 && !with_empty) c = -1;
+        if (c >= 0) local = atomicAdd(&h[c], 1);
     }
     __syncthreads();
     if (threadIdx.x < sar::kNumClasses && h[threadIdx.x])
         base[threadIdx.x] = atomicAdd(&cursor[threadIdx.x], h[threadIdx.x]);
     __syncthreads();
-    if (c > 0) out[base[c] + local] = (uint32_t)r | tag;
+    if (c >= 0) out[base[c] + local] = (uint32_t)r | tag;
 }
 
 struct ClassLayout {
@@ -611,7 +612,7 @@ int derive(sar_blocks* h, hipStream_t st)
     for (int q = 0; q < P; ++q) {
         h->blk[q].rows = rows_all + rows_base[q];
         k_class_place<<<grid_for(n_dst, kThreads, 1 << 23), kThreads, 0, st>>>(h->blk[q].indptr, n_dst,
-                                                            hist_d + q * sar::kNumClasses, 0u,
+                                                            hist_d + q * sar::kNumClasses, 0u, false,
                                                             reinterpret_cast<uint32_t*>(h->blk[q].rows));
         SAR_LAUNCH_CHECK();
     }
@@ -642,9 +643,9 @@ int derive(sar_blocks* h, hipStream_t st)
         ClassLayout L = layout_from_hist(fhist, 0);
         h->n_f_rows = L.n_rows;
         h->n_f_long = L.n_long;
-        SAR_TRY(own(h, &h->f_rows, L.n_rows));
+        SAR_TRY(own(h, &h->f_rows, n_dst));
         SAR_HIP(hipMemcpyAsync(fh, L.start, sizeof(L.start), hipMemcpyHostToDevice, st));
-        k_class_place<<<grid_for(n_dst, kThreads, 1 << 23), kThreads, 0, st>>>(h->f_indptr, n_dst, fh, 0u,
+        k_class_place<<<grid_for(n_dst, kThreads, 1 << 23), kThreads, 0, st>>>(h->f_indptr, n_dst, fh, 0u, true,
                                                             reinterpret_cast<uint32_t*>(h->f_rows));
         SAR_LAUNCH_CHECK();
         SAR_HIP(hipStreamSynchronize(st));
@@ -722,21 +723,23 @@ int derive(sar_blocks* h, hipStream_t st)
         h->n_ft_long = LA.n_long;
         memcpy(&cursors[P * sar::kNumClasses], LA.start, sizeof(LA.start));
         int32_t *t_rows_all = nullptr, *touched_all = nullptr;
-        SAR_TRY(own(h, &t_rows_all, t_rows_total));
+        // the launch lists also carry the sources without edges (last), so that the
+        // backward kernels write every row of dZ_q; `touched` holds only the others
+        SAR_TRY(own(h, &t_rows_all, n_src_total));
         SAR_TRY(own(h, &touched_all, t_rows_total));
-        SAR_TRY(own(h, &h->ft_rows, t_rows_total));
+        SAR_TRY(own(h, &h->ft_rows, n_src_total));
         SAR_HIP(hipMemcpyAsync(hist_d, cursors.data(), n_hist * sizeof(int), hipMemcpyHostToDevice, st));
         for (int q = 0; q < P; ++q) {
             Block& b = h->blk[q];
-            b.t_rows = t_rows_all + t_base[q];
+            b.t_rows = t_rows_all + coff[q];
             b.touched = touched_all + t_base[q];
             k_class_place<<<grid_for(b.n_src, kThreads, 1 << 23), kThreads, 0, st>>>(b.t_indptr, b.n_src,
-                                                                  hist_d + q * sar::kNumClasses, 0u,
+                                                                  hist_d + q * sar::kNumClasses, 0u, true,
                                                                   reinterpret_cast<uint32_t*>(b.t_rows));
             SAR_LAUNCH_CHECK();
             k_class_place<<<grid_for(b.n_src, kThreads, 1 << 23), kThreads, 0, st>>>(b.t_indptr, b.n_src,
                                                                   hist_d + P * sar::kNumClasses,
-                                                                  (uint32_t)q << h->tag_shift, h->ft_rows);
+                                                                  (uint32_t)q << h->tag_shift, true, h->ft_rows);
             SAR_LAUNCH_CHECK();
         }
         // touched = ascending ids of the sources with an edge: compaction by scan

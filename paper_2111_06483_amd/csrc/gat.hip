@@ -20,6 +20,7 @@
 #include <algorithm>
 
 #include "gather_common.h"
+#include "gat_f256.h"
 #include "sar_internal.h"
 
 namespace {
@@ -612,22 +613,6 @@ __global__ __launch_bounds__(kGatherThreads) void k_bwd_end(const T* __restrict_
     }
 }
 
-// Rows the launch lists skip (no edge): typed row = 0, per-head scalar = fill.
-template <typename T>
-__global__ __launch_bounds__(256) void k_fill_rows_without_edges(const int32_t* __restrict__ indptr, int64_t n,
-                                                                 int H, int F, T* __restrict__ rows_out,
-                                                                 float* __restrict__ per_head, float fill)
-{
-    const int64_t total = n * F;
-    for (int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x; k < total; k += (int64_t)gridDim.x * 256) {
-        const int64_t i = k / F;
-        if (indptr[i + 1] != indptr[i]) continue;
-        rows_out[k] = T{};
-        const int f = (int)(k - i * F);
-        if (per_head && f < H) per_head[i * H + f] = fill;
-    }
-}
-
 // --------------------------------------------------------------- host side
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -666,12 +651,94 @@ unsigned nodewise_grid(int64_t n, int slots)
         default: { constexpr int kG = 64; CALL; } break;                              \
     }
 
+// Workgroups that can be resident at once for kernel `fn` (persistent grids are
+// sized to this, so that every workgroup starts immediately).
+template <typename Fn>
+int resident_workgroups(Fn fn)
+{
+    static int n_cu = 0;
+    if (n_cu == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return kMaxPersistentWGs;
+        n_cu = prop.multiProcessorCount;
+    }
+    int per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kGatherThreads, 0) != hipSuccess || per_cu <= 0)
+        return kMaxPersistentWGs;
+    return std::min(kMaxPersistentWGs, n_cu * per_cu);
+}
+
+unsigned persistent_grid_for(int64_t n_rows, int64_t n_long, int resident)
+{
+    const int64_t want = n_long + (n_rows - n_long + kWavesPerWG - 1) / kWavesPerWG;
+    return (unsigned)std::max<int64_t>(1, std::min<int64_t>(want, resident));
+}
+
+// F = 256 and a power-of-two head width: the specialised kernels apply.
+int fast_lph(int H, int D)
+{
+    if (H * D != f256::kF || D % 4 != 0) return 0;
+    const int lph = D / 4;
+    return (lph >= 4 && (lph & (lph - 1)) == 0) ? lph : 0;
+}
+
+template <typename T, int LPH, bool ALL>
+int launch_fwd_f256(const FwdArgs& a, const PtrTab& zt, const PtrTab& tt, hipStream_t st)
+{
+    constexpr int B = LPH >= 8 ? 8 : 4;
+    auto fn = f256::k_gat_fwd_f256<T, LPH, B, ALL>;
+    static const int resident = resident_workgroups(fn);
+    f256::FwdP p{};
+    p.indptr = a.indptr; p.indices = a.indices; p.rows = a.rows;
+    p.n_rows = a.n_rows; p.n_long = a.n_long;
+    p.Z = a.Z; p.t = a.t; p.s = a.s; p.m = a.m; p.l = a.l; p.acc = a.acc; p.out = a.out; p.L = a.L;
+    p.H = a.H; p.tag_shift = a.tag_shift; p.slope = a.slope;
+    f256::Tabs tabs{};
+    for (int q = 0; q < SAR_MAX_BLOCKS; ++q) {
+        tabs.Z[q] = zt.p[q];
+        tabs.t[q] = static_cast<const float*>(tt.p[q]);
+    }
+    fn<<<persistent_grid_for(a.n_rows, a.n_long, resident), kGatherThreads, 0, st>>>(p, tabs);
+    SAR_LAUNCH_CHECK();
+    return SAR_OK;
+}
+
 template <typename T, bool ALL>
 int launch_fwd(const FwdArgs& a, const PtrTab& zt, const PtrTab& tt, int P, hipStream_t st)
 {
     if (a.n_rows == 0) return SAR_OK;
+    switch (fast_lph(a.H, a.D)) {
+        case 4: return launch_fwd_f256<T, 4, ALL>(a, zt, tt, st);
+        case 8: return launch_fwd_f256<T, 8, ALL>(a, zt, tt, st);
+        case 16: return launch_fwd_f256<T, 16, ALL>(a, zt, tt, st);
+        case 32: return launch_fwd_f256<T, 32, ALL>(a, zt, tt, st);
+        case 64: return launch_fwd_f256<T, 64, ALL>(a, zt, tt, st);
+        default: break;
+    }
     const unsigned grid = persistent_grid(a.n_rows, a.n_long);
     SAR_DISPATCH_G(T, a.F, (k_gat_fwd<T, kG, ALL><<<grid, kGatherThreads, 0, st>>>(a, zt, tt, P)));
+    SAR_LAUNCH_CHECK();
+    return SAR_OK;
+}
+
+template <typename T, int LPH, bool ALL>
+int launch_bwd_f256(const BwdArgs& tabs, const BwdScalars& a, unsigned* grid_out, hipStream_t st)
+{
+    constexpr int B = LPH >= 8 ? 8 : 4;
+    auto fn = f256::k_gat_bwd_f256<T, LPH, B, ALL>;
+    static const int resident = resident_workgroups(fn);
+    f256::BwdTabs t{};
+    for (int q = 0; q < SAR_MAX_BLOCKS; ++q) {
+        t.t_indptr[q] = tabs.t_indptr[q]; t.t_indices[q] = tabs.t_indices[q];
+        t.Z[q] = tabs.Z[q]; t.t[q] = tabs.t[q]; t.dZ[q] = tabs.dZ[q]; t.dt[q] = tabs.dt[q];
+    }
+    f256::BwdP p{};
+    p.rows = a.rows; p.n_rows = a.n_rows; p.n_long = a.n_long;
+    p.G = a.G; p.rec = a.rec; p.a_l = a.a_l; p.ds = a.ds; p.partial = a.partial;
+    p.H = a.H; p.tag_shift = a.tag_shift; p.slope = a.slope;
+    *grid_out = persistent_grid_for(a.n_rows, a.n_long, resident);
+    fn<<<*grid_out, kGatherThreads, 0, st>>>(t, p);
     SAR_LAUNCH_CHECK();
     return SAR_OK;
 }
@@ -680,9 +747,18 @@ template <typename T, bool ALL>
 int launch_bwd(const BwdArgs& tabs, BwdScalars& a, float* da_l, hipStream_t st)
 {
     if (a.n_rows == 0) return SAR_OK;
-    const unsigned grid = persistent_grid(a.n_rows, a.n_long);
-    SAR_DISPATCH_G(T, a.F, (k_gat_bwd<T, kG, ALL><<<grid, kGatherThreads, 0, st>>>(tabs, a)));
-    SAR_LAUNCH_CHECK();
+    unsigned grid = persistent_grid(a.n_rows, a.n_long);
+    switch (fast_lph(a.H, a.D)) {
+        case 4: SAR_TRY((launch_bwd_f256<T, 4, ALL>(tabs, a, &grid, st))); break;
+        case 8: SAR_TRY((launch_bwd_f256<T, 8, ALL>(tabs, a, &grid, st))); break;
+        case 16: SAR_TRY((launch_bwd_f256<T, 16, ALL>(tabs, a, &grid, st))); break;
+        case 32: SAR_TRY((launch_bwd_f256<T, 32, ALL>(tabs, a, &grid, st))); break;
+        case 64: SAR_TRY((launch_bwd_f256<T, 64, ALL>(tabs, a, &grid, st))); break;
+        default:
+            SAR_DISPATCH_G(T, a.F, (k_gat_bwd<T, kG, ALL><<<grid, kGatherThreads, 0, st>>>(tabs, a)));
+            SAR_LAUNCH_CHECK();
+            break;
+    }
     k_reduce_partials<<<a.F, 256, 0, st>>>(a.partial, (int)grid, a.F, da_l);
     SAR_LAUNCH_CHECK();
     return SAR_OK;
@@ -800,7 +876,7 @@ extern "C" int sar_gat_fwd_all(const sar_blocks_t* b, const void* const* Zq, con
     a.indptr = b->f_indptr;
     a.indices = b->f_indices;
     a.rows = reinterpret_cast<const uint32_t*>(b->f_rows);
-    a.n_rows = b->n_f_rows;
+    a.n_rows = b->n_dst;   // the list ends with the destinations that have no in-edge: out = 0, L = -inf
     a.n_long = b->n_f_long;
     a.s = s;
     a.out = out;
@@ -810,17 +886,6 @@ extern "C" int sar_gat_fwd_all(const sar_blocks_t* b, const void* const* Zq, con
     a.F = H * D;
     a.tag_shift = b->tag_shift;
     a.slope = slope;
-    if (b->n_f_rows < b->n_dst) {
-        // destinations without any in-edge: out = 0, L = -inf
-        const unsigned gz = (unsigned)std::min<int64_t>((b->n_dst * a.F + 255) / 256, 1 << 16);
-        if (dtype == SAR_F32)
-            k_fill_rows_without_edges<float><<<gz, 256, 0, st>>>(b->f_indptr, b->n_dst, H, a.F,
-                                                                 static_cast<float*>(out), L, -INFINITY);
-        else
-            k_fill_rows_without_edges<bf16_t><<<gz, 256, 0, st>>>(b->f_indptr, b->n_dst, H, a.F,
-                                                                  static_cast<bf16_t*>(out), L, -INFINITY);
-        SAR_LAUNCH_CHECK();
-    }
     int rc;
     if (dtype == SAR_F32)
         rc = launch_fwd<float, true>(a, zt, tt, b->P, st);
@@ -862,16 +927,6 @@ extern "C" int sar_gat_bwd_begin(const void* G, const void* out, const float* s,
 
 namespace {
 
-template <typename T>
-int zero_untouched_sources(const sar::Block& k, int H, int F, void* dZq, float* dtq, hipStream_t st)
-{
-    if (k.n_t_rows == k.n_src) return SAR_OK;
-    const unsigned gz = (unsigned)std::min<int64_t>((k.n_src * F + 255) / 256, 1 << 16);
-    k_fill_rows_without_edges<T><<<gz, 256, 0, st>>>(k.t_indptr, k.n_src, H, F, static_cast<T*>(dZq), dtq, 0.f);
-    SAR_LAUNCH_CHECK();
-    return SAR_OK;
-}
-
 int bwd_common_checks(const sar_blocks_t* b, int dtype, int H, int D, const void* G, const float* rec,
                       const float* a_l, const float* ds, const float* da_l, const void* work, size_t work_bytes)
 {
@@ -910,7 +965,7 @@ extern "C" int sar_gat_bwd_block(const sar_blocks_t* b, int q, const void* Zq, c
     tabs.dt[0] = dtq;
     BwdScalars a{};
     a.rows = reinterpret_cast<const uint32_t*>(k.t_rows);
-    a.n_rows = k.n_t_rows;
+    a.n_rows = k.n_src;    // sources without edges come last and get dZ = 0, dt = 0
     a.n_long = k.n_t_long;
     a.G = G;
     a.rec = reinterpret_cast<const float4*>(rec);
@@ -921,11 +976,7 @@ extern "C" int sar_gat_bwd_block(const sar_blocks_t* b, int q, const void* Zq, c
     a.D = D;
     a.F = H * D;
     a.slope = slope;
-    if (dtype == SAR_F32) {
-        SAR_TRY(zero_untouched_sources<float>(k, H, a.F, dZq, dtq, st));
-        return launch_bwd<float, false>(tabs, a, da_l, st);
-    }
-    SAR_TRY(zero_untouched_sources<bf16_t>(k, H, a.F, dZq, dtq, st));
+    if (dtype == SAR_F32) return launch_bwd<float, false>(tabs, a, da_l, st);
     return launch_bwd<bf16_t, false>(tabs, a, da_l, st);
 }
 
@@ -950,14 +1001,11 @@ extern "C" int sar_gat_bwd_all(const sar_blocks_t* b, const void* const* Zq, con
         tabs.t[q] = tq[q];
         tabs.dZ[q] = dZq[q];
         tabs.dt[q] = dtq[q];
-        if (dtype == SAR_F32)
-            SAR_TRY(zero_untouched_sources<float>(k, H, F, dZq[q], dtq[q], st));
-        else
-            SAR_TRY(zero_untouched_sources<bf16_t>(k, H, F, dZq[q], dtq[q], st));
     }
     BwdScalars a{};
     a.rows = b->ft_rows;
-    a.n_rows = b->n_ft_rows;
+    a.n_rows = 0;
+    for (int q = 0; q < b->P; ++q) a.n_rows += b->blk[q].n_src;
     a.n_long = b->n_ft_long;
     a.G = G;
     a.rec = reinterpret_cast<const float4*>(rec);

@@ -1,0 +1,459 @@
+// Fused attention kernels specialised for rows of F = 256 values (1 KiB fp32 or
+// 512 B bf16): the whole wavefront covers one row, lane x owns features
+// 4x..4x+3, and a head is a group of LPH = D/4 consecutive lanes.
+//
+// Per-edge scalars (score, softmax weight, score gradient) are not computed
+// redundantly by every lane of a head.  Edges are taken in sub-batches of up
+// to B, and inside a head group lane k works on edge k of the sub-batch: the
+// scores of B edges x H heads are formed by one instruction stream, then each
+// weight is broadcast back to its head group (DS_SWIZZLE) for the
+// multiply-add with the gathered row.  Row addresses come from scalar
+// registers (V_READLANE of the coalesced index chunk), so the gathers are
+// SGPR-base + lane-offset loads with up to B rows in flight per wavefront.
+#pragma once
+
+#include <type_traits>
+
+#include "../../include/sar_mi355x.h"
+#include "gather_common.h"
+
+namespace sar {
+namespace f256 {
+
+constexpr int kF = 256;
+
+// ---- cross-lane helpers (wave64, DPP rows of 16 lanes) --------------------
+
+template <int CTRL>
+__device__ inline float dpp(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+constexpr int kQuadXor1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int kQuadXor2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int kRowHalfMirror = 0x141;
+constexpr int kRowRor4 = 0x124;
+constexpr int kRowRor8 = 0x128;
+
+template <int PATTERN>
+__device__ inline float swizzle(float v)
+{
+    return __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(v), PATTERN));
+}
+
+struct OpSum {
+    static __device__ inline float f(float a, float b) { return a + b; }
+};
+struct OpMax {
+    static __device__ inline float f(float a, float b) { return fmaxf(a, b); }
+};
+
+// All-reduce over each group of LPH consecutive lanes (LPH = 4..64, power of two).
+template <int LPH, typename Op>
+__device__ inline float group_all(float v)
+{
+    v = Op::f(v, dpp<kQuadXor1>(v));
+    v = Op::f(v, dpp<kQuadXor2>(v));
+    if constexpr (LPH == 8) v = Op::f(v, dpp<kRowHalfMirror>(v));
+    if constexpr (LPH >= 16) {
+        v = Op::f(v, dpp<kRowRor4>(v));
+        v = Op::f(v, dpp<kRowRor8>(v));
+    }
+    if constexpr (LPH >= 32) v = Op::f(v, swizzle<0x401F>(v));   // xor 16
+    if constexpr (LPH >= 64) v = Op::f(v, __shfl_xor(v, 32));
+    return v;
+}
+
+// Value held by lane K of the caller's head group, delivered to the whole group.
+template <int LPH, int K>
+__device__ inline float group_bcast(float v)
+{
+    if constexpr (LPH >= 64) {
+        return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), K));
+    } else {
+        constexpr int kAnd = (LPH >= 32) ? 0x00 : (0x1F & ~(LPH - 1));
+        return swizzle<(K << 5) | kAnd>(v);
+    }
+}
+
+template <int N, typename Fn>
+__device__ inline void static_for(Fn&& fn)
+{
+    if constexpr (N > 0) {
+        static_for<N - 1>(fn);
+        fn(std::integral_constant<int, N - 1>{});
+    }
+}
+
+// ---- row access: 4 values per lane ---------------------------------------
+
+template <typename T>
+struct Row4;
+template <>
+struct Row4<float> {
+    using Raw = float4;
+    static __device__ inline Raw load(const float* row, int lane) { return reinterpret_cast<const float4*>(row)[lane]; }
+    static __device__ inline void unpack(const Raw& r, float (&v)[4])
+    {
+        v[0] = r.x; v[1] = r.y; v[2] = r.z; v[3] = r.w;
+    }
+    static __device__ inline void store(float* row, int lane, const float (&v)[4])
+    {
+        reinterpret_cast<float4*>(row)[lane] = make_float4(v[0], v[1], v[2], v[3]);
+    }
+};
+template <>
+struct Row4<bf16_t> {
+    using Raw = uint2;
+    static __device__ inline Raw load(const bf16_t* row, int lane) { return reinterpret_cast<const uint2*>(row)[lane]; }
+    static __device__ inline void unpack(const Raw& r, float (&v)[4])
+    {
+        v[0] = __uint_as_float(r.x << 16);
+        v[1] = __uint_as_float(r.x & 0xffff0000u);
+        v[2] = __uint_as_float(r.y << 16);
+        v[3] = __uint_as_float(r.y & 0xffff0000u);
+    }
+    static __device__ inline void store(bf16_t* row, int lane, const float (&v)[4])
+    {
+        uint2 r;
+        r.x = f32_to_bf16_rne(v[0]) | (f32_to_bf16_rne(v[1]) << 16);
+        r.y = f32_to_bf16_rne(v[2]) | (f32_to_bf16_rne(v[3]) << 16);
+        reinterpret_cast<uint2*>(row)[lane] = r;
+    }
+};
+
+struct Tabs {
+    const void* Z[SAR_MAX_BLOCKS];
+    const float* t[SAR_MAX_BLOCKS];
+};
+
+__device__ inline float leaky2(float u, float slope) { return u > 0.f ? u : slope * u; }
+
+// ------------------------------------------------------------------ forward
+
+struct FwdP {
+    const int32_t* indptr;
+    const uint32_t* indices;
+    const uint32_t* rows;
+    int64_t n_rows, n_long;
+    const void* Z;
+    const float* t;
+    const float* s;
+    float* m;
+    float* l;
+    float* acc;
+    void* out;
+    float* L;
+    int H;
+    int tag_shift;
+    float slope;
+};
+
+template <int LPH>
+struct FwdState {
+    float m2;       // running maximum (log2 units), uniform inside a head group
+    float l;        // this lane's share of the running denominator
+    float acc[4];   // running numerator for the lane's 4 features
+};
+
+// One 64-edge chunk position `mine`(lane) holds; folds edges [0,cnt) of it.
+template <typename T, int LPH, int B, bool ALL>
+__device__ inline void fwd_chunk(FwdState<LPH>& st, const FwdP& a, const Tabs& tabs, uint32_t mine, int cnt,
+                                 int lane, int h, int k, float s2)
+{
+    const uint32_t mask = ALL ? ((1u << a.tag_shift) - 1u) : 0xffffffffu;
+    for (int k0 = 0; k0 < cnt; k0 += B) {
+        const int nb = min(B, cnt - k0);
+        // gathers of the B source rows (a short last batch repeats its last edge; weight 0)
+        typename Row4<T>::Raw raw[B];
+        static_for<B>([&](auto kk) {
+            const int e = k0 + min((int)decltype(kk)::value, nb - 1);
+            const uint32_t id = (uint32_t)__builtin_amdgcn_readlane((int)mine, e);
+            const T* zb = static_cast<const T*>(ALL ? tabs.Z[id >> a.tag_shift] : a.Z);
+            raw[decltype(kk)::value] = Row4<T>::load(zb + (int64_t)(id & mask) * kF, lane);
+        });
+        // scores: lane k of every head group takes edge k0+k
+        const bool valid = k < nb;
+        const uint32_t my = (uint32_t)__shfl((int)mine, k0 + (valid ? k : 0));
+        const float* tb = ALL ? tabs.t[my >> a.tag_shift] : a.t;
+        const float tv = tb[(int64_t)(my & mask) * a.H + h];
+        const float e2 = valid ? leaky2(fmaf(tv, kLog2e, s2), a.slope) : -INFINITY;
+        const float cmax = group_all<LPH, OpMax>(e2);
+        if (__builtin_amdgcn_ballot_w64(cmax > st.m2)) {
+            const float mn = fmaxf(st.m2, cmax);
+            const float c = fast_exp2(st.m2 - mn);    // first edges: exp2(-inf) = 0
+            st.l *= c;
+#pragma unroll
+            for (int x = 0; x < 4; ++x) st.acc[x] *= c;
+            st.m2 = mn;
+        }
+        const float p = fast_exp2(e2 - st.m2);        // 0 for the lanes without an edge
+        st.l += p;
+        static_for<B>([&](auto kk) {
+            const float pk = group_bcast<LPH, decltype(kk)::value>(p);
+            float v[4];
+            Row4<T>::unpack(raw[decltype(kk)::value], v);
+#pragma unroll
+            for (int x = 0; x < 4; ++x) st.acc[x] = fmaf(pk, v[x], st.acc[x]);
+        });
+    }
+}
+
+template <typename T, int LPH, int B, bool ALL>
+__global__ __launch_bounds__(kGatherThreads) void k_gat_fwd_f256(FwdP a, Tabs tabs)
+{
+    static_assert(B <= LPH, "a sub-batch must fit a head group");
+    __shared__ float part[kWavesPerWG][kWave][6];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int h = lane / LPH, k = lane % LPH;
+    T* outp = static_cast<T*>(a.out);
+
+    auto init = [&](FwdState<LPH>& st, int i, bool carry) {
+        st.m2 = -INFINITY;
+        st.l = 0.f;
+#pragma unroll
+        for (int x = 0; x < 4; ++x) st.acc[x] = 0.f;
+        if constexpr (!ALL) {
+            if (carry) {   // state carried from the blocks already aggregated
+                st.m2 = a.m[(int64_t)i * a.H + h] * kLog2e;
+                st.l = (k == 0) ? a.l[(int64_t)i * a.H + h] : 0.f;
+                load_f32<4>(a.acc + (int64_t)i * kF + lane * 4, st.acc);
+            }
+        }
+    };
+    auto finish = [&](FwdState<LPH>& st, int i) {
+        const float l = group_all<LPH, OpSum>(st.l);
+        if constexpr (ALL) {
+            const float inv = l > 0.f ? 1.f / l : 0.f;
+            float v[4];
+#pragma unroll
+            for (int x = 0; x < 4; ++x) v[x] = st.acc[x] * inv;
+            Row4<T>::store(outp + (int64_t)i * kF, lane, v);
+            if (k == 0) a.L[(int64_t)i * a.H + h] = l > 0.f ? (st.m2 + fast_log2(l)) * kLn2 : -INFINITY;
+        } else {
+            store_f32<4>(a.acc + (int64_t)i * kF + lane * 4, st.acc);
+            if (k == 0) {
+                a.m[(int64_t)i * a.H + h] = st.m2 * kLn2;
+                a.l[(int64_t)i * a.H + h] = l;
+            }
+        }
+    };
+    auto edges = [&](FwdState<LPH>& st, int i, int chunk0, int stride) {
+        const float s2 = a.s[(int64_t)i * a.H + h] * kLog2e;
+        const int beg = a.indptr[i], end = a.indptr[i + 1];
+        for (int cb = beg + chunk0 * kWave; cb < end; cb += stride * kWave) {
+            const int cnt = min(kWave, end - cb);
+            const uint32_t mine = (lane < cnt) ? a.indices[cb + lane] : 0u;
+            fwd_chunk<T, LPH, B, ALL>(st, a, tabs, mine, cnt, lane, h, k, s2);
+        }
+    };
+
+    // rows of at least kLongRow edges: the four wavefronts share the row
+    for (int64_t r = blockIdx.x; r < a.n_long; r += gridDim.x) {
+        const int i = (int)a.rows[r];
+        FwdState<LPH> st;
+        init(st, i, wave == 0);
+        edges(st, i, wave, kWavesPerWG);
+        const float l = group_all<LPH, OpSum>(st.l);
+#pragma unroll
+        for (int x = 0; x < 4; ++x) part[wave][lane][x] = st.acc[x];
+        part[wave][lane][4] = st.m2;
+        part[wave][lane][5] = l;
+        __syncthreads();
+        if (wave == 0) {
+            float m2 = st.m2, lt = l;
+            for (int w = 1; w < kWavesPerWG; ++w) {
+                const float om = part[w][lane][4], ol = part[w][lane][5];
+                const float mn = fmaxf(m2, om);
+                const float ref = (mn == -INFINITY) ? 0.f : mn;
+                const float ca = fast_exp2(m2 - ref), cb = fast_exp2(om - ref);
+                lt = lt * ca + ol * cb;
+#pragma unroll
+                for (int x = 0; x < 4; ++x) st.acc[x] = st.acc[x] * ca + part[w][lane][x] * cb;
+                m2 = mn;
+            }
+            st.m2 = m2;
+            st.l = (k == 0) ? lt : 0.f;
+            finish(st, i);
+        }
+        __syncthreads();
+    }
+    const int64_t n_waves = (int64_t)gridDim.x * kWavesPerWG;
+    for (int64_t r = a.n_long + (int64_t)blockIdx.x * kWavesPerWG + wave; r < a.n_rows; r += n_waves) {
+        const int i = __builtin_amdgcn_readfirstlane((int)a.rows[r]);
+        FwdState<LPH> st;
+        init(st, i, true);
+        edges(st, i, 0, 1);
+        finish(st, i);
+    }
+}
+
+// ----------------------------------------------------------------- backward
+
+struct BwdTabs {
+    const int32_t* t_indptr[SAR_MAX_BLOCKS];
+    const int32_t* t_indices[SAR_MAX_BLOCKS];
+    const void* Z[SAR_MAX_BLOCKS];
+    const float* t[SAR_MAX_BLOCKS];
+    void* dZ[SAR_MAX_BLOCKS];
+    float* dt[SAR_MAX_BLOCKS];
+};
+
+struct BwdP {
+    const uint32_t* rows;
+    int64_t n_rows, n_long;
+    const void* G;
+    const float4* rec;
+    const float* a_l;
+    float* ds;
+    float* partial;
+    int H;
+    int tag_shift;
+    float slope;
+};
+
+struct BwdAcc4 {
+    float dz[4];   // sum_i alpha G_i for the lane's 4 features
+    float dt;      // this lane's share of sum_i du
+};
+
+template <typename T, int LPH, int B>
+__device__ inline void bwd_chunk(BwdAcc4& ac, const BwdP& a, int mine, int cnt, int lane, int h, int k,
+                                 const float (&zj)[4], float t2)
+{
+    const T* Gp = static_cast<const T*>(a.G);
+    for (int k0 = 0; k0 < cnt; k0 += B) {
+        const int nb = min(B, cnt - k0);
+        typename Row4<T>::Raw raw[B];
+        static_for<B>([&](auto kk) {
+            const int e = k0 + min((int)decltype(kk)::value, nb - 1);
+            const int i = __builtin_amdgcn_readlane(mine, e);
+            raw[decltype(kk)::value] = Row4<T>::load(Gp + (int64_t)i * kF, lane);
+        });
+        const bool valid = k < nb;
+        const int my_i = __shfl(mine, k0 + (valid ? k : 0));
+        const float4 rec = a.rec[(int64_t)my_i * a.H + h];
+        // c_k = <G_i, z_j> per head, reduced over the head's lanes; lane k keeps edge k's value
+        float c_mine = 0.f;
+        static_for<B>([&](auto kk) {
+            float g[4];
+            Row4<T>::unpack(raw[decltype(kk)::value], g);
+            float c = g[0] * zj[0];
+#pragma unroll
+            for (int x = 1; x < 4; ++x) c = fmaf(g[x], zj[x], c);
+            c = group_all<LPH, OpSum>(c);
+            c_mine = (k == decltype(kk)::value) ? c : c_mine;
+        });
+        const float u2 = rec.x + t2;
+        const float alpha = valid ? fast_exp2(leaky2(u2, a.slope) - rec.y) : 0.f;
+        const float de = alpha * (c_mine - rec.z);
+        const float du = u2 > 0.f ? de : a.slope * de;
+        ac.dt += du;
+        if (valid) unsafeAtomicAdd(a.ds + (int64_t)my_i * a.H + h, du);
+        static_for<B>([&](auto kk) {
+            const float ak = group_bcast<LPH, decltype(kk)::value>(alpha);
+            float g[4];
+            Row4<T>::unpack(raw[decltype(kk)::value], g);
+#pragma unroll
+            for (int x = 0; x < 4; ++x) ac.dz[x] = fmaf(ak, g[x], ac.dz[x]);
+        });
+    }
+}
+
+template <typename T, int LPH, int B, bool ALL>
+__global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_f256(BwdTabs tabs, BwdP a)
+{
+    static_assert(B <= LPH, "a sub-batch must fit a head group");
+    __shared__ float part[kWavesPerWG][kWave][5];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int h = lane / LPH, k = lane % LPH;
+    const uint32_t mask = ALL ? ((1u << a.tag_shift) - 1u) : 0xffffffffu;
+
+    float al[4], dal[4];
+    load_f32<4>(a.a_l + lane * 4, al);
+#pragma unroll
+    for (int x = 0; x < 4; ++x) dal[x] = 0.f;
+
+    auto edges = [&](BwdAcc4& ac, int q, int j, int chunk0, int stride, float (&zj)[4]) {
+        Row4<T>::unpack(Row4<T>::load(static_cast<const T*>(tabs.Z[q]) + (int64_t)j * kF, lane), zj);
+        const float t2 = tabs.t[q][(int64_t)j * a.H + h] * kLog2e;
+        const int32_t* ip = tabs.t_indptr[q];
+        const int32_t* idx = tabs.t_indices[q];
+        const int beg = ip[j], end = ip[j + 1];
+#pragma unroll
+        for (int x = 0; x < 4; ++x) ac.dz[x] = 0.f;
+        ac.dt = 0.f;
+        for (int cb = beg + chunk0 * kWave; cb < end; cb += stride * kWave) {
+            const int cnt = min(kWave, end - cb);
+            const int mine = (lane < cnt) ? idx[cb + lane] : 0;
+            bwd_chunk<T, LPH, B>(ac, a, mine, cnt, lane, h, k, zj, t2);
+        }
+    };
+    // dZ_q[j] = sum alpha G + dt a_l ; dt_q[j] = dt ; da_l += dt z_j
+    auto outputs = [&](const BwdAcc4& ac, float dt, int q, int j, const float (&zj)[4]) {
+        float v[4];
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            v[x] = fmaf(dt, al[x], ac.dz[x]);
+            dal[x] = fmaf(dt, zj[x], dal[x]);
+        }
+        Row4<T>::store(static_cast<T*>(tabs.dZ[q]) + (int64_t)j * kF, lane, v);
+        if (k == 0) tabs.dt[q][(int64_t)j * a.H + h] = dt;
+    };
+
+    for (int64_t r = blockIdx.x; r < a.n_long; r += gridDim.x) {
+        const uint32_t id = a.rows[r];
+        const int q = ALL ? (int)(id >> a.tag_shift) : 0, j = (int)(id & mask);
+        BwdAcc4 ac;
+        float zj[4];
+        edges(ac, q, j, wave, kWavesPerWG, zj);
+        const float dt = group_all<LPH, OpSum>(ac.dt);
+#pragma unroll
+        for (int x = 0; x < 4; ++x) part[wave][lane][x] = ac.dz[x];
+        part[wave][lane][4] = dt;
+        __syncthreads();
+        if (wave == 0) {
+            float tot[5];
+#pragma unroll
+            for (int x = 0; x < 5; ++x) {
+                float s = 0.f;
+                for (int w = 0; w < kWavesPerWG; ++w) s += part[w][lane][x];
+                tot[x] = s;
+            }
+#pragma unroll
+            for (int x = 0; x < 4; ++x) ac.dz[x] = tot[x];
+            outputs(ac, tot[4], q, j, zj);
+        }
+        __syncthreads();
+    }
+    const int64_t n_waves = (int64_t)gridDim.x * kWavesPerWG;
+    for (int64_t r = a.n_long + (int64_t)blockIdx.x * kWavesPerWG + wave; r < a.n_rows; r += n_waves) {
+        const uint32_t id = (uint32_t)__builtin_amdgcn_readfirstlane((int)a.rows[r]);
+        const int q = ALL ? (int)(id >> a.tag_shift) : 0, j = (int)(id & mask);
+        BwdAcc4 ac;
+        float zj[4];
+        edges(ac, q, j, 0, 1, zj);
+        outputs(ac, group_all<LPH, OpSum>(ac.dt), q, j, zj);
+    }
+
+    // this workgroup's share of da_l = sum_j dt_j z_j
+    __syncthreads();
+#pragma unroll
+    for (int x = 0; x < 4; ++x) part[wave][lane][x] = dal[x];
+    __syncthreads();
+    if (wave == 0) {
+        float v[4];
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            float s = 0.f;
+            for (int w = 0; w < kWavesPerWG; ++w) s += part[w][lane][x];
+            v[x] = s;
+        }
+        store_f32<4>(a.partial + (int64_t)blockIdx.x * kF + lane * 4, v);
+    }
+}
+
+}  // namespace f256
+}  // namespace sar

@@ -170,18 +170,6 @@ __global__ __launch_bounds__(kGatherThreads) void k_spmm(SpmmArgs a, PtrTab tab,
     }
 }
 
-// Typed rows of destinations that the launch lists skip (no edge at all): 0.
-template <typename T>
-__global__ __launch_bounds__(256) void k_zero_rows_without_edges(const int32_t* __restrict__ indptr,
-                                                                 int64_t n, int F, T* __restrict__ out)
-{
-    const int64_t total = n * F;
-    for (int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x; k < total; k += (int64_t)gridDim.x * 256) {
-        const int64_t i = k / F;
-        if (indptr[i + 1] == indptr[i]) out[k] = T{};
-    }
-}
-
 template <typename T>
 __global__ __launch_bounds__(256) void k_spmm_end(const int32_t* __restrict__ deg, int mean,
                                                   const float* __restrict__ acc, T* __restrict__ out,
@@ -301,29 +289,18 @@ extern "C" int sar_spmm_all(const sar_blocks_t* b, const void* const* Zq, int dt
         tab.p[q] = Zq[q];
     }
     hipStream_t st = sar::as_stream(stream);
-    const unsigned gz = (unsigned)std::min<int64_t>((b->n_dst * F + 255) / 256, 1 << 16);
     SpmmArgs a{};
     a.indptr = b->f_indptr;
     a.indices = b->f_indices;
     a.rows = reinterpret_cast<const uint32_t*>(b->f_rows);
-    a.n_rows = b->n_f_rows;
+    a.n_rows = b->n_dst;   // destinations without in-edges come last in the list and get 0
     a.n_long = b->n_f_long;
     a.out = out;
     a.deg = b->deg;
     a.F = F;
     a.tag_shift = b->tag_shift;
     a.mean = mean;
-    if (dtype == SAR_F32) {
-        if (b->n_f_rows < b->n_dst) {
-            k_zero_rows_without_edges<float><<<gz, 256, 0, st>>>(b->f_indptr, b->n_dst, F, static_cast<float*>(out));
-            SAR_LAUNCH_CHECK();
-        }
-        return launch_spmm<float, Mode::kAll>(a, tab, b->P, st);
-    }
-    if (b->n_f_rows < b->n_dst) {
-        k_zero_rows_without_edges<bf16_t><<<gz, 256, 0, st>>>(b->f_indptr, b->n_dst, F, static_cast<bf16_t*>(out));
-        SAR_LAUNCH_CHECK();
-    }
+    if (dtype == SAR_F32) return launch_spmm<float, Mode::kAll>(a, tab, b->P, st);
     return launch_spmm<bf16_t, Mode::kAll>(a, tab, b->P, st);
 }
 
@@ -343,7 +320,7 @@ extern "C" int sar_spmm_bwd_block(const sar_blocks_t* b, int q, const void* G, i
     a.indptr = k.t_indptr;
     a.indices = reinterpret_cast<const uint32_t*>(k.t_indices);
     a.rows = reinterpret_cast<const uint32_t*>(k.t_rows);
-    a.n_rows = k.n_t_rows;
+    a.n_rows = k.n_src;    // sources without edges come last in the list and get 0
     a.n_long = k.n_t_long;
     a.Z = G;
     a.out = dZq;
@@ -351,17 +328,6 @@ extern "C" int sar_spmm_bwd_block(const sar_blocks_t* b, int q, const void* G, i
     a.F = F;
     a.mean = mean;
     PtrTab tab{};
-    const unsigned gz = (unsigned)std::min<int64_t>((k.n_src * F + 255) / 256, 1 << 16);
-    if (dtype == SAR_F32) {
-        if (k.n_t_rows < k.n_src) {
-            k_zero_rows_without_edges<float><<<gz, 256, 0, st>>>(k.t_indptr, k.n_src, F, static_cast<float*>(dZq));
-            SAR_LAUNCH_CHECK();
-        }
-        return launch_spmm<float, Mode::kBackward>(a, tab, 0, st);
-    }
-    if (k.n_t_rows < k.n_src) {
-        k_zero_rows_without_edges<bf16_t><<<gz, 256, 0, st>>>(k.t_indptr, k.n_src, F, static_cast<bf16_t*>(dZq));
-        SAR_LAUNCH_CHECK();
-    }
+    if (dtype == SAR_F32) return launch_spmm<float, Mode::kBackward>(a, tab, 0, st);
     return launch_spmm<bf16_t, Mode::kBackward>(a, tab, 0, st);
 }
