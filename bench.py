@@ -5,7 +5,6 @@ One "step" is one pass of worker p's GAT layer over all P resident source
 blocks, forward and rematerialising backward:
 
     Z_p = X_p W (+ score halves s, t_p)                     MFMA
-    t_q = <a_l, Z_q> for every fetched block                 node-wise
     fused attention forward over the P blocks               (dominant gather)
     backward begin, fused attention backward over P blocks, backward end
     dW, dX for the worker's own rows                         MFMA
@@ -108,15 +107,16 @@ class Layer:
         sar.sar_linear_fwd(self.X, self.W, self.Zp.reshape(self.n, self.F), self.a_r, self.s, self.a_l, self.tp)
         Zs = list(self.Zs)
         Zs[p] = self.Zp                      # the local block reads the rows just produced
-        for q in range(P):
-            sar.sar_gat_scores(Zs[q], self.a_l, self.ts[q])
+        # the fetched blocks arrive as raw Z_q: their score halves t_q = <a_l, z_j> are formed
+        # inside the gather kernels (tq = None), so no separate pass over Z_q is needed
         mark("fwd0")
         if mode == "all":
-            sar.sar_gat_fwd_all(self.blocks, Zs, self.s, self.ts, w.slope, self.out, self.L)
+            sar.sar_gat_fwd_all(self.blocks, Zs, self.s, None, self.a_l, w.slope, self.out, self.L)
         else:
             sar.sar_gat_fwd_begin(self.m, self.l, self.acc)
             for q in range(P):
-                sar.sar_gat_fwd_block(self.blocks, q, Zs[q], self.s, self.ts[q], w.slope, self.m, self.l, self.acc)
+                sar.sar_gat_fwd_block(self.blocks, q, Zs[q], self.s, None, self.a_l, w.slope, self.m, self.l,
+                                      self.acc)
             sar.sar_gat_fwd_end(self.m, self.l, self.acc, self.out, self.L)
         mark("fwd1")
         sar.sar_gat_bwd_begin(self.G, self.out, self.s, self.L, self.rec, self.ds)
@@ -125,17 +125,17 @@ class Layer:
         self.dW.zero_()
         mark("bwd0")
         if mode == "all":
-            sar.sar_gat_bwd_all(self.blocks, Zs, self.G, self.ts, self.rec, self.a_l, w.slope, self.dZs, self.dts,
+            sar.sar_gat_bwd_all(self.blocks, Zs, self.G, None, self.rec, self.a_l, w.slope, self.dZs, self.dts,
                                 self.ds, self.da_l, self.work)
         else:
             for q in range(P):
-                sar.sar_gat_bwd_block(self.blocks, q, Zs[q], self.G, self.ts[q], self.rec, self.a_l, w.slope,
+                sar.sar_gat_bwd_block(self.blocks, q, Zs[q], self.G, None, self.rec, self.a_l, w.slope,
                                       self.dZs[q], self.dts[q], self.ds, self.da_l, self.work)
         mark("bwd1")
-        sar.sar_gat_bwd_end(self.Zp, self.ds, self.a_r, self.dZdst, self.da_r, self.work)
-        # Z_p.backward(E_p) with the errors this worker itself produced for its rows
+        # E_p = E_{p->p} + destination-score term: everything this worker itself produced for its rows
+        sar.sar_gat_bwd_end(self.Zp, self.ds, self.a_r, self.dZs[p], self.dZdst, self.da_r, self.work)
+        # Z_p.backward(E_p)
         sar.sar_linear_bwd(self.X, self.dZdst, self.W, self.dW, self.dX_dst, self.lwork)
-        sar.sar_linear_bwd(self.X, self.dZs[p], self.W, self.dW, self.dX_src, self.lwork)
         mark("t1")
 
     # ---- algorithmic bytes of the two gather launches (what the method must move)
@@ -145,10 +145,10 @@ class Layer:
         touched = sum(v.n_t_rows for v in self.views)
         n_src = sum(v.n_src for v in self.views)
         fwd = (4 * E + 4 * (n + 1) + 4 * n            # tagged index, row offsets, launch list
-               + touched * (F * fb + H * 4)           # each touched source row and its t once
+               + touched * F * fb                     # each touched source row once
                + n * (H * 4 + F * fb + H * 4))        # s read, out and L written
         bwd = (4 * E + 4 * (n_src + self.P) + 4 * touched   # transposed index, offsets, launch list
-               + touched * (F * fb + H * 4)           # z_j, t_j read once (the rematerialisation)
+               + touched * F * fb                     # z_j read once (the rematerialisation)
                + n_src * (F * fb + H * 4)             # dZ_q, dt_q written once
                + n * (F * fb + H * 16 + 2 * H * 4))   # G and the record read once, ds read-modify-write
         return fwd, bwd

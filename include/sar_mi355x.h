@@ -75,11 +75,13 @@ typedef struct sar_blocks sar_blocks_t; /* opaque, library-owned */
  *                       indices[indptr[i] .. indptr[i+1]), ascending, local to V_q
  *   t_indptr/t_indices  the same edges source-major: destinations of source j,
  *                       ascending, local to V_p          (NULL without TRANSPOSE)
- *   rows / t_rows       the rows (resp. sources) that have at least one edge in
- *                       this block, ordered longest-first by degree class: the
- *                       launch order of the kernels.  The first n_long (resp.
- *                       n_t_long) of them are longer than the long-row threshold.
- *                       The order inside a degree class is unspecified.
+ *   rows / t_rows       the n_rows rows (resp. n_t_rows sources) that have at
+ *                       least one edge in this block, ordered longest-first by
+ *                       degree class: the launch order of the kernels.  The
+ *                       first n_long (resp. n_t_long) of them have at least 512
+ *                       edges.  The order inside a degree class is unspecified.
+ *                       t_rows continues with the n_src - n_t_rows sources that
+ *                       have no edge (the backward kernels zero their rows).
  *   touched             = t_rows sorted ascending: V_{p,q} intersected with V_q,
  *                       the rows of Z_q a remote fetch would have to carry
  *                       (Alg. 1, "Fetch Z_{q->p}")        (NULL without TRANSPOSE)
@@ -188,10 +190,13 @@ int sar_gat_fwd_begin(float* m, float* l, float* acc, int64_t n_dst, int H, int 
  * with an edge in block q, per head: new running maximum m' = max(m, max_j e),
  * l = l exp(m-m') + sum_j exp(e-m'), acc = acc exp(m-m') + sum_j exp(e-m') z_j.
  * No per-edge value is written to memory.  Destinations without an edge in the
- * block are not touched.  s fp32 [n_dst,H]; tq fp32 [n_src_q,H]. */
+ * block are not touched.  s fp32 [n_dst,H].  The source halves come either
+ * from tq (fp32 [n_src_q,H], e.g. shipped along with Z_q by its owner) or, when
+ * tq is NULL, are formed inside the kernel from a_l (fp32 [H,D], 16-byte
+ * aligned) and each gathered row, which saves the separate pass over Z_q. */
 int sar_gat_fwd_block(const sar_blocks_t* b, int q, const void* Zq, const float* s,
-                      const float* tq, int dtype, int H, int D, float slope, float* m, float* l,
-                      float* acc, void* stream);
+                      const float* tq, const float* a_l, int dtype, int H, int D, float slope,
+                      float* m, float* l, float* acc, void* stream);
 
 /* After the last block: out = acc / l (the division of Sec. 3.2), and the
  * log-sum-exp L = m + log l that the backward pass reads.  out [n_dst,H,D] of
@@ -201,10 +206,11 @@ int sar_gat_fwd_end(const float* m, const float* l, const float* acc, void* out,
 
 /* All P blocks in one launch: each destination walks its blocks in order
  * q = 0..P-1 with the same running-maximum updates, state in registers.
- * Zq, tq: host arrays [P] of device pointers.  Needs SAR_BUILD_FUSED. */
+ * Zq, tq: host arrays [P] of device pointers; tq may be NULL (then a_l is used
+ * as in sar_gat_fwd_block).  Needs SAR_BUILD_FUSED. */
 int sar_gat_fwd_all(const sar_blocks_t* b, const void* const* Zq, const float* s,
-                    const float* const* tq, int dtype, int H, int D, float slope, void* out,
-                    float* L, void* stream);
+                    const float* const* tq, const float* a_l, int dtype, int H, int D, float slope,
+                    void* out, float* L, void* stream);
 
 /* Bytes of scratch the backward calls below need for these sizes. */
 int sar_gat_workspace_bytes(int64_t n_dst, int64_t n_src_max, int H, int D, size_t* bytes);
@@ -227,8 +233,9 @@ int sar_gat_bwd_begin(const void* G, const void* out, const float* s, const floa
  *   da_l  += sum_j dtq[j] Zq[j]                (accumulates over blocks, fp32 [H,D])
  * The kernel walks the source-major index (needs SAR_BUILD_TRANSPOSE): every
  * source gathers its destinations' G rows, so dZq is written once, without
- * atomics.  rec from sar_gat_bwd_begin; work: scratch of at least
- * sar_gat_workspace_bytes, 16-byte aligned. */
+ * atomics.  rec from sar_gat_bwd_begin; tq may be NULL, then t_j = <a_l, z_j> is
+ * formed from the row the wavefront owns; a_l 16-byte aligned; work: scratch of
+ * at least sar_gat_workspace_bytes, 16-byte aligned. */
 int sar_gat_bwd_block(const sar_blocks_t* b, int q, const void* Zq, const void* G, const float* tq,
                       const float* rec, const float* a_l, int dtype, int H, int D, float slope,
                       void* dZq, float* dtq, float* ds, float* da_l, void* work, size_t work_bytes,
@@ -243,10 +250,13 @@ int sar_gat_bwd_all(const sar_blocks_t* b, const void* const* Zq, const void* G,
                     void* work, size_t work_bytes, void* stream);
 
 /* After the last block, the destination side of the score:
- * dZdst[i] = ds[i] a_r (OVERWRITTEN, `dtype`), da_r += sum_i ds[i] Zdst[i]. */
-int sar_gat_bwd_end(const void* Zdst, const float* ds, const float* a_r, void* dZdst, float* da_r,
-                    int dtype, int64_t n_dst, int H, int D, void* work, size_t work_bytes,
-                    void* stream);
+ * dZdst[i] = ds[i] a_r + dZadd[i] (OVERWRITTEN, `dtype`), da_r += sum_i ds[i] Zdst[i].
+ * dZadd may be NULL (= 0); a worker passes its local block's dZq here to get
+ * the whole error of its own rows, E_{p->p} plus the destination-score term,
+ * in one tensor for Z_p.backward.  dZadd may alias dZdst. */
+int sar_gat_bwd_end(const void* Zdst, const float* ds, const float* a_r, const void* dZadd,
+                    void* dZdst, float* da_r, int dtype, int64_t n_dst, int H, int D, void* work,
+                    size_t work_bytes, void* stream);
 
 /* ------------------------------------------------- Eq. 1: Z = X W on MFMA */
 

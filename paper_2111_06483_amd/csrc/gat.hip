@@ -43,7 +43,8 @@ struct FwdArgs {
     const uint32_t* rows;
     int64_t n_rows, n_long;
     const void* Z;       // per-block call: this block's source rows
-    const float* t;      //                 and their score halves [n_src,H]
+    const float* t;      //                 and their score halves [n_src,H]; null: formed from a_l
+    const float* a_l;    // [H,D], used only when the source score halves are not given
     const float* s;      // destination score halves [n_dst,H]
     float* m;            // running state (per-block calls), natural-log units
     float* l;
@@ -91,7 +92,8 @@ __device__ inline void state_merge(SoftState<VEC>& st, float om2, float ol, cons
 template <typename T, int G, bool ALL>
 __device__ inline void fwd_edges(SoftState<Vec<T>::N>& st, const FwdArgs& a, const void* const* ztab,
                                  const float* const* ttab, int beg, int end, int chunk0, int stride,
-                                 const LaneMap<T, G>& lm, float s2)
+                                 const LaneMap<T, G>& lm, float s2, const float (&al)[Vec<T>::N], bool fly,
+                                 bool pow2)
 {
     constexpr int VEC = Vec<T>::N;
     constexpr int SLOTS = kWave / G;
@@ -102,12 +104,14 @@ __device__ inline void fwd_edges(SoftState<Vec<T>::N>& st, const FwdArgs& a, con
         for (int k0 = 0; k0 < cnt; k0 += SLOTS * kU) {
             typename Vec<T>::Raw raw[kU];
             float e2[kU];
+            bool ok[kU];
 #pragma unroll
             for (int k = 0; k < kU; ++k) {
                 const int ek = k0 + k * SLOTS + lm.slot;
                 const uint32_t id = __shfl(mine, ek & (kWave - 1));
                 raw[k] = Vec<T>::zero();
-                e2[k] = -INFINITY;
+                e2[k] = 0.f;
+                ok[k] = ek < cnt;
                 if (ek < cnt) {
                     const uint32_t j = id & mask;
                     const T* zb;
@@ -119,15 +123,26 @@ __device__ inline void fwd_edges(SoftState<Vec<T>::N>& st, const FwdArgs& a, con
                         zb = static_cast<const T*>(a.Z);
                         tb = a.t;
                     }
-                    e2[k] = tb[(int64_t)j * a.H + lm.h];
+                    if (!fly) e2[k] = tb[(int64_t)j * a.H + lm.h];
                     if (lm.on) raw[k] = Vec<T>::load(zb + (int64_t)j * a.F + lm.gl * VEC);
+                }
+            }
+            if (fly) {   // t_j = <a_l, z_j> from the row just gathered
+#pragma unroll
+                for (int k = 0; k < kU; ++k) {
+                    float v[VEC];
+                    Vec<T>::unpack(raw[k], v);
+                    float c = 0.f;
+#pragma unroll
+                    for (int x = 0; x < VEC; ++x) c = fmaf(al[x], v[x], c);
+                    e2[k] = pow2 ? group_sum_pow2(c, lm.lph) : group_sum_any(c, lm.head_first, lm.lph);
                 }
             }
             float mx = st.m2;
 #pragma unroll
             for (int k = 0; k < kU; ++k) {
-                // -inf marks an absent edge and survives both operations
-                e2[k] = leaky(fmaf(e2[k], kLog2e, s2), a.slope);
+                // -inf marks an absent edge
+                e2[k] = ok[k] ? leaky(fmaf(e2[k], kLog2e, s2), a.slope) : -INFINITY;
                 mx = fmaxf(mx, e2[k]);
             }
             if (mx > st.m2) {
@@ -208,6 +223,10 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_fwd(FwdArgs a, PtrTab zt
     }
     const LaneMap<T, G> lm(a.F, a.H, a.D);
     const int wave = threadIdx.x / kWave;
+    const bool fly = a.a_l != nullptr, pow2 = is_pow2(lm.lph);
+    float al[VEC];
+#pragma unroll
+    for (int x = 0; x < VEC; ++x) al[x] = (fly && lm.on) ? a.a_l[lm.gl * VEC + x] : 0.f;
 
     auto load_state = [&](SoftState<VEC>& st, int i) {
         state_reset<VEC>(st);
@@ -229,7 +248,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_fwd(FwdArgs a, PtrTab zt
             load_state(st, i);
         else
             state_reset<VEC>(st);
-        fwd_edges<T, G, ALL>(st, a, ztab, ttab, a.indptr[i], a.indptr[i + 1], wave, kWavesPerWG, lm, s2);
+        fwd_edges<T, G, ALL>(st, a, ztab, ttab, a.indptr[i], a.indptr[i + 1], wave, kWavesPerWG, lm, s2, al, fly, pow2);
         fwd_merge_slots<T, G>(st);
         if (lm.slot == 0) {
 #pragma unroll
@@ -255,7 +274,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_fwd(FwdArgs a, PtrTab zt
         const float s2 = a.s[(int64_t)i * a.H + lm.h] * kLog2e;
         SoftState<VEC> st;
         load_state(st, i);
-        fwd_edges<T, G, ALL>(st, a, ztab, ttab, a.indptr[i], a.indptr[i + 1], 0, 1, lm, s2);
+        fwd_edges<T, G, ALL>(st, a, ztab, ttab, a.indptr[i], a.indptr[i + 1], 0, 1, lm, s2, al, fly, pow2);
         fwd_merge_slots<T, G>(st);
         fwd_finish_row<T, G, ALL>(st, a, i, lm);
     }
@@ -376,7 +395,14 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd(BwdArgs tabs, BwdSca
         typename Vec<T>::Raw r = Vec<T>::zero();
         if (lm.on) r = Vec<T>::load(static_cast<const T*>(tabs.Z[q]) + (int64_t)j * a.F + lm.gl * VEC);
         Vec<T>::unpack(r, zj);
-        t2 = tabs.t[q][(int64_t)j * a.H + lm.h] * kLog2e;
+        if (tabs.t[q]) {
+            t2 = tabs.t[q][(int64_t)j * a.H + lm.h] * kLog2e;
+        } else {
+            float c = 0.f;
+#pragma unroll
+            for (int x = 0; x < VEC; ++x) c = fmaf(al[x], zj[x], c);
+            t2 = (pow2 ? group_sum_pow2(c, lm.lph) : group_sum_any(c, lm.head_first, lm.lph)) * kLog2e;
+        }
     };
     // dZ_q[j] = sum alpha G + dt a_l ; dt_q[j] = dt ; da_l += dt z_j
     auto row_outputs = [&](const BwdAcc<VEC>& ac, int q, int j, const float (&zj)[VEC]) {
@@ -564,10 +590,11 @@ __global__ __launch_bounds__(kGatherThreads) void k_bwd_begin(const T* __restric
     }
 }
 
-// dZdst[i] = ds[i] a_r ; per-workgroup partial of da_r = sum_i ds[i] Zdst[i]
+// dZdst[i] = ds[i] a_r (+ dZadd[i]) ; per-workgroup partial of da_r = sum_i ds[i] Zdst[i]
 template <typename T, int G>
 __global__ __launch_bounds__(kGatherThreads) void k_bwd_end(const T* __restrict__ Zdst, const float* __restrict__ ds,
-                                                            const float* __restrict__ a_r, T* __restrict__ dZdst,
+                                                            const float* __restrict__ a_r, const T* dZadd,
+                                                            T* dZdst,
                                                             float* __restrict__ partial, int64_t n, int H, int D,
                                                             int F)
 {
@@ -590,9 +617,15 @@ __global__ __launch_bounds__(kGatherThreads) void k_bwd_end(const T* __restrict_
         const float d = ds[v * H + lm.h];
         float z[VEC], o[VEC];
         Vec<T>::unpack(Vec<T>::load(Zdst + v * F + lm.gl * VEC), z);
+        if (dZadd) {
+            Vec<T>::unpack(Vec<T>::load(dZadd + v * F + lm.gl * VEC), o);
+        } else {
+#pragma unroll
+            for (int x = 0; x < VEC; ++x) o[x] = 0.f;
+        }
 #pragma unroll
         for (int x = 0; x < VEC; ++x) {
-            o[x] = d * ar[x];
+            o[x] = fmaf(d, ar[x], o[x]);
             dar[x] = fmaf(d, z[x], dar[x]);
         }
         Vec<T>::store(dZdst + v * F + lm.gl * VEC, o);
@@ -683,16 +716,16 @@ int fast_lph(int H, int D)
     return (lph >= 4 && (lph & (lph - 1)) == 0) ? lph : 0;
 }
 
-template <typename T, int LPH, bool ALL>
+template <typename T, int LPH, bool ALL, bool FLY>
 int launch_fwd_f256(const FwdArgs& a, const PtrTab& zt, const PtrTab& tt, hipStream_t st)
 {
     constexpr int B = LPH >= 8 ? 8 : 4;
-    auto fn = f256::k_gat_fwd_f256<T, LPH, B, ALL>;
+    auto fn = f256::k_gat_fwd_f256<T, LPH, B, ALL, FLY>;
     static const int resident = resident_workgroups(fn);
     f256::FwdP p{};
     p.indptr = a.indptr; p.indices = a.indices; p.rows = a.rows;
     p.n_rows = a.n_rows; p.n_long = a.n_long;
-    p.Z = a.Z; p.t = a.t; p.s = a.s; p.m = a.m; p.l = a.l; p.acc = a.acc; p.out = a.out; p.L = a.L;
+    p.Z = a.Z; p.t = a.t; p.a_l = a.a_l; p.s = a.s; p.m = a.m; p.l = a.l; p.acc = a.acc; p.out = a.out; p.L = a.L;
     p.H = a.H; p.tag_shift = a.tag_shift; p.slope = a.slope;
     f256::Tabs tabs{};
     for (int q = 0; q < SAR_MAX_BLOCKS; ++q) {
@@ -708,14 +741,18 @@ template <typename T, bool ALL>
 int launch_fwd(const FwdArgs& a, const PtrTab& zt, const PtrTab& tt, int P, hipStream_t st)
 {
     if (a.n_rows == 0) return SAR_OK;
+#define SAR_FWD_F256(LPH)                                                                  \
+    return a.a_l ? launch_fwd_f256<T, LPH, ALL, true>(a, zt, tt, st)                       \
+                 : launch_fwd_f256<T, LPH, ALL, false>(a, zt, tt, st)
     switch (fast_lph(a.H, a.D)) {
-        case 4: return launch_fwd_f256<T, 4, ALL>(a, zt, tt, st);
-        case 8: return launch_fwd_f256<T, 8, ALL>(a, zt, tt, st);
-        case 16: return launch_fwd_f256<T, 16, ALL>(a, zt, tt, st);
-        case 32: return launch_fwd_f256<T, 32, ALL>(a, zt, tt, st);
-        case 64: return launch_fwd_f256<T, 64, ALL>(a, zt, tt, st);
+        case 4: SAR_FWD_F256(4);
+        case 8: SAR_FWD_F256(8);
+        case 16: SAR_FWD_F256(16);
+        case 32: SAR_FWD_F256(32);
+        case 64: SAR_FWD_F256(64);
         default: break;
     }
+#undef SAR_FWD_F256
     const unsigned grid = persistent_grid(a.n_rows, a.n_long);
     SAR_DISPATCH_G(T, a.F, (k_gat_fwd<T, kG, ALL><<<grid, kGatherThreads, 0, st>>>(a, zt, tt, P)));
     SAR_LAUNCH_CHECK();
@@ -802,16 +839,17 @@ extern "C" int sar_gat_fwd_begin(float* m, float* l, float* acc, int64_t n_dst, 
 }
 
 extern "C" int sar_gat_fwd_block(const sar_blocks_t* b, int q, const void* Zq, const float* s,
-                                 const float* tq, int dtype, int H, int D, float slope, float* m, float* l,
-                                 float* acc, void* stream)
+                                 const float* tq, const float* a_l, int dtype, int H, int D, float slope,
+                                 float* m, float* l, float* acc, void* stream)
 {
     SAR_CHECK_ARG(b != nullptr, "handle is null");
     SAR_CHECK_ARG(q >= 0 && q < b->P, "block %d out of range [0,%d)", q, b->P);
     SAR_TRY(check_shape(dtype, H, D));
     const sar::Block& k = b->blk[q];
     if (k.n_rows == 0) return SAR_OK;
-    SAR_CHECK_ARG(Zq && s && tq && m && l && acc, "a tensor argument is null");
-    SAR_CHECK_ARG(aligned16(Zq) && aligned16(acc), "Zq and acc must be 16-byte aligned");
+    SAR_CHECK_ARG(Zq && s && m && l && acc, "a tensor argument is null");
+    SAR_CHECK_ARG(tq || a_l, "either tq or a_l must be given");
+    SAR_CHECK_ARG(aligned16(Zq) && aligned16(acc) && aligned16(a_l), "Zq, acc and a_l must be 16-byte aligned");
     FwdArgs a{};
     a.indptr = k.indptr;
     a.indices = reinterpret_cast<const uint32_t*>(k.indices);
@@ -820,6 +858,7 @@ extern "C" int sar_gat_fwd_block(const sar_blocks_t* b, int q, const void* Zq, c
     a.n_long = k.n_long;
     a.Z = Zq;
     a.t = tq;
+    a.a_l = tq ? nullptr : a_l;
     a.s = s;
     a.m = m;
     a.l = l;
@@ -855,21 +894,22 @@ extern "C" int sar_gat_fwd_end(const float* m, const float* l, const float* acc,
 }
 
 extern "C" int sar_gat_fwd_all(const sar_blocks_t* b, const void* const* Zq, const float* s,
-                               const float* const* tq, int dtype, int H, int D, float slope, void* out,
-                               float* L, void* stream)
+                               const float* const* tq, const float* a_l, int dtype, int H, int D, float slope,
+                               void* out, float* L, void* stream)
 {
     SAR_CHECK_ARG(b != nullptr, "handle is null");
     SAR_TRY(check_shape(dtype, H, D));
     if (!b->f_indptr) return sar::fail(SAR_ERR_STATE, "handle was built without SAR_BUILD_FUSED");
     if (b->n_dst == 0) return SAR_OK;
-    SAR_CHECK_ARG(Zq && tq && s && out && L, "a tensor argument is null");
-    SAR_CHECK_ARG(aligned16(out), "out must be 16-byte aligned");
+    SAR_CHECK_ARG(Zq && s && out && L, "a tensor argument is null");
+    SAR_CHECK_ARG(tq || a_l, "either tq or a_l must be given");
+    SAR_CHECK_ARG(aligned16(out) && aligned16(a_l), "out and a_l must be 16-byte aligned");
     PtrTab zt{}, tt{};
     for (int q = 0; q < b->P; ++q) {
-        SAR_CHECK_ARG((Zq[q] && tq[q]) || b->blk[q].nnz == 0, "Zq[%d] or tq[%d] is null", q, q);
+        SAR_CHECK_ARG((Zq[q] && (!tq || tq[q])) || b->blk[q].nnz == 0, "Zq[%d] or tq[%d] is null", q, q);
         SAR_CHECK_ARG(aligned16(Zq[q]), "Zq[%d] must be 16-byte aligned", q);
         zt.p[q] = Zq[q];
-        tt.p[q] = tq[q];
+        tt.p[q] = tq ? tq[q] : nullptr;
     }
     hipStream_t st = sar::as_stream(stream);
     FwdArgs a{};
@@ -879,6 +919,7 @@ extern "C" int sar_gat_fwd_all(const sar_blocks_t* b, const void* const* Zq, con
     a.n_rows = b->n_dst;   // the list ends with the destinations that have no in-edge: out = 0, L = -inf
     a.n_long = b->n_f_long;
     a.s = s;
+    a.a_l = tq ? nullptr : a_l;
     a.out = out;
     a.L = L;
     a.H = H;
@@ -935,7 +976,7 @@ int bwd_common_checks(const sar_blocks_t* b, int dtype, int H, int D, const void
     if (!(b->flags & SAR_BUILD_TRANSPOSE))
         return sar::fail(SAR_ERR_STATE, "handle was built without SAR_BUILD_TRANSPOSE");
     SAR_CHECK_ARG(G && rec && a_l && ds && da_l, "a tensor argument is null");
-    SAR_CHECK_ARG(aligned16(G) && aligned16(rec), "G and rec must be 16-byte aligned");
+    SAR_CHECK_ARG(aligned16(G) && aligned16(rec) && aligned16(a_l), "G, rec and a_l must be 16-byte aligned");
     SAR_CHECK_ARG(work != nullptr && aligned16(work), "work is null or not 16-byte aligned");
     SAR_CHECK_ARG(work_bytes >= workspace_bytes(H * D), "work_bytes=%zu is below the %zu bytes required",
                   work_bytes, workspace_bytes(H * D));
@@ -953,7 +994,7 @@ extern "C" int sar_gat_bwd_block(const sar_blocks_t* b, int q, const void* Zq, c
     SAR_CHECK_ARG(q >= 0 && q < b->P, "block %d out of range [0,%d)", q, b->P);
     const sar::Block& k = b->blk[q];
     if (k.n_src == 0) return SAR_OK;
-    SAR_CHECK_ARG(Zq && tq && dZq && dtq, "a tensor argument is null");
+    SAR_CHECK_ARG(Zq && dZq && dtq, "a tensor argument is null");
     SAR_CHECK_ARG(aligned16(Zq) && aligned16(dZq), "Zq and dZq must be 16-byte aligned");
     hipStream_t st = sar::as_stream(stream);
     BwdArgs tabs{};
@@ -986,19 +1027,19 @@ extern "C" int sar_gat_bwd_all(const sar_blocks_t* b, const void* const* Zq, con
                                void* work, size_t work_bytes, void* stream)
 {
     SAR_TRY(bwd_common_checks(b, dtype, H, D, G, rec, a_l, ds, da_l, work, work_bytes));
-    SAR_CHECK_ARG(Zq && tq && dZq && dtq, "a pointer table is null");
+    SAR_CHECK_ARG(Zq && dZq && dtq, "a pointer table is null");
     hipStream_t st = sar::as_stream(stream);
     BwdArgs tabs{};
     const int F = H * D;
     for (int q = 0; q < b->P; ++q) {
         const sar::Block& k = b->blk[q];
         if (k.n_src == 0) continue;
-        SAR_CHECK_ARG(Zq[q] && tq[q] && dZq[q] && dtq[q], "a tensor of block %d is null", q);
+        SAR_CHECK_ARG(Zq[q] && (!tq || tq[q]) && dZq[q] && dtq[q], "a tensor of block %d is null", q);
         SAR_CHECK_ARG(aligned16(Zq[q]) && aligned16(dZq[q]), "Zq[%d] and dZq[%d] must be 16-byte aligned", q, q);
         tabs.t_indptr[q] = k.t_indptr;
         tabs.t_indices[q] = k.t_indices;
         tabs.Z[q] = Zq[q];
-        tabs.t[q] = tq[q];
+        tabs.t[q] = tq ? tq[q] : nullptr;
         tabs.dZ[q] = dZq[q];
         tabs.dt[q] = dtq[q];
     }
@@ -1021,15 +1062,16 @@ extern "C" int sar_gat_bwd_all(const sar_blocks_t* b, const void* const* Zq, con
     return launch_bwd<bf16_t, true>(tabs, a, da_l, st);
 }
 
-extern "C" int sar_gat_bwd_end(const void* Zdst, const float* ds, const float* a_r, void* dZdst, float* da_r,
-                               int dtype, int64_t n_dst, int H, int D, void* work, size_t work_bytes,
-                               void* stream)
+extern "C" int sar_gat_bwd_end(const void* Zdst, const float* ds, const float* a_r, const void* dZadd,
+                               void* dZdst, float* da_r, int dtype, int64_t n_dst, int H, int D, void* work,
+                               size_t work_bytes, void* stream)
 {
     SAR_TRY(check_shape(dtype, H, D));
     SAR_CHECK_ARG(n_dst >= 0, "n_dst is negative");
     if (n_dst == 0) return SAR_OK;
     SAR_CHECK_ARG(Zdst && ds && a_r && dZdst && da_r, "a tensor argument is null");
-    SAR_CHECK_ARG(aligned16(Zdst) && aligned16(dZdst), "Zdst and dZdst must be 16-byte aligned");
+    SAR_CHECK_ARG(aligned16(Zdst) && aligned16(dZdst) && aligned16(dZadd),
+                  "Zdst, dZadd and dZdst must be 16-byte aligned");
     SAR_CHECK_ARG(work != nullptr && aligned16(work), "work is null or not 16-byte aligned");
     const int F = H * D;
     SAR_CHECK_ARG(work_bytes >= workspace_bytes(F), "work_bytes=%zu is below the %zu bytes required", work_bytes,
@@ -1039,12 +1081,14 @@ extern "C" int sar_gat_bwd_end(const void* Zdst, const float* ds, const float* a
     if (dtype == SAR_F32) {
         SAR_DISPATCH_G(float, F, (grid = nodewise_grid(n_dst, kWave / kG),
                                   k_bwd_end<float, kG><<<grid, kGatherThreads, 0, st>>>(
-                                      static_cast<const float*>(Zdst), ds, a_r, static_cast<float*>(dZdst),
+                                      static_cast<const float*>(Zdst), ds, a_r, static_cast<const float*>(dZadd),
+                                      static_cast<float*>(dZdst),
                                       static_cast<float*>(work), n_dst, H, D, F)));
     } else {
         SAR_DISPATCH_G(bf16_t, F, (grid = nodewise_grid(n_dst, kWave / kG),
                                    k_bwd_end<bf16_t, kG><<<grid, kGatherThreads, 0, st>>>(
-                                       static_cast<const bf16_t*>(Zdst), ds, a_r, static_cast<bf16_t*>(dZdst),
+                                       static_cast<const bf16_t*>(Zdst), ds, a_r, static_cast<const bf16_t*>(dZadd),
+                                       static_cast<bf16_t*>(dZdst),
                                        static_cast<float*>(work), n_dst, H, D, F)));
     }
     SAR_LAUNCH_CHECK();

@@ -137,7 +137,8 @@ struct FwdP {
     const uint32_t* rows;
     int64_t n_rows, n_long;
     const void* Z;
-    const float* t;
+    const float* t;      // source score halves, or null with FLY (formed from a_l and the gathered row)
+    const float* a_l;
     const float* s;
     float* m;
     float* l;
@@ -157,9 +158,9 @@ struct FwdState {
 };
 
 // One 64-edge chunk position `mine`(lane) holds; folds edges [0,cnt) of it.
-template <typename T, int LPH, int B, bool ALL>
+template <typename T, int LPH, int B, bool ALL, bool FLY>
 __device__ inline void fwd_chunk(FwdState<LPH>& st, const FwdP& a, const Tabs& tabs, uint32_t mine, int cnt,
-                                 int lane, int h, int k, float s2)
+                                 int lane, int h, int k, float s2, const float (&al)[4])
 {
     const uint32_t mask = ALL ? ((1u << a.tag_shift) - 1u) : 0xffffffffu;
     for (int k0 = 0; k0 < cnt; k0 += B) {
@@ -174,9 +175,23 @@ __device__ inline void fwd_chunk(FwdState<LPH>& st, const FwdP& a, const Tabs& t
         });
         // scores: lane k of every head group takes edge k0+k
         const bool valid = k < nb;
-        const uint32_t my = (uint32_t)__shfl((int)mine, k0 + (valid ? k : 0));
-        const float* tb = ALL ? tabs.t[my >> a.tag_shift] : a.t;
-        const float tv = tb[(int64_t)(my & mask) * a.H + h];
+        float tv = 0.f;
+        if constexpr (FLY) {
+            // t_j = <a_l, z_j> from the row just gathered; lane k keeps edge k's value
+            static_for<B>([&](auto kk) {
+                float v[4];
+                Row4<T>::unpack(raw[decltype(kk)::value], v);
+                float c = al[0] * v[0];
+#pragma unroll
+                for (int x = 1; x < 4; ++x) c = fmaf(al[x], v[x], c);
+                c = group_all<LPH, OpSum>(c);
+                tv = (k == decltype(kk)::value) ? c : tv;
+            });
+        } else {
+            const uint32_t my = (uint32_t)__shfl((int)mine, k0 + (valid ? k : 0));
+            const float* tb = ALL ? tabs.t[my >> a.tag_shift] : a.t;
+            tv = tb[(int64_t)(my & mask) * a.H + h];
+        }
         const float e2 = valid ? leaky2(fmaf(tv, kLog2e, s2), a.slope) : -INFINITY;
         const float cmax = group_all<LPH, OpMax>(e2);
         if (__builtin_amdgcn_ballot_w64(cmax > st.m2)) {
@@ -199,7 +214,7 @@ __device__ inline void fwd_chunk(FwdState<LPH>& st, const FwdP& a, const Tabs& t
     }
 }
 
-template <typename T, int LPH, int B, bool ALL>
+template <typename T, int LPH, int B, bool ALL, bool FLY>
 __global__ __launch_bounds__(kGatherThreads) void k_gat_fwd_f256(FwdP a, Tabs tabs)
 {
     static_assert(B <= LPH, "a sub-batch must fit a head group");
@@ -208,6 +223,8 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_fwd_f256(FwdP a, Tabs ta
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int h = lane / LPH, k = lane % LPH;
     T* outp = static_cast<T*>(a.out);
+    float al[4] = {0.f, 0.f, 0.f, 0.f};
+    if constexpr (FLY) load_f32<4>(a.a_l + lane * 4, al);
 
     auto init = [&](FwdState<LPH>& st, int i, bool carry) {
         st.m2 = -INFINITY;
@@ -245,7 +262,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_fwd_f256(FwdP a, Tabs ta
         for (int cb = beg + chunk0 * kWave; cb < end; cb += stride * kWave) {
             const int cnt = min(kWave, end - cb);
             const uint32_t mine = (lane < cnt) ? a.indices[cb + lane] : 0u;
-            fwd_chunk<T, LPH, B, ALL>(st, a, tabs, mine, cnt, lane, h, k, s2);
+            fwd_chunk<T, LPH, B, ALL, FLY>(st, a, tabs, mine, cnt, lane, h, k, s2, al);
         }
     };
 
@@ -378,7 +395,15 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_f256(BwdTabs tabs, B
 
     auto edges = [&](BwdAcc4& ac, int q, int j, int chunk0, int stride, float (&zj)[4]) {
         Row4<T>::unpack(Row4<T>::load(static_cast<const T*>(tabs.Z[q]) + (int64_t)j * kF, lane), zj);
-        const float t2 = tabs.t[q][(int64_t)j * a.H + h] * kLog2e;
+        float t2;
+        if (tabs.t[q]) {
+            t2 = tabs.t[q][(int64_t)j * a.H + h] * kLog2e;
+        } else {   // t_j = <a_l, z_j> from the row this wavefront owns
+            float c = al[0] * zj[0];
+#pragma unroll
+            for (int x = 1; x < 4; ++x) c = fmaf(al[x], zj[x], c);
+            t2 = group_all<LPH, OpSum>(c) * kLog2e;
+        }
         const int32_t* ip = tabs.t_indptr[q];
         const int32_t* idx = tabs.t_indices[q];
         const int beg = ip[j], end = ip[j + 1];

@@ -256,12 +256,13 @@ def sar_gat_fwd_begin(m: torch.Tensor, l: torch.Tensor, acc: torch.Tensor) -> No
     _check(lib().sar_gat_fwd_begin(_ptr(m), _ptr(l), _ptr(acc), _c_i64(n), _c_int(H), _c_int(D), _stream()))
 
 
-def sar_gat_fwd_block(b: Blocks, q: int, Zq: torch.Tensor, s: torch.Tensor, tq: torch.Tensor, slope: float,
+def sar_gat_fwd_block(b: Blocks, q: int, Zq: torch.Tensor, s: torch.Tensor, tq: Optional[torch.Tensor],
+                      a_l: Optional[torch.Tensor], slope: float,
                       m: torch.Tensor, l: torch.Tensor, acc: torch.Tensor) -> None:
     _, H, D = acc.shape
     b.check_rows(q, Zq, tq)
     b.check_dst(s, m, l, acc)
-    _check(lib().sar_gat_fwd_block(b.handle, _c_int(q), _ptr(Zq), _ptr(s), _ptr(tq),
+    _check(lib().sar_gat_fwd_block(b.handle, _c_int(q), _ptr(Zq), _ptr(s), _ptr(tq), _ptr(a_l),
                                    _c_int(dtype_code(Zq.dtype)), _c_int(H), _c_int(D), ctypes.c_float(slope),
                                    _ptr(m), _ptr(l), _ptr(acc), _stream()))
 
@@ -273,13 +274,15 @@ def sar_gat_fwd_end(m: torch.Tensor, l: torch.Tensor, acc: torch.Tensor, out: to
                                  _c_int(dtype_code(out.dtype)), _c_i64(n), _c_int(H), _c_int(D), _stream()))
 
 
-def sar_gat_fwd_all(b: Blocks, Zq: Sequence[torch.Tensor], s: torch.Tensor, tq: Sequence[torch.Tensor],
+def sar_gat_fwd_all(b: Blocks, Zq: Sequence[torch.Tensor], s: torch.Tensor,
+                    tq: Optional[Sequence[torch.Tensor]], a_l: Optional[torch.Tensor],
                     slope: float, out: torch.Tensor, L: torch.Tensor) -> None:
     _, H, D = out.shape
     for q in range(b.P):
-        b.check_rows(q, Zq[q], tq[q])
+        b.check_rows(q, Zq[q], None if tq is None else tq[q])
     b.check_dst(s, out, L)
-    _check(lib().sar_gat_fwd_all(b.handle, _ptr_array(Zq), _ptr(s), _ptr_array(tq),
+    _check(lib().sar_gat_fwd_all(b.handle, _ptr_array(Zq), _ptr(s), None if tq is None else _ptr_array(tq),
+                                 _ptr(a_l),
                                  _c_int(dtype_code(out.dtype)), _c_int(H), _c_int(D), ctypes.c_float(slope),
                                  _ptr(out), _ptr(L), _stream()))
 
@@ -316,18 +319,19 @@ def sar_gat_bwd_all(b: Blocks, Zq: Sequence[torch.Tensor], G: torch.Tensor, tq: 
                     work: torch.Tensor) -> None:
     H, D = a_l.shape
     for q in range(b.P):
-        b.check_rows(q, Zq[q], tq[q], dZq[q], dtq[q])
+        b.check_rows(q, Zq[q], None if tq is None else tq[q], dZq[q], dtq[q])
     b.check_dst(G, rec, ds)
-    _check(lib().sar_gat_bwd_all(b.handle, _ptr_array(Zq), _ptr(G), _ptr_array(tq), _ptr(rec), _ptr(a_l),
+    _check(lib().sar_gat_bwd_all(b.handle, _ptr_array(Zq), _ptr(G), None if tq is None else _ptr_array(tq),
+                                 _ptr(rec), _ptr(a_l),
                                  _c_int(dtype_code(G.dtype)), _c_int(H), _c_int(D), ctypes.c_float(slope),
                                  _ptr_array(dZq), _ptr_array(dtq), _ptr(ds), _ptr(da_l), _ptr(work),
                                  ctypes.c_size_t(work.numel() * work.element_size()), _stream()))
 
 
-def sar_gat_bwd_end(Zdst: torch.Tensor, ds: torch.Tensor, a_r: torch.Tensor, dZdst: torch.Tensor,
-                    da_r: torch.Tensor, work: torch.Tensor) -> None:
+def sar_gat_bwd_end(Zdst: torch.Tensor, ds: torch.Tensor, a_r: torch.Tensor, dZadd: Optional[torch.Tensor],
+                    dZdst: torch.Tensor, da_r: torch.Tensor, work: torch.Tensor) -> None:
     H, D = a_r.shape
-    _check(lib().sar_gat_bwd_end(_ptr(Zdst), _ptr(ds), _ptr(a_r), _ptr(dZdst), _ptr(da_r),
+    _check(lib().sar_gat_bwd_end(_ptr(Zdst), _ptr(ds), _ptr(a_r), _ptr(dZadd), _ptr(dZdst), _ptr(da_r),
                                  _c_int(dtype_code(Zdst.dtype)), _c_i64(Zdst.shape[0]), _c_int(H), _c_int(D),
                                  _ptr(work), ctypes.c_size_t(work.numel() * work.element_size()), _stream()))
 

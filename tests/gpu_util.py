@@ -85,7 +85,8 @@ def gat_scores(Zdst, Zs, a_l, a_r):
     return s, t
 
 
-def gat_fwd_stream(b: sar.Blocks, Zdst, Zs, a_l, a_r, slope, order=None, states=None) -> GatOut:
+def gat_fwd_stream(b: sar.Blocks, Zdst, Zs, a_l, a_r, slope, order=None, states=None, fly=False) -> GatOut:
+    """fly=True: the source score halves are formed inside the kernels (tq = NULL)."""
     H, D = a_l.shape
     s, t = gat_scores(Zdst, Zs, a_l, a_r)
     n = b.n_dst
@@ -94,7 +95,7 @@ def gat_fwd_stream(b: sar.Blocks, Zdst, Zs, a_l, a_r, slope, order=None, states=
     acc = torch.empty((n, H, D), dtype=torch.float32, device=DEV)
     sar.sar_gat_fwd_begin(m, l, acc)
     for q in (order if order is not None else range(b.P)):
-        sar.sar_gat_fwd_block(b, q, Zs[q], s, t[q], slope, m, l, acc)
+        sar.sar_gat_fwd_block(b, q, Zs[q], s, None if fly else t[q], a_l, slope, m, l, acc)
         if states is not None:
             states.append((host(m), host(l), host(acc)))
     out = torch.full((n, H, D), float("nan"), dtype=Zdst.dtype, device=DEV)
@@ -103,12 +104,12 @@ def gat_fwd_stream(b: sar.Blocks, Zdst, Zs, a_l, a_r, slope, order=None, states=
     return GatOut(out, L, s, t)
 
 
-def gat_fwd_all(b: sar.Blocks, Zdst, Zs, a_l, a_r, slope) -> GatOut:
+def gat_fwd_all(b: sar.Blocks, Zdst, Zs, a_l, a_r, slope, fly=False) -> GatOut:
     H, D = a_l.shape
     s, t = gat_scores(Zdst, Zs, a_l, a_r)
     out = torch.full((b.n_dst, H, D), float("nan"), dtype=Zdst.dtype, device=DEV)
     L = torch.full((b.n_dst, H), float("nan"), dtype=torch.float32, device=DEV)
-    sar.sar_gat_fwd_all(b, Zs, s, t, slope, out, L)
+    sar.sar_gat_fwd_all(b, Zs, s, None if fly else t, a_l, slope, out, L)
     return GatOut(out, L, s, t)
 
 
@@ -122,7 +123,8 @@ class GatGrads:
     da_r: torch.Tensor
 
 
-def gat_bwd(b: sar.Blocks, Zdst, Zs, G, a_l, a_r, slope, fw: GatOut, batched: bool) -> GatGrads:
+def gat_bwd(b: sar.Blocks, Zdst, Zs, G, a_l, a_r, slope, fw: GatOut, batched: bool, fly=False,
+            dZadd=None) -> GatGrads:
     H, D = a_l.shape
     n = b.n_dst
     rec = torch.empty((n, H, 4), dtype=torch.float32, device=DEV)
@@ -135,12 +137,13 @@ def gat_bwd(b: sar.Blocks, Zdst, Zs, G, a_l, a_r, slope, fw: GatOut, batched: bo
     dZs = [torch.full(Z.shape, float("nan"), dtype=Z.dtype, device=DEV) for Z in Zs]
     dts = [torch.full((Z.shape[0], H), float("nan"), dtype=torch.float32, device=DEV) for Z in Zs]
     if batched:
-        sar.sar_gat_bwd_all(b, Zs, G, fw.t, rec, a_l, slope, dZs, dts, ds, da_l, work)
+        sar.sar_gat_bwd_all(b, Zs, G, None if fly else fw.t, rec, a_l, slope, dZs, dts, ds, da_l, work)
     else:
         for q in range(b.P):
-            sar.sar_gat_bwd_block(b, q, Zs[q], G, fw.t[q], rec, a_l, slope, dZs[q], dts[q], ds, da_l, work)
+            sar.sar_gat_bwd_block(b, q, Zs[q], G, None if fly else fw.t[q], rec, a_l, slope, dZs[q], dts[q], ds,
+                                  da_l, work)
     dZdst = torch.full(Zdst.shape, float("nan"), dtype=Zdst.dtype, device=DEV)
-    sar.sar_gat_bwd_end(Zdst, ds, a_r, dZdst, da_r, work)
+    sar.sar_gat_bwd_end(Zdst, ds, a_r, dZadd, dZdst, da_r, work)
     return GatGrads(dZs, dts, ds, dZdst, da_l, da_r)
 
 

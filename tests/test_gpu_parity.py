@@ -167,8 +167,9 @@ def gat_case(seed, N, E, P, p, H, D, dtype, scale=1.0, simple=True, empty_block=
     F = H * D
     Zs = [feats(rng, w.n_src, F, dtype, scale).cuda().reshape(-1, H, D) for w in want_b]
     Zdst = feats(rng, b.n_dst, F, dtype, scale).cuda().reshape(-1, H, D)
-    a_l = torch.from_numpy(rng.uniform(-0.5, 0.5, (H, D)).astype(np.float32)).cuda()
-    a_r = torch.from_numpy(rng.uniform(-0.5, 0.5, (H, D)).astype(np.float32)).cuda()
+    bound = np.sqrt(6.0 / (D + 1))      # Xavier-uniform, as in the configurations: scores of O(1)
+    a_l = torch.from_numpy(rng.uniform(-bound, bound, (H, D)).astype(np.float32)).cuda()
+    a_r = torch.from_numpy(rng.uniform(-bound, bound, (H, D)).astype(np.float32)).cuda()
     G = feats(rng, b.n_dst, F, dtype).cuda().reshape(-1, H, D)
     return b, want_b, deg, Zdst, Zs, a_l, a_r, G
 
@@ -185,7 +186,7 @@ def check_fwd(got, want, deg, dtype):
         assert rel_err(f64(tg), tw) < 1e-4
 
 
-SHAPES = [(4, 16), (1, 4), (4, 64), (8, 32), (2, 100), (3, 12)]
+SHAPES = [(4, 16), (1, 4), (4, 64), (8, 32), (2, 100), (3, 12), (1, 256), (2, 128), (16, 16)]
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
@@ -198,6 +199,9 @@ def test_gat_forward_parity(dtype, H, D):
     states = []
     check_fwd(gu.gat_fwd_stream(b, Zdst, Zs, a_l, a_r, SLOPE, states=states), want, deg, dtype)
     check_fwd(gu.gat_fwd_all(b, Zdst, Zs, a_l, a_r, SLOPE), want, deg, dtype)
+    # source score halves formed inside the kernels instead of read from tq
+    check_fwd(gu.gat_fwd_stream(b, Zdst, Zs, a_l, a_r, SLOPE, fly=True), want, deg, dtype)
+    check_fwd(gu.gat_fwd_all(b, Zdst, Zs, a_l, a_r, SLOPE, fly=True), want, deg, dtype)
     # the carried state after block k represents Eq. 3 restricted to blocks 0..k
     for k, (m, l, acc) in enumerate(states[:-1]):
         part = orc.gat_fwd(want_b[:k + 1], f64(Zdst), [f64(z) for z in Zs[:k + 1]], f64(a_l), f64(a_r), SLOPE)
@@ -211,15 +215,15 @@ def test_gat_forward_parity(dtype, H, D):
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("H,D", SHAPES)
-@pytest.mark.parametrize("batched", [False, True])
-def test_gat_backward_parity(dtype, H, D, batched):
+@pytest.mark.parametrize("batched,fly", [(False, False), (True, False), (True, True), (False, True)])
+def test_gat_backward_parity(dtype, H, D, batched, fly):
     if dtype == torch.bfloat16 and D % 8:
         pytest.skip("bf16 rows move 8 values per lane")
     b, want_b, deg, Zdst, Zs, a_l, a_r, G = gat_case(7, 3000, 40000, 3, 1, H, D, dtype)
     wf = orc.gat_fwd(want_b, f64(Zdst), [f64(z) for z in Zs], f64(a_l), f64(a_r), SLOPE)
     wb = orc.gat_bwd(want_b, f64(Zdst), [f64(z) for z in Zs], f64(G), f64(a_l), f64(a_r), SLOPE, wf)
     fw = gu.gat_fwd_all(b, Zdst, Zs, a_l, a_r, SLOPE)
-    g = gu.gat_bwd(b, Zdst, Zs, G, a_l, a_r, SLOPE, fw, batched)
+    g = gu.gat_bwd(b, Zdst, Zs, G, a_l, a_r, SLOPE, fw, batched, fly=fly)
     tol = TOL[dtype]
     for q in range(b.P):
         assert rel_err(f64(g.dZs[q]), wb.dZs[q]) < tol, q
@@ -228,6 +232,9 @@ def test_gat_backward_parity(dtype, H, D, batched):
     assert rel_err(f64(g.dZdst), wb.dZdst) < tol
     assert rel_err(f64(g.da_l), wb.da_l) < tol
     assert rel_err(f64(g.da_r), wb.da_r) < tol
+    # the local block's error added into the destination-side error in the same pass
+    g2 = gu.gat_bwd(b, Zdst, Zs, G, a_l, a_r, SLOPE, fw, batched, fly=fly, dZadd=G)
+    assert rel_err(f64(g2.dZdst), wb.dZdst + f64(G)) < tol
     b.close()
 
 
