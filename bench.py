@@ -41,7 +41,9 @@ def parse():
     ap.add_argument("--mode", default="all", choices=["all", "stream"],
                     help="all: one launch over the P blocks; stream: one launch per block")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-blocks", type=int, default=1, help="blocks in the oracle's timed sample")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="also run one plain device copy of this size (to scale rocprofv3's FETCH_SIZE/WRITE_SIZE)")
+    ap.add_argument("--cpu-blocks", type=int, default=5, help="blocks in the oracle's timed sample")
     return ap.parse_args()
 
 
@@ -240,6 +242,13 @@ def main():
         return
     layer = Layer(w, torch, sar, synth)
 
+    if args.calib_copy_mib:
+        a = torch.ones(args.calib_copy_mib << 18, dtype=torch.float32, device="cuda")
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        b.copy_(a)          # one kernel that reads and writes exactly calib_copy_mib MiB
+        torch.cuda.synchronize()
+        del a, b
     for _ in range(args.warmup):
         layer.step(args.mode)
     torch.cuda.synchronize()

@@ -17,9 +17,10 @@ namespace {
 
 using namespace sar;
 
-constexpr int BM = 128, BN = 128, BK = 16;
+constexpr int BM = 128, BN = 128, BK = 32;
 constexpr int kPad = 4;
 constexpr int kGemmThreads = 256;
+constexpr int kPerThread = BM * BK / kGemmThreads / 4;   // 4-element groups each thread stages per operand
 
 typedef float float16_t __attribute__((ext_vector_type(16)));
 
@@ -37,6 +38,35 @@ __device__ inline float from_f32<float>(float v) { return v; }
 template <>
 __device__ inline bf16_t from_f32<bf16_t>(float v) { return bf16_t{(uint16_t)f32_to_bf16_rne(v)}; }
 
+// four consecutive elements, widened to fp32 (vector access when `vec`)
+template <typename T>
+__device__ inline void load4(const T* p, bool vec, int n_valid, float (&v)[4]);
+template <>
+__device__ inline void load4<float>(const float* p, bool vec, int n_valid, float (&v)[4])
+{
+    if (vec && n_valid == 4) {
+        const float4 x = *reinterpret_cast<const float4*>(p);
+        v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
+    } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v[k] = k < n_valid ? p[k] : 0.f;
+    }
+}
+template <>
+__device__ inline void load4<bf16_t>(const bf16_t* p, bool vec, int n_valid, float (&v)[4])
+{
+    if (vec && n_valid == 4) {
+        const uint2 x = *reinterpret_cast<const uint2*>(p);
+        v[0] = __uint_as_float(x.x << 16);
+        v[1] = __uint_as_float(x.x & 0xffff0000u);
+        v[2] = __uint_as_float(x.y << 16);
+        v[3] = __uint_as_float(x.y & 0xffff0000u);
+    } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v[k] = k < n_valid ? to_f32<bf16_t>(p[k]) : 0.f;
+    }
+}
+
 struct GemmArgs {
     const void* A;
     const void* B;
@@ -44,26 +74,76 @@ struct GemmArgs {
     int64_t M;        // rows of C
     int N;            // cols of C
     int64_t Kd;       // contraction length
-    int64_t sa_i, sa_k;   // A(i,k) = A[i*sa_i + k*sa_k]
-    int64_t sb_k, sb_j;   // B(k,j) = B[k*sb_k + j*sb_j]
+    int64_t lda;      // A_K_FAST: A(i,k) = A[i*lda + k]   else A(i,k) = A[k*lda + i]
+    int64_t ldb;      // B_K_FAST: B(k,j) = B[j*ldb + k]   else B(k,j) = B[k*ldb + j]
     int64_t ldc;
     int64_t k_slab;   // contraction range per blockIdx.z (split-K); C advances by c_split per slab
     int64_t c_split;
+    int vec_a, vec_b; // 4-element groups of A / B are aligned and in one row
 };
 
-// A_K_FAST: consecutive threads walk k when loading A (A is contiguous in k).
-// B_K_FAST: same for B.
+// One operand tile of TILE x BK (TILE = BM or BN) staged through registers:
+// each thread owns kPerThread groups of 4 elements that are consecutive in the
+// operand's contiguous dimension (k when K_FAST, else the tile dimension).
+template <typename T, bool K_FAST>
+struct Stage {
+    float v[kPerThread][4];
+    __device__ inline void fetch(const T* base, int64_t ld, int64_t x0, int64_t x_end, int64_t k0, int64_t k_end,
+                                 bool vec, int tid)
+    {
+#pragma unroll
+        for (int g = 0; g < kPerThread; ++g) {
+            const int e = g * kGemmThreads + tid;
+            if (K_FAST) {
+                const int kk = (e % (BK / 4)) * 4, x = e / (BK / 4);
+                const int64_t nk = k_end - (k0 + kk);
+                const int nv = (x0 + x < x_end) ? (int)(nk >= 4 ? 4 : (nk > 0 ? nk : 0)) : 0;
+                if (nv > 0)
+                    load4<T>(base + (x0 + x) * ld + k0 + kk, vec, nv, v[g]);
+                else
+                    v[g][0] = v[g][1] = v[g][2] = v[g][3] = 0.f;
+            } else {
+                const int x = (e % (BM / 4)) * 4, kk = e / (BM / 4);
+                const int64_t nx = x_end - (x0 + x);
+                const int nv = (k0 + kk < k_end) ? (int)(nx >= 4 ? 4 : (nx > 0 ? nx : 0)) : 0;
+                if (nv > 0)
+                    load4<T>(base + (k0 + kk) * ld + x0 + x, vec, nv, v[g]);
+                else
+                    v[g][0] = v[g][1] = v[g][2] = v[g][3] = 0.f;
+            }
+        }
+    }
+    __device__ inline void commit(float (*tile)[BM + kPad], int tid) const
+    {
+#pragma unroll
+        for (int g = 0; g < kPerThread; ++g) {
+            const int e = g * kGemmThreads + tid;
+            if (K_FAST) {
+                const int kk = (e % (BK / 4)) * 4, x = e / (BK / 4);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) tile[kk + c][x] = v[g][c];
+            } else {
+                const int x = (e % (BM / 4)) * 4, kk = e / (BM / 4);
+                *reinterpret_cast<float4*>(&tile[kk][x]) = make_float4(v[g][0], v[g][1], v[g][2], v[g][3]);
+            }
+        }
+    }
+};
+
+static_assert(BM == BN, "operand staging assumes square workgroup tiles");
+
+// A_K_FAST: A is contiguous along the contraction; B_K_FAST: same for B.
 template <typename TA, typename TB, typename TC, bool A_K_FAST, bool B_K_FAST>
 __global__ __launch_bounds__(kGemmThreads) void k_gemm(GemmArgs g)
 {
-    __shared__ float As[BK][BM + kPad];
-    __shared__ float Bs[BK][BN + kPad];
+    __shared__ __attribute__((aligned(16))) float As[BK][BM + kPad];
+    __shared__ __attribute__((aligned(16))) float Bs[BK][BN + kPad];
     const TA* A = static_cast<const TA*>(g.A);
     const TB* B = static_cast<const TB*>(g.B);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int64_t m0 = (int64_t)blockIdx.x * BM;
-    const int n0 = blockIdx.y * BN;
+    const int64_t n0 = (int64_t)blockIdx.y * BN;
     const int64_t k_beg = (int64_t)blockIdx.z * g.k_slab;
     const int64_t k_end = std::min<int64_t>(g.Kd, k_beg + g.k_slab);
 
@@ -75,39 +155,21 @@ __global__ __launch_bounds__(kGemmThreads) void k_gemm(GemmArgs g)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
+    Stage<TA, A_K_FAST> sa;
+    Stage<TB, B_K_FAST> sb;
+    if (k_beg < k_end) {
+        sa.fetch(A, g.lda, m0, g.M, k_beg, k_end, g.vec_a, tid);
+        sb.fetch(B, g.ldb, n0, g.N, k_beg, k_end, g.vec_b, tid);
+    }
     for (int64_t k0 = k_beg; k0 < k_end; k0 += BK) {
-        // stage A[BM x BK] and B[BK x BN], 8 values per thread each
-#pragma unroll
-        for (int t = 0; t < (BM * BK) / kGemmThreads; ++t) {
-            const int e = t * kGemmThreads + tid;
-            int i, kk;
-            if (A_K_FAST) {
-                kk = e % BK;
-                i = e / BK;
-            } else {
-                i = e % BM;
-                kk = e / BM;
-            }
-            float v = 0.f;
-            if (m0 + i < g.M && k0 + kk < k_end) v = to_f32<TA>(A[(m0 + i) * g.sa_i + (k0 + kk) * g.sa_k]);
-            As[kk][i] = v;
-        }
-#pragma unroll
-        for (int t = 0; t < (BN * BK) / kGemmThreads; ++t) {
-            const int e = t * kGemmThreads + tid;
-            int j, kk;
-            if (B_K_FAST) {
-                kk = e % BK;
-                j = e / BK;
-            } else {
-                j = e % BN;
-                kk = e / BN;
-            }
-            float v = 0.f;
-            if (n0 + j < g.N && k0 + kk < k_end) v = to_f32<TB>(B[(k0 + kk) * g.sb_k + (int64_t)(n0 + j) * g.sb_j]);
-            Bs[kk][j] = v;
-        }
+        sa.commit(As, tid);
+        sb.commit(Bs, tid);
         __syncthreads();
+        // the next tile travels from HBM while this one is multiplied
+        if (k0 + BK < k_end) {
+            sa.fetch(A, g.lda, m0, g.M, k0 + BK, k_end, g.vec_a, tid);
+            sb.fetch(B, g.ldb, n0, g.N, k0 + BK, k_end, g.vec_b, tid);
+        }
 #pragma unroll
         for (int ks = 0; ks < BK; ks += 2) {
             const int kk = ks + (lane >> 5);
@@ -132,7 +194,7 @@ __global__ __launch_bounds__(kGemmThreads) void k_gemm(GemmArgs g)
     for (int x = 0; x < 2; ++x)
 #pragma unroll
         for (int y = 0; y < 2; ++y) {
-            const int j = n0 + wn * 64 + y * 32 + (lane & 31);
+            const int64_t j = n0 + wn * 64 + y * 32 + (lane & 31);
             if (j >= g.N) continue;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
@@ -164,7 +226,11 @@ int slabs_for(int64_t n, int K, int F)
     return (int)std::min(want, by_rows);
 }
 
-bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+// groups of 4 consecutive elements can be moved with one access: rows start aligned
+int vec_ok(const void* p, int64_t ld, int elem_bytes)
+{
+    return (reinterpret_cast<uintptr_t>(p) % (4 * elem_bytes) == 0) && (ld % 4 == 0);
+}
 
 }  // namespace
 
@@ -196,13 +262,13 @@ extern "C" int sar_linear_fwd(const void* X, const float* W, void* Z, int dtype,
     g.M = n;
     g.N = F;
     g.Kd = K;
-    g.sa_i = K;
-    g.sa_k = 1;
-    g.sb_k = F;
-    g.sb_j = 1;
+    g.lda = K;
+    g.ldb = F;
     g.ldc = F;
     g.k_slab = K;
     g.c_split = 0;
+    g.vec_a = vec_ok(X, K, dtype == SAR_F32 ? 4 : 2);
+    g.vec_b = vec_ok(W, F, 4);
     dim3 grid((unsigned)((n + BM - 1) / BM), (unsigned)((F + BN - 1) / BN), 1);
     if (dtype == SAR_F32)
         k_gemm<float, float, float, true, false><<<grid, kGemmThreads, 0, st>>>(g);
@@ -238,13 +304,13 @@ extern "C" int sar_linear_bwd(const void* X, const void* dZ, const float* W, flo
         g.M = K;
         g.N = F;
         g.Kd = n;
-        g.sa_i = 1;
-        g.sa_k = K;
-        g.sb_k = F;
-        g.sb_j = 1;
+        g.lda = K;
+        g.ldb = F;
         g.ldc = F;
         g.k_slab = ((n + slabs - 1) / slabs + BK - 1) / BK * BK;
         g.c_split = (int64_t)K * F;
+        g.vec_a = vec_ok(X, K, dtype == SAR_F32 ? 4 : 2);
+        g.vec_b = vec_ok(dZ, F, dtype == SAR_F32 ? 4 : 2);
         dim3 grid((unsigned)((K + BM - 1) / BM), (unsigned)((F + BN - 1) / BN), (unsigned)slabs);
         if (dtype == SAR_F32)
             k_gemm<float, float, float, false, false><<<grid, kGemmThreads, 0, st>>>(g);
@@ -265,13 +331,13 @@ extern "C" int sar_linear_bwd(const void* X, const void* dZ, const float* W, flo
         g.M = n;
         g.N = K;
         g.Kd = F;
-        g.sa_i = F;
-        g.sa_k = 1;
-        g.sb_k = 1;
-        g.sb_j = F;
+        g.lda = F;
+        g.ldb = F;
         g.ldc = K;
         g.k_slab = F;
         g.c_split = 0;
+        g.vec_a = vec_ok(dZ, F, dtype == SAR_F32 ? 4 : 2);
+        g.vec_b = vec_ok(W, F, 4);
         dim3 grid((unsigned)((n + BM - 1) / BM), (unsigned)((K + BN - 1) / BN), 1);
         if (dtype == SAR_F32)
             k_gemm<float, float, float, true, true><<<grid, kGemmThreads, 0, st>>>(g);

@@ -1,0 +1,213 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times
+(all blocks in one launch, source score halves formed inside the kernels).
+
+The oracle cannot run a 15M- or 200M-edge layer in seconds, so it computes
+sampled outputs one by one: for a sample of destinations (and of sources, for
+the backward pass) the test cuts the closed neighbourhood out of the RAW edge
+list -- every in-edge of every destination involved -- relabels it compactly
+(order preserving, so local ids keep their ranks) and lets the oracle run its
+normal flow on that subgraph with features regenerated from the same
+counter-based generator.  What a sample cannot cover (the parameter gradients,
+which sum over all rows) is checked through identities that hold at any size,
+recomputed in fp64 from tensors that were themselves sample-checked.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import sar_oracle as orc
+from tests.helpers import rel_err
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    from paper_2111_06483_amd import sar, synth
+    from tests import gpu_util as gu
+
+TOL = {torch.float32: 1e-4, torch.bfloat16: 2e-2}
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU in this process")
+    sar.lib()
+
+
+def f64(t):
+    return t.to(torch.float64).cpu().numpy()
+
+
+def lid_of(part, q):
+    """global id -> local id for partition q (rank among members), on the GPU."""
+    return torch.cumsum((part == q).to(torch.int64), 0) - 1
+
+
+class Sample:
+    """Closed neighbourhood of sampled destinations/sources, relabelled compactly."""
+
+    def __init__(self, w, n_dst_samples, n_src_samples, seed):
+        g = torch.Generator(device="cpu").manual_seed(seed)
+        src, dst, part = w.src, w.dst, w.part
+        N = w.N
+        indeg = torch.bincount(dst, minlength=N)
+        outdeg = torch.bincount(src, minlength=N)
+        mem_p = w.members(w.p)
+        pick = lambda pool, k: pool[torch.randperm(pool.numel(), generator=g)[:k].to(pool.device)]
+        d0 = torch.cat([pick(mem_p, n_dst_samples), indeg.argmax()[None], mem_p[indeg[mem_p] == 0][:3]])
+        srcs_with_edges = torch.nonzero(outdeg > 0).flatten()
+        self.S = torch.unique(torch.cat([pick(srcs_with_edges, n_src_samples), outdeg.argmax()[None]])) \
+            if n_src_samples else torch.empty(0, dtype=torch.int64, device=src.device)
+        in_S = torch.zeros(N, dtype=torch.bool, device=src.device)
+        in_S[self.S] = True
+        d1 = dst[in_S[src]]
+        self.D = torch.unique(torch.cat([d0, d1]))
+        in_D = torch.zeros(N, dtype=torch.bool, device=src.device)
+        in_D[self.D] = True
+        keep = in_D[dst]
+        self.e_src, self.e_dst = src[keep], dst[keep]
+        nodes = torch.unique(torch.cat([self.D, self.e_src]))
+        self.nodes = nodes
+        new_id = torch.full((N,), -1, dtype=torch.int64, device=src.device)
+        new_id[nodes] = torch.arange(nodes.numel(), device=src.device)
+        self.c_src = new_id[self.e_src].cpu().numpy()
+        self.c_dst = new_id[self.e_dst].cpu().numpy()
+        self.c_part = part[nodes].cpu().numpy()
+        self.new_id = new_id
+        self.blocks, self.deg = orc.build_blocks(self.c_src, self.c_dst, self.c_part, w.P, w.p)
+        # members of each partition inside the compact graph, as global ids (ascending)
+        self.c_members = [nodes[part[nodes] == q] for q in range(w.P)]
+
+    def rows_in_full(self, w, q, global_ids):
+        """Local ids (in the full problem) of some global ids of partition q."""
+        return lid_of(w.part, q)[global_ids]
+
+    def rows_in_compact(self, w, q, global_ids):
+        cp = torch.from_numpy(self.c_part).to(global_ids.device)
+        c_lid = torch.cumsum((cp == q).to(torch.int64), 0) - 1
+        return c_lid[self.new_id[global_ids]]
+
+
+def check_gat(name, n_dst_samples, n_src_samples):
+    w = synth.make_workload(name, device="cuda")
+    H, D, P, p, F = w.H, w.D, w.P, w.p, w.H * w.D
+    dt = w.dtype
+    tol = TOL[dt]
+    W, a_l, a_r = synth.gat_params(3, w.f_in, H, D, device="cuda")
+    members = [w.members(q) for q in range(P)]
+    b = sar.sar_blocks_build(w.src, w.dst, w.part, P, p)
+    n = b.n_dst
+
+    # ---- the HIP path, as bench.py runs it
+    Zs = []
+    for q in range(P):
+        Xq = synth.normal_rows(2, members[q], w.f_in, dtype=dt)
+        Zs.append(gu.linear_fwd(Xq, W)[0].reshape(-1, H, D))
+        del Xq
+    Xp = synth.normal_rows(2, members[p], w.f_in, dtype=dt)
+    Zdst = Zs[p]
+    G = synth.normal_rows(4, members[p], F, dtype=dt).reshape(n, H, D)
+    s = torch.empty((n, H), dtype=torch.float32, device="cuda")
+    sar.sar_gat_scores(Zdst, a_r, s)
+    out = torch.full((n, H, D), float("nan"), dtype=dt, device="cuda")
+    L = torch.full((n, H), float("nan"), dtype=torch.float32, device="cuda")
+    sar.sar_gat_fwd_all(b, Zs, s, None, a_l, w.slope, out, L)
+    fw = gu.GatOut(out, L, s, None)
+    g = gu.gat_bwd(b, Zdst, Zs, G, a_l, a_r, w.slope, fw, batched=True, fly=True)
+    torch.cuda.synchronize()
+
+    # ---- the oracle on the sampled closed neighbourhood
+    smp = Sample(w, n_dst_samples, n_src_samples, seed=5)
+    Wd, ald, ard = f64(W), f64(a_l), f64(a_r)
+    cXs = [f64(synth.normal_rows(2, m, w.f_in, dtype=dt)) for m in smp.c_members]
+    cZs = [orc.linear_fwd(x, Wd) for x in cXs]
+    if dt == torch.bfloat16:
+        # the path stores Z in bf16: the oracle gets the same rounded features
+        cZs = [f64(torch.from_numpy(z).to(dt)) for z in cZs]
+    cG = f64(synth.normal_rows(4, smp.c_members[p], F, dtype=dt)).reshape(-1, H, D)
+    ofw = orc.gat_fwd(smp.blocks, cZs[p], cZs, ald, ard, w.slope)
+    obw = orc.gat_bwd(smp.blocks, cZs[p], cZs, cG, ald, ard, w.slope, ofw)
+
+    # destinations: every compact destination that is in D has its whole in-neighbourhood
+    D_full = smp.rows_in_full(w, p, smp.D)
+    D_comp = smp.rows_in_compact(w, p, smp.D).cpu().numpy()
+    got_out = f64(out[D_full])
+    assert rel_err(got_out, ofw.out[D_comp]) < tol
+    Lw = ofw.L[D_comp]
+    Lg = f64(L[D_full])
+    fin = np.isfinite(Lw)
+    assert np.array_equal(fin, np.isfinite(Lg))
+    n_empty = int((sar.sar_blocks_degree(b) == 0).sum())
+    assert (~fin).sum() >= min(n_empty, 1)                                # empty rows, if any, were sampled
+    assert rel_err(Lg[fin], Lw[fin]) < (1e-4 if dt == torch.float32 else 2e-3)
+    assert np.all(got_out[~fin] == 0)
+    assert rel_err(f64(g.ds[D_full]), obw.ds[D_comp]) < tol
+    assert rel_err(f64(g.dZdst[D_full]), obw.dZdst[D_comp]) < tol
+    # sources: the sampled ones have all their edges inside the subgraph
+    n_checked = 0
+    for q in range(P):
+        Sq = smp.S[w.part[smp.S] == q]
+        if Sq.numel() == 0:
+            continue
+        jf = smp.rows_in_full(w, q, Sq)
+        jc = smp.rows_in_compact(w, q, Sq).cpu().numpy()
+        assert rel_err(f64(g.dZs[q][jf]), obw.dZs[q].reshape(-1, H, D)[jc]) < tol, q
+        assert rel_err(f64(g.dts[q][jf]), obw.dt[q][jc]) < tol, q
+        n_checked += Sq.numel()
+    assert n_checked >= n_src_samples
+
+    # ---- whole-tensor identities (fp64 on the GPU from sample-checked tensors)
+    d64 = lambda t: t.to(torch.float64)
+    da_r = torch.einsum("nh,nhd->hd", d64(g.ds), d64(Zdst))
+    assert rel_err(f64(g.da_r), da_r.cpu().numpy()) < 1e-4
+    da_l = sum(torch.einsum("nh,nhd->hd", d64(g.dts[q]), d64(Zs[q])) for q in range(P))
+    assert rel_err(f64(g.da_l), da_l.cpu().numpy()) < 1e-4
+    assert rel_err(f64(g.dZdst), (d64(g.ds)[:, :, None] * d64(a_r)[None]).cpu().numpy()) < tol
+    # softmax weights sum to one: a unit feature column aggregates to exactly 1 wherever deg > 0
+    deg = sar.sar_blocks_degree(b)
+    ones = [torch.ones_like(z) for z in Zs]
+    o1 = torch.empty_like(out)
+    L1 = torch.empty_like(L)
+    sar.sar_gat_fwd_all(b, ones, s, [torch.zeros((z.shape[0], H), device="cuda") for z in Zs], None, w.slope, o1, L1)
+    assert torch.all((o1[deg > 0].float() - 1).abs() < (1e-5 if dt == torch.float32 else 1e-2))
+    assert rel_err(f64(L1[deg > 0]), np.log(f64(deg[deg > 0]))[:, None] + f64(s[deg > 0]).clip(min=0)
+                   + 0.2 * f64(s[deg > 0]).clip(max=0)) < 1e-4
+    # dW / dX of the worker's own rows against an fp64 product of the same operands
+    dW = torch.zeros_like(W)
+    dX = gu.linear_bwd(Xp, g.dZdst, W, dW)
+    assert rel_err(f64(dW), (d64(Xp).T @ d64(g.dZdst).reshape(n, F)).cpu().numpy()) < 1e-4
+    assert rel_err(f64(dX), (d64(g.dZdst).reshape(n, F) @ d64(W).T).cpu().numpy()) < tol
+    b.close()
+
+
+def test_cfg3_full_size_sampled():
+    """GAT 4 x 64 fp32, 306k destinations, 15.2M in-edges over 8 blocks (the bench workload)."""
+    check_gat("cfg3", 150, 24)
+
+
+def test_cfg5_full_size_sampled():
+    """Dense Erdos-Renyi GAT 8 x 32 fp32: 50k destinations x ~500 in-edges over 4 blocks."""
+    check_gat("cfg5", 40, 6)
+
+
+def test_cfg2_full_size_sampled():
+    """GraphSage mean aggregation, F = 256 fp32, 15.2M in-edges over 8 blocks."""
+    w = synth.make_workload("cfg2", device="cuda")
+    P, p, F = w.P, w.p, w.H * w.D
+    b = sar.sar_blocks_build(w.src, w.dst, w.part, P, p)
+    Zs = [synth.normal_rows(2, w.members(q), F) for q in range(P)]
+    got_all = gu.spmm_all(b, Zs, True)
+    got_stream = gu.spmm_stream(b, Zs, True)
+    smp = Sample(w, 300, 0, seed=6)
+    cZs = [f64(synth.normal_rows(2, m, F)) for m in smp.c_members]
+    want = orc.spmm(smp.blocks, cZs, True)
+    D_full = smp.rows_in_full(w, p, smp.D)
+    D_comp = smp.rows_in_compact(w, p, smp.D).cpu().numpy()
+    assert rel_err(f64(got_all[D_full]), want[D_comp]) < 1e-4
+    assert rel_err(f64(got_stream[D_full]), want[D_comp]) < 1e-4
+    # all-ones features under sum aggregation give the in-degree, exactly, for every row
+    ones = [torch.ones((z.shape[0], 8), device="cuda") for z in Zs]
+    deg = sar.sar_blocks_degree(b)
+    assert torch.equal(gu.spmm_all(b, ones, False), deg.to(torch.float32)[:, None].expand(-1, 8))
+    assert int(deg.sum()) == w.src.numel()
+    b.close()
