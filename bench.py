@@ -156,6 +156,37 @@ class Layer:
         return fwd, bwd
 
 
+def measure_ceilings(torch, sar, row_bytes):
+    """Ceilings of this machine, measured in this run with the library's probe kernels:
+    streaming read, copy, and uniform-random whole-row gathers over a 2 GiB table."""
+    n_rows = (2 << 30) // row_bytes
+    table = torch.zeros((n_rows, row_bytes // 4), dtype=torch.float32, device="cuda")
+    g = torch.Generator(device="cuda").manual_seed(7)
+    idx = torch.randint(0, n_rows, (16 << 20,), generator=g, device="cuda", dtype=torch.int32)
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    dst = torch.empty((1 << 30) // 4, dtype=torch.float32, device="cuda")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(fn, reps=3):
+        fn()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e-3
+
+    t_read = timed(lambda: sar.sar_probe_stream_read(table, 2, sink))
+    t_gather = timed(lambda: sar.sar_probe_row_gather(table, idx, sink))
+    t_copy = timed(lambda: sar.sar_probe_copy(table[: dst.numel() // table.shape[1]], dst))
+    return {"stream_read_GBs": 2 * (2 << 30) / t_read / 1e9,
+            "random_row_gather_GBs": idx.numel() * row_bytes / t_gather / 1e9,
+            "copy_read_plus_write_GBs": 2 * (1 << 30) / t_copy / 1e9,
+            "note": "probe kernels of the library, timed with HIP events in this run; %d-byte rows, "
+                    "uniform-random over a 2 GiB table" % row_bytes}
+
+
 def cpu_baseline(layer, n_blocks):
     """The oracle, as it stands, on the first n_blocks blocks of the same workload."""
     import numpy as np
@@ -264,6 +295,7 @@ def main():
     avg = lambda a, b: sum(e[a].elapsed_time(e[b]) for e in evs) / len(evs)
     fwd_ms, bwd_ms, all_ms = avg("fwd0", "fwd1"), avg("bwd0", "bwd1"), avg("t0", "t1")
 
+    ceilings = measure_ceilings(torch, sar, layer.F * (2 if w.dtype == torch.bfloat16 else 4))
     fwd_b, bwd_b = layer.alg_bytes()
     if bwd_ms >= fwd_ms:
         dom, dom_b, dom_ms = "gat_bwd", bwd_b, bwd_ms
@@ -293,8 +325,13 @@ def main():
                      "traffic": None,
                      "alg_bytes_per_launch": dom_b, "avg_launch_ms": dom_ms,
                      "gather_volume_GBs": layer.E * layer.F * fb / (dom_ms * 1e-3) / 1e9,
-                     "fwd": {"alg_bytes": fwd_b, "ms": fwd_ms, "GBs": fwd_b / (fwd_ms * 1e-3) / 1e9},
-                     "bwd": {"alg_bytes": bwd_b, "ms": bwd_ms, "GBs": bwd_b / (bwd_ms * 1e-3) / 1e9}},
+                     "gather_volume_vs_measured_gather_ceiling":
+                         layer.E * layer.F * fb / (dom_ms * 1e-3) / 1e9 / ceilings["random_row_gather_GBs"],
+                     "fwd": {"alg_bytes": fwd_b, "ms": fwd_ms, "GBs": fwd_b / (fwd_ms * 1e-3) / 1e9,
+                             "gather_volume_GBs": layer.E * layer.F * fb / (fwd_ms * 1e-3) / 1e9},
+                     "bwd": {"alg_bytes": bwd_b, "ms": bwd_ms, "GBs": bwd_b / (bwd_ms * 1e-3) / 1e9,
+                             "gather_volume_GBs": layer.E * layer.F * fb / (bwd_ms * 1e-3) / 1e9}},
+        "ceilings": ceilings,
     }
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(layer, args.cpu_blocks)

@@ -277,6 +277,25 @@ int sar_linear_bwd(const void* X, const void* dZ, const float* W, float* dW, voi
 
 int sar_linear_workspace_bytes(int64_t n, int K, int F, size_t* bytes);
 
+/* ------------------------------------------------------- bandwidth probes
+ * Not part of the method: plain kernels that measure the ceilings the gather
+ * kernels are held against on the machine at hand (the paper reports its own
+ * kernels only relative to DGL, Sec. 4.1; these give the absolute yardstick).
+ * The caller times them with events on `stream`.  sink: device float[1]. */
+
+/* Reads `bytes` at buf `reps` times with 16-byte lane accesses, grid-stride. */
+int sar_probe_stream_read(const void* buf, size_t bytes, int reps, float* sink, void* stream);
+
+/* dst[0..bytes) = src[0..bytes). */
+int sar_probe_copy(const void* src, void* dst, size_t bytes, void* stream);
+
+/* For every k < n_idx (in groups of 8 per wavefront) reads the whole row
+ * rows[idx[k]] of row_bytes (1024 or 512) bytes; idx values must be in
+ * [0, n_rows).  The access shape of the aggregation kernels without their
+ * arithmetic. */
+int sar_probe_row_gather(const void* rows, int64_t n_rows, int row_bytes, const int32_t* idx,
+                         int64_t n_idx, float* sink, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsar_mi355x.so")
-SOURCES = ["builder.hip", "spmm.hip", "gat.hip", "linear.hip"]
+SOURCES = ["builder.hip", "spmm.hip", "gat.hip", "linear.hip", "probe.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics",

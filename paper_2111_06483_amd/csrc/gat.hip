@@ -294,6 +294,7 @@ struct BwdArgs {
 struct BwdScalars {
     const uint32_t* rows;       // source work list; tagged with the block when ALL
     int64_t n_rows, n_long;
+    int64_t n_wide;             // list entries [n_wide, n_rows) have fewer than 8 edges
     const void* G;              // [n_dst,H,D]
     const float4* rec;          // [n_dst,H]: (s*log2e, L*log2e, delta, unused)
     const float* a_l;           // [H,D]
@@ -763,20 +764,34 @@ template <typename T, int LPH, bool ALL>
 int launch_bwd_f256(const BwdArgs& tabs, const BwdScalars& a, unsigned* grid_out, hipStream_t st)
 {
     constexpr int B = LPH >= 8 ? 8 : 4;
-    auto fn = f256::k_gat_bwd_f256<T, LPH, B, ALL>;
-    static const int resident = resident_workgroups(fn);
+    auto wide = f256::k_gat_bwd_f256<T, LPH, B, ALL>;
+    auto narrow = f256::k_gat_bwd_narrow<T, LPH / 4, ALL>;
+    static const int resident_wide = resident_workgroups(wide);
+    static const int resident_narrow = resident_workgroups(narrow);
     f256::BwdTabs t{};
     for (int q = 0; q < SAR_MAX_BLOCKS; ++q) {
         t.t_indptr[q] = tabs.t_indptr[q]; t.t_indices[q] = tabs.t_indices[q];
         t.Z[q] = tabs.Z[q]; t.t[q] = tabs.t[q]; t.dZ[q] = tabs.dZ[q]; t.dt[q] = tabs.dt[q];
     }
     f256::BwdP p{};
-    p.rows = a.rows; p.n_rows = a.n_rows; p.n_long = a.n_long;
+    p.rows = a.rows; p.n_rows = a.n_wide; p.n_long = std::min(a.n_long, a.n_wide);
     p.G = a.G; p.rec = a.rec; p.a_l = a.a_l; p.ds = a.ds; p.partial = a.partial;
     p.H = a.H; p.tag_shift = a.tag_shift; p.slope = a.slope;
-    *grid_out = persistent_grid_for(a.n_rows, a.n_long, resident);
-    fn<<<*grid_out, kGatherThreads, 0, st>>>(t, p);
-    SAR_LAUNCH_CHECK();
+    unsigned g_wide = 0, g_narrow = 0;
+    if (a.n_wide > 0) {
+        // sources with at least 8 edges: one wavefront (or workgroup) each
+        g_wide = persistent_grid_for(p.n_rows, p.n_long, resident_wide);
+        wide<<<g_wide, kGatherThreads, 0, st>>>(t, p);
+        SAR_LAUNCH_CHECK();
+    }
+    if (a.n_rows > a.n_wide) {
+        // the rest, four per wavefront
+        const int64_t n = a.n_rows - a.n_wide;
+        g_narrow = (unsigned)std::max<int64_t>(1, std::min<int64_t>((n + 15) / 16, resident_narrow));
+        narrow<<<g_narrow, kGatherThreads, 0, st>>>(t, p, a.n_wide, a.n_rows, (int)g_wide);
+        SAR_LAUNCH_CHECK();
+    }
+    *grid_out = g_wide + g_narrow;
     return SAR_OK;
 }
 
@@ -801,7 +816,7 @@ int launch_bwd(const BwdArgs& tabs, BwdScalars& a, float* da_l, hipStream_t st)
     return SAR_OK;
 }
 
-size_t workspace_bytes(int F) { return (size_t)kMaxPersistentWGs * F * sizeof(float); }
+size_t workspace_bytes(int F) { return (size_t)2 * kMaxPersistentWGs * F * sizeof(float); }
 
 }  // namespace
 
@@ -1008,6 +1023,7 @@ extern "C" int sar_gat_bwd_block(const sar_blocks_t* b, int q, const void* Zq, c
     a.rows = reinterpret_cast<const uint32_t*>(k.t_rows);
     a.n_rows = k.n_src;    // sources without edges come last and get dZ = 0, dt = 0
     a.n_long = k.n_t_long;
+    a.n_wide = k.n_t_wide;
     a.G = G;
     a.rec = reinterpret_cast<const float4*>(rec);
     a.a_l = a_l;
@@ -1047,6 +1063,7 @@ extern "C" int sar_gat_bwd_all(const sar_blocks_t* b, const void* const* Zq, con
     a.rows = b->ft_rows;
     a.n_rows = 0;
     for (int q = 0; q < b->P; ++q) a.n_rows += b->blk[q].n_src;
+    a.n_wide = b->n_ft_wide;
     a.n_long = b->n_ft_long;
     a.G = G;
     a.rec = reinterpret_cast<const float4*>(rec);

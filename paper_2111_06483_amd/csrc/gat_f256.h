@@ -48,12 +48,12 @@ struct OpMax {
     static __device__ inline float f(float a, float b) { return fmaxf(a, b); }
 };
 
-// All-reduce over each group of LPH consecutive lanes (LPH = 4..64, power of two).
+// All-reduce over each group of LPH consecutive lanes (LPH = 1..64, power of two).
 template <int LPH, typename Op>
 __device__ inline float group_all(float v)
 {
-    v = Op::f(v, dpp<kQuadXor1>(v));
-    v = Op::f(v, dpp<kQuadXor2>(v));
+    if constexpr (LPH >= 2) v = Op::f(v, dpp<kQuadXor1>(v));
+    if constexpr (LPH >= 4) v = Op::f(v, dpp<kQuadXor2>(v));
     if constexpr (LPH == 8) v = Op::f(v, dpp<kRowHalfMirror>(v));
     if constexpr (LPH >= 16) {
         v = Op::f(v, dpp<kRowRor4>(v));
@@ -477,6 +477,204 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_f256(BwdTabs tabs, B
             v[x] = s;
         }
         store_f32<4>(a.partial + (int64_t)blockIdx.x * kF + lane * 4, v);
+    }
+}
+
+// ------------------------------------------- backward, rows of few edges
+//
+// A source with a handful of edges keeps a whole wavefront waiting on a chain
+// of dependent loads (list entry -> offsets -> indices -> G rows) while moving
+// little data; with ~2 edges per source (the papers100M-sized share) the wide
+// kernel is bound by that latency, not by bandwidth.  Here a wavefront works on
+// FOUR sources at once: 16 lanes per source, 16 consecutive features per lane,
+// every lane group walking its own edge list.  Heads are LPH16 = D/16 lanes
+// wide, so the per-edge scalars are recomputed by only D/16 lanes.
+
+template <typename T>
+struct Row16;
+template <>
+struct Row16<float> {
+    struct Raw { float4 a, b, c, d; };
+    static __device__ inline Raw load(const float* p)
+    {
+        const float4* q = reinterpret_cast<const float4*>(p);
+        return Raw{q[0], q[1], q[2], q[3]};
+    }
+    static __device__ inline void unpack(const Raw& r, float (&v)[16])
+    {
+        v[0] = r.a.x; v[1] = r.a.y; v[2] = r.a.z; v[3] = r.a.w;
+        v[4] = r.b.x; v[5] = r.b.y; v[6] = r.b.z; v[7] = r.b.w;
+        v[8] = r.c.x; v[9] = r.c.y; v[10] = r.c.z; v[11] = r.c.w;
+        v[12] = r.d.x; v[13] = r.d.y; v[14] = r.d.z; v[15] = r.d.w;
+    }
+    static __device__ inline void store(float* p, const float (&v)[16])
+    {
+        float4* q = reinterpret_cast<float4*>(p);
+        q[0] = make_float4(v[0], v[1], v[2], v[3]);
+        q[1] = make_float4(v[4], v[5], v[6], v[7]);
+        q[2] = make_float4(v[8], v[9], v[10], v[11]);
+        q[3] = make_float4(v[12], v[13], v[14], v[15]);
+    }
+};
+template <>
+struct Row16<bf16_t> {
+    struct Raw { uint4 a, b; };
+    static __device__ inline Raw load(const bf16_t* p)
+    {
+        const uint4* q = reinterpret_cast<const uint4*>(p);
+        return Raw{q[0], q[1]};
+    }
+    static __device__ inline void unpack(const Raw& r, float (&v)[16])
+    {
+        const uint32_t w[8] = {r.a.x, r.a.y, r.a.z, r.a.w, r.b.x, r.b.y, r.b.z, r.b.w};
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            v[2 * k] = __uint_as_float(w[k] << 16);
+            v[2 * k + 1] = __uint_as_float(w[k] & 0xffff0000u);
+        }
+    }
+    static __device__ inline void store(bf16_t* p, const float (&v)[16])
+    {
+        uint32_t w[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) w[k] = f32_to_bf16_rne(v[2 * k]) | (f32_to_bf16_rne(v[2 * k + 1]) << 16);
+        uint4* q = reinterpret_cast<uint4*>(p);
+        q[0] = make_uint4(w[0], w[1], w[2], w[3]);
+        q[1] = make_uint4(w[4], w[5], w[6], w[7]);
+    }
+};
+
+// List entries [r_begin, r_end) of a.rows; partial sums of da_l go to
+// a.partial[(partial_row0 + blockIdx.x) * 256 ...].
+template <typename T, int LPH16, bool ALL>
+__global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_narrow(BwdTabs tabs, BwdP a, int64_t r_begin,
+                                                                   int64_t r_end, int partial_row0)
+{
+    constexpr int kSlots = 4;
+    __shared__ float s_al[kF];
+    __shared__ float s_part[kWavesPerWG * kSlots][kF];
+    __shared__ const void* s_Z[SAR_MAX_BLOCKS];
+    __shared__ const float* s_t[SAR_MAX_BLOCKS];
+    __shared__ void* s_dZ[SAR_MAX_BLOCKS];
+    __shared__ float* s_dt[SAR_MAX_BLOCKS];
+    __shared__ const int32_t* s_ip[SAR_MAX_BLOCKS];
+    __shared__ const int32_t* s_ix[SAR_MAX_BLOCKS];
+    for (int f = threadIdx.x; f < kF; f += kGatherThreads) s_al[f] = a.a_l[f];
+    if (threadIdx.x < SAR_MAX_BLOCKS) {
+        s_Z[threadIdx.x] = tabs.Z[threadIdx.x];
+        s_t[threadIdx.x] = tabs.t[threadIdx.x];
+        s_dZ[threadIdx.x] = tabs.dZ[threadIdx.x];
+        s_dt[threadIdx.x] = tabs.dt[threadIdx.x];
+        s_ip[threadIdx.x] = tabs.t_indptr[threadIdx.x];
+        s_ix[threadIdx.x] = tabs.t_indices[threadIdx.x];
+    }
+    __syncthreads();
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    const int slot = lane >> 4, k = lane & 15;
+    const int h = k / LPH16;
+    const bool head_lead = (k % LPH16) == 0;
+    const uint32_t mask = ALL ? ((1u << a.tag_shift) - 1u) : 0xffffffffu;
+    const T* Gp = static_cast<const T*>(a.G);
+    const int64_t n_slots = (int64_t)gridDim.x * kWavesPerWG * kSlots;
+
+    float dal[16];
+#pragma unroll
+    for (int x = 0; x < 16; ++x) dal[x] = 0.f;
+
+    // Software pipeline over this lane group's rows: the list entry is read two rows
+    // ahead and the row's offsets and own features one row ahead, so that only
+    // "indices -> G rows" remains as a dependent chain per row.
+    struct Meta {
+        int q;
+        int64_t j;
+        int beg, end;
+        typename Row16<T>::Raw z;
+    };
+    auto fetch_meta = [&](uint32_t id) {
+        Meta m;
+        m.q = ALL ? (int)(id >> a.tag_shift) : 0;
+        m.j = (int64_t)(id & mask);
+        m.beg = s_ip[m.q][m.j];
+        m.end = s_ip[m.q][m.j + 1];
+        m.z = Row16<T>::load(static_cast<const T*>(s_Z[m.q]) + m.j * kF + k * 16);
+        return m;
+    };
+    const int64_t r0 = r_begin + ((int64_t)blockIdx.x * kWavesPerWG + wave) * kSlots + slot;
+    uint32_t id_next = r0 < r_end ? a.rows[r0] : 0u;
+    uint32_t id_next2 = r0 + n_slots < r_end ? a.rows[r0 + n_slots] : 0u;
+    Meta next{};
+    if (r0 < r_end) next = fetch_meta(id_next);
+    for (int64_t r = r0; r < r_end; r += n_slots) {
+        const Meta cur = next;
+        id_next = id_next2;
+        if (r + 2 * n_slots < r_end) id_next2 = a.rows[r + 2 * n_slots];
+        if (r + n_slots < r_end) next = fetch_meta(id_next);
+        const int q = cur.q;
+        const int64_t j = cur.j;
+        float zj[16];
+        Row16<T>::unpack(cur.z, zj);
+        float t2;
+        if (s_t[q]) {
+            t2 = s_t[q][j * a.H + h] * kLog2e;
+        } else {
+            float c = 0.f;
+#pragma unroll
+            for (int x = 0; x < 16; ++x) c = fmaf(s_al[k * 16 + x], zj[x], c);
+            t2 = group_all<LPH16, OpSum>(c) * kLog2e;
+        }
+        const int32_t* idx = s_ix[q];
+        const int beg = cur.beg, end = cur.end;
+        float dz[16], dt = 0.f;
+#pragma unroll
+        for (int x = 0; x < 16; ++x) dz[x] = 0.f;
+        for (int e = beg; e < end; e += 2) {
+            const bool two = e + 1 < end;
+            const int64_t i0 = idx[e], i1 = idx[two ? e + 1 : e];
+            const typename Row16<T>::Raw r0 = Row16<T>::load(Gp + i0 * kF + k * 16);
+            const typename Row16<T>::Raw r1 = Row16<T>::load(Gp + i1 * kF + k * 16);
+            const float4 rec0 = a.rec[i0 * a.H + h], rec1 = a.rec[i1 * a.H + h];
+            float g0[16], g1[16];
+            Row16<T>::unpack(r0, g0);
+            Row16<T>::unpack(r1, g1);
+            float c0 = 0.f, c1 = 0.f;
+#pragma unroll
+            for (int x = 0; x < 16; ++x) {
+                c0 = fmaf(g0[x], zj[x], c0);
+                c1 = fmaf(g1[x], zj[x], c1);
+            }
+            c0 = group_all<LPH16, OpSum>(c0);
+            c1 = group_all<LPH16, OpSum>(c1);
+            const float u0 = rec0.x + t2, u1 = rec1.x + t2;
+            const float al0 = fast_exp2(leaky2(u0, a.slope) - rec0.y);
+            const float al1 = two ? fast_exp2(leaky2(u1, a.slope) - rec1.y) : 0.f;
+            const float de0 = al0 * (c0 - rec0.z), de1 = al1 * (c1 - rec1.z);
+            const float du0 = u0 > 0.f ? de0 : a.slope * de0, du1 = u1 > 0.f ? de1 : a.slope * de1;
+#pragma unroll
+            for (int x = 0; x < 16; ++x) dz[x] = fmaf(al0, g0[x], fmaf(al1, g1[x], dz[x]));
+            dt += du0 + du1;
+            if (head_lead) {
+                unsafeAtomicAdd(a.ds + i0 * a.H + h, du0);
+                if (two) unsafeAtomicAdd(a.ds + i1 * a.H + h, du1);
+            }
+        }
+        float v[16];
+#pragma unroll
+        for (int x = 0; x < 16; ++x) {
+            v[x] = fmaf(dt, s_al[k * 16 + x], dz[x]);
+            dal[x] = fmaf(dt, zj[x], dal[x]);
+        }
+        Row16<T>::store(static_cast<T*>(s_dZ[q]) + j * kF + k * 16, v);
+        if (head_lead) s_dt[q][j * a.H + h] = dt;
+    }
+
+    // this workgroup's share of da_l
+#pragma unroll
+    for (int x = 0; x < 16; ++x) s_part[wave * kSlots + slot][k * 16 + x] = dal[x];
+    __syncthreads();
+    for (int f = threadIdx.x; f < kF; f += kGatherThreads) {
+        float s = 0.f;
+        for (int w = 0; w < kWavesPerWG * kSlots; ++w) s += s_part[w][f];
+        a.partial[((int64_t)partial_row0 + blockIdx.x) * kF + f] = s;
     }
 }
 

@@ -41,6 +41,9 @@ void clear_error();
 constexpr int kLongRow = 512;
 constexpr int kLongClass = 10;  // 1 + log2(kLongRow)
 constexpr int kNumClasses = 32;
+// Rows of fewer than 8 edges (degree classes 1..3, and the empty class 0) are
+// "narrow": the backward kernels process four of them per wavefront.
+constexpr int kNarrowMaxClass = 3;
 
 struct Block {
     int64_t n_dst = 0, n_src = 0, nnz = 0;
@@ -51,7 +54,7 @@ struct Block {
     int32_t* rows = nullptr;
     int64_t n_rows = 0, n_long = 0;
     int32_t* t_rows = nullptr;
-    int64_t n_t_rows = 0, n_t_long = 0;
+    int64_t n_t_rows = 0, n_t_long = 0, n_t_wide = 0;   // n_t_wide: sources with >= 8 edges
     int32_t* touched = nullptr;
 };
 
@@ -75,6 +78,6 @@ struct sar_blocks {
     // All-blocks source-side work list: (q << tag_shift) | local source id of
     // every source with an edge, longest class first.
     uint32_t* ft_rows = nullptr;
-    int64_t n_ft_rows = 0, n_ft_long = 0;
+    int64_t n_ft_rows = 0, n_ft_long = 0, n_ft_wide = 0;
     std::vector<void*> owned;      // device allocations freed with the handle
 };

@@ -74,6 +74,7 @@ EXPORTS = [
     "sar_gat_scores", "sar_gat_fwd_begin", "sar_gat_fwd_block", "sar_gat_fwd_end", "sar_gat_fwd_all",
     "sar_gat_workspace_bytes", "sar_gat_bwd_begin", "sar_gat_bwd_block", "sar_gat_bwd_all", "sar_gat_bwd_end",
     "sar_linear_fwd", "sar_linear_bwd", "sar_linear_workspace_bytes",
+    "sar_probe_stream_read", "sar_probe_copy", "sar_probe_row_gather",
 ]
 
 
@@ -364,3 +365,21 @@ def sar_linear_bwd(X: Optional[torch.Tensor], dZ: torch.Tensor, W: Optional[torc
     wb = 0 if work is None else work.numel() * work.element_size()
     _check(lib().sar_linear_bwd(_ptr(X), _ptr(dZ), _ptr(W), _ptr(dW), _ptr(dX), _c_int(dtype_code(dZ.dtype)),
                                 _c_i64(n), _c_int(K), _c_int(F), _ptr(work), ctypes.c_size_t(wb), _stream()))
+
+
+# ------------------------------------------------------------------ probes
+
+def sar_probe_stream_read(buf: torch.Tensor, reps: int, sink: torch.Tensor) -> None:
+    _check(lib().sar_probe_stream_read(_ptr(buf), ctypes.c_size_t(buf.numel() * buf.element_size()), _c_int(reps),
+                                       _ptr(sink), _stream()))
+
+
+def sar_probe_copy(src: torch.Tensor, dst: torch.Tensor) -> None:
+    assert src.numel() * src.element_size() == dst.numel() * dst.element_size()
+    _check(lib().sar_probe_copy(_ptr(src), _ptr(dst), ctypes.c_size_t(src.numel() * src.element_size()), _stream()))
+
+
+def sar_probe_row_gather(rows: torch.Tensor, idx: torch.Tensor, sink: torch.Tensor) -> None:
+    assert idx.dtype == torch.int32 and rows.dim() == 2
+    _check(lib().sar_probe_row_gather(_ptr(rows), _c_i64(rows.shape[0]), _c_int(rows.shape[1] * rows.element_size()),
+                                      _ptr(idx), _c_i64(idx.numel()), _ptr(sink), _stream()))
