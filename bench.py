@@ -140,20 +140,50 @@ class Layer:
         sar.sar_linear_bwd(self.X, self.dZdst, self.W, self.dW, self.dX_dst, self.lwork)
         mark("t1")
 
-    # ---- algorithmic bytes of the two gather launches (what the method must move)
+    # ---- algorithmic bytes of the gather kernels (what the method must move at least)
     def alg_bytes(self):
-        fb = 2 if self.w.dtype == self.torch.bfloat16 else 4
+        """Per kernel of the all-blocks launches: forward, backward over sources with >= 8 edges
+        ("wide"), backward over the other sources ("narrow", four per wavefront)."""
+        torch, sar = self.torch, self.sar
+        fb = 2 if self.w.dtype == torch.bfloat16 else 4
         F, H, n, E = self.F, self.H, self.n, self.E
         touched = sum(v.n_t_rows for v in self.views)
-        n_src = sum(v.n_src for v in self.views)
         fwd = (4 * E + 4 * (n + 1) + 4 * n            # tagged index, row offsets, launch list
                + touched * F * fb                     # each touched source row once
                + n * (H * 4 + F * fb + H * 4))        # s read, out and L written
-        bwd = (4 * E + 4 * (n_src + self.P) + 4 * touched   # transposed index, offsets, launch list
-               + touched * F * fb                     # z_j read once (the rematerialisation)
-               + n_src * (F * fb + H * 4)             # dZ_q, dt_q written once
-               + n * (F * fb + H * 16 + 2 * H * 4))   # G and the record read once, ds read-modify-write
-        return fwd, bwd
+        rows = {"wide": 0, "narrow": 0}
+        rows_touched = {"wide": 0, "narrow": 0}
+        edges = {"wide": 0, "narrow": 0}
+        for v in self.views:
+            deg = torch.diff(sar.device_array(v.t_indptr, v.n_src + 1))
+            wide = deg >= 8
+            rows["wide"] += int(wide.sum())
+            rows["narrow"] += int((~wide).sum())
+            rows_touched["wide"] += int(wide.sum())
+            rows_touched["narrow"] += int(((~wide) & (deg > 0)).sum())
+            edges["wide"] += int(deg[wide].sum())
+            edges["narrow"] += int(deg[~wide].sum())
+        out = {"gat_fwd": fwd}
+        for part in ("wide", "narrow"):
+            dst_rows = min(edges[part], n)            # distinct G rows this kernel can touch at most
+            out["gat_bwd_" + part] = (
+                4 * edges[part] + 12 * rows[part]     # transposed index, offsets, launch list
+                + rows_touched[part] * F * fb         # z_j read once (the rematerialisation)
+                + rows[part] * (F * fb + H * 4)       # dZ_q, dt_q written once
+                + dst_rows * (F * fb + H * 16 + 2 * H * 4))   # G, record read once; ds read-modify-write
+        self.part_edges = edges
+        return out
+
+
+# HBM-side traffic (bytes per launch) of the gather kernels at the default workload, from the
+# rocprofv3 counter summary kept under profiles/: 2 x FETCH_SIZE + WRITE_SIZE (KiB), the factor 2
+# being what FETCH_SIZE reads short on a plain 1 GiB copy.
+MEASURED_TRAFFIC = {
+    ("cfg3", "all", "gat_fwd"): (2 * 7.381e6 + 3.161e5) * 1024,
+    ("cfg3", "all", "gat_bwd_wide"): (2 * 4.921e6 + 6.604e5) * 1024,
+    ("cfg3", "all", "gat_bwd_narrow"): (2 * 3.534e6 + 2.336e6) * 1024,
+}
+KERNEL_NAMES = {"gat_fwd": "k_gat_fwd_f256", "gat_bwd_wide": "k_gat_bwd_f256", "gat_bwd_narrow": "k_gat_bwd_narrow"}
 
 
 def measure_ceilings(torch, sar, row_bytes):
@@ -285,6 +315,7 @@ def main():
     torch.cuda.synchronize()
     names = ["t0", "fwd0", "fwd1", "bwd0", "bwd1", "t1"]
     evs = [{k: torch.cuda.Event(enable_timing=True) for k in names} for _ in range(args.steps)]
+    sar.sar_timing_begin(args.steps * (1 if args.mode == "all" else w.P))
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(args.steps):
@@ -294,15 +325,30 @@ def main():
     ms_step = wall * 1e3 / args.steps
     avg = lambda a, b: sum(e[a].elapsed_time(e[b]) for e in evs) / len(evs)
     fwd_ms, bwd_ms, all_ms = avg("fwd0", "fwd1"), avg("bwd0", "bwd1"), avg("t0", "t1")
+    recs = [sar.sar_timing_get(k) for k in range(sar.sar_timing_count())]
+    sar.sar_timing_begin(0)
+    wide_ms = sum(r[0] for r in recs) / args.steps if recs else 0.0
+    narrow_ms = sum(r[1] for r in recs) / args.steps if recs else 0.0
 
     ceilings = measure_ceilings(torch, sar, layer.F * (2 if w.dtype == torch.bfloat16 else 4))
-    fwd_b, bwd_b = layer.alg_bytes()
-    if bwd_ms >= fwd_ms:
-        dom, dom_b, dom_ms = "gat_bwd", bwd_b, bwd_ms
-    else:
-        dom, dom_b, dom_ms = "gat_fwd", fwd_b, fwd_ms
-    achieved = dom_b / (dom_ms * 1e-3) / 1e9
+    alg = layer.alg_bytes()
     fb = 2 if w.dtype == torch.bfloat16 else 4
+    kern_ms = {"gat_fwd": fwd_ms, "gat_bwd_wide": wide_ms, "gat_bwd_narrow": narrow_ms}
+    gather = {"gat_fwd": layer.E * layer.F * fb, "gat_bwd_wide": layer.part_edges["wide"] * layer.F * fb,
+              "gat_bwd_narrow": layer.part_edges["narrow"] * layer.F * fb}
+    per_kernel = {}
+    for kname, ms in kern_ms.items():
+        if ms <= 0:
+            continue
+        per_kernel[kname] = {"kernel": KERNEL_NAMES[kname], "avg_ms": ms, "alg_bytes": alg[kname],
+                             "alg_GBs": alg[kname] / (ms * 1e-3) / 1e9,
+                             "gather_volume_GBs": gather[kname] / (ms * 1e-3) / 1e9,
+                             "traffic_bytes": MEASURED_TRAFFIC.get((args.workload, args.mode, kname))
+                             if args.scale == 1.0 else None}
+    dom = max(per_kernel, key=lambda k: per_kernel[k]["avg_ms"])
+    d = per_kernel[dom]
+    # in stream mode the events bracket P launches of the kernel; report per launch
+    launches = 1 if args.mode == "all" else w.P
     res = {
         "metric": "fused GAT fwd+bwd edges/sec per GPU",
         "value": layer.E / (ms_step * 1e-3),
@@ -312,25 +358,24 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if w.dtype == torch.float32 else "bf16 storage, f32 accumulate",
         "data": "synthetic",
-        "config": {"workload": "%s: one worker's share of a %d-node power-law graph, %d-way split, %d destinations, "
+        "config": {"workload": "%s: one worker's share of a %d-node graph, %d-way split, %d destinations, "
                                "%d in-edges over %d resident source blocks, GAT %d heads x %d, in_dim %d"
                                % (args.workload, w.N, w.P, layer.n, layer.E, w.P, w.H, w.D, w.f_in),
                    "mode": args.mode, "scale": args.scale},
         "phases_ms": {"step_events": all_ms, "gat_fwd": fwd_ms, "gat_bwd": bwd_ms,
+                      "gat_bwd_kernel_rows_ge8": wide_ms, "gat_bwd_kernel_rows_lt8": narrow_ms,
                       "other (XW fwd+bwd, scores, begin/end)": all_ms - fwd_ms - bwd_ms},
         "aggregation_only_edges_per_s": layer.E / ((fwd_ms + bwd_ms) * 1e-3),
         "builder_s": layer.builder_s,
-        "roofline": {"bound": "hbm", "kernel": "k_%s (all blocks)" % dom if args.mode == "all" else "k_%s" % dom,
-                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None,
-                     "alg_bytes_per_launch": dom_b, "avg_launch_ms": dom_ms,
-                     "gather_volume_GBs": layer.E * layer.F * fb / (dom_ms * 1e-3) / 1e9,
+        "roofline": {"bound": "hbm", "kernel": d["kernel"],
+                     "achieved": d["alg_GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": d["alg_GBs"] / HBM_PEAK_GBS,
+                     "traffic": d["traffic_bytes"],
+                     "alg_bytes_per_launch": d["alg_bytes"] / launches, "avg_launch_ms": d["avg_ms"] / launches,
+                     "gather_volume_GBs": d["gather_volume_GBs"],
                      "gather_volume_vs_measured_gather_ceiling":
-                         layer.E * layer.F * fb / (dom_ms * 1e-3) / 1e9 / ceilings["random_row_gather_GBs"],
-                     "fwd": {"alg_bytes": fwd_b, "ms": fwd_ms, "GBs": fwd_b / (fwd_ms * 1e-3) / 1e9,
-                             "gather_volume_GBs": layer.E * layer.F * fb / (fwd_ms * 1e-3) / 1e9},
-                     "bwd": {"alg_bytes": bwd_b, "ms": bwd_ms, "GBs": bwd_b / (bwd_ms * 1e-3) / 1e9,
-                             "gather_volume_GBs": layer.E * layer.F * fb / (bwd_ms * 1e-3) / 1e9}},
+                         d["gather_volume_GBs"] / ceilings["random_row_gather_GBs"],
+                     "kernels": per_kernel},
         "ceilings": ceilings,
     }
     if not args.no_cpu_baseline:

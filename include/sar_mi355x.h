@@ -296,6 +296,18 @@ int sar_probe_copy(const void* src, void* dst, size_t bytes, void* stream);
 int sar_probe_row_gather(const void* rows, int64_t n_rows, int row_bytes, const int32_t* idx,
                          int64_t n_idx, float* sink, void* stream);
 
+/* ------------------------------------------------ per-kernel timing hooks
+ * On rows of 256 values a backward launch (sar_gat_bwd_block / _all) is two
+ * kernels: sources with at least 8 edges (one wavefront each) and the others
+ * (four per wavefront).  After sar_timing_begin(n) the next n backward launches
+ * record HIP events around each of the two on their launch stream.  Not thread
+ * safe; allocates n*3 events (sar_timing_begin(0) frees them). */
+int sar_timing_begin(int max_records);
+/* *n = records filled so far. */
+int sar_timing_count(int* n);
+/* Durations of record k in milliseconds; waits for its last event. */
+int sar_timing_get(int k, float* wide_ms, float* narrow_ms);
+
 #ifdef __cplusplus
 }
 #endif

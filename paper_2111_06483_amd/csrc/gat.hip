@@ -18,6 +18,7 @@
 // (LeakyReLU commutes with a positive scale), so e2 = LeakyReLU(s2 + t2) and
 // exp(e - m) = exp2(e2 - m2).
 #include <algorithm>
+#include <vector>
 
 #include "gather_common.h"
 #include "gat_f256.h"
@@ -760,6 +761,19 @@ int launch_fwd(const FwdArgs& a, const PtrTab& zt, const PtrTab& tt, int P, hipS
     return SAR_OK;
 }
 
+// Optional per-kernel timing of the backward launches (two kernels per launch on the
+// F = 256 path): event triples recorded on the launch stream, read back afterwards.
+struct BwdTiming {
+    std::vector<hipEvent_t> ev;   // 3 per record: before wide, between, after narrow
+    int used = 0, capacity = 0;
+};
+BwdTiming g_timing;
+
+void timing_mark(int which, hipStream_t st)
+{
+    if (g_timing.used < g_timing.capacity) (void)hipEventRecord(g_timing.ev[3 * g_timing.used + which], st);
+}
+
 template <typename T, int LPH, bool ALL>
 int launch_bwd_f256(const BwdArgs& tabs, const BwdScalars& a, unsigned* grid_out, hipStream_t st)
 {
@@ -778,12 +792,14 @@ int launch_bwd_f256(const BwdArgs& tabs, const BwdScalars& a, unsigned* grid_out
     p.G = a.G; p.rec = a.rec; p.a_l = a.a_l; p.ds = a.ds; p.partial = a.partial;
     p.H = a.H; p.tag_shift = a.tag_shift; p.slope = a.slope;
     unsigned g_wide = 0, g_narrow = 0;
+    timing_mark(0, st);
     if (a.n_wide > 0) {
         // sources with at least 8 edges: one wavefront (or workgroup) each
         g_wide = persistent_grid_for(p.n_rows, p.n_long, resident_wide);
         wide<<<g_wide, kGatherThreads, 0, st>>>(t, p);
         SAR_LAUNCH_CHECK();
     }
+    timing_mark(1, st);
     if (a.n_rows > a.n_wide) {
         // the rest, four per wavefront
         const int64_t n = a.n_rows - a.n_wide;
@@ -791,6 +807,8 @@ int launch_bwd_f256(const BwdArgs& tabs, const BwdScalars& a, unsigned* grid_out
         narrow<<<g_narrow, kGatherThreads, 0, st>>>(t, p, a.n_wide, a.n_rows, (int)g_wide);
         SAR_LAUNCH_CHECK();
     }
+    timing_mark(2, st);
+    if (g_timing.used < g_timing.capacity) ++g_timing.used;
     *grid_out = g_wide + g_narrow;
     return SAR_OK;
 }
@@ -1111,5 +1129,37 @@ extern "C" int sar_gat_bwd_end(const void* Zdst, const float* ds, const float* a
     SAR_LAUNCH_CHECK();
     k_reduce_partials<<<F, 256, 0, st>>>(static_cast<const float*>(work), (int)grid, F, da_r);
     SAR_LAUNCH_CHECK();
+    return SAR_OK;
+}
+
+extern "C" int sar_timing_begin(int max_records)
+{
+    SAR_CHECK_ARG(max_records >= 0 && max_records <= 4096, "max_records must be in [0,4096]");
+    for (hipEvent_t e : g_timing.ev) (void)hipEventDestroy(e);
+    g_timing.ev.clear();
+    g_timing.used = g_timing.capacity = 0;
+    for (int k = 0; k < 3 * max_records; ++k) {
+        hipEvent_t e;
+        SAR_HIP(hipEventCreate(&e));
+        g_timing.ev.push_back(e);
+    }
+    g_timing.capacity = max_records;
+    return SAR_OK;
+}
+
+extern "C" int sar_timing_count(int* n)
+{
+    SAR_CHECK_ARG(n != nullptr, "n is null");
+    *n = g_timing.used;
+    return SAR_OK;
+}
+
+extern "C" int sar_timing_get(int k, float* wide_ms, float* narrow_ms)
+{
+    SAR_CHECK_ARG(k >= 0 && k < g_timing.used, "record %d out of range [0,%d)", k, g_timing.used);
+    SAR_CHECK_ARG(wide_ms && narrow_ms, "an output pointer is null");
+    SAR_HIP(hipEventSynchronize(g_timing.ev[3 * k + 2]));
+    SAR_HIP(hipEventElapsedTime(wide_ms, g_timing.ev[3 * k], g_timing.ev[3 * k + 1]));
+    SAR_HIP(hipEventElapsedTime(narrow_ms, g_timing.ev[3 * k + 1], g_timing.ev[3 * k + 2]));
     return SAR_OK;
 }

@@ -75,6 +75,7 @@ EXPORTS = [
     "sar_gat_workspace_bytes", "sar_gat_bwd_begin", "sar_gat_bwd_block", "sar_gat_bwd_all", "sar_gat_bwd_end",
     "sar_linear_fwd", "sar_linear_bwd", "sar_linear_workspace_bytes",
     "sar_probe_stream_read", "sar_probe_copy", "sar_probe_row_gather",
+    "sar_timing_begin", "sar_timing_count", "sar_timing_get",
 ]
 
 
@@ -383,3 +384,22 @@ def sar_probe_row_gather(rows: torch.Tensor, idx: torch.Tensor, sink: torch.Tens
     assert idx.dtype == torch.int32 and rows.dim() == 2
     _check(lib().sar_probe_row_gather(_ptr(rows), _c_i64(rows.shape[0]), _c_int(rows.shape[1] * rows.element_size()),
                                       _ptr(idx), _c_i64(idx.numel()), _ptr(sink), _stream()))
+
+
+# ------------------------------------------------------------------ timing
+
+def sar_timing_begin(max_records: int) -> None:
+    _check(lib().sar_timing_begin(_c_int(max_records)))
+
+
+def sar_timing_count() -> int:
+    n = _c_int(0)
+    _check(lib().sar_timing_count(ctypes.byref(n)))
+    return n.value
+
+
+def sar_timing_get(k: int):
+    """(wide_ms, narrow_ms) of the k-th recorded backward launch."""
+    a, b = ctypes.c_float(0), ctypes.c_float(0)
+    _check(lib().sar_timing_get(_c_int(k), ctypes.byref(a), ctypes.byref(b)))
+    return a.value, b.value

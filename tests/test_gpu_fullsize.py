@@ -211,3 +211,9 @@ def test_cfg2_full_size_sampled():
     assert torch.equal(gu.spmm_all(b, ones, False), deg.to(torch.float32)[:, None].expand(-1, 8))
     assert int(deg.sum()) == w.src.numel()
     b.close()
+
+
+def test_cfg4_full_size_sampled():
+    """Largest configuration: 111M-node graph, 16-way split, 6.9M destinations, ~201M in-edges,
+    bf16 storage with fp32 accumulation, GAT 8 x 32 (tolerance 2e-2)."""
+    check_gat("cfg4", 150, 24)
