@@ -32,9 +32,10 @@
  *     all accumulation is fp32.
  *   - a_r multiplies the destination's z_i and a_l the source's z_j: the vector
  *     a of Eq. 3 is [a_r ; a_l] in the order the equation writes z_i || z_j.
- *   - Supported shapes for the gather kernels: F*sizeof(element) <= 1024 bytes
- *     per row, D a multiple of 4 (fp32) or 8 (bf16).  Anything else returns
- *     SAR_ERR_UNSUPPORTED.
+ *   - Supported shapes: D (and, for the sum/mean calls, F) a multiple of 4 (fp32)
+ *     or 8 (bf16); one head at most 1024 bytes wide.  Rows wider than 1024 bytes
+ *     are processed as several launches over groups of heads (or column ranges).
+ *     Anything else returns SAR_ERR_UNSUPPORTED.
  *   - A destination with no in-edge at all has out = 0 and L = -inf, and
  *     contributes nothing to any gradient; the mean of an empty set is 0.
  *   - A repeated edge counts with its multiplicity (one softmax term / one

@@ -52,7 +52,8 @@ struct FwdArgs {
     float* acc;
     void* out;           // batched call: normalised output rows
     float* L;            //               and log-sum-exp [n_dst,H]
-    int H, D, F;
+    int H, D, F;         // heads, head width and row width handled by this launch
+    int ldz, ldh;        // strides between nodes of the feature rows / of the per-head arrays
     int tag_shift;
     float slope;
 };
@@ -124,8 +125,8 @@ __device__ inline void fwd_edges(SoftState<Vec<T>::N>& st, const FwdArgs& a, con
                         zb = static_cast<const T*>(a.Z);
                         tb = a.t;
                     }
-                    if (!fly) e2[k] = tb[(int64_t)j * a.H + lm.h];
-                    if (lm.on) raw[k] = Vec<T>::load(zb + (int64_t)j * a.F + lm.gl * VEC);
+                    if (!fly) e2[k] = tb[(int64_t)j * a.ldh + lm.h];
+                    if (lm.on) raw[k] = Vec<T>::load(zb + (int64_t)j * a.ldz + lm.gl * VEC);
                 }
             }
             if (fly) {   // t_j = <a_l, z_j> from the row just gathered
@@ -187,7 +188,7 @@ __device__ inline void fwd_finish_row(SoftState<Vec<T>::N>& st, const FwdArgs& a
 {
     constexpr int VEC = Vec<T>::N;
     if (lm.slot != 0 || !lm.on) return;
-    const int64_t o = (int64_t)i * a.F + lm.gl * VEC;
+    const int64_t o = (int64_t)i * a.ldz + lm.gl * VEC;
     if constexpr (ALL) {
         // the division by the normaliser (Sec. 3.2), and L = m + log l for the backward pass
         const float inv = st.l > 0.f ? 1.f / st.l : 0.f;
@@ -196,12 +197,12 @@ __device__ inline void fwd_finish_row(SoftState<Vec<T>::N>& st, const FwdArgs& a
         for (int x = 0; x < VEC; ++x) v[x] = st.acc[x] * inv;
         Vec<T>::store(static_cast<T*>(a.out) + o, v);
         if ((lm.gl % lm.lph) == 0)
-            a.L[(int64_t)i * a.H + lm.h] = st.l > 0.f ? (st.m2 + fast_log2(st.l)) * kLn2 : -INFINITY;
+            a.L[(int64_t)i * a.ldh + lm.h] = st.l > 0.f ? (st.m2 + fast_log2(st.l)) * kLn2 : -INFINITY;
     } else {
         store_f32<VEC>(a.acc + o, st.acc);
         if ((lm.gl % lm.lph) == 0) {
-            a.m[(int64_t)i * a.H + lm.h] = st.m2 * kLn2;
-            a.l[(int64_t)i * a.H + lm.h] = st.l;
+            a.m[(int64_t)i * a.ldh + lm.h] = st.m2 * kLn2;
+            a.l[(int64_t)i * a.ldh + lm.h] = st.l;
         }
     }
 }
@@ -234,16 +235,16 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_fwd(FwdArgs a, PtrTab zt
         if constexpr (!ALL) {
             // the state carried from the previous blocks enters through lane group 0
             if (lm.slot == 0) {
-                st.m2 = a.m[(int64_t)i * a.H + lm.h] * kLog2e;
-                st.l = a.l[(int64_t)i * a.H + lm.h];
-                if (lm.on) load_f32<VEC>(a.acc + (int64_t)i * a.F + lm.gl * VEC, st.acc);
+                st.m2 = a.m[(int64_t)i * a.ldh + lm.h] * kLog2e;
+                st.l = a.l[(int64_t)i * a.ldh + lm.h];
+                if (lm.on) load_f32<VEC>(a.acc + (int64_t)i * a.ldz + lm.gl * VEC, st.acc);
             }
         }
     };
 
     for (int64_t r = blockIdx.x; r < a.n_long; r += gridDim.x) {
         const int i = (int)a.rows[r];
-        const float s2 = a.s[(int64_t)i * a.H + lm.h] * kLog2e;
+        const float s2 = a.s[(int64_t)i * a.ldh + lm.h] * kLog2e;
         SoftState<VEC> st;
         if (wave == 0)
             load_state(st, i);
@@ -272,7 +273,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_fwd(FwdArgs a, PtrTab zt
     const int64_t n_waves = (int64_t)gridDim.x * kWavesPerWG;
     for (int64_t r = a.n_long + (int64_t)blockIdx.x * kWavesPerWG + wave; r < a.n_rows; r += n_waves) {
         const int i = (int)a.rows[r];
-        const float s2 = a.s[(int64_t)i * a.H + lm.h] * kLog2e;
+        const float s2 = a.s[(int64_t)i * a.ldh + lm.h] * kLog2e;
         SoftState<VEC> st;
         load_state(st, i);
         fwd_edges<T, G, ALL>(st, a, ztab, ttab, a.indptr[i], a.indptr[i + 1], 0, 1, lm, s2, al, fly, pow2);
@@ -302,6 +303,7 @@ struct BwdScalars {
     float* ds;                  // [n_dst,H], atomically accumulated
     float* partial;             // [gridDim.x][F] per-workgroup da_l partial sums
     int H, D, F;
+    int ldz, ldh;               // node strides of feature rows / per-head arrays
     int tag_shift;
     float slope;
 };
@@ -336,8 +338,8 @@ __device__ inline void bwd_edges(BwdAcc<Vec<T>::N>& ac, const BwdScalars& a, con
                 raw[k] = Vec<T>::zero();
                 rec[k] = make_float4(0.f, INFINITY, 0.f, 0.f);   // L = +inf gives alpha = 0
                 if (ek < cnt) {
-                    rec[k] = a.rec[(int64_t)i * a.H + lm.h];
-                    if (lm.on) raw[k] = Vec<T>::load(Gp + (int64_t)i * a.F + lm.gl * VEC);
+                    rec[k] = a.rec[(int64_t)i * a.ldh + lm.h];
+                    if (lm.on) raw[k] = Vec<T>::load(Gp + (int64_t)i * a.ldz + lm.gl * VEC);
                 }
             }
 #pragma unroll
@@ -356,7 +358,7 @@ __device__ inline void bwd_edges(BwdAcc<Vec<T>::N>& ac, const BwdScalars& a, con
                 for (int x = 0; x < VEC; ++x) ac.dz[x] = fmaf(alpha, g[x], ac.dz[x]);
                 ac.dt += du;
                 if (dst[k] >= 0 && lm.on && (lm.gl % lm.lph) == 0)
-                    unsafeAtomicAdd(a.ds + (int64_t)dst[k] * a.H + lm.h, du);
+                    unsafeAtomicAdd(a.ds + (int64_t)dst[k] * a.ldh + lm.h, du);
             }
         }
     }
@@ -395,10 +397,10 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd(BwdArgs tabs, BwdSca
         q = ALL ? (int)(id >> a.tag_shift) : 0;
         j = (int)(id & mask);
         typename Vec<T>::Raw r = Vec<T>::zero();
-        if (lm.on) r = Vec<T>::load(static_cast<const T*>(tabs.Z[q]) + (int64_t)j * a.F + lm.gl * VEC);
+        if (lm.on) r = Vec<T>::load(static_cast<const T*>(tabs.Z[q]) + (int64_t)j * a.ldz + lm.gl * VEC);
         Vec<T>::unpack(r, zj);
         if (tabs.t[q]) {
-            t2 = tabs.t[q][(int64_t)j * a.H + lm.h] * kLog2e;
+            t2 = tabs.t[q][(int64_t)j * a.ldh + lm.h] * kLog2e;
         } else {
             float c = 0.f;
 #pragma unroll
@@ -415,8 +417,8 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd(BwdArgs tabs, BwdSca
             v[x] = fmaf(ac.dt, al[x], ac.dz[x]);
             dal[x] = fmaf(ac.dt, zj[x], dal[x]);
         }
-        Vec<T>::store(static_cast<T*>(tabs.dZ[q]) + (int64_t)j * a.F + lm.gl * VEC, v);
-        if ((lm.gl % lm.lph) == 0) tabs.dt[q][(int64_t)j * a.H + lm.h] = ac.dt;
+        Vec<T>::store(static_cast<T*>(tabs.dZ[q]) + (int64_t)j * a.ldz + lm.gl * VEC, v);
+        if ((lm.gl % lm.lph) == 0) tabs.dt[q][(int64_t)j * a.ldh + lm.h] = ac.dt;
     };
 
     for (int64_t r = blockIdx.x; r < a.n_long; r += gridDim.x) {
@@ -499,7 +501,8 @@ __global__ __launch_bounds__(256) void k_reduce_partials(const float* __restrict
 // score[v,h] = <a[h], Z[v,h]>; one lane group per node.
 template <typename T, int G>
 __global__ __launch_bounds__(kGatherThreads) void k_scores(const T* __restrict__ Z, int64_t n, int H, int D,
-                                                           int F, const float* __restrict__ avec,
+                                                           int F, int ldz, int ldh,
+                                                           const float* __restrict__ avec,
                                                            float* __restrict__ score)
 {
     constexpr int VEC = Vec<T>::N;
@@ -514,12 +517,12 @@ __global__ __launch_bounds__(kGatherThreads) void k_scores(const T* __restrict__
     for (int64_t v0 = wave_id * SLOTS; v0 < n; v0 += n_waves * SLOTS) {
         const int64_t v = v0 + lm.slot;
         float z[VEC] = {};
-        if (v < n && lm.on) Vec<T>::unpack(Vec<T>::load(Z + v * F + lm.gl * VEC), z);
+        if (v < n && lm.on) Vec<T>::unpack(Vec<T>::load(Z + v * ldz + lm.gl * VEC), z);
         float c = 0.f;
 #pragma unroll
         for (int x = 0; x < VEC; ++x) c = fmaf(av[x], z[x], c);
         c = pow2 ? group_sum_pow2(c, lm.lph) : group_sum_any(c, lm.head_first, lm.lph);
-        if (v < n && lm.on && (lm.gl % lm.lph) == 0) score[v * H + lm.h] = c;
+        if (v < n && lm.on && (lm.gl % lm.lph) == 0) score[v * ldh + lm.h] = c;
     }
 }
 
@@ -539,7 +542,8 @@ template <typename T, int G>
 __global__ __launch_bounds__(kGatherThreads) void k_fwd_end(const float* __restrict__ m,
                                                             const float* __restrict__ l,
                                                             const float* __restrict__ acc, T* __restrict__ out,
-                                                            float* __restrict__ L, int64_t n, int H, int D, int F)
+                                                            float* __restrict__ L, int64_t n, int H, int D, int F,
+                                                            int ldz, int ldh)
 {
     constexpr int VEC = Vec<T>::N;
     constexpr int SLOTS = kWave / G;
@@ -549,14 +553,15 @@ __global__ __launch_bounds__(kGatherThreads) void k_fwd_end(const float* __restr
     for (int64_t v0 = wave_id * SLOTS; v0 < n; v0 += n_waves * SLOTS) {
         const int64_t v = v0 + lm.slot;
         if (v >= n || !lm.on) continue;
-        const float lv = l[v * H + lm.h];
+        const float lv = l[v * ldh + lm.h];
         const float inv = lv > 0.f ? 1.f / lv : 0.f;
         float a[VEC];
-        load_f32<VEC>(acc + v * F + lm.gl * VEC, a);
+        load_f32<VEC>(acc + v * ldz + lm.gl * VEC, a);
 #pragma unroll
         for (int x = 0; x < VEC; ++x) a[x] *= inv;
-        Vec<T>::store(out + v * F + lm.gl * VEC, a);
-        if ((lm.gl % lm.lph) == 0) L[v * H + lm.h] = lv > 0.f ? m[v * H + lm.h] + fast_log2(lv) * kLn2 : -INFINITY;
+        Vec<T>::store(out + v * ldz + lm.gl * VEC, a);
+        if ((lm.gl % lm.lph) == 0)
+            L[v * ldh + lm.h] = lv > 0.f ? m[v * ldh + lm.h] + fast_log2(lv) * kLn2 : -INFINITY;
     }
 }
 
@@ -565,7 +570,8 @@ template <typename T, int G>
 __global__ __launch_bounds__(kGatherThreads) void k_bwd_begin(const T* __restrict__ Gr, const T* __restrict__ out,
                                                               const float* __restrict__ s,
                                                               const float* __restrict__ L, float4* __restrict__ rec,
-                                                              float* __restrict__ ds, int64_t n, int H, int D, int F)
+                                                              float* __restrict__ ds, int64_t n, int H, int D, int F,
+                                                              int ldz, int ldh)
 {
     constexpr int VEC = Vec<T>::N;
     constexpr int SLOTS = kWave / G;
@@ -577,15 +583,15 @@ __global__ __launch_bounds__(kGatherThreads) void k_bwd_begin(const T* __restric
         const int64_t v = v0 + lm.slot;
         float g[VEC] = {}, o[VEC] = {};
         if (v < n && lm.on) {
-            Vec<T>::unpack(Vec<T>::load(Gr + v * F + lm.gl * VEC), g);
-            Vec<T>::unpack(Vec<T>::load(out + v * F + lm.gl * VEC), o);
+            Vec<T>::unpack(Vec<T>::load(Gr + v * ldz + lm.gl * VEC), g);
+            Vec<T>::unpack(Vec<T>::load(out + v * ldz + lm.gl * VEC), o);
         }
         float c = 0.f;
 #pragma unroll
         for (int x = 0; x < VEC; ++x) c = fmaf(g[x], o[x], c);
         c = pow2 ? group_sum_pow2(c, lm.lph) : group_sum_any(c, lm.head_first, lm.lph);
         if (v < n && lm.on && (lm.gl % lm.lph) == 0) {
-            const int64_t k = v * H + lm.h;
+            const int64_t k = v * ldh + lm.h;
             rec[k] = make_float4(s[k] * kLog2e, L[k] * kLog2e, c, 0.f);
             ds[k] = 0.f;
         }
@@ -598,7 +604,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_bwd_end(const T* __restrict_
                                                             const float* __restrict__ a_r, const T* dZadd,
                                                             T* dZdst,
                                                             float* __restrict__ partial, int64_t n, int H, int D,
-                                                            int F)
+                                                            int F, int ldz, int ldh)
 {
     constexpr int VEC = Vec<T>::N;
     constexpr int SLOTS = kWave / G;
@@ -616,11 +622,11 @@ __global__ __launch_bounds__(kGatherThreads) void k_bwd_end(const T* __restrict_
     for (int64_t v0 = wave_id * SLOTS; v0 < n; v0 += n_waves * SLOTS) {
         const int64_t v = v0 + lm.slot;
         if (v >= n || !lm.on) continue;
-        const float d = ds[v * H + lm.h];
+        const float d = ds[v * ldh + lm.h];
         float z[VEC], o[VEC];
-        Vec<T>::unpack(Vec<T>::load(Zdst + v * F + lm.gl * VEC), z);
+        Vec<T>::unpack(Vec<T>::load(Zdst + v * ldz + lm.gl * VEC), z);
         if (dZadd) {
-            Vec<T>::unpack(Vec<T>::load(dZadd + v * F + lm.gl * VEC), o);
+            Vec<T>::unpack(Vec<T>::load(dZadd + v * ldz + lm.gl * VEC), o);
         } else {
 #pragma unroll
             for (int x = 0; x < VEC; ++x) o[x] = 0.f;
@@ -630,7 +636,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_bwd_end(const T* __restrict_
             o[x] = fmaf(d, ar[x], o[x]);
             dar[x] = fmaf(d, z[x], dar[x]);
         }
-        Vec<T>::store(dZdst + v * F + lm.gl * VEC, o);
+        Vec<T>::store(dZdst + v * ldz + lm.gl * VEC, o);
     }
 #pragma unroll
     for (int x = 0; x < VEC; ++x) part[wave][lm.lane][x] = dar[x];
@@ -660,9 +666,36 @@ int check_shape(int dtype, int H, int D)
     if (H <= 0 || D <= 0) return sar::fail(SAR_ERR_INVALID_ARG, "H and D must be positive (H=%d, D=%d)", H, D);
     if (D % vec != 0)
         return sar::fail(SAR_ERR_UNSUPPORTED, "D=%d must be a multiple of %d for this dtype", D, vec);
-    if ((int64_t)H * D / vec > 64)
-        return sar::fail(SAR_ERR_UNSUPPORTED, "row of H*D=%d values is wider than 1024 bytes", H * D);
+    if (D / vec > 64)
+        return sar::fail(SAR_ERR_UNSUPPORTED, "one head of D=%d values is wider than 1024 bytes", D);
     return SAR_OK;
+}
+
+// Heads are independent in Eq. 3, so a layer whose rows exceed what one wavefront covers
+// (1024 bytes) is processed as several launches over groups of heads, each launch seeing its
+// slice of every row through the row stride.
+struct HeadGroups {
+    int n, Hg, Fg;       // groups, heads per group, values per group
+    size_t fb;           // bytes per feature value
+};
+
+HeadGroups head_groups(int dtype, int H, int D)
+{
+    HeadGroups g;
+    g.fb = dtype == SAR_F32 ? 4 : 2;
+    int hg = std::max<int>(1, (int)(1024 / (D * g.fb)));
+    hg = std::min(hg, H);
+    while (H % hg != 0) --hg;
+    g.Hg = hg;
+    g.n = H / hg;
+    g.Fg = hg * D;
+    return g;
+}
+
+template <typename P>
+P* shift(P* p, size_t bytes)
+{
+    return p ? reinterpret_cast<P*>(reinterpret_cast<uintptr_t>(p) + bytes) : nullptr;
 }
 
 unsigned persistent_grid(int64_t n_rows, int64_t n_long)
@@ -711,9 +744,9 @@ unsigned persistent_grid_for(int64_t n_rows, int64_t n_long, int resident)
 }
 
 // F = 256 and a power-of-two head width: the specialised kernels apply.
-int fast_lph(int H, int D)
+int fast_lph(int H, int D, int ldz)
 {
-    if (H * D != f256::kF || D % 4 != 0) return 0;
+    if (H * D != f256::kF || ldz != f256::kF || D % 4 != 0) return 0;
     const int lph = D / 4;
     return (lph >= 4 && (lph & (lph - 1)) == 0) ? lph : 0;
 }
@@ -746,7 +779,7 @@ int launch_fwd(const FwdArgs& a, const PtrTab& zt, const PtrTab& tt, int P, hipS
 #define SAR_FWD_F256(LPH)                                                                  \
     return a.a_l ? launch_fwd_f256<T, LPH, ALL, true>(a, zt, tt, st)                       \
                  : launch_fwd_f256<T, LPH, ALL, false>(a, zt, tt, st)
-    switch (fast_lph(a.H, a.D)) {
+    switch (fast_lph(a.H, a.D, a.ldz)) {
         case 4: SAR_FWD_F256(4);
         case 8: SAR_FWD_F256(8);
         case 16: SAR_FWD_F256(16);
@@ -818,7 +851,7 @@ int launch_bwd(const BwdArgs& tabs, BwdScalars& a, float* da_l, hipStream_t st)
 {
     if (a.n_rows == 0) return SAR_OK;
     unsigned grid = persistent_grid(a.n_rows, a.n_long);
-    switch (fast_lph(a.H, a.D)) {
+    switch (fast_lph(a.H, a.D, a.ldz)) {
         case 4: SAR_TRY((launch_bwd_f256<T, 4, ALL>(tabs, a, &grid, st))); break;
         case 8: SAR_TRY((launch_bwd_f256<T, 8, ALL>(tabs, a, &grid, st))); break;
         case 16: SAR_TRY((launch_bwd_f256<T, 16, ALL>(tabs, a, &grid, st))); break;
@@ -847,15 +880,21 @@ extern "C" int sar_gat_scores(const void* Z, int dtype, int64_t n, int H, int D,
     SAR_CHECK_ARG(Z && a && score, "Z, a or score is null");
     SAR_CHECK_ARG(aligned16(Z), "Z must be 16-byte aligned");
     const int F = H * D;
+    const HeadGroups hg = head_groups(dtype, H, D);
     hipStream_t st = sar::as_stream(stream);
-    if (dtype == SAR_F32) {
-        SAR_DISPATCH_G(float, F, (k_scores<float, kG><<<nodewise_grid(n, kWave / kG), kGatherThreads, 0, st>>>(
-                                     static_cast<const float*>(Z), n, H, D, F, a, score)));
-    } else {
-        SAR_DISPATCH_G(bf16_t, F, (k_scores<bf16_t, kG><<<nodewise_grid(n, kWave / kG), kGatherThreads, 0, st>>>(
-                                      static_cast<const bf16_t*>(Z), n, H, D, F, a, score)));
+    for (int g = 0; g < hg.n; ++g) {
+        const void* Zg = shift(Z, (size_t)g * hg.Fg * hg.fb);
+        const float* ag = a + (size_t)g * hg.Fg;
+        float* sg = score + (size_t)g * hg.Hg;
+        if (dtype == SAR_F32) {
+            SAR_DISPATCH_G(float, hg.Fg, (k_scores<float, kG><<<nodewise_grid(n, kWave / kG), kGatherThreads, 0, st>>>(
+                                             static_cast<const float*>(Zg), n, hg.Hg, D, hg.Fg, F, H, ag, sg)));
+        } else {
+            SAR_DISPATCH_G(bf16_t, hg.Fg, (k_scores<bf16_t, kG><<<nodewise_grid(n, kWave / kG), kGatherThreads, 0, st>>>(
+                                              static_cast<const bf16_t*>(Zg), n, hg.Hg, D, hg.Fg, F, H, ag, sg)));
+        }
+        SAR_LAUNCH_CHECK();
     }
-    SAR_LAUNCH_CHECK();
     return SAR_OK;
 }
 
@@ -883,26 +922,35 @@ extern "C" int sar_gat_fwd_block(const sar_blocks_t* b, int q, const void* Zq, c
     SAR_CHECK_ARG(Zq && s && m && l && acc, "a tensor argument is null");
     SAR_CHECK_ARG(tq || a_l, "either tq or a_l must be given");
     SAR_CHECK_ARG(aligned16(Zq) && aligned16(acc) && aligned16(a_l), "Zq, acc and a_l must be 16-byte aligned");
-    FwdArgs a{};
-    a.indptr = k.indptr;
-    a.indices = reinterpret_cast<const uint32_t*>(k.indices);
-    a.rows = reinterpret_cast<const uint32_t*>(k.rows);
-    a.n_rows = k.n_rows;
-    a.n_long = k.n_long;
-    a.Z = Zq;
-    a.t = tq;
-    a.a_l = tq ? nullptr : a_l;
-    a.s = s;
-    a.m = m;
-    a.l = l;
-    a.acc = acc;
-    a.H = H;
-    a.D = D;
-    a.F = H * D;
-    a.slope = slope;
-    PtrTab none{};
-    if (dtype == SAR_F32) return launch_fwd<float, false>(a, none, none, 0, sar::as_stream(stream));
-    return launch_fwd<bf16_t, false>(a, none, none, 0, sar::as_stream(stream));
+    const HeadGroups hg = head_groups(dtype, H, D);
+    for (int g = 0; g < hg.n; ++g) {
+        const size_t f0 = (size_t)g * hg.Fg, h0 = (size_t)g * hg.Hg;
+        FwdArgs a{};
+        a.indptr = k.indptr;
+        a.indices = reinterpret_cast<const uint32_t*>(k.indices);
+        a.rows = reinterpret_cast<const uint32_t*>(k.rows);
+        a.n_rows = k.n_rows;
+        a.n_long = k.n_long;
+        a.Z = shift(Zq, f0 * hg.fb);
+        a.t = tq ? tq + h0 : nullptr;
+        a.a_l = tq ? nullptr : a_l + f0;
+        a.s = s + h0;
+        a.m = m + h0;
+        a.l = l + h0;
+        a.acc = acc + f0;
+        a.H = hg.Hg;
+        a.D = D;
+        a.F = hg.Fg;
+        a.ldz = H * D;
+        a.ldh = H;
+        a.slope = slope;
+        PtrTab none{};
+        if (dtype == SAR_F32)
+            SAR_TRY((launch_fwd<float, false>(a, none, none, 0, sar::as_stream(stream))));
+        else
+            SAR_TRY((launch_fwd<bf16_t, false>(a, none, none, 0, sar::as_stream(stream))));
+    }
+    return SAR_OK;
 }
 
 extern "C" int sar_gat_fwd_end(const float* m, const float* l, const float* acc, void* out, float* L,
@@ -914,15 +962,21 @@ extern "C" int sar_gat_fwd_end(const float* m, const float* l, const float* acc,
     SAR_CHECK_ARG(m && l && acc && out && L, "a tensor argument is null");
     SAR_CHECK_ARG(aligned16(acc) && aligned16(out), "acc and out must be 16-byte aligned");
     const int F = H * D;
+    const HeadGroups hg = head_groups(dtype, H, D);
     hipStream_t st = sar::as_stream(stream);
-    if (dtype == SAR_F32) {
-        SAR_DISPATCH_G(float, F, (k_fwd_end<float, kG><<<nodewise_grid(n_dst, kWave / kG), kGatherThreads, 0, st>>>(
-                                     m, l, acc, static_cast<float*>(out), L, n_dst, H, D, F)));
-    } else {
-        SAR_DISPATCH_G(bf16_t, F, (k_fwd_end<bf16_t, kG><<<nodewise_grid(n_dst, kWave / kG), kGatherThreads, 0, st>>>(
-                                      m, l, acc, static_cast<bf16_t*>(out), L, n_dst, H, D, F)));
+    for (int g = 0; g < hg.n; ++g) {
+        const size_t f0 = (size_t)g * hg.Fg, h0 = (size_t)g * hg.Hg;
+        if (dtype == SAR_F32) {
+            SAR_DISPATCH_G(float, hg.Fg, (k_fwd_end<float, kG><<<nodewise_grid(n_dst, kWave / kG), kGatherThreads, 0, st>>>(
+                                             m + h0, l + h0, acc + f0, static_cast<float*>(out) + f0, L + h0, n_dst,
+                                             hg.Hg, D, hg.Fg, F, H)));
+        } else {
+            SAR_DISPATCH_G(bf16_t, hg.Fg, (k_fwd_end<bf16_t, kG><<<nodewise_grid(n_dst, kWave / kG), kGatherThreads, 0, st>>>(
+                                              m + h0, l + h0, acc + f0, static_cast<bf16_t*>(out) + f0, L + h0, n_dst,
+                                              hg.Hg, D, hg.Fg, F, H)));
+        }
+        SAR_LAUNCH_CHECK();
     }
-    SAR_LAUNCH_CHECK();
     return SAR_OK;
 }
 
@@ -937,42 +991,49 @@ extern "C" int sar_gat_fwd_all(const sar_blocks_t* b, const void* const* Zq, con
     SAR_CHECK_ARG(Zq && s && out && L, "a tensor argument is null");
     SAR_CHECK_ARG(tq || a_l, "either tq or a_l must be given");
     SAR_CHECK_ARG(aligned16(out) && aligned16(a_l), "out and a_l must be 16-byte aligned");
-    PtrTab zt{}, tt{};
     for (int q = 0; q < b->P; ++q) {
         SAR_CHECK_ARG((Zq[q] && (!tq || tq[q])) || b->blk[q].nnz == 0, "Zq[%d] or tq[%d] is null", q, q);
         SAR_CHECK_ARG(aligned16(Zq[q]), "Zq[%d] must be 16-byte aligned", q);
-        zt.p[q] = Zq[q];
-        tt.p[q] = tq ? tq[q] : nullptr;
     }
     hipStream_t st = sar::as_stream(stream);
-    FwdArgs a{};
-    a.indptr = b->f_indptr;
-    a.indices = b->f_indices;
-    a.rows = reinterpret_cast<const uint32_t*>(b->f_rows);
-    a.n_rows = b->n_dst;   // the list ends with the destinations that have no in-edge: out = 0, L = -inf
-    a.n_long = b->n_f_long;
-    a.s = s;
-    a.a_l = tq ? nullptr : a_l;
-    a.out = out;
-    a.L = L;
-    a.H = H;
-    a.D = D;
-    a.F = H * D;
-    a.tag_shift = b->tag_shift;
-    a.slope = slope;
-    int rc;
-    if (dtype == SAR_F32)
-        rc = launch_fwd<float, true>(a, zt, tt, b->P, st);
-    else
-        rc = launch_fwd<bf16_t, true>(a, zt, tt, b->P, st);
-    return rc;
+    const HeadGroups hg = head_groups(dtype, H, D);
+    for (int g = 0; g < hg.n; ++g) {
+        const size_t f0 = (size_t)g * hg.Fg, h0 = (size_t)g * hg.Hg;
+        PtrTab zt{}, tt{};
+        for (int q = 0; q < b->P; ++q) {
+            zt.p[q] = shift(Zq[q], f0 * hg.fb);
+            tt.p[q] = (tq && tq[q]) ? tq[q] + h0 : nullptr;
+        }
+        FwdArgs a{};
+        a.indptr = b->f_indptr;
+        a.indices = b->f_indices;
+        a.rows = reinterpret_cast<const uint32_t*>(b->f_rows);
+        a.n_rows = b->n_dst;   // the list ends with the destinations that have no in-edge: out = 0, L = -inf
+        a.n_long = b->n_f_long;
+        a.s = s + h0;
+        a.a_l = tq ? nullptr : a_l + f0;
+        a.out = shift(out, f0 * hg.fb);
+        a.L = L + h0;
+        a.H = hg.Hg;
+        a.D = D;
+        a.F = hg.Fg;
+        a.ldz = H * D;
+        a.ldh = H;
+        a.tag_shift = b->tag_shift;
+        a.slope = slope;
+        if (dtype == SAR_F32)
+            SAR_TRY((launch_fwd<float, true>(a, zt, tt, b->P, st)));
+        else
+            SAR_TRY((launch_fwd<bf16_t, true>(a, zt, tt, b->P, st)));
+    }
+    return SAR_OK;
 }
 
 extern "C" int sar_gat_workspace_bytes(int64_t n_dst, int64_t n_src_max, int H, int D, size_t* bytes)
 {
     SAR_CHECK_ARG(bytes != nullptr, "bytes is null");
     SAR_CHECK_ARG(n_dst >= 0 && n_src_max >= 0 && H > 0 && D > 0, "sizes must be non-negative, H and D positive");
-    *bytes = workspace_bytes(H * D);
+    *bytes = workspace_bytes(std::min(H * D, 256));
     return SAR_OK;
 }
 
@@ -985,17 +1046,24 @@ extern "C" int sar_gat_bwd_begin(const void* G, const void* out, const float* s,
     SAR_CHECK_ARG(G && out && s && L && rec && ds, "a tensor argument is null");
     SAR_CHECK_ARG(aligned16(G) && aligned16(out) && aligned16(rec), "G, out and rec must be 16-byte aligned");
     const int F = H * D;
+    const HeadGroups hg = head_groups(dtype, H, D);
     hipStream_t st = sar::as_stream(stream);
-    if (dtype == SAR_F32) {
-        SAR_DISPATCH_G(float, F, (k_bwd_begin<float, kG><<<nodewise_grid(n_dst, kWave / kG), kGatherThreads, 0, st>>>(
-                                     static_cast<const float*>(G), static_cast<const float*>(out), s, L,
-                                     reinterpret_cast<float4*>(rec), ds, n_dst, H, D, F)));
-    } else {
-        SAR_DISPATCH_G(bf16_t, F, (k_bwd_begin<bf16_t, kG><<<nodewise_grid(n_dst, kWave / kG), kGatherThreads, 0, st>>>(
-                                      static_cast<const bf16_t*>(G), static_cast<const bf16_t*>(out), s, L,
-                                      reinterpret_cast<float4*>(rec), ds, n_dst, H, D, F)));
+    for (int g = 0; g < hg.n; ++g) {
+        const size_t f0 = (size_t)g * hg.Fg, h0 = (size_t)g * hg.Hg;
+        const void* Gg = shift(G, f0 * hg.fb);
+        const void* og = shift(out, f0 * hg.fb);
+        float4* recg = reinterpret_cast<float4*>(rec) + h0;
+        if (dtype == SAR_F32) {
+            SAR_DISPATCH_G(float, hg.Fg, (k_bwd_begin<float, kG><<<nodewise_grid(n_dst, kWave / kG), kGatherThreads, 0, st>>>(
+                                             static_cast<const float*>(Gg), static_cast<const float*>(og), s + h0, L + h0,
+                                             recg, ds + h0, n_dst, hg.Hg, D, hg.Fg, F, H)));
+        } else {
+            SAR_DISPATCH_G(bf16_t, hg.Fg, (k_bwd_begin<bf16_t, kG><<<nodewise_grid(n_dst, kWave / kG), kGatherThreads, 0, st>>>(
+                                              static_cast<const bf16_t*>(Gg), static_cast<const bf16_t*>(og), s + h0,
+                                              L + h0, recg, ds + h0, n_dst, hg.Hg, D, hg.Fg, F, H)));
+        }
+        SAR_LAUNCH_CHECK();
     }
-    SAR_LAUNCH_CHECK();
     return SAR_OK;
 }
 
@@ -1011,9 +1079,27 @@ int bwd_common_checks(const sar_blocks_t* b, int dtype, int H, int D, const void
     SAR_CHECK_ARG(G && rec && a_l && ds && da_l, "a tensor argument is null");
     SAR_CHECK_ARG(aligned16(G) && aligned16(rec) && aligned16(a_l), "G, rec and a_l must be 16-byte aligned");
     SAR_CHECK_ARG(work != nullptr && aligned16(work), "work is null or not 16-byte aligned");
-    SAR_CHECK_ARG(work_bytes >= workspace_bytes(H * D), "work_bytes=%zu is below the %zu bytes required",
-                  work_bytes, workspace_bytes(H * D));
+    const size_t need = workspace_bytes(std::min(H * D, 256));
+    SAR_CHECK_ARG(work_bytes >= need, "work_bytes=%zu is below the %zu bytes required", work_bytes, need);
     return SAR_OK;
+}
+
+// Fields that do not depend on the block(s) or on the head group.
+void fill_bwd_group(BwdScalars& a, const HeadGroups& hg, int g, int H, int D, const void* G, const float* rec,
+                    const float* a_l, float* ds, void* work, float slope)
+{
+    const size_t f0 = (size_t)g * hg.Fg, h0 = (size_t)g * hg.Hg;
+    a.G = shift(G, f0 * hg.fb);
+    a.rec = reinterpret_cast<const float4*>(rec) + h0;
+    a.a_l = a_l + f0;
+    a.ds = ds + h0;
+    a.partial = static_cast<float*>(work);
+    a.H = hg.Hg;
+    a.D = D;
+    a.F = hg.Fg;
+    a.ldz = H * D;
+    a.ldh = H;
+    a.slope = slope;
 }
 
 }  // namespace
@@ -1030,29 +1116,28 @@ extern "C" int sar_gat_bwd_block(const sar_blocks_t* b, int q, const void* Zq, c
     SAR_CHECK_ARG(Zq && dZq && dtq, "a tensor argument is null");
     SAR_CHECK_ARG(aligned16(Zq) && aligned16(dZq), "Zq and dZq must be 16-byte aligned");
     hipStream_t st = sar::as_stream(stream);
-    BwdArgs tabs{};
-    tabs.t_indptr[0] = k.t_indptr;
-    tabs.t_indices[0] = k.t_indices;
-    tabs.Z[0] = Zq;
-    tabs.t[0] = tq;
-    tabs.dZ[0] = dZq;
-    tabs.dt[0] = dtq;
-    BwdScalars a{};
-    a.rows = reinterpret_cast<const uint32_t*>(k.t_rows);
-    a.n_rows = k.n_src;    // sources without edges come last and get dZ = 0, dt = 0
-    a.n_long = k.n_t_long;
-    a.n_wide = k.n_t_wide;
-    a.G = G;
-    a.rec = reinterpret_cast<const float4*>(rec);
-    a.a_l = a_l;
-    a.ds = ds;
-    a.partial = static_cast<float*>(work);
-    a.H = H;
-    a.D = D;
-    a.F = H * D;
-    a.slope = slope;
-    if (dtype == SAR_F32) return launch_bwd<float, false>(tabs, a, da_l, st);
-    return launch_bwd<bf16_t, false>(tabs, a, da_l, st);
+    const HeadGroups hg = head_groups(dtype, H, D);
+    for (int g = 0; g < hg.n; ++g) {
+        const size_t f0 = (size_t)g * hg.Fg, h0 = (size_t)g * hg.Hg;
+        BwdArgs tabs{};
+        tabs.t_indptr[0] = k.t_indptr;
+        tabs.t_indices[0] = k.t_indices;
+        tabs.Z[0] = shift(Zq, f0 * hg.fb);
+        tabs.t[0] = tq ? tq + h0 : nullptr;
+        tabs.dZ[0] = shift(dZq, f0 * hg.fb);
+        tabs.dt[0] = dtq + h0;
+        BwdScalars a{};
+        a.rows = reinterpret_cast<const uint32_t*>(k.t_rows);
+        a.n_rows = k.n_src;    // sources without edges come last and get dZ = 0, dt = 0
+        a.n_long = k.n_t_long;
+        a.n_wide = k.n_t_wide;
+        fill_bwd_group(a, hg, g, H, D, G, rec, a_l, ds, work, slope);
+        if (dtype == SAR_F32)
+            SAR_TRY((launch_bwd<float, false>(tabs, a, da_l + f0, st)));
+        else
+            SAR_TRY((launch_bwd<bf16_t, false>(tabs, a, da_l + f0, st)));
+    }
+    return SAR_OK;
 }
 
 extern "C" int sar_gat_bwd_all(const sar_blocks_t* b, const void* const* Zq, const void* G,
@@ -1063,38 +1148,39 @@ extern "C" int sar_gat_bwd_all(const sar_blocks_t* b, const void* const* Zq, con
     SAR_TRY(bwd_common_checks(b, dtype, H, D, G, rec, a_l, ds, da_l, work, work_bytes));
     SAR_CHECK_ARG(Zq && dZq && dtq, "a pointer table is null");
     hipStream_t st = sar::as_stream(stream);
-    BwdArgs tabs{};
-    const int F = H * D;
     for (int q = 0; q < b->P; ++q) {
-        const sar::Block& k = b->blk[q];
-        if (k.n_src == 0) continue;
+        if (b->blk[q].n_src == 0) continue;
         SAR_CHECK_ARG(Zq[q] && (!tq || tq[q]) && dZq[q] && dtq[q], "a tensor of block %d is null", q);
         SAR_CHECK_ARG(aligned16(Zq[q]) && aligned16(dZq[q]), "Zq[%d] and dZq[%d] must be 16-byte aligned", q, q);
-        tabs.t_indptr[q] = k.t_indptr;
-        tabs.t_indices[q] = k.t_indices;
-        tabs.Z[q] = Zq[q];
-        tabs.t[q] = tq ? tq[q] : nullptr;
-        tabs.dZ[q] = dZq[q];
-        tabs.dt[q] = dtq[q];
     }
-    BwdScalars a{};
-    a.rows = b->ft_rows;
-    a.n_rows = 0;
-    for (int q = 0; q < b->P; ++q) a.n_rows += b->blk[q].n_src;
-    a.n_wide = b->n_ft_wide;
-    a.n_long = b->n_ft_long;
-    a.G = G;
-    a.rec = reinterpret_cast<const float4*>(rec);
-    a.a_l = a_l;
-    a.ds = ds;
-    a.partial = static_cast<float*>(work);
-    a.H = H;
-    a.D = D;
-    a.F = F;
-    a.tag_shift = b->tag_shift;
-    a.slope = slope;
-    if (dtype == SAR_F32) return launch_bwd<float, true>(tabs, a, da_l, st);
-    return launch_bwd<bf16_t, true>(tabs, a, da_l, st);
+    const HeadGroups hg = head_groups(dtype, H, D);
+    for (int g = 0; g < hg.n; ++g) {
+        const size_t f0 = (size_t)g * hg.Fg, h0 = (size_t)g * hg.Hg;
+        BwdArgs tabs{};
+        for (int q = 0; q < b->P; ++q) {
+            const sar::Block& k = b->blk[q];
+            if (k.n_src == 0) continue;
+            tabs.t_indptr[q] = k.t_indptr;
+            tabs.t_indices[q] = k.t_indices;
+            tabs.Z[q] = shift(Zq[q], f0 * hg.fb);
+            tabs.t[q] = tq ? tq[q] + h0 : nullptr;
+            tabs.dZ[q] = shift(dZq[q], f0 * hg.fb);
+            tabs.dt[q] = dtq[q] + h0;
+        }
+        BwdScalars a{};
+        a.rows = b->ft_rows;
+        a.n_rows = 0;
+        for (int q = 0; q < b->P; ++q) a.n_rows += b->blk[q].n_src;
+        a.n_wide = b->n_ft_wide;
+        a.n_long = b->n_ft_long;
+        a.tag_shift = b->tag_shift;
+        fill_bwd_group(a, hg, g, H, D, G, rec, a_l, ds, work, slope);
+        if (dtype == SAR_F32)
+            SAR_TRY((launch_bwd<float, true>(tabs, a, da_l + f0, st)));
+        else
+            SAR_TRY((launch_bwd<bf16_t, true>(tabs, a, da_l + f0, st)));
+    }
+    return SAR_OK;
 }
 
 extern "C" int sar_gat_bwd_end(const void* Zdst, const float* ds, const float* a_r, const void* dZadd,
@@ -1109,26 +1195,32 @@ extern "C" int sar_gat_bwd_end(const void* Zdst, const float* ds, const float* a
                   "Zdst, dZadd and dZdst must be 16-byte aligned");
     SAR_CHECK_ARG(work != nullptr && aligned16(work), "work is null or not 16-byte aligned");
     const int F = H * D;
-    SAR_CHECK_ARG(work_bytes >= workspace_bytes(F), "work_bytes=%zu is below the %zu bytes required", work_bytes,
-                  workspace_bytes(F));
+    const size_t need = workspace_bytes(std::min(F, 256));
+    SAR_CHECK_ARG(work_bytes >= need, "work_bytes=%zu is below the %zu bytes required", work_bytes, need);
     hipStream_t st = sar::as_stream(stream);
-    unsigned grid = 1;
-    if (dtype == SAR_F32) {
-        SAR_DISPATCH_G(float, F, (grid = nodewise_grid(n_dst, kWave / kG),
-                                  k_bwd_end<float, kG><<<grid, kGatherThreads, 0, st>>>(
-                                      static_cast<const float*>(Zdst), ds, a_r, static_cast<const float*>(dZadd),
-                                      static_cast<float*>(dZdst),
-                                      static_cast<float*>(work), n_dst, H, D, F)));
-    } else {
-        SAR_DISPATCH_G(bf16_t, F, (grid = nodewise_grid(n_dst, kWave / kG),
-                                   k_bwd_end<bf16_t, kG><<<grid, kGatherThreads, 0, st>>>(
-                                       static_cast<const bf16_t*>(Zdst), ds, a_r, static_cast<const bf16_t*>(dZadd),
-                                       static_cast<bf16_t*>(dZdst),
-                                       static_cast<float*>(work), n_dst, H, D, F)));
+    const HeadGroups hg = head_groups(dtype, H, D);
+    for (int g = 0; g < hg.n; ++g) {
+        const size_t f0 = (size_t)g * hg.Fg, h0 = (size_t)g * hg.Hg;
+        unsigned grid = 1;
+        if (dtype == SAR_F32) {
+            SAR_DISPATCH_G(float, hg.Fg, (grid = nodewise_grid(n_dst, kWave / kG),
+                                          k_bwd_end<float, kG><<<grid, kGatherThreads, 0, st>>>(
+                                              static_cast<const float*>(Zdst) + f0, ds + h0, a_r + f0,
+                                              dZadd ? static_cast<const float*>(dZadd) + f0 : nullptr,
+                                              static_cast<float*>(dZdst) + f0, static_cast<float*>(work), n_dst, hg.Hg,
+                                              D, hg.Fg, F, H)));
+        } else {
+            SAR_DISPATCH_G(bf16_t, hg.Fg, (grid = nodewise_grid(n_dst, kWave / kG),
+                                           k_bwd_end<bf16_t, kG><<<grid, kGatherThreads, 0, st>>>(
+                                               static_cast<const bf16_t*>(Zdst) + f0, ds + h0, a_r + f0,
+                                               dZadd ? static_cast<const bf16_t*>(dZadd) + f0 : nullptr,
+                                               static_cast<bf16_t*>(dZdst) + f0, static_cast<float*>(work), n_dst,
+                                               hg.Hg, D, hg.Fg, F, H)));
+        }
+        SAR_LAUNCH_CHECK();
+        k_reduce_partials<<<hg.Fg, 256, 0, st>>>(static_cast<const float*>(work), (int)grid, hg.Fg, da_r + f0);
+        SAR_LAUNCH_CHECK();
     }
-    SAR_LAUNCH_CHECK();
-    k_reduce_partials<<<F, 256, 0, st>>>(static_cast<const float*>(work), (int)grid, F, da_r);
-    SAR_LAUNCH_CHECK();
     return SAR_OK;
 }
 

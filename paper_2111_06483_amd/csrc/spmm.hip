@@ -32,7 +32,8 @@ struct SpmmArgs {
     float* acc;               // fp32 accumulator rows, read-modify-write (forward per block)
     void* out;                // typed output rows (batched forward, backward)
     const int32_t* deg;       // |N(i)| for the mean, or null
-    int F;
+    int F;                    // values per row handled by this launch
+    int ld;                   // stride between rows (values)
     int tag_shift;            // all-blocks index: block = id >> tag_shift
     int mean;
 };
@@ -69,7 +70,7 @@ __device__ inline void add_rows(float (&acc)[Vec<T>::N], const SpmmArgs& a, cons
                         base = static_cast<const T*>(ztab[id >> a.tag_shift]);
                     else
                         base = static_cast<const T*>(a.Z);
-                    raw[k] = Vec<T>::load(base + (int64_t)j * a.F + lm.gl * VEC);
+                    raw[k] = Vec<T>::load(base + (int64_t)j * a.ld + lm.gl * VEC);
                     if constexpr (M == Mode::kBackward) {
                         if (a.mean) w[k] = 1.f / (float)max(a.deg[j], 1);
                     }
@@ -106,7 +107,7 @@ __device__ inline void finish_row(const float (&acc)[Vec<T>::N], const SpmmArgs&
 {
     constexpr int VEC = Vec<T>::N;
     if (lm.slot != 0 || !lm.on) return;
-    const int64_t o = (int64_t)i * a.F + lm.gl * VEC;
+    const int64_t o = (int64_t)i * a.ld + lm.gl * VEC;
     if constexpr (M == Mode::kBlock) {
         float cur[VEC];
         load_f32<VEC>(a.acc + o, cur);
@@ -222,9 +223,29 @@ int check_row_shape(int dtype, int F)
     const int vec = dtype == SAR_F32 ? 4 : 8;
     if (F <= 0 || F % vec != 0)
         return sar::fail(SAR_ERR_UNSUPPORTED, "F=%d must be a positive multiple of %d for this dtype", F, vec);
-    if (F / vec > 64)
-        return sar::fail(SAR_ERR_UNSUPPORTED, "row of F=%d values is wider than 1024 bytes", F);
     return SAR_OK;
+}
+
+// Rows wider than one wavefront covers (1024 bytes) are processed as several launches over
+// column ranges, each seeing its slice of every row through the row stride.
+struct ColumnChunks {
+    int n, width;   // launches and values per launch (the last launch may be narrower)
+    size_t fb;
+};
+
+ColumnChunks column_chunks(int dtype, int F)
+{
+    ColumnChunks c;
+    c.fb = dtype == SAR_F32 ? 4 : 2;
+    c.width = (int)(1024 / c.fb);
+    c.n = (F + c.width - 1) / c.width;
+    return c;
+}
+
+template <typename P>
+P* shift(P* p, size_t bytes)
+{
+    return p ? reinterpret_cast<P*>(reinterpret_cast<uintptr_t>(p) + bytes) : nullptr;
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -247,12 +268,20 @@ extern "C" int sar_spmm_block(const sar_blocks_t* b, int q, const void* Zq, int 
     a.rows = reinterpret_cast<const uint32_t*>(k.rows);
     a.n_rows = k.n_rows;
     a.n_long = k.n_long;
-    a.Z = Zq;
-    a.acc = acc;
-    a.F = F;
+    a.ld = F;
     PtrTab tab{};
-    if (dtype == SAR_F32) return launch_spmm<float, Mode::kBlock>(a, tab, 0, sar::as_stream(stream));
-    return launch_spmm<bf16_t, Mode::kBlock>(a, tab, 0, sar::as_stream(stream));
+    const ColumnChunks cc = column_chunks(dtype, F);
+    for (int c = 0; c < cc.n; ++c) {
+        const size_t f0 = (size_t)c * cc.width;
+        a.Z = shift(Zq, f0 * cc.fb);
+        a.acc = acc + f0;
+        a.F = std::min<int>(cc.width, F - (int)f0);
+        if (dtype == SAR_F32)
+            SAR_TRY((launch_spmm<float, Mode::kBlock>(a, tab, 0, sar::as_stream(stream))));
+        else
+            SAR_TRY((launch_spmm<bf16_t, Mode::kBlock>(a, tab, 0, sar::as_stream(stream))));
+    }
+    return SAR_OK;
 }
 
 extern "C" int sar_spmm_end(const int32_t* deg, int mean, const float* acc, void* out, int dtype,
@@ -282,11 +311,9 @@ extern "C" int sar_spmm_all(const sar_blocks_t* b, const void* const* Zq, int dt
     if (b->n_dst == 0) return SAR_OK;
     SAR_CHECK_ARG(Zq && out, "Zq or out is null");
     SAR_CHECK_ARG(aligned16(out), "out must be 16-byte aligned");
-    PtrTab tab{};
     for (int q = 0; q < b->P; ++q) {
         SAR_CHECK_ARG(Zq[q] != nullptr || b->blk[q].nnz == 0, "Zq[%d] is null", q);
         SAR_CHECK_ARG(aligned16(Zq[q]), "Zq[%d] must be 16-byte aligned", q);
-        tab.p[q] = Zq[q];
     }
     hipStream_t st = sar::as_stream(stream);
     SpmmArgs a{};
@@ -295,13 +322,23 @@ extern "C" int sar_spmm_all(const sar_blocks_t* b, const void* const* Zq, int dt
     a.rows = reinterpret_cast<const uint32_t*>(b->f_rows);
     a.n_rows = b->n_dst;   // destinations without in-edges come last in the list and get 0
     a.n_long = b->n_f_long;
-    a.out = out;
     a.deg = b->deg;
-    a.F = F;
+    a.ld = F;
     a.tag_shift = b->tag_shift;
     a.mean = mean;
-    if (dtype == SAR_F32) return launch_spmm<float, Mode::kAll>(a, tab, b->P, st);
-    return launch_spmm<bf16_t, Mode::kAll>(a, tab, b->P, st);
+    const ColumnChunks cc = column_chunks(dtype, F);
+    for (int c = 0; c < cc.n; ++c) {
+        const size_t f0 = (size_t)c * cc.width;
+        PtrTab tab{};
+        for (int q = 0; q < b->P; ++q) tab.p[q] = shift(Zq[q], f0 * cc.fb);
+        a.out = shift(out, f0 * cc.fb);
+        a.F = std::min<int>(cc.width, F - (int)f0);
+        if (dtype == SAR_F32)
+            SAR_TRY((launch_spmm<float, Mode::kAll>(a, tab, b->P, st)));
+        else
+            SAR_TRY((launch_spmm<bf16_t, Mode::kAll>(a, tab, b->P, st)));
+    }
+    return SAR_OK;
 }
 
 extern "C" int sar_spmm_bwd_block(const sar_blocks_t* b, int q, const void* G, int mean, int dtype, int F,
@@ -322,12 +359,20 @@ extern "C" int sar_spmm_bwd_block(const sar_blocks_t* b, int q, const void* G, i
     a.rows = reinterpret_cast<const uint32_t*>(k.t_rows);
     a.n_rows = k.n_src;    // sources without edges come last in the list and get 0
     a.n_long = k.n_t_long;
-    a.Z = G;
-    a.out = dZq;
     a.deg = b->deg;
-    a.F = F;
+    a.ld = F;
     a.mean = mean;
     PtrTab tab{};
-    if (dtype == SAR_F32) return launch_spmm<float, Mode::kBackward>(a, tab, 0, st);
-    return launch_spmm<bf16_t, Mode::kBackward>(a, tab, 0, st);
+    const ColumnChunks cc = column_chunks(dtype, F);
+    for (int c = 0; c < cc.n; ++c) {
+        const size_t f0 = (size_t)c * cc.width;
+        a.Z = shift(G, f0 * cc.fb);
+        a.out = shift(dZq, f0 * cc.fb);
+        a.F = std::min<int>(cc.width, F - (int)f0);
+        if (dtype == SAR_F32)
+            SAR_TRY((launch_spmm<float, Mode::kBackward>(a, tab, 0, st)));
+        else
+            SAR_TRY((launch_spmm<bf16_t, Mode::kBackward>(a, tab, 0, st)));
+    }
+    return SAR_OK;
 }

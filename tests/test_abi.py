@@ -51,8 +51,10 @@ def test_validation_errors_need_no_gpu(lib):
     assert rc == sar.SAR_ERR_UNSUPPORTED
     rc = lib.sar_gat_scores(None, 0, i64(5), 2, 4, None, None, None)
     assert rc == sar.SAR_ERR_INVALID_ARG and b"null" in lib.sar_last_error()
-    rc = lib.sar_gat_scores(None, 0, i64(5), 8, 64, None, None, None)      # 2 KiB row
-    assert rc == sar.SAR_ERR_UNSUPPORTED
+    rc = lib.sar_gat_scores(None, 0, i64(5), 1, 512, None, None, None)     # one head wider than 1 KiB
+    assert rc == sar.SAR_ERR_UNSUPPORTED and b"1024" in lib.sar_last_error()
+    rc = lib.sar_gat_scores(None, 0, i64(5), 8, 64, None, None, None)      # 2 KiB row of 8 heads: head groups
+    assert rc == sar.SAR_ERR_INVALID_ARG and b"null" in lib.sar_last_error()
     h = ctypes.c_void_p()
     rc = lib.sar_blocks_build(None, None, 3, i64(0), None, i64(1), 1, 0, 0, None, ctypes.byref(h))
     assert rc == sar.SAR_ERR_INVALID_ARG and b"idx_bytes" in lib.sar_last_error()

@@ -126,7 +126,7 @@ def test_wrap_equals_build():
 # --------------------------------------------------------------------- spmm
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
-@pytest.mark.parametrize("F", [8, 64, 200, 256])
+@pytest.mark.parametrize("F", [8, 64, 200, 256, 800, 1032])
 @pytest.mark.parametrize("mean", [False, True])
 def test_spmm_parity(dtype, F, mean):
     if dtype == torch.bfloat16 and F % 8:
@@ -186,7 +186,10 @@ def check_fwd(got, want, deg, dtype):
         assert rel_err(f64(tg), tw) < 1e-4
 
 
-SHAPES = [(4, 16), (1, 4), (4, 64), (8, 32), (2, 100), (3, 12), (1, 256), (2, 128), (16, 16)]
+# (heads, head width): every lane mapping of the generic kernels, every head width of the F = 256
+# kernels, non-power-of-two heads, and rows wider than 1 KiB (processed as groups of heads)
+SHAPES = [(4, 16), (1, 4), (4, 64), (8, 32), (2, 100), (3, 12), (1, 256), (2, 128), (16, 16),
+          (8, 100), (8, 64), (3, 200)]
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
