@@ -36,7 +36,8 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "fak"],
+                    help="cfgN: BASELINE configurations; fak: head-count sweep of the paper's single-host kernel experiment")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the graph (debugging only)")
     ap.add_argument("--mode", default="all", choices=["all", "stream"],
                     help="all: one launch over the P blocks; stream: one launch per block")
@@ -286,6 +287,35 @@ def spmm_bench(args, w, torch, sar, synth):
                                    "alg_bytes_per_launch": alg, "gather_volume_GBs": E * F * fb / (ms * 1e-3) / 1e9}}))
 
 
+def fak_sweep(args, torch, sar, synth):
+    """Heads 2/4/8 at constant head width 100 on the products-sized graph, one block (Sec. 4.1):
+    how the cost of the fused forward and of the rematerialising backward grows with the heads."""
+    rows = []
+    for H in (2, 4, 8):
+        w = synth.make_workload("fak%d" % H, device="cuda", scale=args.scale)
+        layer = Layer(w, torch, sar, synth)
+        for _ in range(args.warmup):
+            layer.step("all")
+        names = ["t0", "fwd0", "fwd1", "bwd0", "bwd1", "t1"]
+        evs = [{k: torch.cuda.Event(enable_timing=True) for k in names} for _ in range(args.steps)]
+        torch.cuda.synchronize()
+        for k in range(args.steps):
+            layer.step("all", evs[k])
+        torch.cuda.synchronize()
+        avg = lambda a, b: sum(e[a].elapsed_time(e[b]) for e in evs) / len(evs)
+        fwd_ms, bwd_ms, all_ms = avg("fwd0", "fwd1"), avg("bwd0", "bwd1"), avg("t0", "t1")
+        rows.append({"heads": H, "dims": 100 * H, "edges": layer.E, "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
+                     "layer_ms": all_ms, "fwd_gather_GBs": layer.E * layer.F * 4 / (fwd_ms * 1e-3) / 1e9,
+                     "bwd_over_fwd": bwd_ms / fwd_ms,
+                     "edges_per_s_fwd_bwd": layer.E / ((fwd_ms + bwd_ms) * 1e-3)})
+        del layer, w
+        torch.cuda.empty_cache()
+    print(json.dumps({"metric": "fused GAT kernel fwd/bwd time vs heads (head width 100, one block)",
+                      "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "data": "synthetic",
+                      "config": {"workload": "fak: %d-node power-law graph, one block" % int(2_450_000 * args.scale)},
+                      "sweep": rows}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -297,6 +327,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     sar.lib()
     torch.cuda.set_device(0)
+    if args.workload == "fak":
+        fak_sweep(args, torch, sar, synth)
+        return
     w = synth.make_workload(args.workload, device="cuda", scale=args.scale)
     if args.workload == "cfg2":
         spmm_bench(args, w, torch, sar, synth)

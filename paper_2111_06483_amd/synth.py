@@ -295,4 +295,12 @@ def make_workload(name: str, device="cpu", scale: float = 1.0) -> Workload:
         part = random_partition(N, 4, 1, device)
         src, dst = erdos_renyi_worker_share(N, 500 if scale == 1.0 else min(500, N // 8), part, 0, 0)
         return Workload(name, N, 4, 0, src, dst, part, 256, 8, 32, torch.float32)
+    if name.startswith("fak"):
+        # Sec. 4.1's single-host kernel experiment: one GAT layer on the whole products-sized
+        # graph (one block), H = 2/4/8 heads of constant width 100, in = out = 100 H features.
+        H = int(name[3:])
+        N = max(1024, int(2_450_000 * scale))
+        part = torch.zeros(N, dtype=torch.int32, device=device)
+        src, dst = chung_lu_worker_share(N, 50, 2.1, part, 0, 0)
+        return Workload(name, N, 1, 0, src, dst, part, 100 * H, H, 100, torch.float32)
     raise ValueError(name)
