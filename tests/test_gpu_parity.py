@@ -335,3 +335,69 @@ def test_linear_parity(dtype, n, K, F):
     # accumulates
     gu.linear_bwd(X, dZ, W, dW)
     assert rel_err(f64(dW), 2 * want_dW) < 1e-4
+
+
+# ------------------------------------------------------- streams, determinism, errors
+
+def test_stream_argument_and_determinism():
+    """Launches go to the stream they are given; everything except the atomically accumulated
+    ds (and what is derived from it) is bitwise reproducible."""
+    H, D = 4, 64
+    b, want_b, deg, Zdst, Zs, a_l, a_r, G = gat_case(11, 3000, 40000, 3, 0, H, D, torch.float32)
+    ref = gu.gat_fwd_all(b, Zdst, Zs, a_l, a_r, SLOPE, fly=True)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        again = gu.gat_fwd_all(b, Zdst, Zs, a_l, a_r, SLOPE, fly=True)
+    side.synchronize()
+    assert torch.equal(ref.out, again.out) and torch.equal(ref.L, again.L)
+    g1 = gu.gat_bwd(b, Zdst, Zs, G, a_l, a_r, SLOPE, ref, True, fly=True)
+    with torch.cuda.stream(side):
+        g2 = gu.gat_bwd(b, Zdst, Zs, G, a_l, a_r, SLOPE, ref, True, fly=True)
+    side.synchronize()
+    for q in range(b.P):
+        assert torch.equal(g1.dZs[q], g2.dZs[q]) and torch.equal(g1.dts[q], g2.dts[q])
+    assert torch.equal(g1.da_l, g2.da_l)
+    assert rel_err(f64(g2.ds), f64(g1.ds)) < 1e-5       # atomics: order may differ, values agree
+    b.close()
+
+
+def test_error_paths():
+    src, dst, part, rng = make_graph(12, 1000, 8000, 2, hubs=False)
+    H, D = 2, 16
+    b0 = gu.build_blocks(src, dst, part, 2, 0, flags=0)          # no transpose, no all-blocks index
+    n = b0.n_dst
+    Zs = [feats(rng, b0.view(q).n_src, H * D, torch.float32).cuda().reshape(-1, H, D) for q in range(2)]
+    a = torch.zeros((H, D), device="cuda")
+    s = torch.zeros((n, H), device="cuda")
+    out = torch.empty((n, H, D), device="cuda")
+    L = torch.empty((n, H), device="cuda")
+    with pytest.raises(sar.SarError) as e:
+        sar.sar_gat_fwd_all(b0, Zs, s, None, a, SLOPE, out, L)
+    assert e.value.code == sar.SAR_ERR_STATE
+    rec = torch.zeros((n, H, 4), device="cuda")
+    ds = torch.zeros((n, H), device="cuda")
+    work = torch.empty(sar.sar_gat_workspace_bytes(n, n, H, D) // 4, device="cuda")
+    with pytest.raises(sar.SarError) as e:
+        sar.sar_gat_bwd_block(b0, 0, Zs[0], out, None, rec, a, SLOPE, torch.empty_like(Zs[0]),
+                              torch.empty((Zs[0].shape[0], H), device="cuda"), ds, torch.zeros_like(a), work)
+    assert e.value.code == sar.SAR_ERR_STATE
+    b0.close()
+    b = gu.build_blocks(src, dst, part, 2, 0)
+    with pytest.raises(sar.SarError) as e:      # scratch too small
+        sar.sar_gat_bwd_block(b, 0, Zs[0], out, None, rec, a, SLOPE, torch.empty_like(Zs[0]),
+                              torch.empty((Zs[0].shape[0], H), device="cuda"), ds, torch.zeros_like(a), work[:16])
+    assert e.value.code == sar.SAR_ERR_INVALID_ARG
+    with pytest.raises(sar.SarError) as e:      # wrong number of source rows: caught by the binding
+        sar.sar_gat_fwd_all(b, [Zs[0][:-1], Zs[1]], s, None, a, SLOPE, out, L)
+    assert e.value.code == sar.SAR_ERR_INVALID_ARG
+    mis = torch.empty(n * H * D + 1, device="cuda")[1:].reshape(n, H, D)      # 4-byte aligned only
+    with pytest.raises(sar.SarError) as e:
+        sar.sar_gat_fwd_all(b, Zs, s, None, a, SLOPE, mis, L)
+    assert e.value.code == sar.SAR_ERR_INVALID_ARG and "aligned" in str(e.value)
+    with pytest.raises(sar.SarError) as e:      # neither tq nor a_l
+        sar.sar_gat_fwd_all(b, Zs, s, None, None, SLOPE, out, L)
+    assert e.value.code == sar.SAR_ERR_INVALID_ARG
+    b.close()
+    with pytest.raises(sar.SarError):
+        b.handle
