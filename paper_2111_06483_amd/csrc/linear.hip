@@ -5,9 +5,11 @@
 // One tiled GEMM kernel C = A B serves the three products through strides.
 // Operands are widened to fp32 while being staged in LDS and multiplied with
 // V_MFMA_F32_32X32X2_F32 (fp32 in, fp32 accumulate), so fp32 configurations
-// keep fp32 accuracy and bf16-stored operands are multiplied exactly.
-// Workgroup tile 128 x 128 x 16, four wavefronts in a 2 x 2 grid, each owning
-// a 64 x 64 patch as 2 x 2 MFMA tiles (64 accumulator registers per lane).
+// keep fp32 accuracy; bf16-stored operands go through V_MFMA_F32_32X32X16_BF16
+// (see below).  Workgroup tile 128 x 128 x 32, four wavefronts in a 2 x 2 grid,
+// each owning a 64 x 64 patch as 2 x 2 MFMA tiles (64 accumulator registers per
+// lane); the next tile is fetched into registers while the current one is
+// multiplied.
 #include <algorithm>
 
 #include "gather_common.h"
@@ -204,6 +206,120 @@ __global__ __launch_bounds__(kGemmThreads) void k_gemm(GemmArgs g)
         }
 }
 
+// ---- bf16-stored operands: bf16 MFMA --------------------------------------
+//
+// With bf16 storage the products are exact in a bf16 MFMA with fp32
+// accumulation, at several times the fp32 MFMA rate.  The fp32 weight matrix is
+// split into two bf16 terms, W = hi + lo (+ an error below 2^-17 |W|), and
+// multiplied in two instructions, which is far below the bf16 rounding of the
+// stored result.  Tiles are staged in LDS as bf16 with the contraction index
+// contiguous, the layout V_MFMA_F32_32X32X16_BF16 wants: lane l supplies
+// A[l%32][8*(l/32) .. +7] and B[8*(l/32) .. +7][l%32].
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+constexpr int kPadH = 8;
+
+template <bool K_FAST>
+__device__ inline void commit_bf16(const float (&v)[kPerThread][4], uint16_t (*hi)[BK + kPadH],
+                                   uint16_t (*lo)[BK + kPadH], int tid)
+{
+#pragma unroll
+    for (int g = 0; g < kPerThread; ++g) {
+        const int e = g * kGemmThreads + tid;
+        uint32_t h[4], l[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            h[c] = f32_to_bf16_rne(v[g][c]);
+            l[c] = lo ? f32_to_bf16_rne(v[g][c] - __uint_as_float(h[c] << 16)) : 0u;
+        }
+        if (K_FAST) {
+            const int kk = (e % (BK / 4)) * 4, x = e / (BK / 4);
+            *reinterpret_cast<uint2*>(&hi[x][kk]) = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+            if (lo) *reinterpret_cast<uint2*>(&lo[x][kk]) = make_uint2(l[0] | (l[1] << 16), l[2] | (l[3] << 16));
+        } else {
+            const int x = (e % (BM / 4)) * 4, kk = e / (BM / 4);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                hi[x + c][kk] = (uint16_t)h[c];
+                if (lo) lo[x + c][kk] = (uint16_t)l[c];
+            }
+        }
+    }
+}
+
+template <typename TA, typename TB, typename TC, bool A_K_FAST, bool B_K_FAST, bool SPLIT_B>
+__global__ __launch_bounds__(kGemmThreads) void k_gemm_bf16(GemmArgs g)
+{
+    __shared__ __attribute__((aligned(16))) uint16_t As[BM][BK + kPadH];
+    __shared__ __attribute__((aligned(16))) uint16_t Bh[BN][BK + kPadH];
+    __shared__ __attribute__((aligned(16))) uint16_t Bl[SPLIT_B ? BN : 1][BK + kPadH];
+    const TA* A = static_cast<const TA*>(g.A);
+    const TB* B = static_cast<const TB*>(g.B);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int64_t m0 = (int64_t)blockIdx.x * BM;
+    const int64_t n0 = (int64_t)blockIdx.y * BN;
+    const int64_t k_beg = (int64_t)blockIdx.z * g.k_slab;
+    const int64_t k_end = std::min<int64_t>(g.Kd, k_beg + g.k_slab);
+
+    float16_t acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+
+    Stage<TA, A_K_FAST> sa;
+    Stage<TB, B_K_FAST> sb;
+    if (k_beg < k_end) {
+        sa.fetch(A, g.lda, m0, g.M, k_beg, k_end, g.vec_a, tid);
+        sb.fetch(B, g.ldb, n0, g.N, k_beg, k_end, g.vec_b, tid);
+    }
+    for (int64_t k0 = k_beg; k0 < k_end; k0 += BK) {
+        commit_bf16<A_K_FAST>(sa.v, As, nullptr, tid);
+        commit_bf16<B_K_FAST>(sb.v, Bh, SPLIT_B ? Bl : nullptr, tid);
+        __syncthreads();
+        if (k0 + BK < k_end) {
+            sa.fetch(A, g.lda, m0, g.M, k0 + BK, k_end, g.vec_a, tid);
+            sb.fetch(B, g.ldb, n0, g.N, k0 + BK, k_end, g.vec_b, tid);
+        }
+#pragma unroll
+        for (int ks = 0; ks < BK; ks += 16) {
+            const int kk = ks + 8 * (lane >> 5);
+            bf16x8_t a[2], bh[2], bl[2];
+#pragma unroll
+            for (int x = 0; x < 2; ++x) {
+                a[x] = *reinterpret_cast<const bf16x8_t*>(&As[wm * 64 + x * 32 + (lane & 31)][kk]);
+                bh[x] = *reinterpret_cast<const bf16x8_t*>(&Bh[wn * 64 + x * 32 + (lane & 31)][kk]);
+                if (SPLIT_B) bl[x] = *reinterpret_cast<const bf16x8_t*>(&Bl[wn * 64 + x * 32 + (lane & 31)][kk]);
+            }
+#pragma unroll
+            for (int x = 0; x < 2; ++x)
+#pragma unroll
+                for (int y = 0; y < 2; ++y) {
+                    acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[x], bh[y], acc[x][y], 0, 0, 0);
+                    if (SPLIT_B) acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[x], bl[y], acc[x][y], 0, 0, 0);
+                }
+        }
+        __syncthreads();
+    }
+
+    TC* C = static_cast<TC*>(g.C) + (int64_t)blockIdx.z * g.c_split;
+#pragma unroll
+    for (int x = 0; x < 2; ++x)
+#pragma unroll
+        for (int y = 0; y < 2; ++y) {
+            const int64_t j = n0 + wn * 64 + y * 32 + (lane & 31);
+            if (j >= g.N) continue;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t i = m0 + wm * 64 + x * 32 + 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
+                if (i < g.M) C[i * g.ldc + j] = from_f32<TC>(acc[x][y][r]);
+            }
+        }
+}
+
 // dW[k] += sum over slabs of partial[slab][k]
 __global__ __launch_bounds__(256) void k_sum_slabs(const float* __restrict__ partial, int n_slabs, int64_t count,
                                                    float* __restrict__ dW)
@@ -273,7 +389,7 @@ extern "C" int sar_linear_fwd(const void* X, const float* W, void* Z, int dtype,
     if (dtype == SAR_F32)
         k_gemm<float, float, float, true, false><<<grid, kGemmThreads, 0, st>>>(g);
     else
-        k_gemm<bf16_t, float, bf16_t, true, false><<<grid, kGemmThreads, 0, st>>>(g);
+        k_gemm_bf16<bf16_t, float, bf16_t, true, false, true><<<grid, kGemmThreads, 0, st>>>(g);
     SAR_LAUNCH_CHECK();
     if (a_score) SAR_TRY(sar_gat_scores(Z, dtype, n, H, D, a_score, score, stream));
     if (a_score2) SAR_TRY(sar_gat_scores(Z, dtype, n, H, D, a_score2, score2, stream));
@@ -315,7 +431,7 @@ extern "C" int sar_linear_bwd(const void* X, const void* dZ, const float* W, flo
         if (dtype == SAR_F32)
             k_gemm<float, float, float, false, false><<<grid, kGemmThreads, 0, st>>>(g);
         else
-            k_gemm<bf16_t, bf16_t, float, false, false><<<grid, kGemmThreads, 0, st>>>(g);
+            k_gemm_bf16<bf16_t, bf16_t, float, false, false, false><<<grid, kGemmThreads, 0, st>>>(g);
         SAR_LAUNCH_CHECK();
         const int64_t count = (int64_t)K * F;
         k_sum_slabs<<<(unsigned)std::min<int64_t>((count + 255) / 256, 4096), 256, 0, st>>>(
@@ -342,7 +458,7 @@ extern "C" int sar_linear_bwd(const void* X, const void* dZ, const float* W, flo
         if (dtype == SAR_F32)
             k_gemm<float, float, float, true, true><<<grid, kGemmThreads, 0, st>>>(g);
         else
-            k_gemm<bf16_t, float, bf16_t, true, true><<<grid, kGemmThreads, 0, st>>>(g);
+            k_gemm_bf16<bf16_t, float, bf16_t, true, true, true><<<grid, kGemmThreads, 0, st>>>(g);
         SAR_LAUNCH_CHECK();
     }
     return SAR_OK;
