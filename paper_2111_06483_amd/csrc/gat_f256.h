@@ -547,7 +547,7 @@ struct Row16<bf16_t> {
 // List entries [r_begin, r_end) of a.rows; partial sums of da_l go to
 // a.partial[(partial_row0 + blockIdx.x) * 256 ...].
 template <typename T, int LPH16, bool ALL>
-__global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_narrow(BwdTabs tabs, BwdP a, int64_t r_begin,
+__global__ __launch_bounds__(kGatherThreads, 4) void k_gat_bwd_narrow(BwdTabs tabs, BwdP a, int64_t r_begin,
                                                                    int64_t r_end, int partial_row0)
 {
     constexpr int kSlots = 4;
@@ -577,9 +577,10 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_narrow(BwdTabs tabs,
     const T* Gp = static_cast<const T*>(a.G);
     const int64_t n_slots = (int64_t)gridDim.x * kWavesPerWG * kSlots;
 
-    float dal[16];
+    // this lane's share of da_l lives in LDS (16 private cells), not in registers
+    float* my_dal = &s_part[wave * kSlots + slot][k * 16];
 #pragma unroll
-    for (int x = 0; x < 16; ++x) dal[x] = 0.f;
+    for (int x = 0; x < 16; ++x) my_dal[x] = 0.f;
 
     // Software pipeline over this lane group's rows: the list entry is read two rows
     // ahead and the row's offsets and own features one row ahead, so that only
@@ -661,15 +662,13 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_narrow(BwdTabs tabs,
 #pragma unroll
         for (int x = 0; x < 16; ++x) {
             v[x] = fmaf(dt, s_al[k * 16 + x], dz[x]);
-            dal[x] = fmaf(dt, zj[x], dal[x]);
+            my_dal[x] = fmaf(dt, zj[x], my_dal[x]);
         }
         Row16<T>::store(static_cast<T*>(s_dZ[q]) + j * kF + k * 16, v);
         if (head_lead) s_dt[q][j * a.H + h] = dt;
     }
 
     // this workgroup's share of da_l
-#pragma unroll
-    for (int x = 0; x < 16; ++x) s_part[wave * kSlots + slot][k * 16 + x] = dal[x];
     __syncthreads();
     for (int f = threadIdx.x; f < kF; f += kGatherThreads) {
         float s = 0.f;
