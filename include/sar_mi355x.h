@@ -108,9 +108,8 @@ const char* sar_last_error(void);
 int sar_version(void);
 
 /* ------------------------------------------------------------------ blocks
- * Sec. 3.2: "for each worker p, SAR constructs N subgraphs G_{p,1..N}; E_{p,q}
- * are all the edges from the vertices in partition q to the vertices in
- * partition p".
+ * Sec. 3.2: worker p holds one subgraph per source partition q; its edge set
+ * E_{p,q} is every edge that starts in partition q and ends in partition p.
  */
 
 /* Build worker p's P blocks from a global edge list.

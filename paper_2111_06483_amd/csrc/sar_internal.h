@@ -12,7 +12,6 @@ namespace sar {
 
 // Records the message for sar_last_error() and returns `code`.
 int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
-void clear_error();
 
 #define SAR_HIP(expr)                                                                   \
     do {                                                                                \

@@ -44,8 +44,7 @@ enum class Mode { kBlock, kAll, kBackward };
 // 64-edge chunks chunk0, chunk0+stride, ...
 template <typename T, int G, Mode M>
 __device__ inline void add_rows(float (&acc)[Vec<T>::N], const SpmmArgs& a, const void* const* ztab,
-                                int beg, int end, int chunk0, int stride, const LaneMap<T, G>& lm,
-                                float inv_scale_unused)
+                                int beg, int end, int chunk0, int stride, const LaneMap<T, G>& lm)
 {
     constexpr int VEC = Vec<T>::N;
     constexpr int SLOTS = kWave / G;
@@ -143,7 +142,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_spmm(SpmmArgs a, PtrTab tab,
     for (int64_t r = blockIdx.x; r < a.n_long; r += gridDim.x) {
         const int i = (int)a.rows[r];
         float acc[VEC] = {};
-        add_rows<T, G, M>(acc, a, ztab, a.indptr[i], a.indptr[i + 1], wave, kWavesPerWG, lm, 1.f);
+        add_rows<T, G, M>(acc, a, ztab, a.indptr[i], a.indptr[i + 1], wave, kWavesPerWG, lm);
         merge_slots<T, G>(acc);
         if (lm.slot == 0)
 #pragma unroll
@@ -165,7 +164,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_spmm(SpmmArgs a, PtrTab tab,
     for (int64_t r = a.n_long + (int64_t)blockIdx.x * kWavesPerWG + wave; r < a.n_rows; r += n_waves) {
         const int i = (int)a.rows[r];
         float acc[VEC] = {};
-        add_rows<T, G, M>(acc, a, ztab, a.indptr[i], a.indptr[i + 1], 0, 1, lm, 1.f);
+        add_rows<T, G, M>(acc, a, ztab, a.indptr[i], a.indptr[i + 1], 0, 1, lm);
         merge_slots<T, G>(acc);
         finish_row<T, G, M>(acc, a, i, lm);
     }
