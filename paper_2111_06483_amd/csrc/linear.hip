@@ -6,7 +6,10 @@
 // Operands are widened to fp32 while being staged in LDS and multiplied with
 // V_MFMA_F32_32X32X2_F32 (fp32 in, fp32 accumulate), so fp32 configurations
 // keep fp32 accuracy; bf16-stored operands go through V_MFMA_F32_32X32X16_BF16
-// (see below).  Workgroup tile 128 x 128 x 32, four wavefronts in a 2 x 2 grid,
+// (see below).  Z = X W and dX = dZ W^T normally take the skinny kernel further
+// down (small operand resident in LDS, big operand straight into registers);
+// the tiled kernel remains for dW and for shapes the skinny one does not cover.
+// Workgroup tile 128 x 128 x 32, four wavefronts in a 2 x 2 grid,
 // each owning a 64 x 64 patch as 2 x 2 MFMA tiles (64 accumulator registers per
 // lane); the next tile is fetched into registers while the current one is
 // multiplied.
@@ -320,6 +323,240 @@ __global__ __launch_bounds__(kGemmThreads) void k_gemm_bf16(GemmArgs g)
         }
 }
 
+// ---- skinny products: the small operand resident in LDS --------------------
+//
+// In Z = X W and dX = dZ W^T the left operand has millions of rows whose
+// contraction index is contiguous in memory, which is exactly what an MFMA A
+// fragment wants from a lane: lane l of a 32-row tile supplies row l%32 and a
+// 16-byte piece of it (4 floats or 8 bf16 values) chosen by l/32.  So the big
+// operand goes from HBM straight into registers, never through LDS.  The small
+// operand (at most a few hundred KB) is laid out in LDS once per workgroup, in
+// the order the B fragments are consumed: one 16-byte unit per lane, 64 units
+// per fragment, so every ds_read_b128 is conflict-free.  After that one
+// barrier the wavefronts never synchronise again: each walks over its own
+// 32-row tiles, keeping NT 32x32 accumulators (32 x NT*32 outputs) in
+// registers and a ring of kPrefetch chunks of its rows in flight.
+//
+// fp32: a chunk is 8 contraction values; lane group g = l/32 holds values
+//       8t+4g .. 8t+4g+3, consumed by four V_MFMA_F32_32X32X2_F32 (whose A and
+//       B operands both take "their k" from the lane group, so any pairing of
+//       k with (step, group) is valid as long as both operands use the same).
+// bf16: a chunk is 16 values, one V_MFMA_F32_32X32X16_BF16 per bf16 half of the
+//       fp32 small operand (hi and lo, as above).
+
+constexpr int kSkinnyWaves = 8;
+constexpr int kSkinnyThreads = 64 * kSkinnyWaves;
+constexpr int kPrefetch = 4;
+constexpr size_t kSkinnyMaxLds = 150 * 1024;
+
+struct SkinnyArgs {
+    const void* A;     // [M, K], row stride lda, contraction index contiguous
+    int64_t lda, M;
+    const float* B;    // B(k, n) = B[k * sbk + n * sbn]
+    int64_t sbk, sbn;
+    void* C;           // [M, N], row stride ldc
+    int64_t ldc;
+    int K, N;
+    int chunks;        // ceil(K / chunk length)
+};
+
+template <typename TA, typename TC, int NT>
+__global__ __launch_bounds__(kSkinnyThreads) void k_gemm_skinny(SkinnyArgs g)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char skinny_lds[];
+    constexpr bool BF = sizeof(TA) == 2;
+    constexpr int kChunk = BF ? 16 : 8;
+    constexpr int kFragsPerTile = BF ? 2 : 1;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 31, gq = lane >> 5;
+    const int64_t n0 = (int64_t)blockIdx.y * (NT * 32);
+    uint4* frag = reinterpret_cast<uint4*>(skinny_lds);
+
+    const int units = g.chunks * NT * kFragsPerTile * 64;
+    for (int u = tid; u < units; u += kSkinnyThreads) {
+        const int l = u & 63;
+        int f = u >> 6, half = 0;
+        if (BF) {
+            half = f & 1;
+            f >>= 1;
+        }
+        const int nt = f % NT, t = f / NT;
+        const int64_t n = n0 + nt * 32 + (l & 31);
+        const int kb = t * kChunk + (l >> 5) * (kChunk / 2);
+        uint32_t w[4];
+        if (!BF) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                w[j] = (kb + j < g.K && n < g.N) ? __float_as_uint(g.B[(int64_t)(kb + j) * g.sbk + n * g.sbn]) : 0u;
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                uint32_t part[2];
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    const int k = kb + 2 * j + e;
+                    const float v = (k < g.K && n < g.N) ? g.B[(int64_t)k * g.sbk + n * g.sbn] : 0.f;
+                    const uint32_t hi = f32_to_bf16_rne(v);
+                    part[e] = half ? f32_to_bf16_rne(v - __uint_as_float(hi << 16)) : hi;
+                }
+                w[j] = part[0] | (part[1] << 16);
+            }
+        }
+        frag[u] = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+    __syncthreads();
+
+    const TA* A = static_cast<const TA*>(g.A);
+    const int64_t n_tiles = (g.M + 31) / 32;
+    const int64_t stride = (int64_t)gridDim.x * kSkinnyWaves;
+    int64_t tile = (int64_t)blockIdx.x * kSkinnyWaves + wave;
+    if (tile >= n_tiles) return;
+
+    // K is a multiple of the lane's piece, so a piece is inside the row or beyond it
+    auto load_piece = [&](const TA* rowp, int t) -> uint4 {
+        const int k = t * kChunk + gq * (kChunk / 2);
+        return k < g.K ? *reinterpret_cast<const uint4*>(rowp + k) : make_uint4(0u, 0u, 0u, 0u);
+    };
+    auto row_ptr = [&](int64_t tl) { return A + std::min<int64_t>(tl * 32 + c, g.M - 1) * g.lda; };
+
+    uint4 a[kPrefetch];
+    const TA* rowp = row_ptr(tile);
+#pragma unroll
+    for (int u = 0; u < kPrefetch; ++u) a[u] = u < g.chunks ? load_piece(rowp, u) : make_uint4(0u, 0u, 0u, 0u);
+
+    for (; tile < n_tiles; tile += stride) {
+        float16_t acc[NT];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[nt][r] = 0.f;
+
+        for (int t0 = 0; t0 < g.chunks; t0 += kPrefetch) {
+#pragma unroll
+            for (int u = 0; u < kPrefetch; ++u) {
+                const int t = t0 + u;
+                if (t < g.chunks) {
+                    const uint4 av = a[u];
+                    if (t + kPrefetch < g.chunks) a[u] = load_piece(rowp, t + kPrefetch);
+                    const uint4* fr = frag + (size_t)t * (NT * kFragsPerTile * 64) + lane;
+                    if (!BF) {
+                        uint4 b[NT];
+#pragma unroll
+                        for (int nt = 0; nt < NT; ++nt) b[nt] = fr[nt * 64];
+#pragma unroll
+                        for (int nt = 0; nt < NT; ++nt)
+                            acc[nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av.x), __uint_as_float(b[nt].x),
+                                                                           acc[nt], 0, 0, 0);
+#pragma unroll
+                        for (int nt = 0; nt < NT; ++nt)
+                            acc[nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av.y), __uint_as_float(b[nt].y),
+                                                                           acc[nt], 0, 0, 0);
+#pragma unroll
+                        for (int nt = 0; nt < NT; ++nt)
+                            acc[nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av.z), __uint_as_float(b[nt].z),
+                                                                           acc[nt], 0, 0, 0);
+#pragma unroll
+                        for (int nt = 0; nt < NT; ++nt)
+                            acc[nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av.w), __uint_as_float(b[nt].w),
+                                                                           acc[nt], 0, 0, 0);
+                    } else {
+                        const bf16x8_t ax = __builtin_bit_cast(bf16x8_t, av);
+#pragma unroll
+                        for (int nt = 0; nt < NT; ++nt) {
+                            const bf16x8_t bh = __builtin_bit_cast(bf16x8_t, fr[(2 * nt) * 64]);
+                            acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ax, bh, acc[nt], 0, 0, 0);
+                        }
+#pragma unroll
+                        for (int nt = 0; nt < NT; ++nt) {
+                            const bf16x8_t bl = __builtin_bit_cast(bf16x8_t, fr[(2 * nt + 1) * 64]);
+                            acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ax, bl, acc[nt], 0, 0, 0);
+                        }
+                    }
+                }
+            }
+        }
+
+        // the next tile's first pieces travel while this one is stored
+        const int64_t row0 = tile * 32;
+        if (tile + stride < n_tiles) {
+            rowp = row_ptr(tile + stride);
+#pragma unroll
+            for (int u = 0; u < kPrefetch; ++u)
+                a[u] = u < g.chunks ? load_piece(rowp, u) : make_uint4(0u, 0u, 0u, 0u);
+        }
+        // lane holds column c; register r holds row 8*(r/4) + 4*(lane/32) + r%4
+        TC* C = static_cast<TC*>(g.C);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const int64_t n = n0 + nt * 32 + c;
+            if (n >= g.N) continue;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t i = row0 + 8 * (r / 4) + 4 * gq + (r % 4);
+                if (i < g.M) C[i * g.ldc + n] = from_f32<TC>(acc[nt][r]);
+            }
+        }
+    }
+}
+
+struct SkinnyPlan {
+    int nt = 0;          // accumulator tiles per workgroup slab (1, 2, 4 or 8)
+    unsigned slabs = 0;  // column slabs of nt*32
+    size_t lds = 0;
+    int chunks = 0;
+};
+
+// Whether the skinny kernel applies: 16-byte pieces of A rows must be aligned
+// and whole, and the small operand must fit in LDS in at most four column slabs.
+bool plan_skinny(const void* A, int64_t lda, int K, int N, int dtype, SkinnyPlan* p)
+{
+    const int elem = dtype == SAR_F32 ? 4 : 2, piece = 16 / elem;
+    if (reinterpret_cast<uintptr_t>(A) % 16 != 0 || (lda * elem) % 16 != 0 || K % piece != 0) return false;
+    const int chunk = 2 * piece;
+    p->chunks = (K + chunk - 1) / chunk;
+    const size_t unit = dtype == SAR_F32 ? 1024 : 2048;
+    const int need = (N + 31) / 32;
+    int nt = 1;
+    while (nt < need && nt < 8) nt *= 2;
+    while (nt >= 1 && (size_t)p->chunks * nt * unit > kSkinnyMaxLds) nt /= 2;
+    if (nt < 1) return false;
+    p->nt = nt;
+    p->slabs = (unsigned)((need + nt - 1) / nt);
+    p->lds = (size_t)p->chunks * nt * unit;
+    return p->slabs <= 4;
+}
+
+template <typename TA, typename TC, int NT>
+int launch_skinny_nt(const SkinnyArgs& g, const SkinnyPlan& p, hipStream_t st)
+{
+    int dev = 0;
+    SAR_HIP(hipGetDevice(&dev));
+    int n_cu = 0;
+    SAR_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+    SAR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_skinny<TA, TC, NT>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.lds));
+    const int64_t tiles = (g.M + 31) / 32;
+    const int64_t want = (tiles + kSkinnyWaves - 1) / kSkinnyWaves;
+    // one workgroup per CU; two where registers (NT <= 4) and LDS leave room
+    const int per_cu = (NT <= 4 && 2 * p.lds <= kSkinnyMaxLds) ? 2 : 1;
+    const int64_t resident = std::max<int64_t>(1, (int64_t)n_cu * per_cu / p.slabs);
+    dim3 grid((unsigned)std::max<int64_t>(1, std::min(want, resident)), p.slabs, 1);
+    k_gemm_skinny<TA, TC, NT><<<grid, kSkinnyThreads, p.lds, st>>>(g);
+    SAR_LAUNCH_CHECK();
+    return SAR_OK;
+}
+
+template <typename TA, typename TC>
+int launch_skinny(const SkinnyArgs& g, const SkinnyPlan& p, hipStream_t st)
+{
+    switch (p.nt) {
+        case 1: return launch_skinny_nt<TA, TC, 1>(g, p, st);
+        case 2: return launch_skinny_nt<TA, TC, 2>(g, p, st);
+        case 4: return launch_skinny_nt<TA, TC, 4>(g, p, st);
+        default: return launch_skinny_nt<TA, TC, 8>(g, p, st);
+    }
+}
+
 // dW[k] += sum over slabs of partial[slab][k]
 __global__ __launch_bounds__(256) void k_sum_slabs(const float* __restrict__ partial, int n_slabs, int64_t count,
                                                    float* __restrict__ dW)
@@ -385,12 +622,21 @@ extern "C" int sar_linear_fwd(const void* X, const float* W, void* Z, int dtype,
     g.c_split = 0;
     g.vec_a = vec_ok(X, K, dtype == SAR_F32 ? 4 : 2);
     g.vec_b = vec_ok(W, F, 4);
-    dim3 grid((unsigned)((n + BM - 1) / BM), (unsigned)((F + BN - 1) / BN), 1);
-    if (dtype == SAR_F32)
-        k_gemm<float, float, float, true, false><<<grid, kGemmThreads, 0, st>>>(g);
-    else
-        k_gemm_bf16<bf16_t, float, bf16_t, true, false, true><<<grid, kGemmThreads, 0, st>>>(g);
-    SAR_LAUNCH_CHECK();
+    SkinnyPlan plan;
+    if (plan_skinny(X, K, K, F, dtype, &plan)) {
+        SkinnyArgs sk{X, K, n, W, F, 1, Z, F, K, F, plan.chunks};
+        if (dtype == SAR_F32)
+            SAR_TRY((launch_skinny<float, float>(sk, plan, st)));
+        else
+            SAR_TRY((launch_skinny<bf16_t, bf16_t>(sk, plan, st)));
+    } else {
+        dim3 grid((unsigned)((n + BM - 1) / BM), (unsigned)((F + BN - 1) / BN), 1);
+        if (dtype == SAR_F32)
+            k_gemm<float, float, float, true, false><<<grid, kGemmThreads, 0, st>>>(g);
+        else
+            k_gemm_bf16<bf16_t, float, bf16_t, true, false, true><<<grid, kGemmThreads, 0, st>>>(g);
+        SAR_LAUNCH_CHECK();
+    }
     if (a_score) SAR_TRY(sar_gat_scores(Z, dtype, n, H, D, a_score, score, stream));
     if (a_score2) SAR_TRY(sar_gat_scores(Z, dtype, n, H, D, a_score2, score2, stream));
     return SAR_OK;
@@ -454,12 +700,22 @@ extern "C" int sar_linear_bwd(const void* X, const void* dZ, const float* W, flo
         g.c_split = 0;
         g.vec_a = vec_ok(dZ, F, dtype == SAR_F32 ? 4 : 2);
         g.vec_b = vec_ok(W, F, 4);
-        dim3 grid((unsigned)((n + BM - 1) / BM), (unsigned)((K + BN - 1) / BN), 1);
-        if (dtype == SAR_F32)
-            k_gemm<float, float, float, true, true><<<grid, kGemmThreads, 0, st>>>(g);
-        else
-            k_gemm_bf16<bf16_t, float, bf16_t, true, true, true><<<grid, kGemmThreads, 0, st>>>(g);
-        SAR_LAUNCH_CHECK();
+        SkinnyPlan plan;
+        if (plan_skinny(dZ, F, F, K, dtype, &plan)) {
+            // B(k = f, n = kcol) = W[kcol * F + f]
+            SkinnyArgs sk{dZ, F, n, W, 1, F, dX, K, F, K, plan.chunks};
+            if (dtype == SAR_F32)
+                SAR_TRY((launch_skinny<float, float>(sk, plan, st)));
+            else
+                SAR_TRY((launch_skinny<bf16_t, bf16_t>(sk, plan, st)));
+        } else {
+            dim3 grid((unsigned)((n + BM - 1) / BM), (unsigned)((K + BN - 1) / BN), 1);
+            if (dtype == SAR_F32)
+                k_gemm<float, float, float, true, true><<<grid, kGemmThreads, 0, st>>>(g);
+            else
+                k_gemm_bf16<bf16_t, float, bf16_t, true, true, true><<<grid, kGemmThreads, 0, st>>>(g);
+            SAR_LAUNCH_CHECK();
+        }
     }
     return SAR_OK;
 }

@@ -319,7 +319,8 @@ def test_config1_full():
 # ------------------------------------------------------------------- linear
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
-@pytest.mark.parametrize("n,K,F", [(1000, 100, 256), (333, 64, 64), (4097, 128, 256), (130, 256, 40)])
+@pytest.mark.parametrize("n,K,F", [(1000, 100, 256), (333, 64, 64), (4097, 128, 256), (130, 256, 40),
+                                   (2050, 104, 800), (517, 36, 200), (700, 602, 64), (31, 8, 8), (77, 30, 50)])
 def test_linear_parity(dtype, n, K, F):
     rng = np.random.default_rng(10)
     X = feats(rng, n, K, dtype).cuda()
