@@ -358,11 +358,19 @@ struct SkinnyArgs {
     int64_t ldc;
     int K, N;
     int chunks;        // ceil(K / chunk length)
+    // score projections (Eq. 3: the two halves of a^T (z_i || z_j)) as one more
+    // accumulator tile: column h of it is x . (W_h a1_h), column H+h is x . (W_h a2_h)
+    const float* a1;   // [H, D] or null
+    const float* a2;
+    float* s1;         // [M, H] or null
+    float* s2;
+    int H, D;
 };
 
-template <typename TA, typename TC, int NT>
+template <typename TA, typename TC, int NT, bool SC>
 __global__ __launch_bounds__(kSkinnyThreads) void k_gemm_skinny(SkinnyArgs g)
 {
+    constexpr int NA = NT + (SC ? 1 : 0);   // accumulator tiles: NT of the product, one of scores
     extern __shared__ __attribute__((aligned(16))) unsigned char skinny_lds[];
     constexpr bool BF = sizeof(TA) == 2;
     constexpr int kChunk = BF ? 16 : 8;
@@ -372,7 +380,7 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_gemm_skinny(SkinnyArgs g)
     const int64_t n0 = (int64_t)blockIdx.y * (NT * 32);
     uint4* frag = reinterpret_cast<uint4*>(skinny_lds);
 
-    const int units = g.chunks * NT * kFragsPerTile * 64;
+    const int units = g.chunks * NA * kFragsPerTile * 64;
     for (int u = tid; u < units; u += kSkinnyThreads) {
         const int l = u & 63;
         int f = u >> 6, half = 0;
@@ -380,8 +388,9 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_gemm_skinny(SkinnyArgs g)
             half = f & 1;
             f >>= 1;
         }
-        const int nt = f % NT, t = f / NT;
-        const int64_t n = n0 + nt * 32 + (l & 31);
+        const int nt = f % NA, t = f / NA;
+        // the score tile starts as zeros; its entries are written below
+        const int64_t n = (SC && nt == NT) ? g.N : n0 + nt * 32 + (l & 31);
         const int kb = t * kChunk + (l >> 5) * (kChunk / 2);
         uint32_t w[4];
         if (!BF) {
@@ -404,6 +413,32 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_gemm_skinny(SkinnyArgs g)
         }
         frag[u] = make_uint4(w[0], w[1], w[2], w[3]);
     }
+    if (SC) {
+        // (W a)[k][h] = sum_d W[k][h*D + d] a[h][d]: z_h . a_h = x . (W_h a_h), so the scores
+        // are 2H more output columns of the same product, taken from the unrounded sums
+        __syncthreads();
+        const int cols = 2 * g.H;
+        for (int p = tid; p < g.K * cols; p += kSkinnyThreads) {
+            const int k = p / cols, col = p % cols;
+            const int h = col < g.H ? col : col - g.H;
+            const float* av = col < g.H ? g.a1 : g.a2;
+            float v = 0.f;
+            if (av) {
+                const float* wrow = g.B + (int64_t)k * g.sbk + (int64_t)h * g.D * g.sbn;
+                for (int d = 0; d < g.D; ++d) v = fmaf(wrow[d * g.sbn], av[h * g.D + d], v);
+            }
+            const int t = k / kChunk, gk = (k / (kChunk / 2)) & 1, e = k % (kChunk / 2);
+            if (!BF) {
+                reinterpret_cast<float*>(frag)[(((size_t)t * NA + NT) * 64 + gk * 32 + col) * 4 + e] = v;
+            } else {
+                uint16_t* fh = reinterpret_cast<uint16_t*>(frag);
+                const uint32_t hi = f32_to_bf16_rne(v);
+                const size_t at = ((size_t)t * NA + NT) * 2 * 64 + gk * 32 + col;
+                fh[at * 8 + e] = (uint16_t)hi;
+                fh[(at + 64) * 8 + e] = (uint16_t)f32_to_bf16_rne(v - __uint_as_float(hi << 16));
+            }
+        }
+    }
     __syncthreads();
 
     const TA* A = static_cast<const TA*>(g.A);
@@ -425,9 +460,9 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_gemm_skinny(SkinnyArgs g)
     for (int u = 0; u < kPrefetch; ++u) a[u] = u < g.chunks ? load_piece(rowp, u) : make_uint4(0u, 0u, 0u, 0u);
 
     for (; tile < n_tiles; tile += stride) {
-        float16_t acc[NT];
+        float16_t acc[NA];
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
+        for (int nt = 0; nt < NA; ++nt)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[nt][r] = 0.f;
 
@@ -438,36 +473,36 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_gemm_skinny(SkinnyArgs g)
                 if (t < g.chunks) {
                     const uint4 av = a[u];
                     if (t + kPrefetch < g.chunks) a[u] = load_piece(rowp, t + kPrefetch);
-                    const uint4* fr = frag + (size_t)t * (NT * kFragsPerTile * 64) + lane;
+                    const uint4* fr = frag + (size_t)t * (NA * kFragsPerTile * 64) + lane;
                     if (!BF) {
-                        uint4 b[NT];
+                        uint4 b[NA];
 #pragma unroll
-                        for (int nt = 0; nt < NT; ++nt) b[nt] = fr[nt * 64];
+                        for (int nt = 0; nt < NA; ++nt) b[nt] = fr[nt * 64];
 #pragma unroll
-                        for (int nt = 0; nt < NT; ++nt)
+                        for (int nt = 0; nt < NA; ++nt)
                             acc[nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av.x), __uint_as_float(b[nt].x),
                                                                            acc[nt], 0, 0, 0);
 #pragma unroll
-                        for (int nt = 0; nt < NT; ++nt)
+                        for (int nt = 0; nt < NA; ++nt)
                             acc[nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av.y), __uint_as_float(b[nt].y),
                                                                            acc[nt], 0, 0, 0);
 #pragma unroll
-                        for (int nt = 0; nt < NT; ++nt)
+                        for (int nt = 0; nt < NA; ++nt)
                             acc[nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av.z), __uint_as_float(b[nt].z),
                                                                            acc[nt], 0, 0, 0);
 #pragma unroll
-                        for (int nt = 0; nt < NT; ++nt)
+                        for (int nt = 0; nt < NA; ++nt)
                             acc[nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av.w), __uint_as_float(b[nt].w),
                                                                            acc[nt], 0, 0, 0);
                     } else {
                         const bf16x8_t ax = __builtin_bit_cast(bf16x8_t, av);
 #pragma unroll
-                        for (int nt = 0; nt < NT; ++nt) {
+                        for (int nt = 0; nt < NA; ++nt) {
                             const bf16x8_t bh = __builtin_bit_cast(bf16x8_t, fr[(2 * nt) * 64]);
                             acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ax, bh, acc[nt], 0, 0, 0);
                         }
 #pragma unroll
-                        for (int nt = 0; nt < NT; ++nt) {
+                        for (int nt = 0; nt < NA; ++nt) {
                             const bf16x8_t bl = __builtin_bit_cast(bf16x8_t, fr[(2 * nt + 1) * 64]);
                             acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ax, bl, acc[nt], 0, 0, 0);
                         }
@@ -496,6 +531,17 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_gemm_skinny(SkinnyArgs g)
                 if (i < g.M) C[i * g.ldc + n] = from_f32<TC>(acc[nt][r]);
             }
         }
+        if (SC && blockIdx.y == 0 && c < 2 * g.H) {
+            float* dst = c < g.H ? g.s1 : g.s2;
+            const int h = c < g.H ? c : c - g.H;
+            if (dst) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int64_t i = row0 + 8 * (r / 4) + 4 * gq + (r % 4);
+                    if (i < g.M) dst[i * g.H + h] = acc[NA - 1][r];
+                }
+            }
+        }
     }
 }
 
@@ -508,7 +554,7 @@ struct SkinnyPlan {
 
 // Whether the skinny kernel applies: 16-byte pieces of A rows must be aligned
 // and whole, and the small operand must fit in LDS in at most four column slabs.
-bool plan_skinny(const void* A, int64_t lda, int K, int N, int dtype, SkinnyPlan* p)
+bool plan_skinny(const void* A, int64_t lda, int K, int N, int dtype, int extra_tiles, SkinnyPlan* p)
 {
     const int elem = dtype == SAR_F32 ? 4 : 2, piece = 16 / elem;
     if (reinterpret_cast<uintptr_t>(A) % 16 != 0 || (lda * elem) % 16 != 0 || K % piece != 0) return false;
@@ -518,22 +564,22 @@ bool plan_skinny(const void* A, int64_t lda, int K, int N, int dtype, SkinnyPlan
     const int need = (N + 31) / 32;
     int nt = 1;
     while (nt < need && nt < 8) nt *= 2;
-    while (nt >= 1 && (size_t)p->chunks * nt * unit > kSkinnyMaxLds) nt /= 2;
+    while (nt >= 1 && (size_t)p->chunks * (nt + extra_tiles) * unit > kSkinnyMaxLds) nt /= 2;
     if (nt < 1) return false;
     p->nt = nt;
     p->slabs = (unsigned)((need + nt - 1) / nt);
-    p->lds = (size_t)p->chunks * nt * unit;
+    p->lds = (size_t)p->chunks * (nt + extra_tiles) * unit;
     return p->slabs <= 4;
 }
 
-template <typename TA, typename TC, int NT>
+template <typename TA, typename TC, int NT, bool SC>
 int launch_skinny_nt(const SkinnyArgs& g, const SkinnyPlan& p, hipStream_t st)
 {
     int dev = 0;
     SAR_HIP(hipGetDevice(&dev));
     int n_cu = 0;
     SAR_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
-    SAR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_skinny<TA, TC, NT>),
+    SAR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_skinny<TA, TC, NT, SC>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.lds));
     const int64_t tiles = (g.M + 31) / 32;
     const int64_t want = (tiles + kSkinnyWaves - 1) / kSkinnyWaves;
@@ -541,19 +587,19 @@ int launch_skinny_nt(const SkinnyArgs& g, const SkinnyPlan& p, hipStream_t st)
     const int per_cu = (NT <= 4 && 2 * p.lds <= kSkinnyMaxLds) ? 2 : 1;
     const int64_t resident = std::max<int64_t>(1, (int64_t)n_cu * per_cu / p.slabs);
     dim3 grid((unsigned)std::max<int64_t>(1, std::min(want, resident)), p.slabs, 1);
-    k_gemm_skinny<TA, TC, NT><<<grid, kSkinnyThreads, p.lds, st>>>(g);
+    k_gemm_skinny<TA, TC, NT, SC><<<grid, kSkinnyThreads, p.lds, st>>>(g);
     SAR_LAUNCH_CHECK();
     return SAR_OK;
 }
 
-template <typename TA, typename TC>
+template <typename TA, typename TC, bool SC>
 int launch_skinny(const SkinnyArgs& g, const SkinnyPlan& p, hipStream_t st)
 {
     switch (p.nt) {
-        case 1: return launch_skinny_nt<TA, TC, 1>(g, p, st);
-        case 2: return launch_skinny_nt<TA, TC, 2>(g, p, st);
-        case 4: return launch_skinny_nt<TA, TC, 4>(g, p, st);
-        default: return launch_skinny_nt<TA, TC, 8>(g, p, st);
+        case 1: return launch_skinny_nt<TA, TC, 1, SC>(g, p, st);
+        case 2: return launch_skinny_nt<TA, TC, 2, SC>(g, p, st);
+        case 4: return launch_skinny_nt<TA, TC, 4, SC>(g, p, st);
+        default: return launch_skinny_nt<TA, TC, 8, SC>(g, p, st);
     }
 }
 
@@ -623,12 +669,21 @@ extern "C" int sar_linear_fwd(const void* X, const float* W, void* Z, int dtype,
     g.vec_a = vec_ok(X, K, dtype == SAR_F32 ? 4 : 2);
     g.vec_b = vec_ok(W, F, 4);
     SkinnyPlan plan;
-    if (plan_skinny(X, K, K, F, dtype, &plan)) {
-        SkinnyArgs sk{X, K, n, W, F, 1, Z, F, K, F, plan.chunks};
+    const bool want_scores = a_score || a_score2;
+    if (want_scores && 2 * H <= 32 && plan_skinny(X, K, K, F, dtype, 1, &plan)) {
+        SkinnyArgs sk{X, K, n, W, F, 1, Z, F, K, F, plan.chunks, a_score, a_score2, score, score2, H, D};
         if (dtype == SAR_F32)
-            SAR_TRY((launch_skinny<float, float>(sk, plan, st)));
+            SAR_TRY((launch_skinny<float, float, true>(sk, plan, st)));
         else
-            SAR_TRY((launch_skinny<bf16_t, bf16_t>(sk, plan, st)));
+            SAR_TRY((launch_skinny<bf16_t, bf16_t, true>(sk, plan, st)));
+        return SAR_OK;
+    }
+    if (plan_skinny(X, K, K, F, dtype, 0, &plan)) {
+        SkinnyArgs sk{X, K, n, W, F, 1, Z, F, K, F, plan.chunks, nullptr, nullptr, nullptr, nullptr, 0, 0};
+        if (dtype == SAR_F32)
+            SAR_TRY((launch_skinny<float, float, false>(sk, plan, st)));
+        else
+            SAR_TRY((launch_skinny<bf16_t, bf16_t, false>(sk, plan, st)));
     } else {
         dim3 grid((unsigned)((n + BM - 1) / BM), (unsigned)((F + BN - 1) / BN), 1);
         if (dtype == SAR_F32)
@@ -701,13 +756,13 @@ extern "C" int sar_linear_bwd(const void* X, const void* dZ, const float* W, flo
         g.vec_a = vec_ok(dZ, F, dtype == SAR_F32 ? 4 : 2);
         g.vec_b = vec_ok(W, F, 4);
         SkinnyPlan plan;
-        if (plan_skinny(dZ, F, F, K, dtype, &plan)) {
+        if (plan_skinny(dZ, F, F, K, dtype, 0, &plan)) {
             // B(k = f, n = kcol) = W[kcol * F + f]
-            SkinnyArgs sk{dZ, F, n, W, 1, F, dX, K, F, K, plan.chunks};
+            SkinnyArgs sk{dZ, F, n, W, 1, F, dX, K, F, K, plan.chunks, nullptr, nullptr, nullptr, nullptr, 0, 0};
             if (dtype == SAR_F32)
-                SAR_TRY((launch_skinny<float, float>(sk, plan, st)));
+                SAR_TRY((launch_skinny<float, float, false>(sk, plan, st)));
             else
-                SAR_TRY((launch_skinny<bf16_t, bf16_t>(sk, plan, st)));
+                SAR_TRY((launch_skinny<bf16_t, bf16_t, false>(sk, plan, st)));
         } else {
             dim3 grid((unsigned)((n + BM - 1) / BM), (unsigned)((K + BN - 1) / BN), 1);
             if (dtype == SAR_F32)

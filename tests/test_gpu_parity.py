@@ -338,6 +338,29 @@ def test_linear_parity(dtype, n, K, F):
     assert rel_err(f64(dW), 2 * want_dW) < 1e-4
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("n,K,H,D", [(1500, 100, 4, 64), (700, 128, 8, 32), (333, 64, 1, 256), (260, 40, 2, 100),
+                                     (90, 30, 3, 24), (300, 64, 20, 8), (500, 602, 4, 16)])
+def test_linear_scores_parity(dtype, n, K, H, D):
+    """The two score projections of Eq. 3 that come out of the transform: s = a1 . z and
+    t = a2 . z per head, against the oracle's scores of its own fp64 Z = X W."""
+    rng = np.random.default_rng(13)
+    F = H * D
+    X = feats(rng, n, K, dtype).cuda()
+    W = torch.from_numpy((rng.standard_normal((K, F)) * 0.1).astype(np.float32)).cuda()
+    a1 = torch.from_numpy(rng.standard_normal((H, D)).astype(np.float32)).cuda()
+    a2 = torch.from_numpy(rng.standard_normal((H, D)).astype(np.float32)).cuda()
+    Z, s, t = gu.linear_fwd(X, W, a1, a2)
+    wantZ = orc.linear_fwd(f64(X), f64(W))
+    tol = 1e-4 if dtype == torch.float32 else 2e-2
+    assert rel_err(f64(Z), wantZ) < tol
+    assert rel_err(f64(s), orc.gat_scores(wantZ.reshape(n, H, D), f64(a1))) < tol
+    assert rel_err(f64(t), orc.gat_scores(wantZ.reshape(n, H, D), f64(a2))) < tol
+    # one projection only
+    _, s_only, _ = gu.linear_fwd(X, W, a1, None)
+    assert torch.equal(s_only, s)
+
+
 # ------------------------------------------------------- streams, determinism, errors
 
 def test_stream_argument_and_determinism():
