@@ -603,18 +603,194 @@ int launch_skinny(const SkinnyArgs& g, const SkinnyPlan& p, hipStream_t st)
     }
 }
 
-// dW[k] += sum over slabs of partial[slab][k]
+// ---- dW = X^T dZ: contraction over the rows ---------------------------------
+//
+// Here both operands have the contraction index (the node) as their slow
+// dimension, the opposite of what an MFMA fragment wants from a lane.  A
+// workgroup copies chunks of rows of X (up to 128 columns) and dZ (up to 256
+// columns) into LDS as they are (16-byte accesses both sides, double
+// buffered, one barrier per chunk) and the wavefronts read their fragments
+// column-wise from there: one element per lane and row, which costs LDS
+// instructions but no bank conflicts (row strides put the two lane groups of
+// a fragment on different banks).  The output tile is 128 x 256: four kf-tiles
+// by two n-tiles per wavefront, 128 accumulator registers.  Rows are split
+// into slabs over the grid; each slab writes its partial tile, summed below.
+
+constexpr int kDwKf = 128, kDwN = 256;
+
+template <typename T>
+struct DwShape;
+template <>
+struct DwShape<float> {
+    static constexpr int kRows = 16;          // rows per chunk
+    static constexpr int kXs = kDwKf + 32;    // LDS row strides in elements: consecutive rows
+    static constexpr int kDs = kDwN + 32;     // (the two lane groups) 32 banks apart
+    static constexpr int kVec = 4;            // elements per 16 bytes
+};
+template <>
+struct DwShape<bf16_t> {
+    static constexpr int kRows = 32;
+    static constexpr int kXs = kDwKf + 8;     // rows 8 apart (the two lane groups) 32 banks apart
+    static constexpr int kDs = kDwN + 8;
+    static constexpr int kVec = 8;
+};
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_dw(const T* __restrict__ X, const T* __restrict__ dZ,
+                                            float* __restrict__ partial, int64_t M, int K, int N,
+                                            int64_t rows_per_slab)
+{
+    using S = DwShape<T>;
+    constexpr bool BF = sizeof(T) == 2;
+    constexpr int kXUnits = S::kRows * kDwKf / S::kVec / 256;   // 16-byte units per thread and chunk
+    constexpr int kDUnits = S::kRows * kDwN / S::kVec / 256;
+    __shared__ __attribute__((aligned(16))) T Xs[2][S::kRows][S::kXs];
+    __shared__ __attribute__((aligned(16))) T Ds[2][S::kRows][S::kDs];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 31, gq = lane >> 5;
+    const int kf0 = blockIdx.z * kDwKf, n0 = blockIdx.y * kDwN;
+    const int64_t m_beg = (int64_t)blockIdx.x * rows_per_slab;
+    const int64_t m_end = std::min<int64_t>(M, m_beg + rows_per_slab);
+
+    uint4 gx[kXUnits], gd[kDUnits];
+    auto fetch = [&](int64_t m0) {
+#pragma unroll
+        for (int q = 0; q < kXUnits; ++q) {
+            const int u = tid + 256 * q, row = u / (kDwKf / S::kVec), col = (u % (kDwKf / S::kVec)) * S::kVec;
+            const bool ok = m0 + row < m_end && kf0 + col < K;
+            gx[q] = ok ? *reinterpret_cast<const uint4*>(X + (m0 + row) * K + kf0 + col) : make_uint4(0u, 0u, 0u, 0u);
+        }
+#pragma unroll
+        for (int q = 0; q < kDUnits; ++q) {
+            const int u = tid + 256 * q, row = u / (kDwN / S::kVec), col = (u % (kDwN / S::kVec)) * S::kVec;
+            const bool ok = m0 + row < m_end && n0 + col < N;
+            gd[q] = ok ? *reinterpret_cast<const uint4*>(dZ + (m0 + row) * N + n0 + col) : make_uint4(0u, 0u, 0u, 0u);
+        }
+    };
+    auto commit = [&](int buf) {
+#pragma unroll
+        for (int q = 0; q < kXUnits; ++q) {
+            const int u = tid + 256 * q, row = u / (kDwKf / S::kVec), col = (u % (kDwKf / S::kVec)) * S::kVec;
+            *reinterpret_cast<uint4*>(&Xs[buf][row][col]) = gx[q];
+        }
+#pragma unroll
+        for (int q = 0; q < kDUnits; ++q) {
+            const int u = tid + 256 * q, row = u / (kDwN / S::kVec), col = (u % (kDwN / S::kVec)) * S::kVec;
+            *reinterpret_cast<uint4*>(&Ds[buf][row][col]) = gd[q];
+        }
+    };
+
+    float16_t acc[4][2];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+
+    if (m_beg < m_end) {
+        fetch(m_beg);
+        commit(0);
+    }
+    __syncthreads();
+    int buf = 0;
+    for (int64_t m0 = m_beg; m0 < m_end; m0 += S::kRows, buf ^= 1) {
+        const bool more = m0 + S::kRows < m_end;
+        if (more) fetch(m0 + S::kRows);
+        if (BF) {
+            const uint16_t(*xs)[S::kXs] = reinterpret_cast<const uint16_t(*)[S::kXs]>(Xs[buf]);
+            const uint16_t(*ds)[S::kDs] = reinterpret_cast<const uint16_t(*)[S::kDs]>(Ds[buf]);
+#pragma unroll
+            for (int s = 0; s < S::kRows / 16; ++s) {
+                const int r0 = 16 * s + 8 * gq;
+                bf16x8_t a[4], b[2];
+#pragma unroll
+                for (int kt = 0; kt < 4; ++kt) {
+                    uint32_t w[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        w[e] = (uint32_t)xs[r0 + 2 * e][32 * kt + c] | ((uint32_t)xs[r0 + 2 * e + 1][32 * kt + c] << 16);
+                    a[kt] = __builtin_bit_cast(bf16x8_t, make_uint4(w[0], w[1], w[2], w[3]));
+                }
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt) {
+                    uint32_t w[4];
+                    const int col = 64 * wave + 32 * nt + c;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        w[e] = (uint32_t)ds[r0 + 2 * e][col] | ((uint32_t)ds[r0 + 2 * e + 1][col] << 16);
+                    b[nt] = __builtin_bit_cast(bf16x8_t, make_uint4(w[0], w[1], w[2], w[3]));
+                }
+#pragma unroll
+                for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+                    for (int nt = 0; nt < 2; ++nt)
+                        acc[kt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kt], b[nt], acc[kt][nt], 0, 0, 0);
+            }
+        } else {
+            const float(*xs)[S::kXs] = reinterpret_cast<const float(*)[S::kXs]>(Xs[buf]);
+            const float(*ds)[S::kDs] = reinterpret_cast<const float(*)[S::kDs]>(Ds[buf]);
+#pragma unroll
+            for (int s = 0; s < S::kRows / 2; ++s) {
+                const int r0 = 2 * s + gq;
+                float a[4], b[2];
+#pragma unroll
+                for (int kt = 0; kt < 4; ++kt) a[kt] = xs[r0][32 * kt + c];
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt) b[nt] = ds[r0][64 * wave + 32 * nt + c];
+#pragma unroll
+                for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+                    for (int nt = 0; nt < 2; ++nt)
+                        acc[kt][nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[kt], b[nt], acc[kt][nt], 0, 0, 0);
+            }
+        }
+        if (more) commit(buf ^ 1);
+        __syncthreads();
+    }
+
+    // lane holds column c; register r holds row 8*(r/4) + 4*(lane/32) + r%4
+    float* out = partial + (int64_t)blockIdx.x * K * N;
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+            const int n = n0 + 64 * wave + 32 * nt + c;
+            if (n >= N) continue;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int kf = kf0 + 32 * kt + 8 * (r / 4) + 4 * gq + (r % 4);
+                if (kf < K) out[(int64_t)kf * N + n] = acc[kt][nt][r];
+            }
+        }
+}
+
+// dW[k] += sum over slabs of partial[slab][k].  32 consecutive elements per
+// workgroup, eight threads per element taking every eighth slab; the eight
+// partial sums are added in a fixed order, so the result is reproducible.
 __global__ __launch_bounds__(256) void k_sum_slabs(const float* __restrict__ partial, int n_slabs, int64_t count,
                                                    float* __restrict__ dW)
 {
-    for (int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x; k < count; k += (int64_t)gridDim.x * 256) {
+    __shared__ float part[8][32];
+    const int e = threadIdx.x & 31, zl = threadIdx.x >> 5;
+    for (int64_t k0 = (int64_t)blockIdx.x * 32; k0 < count; k0 += (int64_t)gridDim.x * 32) {
+        const int64_t k = k0 + e;
         float s = 0.f;
-        for (int z = 0; z < n_slabs; ++z) s += partial[(int64_t)z * count + k];
-        dW[k] += s;
+        if (k < count)
+            for (int z = zl; z < n_slabs; z += 8) s += partial[(int64_t)z * count + k];
+        part[zl][e] = s;
+        __syncthreads();
+        if (zl == 0 && k < count) {
+            float t = part[0][e];
+#pragma unroll
+            for (int j = 1; j < 8; ++j) t += part[j][e];
+            dW[k] += t;
+        }
+        __syncthreads();
     }
 }
 
-constexpr int kMaxSlabs = 256;
+constexpr int kMaxSlabs = 512;
 
 int slabs_for(int64_t n, int K, int F)
 {
@@ -714,28 +890,43 @@ extern "C" int sar_linear_bwd(const void* X, const void* dZ, const float* W, flo
         SAR_CHECK_ARG(work != nullptr && work_bytes >= need, "work_bytes=%zu is below the %zu bytes required",
                       work_bytes, need);
         // dW[K,F] = X^T dZ, contraction over the n rows, split into slabs
-        GemmArgs g{};
-        g.A = X;
-        g.B = dZ;
-        g.C = work;
-        g.M = K;
-        g.N = F;
-        g.Kd = n;
-        g.lda = K;
-        g.ldb = F;
-        g.ldc = F;
-        g.k_slab = ((n + slabs - 1) / slabs + BK - 1) / BK * BK;
-        g.c_split = (int64_t)K * F;
-        g.vec_a = vec_ok(X, K, dtype == SAR_F32 ? 4 : 2);
-        g.vec_b = vec_ok(dZ, F, dtype == SAR_F32 ? 4 : 2);
-        dim3 grid((unsigned)((K + BM - 1) / BM), (unsigned)((F + BN - 1) / BN), (unsigned)slabs);
-        if (dtype == SAR_F32)
-            k_gemm<float, float, float, false, false><<<grid, kGemmThreads, 0, st>>>(g);
-        else
-            k_gemm_bf16<bf16_t, bf16_t, float, false, false, false><<<grid, kGemmThreads, 0, st>>>(g);
-        SAR_LAUNCH_CHECK();
+        const int elem = dtype == SAR_F32 ? 4 : 2, vec = 16 / elem;
+        if (K % vec == 0 && F % vec == 0 && reinterpret_cast<uintptr_t>(X) % 16 == 0 &&
+            reinterpret_cast<uintptr_t>(dZ) % 16 == 0) {
+            const int chunk = dtype == SAR_F32 ? DwShape<float>::kRows : DwShape<bf16_t>::kRows;
+            const int64_t rows_per_slab = ((n + slabs - 1) / slabs + chunk - 1) / chunk * chunk;
+            dim3 grid((unsigned)slabs, (unsigned)((F + kDwN - 1) / kDwN), (unsigned)((K + kDwKf - 1) / kDwKf));
+            if (dtype == SAR_F32)
+                k_dw<float><<<grid, 256, 0, st>>>(static_cast<const float*>(X), static_cast<const float*>(dZ),
+                                                  static_cast<float*>(work), n, K, F, rows_per_slab);
+            else
+                k_dw<bf16_t><<<grid, 256, 0, st>>>(static_cast<const bf16_t*>(X), static_cast<const bf16_t*>(dZ),
+                                                   static_cast<float*>(work), n, K, F, rows_per_slab);
+            SAR_LAUNCH_CHECK();
+        } else {
+            GemmArgs g{};
+            g.A = X;
+            g.B = dZ;
+            g.C = work;
+            g.M = K;
+            g.N = F;
+            g.Kd = n;
+            g.lda = K;
+            g.ldb = F;
+            g.ldc = F;
+            g.k_slab = ((n + slabs - 1) / slabs + BK - 1) / BK * BK;
+            g.c_split = (int64_t)K * F;
+            g.vec_a = vec_ok(X, K, elem);
+            g.vec_b = vec_ok(dZ, F, elem);
+            dim3 grid((unsigned)((K + BM - 1) / BM), (unsigned)((F + BN - 1) / BN), (unsigned)slabs);
+            if (dtype == SAR_F32)
+                k_gemm<float, float, float, false, false><<<grid, kGemmThreads, 0, st>>>(g);
+            else
+                k_gemm_bf16<bf16_t, bf16_t, float, false, false, false><<<grid, kGemmThreads, 0, st>>>(g);
+            SAR_LAUNCH_CHECK();
+        }
         const int64_t count = (int64_t)K * F;
-        k_sum_slabs<<<(unsigned)std::min<int64_t>((count + 255) / 256, 4096), 256, 0, st>>>(
+        k_sum_slabs<<<(unsigned)std::min<int64_t>((count + 31) / 32, 8192), 256, 0, st>>>(
             static_cast<const float*>(work), slabs, count, dW);
         SAR_LAUNCH_CHECK();
     }
