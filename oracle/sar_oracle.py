@@ -12,8 +12,10 @@ this file holds the block builder (numpy sorts), the node-wise steps (numpy
 matmul) and the loops over blocks.
 
 Parity pins (tests/test_oracle_*.py): brute-force dense masked softmax,
-finite differences, dense autograd, degree counts, textbook CSR products and
-the invariants of Eq. 3.  Unpinned by the paper: the Xavier constants of the
+finite differences, dense autograd (also of the whole layers with the residual
+weights of Eq. 2 and the non-linearity), degree counts, textbook CSR products,
+hand-checked small cases and the invariants of Eq. 3.  The paper leaves sigma
+open: ReLU is the reading taken here.  Unpinned by the paper: the Xavier constants of the
 synthetic parameters and the exact form of "max relative error" (both are
 conventions of the test harness, not of the method).
 """
@@ -291,6 +293,29 @@ def linear_bwd(X, dZ, W):
     return X.T @ dZ, dZ @ W.T
 
 
+ACT_NONE, ACT_RELU = 0, 1
+
+
+def act_fwd(x: np.ndarray, act: int) -> np.ndarray:
+    """The non-linearity sigma of Eq. 2 / Eq. 3 (left open by the paper; ReLU is the reading here)."""
+    x = _d(x)
+    if act == ACT_NONE:
+        return x.copy()
+    if act == ACT_RELU:
+        return np.where(x > 0.0, x, 0.0)
+    raise ValueError("unknown act %r" % (act,))
+
+
+def act_bwd(pre: np.ndarray, dH: np.ndarray, act: int) -> np.ndarray:
+    """Error of the argument of sigma given the error dH of its value: dH * sigma'(pre)."""
+    pre, dH = _d(pre), _d(dH)
+    if act == ACT_NONE:
+        return dH.copy()
+    if act == ACT_RELU:
+        return np.where(pre > 0.0, dH, 0.0)
+    raise ValueError("unknown act %r" % (act,))
+
+
 @dataclass
 class LayerResult:
     fwd: GatForward
@@ -300,24 +325,63 @@ class LayerResult:
     dW: np.ndarray
     dXdst: np.ndarray
     dXs: List[np.ndarray]
+    h: np.ndarray           # sigma(aggregate), [n_dst,H,D]
+    Gagg: np.ndarray        # error of the aggregate, G * sigma'
 
 
-def gat_layer(blocks: Sequence[Block], Xdst, Xs, W, a_l, a_r, slope: float, G) -> LayerResult:
-    """One GAT layer on worker p with every source block present.
+def gat_layer(blocks: Sequence[Block], Xdst, Xs, W, a_l, a_r, slope: float, G, act: int = ACT_NONE) -> LayerResult:
+    """One GAT layer (Eq. 1 + Eq. 3) on worker p with every source block present.
 
-    Differentiates sum_{i in V_p} <out_i, G_i>.  The destination features and
-    each block's source features are separate arguments with separate grads,
-    also for the local block; dW sums the contribution of all of them.
+    Differentiates sum_{i in V_p} <h_i, G_i> with h = sigma(out).  The destination
+    features and each block's source features are separate arguments with separate
+    grads, also for the local block; dW sums the contribution of all of them.
     """
     H, D = np.asarray(a_l).shape
     Zdst = linear_fwd(Xdst, W)
     Zs = [linear_fwd(X, W) for X in Xs]
     fwd = gat_fwd(blocks, Zdst, Zs, a_l, a_r, slope)
-    bwd = gat_bwd(blocks, Zdst, Zs, G, a_l, a_r, slope, fwd)
+    h = act_fwd(fwd.out, act)
+    Gagg = act_bwd(fwd.out, _d(G).reshape(fwd.out.shape), act)
+    bwd = gat_bwd(blocks, Zdst, Zs, Gagg, a_l, a_r, slope, fwd)
     dW, dXdst = linear_bwd(Xdst, bwd.dZdst, W)
     dXs = []
     for X, dZ in zip(Xs, bwd.dZs):
         dWq, dXq = linear_bwd(X, dZ, W)
         dW = dW + dWq
         dXs.append(dXq)
-    return LayerResult(fwd, bwd, Zdst.reshape(-1, H, D), Zs, dW, dXdst, dXs)
+    return LayerResult(fwd, bwd, Zdst.reshape(-1, H, D), Zs, dW, dXdst, dXs, h, Gagg)
+
+
+@dataclass
+class SageResult:
+    Zs: List[np.ndarray]    # z = W h of every source block (Eq. 1)
+    agg: np.ndarray         # mean over the in-neighbours
+    res: np.ndarray         # W_res h_i
+    h: np.ndarray           # sigma(res + agg)
+    Gpre: np.ndarray        # error of res + agg
+    dZs: List[np.ndarray]
+    dW: np.ndarray
+    dW_res: np.ndarray
+    dXdst: np.ndarray       # through the residual only
+    dXs: List[np.ndarray]   # through the messages only
+
+
+def sage_layer(blocks: Sequence[Block], Xdst, Xs, W, W_res, dH, act: int = ACT_RELU, mean: bool = True) -> SageResult:
+    """One GraphSage layer (Eq. 1 + Eq. 2) on worker p and its backward for the loss
+    sum_i <h_i, dH_i>: h_i = sigma(W_res x_i + mean_j z_j), z = W x.  The aggregation is
+    case 1 of Sec. 3.2: its backward needs no features, only the error of the aggregate."""
+    Zs = [linear_fwd(X, W) for X in Xs]
+    agg = spmm(blocks, Zs, mean)
+    res = linear_fwd(Xdst, W_res)
+    pre = res + agg
+    h = act_fwd(pre, act)
+    Gpre = act_bwd(pre, dH, act)
+    dW_res, dXdst = linear_bwd(Xdst, Gpre, W_res)
+    dZs = spmm_bwd(blocks, Gpre, mean)
+    dW = np.zeros_like(_d(W))
+    dXs = []
+    for X, dZ in zip(Xs, dZs):
+        dWq, dXq = linear_bwd(X, dZ, W)
+        dW = dW + dWq
+        dXs.append(dXq)
+    return SageResult(Zs, agg, res, h, Gpre, dZs, dW, dW_res, dXdst, dXs)
