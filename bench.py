@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the graph (debugging only)")
     ap.add_argument("--mode", default="all", choices=["all", "stream"],
                     help="all: one launch over the P blocks; stream: one launch per block")
+    ap.add_argument("--act", default="none", choices=["none", "relu"],
+                    help="non-linearity of Eq. 3 fused into the GAT forward epilogue and backward begin")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this size (to scale rocprofv3's FETCH_SIZE/WRITE_SIZE)")
@@ -51,8 +53,8 @@ def parse():
 class Layer:
     """Device state of one worker's GAT layer; methods only call the C ABI."""
 
-    def __init__(self, w, torch, sar, synth):
-        self.torch, self.sar, self.w = torch, sar, w
+    def __init__(self, w, torch, sar, synth, act=0):
+        self.torch, self.sar, self.w, self.act = torch, sar, w, act
         dev = "cuda"
         H, D, P, p = w.H, w.D, w.P, w.p
         self.H, self.D, self.F, self.P, self.p = H, D, H * D, P, p
@@ -88,6 +90,7 @@ class Layer:
         self.out = torch.empty((n, H, D), dtype=w.dtype, device=dev)
         self.L = torch.empty((n, H), **f32)
         self.rec = torch.empty((n, H, 4), **f32)
+        self.Gact = torch.empty_like(self.G) if act else None
         self.ds = torch.empty((n, H), **f32)
         self.dZs = [torch.empty_like(z) for z in self.Zs]
         self.dts = [torch.empty((z.shape[0], H), **f32) for z in self.Zs]
@@ -114,25 +117,26 @@ class Layer:
         # inside the gather kernels (tq = None), so no separate pass over Z_q is needed
         mark("fwd0")
         if mode == "all":
-            sar.sar_gat_fwd_all(self.blocks, Zs, self.s, None, self.a_l, w.slope, self.out, self.L)
+            sar.sar_gat_fwd_all(self.blocks, Zs, self.s, None, self.a_l, w.slope, self.out, self.L, self.act)
         else:
             sar.sar_gat_fwd_begin(self.m, self.l, self.acc)
             for q in range(P):
                 sar.sar_gat_fwd_block(self.blocks, q, Zs[q], self.s, None, self.a_l, w.slope, self.m, self.l,
                                       self.acc)
-            sar.sar_gat_fwd_end(self.m, self.l, self.acc, self.out, self.L)
+            sar.sar_gat_fwd_end(self.m, self.l, self.acc, self.out, self.L, self.act)
         mark("fwd1")
-        sar.sar_gat_bwd_begin(self.G, self.out, self.s, self.L, self.rec, self.ds)
+        sar.sar_gat_bwd_begin(self.G, self.out, self.s, self.L, self.rec, self.ds, self.act, self.Gact)
+        G = self.Gact if self.act else self.G
         self.da_l.zero_()
         self.da_r.zero_()
         self.dW.zero_()
         mark("bwd0")
         if mode == "all":
-            sar.sar_gat_bwd_all(self.blocks, Zs, self.G, None, self.rec, self.a_l, w.slope, self.dZs, self.dts,
+            sar.sar_gat_bwd_all(self.blocks, Zs, G, None, self.rec, self.a_l, w.slope, self.dZs, self.dts,
                                 self.ds, self.da_l, self.work)
         else:
             for q in range(P):
-                sar.sar_gat_bwd_block(self.blocks, q, Zs[q], self.G, None, self.rec, self.a_l, w.slope,
+                sar.sar_gat_bwd_block(self.blocks, q, Zs[q], G, None, self.rec, self.a_l, w.slope,
                                       self.dZs[q], self.dts[q], self.ds, self.da_l, self.work)
         mark("bwd1")
         # E_p = E_{p->p} + destination-score term: everything this worker itself produced for its rows
@@ -246,45 +250,109 @@ def cpu_baseline(layer, n_blocks):
                       % (n_blocks, w.P, edges, dt)}
 
 
-def spmm_bench(args, w, torch, sar, synth):
-    """Config 2: GraphSage mean aggregation only (Eq. 2) over the P resident blocks."""
+def sage_bench(args, w, torch, sar, synth):
+    """Config 2: one worker's GraphSage layer (Eq. 1 + Eq. 2), forward and backward, over the P
+    resident blocks: Z_p = X_p W and R = X_p W_res on MFMA, mean aggregation with the residual and
+    ReLU fused into its epilogue, error through ReLU, case-1 backward per block (no features
+    needed), dW / dW_res / dX for the worker's own rows."""
+    dev = "cuda"
     P, p, F = w.P, w.p, w.H * w.D
     blocks = sar.sar_blocks_build(w.src, w.dst, w.part, P, p)
     views = [blocks.view(q) for q in range(P)]
     E = sum(v.nnz for v in views)
     n = blocks.n_dst
-    Zs = [synth.normal_rows(2, w.members(q), F, dtype=w.dtype) for q in range(P)]
-    acc = torch.zeros((n, F), dtype=torch.float32, device="cuda")
-    out = torch.empty((n, F), dtype=w.dtype, device="cuda")
+    W = synth.xavier_uniform(3, 0, (w.f_in, F), w.f_in, F, dev)
+    W_res = synth.xavier_uniform(3, 3, (w.f_in, F), w.f_in, F, dev)
+    X = synth.normal_rows(2, w.members(p), w.f_in, dtype=w.dtype)
+    dH = synth.normal_rows(4, w.members(p), F, dtype=w.dtype)
+    Zs = []
+    for q in range(P):       # the other partitions' rows as fetched: Z_q = X_q W, produced before timing
+        Xq = synth.normal_rows(2, w.members(q), w.f_in, dtype=w.dtype)
+        Zq = torch.empty((Xq.shape[0], F), dtype=w.dtype, device=dev)
+        sar.sar_linear_fwd(Xq, W, Zq)
+        Zs.append(Zq)
+        del Xq
+    f32 = dict(dtype=torch.float32, device=dev)
+    Zp = torch.empty((n, F), dtype=w.dtype, device=dev)
+    R = torch.empty((n, F), dtype=w.dtype, device=dev)
+    acc = torch.zeros((n, F), **f32)
+    h = torch.empty((n, F), dtype=w.dtype, device=dev)
+    G = torch.empty((n, F), dtype=w.dtype, device=dev)
+    dZs = [torch.empty_like(z) for z in Zs]
+    dW, dW_res = torch.zeros_like(W), torch.zeros_like(W_res)
+    dX_msg, dX_res = torch.empty_like(X), torch.empty_like(X)
+    lwork = torch.empty(max(1, sar.sar_linear_workspace_bytes(n, w.f_in, F) // 4), **f32)
     deg = sar.sar_blocks_degree(blocks)
+    act = sar.SAR_ACT_RELU
 
-    def step():
+    def step(ev=None):
+        mark = (lambda k: ev[k].record()) if ev is not None else (lambda k: None)
+        mark("t0")
+        sar.sar_linear_fwd(X, W, Zp)
+        sar.sar_linear_fwd(X, W_res, R)
+        zs = list(Zs)
+        zs[p] = Zp
+        mark("fwd0")
         if args.mode == "all":
-            sar.sar_spmm_all(blocks, Zs, True, out)
+            sar.sar_spmm_all(blocks, zs, True, h, R, act)
         else:
             acc.zero_()
             for q in range(P):
-                sar.sar_spmm_block(blocks, q, Zs[q], acc)
-            sar.sar_spmm_end(deg, True, acc, out)
+                sar.sar_spmm_block(blocks, q, zs[q], acc)
+            sar.sar_spmm_end(deg, True, acc, h, R, act)
+        mark("fwd1")
+        sar.sar_act_bwd(h, dH, act, G)
+        dW.zero_()
+        dW_res.zero_()
+        mark("bwd0")
+        if args.mode == "all":
+            sar.sar_spmm_bwd_all(blocks, G, True, dZs)
+        else:
+            for q in range(P):
+                sar.sar_spmm_bwd_block(blocks, q, G, True, dZs[q])
+        mark("bwd1")
+        sar.sar_linear_bwd(X, G, W_res, dW_res, dX_res, lwork)
+        sar.sar_linear_bwd(X, dZs[p], W, dW, dX_msg, lwork)
+        mark("t1")
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    names = ["t0", "fwd0", "fwd1", "bwd0", "bwd1", "t1"]
+    evs = [{k: torch.cuda.Event(enable_timing=True) for k in names} for _ in range(args.steps)]
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
+    for k in range(args.steps):
+        step(evs[k])
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / args.steps
-    fb = 4
+    avg = lambda a, b: sum(e[a].elapsed_time(e[b]) for e in evs) / len(evs)
+    fwd_ms, bwd_ms, all_ms = avg("fwd0", "fwd1"), avg("bwd0", "bwd1"), avg("t0", "t1")
+    fb = 2 if w.dtype == torch.bfloat16 else 4
     touched = sum(v.n_t_rows for v in views)
-    alg = 4 * E + 8 * n + touched * F * fb + n * F * fb
-    print(json.dumps({"metric": "SpMM mean aggregation edges/sec per GPU", "value": E / (ms * 1e-3), "unit": "edges/s",
-                      "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
-                      "config": {"workload": "cfg2: %d destinations, %d in-edges, %d blocks, F=%d fp32" % (n, E, P, F),
-                                 "mode": args.mode},
-                      "roofline": {"bound": "hbm", "achieved": alg / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
-                                   "unit": "GB/s", "frac": alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                                   "alg_bytes_per_launch": alg, "gather_volume_GBs": E * F * fb / (ms * 1e-3) / 1e9}}))
+    n_src = sum(v.n_src for v in views)
+    # forward: index, each touched source row once, residual read, h written
+    alg_fwd = 4 * E + 8 * n + touched * F * fb + 2 * n * F * fb
+    # backward: transposed index, each destination's error row once per block that touches it at
+    # most (counted once per block), every source row of every block written
+    alg_bwd = 4 * E + 12 * n_src + P * 4 * n + min(E, P * n) * F * fb + n_src * F * fb
+    print(json.dumps({
+        "metric": "GraphSage layer fwd+bwd edges/sec per GPU", "value": E / (ms * 1e-3), "unit": "edges/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if w.dtype == torch.float32 else "bf16 storage, f32 accumulate", "data": "synthetic",
+        "config": {"workload": "cfg2: one worker's share of a %d-node graph, %d-way split, %d destinations, "
+                               "%d in-edges over %d resident source blocks, GraphSage F=%d, in_dim %d, ReLU"
+                               % (w.N, P, n, E, P, F, w.f_in), "mode": args.mode, "scale": args.scale},
+        "phases_ms": {"step_events": all_ms, "mean_aggregation_fwd (+residual, ReLU)": fwd_ms,
+                      "aggregation_bwd (%d launches)" % (1 if args.mode == "all" else P): bwd_ms,
+                      "other (XW, X W_res fwd+bwd, ReLU bwd)": all_ms - fwd_ms - bwd_ms},
+        "roofline": {"bound": "hbm", "kernel": "k_spmm (all blocks)" if args.mode == "all" else "k_spmm (per block)",
+                     "achieved": alg_fwd / (fwd_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": alg_fwd / (fwd_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                     "alg_bytes_per_launch": alg_fwd, "avg_launch_ms": fwd_ms,
+                     "gather_volume_GBs": E * F * fb / (fwd_ms * 1e-3) / 1e9,
+                     "backward": {"alg_bytes": alg_bwd, "ms": bwd_ms, "alg_GBs": alg_bwd / (bwd_ms * 1e-3) / 1e9,
+                                  "gather_volume_GBs": E * F * fb / (bwd_ms * 1e-3) / 1e9}}}))
 
 
 def fak_sweep(args, torch, sar, synth):
@@ -332,9 +400,9 @@ def main():
         return
     w = synth.make_workload(args.workload, device="cuda", scale=args.scale)
     if args.workload == "cfg2":
-        spmm_bench(args, w, torch, sar, synth)
+        sage_bench(args, w, torch, sar, synth)
         return
-    layer = Layer(w, torch, sar, synth)
+    layer = Layer(w, torch, sar, synth, act=sar.SAR_ACT_RELU if args.act == "relu" else sar.SAR_ACT_NONE)
 
     if args.calib_copy_mib:
         a = torch.ones(args.calib_copy_mib << 18, dtype=torch.float32, device="cuda")
@@ -394,7 +462,7 @@ def main():
         "config": {"workload": "%s: one worker's share of a %d-node graph, %d-way split, %d destinations, "
                                "%d in-edges over %d resident source blocks, GAT %d heads x %d, in_dim %d"
                                % (args.workload, w.N, w.P, layer.n, layer.E, w.P, w.H, w.D, w.f_in),
-                   "mode": args.mode, "scale": args.scale},
+                   "mode": args.mode, "scale": args.scale, "act": args.act},
         "phases_ms": {"step_events": all_ms, "gat_fwd": fwd_ms, "gat_bwd": bwd_ms,
                       "gat_bwd_kernel_rows_ge8": wide_ms, "gat_bwd_kernel_rows_lt8": narrow_ms,
                       "other (XW fwd+bwd, scores, begin/end)": all_ms - fwd_ms - bwd_ms},

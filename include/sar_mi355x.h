@@ -61,6 +61,10 @@ typedef enum {
 
 typedef enum { SAR_F32 = 0, SAR_BF16 = 1 } sar_dtype;
 
+/* The non-linearity sigma of Eq. 2 / Eq. 3.  The paper leaves sigma open; ReLU is
+ * the one offered, its derivative being a function of the output alone. */
+typedef enum { SAR_ACT_NONE = 0, SAR_ACT_RELU = 1 } sar_act;
+
 /* Most blocks one batched (..._all) call or one handle can hold. */
 #define SAR_MAX_BLOCKS 64
 
@@ -104,7 +108,7 @@ typedef struct {
  * the next failing call on the same thread. */
 const char* sar_last_error(void);
 
-/* ABI version of this header (currently 1). */
+/* ABI version of this header (currently 2). */
 int sar_version(void);
 
 /* ------------------------------------------------------------------ blocks
@@ -154,16 +158,28 @@ int sar_blocks_free(sar_blocks_t* b);
 int sar_spmm_block(const sar_blocks_t* b, int q, const void* Zq, int dtype, int F, float* acc,
                    void* stream);
 
-/* After the last block: out = acc (mean == 0) or acc / |N(i)| (Eq. 2; 0 when
- * |N(i)| = 0).  out [n_dst,F] of `dtype`; deg from sar_blocks_degree. */
-int sar_spmm_end(const int32_t* deg, int mean, const float* acc, void* out, int dtype,
-                 int64_t n_dst, int F, void* stream);
+/* After the last block: agg = acc (mean == 0) or acc / |N(i)| (Eq. 2; 0 when
+ * |N(i)| = 0), then the node update of Eq. 2, out = act(agg + residual).
+ * residual [n_dst,F] of `dtype` holds the rows W_res h_i (e.g. from
+ * sar_linear_fwd) or is NULL (= 0); act is SAR_ACT_*.  With residual = NULL and
+ * act = SAR_ACT_NONE out is the plain aggregate.  out [n_dst,F] of `dtype`
+ * (may alias residual); deg from sar_blocks_degree. */
+int sar_spmm_end(const int32_t* deg, int mean, const float* acc, const void* residual, int act,
+                 void* out, int dtype, int64_t n_dst, int F, void* stream);
 
 /* All P blocks in one launch, the accumulator never leaving registers; same
  * result as P sar_spmm_block calls in block order followed by sar_spmm_end.
  * Zq: host array [P] of device pointers.  Needs SAR_BUILD_FUSED. */
 int sar_spmm_all(const sar_blocks_t* b, const void* const* Zq, int dtype, int F, int mean,
-                 void* out, void* stream);
+                 const void* residual, int act, void* out, void* stream);
+
+/* Backward through the non-linearity of Eq. 2 / Eq. 3, with its derivative
+ * taken from the output: G = dH * act'(.), for ReLU G = dH where h > 0, else 0.
+ * h, dH, G: `count` values of `dtype` (count a multiple of 4 for fp32, 8 for
+ * bf16; 16-byte aligned; G may alias dH).  G is then the error of the aggregate
+ * (for sar_spmm_bwd_block) and of the residual rows (for sar_linear_bwd). */
+int sar_act_bwd(const void* h, const void* dH, int act, void* G, int dtype, int64_t count,
+                void* stream);
 
 /* Case 1 of Sec. 3.2 (the gradient of a sum does not need the features):
  * dZq[j,:] = sum_{(j->i) in block q} G[i,:] / (mean ? |N(i)| : 1).
@@ -171,6 +187,11 @@ int sar_spmm_all(const sar_blocks_t* b, const void* const* Zq, int dtype, int F,
  * Alg. 2).  G [n_dst,F] of `dtype`.  Needs SAR_BUILD_TRANSPOSE. */
 int sar_spmm_bwd_block(const sar_blocks_t* b, int q, const void* G, int mean, int dtype, int F,
                        void* dZq, void* stream);
+
+/* The same for all P blocks in one launch (same results as P
+ * sar_spmm_bwd_block calls).  dZq: host array [P] of device pointers. */
+int sar_spmm_bwd_all(const sar_blocks_t* b, const void* G, int mean, int dtype, int F,
+                     void* const* dZq, void* stream);
 
 /* ------------------------------------------------------ Eq. 3: attention
  * e_{j->i} = LeakyReLU(a^T (z_i || z_j)) = LeakyReLU(s_i + t_j) per head with
@@ -198,10 +219,11 @@ int sar_gat_fwd_block(const sar_blocks_t* b, int q, const void* Zq, const float*
                       const float* tq, const float* a_l, int dtype, int H, int D, float slope,
                       float* m, float* l, float* acc, void* stream);
 
-/* After the last block: out = acc / l (the division of Sec. 3.2), and the
- * log-sum-exp L = m + log l that the backward pass reads.  out [n_dst,H,D] of
- * `dtype`, L fp32 [n_dst,H]. */
-int sar_gat_fwd_end(const float* m, const float* l, const float* acc, void* out, float* L,
+/* After the last block: out = act(acc / l) (the division of Sec. 3.2 and the
+ * non-linearity of Eq. 3; act = SAR_ACT_NONE leaves the aggregate as it is),
+ * and the log-sum-exp L = m + log l that the backward pass reads.
+ * out [n_dst,H,D] of `dtype`, L fp32 [n_dst,H]. */
+int sar_gat_fwd_end(const float* m, const float* l, const float* acc, int act, void* out, float* L,
                     int dtype, int64_t n_dst, int H, int D, void* stream);
 
 /* All P blocks in one launch: each destination walks its blocks in order
@@ -210,7 +232,7 @@ int sar_gat_fwd_end(const float* m, const float* l, const float* acc, void* out,
  * as in sar_gat_fwd_block).  Needs SAR_BUILD_FUSED. */
 int sar_gat_fwd_all(const sar_blocks_t* b, const void* const* Zq, const float* s,
                     const float* const* tq, const float* a_l, int dtype, int H, int D, float slope,
-                    void* out, float* L, void* stream);
+                    int act, void* out, float* L, void* stream);
 
 /* Bytes of scratch the backward calls below need for these sizes. */
 int sar_gat_workspace_bytes(int64_t n_dst, int64_t n_src_max, int H, int D, size_t* bytes);
@@ -219,9 +241,15 @@ int sar_gat_workspace_bytes(int64_t n_dst, int64_t n_src_max, int H, int D, size
  * and head into one 16-byte record rec[i,h] = (s log2(e), L log2(e), delta, 0)
  * with delta[i,h] = <G[i,h,:], out[i,h,:]>, and sets ds = 0.
  * G (the error e_Acc) and out [n_dst,H,D] of `dtype`; s, L fp32 [n_dst,H] (from
- * the forward pass); rec fp32 [n_dst,H,4] (16-byte aligned); ds fp32 [n_dst,H]. */
-int sar_gat_bwd_begin(const void* G, const void* out, const float* s, const float* L, int dtype,
-                      float* rec, float* ds, int64_t n_dst, int H, int D, void* stream);
+ * the forward pass); rec fp32 [n_dst,H,4] (16-byte aligned); ds fp32 [n_dst,H].
+ * When the forward pass applied a non-linearity (act != SAR_ACT_NONE), out is
+ * its output h and G the error of h; the error of the aggregate, G * act'(.),
+ * is written to Gact ([n_dst,H,D] of `dtype`, may alias G) and it is Gact that
+ * the block calls below take as their G.  With SAR_ACT_NONE Gact is not used
+ * and may be NULL. */
+int sar_gat_bwd_begin(const void* G, const void* out, const float* s, const float* L, int act,
+                      void* Gact, int dtype, float* rec, float* ds, int64_t n_dst, int H, int D,
+                      void* stream);
 
 /* One block of Alg. 2 with the rematerialising kernel of Sec. 3.3.  For every
  * edge the coefficient alpha = exp(e - L_i) is recomputed from s_i, t_j, L_i:

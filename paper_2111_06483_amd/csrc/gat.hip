@@ -56,6 +56,7 @@ struct FwdArgs {
     int ldz, ldh;        // strides between nodes of the feature rows / of the per-head arrays
     int tag_shift;
     float slope;
+    int act;             // SAR_ACT_*: the non-linearity of Eq. 3 on the normalised rows (batched call)
 };
 
 template <int VEC>
@@ -194,7 +195,10 @@ __device__ inline void fwd_finish_row(SoftState<Vec<T>::N>& st, const FwdArgs& a
         const float inv = st.l > 0.f ? 1.f / st.l : 0.f;
         float v[VEC];
 #pragma unroll
-        for (int x = 0; x < VEC; ++x) v[x] = st.acc[x] * inv;
+        for (int x = 0; x < VEC; ++x) {
+            v[x] = st.acc[x] * inv;
+            if (a.act == SAR_ACT_RELU) v[x] = fmaxf(v[x], 0.f);
+        }
         Vec<T>::store(static_cast<T*>(a.out) + o, v);
         if ((lm.gl % lm.lph) == 0)
             a.L[(int64_t)i * a.ldh + lm.h] = st.l > 0.f ? (st.m2 + fast_log2(st.l)) * kLn2 : -INFINITY;
@@ -543,7 +547,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_fwd_end(const float* __restr
                                                             const float* __restrict__ l,
                                                             const float* __restrict__ acc, T* __restrict__ out,
                                                             float* __restrict__ L, int64_t n, int H, int D, int F,
-                                                            int ldz, int ldh)
+                                                            int ldz, int ldh, int act)
 {
     constexpr int VEC = Vec<T>::N;
     constexpr int SLOTS = kWave / G;
@@ -558,20 +562,26 @@ __global__ __launch_bounds__(kGatherThreads) void k_fwd_end(const float* __restr
         float a[VEC];
         load_f32<VEC>(acc + v * ldz + lm.gl * VEC, a);
 #pragma unroll
-        for (int x = 0; x < VEC; ++x) a[x] *= inv;
+        for (int x = 0; x < VEC; ++x) {
+            a[x] *= inv;
+            if (act == SAR_ACT_RELU) a[x] = fmaxf(a[x], 0.f);
+        }
         Vec<T>::store(out + v * ldz + lm.gl * VEC, a);
         if ((lm.gl % lm.lph) == 0)
             L[v * ldh + lm.h] = lv > 0.f ? m[v * ldh + lm.h] + fast_log2(lv) * kLn2 : -INFINITY;
     }
 }
 
-// rec[i,h] = (s log2e, L log2e, <G_i, out_i>, 0) and ds = 0
+// rec[i,h] = (s log2e, L log2e, <G_i, out_i>, 0) and ds = 0.  With a non-linearity, `out` holds
+// h = act(aggregate) and Gr the error of h: the error of the aggregate, Gr * act'(.), is formed
+// here from h alone (ReLU: h > 0 exactly where the aggregate is, and there they are equal, so
+// <G_i, out_i> is unchanged) and written to Gact for the block kernels to gather.
 template <typename T, int G>
-__global__ __launch_bounds__(kGatherThreads) void k_bwd_begin(const T* __restrict__ Gr, const T* __restrict__ out,
+__global__ __launch_bounds__(kGatherThreads) void k_bwd_begin(const T* Gr, const T* __restrict__ out,
                                                               const float* __restrict__ s,
                                                               const float* __restrict__ L, float4* __restrict__ rec,
                                                               float* __restrict__ ds, int64_t n, int H, int D, int F,
-                                                              int ldz, int ldh)
+                                                              int ldz, int ldh, int act, T* Gact)
 {
     constexpr int VEC = Vec<T>::N;
     constexpr int SLOTS = kWave / G;
@@ -585,6 +595,11 @@ __global__ __launch_bounds__(kGatherThreads) void k_bwd_begin(const T* __restric
         if (v < n && lm.on) {
             Vec<T>::unpack(Vec<T>::load(Gr + v * ldz + lm.gl * VEC), g);
             Vec<T>::unpack(Vec<T>::load(out + v * ldz + lm.gl * VEC), o);
+            if (act == SAR_ACT_RELU) {
+#pragma unroll
+                for (int x = 0; x < VEC; ++x) g[x] = o[x] > 0.f ? g[x] : 0.f;
+                Vec<T>::store(Gact + v * ldz + lm.gl * VEC, g);
+            }
         }
         float c = 0.f;
 #pragma unroll
@@ -657,6 +672,13 @@ __global__ __launch_bounds__(kGatherThreads) void k_bwd_end(const T* __restrict_
 // --------------------------------------------------------------- host side
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_act(int act)
+{
+    if (act != SAR_ACT_NONE && act != SAR_ACT_RELU)
+        return sar::fail(SAR_ERR_UNSUPPORTED, "act %d is neither SAR_ACT_NONE nor SAR_ACT_RELU", act);
+    return SAR_OK;
+}
 
 int check_shape(int dtype, int H, int D)
 {
@@ -761,7 +783,7 @@ int launch_fwd_f256(const FwdArgs& a, const PtrTab& zt, const PtrTab& tt, hipStr
     p.indptr = a.indptr; p.indices = a.indices; p.rows = a.rows;
     p.n_rows = a.n_rows; p.n_long = a.n_long;
     p.Z = a.Z; p.t = a.t; p.a_l = a.a_l; p.s = a.s; p.m = a.m; p.l = a.l; p.acc = a.acc; p.out = a.out; p.L = a.L;
-    p.H = a.H; p.tag_shift = a.tag_shift; p.slope = a.slope;
+    p.H = a.H; p.tag_shift = a.tag_shift; p.slope = a.slope; p.act = a.act;
     f256::Tabs tabs{};
     for (int q = 0; q < SAR_MAX_BLOCKS; ++q) {
         tabs.Z[q] = zt.p[q];
@@ -953,10 +975,11 @@ extern "C" int sar_gat_fwd_block(const sar_blocks_t* b, int q, const void* Zq, c
     return SAR_OK;
 }
 
-extern "C" int sar_gat_fwd_end(const float* m, const float* l, const float* acc, void* out, float* L,
+extern "C" int sar_gat_fwd_end(const float* m, const float* l, const float* acc, int act, void* out, float* L,
                                int dtype, int64_t n_dst, int H, int D, void* stream)
 {
     SAR_TRY(check_shape(dtype, H, D));
+    SAR_TRY(check_act(act));
     SAR_CHECK_ARG(n_dst >= 0, "n_dst is negative");
     if (n_dst == 0) return SAR_OK;
     SAR_CHECK_ARG(m && l && acc && out && L, "a tensor argument is null");
@@ -969,11 +992,11 @@ extern "C" int sar_gat_fwd_end(const float* m, const float* l, const float* acc,
         if (dtype == SAR_F32) {
             SAR_DISPATCH_G(float, hg.Fg, (k_fwd_end<float, kG><<<nodewise_grid(n_dst, kWave / kG), kGatherThreads, 0, st>>>(
                                              m + h0, l + h0, acc + f0, static_cast<float*>(out) + f0, L + h0, n_dst,
-                                             hg.Hg, D, hg.Fg, F, H)));
+                                             hg.Hg, D, hg.Fg, F, H, act)));
         } else {
             SAR_DISPATCH_G(bf16_t, hg.Fg, (k_fwd_end<bf16_t, kG><<<nodewise_grid(n_dst, kWave / kG), kGatherThreads, 0, st>>>(
                                               m + h0, l + h0, acc + f0, static_cast<bf16_t*>(out) + f0, L + h0, n_dst,
-                                              hg.Hg, D, hg.Fg, F, H)));
+                                              hg.Hg, D, hg.Fg, F, H, act)));
         }
         SAR_LAUNCH_CHECK();
     }
@@ -982,10 +1005,11 @@ extern "C" int sar_gat_fwd_end(const float* m, const float* l, const float* acc,
 
 extern "C" int sar_gat_fwd_all(const sar_blocks_t* b, const void* const* Zq, const float* s,
                                const float* const* tq, const float* a_l, int dtype, int H, int D, float slope,
-                               void* out, float* L, void* stream)
+                               int act, void* out, float* L, void* stream)
 {
     SAR_CHECK_ARG(b != nullptr, "handle is null");
     SAR_TRY(check_shape(dtype, H, D));
+    SAR_TRY(check_act(act));
     if (!b->f_indptr) return sar::fail(SAR_ERR_STATE, "handle was built without SAR_BUILD_FUSED");
     if (b->n_dst == 0) return SAR_OK;
     SAR_CHECK_ARG(Zq && s && out && L, "a tensor argument is null");
@@ -1021,6 +1045,7 @@ extern "C" int sar_gat_fwd_all(const sar_blocks_t* b, const void* const* Zq, con
         a.ldh = H;
         a.tag_shift = b->tag_shift;
         a.slope = slope;
+        a.act = act;
         if (dtype == SAR_F32)
             SAR_TRY((launch_fwd<float, true>(a, zt, tt, b->P, st)));
         else
@@ -1037,14 +1062,17 @@ extern "C" int sar_gat_workspace_bytes(int64_t n_dst, int64_t n_src_max, int H, 
     return SAR_OK;
 }
 
-extern "C" int sar_gat_bwd_begin(const void* G, const void* out, const float* s, const float* L, int dtype,
-                                 float* rec, float* ds, int64_t n_dst, int H, int D, void* stream)
+extern "C" int sar_gat_bwd_begin(const void* G, const void* out, const float* s, const float* L, int act,
+                                 void* Gact, int dtype, float* rec, float* ds, int64_t n_dst, int H, int D,
+                                 void* stream)
 {
     SAR_TRY(check_shape(dtype, H, D));
+    SAR_TRY(check_act(act));
     SAR_CHECK_ARG(n_dst >= 0, "n_dst is negative");
     if (n_dst == 0) return SAR_OK;
     SAR_CHECK_ARG(G && out && s && L && rec && ds, "a tensor argument is null");
     SAR_CHECK_ARG(aligned16(G) && aligned16(out) && aligned16(rec), "G, out and rec must be 16-byte aligned");
+    SAR_CHECK_ARG(act == SAR_ACT_NONE || (Gact && aligned16(Gact)), "a non-linearity needs Gact (16-byte aligned)");
     const int F = H * D;
     const HeadGroups hg = head_groups(dtype, H, D);
     hipStream_t st = sar::as_stream(stream);
@@ -1056,11 +1084,13 @@ extern "C" int sar_gat_bwd_begin(const void* G, const void* out, const float* s,
         if (dtype == SAR_F32) {
             SAR_DISPATCH_G(float, hg.Fg, (k_bwd_begin<float, kG><<<nodewise_grid(n_dst, kWave / kG), kGatherThreads, 0, st>>>(
                                              static_cast<const float*>(Gg), static_cast<const float*>(og), s + h0, L + h0,
-                                             recg, ds + h0, n_dst, hg.Hg, D, hg.Fg, F, H)));
+                                             recg, ds + h0, n_dst, hg.Hg, D, hg.Fg, F, H, act,
+                                             static_cast<float*>(shift(Gact, f0 * hg.fb)))));
         } else {
             SAR_DISPATCH_G(bf16_t, hg.Fg, (k_bwd_begin<bf16_t, kG><<<nodewise_grid(n_dst, kWave / kG), kGatherThreads, 0, st>>>(
                                               static_cast<const bf16_t*>(Gg), static_cast<const bf16_t*>(og), s + h0,
-                                              L + h0, recg, ds + h0, n_dst, hg.Hg, D, hg.Fg, F, H)));
+                                              L + h0, recg, ds + h0, n_dst, hg.Hg, D, hg.Fg, F, H, act,
+                                              static_cast<bf16_t*>(shift(Gact, f0 * hg.fb)))));
         }
         SAR_LAUNCH_CHECK();
     }

@@ -148,6 +148,7 @@ struct FwdP {
     int H;
     int tag_shift;
     float slope;
+    int act;             // SAR_ACT_*: applied to the normalised output rows (ALL only)
 };
 
 template <int LPH>
@@ -245,7 +246,10 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_fwd_f256(FwdP a, Tabs ta
             const float inv = l > 0.f ? 1.f / l : 0.f;
             float v[4];
 #pragma unroll
-            for (int x = 0; x < 4; ++x) v[x] = st.acc[x] * inv;
+            for (int x = 0; x < 4; ++x) {
+                v[x] = st.acc[x] * inv;
+                if (a.act == SAR_ACT_RELU) v[x] = fmaxf(v[x], 0.f);
+            }
             Row4<T>::store(outp + (int64_t)i * kF, lane, v);
             if (k == 0) a.L[(int64_t)i * a.H + h] = l > 0.f ? (st.m2 + fast_log2(l)) * kLn2 : -INFINITY;
         } else {

@@ -36,6 +36,8 @@ struct SpmmArgs {
     int ld;                   // stride between rows (values)
     int tag_shift;            // all-blocks index: block = id >> tag_shift
     int mean;
+    const void* res;          // batched forward: rows added to the aggregate (Eq. 2's W_res h), or null
+    int act;                  //                  SAR_ACT_* applied after that
 };
 
 enum class Mode { kBlock, kAll, kBackward };
@@ -121,6 +123,18 @@ __device__ inline void finish_row(const float (&acc)[Vec<T>::N], const SpmmArgs&
         }
 #pragma unroll
         for (int x = 0; x < VEC; ++x) v[x] = acc[x] * sc;
+        if constexpr (M == Mode::kAll) {
+            if (a.res) {
+                float r[VEC];
+                Vec<T>::unpack(Vec<T>::load(static_cast<const T*>(a.res) + o), r);
+#pragma unroll
+                for (int x = 0; x < VEC; ++x) v[x] += r[x];
+            }
+            if (a.act == SAR_ACT_RELU) {
+#pragma unroll
+                for (int x = 0; x < VEC; ++x) v[x] = fmaxf(v[x], 0.f);
+            }
+        }
         Vec<T>::store(static_cast<T*>(a.out) + o, v);
     }
 }
@@ -172,7 +186,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_spmm(SpmmArgs a, PtrTab tab,
 
 template <typename T>
 __global__ __launch_bounds__(256) void k_spmm_end(const int32_t* __restrict__ deg, int mean,
-                                                  const float* __restrict__ acc, T* __restrict__ out,
+                                                  const float* __restrict__ acc, const T* res, int act, T* out,
                                                   int64_t n, int F)
 {
     constexpr int VEC = Vec<T>::N;
@@ -188,7 +202,92 @@ __global__ __launch_bounds__(256) void k_spmm_end(const int32_t* __restrict__ de
         }
 #pragma unroll
         for (int x = 0; x < VEC; ++x) v[x] *= sc;
+        if (res) {
+            float r[VEC];
+            Vec<T>::unpack(Vec<T>::load(res + k * VEC), r);
+#pragma unroll
+            for (int x = 0; x < VEC; ++x) v[x] += r[x];
+        }
+        if (act == SAR_ACT_RELU) {
+#pragma unroll
+            for (int x = 0; x < VEC; ++x) v[x] = fmaxf(v[x], 0.f);
+        }
         Vec<T>::store(out + k * VEC, v);
+    }
+}
+
+// G = dH * act'(.) with the derivative expressed through the output h (ReLU: 1 where h > 0)
+template <typename T>
+__global__ __launch_bounds__(256) void k_act_bwd(const T* h, const T* dH, T* G, int64_t n_vec)
+{
+    constexpr int VEC = Vec<T>::N;
+    for (int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x; k < n_vec; k += (int64_t)gridDim.x * 256) {
+        float hv[VEC], g[VEC];
+        Vec<T>::unpack(Vec<T>::load(h + k * VEC), hv);
+        Vec<T>::unpack(Vec<T>::load(dH + k * VEC), g);
+#pragma unroll
+        for (int x = 0; x < VEC; ++x) g[x] = hv[x] > 0.f ? g[x] : 0.f;
+        Vec<T>::store(G + k * VEC, g);
+    }
+}
+
+// Case-1 backward over the sources of ALL blocks in one launch.  The work list holds
+// (block << tag_shift) | source for every source of every block, longest first and
+// the sources without an edge last (they get dZ = 0); each entry is one row of one
+// block's transposed index.
+struct BwdAllTabs {
+    const int32_t* t_indptr[SAR_MAX_BLOCKS];
+    const uint32_t* t_indices[SAR_MAX_BLOCKS];
+    void* dZ[SAR_MAX_BLOCKS];
+};
+
+template <typename T, int G>
+__global__ __launch_bounds__(kGatherThreads) void k_spmm_bwd_all(SpmmArgs a, BwdAllTabs tabs)
+{
+    constexpr int VEC = Vec<T>::N;
+    constexpr Mode M = Mode::kBackward;
+    __shared__ float part[kWavesPerWG][G][VEC];
+    const LaneMap<T, G> lm(a.F, 1, a.F);
+    const int wave = threadIdx.x / kWave;
+    const uint32_t mask = (1u << a.tag_shift) - 1u;
+    auto locate = [&](int64_t r, SpmmArgs& la) -> int {
+        const uint32_t id = __builtin_amdgcn_readfirstlane(a.rows[r]);
+        const uint32_t q = id >> a.tag_shift;
+        la.indptr = tabs.t_indptr[q];
+        la.indices = tabs.t_indices[q];
+        la.out = tabs.dZ[q];
+        return (int)(id & mask);
+    };
+
+    for (int64_t r = blockIdx.x; r < a.n_long; r += gridDim.x) {
+        SpmmArgs la = a;
+        const int j = locate(r, la);
+        float acc[VEC] = {};
+        add_rows<T, G, M>(acc, la, nullptr, la.indptr[j], la.indptr[j + 1], wave, kWavesPerWG, lm);
+        merge_slots<T, G>(acc);
+        if (lm.slot == 0)
+#pragma unroll
+            for (int x = 0; x < VEC; ++x) part[wave][lm.gl][x] = acc[x];
+        __syncthreads();
+        if (wave == 0) {
+#pragma unroll
+            for (int x = 0; x < VEC; ++x) {
+                float t = 0.f;
+                for (int w = 0; w < kWavesPerWG; ++w) t += part[w][lm.gl][x];
+                acc[x] = t;
+            }
+            finish_row<T, G, M>(acc, la, j, lm);
+        }
+        __syncthreads();
+    }
+    const int64_t n_waves = (int64_t)gridDim.x * kWavesPerWG;
+    for (int64_t r = a.n_long + (int64_t)blockIdx.x * kWavesPerWG + wave; r < a.n_rows; r += n_waves) {
+        SpmmArgs la = a;
+        const int j = locate(r, la);
+        float acc[VEC] = {};
+        add_rows<T, G, M>(acc, la, nullptr, la.indptr[j], la.indptr[j + 1], 0, 1, lm);
+        merge_slots<T, G>(acc);
+        finish_row<T, G, M>(acc, la, j, lm);
     }
 }
 
@@ -209,6 +308,23 @@ int launch_spmm(const SpmmArgs& a, const PtrTab& tab, int P, hipStream_t st)
         case 16: k_spmm<T, 16, M><<<grid, kGatherThreads, 0, st>>>(a, tab, P); break;
         case 32: k_spmm<T, 32, M><<<grid, kGatherThreads, 0, st>>>(a, tab, P); break;
         case 64: k_spmm<T, 64, M><<<grid, kGatherThreads, 0, st>>>(a, tab, P); break;
+        default: return sar::fail(SAR_ERR_UNSUPPORTED, "row of F=%d values is wider than 1024 bytes", a.F);
+    }
+    SAR_LAUNCH_CHECK();
+    return SAR_OK;
+}
+
+template <typename T>
+int launch_spmm_bwd_all(const SpmmArgs& a, const BwdAllTabs& tabs, hipStream_t st)
+{
+    if (a.n_rows == 0) return SAR_OK;
+    const unsigned grid = persistent_grid(a.n_rows, a.n_long);
+    switch (lanes_for(a.F, Vec<T>::N)) {
+        case 4: k_spmm_bwd_all<T, 4><<<grid, kGatherThreads, 0, st>>>(a, tabs); break;
+        case 8: k_spmm_bwd_all<T, 8><<<grid, kGatherThreads, 0, st>>>(a, tabs); break;
+        case 16: k_spmm_bwd_all<T, 16><<<grid, kGatherThreads, 0, st>>>(a, tabs); break;
+        case 32: k_spmm_bwd_all<T, 32><<<grid, kGatherThreads, 0, st>>>(a, tabs); break;
+        case 64: k_spmm_bwd_all<T, 64><<<grid, kGatherThreads, 0, st>>>(a, tabs); break;
         default: return sar::fail(SAR_ERR_UNSUPPORTED, "row of F=%d values is wider than 1024 bytes", a.F);
     }
     SAR_LAUNCH_CHECK();
@@ -283,10 +399,51 @@ extern "C" int sar_spmm_block(const sar_blocks_t* b, int q, const void* Zq, int 
     return SAR_OK;
 }
 
-extern "C" int sar_spmm_end(const int32_t* deg, int mean, const float* acc, void* out, int dtype,
-                            int64_t n_dst, int F, void* stream)
+namespace {
+
+int check_act(int act)
+{
+    if (act != SAR_ACT_NONE && act != SAR_ACT_RELU)
+        return sar::fail(SAR_ERR_UNSUPPORTED, "act %d is neither SAR_ACT_NONE nor SAR_ACT_RELU", act);
+    return SAR_OK;
+}
+
+}  // namespace
+
+extern "C" int sar_act_bwd(const void* h, const void* dH, int act, void* G, int dtype, int64_t count, void* stream)
+{
+    if (dtype != SAR_F32 && dtype != SAR_BF16)
+        return sar::fail(SAR_ERR_UNSUPPORTED, "dtype %d is neither SAR_F32 nor SAR_BF16", dtype);
+    SAR_TRY(check_act(act));
+    const int vec = dtype == SAR_F32 ? 4 : 8;
+    SAR_CHECK_ARG(count >= 0 && count % vec == 0, "count=%lld must be a non-negative multiple of %d",
+                  (long long)count, vec);
+    if (count == 0) return SAR_OK;
+    SAR_CHECK_ARG(h && dH && G, "h, dH or G is null");
+    SAR_CHECK_ARG(aligned16(h) && aligned16(dH) && aligned16(G), "h, dH and G must be 16-byte aligned");
+    hipStream_t st = sar::as_stream(stream);
+    if (act == SAR_ACT_NONE) {
+        if (G != dH) SAR_HIP(hipMemcpyAsync(G, dH, (size_t)count * (dtype == SAR_F32 ? 4 : 2), hipMemcpyDeviceToDevice, st));
+        return SAR_OK;
+    }
+    const int64_t n_vec = count / vec;
+    const unsigned grid = (unsigned)std::min<int64_t>((n_vec + 255) / 256, 1 << 20);
+    if (dtype == SAR_F32)
+        k_act_bwd<float><<<grid, 256, 0, st>>>(static_cast<const float*>(h), static_cast<const float*>(dH),
+                                               static_cast<float*>(G), n_vec);
+    else
+        k_act_bwd<bf16_t><<<grid, 256, 0, st>>>(static_cast<const bf16_t*>(h), static_cast<const bf16_t*>(dH),
+                                                static_cast<bf16_t*>(G), n_vec);
+    SAR_LAUNCH_CHECK();
+    return SAR_OK;
+}
+
+extern "C" int sar_spmm_end(const int32_t* deg, int mean, const float* acc, const void* residual, int act,
+                            void* out, int dtype, int64_t n_dst, int F, void* stream)
 {
     SAR_TRY(check_row_shape(dtype, F));
+    SAR_TRY(check_act(act));
+    SAR_CHECK_ARG(aligned16(residual), "residual must be 16-byte aligned");
     SAR_CHECK_ARG(n_dst >= 0, "n_dst is negative");
     if (n_dst == 0) return SAR_OK;
     SAR_CHECK_ARG(acc && out && (!mean || deg), "acc, out or deg is null");
@@ -294,18 +451,22 @@ extern "C" int sar_spmm_end(const int32_t* deg, int mean, const float* acc, void
     const int vec = dtype == SAR_F32 ? 4 : 8;
     const unsigned grid = (unsigned)std::min<int64_t>((n_dst * (F / vec) + 255) / 256, 1 << 20);
     if (dtype == SAR_F32)
-        k_spmm_end<float><<<grid, 256, 0, sar::as_stream(stream)>>>(deg, mean, acc, static_cast<float*>(out), n_dst, F);
+        k_spmm_end<float><<<grid, 256, 0, sar::as_stream(stream)>>>(deg, mean, acc, static_cast<const float*>(residual),
+                                                                    act, static_cast<float*>(out), n_dst, F);
     else
-        k_spmm_end<bf16_t><<<grid, 256, 0, sar::as_stream(stream)>>>(deg, mean, acc, static_cast<bf16_t*>(out), n_dst, F);
+        k_spmm_end<bf16_t><<<grid, 256, 0, sar::as_stream(stream)>>>(deg, mean, acc, static_cast<const bf16_t*>(residual),
+                                                                     act, static_cast<bf16_t*>(out), n_dst, F);
     SAR_LAUNCH_CHECK();
     return SAR_OK;
 }
 
 extern "C" int sar_spmm_all(const sar_blocks_t* b, const void* const* Zq, int dtype, int F, int mean,
-                            void* out, void* stream)
+                            const void* residual, int act, void* out, void* stream)
 {
     SAR_CHECK_ARG(b != nullptr, "handle is null");
     SAR_TRY(check_row_shape(dtype, F));
+    SAR_TRY(check_act(act));
+    SAR_CHECK_ARG(aligned16(residual), "residual must be 16-byte aligned");
     if (!b->f_indptr) return sar::fail(SAR_ERR_STATE, "handle was built without SAR_BUILD_FUSED");
     if (b->n_dst == 0) return SAR_OK;
     SAR_CHECK_ARG(Zq && out, "Zq or out is null");
@@ -331,6 +492,8 @@ extern "C" int sar_spmm_all(const sar_blocks_t* b, const void* const* Zq, int dt
         PtrTab tab{};
         for (int q = 0; q < b->P; ++q) tab.p[q] = shift(Zq[q], f0 * cc.fb);
         a.out = shift(out, f0 * cc.fb);
+        a.res = residual ? shift(residual, f0 * cc.fb) : nullptr;
+        a.act = act;
         a.F = std::min<int>(cc.width, F - (int)f0);
         if (dtype == SAR_F32)
             SAR_TRY((launch_spmm<float, Mode::kAll>(a, tab, b->P, st)));
@@ -372,6 +535,51 @@ extern "C" int sar_spmm_bwd_block(const sar_blocks_t* b, int q, const void* G, i
             SAR_TRY((launch_spmm<float, Mode::kBackward>(a, tab, 0, st)));
         else
             SAR_TRY((launch_spmm<bf16_t, Mode::kBackward>(a, tab, 0, st)));
+    }
+    return SAR_OK;
+}
+
+extern "C" int sar_spmm_bwd_all(const sar_blocks_t* b, const void* G, int mean, int dtype, int F,
+                                void* const* dZq, void* stream)
+{
+    SAR_CHECK_ARG(b != nullptr, "handle is null");
+    SAR_TRY(check_row_shape(dtype, F));
+    if (!b->ft_rows) return sar::fail(SAR_ERR_STATE, "handle was built without SAR_BUILD_TRANSPOSE");
+    int64_t n_src_total = 0;
+    for (int q = 0; q < b->P; ++q) n_src_total += b->blk[q].n_src;
+    if (n_src_total == 0) return SAR_OK;
+    SAR_CHECK_ARG(G && dZq, "G or dZq is null");
+    SAR_CHECK_ARG(aligned16(G), "G must be 16-byte aligned");
+    for (int q = 0; q < b->P; ++q) {
+        if (b->blk[q].n_src == 0) continue;
+        SAR_CHECK_ARG(dZq[q] && aligned16(dZq[q]), "dZq[%d] is null or not 16-byte aligned", q);
+    }
+    hipStream_t st = sar::as_stream(stream);
+    SpmmArgs a{};
+    a.rows = b->ft_rows;
+    a.n_rows = n_src_total;
+    a.n_long = b->n_ft_long;
+    a.deg = b->deg;
+    a.ld = F;
+    a.mean = mean;
+    a.tag_shift = b->tag_shift;
+    const ColumnChunks cc = column_chunks(dtype, F);
+    for (int c = 0; c < cc.n; ++c) {
+        const size_t f0 = (size_t)c * cc.width;
+        BwdAllTabs tabs{};
+        for (int q = 0; q < b->P; ++q) {
+            const sar::Block& k = b->blk[q];
+            if (k.n_src == 0) continue;
+            tabs.t_indptr[q] = k.t_indptr;
+            tabs.t_indices[q] = reinterpret_cast<const uint32_t*>(k.t_indices);
+            tabs.dZ[q] = shift(dZq[q], f0 * cc.fb);
+        }
+        a.Z = shift(G, f0 * cc.fb);
+        a.F = std::min<int>(cc.width, F - (int)f0);
+        if (dtype == SAR_F32)
+            SAR_TRY(launch_spmm_bwd_all<float>(a, tabs, st));
+        else
+            SAR_TRY(launch_spmm_bwd_all<bf16_t>(a, tabs, st));
     }
     return SAR_OK;
 }

@@ -23,6 +23,8 @@ SAR_ERR_HIP = -3
 SAR_ERR_STATE = -4
 SAR_F32 = 0
 SAR_BF16 = 1
+SAR_ACT_NONE = 0
+SAR_ACT_RELU = 1
 SAR_MAX_BLOCKS = 64
 SAR_BUILD_TRANSPOSE = 1
 SAR_BUILD_FUSED = 2
@@ -70,13 +72,20 @@ EXPORTS = [
     "sar_last_error", "sar_version",
     "sar_blocks_build", "sar_blocks_wrap", "sar_blocks_info", "sar_blocks_get", "sar_blocks_degree",
     "sar_blocks_free",
-    "sar_spmm_block", "sar_spmm_end", "sar_spmm_all", "sar_spmm_bwd_block",
+    "sar_spmm_block", "sar_spmm_end", "sar_spmm_all", "sar_act_bwd", "sar_spmm_bwd_block", "sar_spmm_bwd_all",
     "sar_gat_scores", "sar_gat_fwd_begin", "sar_gat_fwd_block", "sar_gat_fwd_end", "sar_gat_fwd_all",
     "sar_gat_workspace_bytes", "sar_gat_bwd_begin", "sar_gat_bwd_block", "sar_gat_bwd_all", "sar_gat_bwd_end",
     "sar_linear_fwd", "sar_linear_bwd", "sar_linear_workspace_bytes",
     "sar_probe_stream_read", "sar_probe_copy", "sar_probe_row_gather",
     "sar_timing_begin", "sar_timing_count", "sar_timing_get",
 ]
+
+
+def _same_shape(a: torch.Tensor, b: Optional[torch.Tensor]) -> None:
+    """The C side takes one size for both: refuse a second tensor of another shape or dtype."""
+    if b is not None and (tuple(a.shape) != tuple(b.shape) or a.dtype != b.dtype):
+        raise SarError(SAR_ERR_INVALID_ARG, "tensors of shape %s %s and %s %s must match"
+                       % (tuple(a.shape), a.dtype, tuple(b.shape), b.dtype))
 
 
 def _check(rc: int) -> None:
@@ -224,18 +233,30 @@ def sar_spmm_block(b: Blocks, q: int, Zq: torch.Tensor, acc: torch.Tensor) -> No
                                 _c_int(Zq.shape[-1]), _ptr(acc), _stream()))
 
 
-def sar_spmm_end(deg: torch.Tensor, mean: bool, acc: torch.Tensor, out: torch.Tensor) -> None:
-    _check(lib().sar_spmm_end(_ptr(deg), _c_int(int(mean)), _ptr(acc), _ptr(out),
+def sar_spmm_end(deg: torch.Tensor, mean: bool, acc: torch.Tensor, out: torch.Tensor,
+                 residual: Optional[torch.Tensor] = None, act: int = SAR_ACT_NONE) -> None:
+    _same_shape(out, residual)
+    _check(lib().sar_spmm_end(_ptr(deg), _c_int(int(mean)), _ptr(acc), _ptr(residual), _c_int(act), _ptr(out),
                               _c_int(dtype_code(out.dtype)), _c_i64(acc.shape[0]), _c_int(acc.shape[1]),
                               _stream()))
 
 
-def sar_spmm_all(b: Blocks, Zq: Sequence[torch.Tensor], mean: bool, out: torch.Tensor) -> None:
+def sar_spmm_all(b: Blocks, Zq: Sequence[torch.Tensor], mean: bool, out: torch.Tensor,
+                 residual: Optional[torch.Tensor] = None, act: int = SAR_ACT_NONE) -> None:
     for q in range(b.P):
         b.check_rows(q, Zq[q])
     b.check_dst(out)
+    _same_shape(out, residual)
     _check(lib().sar_spmm_all(b.handle, _ptr_array(Zq), _c_int(dtype_code(out.dtype)),
-                              _c_int(out.shape[-1]), _c_int(int(mean)), _ptr(out), _stream()))
+                              _c_int(out.shape[-1]), _c_int(int(mean)), _ptr(residual), _c_int(act), _ptr(out),
+                              _stream()))
+
+
+def sar_act_bwd(h: torch.Tensor, dH: torch.Tensor, act: int, G: torch.Tensor) -> None:
+    _same_shape(h, dH)
+    _same_shape(h, G)
+    _check(lib().sar_act_bwd(_ptr(h), _ptr(dH), _c_int(act), _ptr(G), _c_int(dtype_code(h.dtype)),
+                             _c_i64(h.numel()), _stream()))
 
 
 def sar_spmm_bwd_block(b: Blocks, q: int, G: torch.Tensor, mean: bool, dZq: torch.Tensor) -> None:
@@ -243,6 +264,14 @@ def sar_spmm_bwd_block(b: Blocks, q: int, G: torch.Tensor, mean: bool, dZq: torc
     b.check_dst(G)
     _check(lib().sar_spmm_bwd_block(b.handle, _c_int(q), _ptr(G), _c_int(int(mean)),
                                     _c_int(dtype_code(G.dtype)), _c_int(G.shape[-1]), _ptr(dZq), _stream()))
+
+
+def sar_spmm_bwd_all(b: Blocks, G: torch.Tensor, mean: bool, dZq: Sequence[torch.Tensor]) -> None:
+    for q in range(b.P):
+        b.check_rows(q, dZq[q])
+    b.check_dst(G)
+    _check(lib().sar_spmm_bwd_all(b.handle, _ptr(G), _c_int(int(mean)), _c_int(dtype_code(G.dtype)),
+                                  _c_int(G.shape[-1]), _ptr_array(dZq), _stream()))
 
 
 # --------------------------------------------------------------------- GAT
@@ -270,15 +299,15 @@ def sar_gat_fwd_block(b: Blocks, q: int, Zq: torch.Tensor, s: torch.Tensor, tq: 
 
 
 def sar_gat_fwd_end(m: torch.Tensor, l: torch.Tensor, acc: torch.Tensor, out: torch.Tensor,
-                    L: torch.Tensor) -> None:
+                    L: torch.Tensor, act: int = SAR_ACT_NONE) -> None:
     n, H, D = acc.shape
-    _check(lib().sar_gat_fwd_end(_ptr(m), _ptr(l), _ptr(acc), _ptr(out), _ptr(L),
+    _check(lib().sar_gat_fwd_end(_ptr(m), _ptr(l), _ptr(acc), _c_int(act), _ptr(out), _ptr(L),
                                  _c_int(dtype_code(out.dtype)), _c_i64(n), _c_int(H), _c_int(D), _stream()))
 
 
 def sar_gat_fwd_all(b: Blocks, Zq: Sequence[torch.Tensor], s: torch.Tensor,
                     tq: Optional[Sequence[torch.Tensor]], a_l: Optional[torch.Tensor],
-                    slope: float, out: torch.Tensor, L: torch.Tensor) -> None:
+                    slope: float, out: torch.Tensor, L: torch.Tensor, act: int = SAR_ACT_NONE) -> None:
     _, H, D = out.shape
     for q in range(b.P):
         b.check_rows(q, Zq[q], None if tq is None else tq[q])
@@ -286,7 +315,7 @@ def sar_gat_fwd_all(b: Blocks, Zq: Sequence[torch.Tensor], s: torch.Tensor,
     _check(lib().sar_gat_fwd_all(b.handle, _ptr_array(Zq), _ptr(s), None if tq is None else _ptr_array(tq),
                                  _ptr(a_l),
                                  _c_int(dtype_code(out.dtype)), _c_int(H), _c_int(D), ctypes.c_float(slope),
-                                 _ptr(out), _ptr(L), _stream()))
+                                 _c_int(act), _ptr(out), _ptr(L), _stream()))
 
 
 def sar_gat_workspace_bytes(n_dst: int, n_src_max: int, H: int, D: int) -> int:
@@ -297,10 +326,14 @@ def sar_gat_workspace_bytes(n_dst: int, n_src_max: int, H: int, D: int) -> int:
 
 
 def sar_gat_bwd_begin(G: torch.Tensor, out: torch.Tensor, s: torch.Tensor, L: torch.Tensor,
-                      rec: torch.Tensor, ds: torch.Tensor) -> None:
+                      rec: torch.Tensor, ds: torch.Tensor, act: int = SAR_ACT_NONE,
+                      Gact: Optional[torch.Tensor] = None) -> None:
     n, H, D = G.shape
-    _check(lib().sar_gat_bwd_begin(_ptr(G), _ptr(out), _ptr(s), _ptr(L), _c_int(dtype_code(G.dtype)),
-                                   _ptr(rec), _ptr(ds), _c_i64(n), _c_int(H), _c_int(D), _stream()))
+    _same_shape(G, out)
+    _same_shape(G, Gact)
+    _check(lib().sar_gat_bwd_begin(_ptr(G), _ptr(out), _ptr(s), _ptr(L), _c_int(act), _ptr(Gact),
+                                   _c_int(dtype_code(G.dtype)), _ptr(rec), _ptr(ds), _c_i64(n), _c_int(H),
+                                   _c_int(D), _stream()))
 
 
 def sar_gat_bwd_block(b: Blocks, q: int, Zq: torch.Tensor, G: torch.Tensor, tq: torch.Tensor,

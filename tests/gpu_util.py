@@ -49,20 +49,53 @@ def view_arrays(b: sar.Blocks, q: int) -> dict:
     return out
 
 
-def spmm_stream(b: sar.Blocks, Zs: Sequence[torch.Tensor], mean: bool) -> torch.Tensor:
+def spmm_stream(b: sar.Blocks, Zs: Sequence[torch.Tensor], mean: bool, residual=None,
+                act=sar.SAR_ACT_NONE) -> torch.Tensor:
     F = Zs[0].shape[-1]
     acc = torch.zeros((b.n_dst, F), dtype=torch.float32, device=DEV)
     for q in range(b.P):
         sar.sar_spmm_block(b, q, Zs[q], acc)
     out = torch.empty((b.n_dst, F), dtype=Zs[0].dtype, device=DEV)
-    sar.sar_spmm_end(sar.sar_blocks_degree(b), mean, acc, out)
+    sar.sar_spmm_end(sar.sar_blocks_degree(b), mean, acc, out, residual, act)
     return out
 
 
-def spmm_all(b: sar.Blocks, Zs: Sequence[torch.Tensor], mean: bool) -> torch.Tensor:
+def spmm_all(b: sar.Blocks, Zs: Sequence[torch.Tensor], mean: bool, residual=None,
+             act=sar.SAR_ACT_NONE) -> torch.Tensor:
     out = torch.full((b.n_dst, Zs[0].shape[-1]), float("nan"), dtype=Zs[0].dtype, device=DEV)
-    sar.sar_spmm_all(b, Zs, mean, out)
+    sar.sar_spmm_all(b, Zs, mean, out, residual, act)
     return out
+
+
+@dataclass
+class SageGrads:
+    h: torch.Tensor
+    Gpre: torch.Tensor
+    dZs: List[torch.Tensor]
+    dW: torch.Tensor
+    dW_res: torch.Tensor
+    dXdst: torch.Tensor
+    dXs: List[torch.Tensor]
+
+
+def sage_layer(b: sar.Blocks, Xdst, Xs, W, W_res, dH, act, batched: bool) -> SageGrads:
+    """Eq. 1 + Eq. 2 forward and backward through the entry points, in the order Alg. 1/2 give."""
+    Zs = [linear_fwd(X, W)[0] for X in Xs]
+    res = linear_fwd(Xdst, W_res)[0]
+    h = (spmm_all if batched else spmm_stream)(b, Zs, True, res, act)
+    Gpre = torch.full(h.shape, float("nan"), dtype=h.dtype, device=DEV)
+    sar.sar_act_bwd(h, dH, act, Gpre)
+    dW = torch.zeros_like(W)
+    dW_res = torch.zeros_like(W_res)
+    dXdst = linear_bwd(Xdst, Gpre, W_res, dW_res)
+    dZs = [torch.full(Z.shape, float("nan"), dtype=Z.dtype, device=DEV) for Z in Zs]
+    if batched:
+        sar.sar_spmm_bwd_all(b, Gpre, True, dZs)
+    else:
+        for q in range(b.P):
+            sar.sar_spmm_bwd_block(b, q, Gpre, True, dZs[q])
+    dXs = [linear_bwd(Xs[q], dZs[q], W, dW) for q in range(b.P)]
+    return SageGrads(h, Gpre, dZs, dW, dW_res, dXdst, dXs)
 
 
 @dataclass
@@ -85,7 +118,8 @@ def gat_scores(Zdst, Zs, a_l, a_r):
     return s, t
 
 
-def gat_fwd_stream(b: sar.Blocks, Zdst, Zs, a_l, a_r, slope, order=None, states=None, fly=False) -> GatOut:
+def gat_fwd_stream(b: sar.Blocks, Zdst, Zs, a_l, a_r, slope, order=None, states=None, fly=False,
+                   act=sar.SAR_ACT_NONE) -> GatOut:
     """fly=True: the source score halves are formed inside the kernels (tq = NULL)."""
     H, D = a_l.shape
     s, t = gat_scores(Zdst, Zs, a_l, a_r)
@@ -100,16 +134,16 @@ def gat_fwd_stream(b: sar.Blocks, Zdst, Zs, a_l, a_r, slope, order=None, states=
             states.append((host(m), host(l), host(acc)))
     out = torch.full((n, H, D), float("nan"), dtype=Zdst.dtype, device=DEV)
     L = torch.full((n, H), float("nan"), dtype=torch.float32, device=DEV)
-    sar.sar_gat_fwd_end(m, l, acc, out, L)
+    sar.sar_gat_fwd_end(m, l, acc, out, L, act)
     return GatOut(out, L, s, t)
 
 
-def gat_fwd_all(b: sar.Blocks, Zdst, Zs, a_l, a_r, slope, fly=False) -> GatOut:
+def gat_fwd_all(b: sar.Blocks, Zdst, Zs, a_l, a_r, slope, fly=False, act=sar.SAR_ACT_NONE) -> GatOut:
     H, D = a_l.shape
     s, t = gat_scores(Zdst, Zs, a_l, a_r)
     out = torch.full((b.n_dst, H, D), float("nan"), dtype=Zdst.dtype, device=DEV)
     L = torch.full((b.n_dst, H), float("nan"), dtype=torch.float32, device=DEV)
-    sar.sar_gat_fwd_all(b, Zs, s, None if fly else t, a_l, slope, out, L)
+    sar.sar_gat_fwd_all(b, Zs, s, None if fly else t, a_l, slope, out, L, act)
     return GatOut(out, L, s, t)
 
 
@@ -124,12 +158,18 @@ class GatGrads:
 
 
 def gat_bwd(b: sar.Blocks, Zdst, Zs, G, a_l, a_r, slope, fw: GatOut, batched: bool, fly=False,
-            dZadd=None) -> GatGrads:
+            dZadd=None, act=sar.SAR_ACT_NONE) -> GatGrads:
+    """With a non-linearity fw.out is h = act(aggregate) and G the error of h."""
     H, D = a_l.shape
     n = b.n_dst
     rec = torch.empty((n, H, 4), dtype=torch.float32, device=DEV)
     ds = torch.full((n, H), float("nan"), dtype=torch.float32, device=DEV)
-    sar.sar_gat_bwd_begin(G, fw.out, fw.s, fw.L, rec, ds)
+    if act == sar.SAR_ACT_NONE:
+        sar.sar_gat_bwd_begin(G, fw.out, fw.s, fw.L, rec, ds)
+    else:
+        Gact = torch.full(G.shape, float("nan"), dtype=G.dtype, device=DEV)
+        sar.sar_gat_bwd_begin(G, fw.out, fw.s, fw.L, rec, ds, act, Gact)
+        G = Gact
     n_src_max = max(Z.shape[0] for Z in Zs)
     work = torch.empty(sar.sar_gat_workspace_bytes(n, n_src_max, H, D) // 4, dtype=torch.float32, device=DEV)
     da_l = torch.zeros((H, D), dtype=torch.float32, device=DEV)

@@ -44,7 +44,7 @@ def test_binding_covers_the_header():
 def test_validation_errors_need_no_gpu(lib):
     from paper_2111_06483_amd import sar
     i64 = ctypes.c_int64
-    assert lib.sar_version() == 1
+    assert lib.sar_version() == 2
     rc = lib.sar_gat_scores(None, 0, i64(5), 2, 3, None, None, None)
     assert rc == sar.SAR_ERR_UNSUPPORTED and b"multiple of 4" in lib.sar_last_error()
     rc = lib.sar_gat_scores(None, 7, i64(5), 2, 4, None, None, None)

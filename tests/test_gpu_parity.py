@@ -145,6 +145,10 @@ def test_spmm_parity(dtype, F, mean):
         dZ = torch.full(Zs[q].shape, float("nan"), dtype=dtype, device="cuda")
         sar.sar_spmm_bwd_block(b, q, G, mean, dZ)
         assert rel_err(f64(dZ), want_d[q]) < TOL[dtype]
+    dZs = [torch.full(z.shape, float("nan"), dtype=dtype, device="cuda") for z in Zs]
+    sar.sar_spmm_bwd_all(b, G, mean, dZs)
+    for q in range(3):
+        assert rel_err(f64(dZs[q]), want_d[q]) < TOL[dtype]
     b.close()
 
 
