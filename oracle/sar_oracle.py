@@ -128,6 +128,28 @@ def build_blocks(src, dst, part, P: int, p: int):
     return blocks, deg
 
 
+def subset_blocks(blocks: Sequence[Block], dst_ids):
+    """Blocks restricted to the destinations a layer's output is needed for (the message flow
+    graphs of App. B): row r of every new block is row dst_ids[r] of the old one, sources keep
+    their ids.  Returns (blocks, deg) like build_blocks."""
+    ids = np.asarray(dst_ids, dtype=np.int64)
+    out: List[Block] = []
+    deg = np.zeros(ids.shape[0], dtype=np.int32)
+    for b in blocks:
+        rows, cols = [], []
+        for r, i in enumerate(ids):
+            nb = b.indices[b.indptr[i]:b.indptr[i + 1]]
+            rows.append(np.full(nb.shape[0], r, dtype=np.int64))
+            cols.append(nb.astype(np.int64))
+        rows = np.concatenate(rows) if rows else np.zeros(0, dtype=np.int64)
+        cols = np.concatenate(cols) if cols else np.zeros(0, dtype=np.int64)
+        indptr, indices = csr_from_pairs(rows, cols, ids.shape[0])
+        t_indptr, t_indices = csr_from_pairs(cols, rows, b.n_src)
+        out.append(Block(int(ids.shape[0]), b.n_src, indptr, indices, t_indptr, t_indices))
+        deg += np.diff(indptr).astype(np.int32)
+    return out, deg
+
+
 # --------------------------------------------------------------------------
 # Eq. 2: sum / mean aggregation over blocks (Alg. 1 with m_{j->i} = z_j)
 # --------------------------------------------------------------------------

@@ -144,3 +144,49 @@ def test_synth_workload_blocks_are_consistent():
         rows = np.repeat(np.arange(b.n_dst), np.diff(b.indptr))
         same_row = rows[1:] == rows[:-1]
         assert np.all(np.diff(b.indices.astype(np.int64))[same_row] > 0)
+
+
+# ------------------------------------------------------- destination subsets (App. B)
+
+@pytest.mark.parametrize("P,p", [(1, 0), (3, 2)])
+def test_subset_blocks_equal_blocks_of_the_filtered_edge_list(P, p):
+    """Restricting the destinations is the same as dropping every edge into another destination
+    from the edge list and renumbering: checked edge by edge against a brute-force filter."""
+    rng = np.random.default_rng(31)
+    src, dst, part = tiny_graph(rng, 80, 700, P, simple=False)
+    blocks, deg = orc.build_blocks(src, dst, part, P, p)
+    members = [np.flatnonzero(part == q) for q in range(P)]
+    n_p = len(members[p])
+    ids = rng.permutation(n_p)[: n_p // 3]                 # any order, not sorted
+    sub, sub_deg = orc.subset_blocks(blocks, ids)
+    row_of = {int(members[p][i]): r for r, i in enumerate(ids)}
+    for q in range(P):
+        lid = {int(v): k for k, v in enumerate(members[q])}
+        want = sorted((row_of[int(d)], lid[int(s_)]) for s_, d in zip(src, dst)
+                      if int(d) in row_of and part[s_] == q)
+        b = sub[q]
+        got = sorted((r, int(j)) for r in range(len(ids)) for j in b.indices[b.indptr[r]:b.indptr[r + 1]])
+        assert got == want
+        got_t = sorted((int(i), j) for j in range(b.n_src) for i in b.t_indices[b.t_indptr[j]:b.t_indptr[j + 1]])
+        assert got_t == want
+        assert b.n_dst == len(ids) and b.n_src == len(members[q])
+    assert np.array_equal(sub_deg, deg[ids])
+
+
+def test_subset_aggregation_is_the_row_subset_of_the_full_one():
+    rng = np.random.default_rng(32)
+    P, p, F = 3, 0, 5
+    src, dst, part = tiny_graph(rng, 60, 500, P)
+    blocks, deg = orc.build_blocks(src, dst, part, P, p)
+    Z, Zs, members = global_features(rng, part, P, F)
+    ids = np.array([5, 0, 7, 7, 2])                        # a repeated id gives a repeated row
+    sub, _ = orc.subset_blocks(blocks, ids)
+    assert np.array_equal(orc.spmm(sub, Zs, True), orc.spmm(blocks, Zs, True)[ids])
+    G = rng.standard_normal((len(ids), F))
+    full_G = np.zeros((blocks[0].n_dst, F))
+    np.add.at(full_G, ids, G)
+    # sum aggregation: the error of a subset is the full backward of the error scattered to its rows
+    want = orc.spmm_bwd(blocks, full_G, False)
+    got = orc.spmm_bwd(sub, G, False)
+    for q in range(P):
+        assert np.allclose(got[q], want[q], rtol=0, atol=1e-12)
