@@ -43,6 +43,9 @@ def parse():
                     help="all: one launch over the P blocks; stream: one launch per block")
     ap.add_argument("--act", default="none", choices=["none", "relu"],
                     help="non-linearity of Eq. 3 fused into the GAT forward epilogue and backward begin")
+    ap.add_argument("--dst-frac", type=float, default=1.0,
+                    help="aggregate only into this fraction of the worker's destinations (a seeded random "
+                         "subset, as a message flow graph restricts a layer, App. B); sources stay complete")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this size (to scale rocprofv3's FETCH_SIZE/WRITE_SIZE)")
@@ -53,8 +56,9 @@ def parse():
 class Layer:
     """Device state of one worker's GAT layer; methods only call the C ABI."""
 
-    def __init__(self, w, torch, sar, synth, act=0):
+    def __init__(self, w, torch, sar, synth, act=0, dst_frac=1.0):
         self.torch, self.sar, self.w, self.act = torch, sar, w, act
+        self.subset = dst_frac < 1.0
         dev = "cuda"
         H, D, P, p = w.H, w.D, w.P, w.p
         self.H, self.D, self.F, self.P, self.p = H, D, H * D, P, p
@@ -62,15 +66,28 @@ class Layer:
         self.blocks = sar.sar_blocks_build(w.src, w.dst, w.part, P, p)
         torch.cuda.synchronize()
         self.builder_s = time.perf_counter() - t0
+        members = [w.members(q) for q in range(P)]
+        dst_members = members[p]
+        if self.subset:
+            n_p = self.blocks.n_dst
+            u = synth.uniform01(9, 0, torch.arange(n_p, device=dev))
+            ids = torch.nonzero(u < dst_frac).flatten().to(torch.int32)
+            t0 = time.perf_counter()
+            self.blocks_full = self.blocks
+            self.blocks = sar.sar_blocks_subset(self.blocks_full, ids)
+            torch.cuda.synchronize()
+            self.subset_s = time.perf_counter() - t0
+            dst_members = members[p][ids.long()]
         self.views = [self.blocks.view(q) for q in range(P)]
         self.E = sum(v.nnz for v in self.views)
         n = self.blocks.n_dst
         self.n = n
         self.W, self.a_l, self.a_r = synth.gat_params(3, w.f_in, H, D, device=dev)
-        members = [w.members(q) for q in range(P)]
         self.members = members
         self.X = synth.normal_rows(2, members[p], w.f_in, dtype=w.dtype)
-        self.G = synth.normal_rows(4, members[p], self.F, dtype=w.dtype).reshape(n, H, D)
+        # destination side: the same rows, or with a subset only the listed ones
+        self.Xd = synth.normal_rows(2, dst_members, w.f_in, dtype=w.dtype) if self.subset else self.X
+        self.G = synth.normal_rows(4, dst_members, self.F, dtype=w.dtype).reshape(n, H, D)
         # features of the other partitions, as fetched: Z_q = X_q W produced before timing
         self.Zs, self.ts = [], []
         for q in range(P):
@@ -82,6 +99,7 @@ class Layer:
             del Xq
         f32 = dict(dtype=torch.float32, device=dev)
         self.Zp = torch.empty((n, H, D), dtype=w.dtype, device=dev)
+        self.Zp_src = torch.empty((self.X.shape[0], H, D), dtype=w.dtype, device=dev) if self.subset else self.Zp
         self.s = torch.empty((n, H), **f32)
         self.tp = torch.empty((n, H), **f32)
         self.m = torch.empty((n, H), **f32)
@@ -98,11 +116,11 @@ class Layer:
         self.da_l = torch.zeros((H, D), **f32)
         self.da_r = torch.zeros((H, D), **f32)
         self.dW = torch.zeros_like(self.W)
-        self.dX_dst = torch.empty_like(self.X)
+        self.dX_dst = torch.empty_like(self.Xd)
         self.dX_src = torch.empty_like(self.X)
         n_src_max = max(v.n_src for v in self.views)
         self.work = torch.empty(sar.sar_gat_workspace_bytes(n, n_src_max, H, D) // 4, **f32)
-        self.lwork = torch.empty(max(1, sar.sar_linear_workspace_bytes(n, w.f_in, self.F) // 4), **f32)
+        self.lwork = torch.empty(max(1, sar.sar_linear_workspace_bytes(self.X.shape[0], w.f_in, self.F) // 4), **f32)
         torch.cuda.synchronize()
 
     def step(self, mode, ev=None):
@@ -110,9 +128,11 @@ class Layer:
         mark = (lambda k: ev[k].record()) if ev is not None else (lambda k: None)
         mark("t0")
         # Eq. 1 for the worker's own rows, with both score halves
-        sar.sar_linear_fwd(self.X, self.W, self.Zp.reshape(self.n, self.F), self.a_r, self.s, self.a_l, self.tp)
+        sar.sar_linear_fwd(self.Xd, self.W, self.Zp.reshape(self.n, self.F), self.a_r, self.s, self.a_l, self.tp)
+        if self.subset:                      # the local block needs every row of Z_p as a source
+            sar.sar_linear_fwd(self.X, self.W, self.Zp_src.reshape(-1, self.F))
         Zs = list(self.Zs)
-        Zs[p] = self.Zp                      # the local block reads the rows just produced
+        Zs[p] = self.Zp_src                  # the local block reads the rows just produced
         # the fetched blocks arrive as raw Z_q: their score halves t_q = <a_l, z_j> are formed
         # inside the gather kernels (tq = None), so no separate pass over Z_q is needed
         mark("fwd0")
@@ -140,9 +160,12 @@ class Layer:
                                       self.dZs[q], self.dts[q], self.ds, self.da_l, self.work)
         mark("bwd1")
         # E_p = E_{p->p} + destination-score term: everything this worker itself produced for its rows
-        sar.sar_gat_bwd_end(self.Zp, self.ds, self.a_r, self.dZs[p], self.dZdst, self.da_r, self.work)
+        sar.sar_gat_bwd_end(self.Zp, self.ds, self.a_r, None if self.subset else self.dZs[p], self.dZdst,
+                            self.da_r, self.work)
         # Z_p.backward(E_p)
-        sar.sar_linear_bwd(self.X, self.dZdst, self.W, self.dW, self.dX_dst, self.lwork)
+        sar.sar_linear_bwd(self.Xd, self.dZdst, self.W, self.dW, self.dX_dst, self.lwork)
+        if self.subset:                      # destination and source roles of the own rows kept apart
+            sar.sar_linear_bwd(self.X, self.dZs[p], self.W, self.dW, self.dX_src, self.lwork)
         mark("t1")
 
     # ---- algorithmic bytes of the gather kernels (what the method must move at least)
@@ -402,7 +425,8 @@ def main():
     if args.workload == "cfg2":
         sage_bench(args, w, torch, sar, synth)
         return
-    layer = Layer(w, torch, sar, synth, act=sar.SAR_ACT_RELU if args.act == "relu" else sar.SAR_ACT_NONE)
+    layer = Layer(w, torch, sar, synth, act=sar.SAR_ACT_RELU if args.act == "relu" else sar.SAR_ACT_NONE,
+                  dst_frac=args.dst_frac)
 
     if args.calib_copy_mib:
         a = torch.ones(args.calib_copy_mib << 18, dtype=torch.float32, device="cuda")
@@ -445,7 +469,7 @@ def main():
                              "alg_GBs": alg[kname] / (ms * 1e-3) / 1e9,
                              "gather_volume_GBs": gather[kname] / (ms * 1e-3) / 1e9,
                              "traffic_bytes": MEASURED_TRAFFIC.get((args.workload, args.mode, kname))
-                             if args.scale == 1.0 else None}
+                             if args.scale == 1.0 and args.dst_frac == 1.0 else None}
     dom = max(per_kernel, key=lambda k: per_kernel[k]["avg_ms"])
     d = per_kernel[dom]
     # in stream mode the events bracket P launches of the kernel; report per launch
@@ -462,12 +486,13 @@ def main():
         "config": {"workload": "%s: one worker's share of a %d-node graph, %d-way split, %d destinations, "
                                "%d in-edges over %d resident source blocks, GAT %d heads x %d, in_dim %d"
                                % (args.workload, w.N, w.P, layer.n, layer.E, w.P, w.H, w.D, w.f_in),
-                   "mode": args.mode, "scale": args.scale, "act": args.act},
+                   "mode": args.mode, "scale": args.scale, "act": args.act, "dst_frac": args.dst_frac},
         "phases_ms": {"step_events": all_ms, "gat_fwd": fwd_ms, "gat_bwd": bwd_ms,
                       "gat_bwd_kernel_rows_ge8": wide_ms, "gat_bwd_kernel_rows_lt8": narrow_ms,
                       "other (XW fwd+bwd, scores, begin/end)": all_ms - fwd_ms - bwd_ms},
         "aggregation_only_edges_per_s": layer.E / ((fwd_ms + bwd_ms) * 1e-3),
         "builder_s": layer.builder_s,
+        **({"subset_builder_s": layer.subset_s} if layer.subset else {}),
         "roofline": {"bound": "hbm", "kernel": d["kernel"],
                      "achieved": d["alg_GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": d["alg_GBs"] / HBM_PEAK_GBS,
@@ -479,7 +504,7 @@ def main():
                      "kernels": per_kernel},
         "ceilings": ceilings,
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not layer.subset:
         res["cpu_baseline"] = cpu_baseline(layer, args.cpu_blocks)
     print(json.dumps(res))
 

@@ -137,6 +137,18 @@ int sar_blocks_build(const void* src, const void* dst, int idx_bytes, int64_t E,
 int sar_blocks_wrap(int P, int64_t n_dst, const int64_t* n_src, const int32_t* const* indptr,
                     const int32_t* const* indices, int flags, void* stream, sar_blocks_t** out);
 
+/* Blocks restricted to the destinations a layer's output is needed for (the
+ * message flow graphs of App. B: only the nodes that can influence a labelled
+ * output are updated at each layer).  Row r of every block of the new handle
+ * is row dst_ids[r] of b (device int32 [n_sub], each in [0, n_dst), any order;
+ * a repeated id gives a repeated row); sources keep their local ids, so Z_q,
+ * dZ_q keep their shapes and the new handle's `touched` lists name the source
+ * rows the previous layer has to produce.  Destination-side tensors of calls
+ * on the new handle have n_sub rows.  The new handle owns its arrays and is
+ * independent of b; free it with sar_blocks_free. */
+int sar_blocks_subset(const sar_blocks_t* b, const int32_t* dst_ids, int64_t n_sub, int flags,
+                      void* stream, sar_blocks_t** out);
+
 /* *P = number of blocks, *n_dst = |V_p|. */
 int sar_blocks_info(const sar_blocks_t* b, int* P, int64_t* n_dst);
 

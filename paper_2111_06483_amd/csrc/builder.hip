@@ -773,6 +773,7 @@ int check_err_flag(int* err_d, hipStream_t st)
     if (err & 2) return sar::fail(SAR_ERR_INVALID_ARG, "edge list holds a node id outside [0,N)");
     if (err & 4) return sar::fail(SAR_ERR_INVALID_ARG, "indices[] holds a column outside [0,n_src)");
     if (err & 8) return sar::fail(SAR_ERR_INVALID_ARG, "indptr[] is not non-decreasing");
+    if (err & 16) return sar::fail(SAR_ERR_INVALID_ARG, "dst_ids[] holds a row outside [0,n_dst)");
     return SAR_OK;
 }
 
@@ -857,6 +858,43 @@ int build_from_edges(sar_blocks* h, const void* src, const void* dst, int idx_by
     }
     SAR_HIP(hipStreamSynchronize(st));
     return SAR_OK;
+}
+
+// ------------------------------------------------ destination subsets
+
+// cnt[r] = length of row ids[r] (0 and an error flag for an id out of range); cnt[n_sub] = 0
+__global__ __launch_bounds__(kThreads) void k_subset_count(const int32_t* __restrict__ indptr,
+                                                           const int32_t* __restrict__ ids, int64_t n_sub,
+                                                           int64_t n_dst, int32_t* __restrict__ cnt, int* err)
+{
+    for (int64_t r = (int64_t)blockIdx.x * kThreads + threadIdx.x; r <= n_sub; r += (int64_t)gridDim.x * kThreads) {
+        int c = 0;
+        if (r < n_sub) {
+            const int i = ids[r];
+            if (i < 0 || i >= n_dst)
+                atomicOr(err, 16);
+            else
+                c = indptr[i + 1] - indptr[i];
+        }
+        cnt[r] = c;
+    }
+}
+
+// new row r = old row ids[r], one wavefront per row
+__global__ __launch_bounds__(kThreads) void k_subset_copy(const int32_t* __restrict__ indptr,
+                                                          const int32_t* __restrict__ indices,
+                                                          const int32_t* __restrict__ ids, int64_t n_sub,
+                                                          const int32_t* __restrict__ new_indptr,
+                                                          int32_t* __restrict__ new_indices)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = ((int64_t)blockIdx.x * kThreads + threadIdx.x) >> 6;
+    const int64_t n_waves = ((int64_t)gridDim.x * kThreads) >> 6;
+    for (int64_t r = wave; r < n_sub; r += n_waves) {
+        const int i = ids[r];
+        const int beg = indptr[i], len = indptr[i + 1] - beg, at = new_indptr[r];
+        for (int k = lane; k < len; k += 64) new_indices[at + k] = indices[beg + k];
+    }
 }
 
 void destroy(sar_blocks* h)
@@ -995,5 +1033,63 @@ extern "C" int sar_blocks_degree(const sar_blocks_t* b, const int32_t** deg)
 extern "C" int sar_blocks_free(sar_blocks_t* b)
 {
     destroy(b);
+    return SAR_OK;
+}
+
+extern "C" int sar_blocks_subset(const sar_blocks_t* b, const int32_t* dst_ids, int64_t n_sub, int flags,
+                                 void* stream, sar_blocks_t** out)
+{
+    SAR_CHECK_ARG(out != nullptr, "out is null");
+    *out = nullptr;
+    SAR_CHECK_ARG(b != nullptr, "handle is null");
+    SAR_CHECK_ARG(n_sub >= 0 && n_sub < ((int64_t)1 << 31), "n_sub must be in [0, 2^31)");
+    SAR_CHECK_ARG(n_sub == 0 || dst_ids != nullptr, "dst_ids is null");
+    SAR_CHECK_ARG((flags & ~(SAR_BUILD_TRANSPOSE | SAR_BUILD_FUSED)) == 0, "unknown flags 0x%x", flags);
+    hipStream_t st = sar::as_stream(stream);
+    sar_blocks* h = new (std::nothrow) sar_blocks();
+    if (!h) return sar::fail(SAR_ERR_HIP, "out of host memory");
+    h->P = b->P;
+    h->n_dst = n_sub;
+    h->flags = flags;
+    h->blk.resize(b->P);
+    auto body = [&]() -> int {
+        DeviceTemps tmp;
+        int* err_d = nullptr;
+        SAR_TRY(tmp.alloc(&err_d, 1));
+        SAR_HIP(hipMemsetAsync(err_d, 0, sizeof(int), st));
+        for (int q = 0; q < b->P; ++q) {
+            const Block& from = b->blk[q];
+            Block& to = h->blk[q];
+            to.n_dst = n_sub;
+            to.n_src = from.n_src;
+            int32_t* indptr = nullptr;
+            SAR_TRY(own(h, &indptr, n_sub + 1));
+            k_subset_count<<<grid_for(n_sub + 1, kThreads, 4096), kThreads, 0, st>>>(from.indptr, dst_ids, n_sub,
+                                                                                    b->n_dst, indptr, err_d);
+            SAR_LAUNCH_CHECK();
+            SAR_TRY(exclusive_scan(indptr, indptr, n_sub + 1, st, tmp));
+            int32_t nnz = 0;
+            SAR_HIP(hipMemcpyAsync(&nnz, indptr + n_sub, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+            SAR_TRY(check_err_flag(err_d, st));      // synchronises; ids are in range beyond this point
+            if (nnz < 0) return sar::fail(SAR_ERR_UNSUPPORTED, "block %d of the subset holds 2^31 edges or more", q);
+            int32_t* indices = nullptr;
+            SAR_TRY(own(h, &indices, nnz));
+            if (nnz > 0) {
+                k_subset_copy<<<grid_for(n_sub * 64, kThreads, 1 << 16), kThreads, 0, st>>>(
+                    from.indptr, from.indices, dst_ids, n_sub, indptr, indices);
+                SAR_LAUNCH_CHECK();
+            }
+            to.indptr = indptr;
+            to.indices = indices;
+            to.nnz = nnz;
+        }
+        return derive(h, st);
+    };
+    int rc = body();
+    if (rc != SAR_OK) {
+        destroy(h);
+        return rc;
+    }
+    *out = h;
     return SAR_OK;
 }

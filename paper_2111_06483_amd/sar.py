@@ -70,7 +70,7 @@ def lib() -> ctypes.CDLL:
 
 EXPORTS = [
     "sar_last_error", "sar_version",
-    "sar_blocks_build", "sar_blocks_wrap", "sar_blocks_info", "sar_blocks_get", "sar_blocks_degree",
+    "sar_blocks_build", "sar_blocks_wrap", "sar_blocks_subset", "sar_blocks_info", "sar_blocks_get", "sar_blocks_degree",
     "sar_blocks_free",
     "sar_spmm_block", "sar_spmm_end", "sar_spmm_all", "sar_act_bwd", "sar_spmm_bwd_block", "sar_spmm_bwd_all",
     "sar_gat_scores", "sar_gat_fwd_begin", "sar_gat_fwd_block", "sar_gat_fwd_end", "sar_gat_fwd_all",
@@ -216,6 +216,16 @@ def sar_blocks_wrap(n_dst: int, n_src: Sequence[int], indptr: Sequence[torch.Ten
     _check(lib().sar_blocks_wrap(_c_int(P), _c_i64(n_dst), ns, _ptr_array(indptr), _ptr_array(indices),
                                  _c_int(flags), _stream(), ctypes.byref(h)))
     return Blocks(h, keep=(list(indptr), list(indices)))
+
+
+def sar_blocks_subset(b: Blocks, dst_ids: torch.Tensor,
+                      flags: int = SAR_BUILD_TRANSPOSE | SAR_BUILD_FUSED) -> Blocks:
+    if dst_ids.dtype != torch.int32 or dst_ids.dim() != 1 or not dst_ids.is_contiguous():
+        raise SarError(SAR_ERR_INVALID_ARG, "dst_ids must be a contiguous 1-d int32 tensor")
+    h = _vp(None)
+    _check(lib().sar_blocks_subset(b.handle, _ptr(dst_ids), _c_i64(dst_ids.numel()), _c_int(flags), _stream(),
+                                   ctypes.byref(h)))
+    return Blocks(h)
 
 
 def sar_blocks_degree(b: Blocks) -> torch.Tensor:

@@ -161,3 +161,90 @@ def test_act_bwd_and_errors():
     assert e.value.code == sar.SAR_ERR_UNSUPPORTED
     with pytest.raises(sar.SarError):
         sar.sar_act_bwd(h, dH[:, :4], sar.SAR_ACT_RELU, G)
+
+
+# ------------------------------------------------------- destination subsets (App. B)
+
+@pytest.mark.parametrize("P,p,frac", [(3, 1, 0.3), (1, 0, 0.05), (4, 0, 1.0)])
+def test_subset_blocks_bit_exact_and_aggregations(P, p, frac):
+    """Blocks restricted to a destination subset: index arrays bit-exact against the oracle's,
+    and both aggregations on the subset equal (bit for bit in the forward pass) the matching
+    rows of the full ones."""
+    src, dst, part, rng = make_graph(41, 4000, 50000, P, simple=False)
+    want_full, _ = orc.build_blocks(src, dst, part, P, p)
+    b = gu.build_blocks(src, dst, part, P, p)
+    n = b.n_dst
+    ids = rng.permutation(n)[: max(1, int(n * frac))].astype(np.int32)
+    want, want_deg = orc.subset_blocks(want_full, ids)
+    ids_d = gu.dev(ids, torch.int32)
+    sb = sar.sar_blocks_subset(b, ids_d)
+    assert sb.n_dst == len(ids) and sb.P == P
+    assert np.array_equal(sar.sar_blocks_degree(sb).cpu().numpy(), want_deg)
+    for q in range(P):
+        v = gu.view_arrays(sb, q)
+        assert v["n_src"] == want[q].n_src and v["nnz"] == want[q].nnz
+        assert np.array_equal(v["indptr"], want[q].indptr.astype(np.int32))
+        assert np.array_equal(v["indices"], want[q].indices)
+        assert np.array_equal(v["t_indptr"], want[q].t_indptr.astype(np.int32))
+        assert np.array_equal(v["t_indices"], want[q].t_indices)
+        # the sources the previous layer has to produce for this block
+        assert np.array_equal(v["touched"], np.flatnonzero(np.diff(want[q].t_indptr) > 0))
+
+    H, D = 4, 64
+    F = H * D
+    Zs = [feats(rng, w.n_src, F, torch.float32).cuda() for w in want]
+    full = gu.spmm_all(b, Zs, True)
+    sub = gu.spmm_all(sb, Zs, True)
+    assert torch.equal(sub, full[ids_d.long()])
+    assert rel_err(f64(sub), orc.spmm(want, [f64(z) for z in Zs], True)) < 1e-4
+
+    bound = np.sqrt(6.0 / (D + 1))
+    a_l = torch.from_numpy(rng.uniform(-bound, bound, (H, D)).astype(np.float32)).cuda()
+    a_r = torch.from_numpy(rng.uniform(-bound, bound, (H, D)).astype(np.float32)).cuda()
+    Z3 = [z.reshape(-1, H, D) for z in Zs]
+    Zdst_full = Z3[p]
+    Zdst = Zdst_full[ids_d.long()].contiguous()
+    fw_full = gu.gat_fwd_all(b, Zdst_full, Z3, a_l, a_r, SLOPE, fly=True)
+    fw = gu.gat_fwd_all(sb, Zdst, Z3, a_l, a_r, SLOPE, fly=True)
+    assert torch.equal(fw.out, fw_full.out[ids_d.long()]) and torch.equal(fw.L, fw_full.L[ids_d.long()])
+    wf = orc.gat_fwd(want, f64(Zdst), [f64(z) for z in Z3], f64(a_l), f64(a_r), SLOPE)
+    assert rel_err(f64(fw.out), wf.out) < 1e-4
+    G = feats(rng, len(ids), F, torch.float32).cuda().reshape(-1, H, D)
+    wb = orc.gat_bwd(want, f64(Zdst), [f64(z) for z in Z3], f64(G), f64(a_l), f64(a_r), SLOPE, wf)
+    for batched in (False, True):
+        g = gu.gat_bwd(sb, Zdst, Z3, G, a_l, a_r, SLOPE, fw, batched, fly=True)
+        for q in range(P):
+            assert rel_err(f64(g.dZs[q]), wb.dZs[q]) < 1e-4, q
+            # sources no listed destination reads get no error
+            untouched = np.diff(want[q].t_indptr) == 0
+            assert not f64(g.dZs[q])[untouched].any()
+        assert rel_err(f64(g.dZdst), wb.dZdst) < 1e-4
+        assert rel_err(f64(g.da_l), wb.da_l) < 1e-4
+        assert rel_err(f64(g.da_r), wb.da_r) < 1e-4
+    sb.close()
+    b.close()
+
+
+def test_subset_edge_cases_and_errors():
+    src, dst, part, rng = make_graph(42, 1000, 8000, 2, hubs=False)
+    b = gu.build_blocks(src, dst, part, 2, 0)
+    want_full, _ = orc.build_blocks(src, dst, part, 2, 0)
+    # empty subset, repeated ids
+    e = sar.sar_blocks_subset(b, torch.zeros(0, dtype=torch.int32, device="cuda"))
+    assert e.n_dst == 0 and e.view(0).nnz == 0
+    e.close()
+    ids = np.array([3, 3, 0, 3], dtype=np.int32)
+    r = sar.sar_blocks_subset(b, gu.dev(ids, torch.int32))
+    want, _ = orc.subset_blocks(want_full, ids)
+    for q in range(2):
+        v = gu.view_arrays(r, q)
+        assert np.array_equal(v["indptr"], want[q].indptr.astype(np.int32))
+        assert np.array_equal(v["indices"], want[q].indices)
+    r.close()
+    for bad in ([0, b.n_dst], [-1]):
+        with pytest.raises(sar.SarError) as err:
+            sar.sar_blocks_subset(b, torch.tensor(bad, dtype=torch.int32, device="cuda"))
+        assert err.value.code == sar.SAR_ERR_INVALID_ARG
+    with pytest.raises(sar.SarError):
+        sar.sar_blocks_subset(b, torch.zeros(3, dtype=torch.int64, device="cuda"))
+    b.close()
