@@ -88,6 +88,24 @@ class Sample:
         return c_lid[self.new_id[global_ids]]
 
 
+def kink_rows(blocks, s, ts, rel=3e-6):
+    """Destinations and, per block, sources with an edge whose LeakyReLU argument s_i + t_j is so
+    close to zero that fp32 and fp64 need not agree on its sign.  The slope the error of that
+    edge is multiplied with (1 or `slope`) is then a discrete choice the two sides may take
+    differently, and it moves ds_i and dt_j by a whole term: those rows are left out of the
+    comparisons of the score gradients (from the oracle's own values, before any comparison).
+    rel: the scores of the two sides differ by up to about 1e-6 of their scale in fp32."""
+    scale = max(np.abs(s).max(), max(np.abs(t).max() for t in ts))
+    bad_dst = np.zeros(blocks[0].n_dst, dtype=bool)
+    bad_src = [np.zeros(b.n_src, dtype=bool) for b in blocks]
+    for q, b in enumerate(blocks):
+        rows = np.repeat(np.arange(b.n_dst), np.diff(b.indptr))
+        amb = (np.abs(s[rows] + ts[q][b.indices]) < rel * scale).any(axis=1)
+        bad_dst[rows[amb]] = True
+        bad_src[q][b.indices[amb]] = True
+    return bad_dst, bad_src
+
+
 def check_gat(name, n_dst_samples, n_src_samples):
     w = synth.make_workload(name, device="cuda")
     H, D, P, p, F = w.H, w.D, w.P, w.p, w.H * w.D
@@ -141,8 +159,11 @@ def check_gat(name, n_dst_samples, n_src_samples):
     assert (~fin).sum() >= min(n_empty, 1)                                # empty rows, if any, were sampled
     assert rel_err(Lg[fin], Lw[fin]) < (1e-4 if dt == torch.float32 else 2e-3)
     assert np.all(got_out[~fin] == 0)
-    assert rel_err(f64(g.ds[D_full]), obw.ds[D_comp]) < tol
-    assert rel_err(f64(g.dZdst[D_full]), obw.dZdst[D_comp]) < tol
+    bad_dst, bad_src = kink_rows(smp.blocks, ofw.s, ofw.t)
+    ok = ~bad_dst[D_comp]
+    assert ok.mean() > 0.9
+    assert rel_err(f64(g.ds[D_full])[ok], obw.ds[D_comp][ok]) < tol
+    assert rel_err(f64(g.dZdst[D_full])[ok], obw.dZdst[D_comp][ok]) < tol
     # sources: the sampled ones have all their edges inside the subgraph
     n_checked = 0
     for q in range(P):
@@ -151,8 +172,9 @@ def check_gat(name, n_dst_samples, n_src_samples):
             continue
         jf = smp.rows_in_full(w, q, Sq)
         jc = smp.rows_in_compact(w, q, Sq).cpu().numpy()
-        assert rel_err(f64(g.dZs[q][jf]), obw.dZs[q].reshape(-1, H, D)[jc]) < tol, q
-        assert rel_err(f64(g.dts[q][jf]), obw.dt[q][jc]) < tol, q
+        okq = ~bad_src[q][jc]
+        assert rel_err(f64(g.dZs[q][jf])[okq], obw.dZs[q].reshape(-1, H, D)[jc][okq]) < tol, q
+        assert rel_err(f64(g.dts[q][jf])[okq], obw.dt[q][jc][okq]) < tol, q
         n_checked += Sq.numel()
     assert n_checked >= n_src_samples
 
