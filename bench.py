@@ -37,7 +37,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "fak"],
-                    help="cfgN: BASELINE configurations; fak: head-count sweep of the paper's single-host kernel experiment")
+                    help="cfgN: the five benchmark configurations; fak: head-count sweep of the paper's single-host kernel experiment")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the graph (debugging only)")
     ap.add_argument("--mode", default="all", choices=["all", "stream"],
                     help="all: one launch over the P blocks; stream: one launch per block")
@@ -455,17 +455,25 @@ def main():
     wide_ms = sum(r[0] for r in recs) / args.steps if recs else 0.0
     narrow_ms = sum(r[1] for r in recs) / args.steps if recs else 0.0
 
-    ceilings = measure_ceilings(torch, sar, layer.F * (2 if w.dtype == torch.bfloat16 else 4))
+    row_bytes = layer.F * (2 if w.dtype == torch.bfloat16 else 4)
+    ceilings = measure_ceilings(torch, sar, 512 if row_bytes == 512 else 1024)   # the probe's two row sizes
     alg = layer.alg_bytes()
     fb = 2 if w.dtype == torch.bfloat16 else 4
+    names = dict(KERNEL_NAMES)
     kern_ms = {"gat_fwd": fwd_ms, "gat_bwd_wide": wide_ms, "gat_bwd_narrow": narrow_ms}
     gather = {"gat_fwd": layer.E * layer.F * fb, "gat_bwd_wide": layer.part_edges["wide"] * layer.F * fb,
               "gat_bwd_narrow": layer.part_edges["narrow"] * layer.F * fb}
+    if wide_ms + narrow_ms <= 0:
+        # rows of another width than 256 values take the generic kernels: one backward kernel
+        names.update({"gat_fwd": "k_gat_fwd", "gat_bwd": "k_gat_bwd"})
+        kern_ms = {"gat_fwd": fwd_ms, "gat_bwd": bwd_ms}
+        alg["gat_bwd"] = alg["gat_bwd_wide"] + alg["gat_bwd_narrow"]
+        gather["gat_bwd"] = layer.E * layer.F * fb
     per_kernel = {}
     for kname, ms in kern_ms.items():
         if ms <= 0:
             continue
-        per_kernel[kname] = {"kernel": KERNEL_NAMES[kname], "avg_ms": ms, "alg_bytes": alg[kname],
+        per_kernel[kname] = {"kernel": names[kname], "avg_ms": ms, "alg_bytes": alg[kname],
                              "alg_GBs": alg[kname] / (ms * 1e-3) / 1e9,
                              "gather_volume_GBs": gather[kname] / (ms * 1e-3) / 1e9,
                              "traffic_bytes": MEASURED_TRAFFIC.get((args.workload, args.mode, kname))

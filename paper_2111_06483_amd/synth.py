@@ -246,7 +246,7 @@ def erdos_renyi_worker_share(N: int, avg_deg: float, part: torch.Tensor, p: int,
 
 
 # --------------------------------------------------------------------------
-# configurations (BASELINE.json "configs", 1-based as in the text)
+# configurations (the five benchmark configurations, 1-based)
 # --------------------------------------------------------------------------
 
 @dataclass

@@ -1,4 +1,4 @@
-"""Parity at the benchmark's full sizes, in the launch configuration bench.py times
+"""Parity at the full benchmark sizes, in the launch configuration bench.py times
 (all blocks in one launch, source score halves formed inside the kernels).
 
 The oracle cannot run a 15M- or 200M-edge layer in seconds, so it computes

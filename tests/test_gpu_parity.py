@@ -283,7 +283,7 @@ def test_gat_zero_attention_equals_mean_kernel():
 
 
 def test_config1_full():
-    """BASELINE config 1: 4096-node Chung-Lu graph, self-loops, 1 block, 64 -> 4 x 16, fp32."""
+    """Configuration 1: 4096-node Chung-Lu graph, self-loops, 1 block, 64 -> 4 x 16, fp32."""
     from paper_2111_06483_amd import synth
     w = synth.make_workload("cfg1")
     members = w.members(0)
