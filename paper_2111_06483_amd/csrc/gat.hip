@@ -703,6 +703,15 @@ struct HeadGroups {
     size_t fb;           // bytes per feature value
 };
 
+// Lanes per head of the specialised kernels for head width D: the power of two >= D/4 (4..64), or 0.
+int lanes_per_head(int D)
+{
+    if (D % 4 != 0 || D > 256) return 0;
+    int lph = 4;
+    while (lph * 4 < D) lph *= 2;
+    return lph;
+}
+
 HeadGroups head_groups(int dtype, int H, int D)
 {
     HeadGroups g;
@@ -710,6 +719,9 @@ HeadGroups head_groups(int dtype, int H, int D)
     int hg = std::max<int>(1, (int)(1024 / (D * g.fb)));
     hg = std::min(hg, H);
     while (H % hg != 0) --hg;
+    // groups of 64/LPH heads fill one wavefront of the specialised kernels exactly
+    const int lph = lanes_per_head(D);
+    if (lph >= 16 && H % (64 / lph) == 0) hg = 64 / lph;
     g.Hg = hg;
     g.n = H / hg;
     g.Fg = hg * D;
@@ -767,25 +779,35 @@ unsigned persistent_grid_for(int64_t n_rows, int64_t n_long, int resident)
     return (unsigned)std::max<int64_t>(1, std::min<int64_t>(want, resident));
 }
 
-// F = 256 and a power-of-two head width: the specialised kernels apply.
-int fast_lph(int H, int D, int ldz)
+// Whether the specialised kernels take a launch of H heads of width D in rows of stride ldz, and
+// in which geometry: exact (contiguous rows of 256 values, power-of-two head width) or padded
+// (64/LPH heads of any width up to 4*LPH, any row stride; built for LPH = 16, 32, 64).
+struct FastGeo {
+    int lph;     // 0: not applicable
+    bool pad;
+};
+
+FastGeo fast_geo(int H, int D, int ldz)
 {
-    if (H * D != f256::kF || ldz != f256::kF || D % 4 != 0) return 0;
-    const int lph = D / 4;
-    return (lph >= 4 && (lph & (lph - 1)) == 0) ? lph : 0;
+    const int lph = lanes_per_head(D);
+    if (lph == 0 || H * lph != 64) return FastGeo{0, false};
+    const bool exact = D == 4 * lph && ldz == f256::kF;
+    if (!exact && lph < 16) return FastGeo{0, false};
+    return FastGeo{lph, !exact};
 }
 
-template <typename T, int LPH, bool ALL, bool FLY>
+template <typename T, int LPH, bool ALL, bool FLY, bool PAD>
 int launch_fwd_f256(const FwdArgs& a, const PtrTab& zt, const PtrTab& tt, hipStream_t st)
 {
     constexpr int B = LPH >= 8 ? 8 : 4;
-    auto fn = f256::k_gat_fwd_f256<T, LPH, B, ALL, FLY>;
+    auto fn = f256::k_gat_fwd_f256<T, LPH, B, ALL, FLY, PAD>;
     static const int resident = resident_workgroups(fn);
     f256::FwdP p{};
     p.indptr = a.indptr; p.indices = a.indices; p.rows = a.rows;
     p.n_rows = a.n_rows; p.n_long = a.n_long;
     p.Z = a.Z; p.t = a.t; p.a_l = a.a_l; p.s = a.s; p.m = a.m; p.l = a.l; p.acc = a.acc; p.out = a.out; p.L = a.L;
     p.H = a.H; p.tag_shift = a.tag_shift; p.slope = a.slope; p.act = a.act;
+    p.ld = a.ldz; p.ldh = a.ldh; p.D = a.D;
     f256::Tabs tabs{};
     for (int q = 0; q < SAR_MAX_BLOCKS; ++q) {
         tabs.Z[q] = zt.p[q];
@@ -800,16 +822,26 @@ template <typename T, bool ALL>
 int launch_fwd(const FwdArgs& a, const PtrTab& zt, const PtrTab& tt, int P, hipStream_t st)
 {
     if (a.n_rows == 0) return SAR_OK;
-#define SAR_FWD_F256(LPH)                                                                  \
-    return a.a_l ? launch_fwd_f256<T, LPH, ALL, true>(a, zt, tt, st)                       \
-                 : launch_fwd_f256<T, LPH, ALL, false>(a, zt, tt, st)
-    switch (fast_lph(a.H, a.D, a.ldz)) {
-        case 4: SAR_FWD_F256(4);
-        case 8: SAR_FWD_F256(8);
-        case 16: SAR_FWD_F256(16);
-        case 32: SAR_FWD_F256(32);
-        case 64: SAR_FWD_F256(64);
-        default: break;
+#define SAR_FWD_F256(LPH, PAD)                                                             \
+    return a.a_l ? launch_fwd_f256<T, LPH, ALL, true, PAD>(a, zt, tt, st)                  \
+                 : launch_fwd_f256<T, LPH, ALL, false, PAD>(a, zt, tt, st)
+    const FastGeo geo = fast_geo(a.H, a.D, a.ldz);
+    if (geo.pad) {
+        switch (geo.lph) {
+            case 16: SAR_FWD_F256(16, true);
+            case 32: SAR_FWD_F256(32, true);
+            case 64: SAR_FWD_F256(64, true);
+            default: break;
+        }
+    } else {
+        switch (geo.lph) {
+            case 4: SAR_FWD_F256(4, false);
+            case 8: SAR_FWD_F256(8, false);
+            case 16: SAR_FWD_F256(16, false);
+            case 32: SAR_FWD_F256(32, false);
+            case 64: SAR_FWD_F256(64, false);
+            default: break;
+        }
     }
 #undef SAR_FWD_F256
     const unsigned grid = persistent_grid(a.n_rows, a.n_long);
@@ -838,11 +870,59 @@ void timing_mark(int which, hipStream_t st)
     if (g_timing.used < g_timing.capacity) (void)hipEventRecord(g_timing.ev[3 * g_timing.used + which], st);
 }
 
+// the padded geometry has no four-sources-per-wavefront kernel: every source takes the wide one
+template <typename T, int LPH, bool ALL>
+int launch_bwd_f256_padded(const BwdArgs& tabs, const BwdScalars& a, unsigned* grid_out, hipStream_t st)
+{
+    constexpr int B = 8;
+    auto wide = f256::k_gat_bwd_f256<T, LPH, B, ALL, true>;
+    static const int resident_wide = resident_workgroups(wide);
+    f256::BwdTabs t{};
+    for (int q = 0; q < SAR_MAX_BLOCKS; ++q) {
+        t.t_indptr[q] = tabs.t_indptr[q]; t.t_indices[q] = tabs.t_indices[q];
+        t.Z[q] = tabs.Z[q]; t.t[q] = tabs.t[q]; t.dZ[q] = tabs.dZ[q]; t.dt[q] = tabs.dt[q];
+    }
+    f256::BwdP p{};
+    p.rows = a.rows; p.n_rows = a.n_rows; p.n_long = a.n_long;
+    p.G = a.G; p.rec = a.rec; p.a_l = a.a_l; p.ds = a.ds; p.partial = a.partial;
+    p.H = a.H; p.tag_shift = a.tag_shift; p.slope = a.slope;
+    p.ld = a.ldz; p.ldh = a.ldh; p.D = a.D;
+    const unsigned g = persistent_grid_for(p.n_rows, p.n_long, resident_wide);
+    timing_mark(0, st);
+    wide<<<g, kGatherThreads, 0, st>>>(t, p);
+    SAR_LAUNCH_CHECK();
+    timing_mark(1, st);
+    timing_mark(2, st);
+    if (g_timing.used < g_timing.capacity) ++g_timing.used;
+    *grid_out = g;
+    return SAR_OK;
+}
+
+// da_l[h*D + 4k + x] += sum_w partial[w][(h*LPH + k)*4 + x]: the padded kernels leave their
+// partial sums in lane order (256 slots per workgroup)
+__global__ __launch_bounds__(256) void k_reduce_partials_padded(const float* __restrict__ partial, int n_part,
+                                                                int lph, int D, float* __restrict__ out)
+{
+    __shared__ float red[256];
+    const int slot = blockIdx.x, lane = slot >> 2, x = slot & 3;
+    const int h = lane / lph, k = lane % lph;
+    if (4 * k >= D) return;
+    float s = 0.f;
+    for (int w = threadIdx.x; w < n_part; w += 256) s += partial[(int64_t)w * 256 + slot];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) out[h * D + 4 * k + x] += red[0];
+}
+
 template <typename T, int LPH, bool ALL>
 int launch_bwd_f256(const BwdArgs& tabs, const BwdScalars& a, unsigned* grid_out, hipStream_t st)
 {
     constexpr int B = LPH >= 8 ? 8 : 4;
-    auto wide = f256::k_gat_bwd_f256<T, LPH, B, ALL>;
+    auto wide = f256::k_gat_bwd_f256<T, LPH, B, ALL, false>;
     auto narrow = f256::k_gat_bwd_narrow<T, LPH / 4, ALL>;
     static const int resident_wide = resident_workgroups(wide);
     static const int resident_narrow = resident_workgroups(narrow);
@@ -882,7 +962,18 @@ int launch_bwd(const BwdArgs& tabs, BwdScalars& a, float* da_l, hipStream_t st)
 {
     if (a.n_rows == 0) return SAR_OK;
     unsigned grid = persistent_grid(a.n_rows, a.n_long);
-    switch (fast_lph(a.H, a.D, a.ldz)) {
+    const FastGeo geo = fast_geo(a.H, a.D, a.ldz);
+    if (geo.pad) {
+        switch (geo.lph) {
+            case 16: SAR_TRY((launch_bwd_f256_padded<T, 16, ALL>(tabs, a, &grid, st))); break;
+            case 32: SAR_TRY((launch_bwd_f256_padded<T, 32, ALL>(tabs, a, &grid, st))); break;
+            default: SAR_TRY((launch_bwd_f256_padded<T, 64, ALL>(tabs, a, &grid, st))); break;
+        }
+        k_reduce_partials_padded<<<256, 256, 0, st>>>(a.partial, (int)grid, geo.lph, a.D, da_l);
+        SAR_LAUNCH_CHECK();
+        return SAR_OK;
+    }
+    switch (geo.lph) {
         case 4: SAR_TRY((launch_bwd_f256<T, 4, ALL>(tabs, a, &grid, st))); break;
         case 8: SAR_TRY((launch_bwd_f256<T, 8, ALL>(tabs, a, &grid, st))); break;
         case 16: SAR_TRY((launch_bwd_f256<T, 16, ALL>(tabs, a, &grid, st))); break;
@@ -898,6 +989,7 @@ int launch_bwd(const BwdArgs& tabs, BwdScalars& a, float* da_l, hipStream_t st)
     return SAR_OK;
 }
 
+// room for one row of 256 partial sums per workgroup of the two backward kernels of a launch
 size_t workspace_bytes(int F) { return (size_t)2 * kMaxPersistentWGs * F * sizeof(float); }
 
 }  // namespace
@@ -1067,7 +1159,7 @@ extern "C" int sar_gat_workspace_bytes(int64_t n_dst, int64_t n_src_max, int H, 
 {
     SAR_CHECK_ARG(bytes != nullptr, "bytes is null");
     SAR_CHECK_ARG(n_dst >= 0 && n_src_max >= 0 && H > 0 && D > 0, "sizes must be non-negative, H and D positive");
-    *bytes = workspace_bytes(std::min(H * D, 256));
+    *bytes = workspace_bytes(256);
     return SAR_OK;
 }
 
@@ -1118,7 +1210,7 @@ int bwd_common_checks(const sar_blocks_t* b, int dtype, int H, int D, const void
     SAR_CHECK_ARG(G && rec && a_l && ds && da_l, "a tensor argument is null");
     SAR_CHECK_ARG(aligned16(G) && aligned16(rec) && aligned16(a_l), "G, rec and a_l must be 16-byte aligned");
     SAR_CHECK_ARG(work != nullptr && aligned16(work), "work is null or not 16-byte aligned");
-    const size_t need = workspace_bytes(std::min(H * D, 256));
+    const size_t need = workspace_bytes(256);
     SAR_CHECK_ARG(work_bytes >= need, "work_bytes=%zu is below the %zu bytes required", work_bytes, need);
     return SAR_OK;
 }
@@ -1234,7 +1326,7 @@ extern "C" int sar_gat_bwd_end(const void* Zdst, const float* ds, const float* a
                   "Zdst, dZadd and dZdst must be 16-byte aligned");
     SAR_CHECK_ARG(work != nullptr && aligned16(work), "work is null or not 16-byte aligned");
     const int F = H * D;
-    const size_t need = workspace_bytes(std::min(F, 256));
+    const size_t need = workspace_bytes(256);
     SAR_CHECK_ARG(work_bytes >= need, "work_bytes=%zu is below the %zu bytes required", work_bytes, need);
     hipStream_t st = sar::as_stream(stream);
     const HeadGroups hg = head_groups(dtype, H, D);

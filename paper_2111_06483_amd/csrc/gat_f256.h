@@ -10,6 +10,14 @@
 // multiply-add with the gathered row.  Row addresses come from scalar
 // registers (V_READLANE of the coalesced index chunk), so the gathers are
 // SGPR-base + lane-offset loads with up to B rows in flight per wavefront.
+//
+// Two lane geometries.  Exact: the row is 256 contiguous values, lane x owns
+// 4x..4x+3.  Padded (template flag PAD): the launch covers 64/LPH heads of any
+// width D <= 4*LPH (D a multiple of 4) inside rows of stride `ld`; head h sits in
+// lanes [h*LPH, (h+1)*LPH), lane k of it owns features h*D + 4k.. while 4k < D
+// and is idle otherwise (it still takes its turn at the per-edge scalars).  That
+// brings head widths such as 100 and rows wider than one wavefront (several
+// launches over groups of heads) onto these kernels.
 #pragma once
 
 #include <type_traits>
@@ -122,6 +130,25 @@ struct Row4<bf16_t> {
     }
 };
 
+// The lane's 4 values of a row (zeros for an idle lane of the padded geometry).
+template <typename T, bool PAD>
+__device__ inline typename Row4<T>::Raw load_lane(const T* row, int foff, bool on)
+{
+    using Raw = typename Row4<T>::Raw;
+    if constexpr (PAD) {
+        Raw r{};
+        if (on) r = *reinterpret_cast<const Raw*>(row + foff);
+        return r;
+    } else {
+        return *reinterpret_cast<const Raw*>(row + foff);
+    }
+}
+template <typename T, bool PAD>
+__device__ inline void store_lane(T* row, int foff, bool on, const float (&v)[4])
+{
+    if (!PAD || on) Row4<T>::store(row + foff, 0, v);
+}
+
 struct Tabs {
     const void* Z[SAR_MAX_BLOCKS];
     const float* t[SAR_MAX_BLOCKS];
@@ -149,6 +176,7 @@ struct FwdP {
     int tag_shift;
     float slope;
     int act;             // SAR_ACT_*: applied to the normalised output rows (ALL only)
+    int ld, ldh, D;      // padded geometry: row stride (values), stride of the per-head arrays, head width
 };
 
 template <int LPH>
@@ -159,10 +187,11 @@ struct FwdState {
 };
 
 // One 64-edge chunk position `mine`(lane) holds; folds edges [0,cnt) of it.
-template <typename T, int LPH, int B, bool ALL, bool FLY>
+template <typename T, int LPH, int B, bool ALL, bool FLY, bool PAD>
 __device__ inline void fwd_chunk(FwdState<LPH>& st, const FwdP& a, const Tabs& tabs, uint32_t mine, int cnt,
-                                 int lane, int h, int k, float s2, const float (&al)[4])
+                                 int foff, bool on, int h, int k, float s2, const float (&al)[4])
 {
+    const int ld = PAD ? a.ld : kF, ldh = PAD ? a.ldh : a.H;
     const uint32_t mask = ALL ? ((1u << a.tag_shift) - 1u) : 0xffffffffu;
     for (int k0 = 0; k0 < cnt; k0 += B) {
         const int nb = min(B, cnt - k0);
@@ -172,7 +201,7 @@ __device__ inline void fwd_chunk(FwdState<LPH>& st, const FwdP& a, const Tabs& t
             const int e = k0 + min((int)decltype(kk)::value, nb - 1);
             const uint32_t id = (uint32_t)__builtin_amdgcn_readlane((int)mine, e);
             const T* zb = static_cast<const T*>(ALL ? tabs.Z[id >> a.tag_shift] : a.Z);
-            raw[decltype(kk)::value] = Row4<T>::load(zb + (int64_t)(id & mask) * kF, lane);
+            raw[decltype(kk)::value] = load_lane<T, PAD>(zb + (int64_t)(id & mask) * ld, foff, on);
         });
         // scores: lane k of every head group takes edge k0+k
         const bool valid = k < nb;
@@ -191,7 +220,7 @@ __device__ inline void fwd_chunk(FwdState<LPH>& st, const FwdP& a, const Tabs& t
         } else {
             const uint32_t my = (uint32_t)__shfl((int)mine, k0 + (valid ? k : 0));
             const float* tb = ALL ? tabs.t[my >> a.tag_shift] : a.t;
-            tv = tb[(int64_t)(my & mask) * a.H + h];
+            tv = tb[(int64_t)(my & mask) * ldh + h];
         }
         const float e2 = valid ? leaky2(fmaf(tv, kLog2e, s2), a.slope) : -INFINITY;
         const float cmax = group_all<LPH, OpMax>(e2);
@@ -215,7 +244,7 @@ __device__ inline void fwd_chunk(FwdState<LPH>& st, const FwdP& a, const Tabs& t
     }
 }
 
-template <typename T, int LPH, int B, bool ALL, bool FLY>
+template <typename T, int LPH, int B, bool ALL, bool FLY, bool PAD>
 __global__ __launch_bounds__(kGatherThreads) void k_gat_fwd_f256(FwdP a, Tabs tabs)
 {
     static_assert(B <= LPH, "a sub-batch must fit a head group");
@@ -223,9 +252,14 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_fwd_f256(FwdP a, Tabs ta
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int h = lane / LPH, k = lane % LPH;
+    const int ld = PAD ? a.ld : kF, ldh = PAD ? a.ldh : a.H;
+    const int foff = PAD ? h * a.D + 4 * k : lane * 4;
+    const bool on = PAD ? 4 * k < a.D : true;
     T* outp = static_cast<T*>(a.out);
     float al[4] = {0.f, 0.f, 0.f, 0.f};
-    if constexpr (FLY) load_f32<4>(a.a_l + lane * 4, al);
+    if constexpr (FLY) {
+        if (on) load_f32<4>(a.a_l + foff, al);
+    }
 
     auto init = [&](FwdState<LPH>& st, int i, bool carry) {
         st.m2 = -INFINITY;
@@ -234,9 +268,9 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_fwd_f256(FwdP a, Tabs ta
         for (int x = 0; x < 4; ++x) st.acc[x] = 0.f;
         if constexpr (!ALL) {
             if (carry) {   // state carried from the blocks already aggregated
-                st.m2 = a.m[(int64_t)i * a.H + h] * kLog2e;
-                st.l = (k == 0) ? a.l[(int64_t)i * a.H + h] : 0.f;
-                load_f32<4>(a.acc + (int64_t)i * kF + lane * 4, st.acc);
+                st.m2 = a.m[(int64_t)i * ldh + h] * kLog2e;
+                st.l = (k == 0) ? a.l[(int64_t)i * ldh + h] : 0.f;
+                if (on) load_f32<4>(a.acc + (int64_t)i * ld + foff, st.acc);
             }
         }
     };
@@ -250,23 +284,23 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_fwd_f256(FwdP a, Tabs ta
                 v[x] = st.acc[x] * inv;
                 if (a.act == SAR_ACT_RELU) v[x] = fmaxf(v[x], 0.f);
             }
-            Row4<T>::store(outp + (int64_t)i * kF, lane, v);
-            if (k == 0) a.L[(int64_t)i * a.H + h] = l > 0.f ? (st.m2 + fast_log2(l)) * kLn2 : -INFINITY;
+            store_lane<T, PAD>(outp + (int64_t)i * ld, foff, on, v);
+            if (k == 0) a.L[(int64_t)i * ldh + h] = l > 0.f ? (st.m2 + fast_log2(l)) * kLn2 : -INFINITY;
         } else {
-            store_f32<4>(a.acc + (int64_t)i * kF + lane * 4, st.acc);
+            if (on) store_f32<4>(a.acc + (int64_t)i * ld + foff, st.acc);
             if (k == 0) {
-                a.m[(int64_t)i * a.H + h] = st.m2 * kLn2;
-                a.l[(int64_t)i * a.H + h] = l;
+                a.m[(int64_t)i * ldh + h] = st.m2 * kLn2;
+                a.l[(int64_t)i * ldh + h] = l;
             }
         }
     };
     auto edges = [&](FwdState<LPH>& st, int i, int chunk0, int stride) {
-        const float s2 = a.s[(int64_t)i * a.H + h] * kLog2e;
+        const float s2 = a.s[(int64_t)i * ldh + h] * kLog2e;
         const int beg = a.indptr[i], end = a.indptr[i + 1];
         for (int cb = beg + chunk0 * kWave; cb < end; cb += stride * kWave) {
             const int cnt = min(kWave, end - cb);
             const uint32_t mine = (lane < cnt) ? a.indices[cb + lane] : 0u;
-            fwd_chunk<T, LPH, B, ALL, FLY>(st, a, tabs, mine, cnt, lane, h, k, s2, al);
+            fwd_chunk<T, LPH, B, ALL, FLY, PAD>(st, a, tabs, mine, cnt, foff, on, h, k, s2, al);
         }
     };
 
@@ -332,6 +366,7 @@ struct BwdP {
     int H;
     int tag_shift;
     float slope;
+    int ld, ldh, D;      // padded geometry, as in FwdP
 };
 
 struct BwdAcc4 {
@@ -339,10 +374,11 @@ struct BwdAcc4 {
     float dt;      // this lane's share of sum_i du
 };
 
-template <typename T, int LPH, int B>
-__device__ inline void bwd_chunk(BwdAcc4& ac, const BwdP& a, int mine, int cnt, int lane, int h, int k,
+template <typename T, int LPH, int B, bool PAD>
+__device__ inline void bwd_chunk(BwdAcc4& ac, const BwdP& a, int mine, int cnt, int foff, bool on, int h, int k,
                                  const float (&zj)[4], float t2)
 {
+    const int ld = PAD ? a.ld : kF, ldh = PAD ? a.ldh : a.H;
     const T* Gp = static_cast<const T*>(a.G);
     for (int k0 = 0; k0 < cnt; k0 += B) {
         const int nb = min(B, cnt - k0);
@@ -350,11 +386,11 @@ __device__ inline void bwd_chunk(BwdAcc4& ac, const BwdP& a, int mine, int cnt, 
         static_for<B>([&](auto kk) {
             const int e = k0 + min((int)decltype(kk)::value, nb - 1);
             const int i = __builtin_amdgcn_readlane(mine, e);
-            raw[decltype(kk)::value] = Row4<T>::load(Gp + (int64_t)i * kF, lane);
+            raw[decltype(kk)::value] = load_lane<T, PAD>(Gp + (int64_t)i * ld, foff, on);
         });
         const bool valid = k < nb;
         const int my_i = __shfl(mine, k0 + (valid ? k : 0));
-        const float4 rec = a.rec[(int64_t)my_i * a.H + h];
+        const float4 rec = a.rec[(int64_t)my_i * ldh + h];
         // c_k = <G_i, z_j> per head, reduced over the head's lanes; lane k keeps edge k's value
         float c_mine = 0.f;
         static_for<B>([&](auto kk) {
@@ -371,7 +407,7 @@ __device__ inline void bwd_chunk(BwdAcc4& ac, const BwdP& a, int mine, int cnt, 
         const float de = alpha * (c_mine - rec.z);
         const float du = u2 > 0.f ? de : a.slope * de;
         ac.dt += du;
-        if (valid) unsafeAtomicAdd(a.ds + (int64_t)my_i * a.H + h, du);
+        if (valid) unsafeAtomicAdd(a.ds + (int64_t)my_i * ldh + h, du);
         static_for<B>([&](auto kk) {
             const float ak = group_bcast<LPH, decltype(kk)::value>(alpha);
             float g[4];
@@ -382,7 +418,7 @@ __device__ inline void bwd_chunk(BwdAcc4& ac, const BwdP& a, int mine, int cnt, 
     }
 }
 
-template <typename T, int LPH, int B, bool ALL>
+template <typename T, int LPH, int B, bool ALL, bool PAD>
 __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_f256(BwdTabs tabs, BwdP a)
 {
     static_assert(B <= LPH, "a sub-batch must fit a head group");
@@ -390,18 +426,21 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_f256(BwdTabs tabs, B
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int h = lane / LPH, k = lane % LPH;
+    const int ld = PAD ? a.ld : kF, ldh = PAD ? a.ldh : a.H;
+    const int foff = PAD ? h * a.D + 4 * k : lane * 4;
+    const bool on = PAD ? 4 * k < a.D : true;
     const uint32_t mask = ALL ? ((1u << a.tag_shift) - 1u) : 0xffffffffu;
 
-    float al[4], dal[4];
-    load_f32<4>(a.a_l + lane * 4, al);
+    float al[4] = {0.f, 0.f, 0.f, 0.f}, dal[4];
+    if (on) load_f32<4>(a.a_l + foff, al);
 #pragma unroll
     for (int x = 0; x < 4; ++x) dal[x] = 0.f;
 
     auto edges = [&](BwdAcc4& ac, int q, int j, int chunk0, int stride, float (&zj)[4]) {
-        Row4<T>::unpack(Row4<T>::load(static_cast<const T*>(tabs.Z[q]) + (int64_t)j * kF, lane), zj);
+        Row4<T>::unpack(load_lane<T, PAD>(static_cast<const T*>(tabs.Z[q]) + (int64_t)j * ld, foff, on), zj);
         float t2;
         if (tabs.t[q]) {
-            t2 = tabs.t[q][(int64_t)j * a.H + h] * kLog2e;
+            t2 = tabs.t[q][(int64_t)j * ldh + h] * kLog2e;
         } else {   // t_j = <a_l, z_j> from the row this wavefront owns
             float c = al[0] * zj[0];
 #pragma unroll
@@ -417,7 +456,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_f256(BwdTabs tabs, B
         for (int cb = beg + chunk0 * kWave; cb < end; cb += stride * kWave) {
             const int cnt = min(kWave, end - cb);
             const int mine = (lane < cnt) ? idx[cb + lane] : 0;
-            bwd_chunk<T, LPH, B>(ac, a, mine, cnt, lane, h, k, zj, t2);
+            bwd_chunk<T, LPH, B, PAD>(ac, a, mine, cnt, foff, on, h, k, zj, t2);
         }
     };
     // dZ_q[j] = sum alpha G + dt a_l ; dt_q[j] = dt ; da_l += dt z_j
@@ -428,8 +467,8 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_f256(BwdTabs tabs, B
             v[x] = fmaf(dt, al[x], ac.dz[x]);
             dal[x] = fmaf(dt, zj[x], dal[x]);
         }
-        Row4<T>::store(static_cast<T*>(tabs.dZ[q]) + (int64_t)j * kF, lane, v);
-        if (k == 0) tabs.dt[q][(int64_t)j * a.H + h] = dt;
+        store_lane<T, PAD>(static_cast<T*>(tabs.dZ[q]) + (int64_t)j * ld, foff, on, v);
+        if (k == 0) tabs.dt[q][(int64_t)j * ldh + h] = dt;
     };
 
     for (int64_t r = blockIdx.x; r < a.n_long; r += gridDim.x) {
