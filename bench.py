@@ -46,6 +46,9 @@ def parse():
     ap.add_argument("--dst-frac", type=float, default=1.0,
                     help="aggregate only into this fraction of the worker's destinations (a seeded random "
                          "subset, as a message flow graph restricts a layer, App. B); sources stay complete")
+    ap.add_argument("--skip-untouched", action="store_true",
+                    help="backward passes do not write the rows of sources without an edge in a block "
+                         "(only the rows V_{p,q} are exchanged, Sec. 3.2); the buffers are zeroed once")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this size (to scale rocprofv3's FETCH_SIZE/WRITE_SIZE)")
@@ -56,14 +59,15 @@ def parse():
 class Layer:
     """Device state of one worker's GAT layer; methods only call the C ABI."""
 
-    def __init__(self, w, torch, sar, synth, act=0, dst_frac=1.0):
+    def __init__(self, w, torch, sar, synth, act=0, dst_frac=1.0, skip_untouched=False):
         self.torch, self.sar, self.w, self.act = torch, sar, w, act
         self.subset = dst_frac < 1.0
         dev = "cuda"
         H, D, P, p = w.H, w.D, w.P, w.p
         self.H, self.D, self.F, self.P, self.p = H, D, H * D, P, p
         t0 = time.perf_counter()
-        self.blocks = sar.sar_blocks_build(w.src, w.dst, w.part, P, p)
+        flags = sar.SAR_BUILD_TRANSPOSE | sar.SAR_BUILD_FUSED | (sar.SAR_BUILD_SKIP_UNTOUCHED if skip_untouched else 0)
+        self.blocks = sar.sar_blocks_build(w.src, w.dst, w.part, P, p, flags)
         torch.cuda.synchronize()
         self.builder_s = time.perf_counter() - t0
         members = [w.members(q) for q in range(P)]
@@ -74,7 +78,7 @@ class Layer:
             ids = torch.nonzero(u < dst_frac).flatten().to(torch.int32)
             t0 = time.perf_counter()
             self.blocks_full = self.blocks
-            self.blocks = sar.sar_blocks_subset(self.blocks_full, ids)
+            self.blocks = sar.sar_blocks_subset(self.blocks_full, ids, flags)
             torch.cuda.synchronize()
             self.subset_s = time.perf_counter() - t0
             dst_members = members[p][ids.long()]
@@ -110,8 +114,8 @@ class Layer:
         self.rec = torch.empty((n, H, 4), **f32)
         self.Gact = torch.empty_like(self.G) if act else None
         self.ds = torch.empty((n, H), **f32)
-        self.dZs = [torch.empty_like(z) for z in self.Zs]
-        self.dts = [torch.empty((z.shape[0], H), **f32) for z in self.Zs]
+        self.dZs = [torch.zeros_like(z) for z in self.Zs]     # zeroed once: skipped rows stay zero
+        self.dts = [torch.zeros((z.shape[0], H), **f32) for z in self.Zs]
         self.dZdst = torch.empty((n, H, D), dtype=w.dtype, device=dev)
         self.da_l = torch.zeros((H, D), **f32)
         self.da_r = torch.zeros((H, D), **f32)
@@ -426,7 +430,7 @@ def main():
         sage_bench(args, w, torch, sar, synth)
         return
     layer = Layer(w, torch, sar, synth, act=sar.SAR_ACT_RELU if args.act == "relu" else sar.SAR_ACT_NONE,
-                  dst_frac=args.dst_frac)
+                  dst_frac=args.dst_frac, skip_untouched=args.skip_untouched)
 
     if args.calib_copy_mib:
         a = torch.ones(args.calib_copy_mib << 18, dtype=torch.float32, device="cuda")
@@ -494,7 +498,8 @@ def main():
         "config": {"workload": "%s: one worker's share of a %d-node graph, %d-way split, %d destinations, "
                                "%d in-edges over %d resident source blocks, GAT %d heads x %d, in_dim %d"
                                % (args.workload, w.N, w.P, layer.n, layer.E, w.P, w.H, w.D, w.f_in),
-                   "mode": args.mode, "scale": args.scale, "act": args.act, "dst_frac": args.dst_frac},
+                   "mode": args.mode, "scale": args.scale, "act": args.act, "dst_frac": args.dst_frac,
+                   "skip_untouched": args.skip_untouched},
         "phases_ms": {"step_events": all_ms, "gat_fwd": fwd_ms, "gat_bwd": bwd_ms,
                       "gat_bwd_kernel_rows_ge8": wide_ms, "gat_bwd_kernel_rows_lt8": narrow_ms,
                       "other (XW fwd+bwd, scores, begin/end)": all_ms - fwd_ms - bwd_ms},

@@ -71,6 +71,12 @@ typedef enum { SAR_ACT_NONE = 0, SAR_ACT_RELU = 1 } sar_act;
 /* flags of sar_blocks_build / sar_blocks_wrap */
 #define SAR_BUILD_TRANSPOSE 1 /* also build the source-major index (needed by every *_bwd_*) */
 #define SAR_BUILD_FUSED 2     /* also build the all-blocks row index (needed by every *_all) */
+/* Backward passes skip the sources that have no edge in a block: their rows of dZ_q (and dt_q)
+ * are NOT written.  A worker exchanges only the rows V_{p,q} of a partition that its
+ * destinations read (Sec. 3.2), so the error E_{p->q} has no other rows; with full-height
+ * buffers zero them once, the skipped rows never change (the handle's `touched` lists name
+ * the others).  Without this flag every row of dZ_q, dt_q is written (zeros where no edge). */
+#define SAR_BUILD_SKIP_UNTOUCHED 4
 
 typedef struct sar_blocks sar_blocks_t; /* opaque, library-owned */
 

@@ -917,7 +917,7 @@ extern "C" int sar_blocks_build(const void* src, const void* dst, int idx_bytes,
     SAR_CHECK_ARG(E == 0 || (src && dst), "src/dst is null");
     SAR_CHECK_ARG(part != nullptr, "part is null");
     SAR_CHECK_ARG(P >= 1 && p >= 0 && p < P, "need 0 <= p < P, got p=%d P=%d", p, P);
-    SAR_CHECK_ARG((flags & ~(SAR_BUILD_TRANSPOSE | SAR_BUILD_FUSED)) == 0, "unknown flags 0x%x", flags);
+    SAR_CHECK_ARG((flags & ~(SAR_BUILD_TRANSPOSE | SAR_BUILD_FUSED | SAR_BUILD_SKIP_UNTOUCHED)) == 0, "unknown flags 0x%x", flags);
     if (P > SAR_MAX_BLOCKS)
         return sar::fail(SAR_ERR_UNSUPPORTED, "P=%d exceeds SAR_MAX_BLOCKS=%d", P, SAR_MAX_BLOCKS);
     if (E >= ((int64_t)1 << 31) || N >= ((int64_t)1 << 31))
@@ -944,7 +944,7 @@ extern "C" int sar_blocks_wrap(int P, int64_t n_dst, const int64_t* n_src, const
     *out = nullptr;
     SAR_CHECK_ARG(P >= 1 && n_dst >= 0, "need P >= 1 and n_dst >= 0");
     SAR_CHECK_ARG(n_src && indptr && indices, "n_src/indptr/indices is null");
-    SAR_CHECK_ARG((flags & ~(SAR_BUILD_TRANSPOSE | SAR_BUILD_FUSED)) == 0, "unknown flags 0x%x", flags);
+    SAR_CHECK_ARG((flags & ~(SAR_BUILD_TRANSPOSE | SAR_BUILD_FUSED | SAR_BUILD_SKIP_UNTOUCHED)) == 0, "unknown flags 0x%x", flags);
     if (P > SAR_MAX_BLOCKS)
         return sar::fail(SAR_ERR_UNSUPPORTED, "P=%d exceeds SAR_MAX_BLOCKS=%d", P, SAR_MAX_BLOCKS);
     for (int q = 0; q < P; ++q) {
@@ -1044,7 +1044,7 @@ extern "C" int sar_blocks_subset(const sar_blocks_t* b, const int32_t* dst_ids, 
     SAR_CHECK_ARG(b != nullptr, "handle is null");
     SAR_CHECK_ARG(n_sub >= 0 && n_sub < ((int64_t)1 << 31), "n_sub must be in [0, 2^31)");
     SAR_CHECK_ARG(n_sub == 0 || dst_ids != nullptr, "dst_ids is null");
-    SAR_CHECK_ARG((flags & ~(SAR_BUILD_TRANSPOSE | SAR_BUILD_FUSED)) == 0, "unknown flags 0x%x", flags);
+    SAR_CHECK_ARG((flags & ~(SAR_BUILD_TRANSPOSE | SAR_BUILD_FUSED | SAR_BUILD_SKIP_UNTOUCHED)) == 0, "unknown flags 0x%x", flags);
     hipStream_t st = sar::as_stream(stream);
     sar_blocks* h = new (std::nothrow) sar_blocks();
     if (!h) return sar::fail(SAR_ERR_HIP, "out of host memory");

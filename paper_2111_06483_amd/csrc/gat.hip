@@ -1259,7 +1259,8 @@ extern "C" int sar_gat_bwd_block(const sar_blocks_t* b, int q, const void* Zq, c
         tabs.dt[0] = dtq + h0;
         BwdScalars a{};
         a.rows = reinterpret_cast<const uint32_t*>(k.t_rows);
-        a.n_rows = k.n_src;    // sources without edges come last and get dZ = 0, dt = 0
+        // sources without edges come last and get dZ = 0, dt = 0, unless the handle skips them
+        a.n_rows = (b->flags & SAR_BUILD_SKIP_UNTOUCHED) ? k.n_t_rows : k.n_src;
         a.n_long = k.n_t_long;
         a.n_wide = k.n_t_wide;
         fill_bwd_group(a, hg, g, H, D, G, rec, a_l, ds, work, slope);
@@ -1302,6 +1303,7 @@ extern "C" int sar_gat_bwd_all(const sar_blocks_t* b, const void* const* Zq, con
         a.rows = b->ft_rows;
         a.n_rows = 0;
         for (int q = 0; q < b->P; ++q) a.n_rows += b->blk[q].n_src;
+        if (b->flags & SAR_BUILD_SKIP_UNTOUCHED) a.n_rows = b->n_ft_rows;
         a.n_wide = b->n_ft_wide;
         a.n_long = b->n_ft_long;
         a.tag_shift = b->tag_shift;

@@ -519,7 +519,8 @@ extern "C" int sar_spmm_bwd_block(const sar_blocks_t* b, int q, const void* G, i
     a.indptr = k.t_indptr;
     a.indices = reinterpret_cast<const uint32_t*>(k.t_indices);
     a.rows = reinterpret_cast<const uint32_t*>(k.t_rows);
-    a.n_rows = k.n_src;    // sources without edges come last in the list and get 0
+    // sources without edges come last in the list and get 0, unless the handle skips them
+    a.n_rows = (b->flags & SAR_BUILD_SKIP_UNTOUCHED) ? k.n_t_rows : k.n_src;
     a.n_long = k.n_t_long;
     a.deg = b->deg;
     a.ld = F;
@@ -557,7 +558,7 @@ extern "C" int sar_spmm_bwd_all(const sar_blocks_t* b, const void* G, int mean, 
     hipStream_t st = sar::as_stream(stream);
     SpmmArgs a{};
     a.rows = b->ft_rows;
-    a.n_rows = n_src_total;
+    a.n_rows = (b->flags & SAR_BUILD_SKIP_UNTOUCHED) ? b->n_ft_rows : n_src_total;
     a.n_long = b->n_ft_long;
     a.deg = b->deg;
     a.ld = F;

@@ -28,6 +28,7 @@ SAR_ACT_RELU = 1
 SAR_MAX_BLOCKS = 64
 SAR_BUILD_TRANSPOSE = 1
 SAR_BUILD_FUSED = 2
+SAR_BUILD_SKIP_UNTOUCHED = 4
 
 _c_i64 = ctypes.c_int64
 _c_int = ctypes.c_int

@@ -248,3 +248,62 @@ def test_subset_edge_cases_and_errors():
     with pytest.raises(sar.SarError):
         sar.sar_blocks_subset(b, torch.zeros(3, dtype=torch.int64, device="cuda"))
     b.close()
+
+
+def test_skip_untouched_sources_leaves_their_rows_alone():
+    """SAR_BUILD_SKIP_UNTOUCHED: the backward passes write exactly the rows of the touched sources
+    (the rows V_{p,q} a worker exchanges); all others keep what the buffer held."""
+    P, p, H, D = 3, 0, 4, 64
+    F = H * D
+    src, dst, part, rng = make_graph(43, 6000, 9000, P, hubs=False)      # sparse: many sources without an edge
+    want_b, deg = orc.build_blocks(src, dst, part, P, p)
+    flags = sar.SAR_BUILD_TRANSPOSE | sar.SAR_BUILD_FUSED | sar.SAR_BUILD_SKIP_UNTOUCHED
+    b = gu.build_blocks(src, dst, part, P, p, flags=flags)
+    untouched = [np.diff(w.t_indptr) == 0 for w in want_b]
+    assert all(u.mean() > 0.2 for u in untouched)
+    Zs = [feats(rng, w.n_src, F, torch.float32).cuda().reshape(-1, H, D) for w in want_b]
+    Zdst = Zs[p]
+    bound = np.sqrt(6.0 / (D + 1))
+    a_l = torch.from_numpy(rng.uniform(-bound, bound, (H, D)).astype(np.float32)).cuda()
+    a_r = torch.from_numpy(rng.uniform(-bound, bound, (H, D)).astype(np.float32)).cuda()
+    G = feats(rng, b.n_dst, F, torch.float32).cuda().reshape(-1, H, D)
+    wf = orc.gat_fwd(want_b, f64(Zdst), [f64(z) for z in Zs], f64(a_l), f64(a_r), SLOPE)
+    wb = orc.gat_bwd(want_b, f64(Zdst), [f64(z) for z in Zs], f64(G), f64(a_l), f64(a_r), SLOPE, wf)
+    fw = gu.gat_fwd_all(b, Zdst, Zs, a_l, a_r, SLOPE, fly=True)
+    n = b.n_dst
+    SENT = 7.0
+    for batched in (False, True):
+        rec = torch.empty((n, H, 4), dtype=torch.float32, device="cuda")
+        ds = torch.empty((n, H), dtype=torch.float32, device="cuda")
+        sar.sar_gat_bwd_begin(G, fw.out, fw.s, fw.L, rec, ds)
+        work = torch.empty(sar.sar_gat_workspace_bytes(n, max(z.shape[0] for z in Zs), H, D) // 4, device="cuda")
+        da_l = torch.zeros((H, D), device="cuda")
+        dZs = [torch.full(z.shape, SENT, device="cuda") for z in Zs]
+        dts = [torch.full((z.shape[0], H), SENT, device="cuda") for z in Zs]
+        if batched:
+            sar.sar_gat_bwd_all(b, Zs, G, None, rec, a_l, SLOPE, dZs, dts, ds, da_l, work)
+        else:
+            for q in range(P):
+                sar.sar_gat_bwd_block(b, q, Zs[q], G, None, rec, a_l, SLOPE, dZs[q], dts[q], ds, da_l, work)
+        for q in range(P):
+            got, u = f64(dZs[q]), untouched[q]
+            assert (got[u] == SENT).all() and (f64(dts[q])[u] == SENT).all()
+            assert rel_err(got[~u], wb.dZs[q].reshape(got.shape)[~u]) < 1e-4
+            assert rel_err(f64(dts[q])[~u], wb.dt[q][~u]) < 1e-4
+        assert rel_err(f64(ds), wb.ds) < 1e-4
+        assert rel_err(f64(da_l), wb.da_l) < 1e-4
+    # case-1 backward of the mean aggregation
+    G2 = G.reshape(n, F)
+    want_d = orc.spmm_bwd(want_b, f64(G2), True)
+    for batched in (False, True):
+        dZs = [torch.full((z.shape[0], F), SENT, device="cuda") for z in Zs]
+        if batched:
+            sar.sar_spmm_bwd_all(b, G2, True, dZs)
+        else:
+            for q in range(P):
+                sar.sar_spmm_bwd_block(b, q, G2, True, dZs[q])
+        for q in range(P):
+            got, u = f64(dZs[q]), untouched[q]
+            assert (got[u] == SENT).all()
+            assert rel_err(got[~u], want_d[q][~u]) < 1e-4
+    b.close()
