@@ -347,7 +347,7 @@ __global__ __launch_bounds__(kGemmThreads) void k_gemm_bf16(GemmArgs g)
 constexpr int kSkinnyWaves = 8;
 constexpr int kSkinnyThreads = 64 * kSkinnyWaves;
 constexpr int kPrefetch = 4;
-constexpr size_t kSkinnyMaxLds = 150 * 1024;
+constexpr size_t kSkinnyMaxLds = 160 * 1024;   // all of a CU's LDS: one workgroup per CU then
 
 struct SkinnyArgs {
     const void* A;     // [M, K], row stride lda, contraction index contiguous
@@ -365,7 +365,12 @@ struct SkinnyArgs {
     float* s1;         // [M, H] or null
     float* s2;
     int H, D;
+    // 2-byte outputs: byte offset in LDS of the per-wavefront 32 x 32 staging tiles through
+    // which they are stored as whole 64-byte row segments, or 0 to store element-wise
+    int stage_off;
 };
+
+constexpr int kStageBytes = 32 * 32 * 2;   // per wavefront
 
 template <typename TA, typename TC, int NT, bool SC>
 __global__ __launch_bounds__(kSkinnyThreads) void k_gemm_skinny(SkinnyArgs g)
@@ -521,14 +526,44 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_gemm_skinny(SkinnyArgs g)
         }
         // lane holds column c; register r holds row 8*(r/4) + 4*(lane/32) + r%4
         TC* C = static_cast<TC*>(g.C);
+        if (sizeof(TC) == 2 && g.stage_off) {
+            // A lane's 16 values of a tile are 16 different rows: stored directly they are 2-byte
+            // scattered writes.  The tile is turned through the wavefront's own 2 KB of LDS
+            // instead and leaves as 16-byte pieces, 64 contiguous bytes per row.
+            uint16_t* stg = reinterpret_cast<uint16_t*>(skinny_lds + g.stage_off + wave * kStageBytes);
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            const int64_t n = n0 + nt * 32 + c;
-            if (n >= g.N) continue;
+            for (int nt = 0; nt < NT; ++nt) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int64_t i = row0 + 8 * (r / 4) + 4 * gq + (r % 4);
-                if (i < g.M) C[i * g.ldc + n] = from_f32<TC>(acc[nt][r]);
+                for (int r = 0; r < 16; ++r)
+                    stg[(8 * (r / 4) + 4 * gq + (r % 4)) * 32 + c] = (uint16_t)f32_to_bf16_rne(acc[nt][r]);
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    const int row = half * 16 + (lane >> 2), piece = lane & 3;
+                    const uint4 v = *reinterpret_cast<const uint4*>(stg + row * 32 + piece * 8);
+                    const int64_t i = row0 + row, n = n0 + nt * 32 + piece * 8;
+                    if (i < g.M) {
+                        if (n + 8 <= g.N) {
+                            *reinterpret_cast<uint4*>(C + i * g.ldc + n) = v;
+                        } else {
+                            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+                            for (int e = 0; e < 8 && n + e < g.N; ++e)
+                                reinterpret_cast<uint16_t*>(C)[i * g.ldc + n + e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+                        }
+                    }
+                }
+                __builtin_amdgcn_wave_barrier();
+            }
+        } else {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                const int64_t n = n0 + nt * 32 + c;
+                if (n >= g.N) continue;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int64_t i = row0 + 8 * (r / 4) + 4 * gq + (r % 4);
+                    if (i < g.M) C[i * g.ldc + n] = from_f32<TC>(acc[nt][r]);
+                }
             }
         }
         if (SC && blockIdx.y == 0 && c < 2 * g.H) {
@@ -550,11 +585,13 @@ struct SkinnyPlan {
     unsigned slabs = 0;  // column slabs of nt*32
     size_t lds = 0;
     int chunks = 0;
+    int stage_off = 0;   // see SkinnyArgs
 };
 
 // Whether the skinny kernel applies: 16-byte pieces of A rows must be aligned
 // and whole, and the small operand must fit in LDS in at most four column slabs.
-bool plan_skinny(const void* A, int64_t lda, int K, int N, int dtype, int extra_tiles, SkinnyPlan* p)
+bool plan_skinny(const void* A, int64_t lda, const void* C, int64_t ldc, int K, int N, int dtype, int extra_tiles,
+                 SkinnyPlan* p)
 {
     const int elem = dtype == SAR_F32 ? 4 : 2, piece = 16 / elem;
     if (reinterpret_cast<uintptr_t>(A) % 16 != 0 || (lda * elem) % 16 != 0 || K % piece != 0) return false;
@@ -564,11 +601,16 @@ bool plan_skinny(const void* A, int64_t lda, int K, int N, int dtype, int extra_
     const int need = (N + 31) / 32;
     int nt = 1;
     while (nt < need && nt < 8) nt *= 2;
-    while (nt >= 1 && (size_t)p->chunks * (nt + extra_tiles) * unit > kSkinnyMaxLds) nt /= 2;
+    // 2-byte outputs go through staging tiles when their 16-byte pieces are aligned
+    const bool stage = dtype != SAR_F32 && reinterpret_cast<uintptr_t>(C) % 16 == 0 && (ldc * elem) % 16 == 0;
+    const size_t stage_bytes = stage ? (size_t)kSkinnyWaves * kStageBytes : 0;
+    while (nt >= 1 && (size_t)p->chunks * (nt + extra_tiles) * unit + stage_bytes > kSkinnyMaxLds) nt /= 2;
     if (nt < 1) return false;
     p->nt = nt;
     p->slabs = (unsigned)((need + nt - 1) / nt);
     p->lds = (size_t)p->chunks * (nt + extra_tiles) * unit;
+    p->stage_off = stage ? (int)p->lds : 0;
+    p->lds += stage_bytes;
     return p->slabs <= 4;
 }
 
@@ -584,7 +626,7 @@ int launch_skinny_nt(const SkinnyArgs& g, const SkinnyPlan& p, hipStream_t st)
     const int64_t tiles = (g.M + 31) / 32;
     const int64_t want = (tiles + kSkinnyWaves - 1) / kSkinnyWaves;
     // one workgroup per CU; two where registers (NT <= 4) and LDS leave room
-    const int per_cu = (NT <= 4 && 2 * p.lds <= kSkinnyMaxLds) ? 2 : 1;
+    const int per_cu = (NT <= 4 && 2 * p.lds <= 150 * 1024) ? 2 : 1;
     const int64_t resident = std::max<int64_t>(1, (int64_t)n_cu * per_cu / p.slabs);
     dim3 grid((unsigned)std::max<int64_t>(1, std::min(want, resident)), p.slabs, 1);
     k_gemm_skinny<TA, TC, NT, SC><<<grid, kSkinnyThreads, p.lds, st>>>(g);
@@ -846,16 +888,18 @@ extern "C" int sar_linear_fwd(const void* X, const float* W, void* Z, int dtype,
     g.vec_b = vec_ok(W, F, 4);
     SkinnyPlan plan;
     const bool want_scores = a_score || a_score2;
-    if (want_scores && 2 * H <= 32 && plan_skinny(X, K, K, F, dtype, 1, &plan)) {
-        SkinnyArgs sk{X, K, n, W, F, 1, Z, F, K, F, plan.chunks, a_score, a_score2, score, score2, H, D};
+    if (want_scores && 2 * H <= 32 && plan_skinny(X, K, Z, F, K, F, dtype, 1, &plan)) {
+        SkinnyArgs sk{X, K, n, W, F, 1, Z, F, K, F, plan.chunks, a_score, a_score2, score, score2, H, D,
+                      plan.stage_off};
         if (dtype == SAR_F32)
             SAR_TRY((launch_skinny<float, float, true>(sk, plan, st)));
         else
             SAR_TRY((launch_skinny<bf16_t, bf16_t, true>(sk, plan, st)));
         return SAR_OK;
     }
-    if (plan_skinny(X, K, K, F, dtype, 0, &plan)) {
-        SkinnyArgs sk{X, K, n, W, F, 1, Z, F, K, F, plan.chunks, nullptr, nullptr, nullptr, nullptr, 0, 0};
+    if (plan_skinny(X, K, Z, F, K, F, dtype, 0, &plan)) {
+        SkinnyArgs sk{X, K, n, W, F, 1, Z, F, K, F, plan.chunks, nullptr, nullptr, nullptr, nullptr, 0, 0,
+                      plan.stage_off};
         if (dtype == SAR_F32)
             SAR_TRY((launch_skinny<float, float, false>(sk, plan, st)));
         else
@@ -947,9 +991,10 @@ extern "C" int sar_linear_bwd(const void* X, const void* dZ, const float* W, flo
         g.vec_a = vec_ok(dZ, F, dtype == SAR_F32 ? 4 : 2);
         g.vec_b = vec_ok(W, F, 4);
         SkinnyPlan plan;
-        if (plan_skinny(dZ, F, F, K, dtype, 0, &plan)) {
+        if (plan_skinny(dZ, F, dX, K, F, K, dtype, 0, &plan)) {
             // B(k = f, n = kcol) = W[kcol * F + f]
-            SkinnyArgs sk{dZ, F, n, W, 1, F, dX, K, F, K, plan.chunks, nullptr, nullptr, nullptr, nullptr, 0, 0};
+            SkinnyArgs sk{dZ, F, n, W, 1, F, dX, K, F, K, plan.chunks, nullptr, nullptr, nullptr, nullptr, 0, 0,
+                          plan.stage_off};
             if (dtype == SAR_F32)
                 SAR_TRY((launch_skinny<float, float, false>(sk, plan, st)));
             else
