@@ -52,7 +52,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this size (to scale rocprofv3's FETCH_SIZE/WRITE_SIZE)")
-    ap.add_argument("--cpu-blocks", type=int, default=5, help="blocks in the oracle's timed sample")
+    ap.add_argument("--cpu-blocks", type=int, default=8,
+                    help="source blocks in the oracle's timed sample (capped at P; 8 = all of config 3, about 15 s)")
     return ap.parse_args()
 
 
@@ -251,6 +252,7 @@ def measure_ceilings(torch, sar, row_bytes):
 
 def cpu_baseline(layer, n_blocks):
     """The oracle, as it stands, on the first n_blocks blocks of the same workload."""
+    n_blocks = max(1, min(n_blocks, layer.P))
     import numpy as np
     from oracle import sar_oracle as orc
     torch, w = layer.torch, layer.w

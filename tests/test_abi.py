@@ -66,3 +66,13 @@ def test_validation_errors_need_no_gpu(lib):
     assert lib.sar_gat_workspace_bytes(i64(10), i64(10), 4, 64, ctypes.byref(n)) == 0 and n.value > 0
     assert lib.sar_linear_workspace_bytes(i64(100000), 100, 256, ctypes.byref(n)) == 0 and n.value > 0
     assert lib.sar_linear_fwd(None, None, None, 0, i64(0), 4, 4, 0, 0, None, None, None, None, None) == 0
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build is single-GPU: bench.py says so and exits before touching any device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
