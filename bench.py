@@ -243,9 +243,13 @@ def measure_ceilings(torch, sar, row_bytes):
     t_read = timed(lambda: sar.sar_probe_stream_read(table, 2, sink))
     t_gather = timed(lambda: sar.sar_probe_row_gather(table, idx, sink))
     t_copy = timed(lambda: sar.sar_probe_copy(table[: dst.numel() // table.shape[1]], dst))
+    # the backward kernels' mix: three rows written for every eight gathered
+    out = torch.empty(((idx.numel() // 8) * 3, row_bytes // 4), dtype=torch.float32, device="cuda")
+    t_mix = timed(lambda: sar.sar_probe_gather_write(table, idx, 3, out))
     return {"stream_read_GBs": 2 * (2 << 30) / t_read / 1e9,
             "random_row_gather_GBs": idx.numel() * row_bytes / t_gather / 1e9,
             "copy_read_plus_write_GBs": 2 * (1 << 30) / t_copy / 1e9,
+            "gather_8_write_3_GBs": (idx.numel() + (idx.numel() // 8) * 3) * row_bytes / t_mix / 1e9,
             "note": "probe kernels of the library, timed with HIP events in this run; %d-byte rows, "
                     "uniform-random over a 2 GiB table" % row_bytes}
 

@@ -342,6 +342,12 @@ int sar_probe_copy(const void* src, void* dst, size_t bytes, void* stream);
 int sar_probe_row_gather(const void* rows, int64_t n_rows, int row_bytes, const int32_t* idx,
                          int64_t n_idx, float* sink, void* stream);
 
+/* The same gathers with writes mixed in: after every 8 gathered rows, writes_per_8 (0..8) of them
+ * are written to consecutive rows of out, which must hold (n_idx / 8) * writes_per_8 rows.  The
+ * read/write mix of the backward kernels without their arithmetic. */
+int sar_probe_gather_write(const void* rows, int64_t n_rows, int row_bytes, const int32_t* idx,
+                           int64_t n_idx, int writes_per_8, void* out, void* stream);
+
 /* ------------------------------------------------ per-kernel timing hooks
  * On rows of 256 values a backward launch (sar_gat_bwd_block / _all) is two
  * kernels: sources with at least 8 edges (one wavefront each) and the others

@@ -59,6 +59,37 @@ __global__ __launch_bounds__(256) void k_probe_gather(const char* __restrict__ r
     if (acc == 1.2345e38f) sink[0] = 1.f;
 }
 
+// The same gathers, and after every 8 of them `w` of the gathered rows are written to consecutive
+// rows of `out`: the read/write mix of the backward kernels (each source row read and its error
+// row written once, a few gathered rows in between) without their arithmetic.
+template <int LANE_BYTES>
+__global__ __launch_bounds__(256) void k_probe_gather_write(const char* __restrict__ rows, int row_bytes,
+                                                            const int32_t* __restrict__ idx, int64_t n_idx, int w,
+                                                            char* __restrict__ out)
+{
+    constexpr int U = 8;
+    using V = typename std::conditional<LANE_BYTES == 16, float4, float2>::type;
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 6;
+    const int64_t n_waves = ((int64_t)gridDim.x * 256) >> 6;
+    float acc = 0.f;
+    for (int64_t base = wave * U; base + U <= n_idx; base += n_waves * U) {
+        V v[U];
+#pragma unroll
+        for (int k = 0; k < U; ++k) {
+            const int j = __builtin_amdgcn_readfirstlane(idx[base + k]);
+            v[k] = *reinterpret_cast<const V*>(rows + (int64_t)j * row_bytes + lane * LANE_BYTES);
+        }
+        const int64_t o = base / U * w;
+#pragma unroll
+        for (int k = 0; k < U; ++k) {
+            acc += v[k].x + v[k].y;     // every gathered row is used, written or not
+            if (k < w) *reinterpret_cast<V*>(out + (o + k) * row_bytes + lane * LANE_BYTES) = v[k];
+        }
+    }
+    if (acc == 1.2345e38f) out[0] = 1;
+}
+
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 }  // namespace
@@ -94,6 +125,25 @@ extern "C" int sar_probe_row_gather(const void* rows, int64_t n_rows, int row_by
         k_probe_gather<16><<<kMaxPersistentWGs, 256, 0, st>>>(static_cast<const char*>(rows), row_bytes, idx, n_idx, sink);
     else
         k_probe_gather<8><<<kMaxPersistentWGs, 256, 0, st>>>(static_cast<const char*>(rows), row_bytes, idx, n_idx, sink);
+    SAR_LAUNCH_CHECK();
+    return SAR_OK;
+}
+
+extern "C" int sar_probe_gather_write(const void* rows, int64_t n_rows, int row_bytes, const int32_t* idx,
+                                      int64_t n_idx, int writes_per_8, void* out, void* stream)
+{
+    SAR_CHECK_ARG(rows && idx && out && aligned16(rows) && aligned16(out), "rows/idx/out is null or not 16-byte aligned");
+    SAR_CHECK_ARG(n_rows > 0 && n_idx >= 0, "need n_rows > 0 and n_idx >= 0");
+    SAR_CHECK_ARG(writes_per_8 >= 0 && writes_per_8 <= 8, "writes_per_8 must be in [0,8]");
+    if (row_bytes != 1024 && row_bytes != 512)
+        return sar::fail(SAR_ERR_UNSUPPORTED, "row_bytes must be 1024 or 512, got %d", row_bytes);
+    hipStream_t st = sar::as_stream(stream);
+    if (row_bytes == 1024)
+        k_probe_gather_write<16><<<kMaxPersistentWGs, 256, 0, st>>>(static_cast<const char*>(rows), row_bytes, idx, n_idx,
+                                                                    writes_per_8, static_cast<char*>(out));
+    else
+        k_probe_gather_write<8><<<kMaxPersistentWGs, 256, 0, st>>>(static_cast<const char*>(rows), row_bytes, idx, n_idx,
+                                                                   writes_per_8, static_cast<char*>(out));
     SAR_LAUNCH_CHECK();
     return SAR_OK;
 }

@@ -77,7 +77,7 @@ EXPORTS = [
     "sar_gat_scores", "sar_gat_fwd_begin", "sar_gat_fwd_block", "sar_gat_fwd_end", "sar_gat_fwd_all",
     "sar_gat_workspace_bytes", "sar_gat_bwd_begin", "sar_gat_bwd_block", "sar_gat_bwd_all", "sar_gat_bwd_end",
     "sar_linear_fwd", "sar_linear_bwd", "sar_linear_workspace_bytes",
-    "sar_probe_stream_read", "sar_probe_copy", "sar_probe_row_gather",
+    "sar_probe_stream_read", "sar_probe_copy", "sar_probe_row_gather", "sar_probe_gather_write",
     "sar_timing_begin", "sar_timing_count", "sar_timing_get",
 ]
 
@@ -428,6 +428,14 @@ def sar_probe_row_gather(rows: torch.Tensor, idx: torch.Tensor, sink: torch.Tens
     assert idx.dtype == torch.int32 and rows.dim() == 2
     _check(lib().sar_probe_row_gather(_ptr(rows), _c_i64(rows.shape[0]), _c_int(rows.shape[1] * rows.element_size()),
                                       _ptr(idx), _c_i64(idx.numel()), _ptr(sink), _stream()))
+
+
+def sar_probe_gather_write(rows: torch.Tensor, idx: torch.Tensor, writes_per_8: int, out: torch.Tensor) -> None:
+    assert idx.dtype == torch.int32 and rows.dim() == 2 and out.dim() == 2 and out.shape[1] == rows.shape[1]
+    if out.shape[0] < (idx.numel() // 8) * writes_per_8 or out.dtype != rows.dtype:
+        raise SarError(SAR_ERR_INVALID_ARG, "out needs (n_idx / 8) * writes_per_8 rows of the table's type")
+    _check(lib().sar_probe_gather_write(_ptr(rows), _c_i64(rows.shape[0]), _c_int(rows.shape[1] * rows.element_size()),
+                                        _ptr(idx), _c_i64(idx.numel()), _c_int(writes_per_8), _ptr(out), _stream()))
 
 
 # ------------------------------------------------------------------ timing
