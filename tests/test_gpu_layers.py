@@ -307,3 +307,47 @@ def test_skip_untouched_sources_leaves_their_rows_alone():
             assert (got[u] == SENT).all()
             assert rel_err(got[~u], want_d[q][~u]) < 1e-4
     b.close()
+
+
+# ------------------------------------------------------------ the largest block count
+
+@pytest.mark.parametrize("H,D", [(4, 64), (2, 100), (3, 12)])
+def test_max_blocks(H, D):
+    """P = SAR_MAX_BLOCKS = 64 source blocks: builder, both aggregations, every launch shape; one more
+    block is refused."""
+    P, p, F = sar.SAR_MAX_BLOCKS, 63, H * D
+    src, dst, part, rng = make_graph(44, 6400, 60000, P, simple=False)
+    want_b, deg = orc.build_blocks(src, dst, part, P, p)
+    b = gu.build_blocks(src, dst, part, P, p)
+    assert b.P == P
+    for q in (0, 31, 63):
+        v = gu.view_arrays(b, q)
+        assert np.array_equal(v["indptr"], want_b[q].indptr.astype(np.int32))
+        assert np.array_equal(v["indices"], want_b[q].indices)
+        assert np.array_equal(v["t_indices"], want_b[q].t_indices)
+    Zs = [feats(rng, w.n_src, F, torch.float32).cuda() for w in want_b]
+    want = orc.spmm(want_b, [f64(z) for z in Zs], True)
+    assert rel_err(f64(gu.spmm_all(b, Zs, True)), want) < 1e-4
+    assert rel_err(f64(gu.spmm_stream(b, Zs, True)), want) < 1e-4
+    Z3 = [z.reshape(-1, H, D) for z in Zs]
+    Zdst = Z3[p]
+    bound = np.sqrt(6.0 / (D + 1))
+    a_l = torch.from_numpy(rng.uniform(-bound, bound, (H, D)).astype(np.float32)).cuda()
+    a_r = torch.from_numpy(rng.uniform(-bound, bound, (H, D)).astype(np.float32)).cuda()
+    G = feats(rng, b.n_dst, F, torch.float32).cuda().reshape(-1, H, D)
+    wf = orc.gat_fwd(want_b, f64(Zdst), [f64(z) for z in Z3], f64(a_l), f64(a_r), SLOPE)
+    wb = orc.gat_bwd(want_b, f64(Zdst), [f64(z) for z in Z3], f64(G), f64(a_l), f64(a_r), SLOPE, wf)
+    for fwd in (gu.gat_fwd_all, gu.gat_fwd_stream):
+        fw = fwd(b, Zdst, Z3, a_l, a_r, SLOPE, fly=True)
+        assert rel_err(f64(fw.out), wf.out) < 1e-4
+    for batched in (True, False):
+        g = gu.gat_bwd(b, Zdst, Z3, G, a_l, a_r, SLOPE, fw, batched, fly=True)
+        for q in range(P):
+            assert rel_err(f64(g.dZs[q]), wb.dZs[q]) < 1e-4, q
+        assert rel_err(f64(g.ds), wb.ds) < 1e-4
+        assert rel_err(f64(g.da_l), wb.da_l) < 1e-4
+    b.close()
+    part65 = (np.arange(len(part)) % 65).astype(np.int32)
+    with pytest.raises(sar.SarError) as e:
+        gu.build_blocks(src, dst, part65, 65, 0)
+    assert e.value.code == sar.SAR_ERR_UNSUPPORTED
