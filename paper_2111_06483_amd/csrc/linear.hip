@@ -335,7 +335,7 @@ __global__ __launch_bounds__(kGemmThreads) void k_gemm_bf16(GemmArgs g)
 // per fragment, so every ds_read_b128 is conflict-free.  After that one
 // barrier the wavefronts never synchronise again: each walks over its own
 // 32-row tiles, keeping NT 32x32 accumulators (32 x NT*32 outputs) in
-// registers and a ring of kPrefetch chunks of its rows in flight.
+// registers and two pairs of 16-byte pieces of its rows, one in flight while the other is used.
 //
 // fp32: a chunk is 8 contraction values; lane group g = l/32 holds values
 //       8t+4g .. 8t+4g+3, consumed by four V_MFMA_F32_32X32X2_F32 (whose A and
@@ -346,7 +346,6 @@ __global__ __launch_bounds__(kGemmThreads) void k_gemm_bf16(GemmArgs g)
 
 constexpr int kSkinnyWaves = 8;
 constexpr int kSkinnyThreads = 64 * kSkinnyWaves;
-constexpr int kPrefetch = 4;
 constexpr size_t kSkinnyMaxLds = 160 * 1024;   // all of a CU's LDS: one workgroup per CU then
 
 struct SkinnyArgs {
@@ -452,17 +451,29 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_gemm_skinny(SkinnyArgs g)
     int64_t tile = (int64_t)blockIdx.x * kSkinnyWaves + wave;
     if (tile >= n_tiles) return;
 
-    // K is a multiple of the lane's piece, so a piece is inside the row or beyond it
+    // K is a multiple of the lane's piece, so a piece is inside the row or beyond it.  Loads are
+    // unconditional (a piece beyond the row is read from the row's last piece, and zeroed where it
+    // is used) and the main loop below is straight-line code, so that the compiler can count the
+    // loads in flight and wait for the oldest only; with branches around them it waits for all of
+    // them at every chunk, which leaves the ring no depth.
+    const int k_last = g.K - kChunk / 2;
     auto load_piece = [&](const TA* rowp, int t) -> uint4 {
         const int k = t * kChunk + gq * (kChunk / 2);
-        return k < g.K ? *reinterpret_cast<const uint4*>(rowp + k) : make_uint4(0u, 0u, 0u, 0u);
+        return *reinterpret_cast<const uint4*>(rowp + min(k, k_last));
     };
     auto row_ptr = [&](int64_t tl) { return A + std::min<int64_t>(tl * 32 + c, g.M - 1) * g.lda; };
 
-    uint4 a[kPrefetch];
+    // Two sets of pieces: while the chunks of one set are multiplied, the other set travels.
+    // The loads of a set are issued together, ahead of the other set's MFMAs, and are first
+    // needed a whole set later.  (The compiler waits for every load in flight, not for the oldest,
+    // wherever stores may be in flight too, so a deeper ring of single loads gains nothing.)
+    // chunks per set: about 2000 MFMA cycles of one wavefront either way (two where registers run out)
+    constexpr int PS = (BF && !(SC && NT == 8)) ? 4 : 2;
+    uint4 a[PS], b[PS];
     const TA* rowp = row_ptr(tile);
 #pragma unroll
-    for (int u = 0; u < kPrefetch; ++u) a[u] = u < g.chunks ? load_piece(rowp, u) : make_uint4(0u, 0u, 0u, 0u);
+    for (int u = 0; u < PS; ++u) a[u] = load_piece(rowp, u);
+    const int full = g.chunks / (2 * PS) * (2 * PS);
 
     for (; tile < n_tiles; tile += stride) {
         float16_t acc[NA];
@@ -471,58 +482,77 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_gemm_skinny(SkinnyArgs g)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[nt][r] = 0.f;
 
-        for (int t0 = 0; t0 < g.chunks; t0 += kPrefetch) {
+        auto multiply = [&](const uint4& piece, int t) {
+            const bool beyond = t * kChunk + gq * (kChunk / 2) >= g.K;
+            const uint4 av = make_uint4(beyond ? 0u : piece.x, beyond ? 0u : piece.y, beyond ? 0u : piece.z,
+                                        beyond ? 0u : piece.w);
+            const uint4* fr = frag + (size_t)t * (NA * kFragsPerTile * 64) + lane;
+            if (!BF) {
+                uint4 w[NA];
 #pragma unroll
-            for (int u = 0; u < kPrefetch; ++u) {
-                const int t = t0 + u;
-                if (t < g.chunks) {
-                    const uint4 av = a[u];
-                    if (t + kPrefetch < g.chunks) a[u] = load_piece(rowp, t + kPrefetch);
-                    const uint4* fr = frag + (size_t)t * (NA * kFragsPerTile * 64) + lane;
-                    if (!BF) {
-                        uint4 b[NA];
+                for (int nt = 0; nt < NA; ++nt) w[nt] = fr[nt * 64];
 #pragma unroll
-                        for (int nt = 0; nt < NA; ++nt) b[nt] = fr[nt * 64];
+                for (int nt = 0; nt < NA; ++nt)
+                    acc[nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av.x), __uint_as_float(w[nt].x),
+                                                                   acc[nt], 0, 0, 0);
 #pragma unroll
-                        for (int nt = 0; nt < NA; ++nt)
-                            acc[nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av.x), __uint_as_float(b[nt].x),
-                                                                           acc[nt], 0, 0, 0);
+                for (int nt = 0; nt < NA; ++nt)
+                    acc[nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av.y), __uint_as_float(w[nt].y),
+                                                                   acc[nt], 0, 0, 0);
 #pragma unroll
-                        for (int nt = 0; nt < NA; ++nt)
-                            acc[nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av.y), __uint_as_float(b[nt].y),
-                                                                           acc[nt], 0, 0, 0);
+                for (int nt = 0; nt < NA; ++nt)
+                    acc[nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av.z), __uint_as_float(w[nt].z),
+                                                                   acc[nt], 0, 0, 0);
 #pragma unroll
-                        for (int nt = 0; nt < NA; ++nt)
-                            acc[nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av.z), __uint_as_float(b[nt].z),
-                                                                           acc[nt], 0, 0, 0);
+                for (int nt = 0; nt < NA; ++nt)
+                    acc[nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av.w), __uint_as_float(w[nt].w),
+                                                                   acc[nt], 0, 0, 0);
+            } else {
+                const bf16x8_t ax = __builtin_bit_cast(bf16x8_t, av);
 #pragma unroll
-                        for (int nt = 0; nt < NA; ++nt)
-                            acc[nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av.w), __uint_as_float(b[nt].w),
-                                                                           acc[nt], 0, 0, 0);
-                    } else {
-                        const bf16x8_t ax = __builtin_bit_cast(bf16x8_t, av);
+                for (int nt = 0; nt < NA; ++nt) {
+                    const bf16x8_t bh = __builtin_bit_cast(bf16x8_t, fr[(2 * nt) * 64]);
+                    acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ax, bh, acc[nt], 0, 0, 0);
+                }
 #pragma unroll
-                        for (int nt = 0; nt < NA; ++nt) {
-                            const bf16x8_t bh = __builtin_bit_cast(bf16x8_t, fr[(2 * nt) * 64]);
-                            acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ax, bh, acc[nt], 0, 0, 0);
-                        }
-#pragma unroll
-                        for (int nt = 0; nt < NA; ++nt) {
-                            const bf16x8_t bl = __builtin_bit_cast(bf16x8_t, fr[(2 * nt + 1) * 64]);
-                            acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ax, bl, acc[nt], 0, 0, 0);
-                        }
-                    }
+                for (int nt = 0; nt < NA; ++nt) {
+                    const bf16x8_t bl = __builtin_bit_cast(bf16x8_t, fr[(2 * nt + 1) * 64]);
+                    acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ax, bl, acc[nt], 0, 0, 0);
                 }
             }
+        };
+        for (int t0 = 0; t0 < full; t0 += 2 * PS) {
+#pragma unroll
+            for (int u = 0; u < PS; ++u) b[u] = load_piece(rowp, t0 + PS + u);
+            __builtin_amdgcn_sched_barrier(0);     // the loads stay ahead of the MFMAs
+#pragma unroll
+            for (int u = 0; u < PS; ++u) multiply(a[u], t0 + u);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < PS; ++u) a[u] = load_piece(rowp, t0 + 2 * PS + u);   // beyond the end: nobody reads it
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < PS; ++u) multiply(b[u], t0 + PS + u);
+            __builtin_amdgcn_sched_barrier(0);
         }
+        // the last chunks, fewer than two sets: the first set is loaded already
+        if (full + PS < g.chunks) {
+#pragma unroll
+            for (int u = 0; u < PS; ++u) b[u] = load_piece(rowp, full + PS + u);
+        }
+#pragma unroll
+        for (int u = 0; u < PS; ++u)
+            if (full + u < g.chunks) multiply(a[u], full + u);
+#pragma unroll
+        for (int u = 0; u < PS; ++u)
+            if (full + PS + u < g.chunks) multiply(b[u], full + PS + u);
 
         // the next tile's first pieces travel while this one is stored
         const int64_t row0 = tile * 32;
         if (tile + stride < n_tiles) {
             rowp = row_ptr(tile + stride);
 #pragma unroll
-            for (int u = 0; u < kPrefetch; ++u)
-                a[u] = u < g.chunks ? load_piece(rowp, u) : make_uint4(0u, 0u, 0u, 0u);
+            for (int u = 0; u < PS; ++u) a[u] = load_piece(rowp, u);
         }
         // lane holds column c; register r holds row 8*(r/4) + 4*(lane/32) + r%4
         TC* C = static_cast<TC*>(g.C);
