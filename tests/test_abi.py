@@ -66,6 +66,27 @@ def test_validation_errors_need_no_gpu(lib):
     assert lib.sar_gat_workspace_bytes(i64(10), i64(10), 4, 64, ctypes.byref(n)) == 0 and n.value > 0
     assert lib.sar_linear_workspace_bytes(i64(100000), 100, 256, ctypes.byref(n)) == 0 and n.value > 0
     assert lib.sar_linear_fwd(None, None, None, 0, i64(0), 4, 4, 0, 0, None, None, None, None, None) == 0
+    # the layer epilogues, the all-blocks backward and the destination subsets
+    rc = lib.sar_act_bwd(None, None, 9, None, 0, i64(8), None)
+    assert rc == sar.SAR_ERR_UNSUPPORTED and b"SAR_ACT" in lib.sar_last_error()
+    rc = lib.sar_act_bwd(None, None, sar.SAR_ACT_RELU, None, 0, i64(6), None)
+    assert rc == sar.SAR_ERR_INVALID_ARG and b"multiple of 4" in lib.sar_last_error()
+    assert lib.sar_act_bwd(None, None, sar.SAR_ACT_RELU, None, 1, i64(0), None) == 0       # nothing to do
+    rc = lib.sar_spmm_end(None, 0, None, None, 5, None, 0, i64(4), 8, None)
+    assert rc == sar.SAR_ERR_UNSUPPORTED
+    rc = lib.sar_gat_fwd_end(None, None, None, 5, None, None, 0, i64(4), 2, 4, None)
+    assert rc == sar.SAR_ERR_UNSUPPORTED
+    rc = lib.sar_gat_bwd_begin(None, None, None, None, 5, None, 0, None, None, i64(4), 2, 4, None)
+    assert rc == sar.SAR_ERR_UNSUPPORTED
+    rc = lib.sar_spmm_bwd_all(None, None, 1, 0, 8, None, None)
+    assert rc == sar.SAR_ERR_INVALID_ARG and b"handle" in lib.sar_last_error()
+    rc = lib.sar_blocks_subset(None, None, i64(0), 0, None, ctypes.byref(h))
+    assert rc == sar.SAR_ERR_INVALID_ARG and b"handle" in lib.sar_last_error()
+    part = (ctypes.c_int32 * 1)(0)       # only its being non-null is looked at before the flags
+    rc = lib.sar_blocks_build(None, None, 4, i64(0), part, i64(1), 1, 0, 64, None, ctypes.byref(h))
+    assert rc == sar.SAR_ERR_INVALID_ARG and b"flags" in lib.sar_last_error()
+    rc = lib.sar_probe_gather_write(None, i64(1), 1024, None, i64(0), 9, None, None)
+    assert rc == sar.SAR_ERR_INVALID_ARG
 
 
 def test_bench_refuses_more_than_one_gpu():
