@@ -175,8 +175,9 @@ class Layer:
 
     # ---- algorithmic bytes of the gather kernels (what the method must move at least)
     def alg_bytes(self):
-        """Per kernel of the all-blocks launches: forward, backward over sources with >= 8 edges
-        ("wide"), backward over the other sources ("narrow", four per wavefront)."""
+        """Per kernel of the all-blocks launches: forward, backward over sources with at least 4
+        (fp32 rows) or 8 (bf16 rows) edges ("wide"), backward over the other sources ("narrow",
+        four per wavefront)."""
         torch, sar = self.torch, self.sar
         fb = 2 if self.w.dtype == torch.bfloat16 else 4
         F, H, n, E = self.F, self.H, self.n, self.E
@@ -189,7 +190,7 @@ class Layer:
         edges = {"wide": 0, "narrow": 0}
         for v in self.views:
             deg = torch.diff(sar.device_array(v.t_indptr, v.n_src + 1))
-            wide = deg >= 8
+            wide = deg >= (8 if self.w.dtype == torch.bfloat16 else 4)
             rows["wide"] += int(wide.sum())
             rows["narrow"] += int((~wide).sum())
             rows_touched["wide"] += int(wide.sum())
@@ -507,7 +508,7 @@ def main():
                    "mode": args.mode, "scale": args.scale, "act": args.act, "dst_frac": args.dst_frac,
                    "skip_untouched": args.skip_untouched},
         "phases_ms": {"step_events": all_ms, "gat_fwd": fwd_ms, "gat_bwd": bwd_ms,
-                      "gat_bwd_kernel_rows_ge8": wide_ms, "gat_bwd_kernel_rows_lt8": narrow_ms,
+                      "gat_bwd_kernel_wide": wide_ms, "gat_bwd_kernel_narrow": narrow_ms,
                       "other (XW fwd+bwd, scores, begin/end)": all_ms - fwd_ms - bwd_ms},
         "aggregation_only_edges_per_s": layer.E / ((fwd_ms + bwd_ms) * 1e-3),
         "builder_s": layer.builder_s,

@@ -302,7 +302,7 @@ struct BwdArgs {
 struct BwdScalars {
     const uint32_t* rows;       // source work list; tagged with the block when ALL
     int64_t n_rows, n_long;
-    int64_t n_wide;             // list entries [n_wide, n_rows) have fewer than 8 edges
+    int64_t n_wide;             // list entries [n_wide, n_rows) have few edges: four sources per wavefront
     const void* G;              // [n_dst,H,D]
     const float4* rec;          // [n_dst,H]: (s*log2e, L*log2e, delta, unused)
     const float* a_l;           // [H,D]
@@ -1262,7 +1262,7 @@ extern "C" int sar_gat_bwd_block(const sar_blocks_t* b, int q, const void* Zq, c
         // sources without edges come last and get dZ = 0, dt = 0, unless the handle skips them
         a.n_rows = (b->flags & SAR_BUILD_SKIP_UNTOUCHED) ? k.n_t_rows : k.n_src;
         a.n_long = k.n_t_long;
-        a.n_wide = k.n_t_wide;
+        a.n_wide = dtype == SAR_F32 ? k.n_t_wide_f32 : k.n_t_wide;
         fill_bwd_group(a, hg, g, H, D, G, rec, a_l, ds, work, slope);
         if (dtype == SAR_F32)
             SAR_TRY((launch_bwd<float, false>(tabs, a, da_l + f0, st)));
@@ -1304,7 +1304,7 @@ extern "C" int sar_gat_bwd_all(const sar_blocks_t* b, const void* const* Zq, con
         a.n_rows = 0;
         for (int q = 0; q < b->P; ++q) a.n_rows += b->blk[q].n_src;
         if (b->flags & SAR_BUILD_SKIP_UNTOUCHED) a.n_rows = b->n_ft_rows;
-        a.n_wide = b->n_ft_wide;
+        a.n_wide = dtype == SAR_F32 ? b->n_ft_wide_f32 : b->n_ft_wide;
         a.n_long = b->n_ft_long;
         a.tag_shift = b->tag_shift;
         fill_bwd_group(a, hg, g, H, D, G, rec, a_l, ds, work, slope);
