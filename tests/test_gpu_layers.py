@@ -351,3 +351,50 @@ def test_max_blocks(H, D):
     with pytest.raises(sar.SarError) as e:
         gu.build_blocks(src, dst, part65, 65, 0)
     assert e.value.code == sar.SAR_ERR_UNSUPPORTED
+
+
+# ------------------------------------------------------------------ HIP graph replay
+
+def test_step_replays_as_a_hip_graph():
+    """The entry points of a layer step neither allocate nor synchronise, so the whole step can be
+    captured into a HIP graph.  The graph is replayed several times with eager steps and
+    synchronisations in between, and every replay is checked against the eager results."""
+    import bench
+    from paper_2111_06483_amd import synth
+    w = synth.make_workload("cfg3", device="cuda", scale=0.01)
+    layer = bench.Layer(w, torch, sar, synth, act=sar.SAR_ACT_RELU)
+    for _ in range(2):
+        layer.step("all")                      # warm-up: one-time queries happen outside the capture
+    torch.cuda.synchronize()
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [t.clone() for t in (layer.out, layer.L, layer.dZdst, layer.dW, layer.dX_dst, layer.da_l, layer.da_r,
+                                    layer.ds, *layer.dZs)]
+
+    want = snapshot()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        layer.step("all")                      # once more on the capture stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            layer.step("all")
+    torch.cuda.synchronize()
+
+    def poison():
+        for t in (layer.out, layer.dZdst, layer.dX_dst, *layer.dZs):
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+
+    for k in range(3):
+        poison()
+        graph.replay()
+        got = snapshot()
+        for a, b in zip(got, want):
+            assert not torch.isnan(a.float()).any()
+            # sums that pass through the atomically accumulated ds may differ in their last bits
+            assert rel_err(f64(a), f64(b)) < 1e-5
+        assert torch.equal(got[0], want[0]) and torch.equal(got[1], want[1])     # the forward is reproducible
+        layer.step("all")                      # eager work between the replays
+        torch.cuda.synchronize()
