@@ -49,6 +49,9 @@ def parse():
     ap.add_argument("--skip-untouched", action="store_true",
                     help="backward passes do not write the rows of sources without an edge in a block "
                          "(only the rows V_{p,q} are exchanged, Sec. 3.2); the buffers are zeroed once")
+    ap.add_argument("--storage", default="config", choices=["config", "f32", "bf16"],
+                    help="storage type of the feature rows; 'config' keeps what the configuration names "
+                         "(the headline, config 3, is fp32); accumulation is fp32 either way")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this size (to scale rocprofv3's FETCH_SIZE/WRITE_SIZE)")
@@ -433,6 +436,8 @@ def main():
         fak_sweep(args, torch, sar, synth)
         return
     w = synth.make_workload(args.workload, device="cuda", scale=args.scale)
+    if args.storage != "config":
+        w.dtype = torch.float32 if args.storage == "f32" else torch.bfloat16
     if args.workload == "cfg2":
         sage_bench(args, w, torch, sar, synth)
         return
