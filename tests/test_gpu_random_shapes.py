@@ -1,0 +1,159 @@
+"""Seeded random shapes through every entry point of the path, against the oracle.
+
+Each case draws a graph size, a partition count, a head geometry, a row type and the
+launch options (per-block or all-blocks launches, source scores read or formed in the
+kernel, untouched source rows written or skipped, an empty block) and checks the block
+index bit for bit and every tensor of the forward and backward passes to the
+tolerance of its row type.  All inputs are valid; the point is the corners between the
+fixed shapes of test_gpu_parity.py: one-node partitions, blocks without edges, heads
+that leave lanes idle, rows of several head groups.
+"""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import sar_oracle as orc
+from tests.helpers import rel_err
+from tests.test_gpu_parity import TOL, SLOPE, check_fwd, f64, feats, make_graph
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    from paper_2111_06483_amd import sar
+    from tests import gpu_util as gu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU in this process")
+    sar.lib()
+
+
+def draw(case):
+    rng = np.random.default_rng(7000 + case)
+    N = int(rng.choice([40, 300, 1000, 4000, 12000]))
+    E = int(N * rng.choice([0.5, 2, 8, 30]))
+    P = min(int(rng.choice([1, 2, 3, 5, 8, 16, 33, 64])), N)
+    dtype = [torch.float32, torch.bfloat16][int(rng.integers(0, 2))]
+    vec = 8 if dtype == torch.bfloat16 else 4
+    H = int(rng.choice([1, 2, 3, 4, 5, 8, 12, 16]))
+    D = int(rng.choice([1, 2, 3, 4, 6, 8, 13, 16, 25, 32, 50, 64])) * vec
+    while H * D > 2048:
+        D = max(vec, D // 2 // vec * vec)
+    opts = dict(p=int(rng.integers(0, P)), simple=bool(rng.integers(0, 2)), hubs=bool(rng.integers(0, 2)),
+                skip=bool(rng.integers(0, 2)), batched=bool(rng.integers(0, 2)), fly=bool(rng.integers(0, 2)),
+                mean=bool(rng.integers(0, 2)),
+                empty=int(rng.integers(0, P)) if (P > 1 and rng.integers(0, 4) == 0) else None,
+                n_lin=int(rng.choice([1, 31, 33, 257, 1000, 5000])),
+                K=int(rng.choice([4, 8, 24, 40, 64, 100, 128, 200, 256])))
+    return rng, N, E, P, H, D, dtype, opts
+
+
+def close(got, want, tol, floor):
+    """Relative to the tensor's scale; `floor` is the scale of the terms whose sum the tensor is,
+    for sums that cancel to (nearly) nothing."""
+    want = np.asarray(want)
+    if want.size == 0:
+        return True
+    got = got if isinstance(got, np.ndarray) else f64(got)
+    return np.abs(got - want).max() <= tol * max(np.abs(want).max(), floor)
+
+
+@pytest.mark.parametrize("case", range(32))
+def test_random_shape(case):
+    rng, N, E, P, H, D, dtype, o = draw(case)
+    tol, F, p = TOL[dtype], H * D, o["p"]
+    src, dst, part, r2 = make_graph(7000 + case, N, E, P, hubs=o["hubs"], simple=o["simple"],
+                                    empty_block=o["empty"])
+    want_b, deg = orc.build_blocks(src, dst, part, P, p)
+    flags = sar.SAR_BUILD_TRANSPOSE | sar.SAR_BUILD_FUSED | (sar.SAR_BUILD_SKIP_UNTOUCHED if o["skip"] else 0)
+    b = gu.build_blocks(src, dst, part, P, p, flags=flags)
+    touched = [np.diff(w.t_indptr) > 0 if o["skip"] else np.ones(w.n_src, bool) for w in want_b]
+    for q in range(P):
+        v = gu.view_arrays(b, q)
+        assert np.array_equal(v["indptr"], want_b[q].indptr.astype(np.int32))
+        assert np.array_equal(v["indices"], want_b[q].indices)
+        assert np.array_equal(v["t_indptr"], want_b[q].t_indptr.astype(np.int32))
+        assert np.array_equal(v["t_indices"], want_b[q].t_indices)
+
+    Zs = [feats(r2, w.n_src, F, dtype).cuda().reshape(-1, H, D) for w in want_b]
+    Zdst = feats(r2, b.n_dst, F, dtype).cuda().reshape(-1, H, D)
+    bound = np.sqrt(6.0 / (D + 1))
+    a_l = torch.from_numpy(r2.uniform(-bound, bound, (H, D)).astype(np.float32)).cuda()
+    a_r = torch.from_numpy(r2.uniform(-bound, bound, (H, D)).astype(np.float32)).cuda()
+    G = feats(r2, b.n_dst, F, dtype).cuda().reshape(-1, H, D)
+    Z2, G2 = [z.reshape(-1, F) for z in Zs], G.reshape(-1, F)
+
+    # sum / mean aggregation and its case-1 backward (Eq. 2; Alg. 2)
+    want = orc.spmm(want_b, [f64(z) for z in Z2], o["mean"])
+    assert rel_err(f64(gu.spmm_all(b, Z2, o["mean"])), want) < tol
+    assert rel_err(f64(gu.spmm_stream(b, Z2, o["mean"])), want) < tol
+    want_d = orc.spmm_bwd(want_b, f64(G2), o["mean"])
+    d_all = [torch.full((w.n_src, F), float("nan"), dtype=dtype, device="cuda") for w in want_b]
+    d_blk = [torch.full((w.n_src, F), float("nan"), dtype=dtype, device="cuda") for w in want_b]
+    sar.sar_spmm_bwd_all(b, G2, o["mean"], d_all)
+    for q in range(P):
+        sar.sar_spmm_bwd_block(b, q, G2, o["mean"], d_blk[q])
+        t = touched[q]
+        assert rel_err(f64(d_all[q])[t], want_d[q][t]) < tol, q
+        assert rel_err(f64(d_blk[q])[t], want_d[q][t]) < tol, q
+
+    # attention aggregation (Eq. 3), both launch shapes
+    Z64 = [f64(z) for z in Zs]
+    wf = orc.gat_fwd(want_b, f64(Zdst), Z64, f64(a_l), f64(a_r), SLOPE)
+    fa = gu.gat_fwd_all(b, Zdst, Zs, a_l, a_r, SLOPE, fly=o["fly"])
+    check_fwd(fa, wf, deg, dtype)
+    check_fwd(gu.gat_fwd_stream(b, Zdst, Zs, a_l, a_r, SLOPE, fly=o["fly"]), wf, deg, dtype)
+    # The backward pass reads the stored forward output: with 2-byte rows that is the rounded one
+    # (the oracle's own, rounded the same way).
+    if dtype == torch.bfloat16:
+        wf = dataclasses.replace(wf, out=torch.from_numpy(wf.out).to(torch.bfloat16).to(torch.float64).numpy())
+    wb = orc.gat_bwd(want_b, f64(Zdst), Z64, f64(G), f64(a_l), f64(a_r), SLOPE, wf)
+    g = gu.gat_bwd(b, Zdst, Zs, G, a_l, a_r, SLOPE, fa, o["batched"], fly=o["fly"])
+    for q in range(P):
+        t = touched[q]
+        assert rel_err(f64(g.dZs[q])[t], wb.dZs[q][t]) < tol, q
+        assert close(f64(g.dts[q])[t], wb.dt[q][t], tol, np.sqrt(D)), q
+    # ds sums alpha (c - delta) du/de over a destination's edges: terms of size ~sqrt(D) that cancel
+    # exactly when all its edges sit on one side of the LeakyReLU (always so with one edge).
+    assert close(g.ds, wb.ds, tol, np.sqrt(D))
+    assert close(g.dZdst, wb.dZdst, tol, np.sqrt(D) * bound)
+    assert close(g.da_r, wb.da_r, tol, np.sqrt(D))
+    assert close(g.da_l, wb.da_l, tol, np.sqrt(D))
+
+    # destination subset (App. B): index bit-exact, forward equal to the rows of the full one
+    if b.n_dst > 0:
+        ids = rng.integers(0, b.n_dst, size=max(1, b.n_dst // 3)).astype(np.int32)
+        want_s, _ = orc.subset_blocks(want_b, ids)
+        ids_d = gu.dev(ids, torch.int32)
+        sb = sar.sar_blocks_subset(b, ids_d)
+        for q in range(P):
+            v = gu.view_arrays(sb, q)
+            assert np.array_equal(v["indptr"], want_s[q].indptr.astype(np.int32))
+            assert np.array_equal(v["indices"], want_s[q].indices)
+            assert np.array_equal(v["t_indptr"], want_s[q].t_indptr.astype(np.int32))
+            assert np.array_equal(v["t_indices"], want_s[q].t_indices)
+        fs = gu.gat_fwd_all(sb, Zdst[ids_d.long()].contiguous(), Zs, a_l, a_r, SLOPE, fly=o["fly"])
+        assert torch.equal(fs.out, fa.out[ids_d.long()])
+        sb.close()
+    b.close()
+
+    # transform with the score columns, and its backward (Eq. 1; Alg. 2)
+    n, K = o["n_lin"], o["K"]
+    X = feats(r2, n, K, dtype).cuda()
+    W = torch.from_numpy(r2.uniform(-0.2, 0.2, (K, F)).astype(np.float32)).cuda()
+    Z, s1, s2 = gu.linear_fwd(X, W, a_r, a_l)
+    wz = orc.linear_fwd(f64(X), f64(W))
+    assert rel_err(f64(Z), wz) < tol
+    assert rel_err(f64(s1), (wz.reshape(n, H, D) * f64(a_r)[None]).sum(-1)) < tol
+    assert rel_err(f64(s2), (wz.reshape(n, H, D) * f64(a_l)[None]).sum(-1)) < tol
+    dZ = feats(r2, n, F, dtype).cuda()
+    dW0 = torch.from_numpy(r2.standard_normal((K, F)).astype(np.float32)).cuda()
+    dW = dW0.clone()
+    dX = gu.linear_bwd(X, dZ, W, dW)
+    want_dW, want_dX = orc.linear_bwd(f64(X), f64(dZ), f64(W))
+    assert rel_err(f64(dW), want_dW + f64(dW0)) < tol
+    assert rel_err(f64(dX), want_dX) < tol
