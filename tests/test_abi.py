@@ -97,3 +97,41 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0
     assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+C_CALLER = r"""
+#include <stdio.h>
+#include <string.h>
+#include "sar_mi355x.h"
+int main(void)
+{
+    size_t n = 0;
+    if (sar_version() != 2) return 1;
+    if (sar_gat_workspace_bytes(10, 10, 4, 64, &n) != SAR_OK || n == 0) return 2;
+    if (sar_spmm_block(NULL, 0, NULL, SAR_F32, 16, NULL, NULL) != SAR_ERR_INVALID_ARG) return 3;
+    if (strstr(sar_last_error(), "handle") == NULL) return 4;
+    printf("ok\n");
+    return 0;
+}
+"""
+
+
+def test_header_serves_a_plain_c_caller(lib, tmp_path):
+    """The header is C (not C++): a C99 program compiled with -pedantic includes it, links the
+    library and gets status codes and error text back, with no Python in between."""
+    import shutil
+    import subprocess
+    from paper_2111_06483_amd import sar
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "caller.c"
+    src.write_text(C_CALLER)
+    exe = tmp_path / "caller"
+    libdir = os.path.dirname(sar.LIB_PATH)
+    name = os.path.basename(sar.LIB_PATH)[3:-3]          # lib<name>.so
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I",
+                        os.path.join(ROOT, "include"), str(src), "-o", str(exe), "-L", libdir, "-l" + name,
+                        "-Wl,-rpath," + libdir], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    r = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert r.returncode == 0 and r.stdout.strip() == "ok", (r.returncode, r.stdout, r.stderr)
