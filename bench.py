@@ -274,13 +274,17 @@ def cpu_baseline(layer, n_blocks):
     from paper_2111_06483_amd import synth
     Xs = [f64(synth.normal_rows(2, layer.members[q].cpu(), w.f_in, dtype=w.dtype)) for q in range(n_blocks)]
     a_l, a_r, G = f64(layer.a_l), f64(layer.a_r), f64(layer.G)
-    t0 = time.perf_counter()
-    Zdst = orc.linear_fwd(Xp, W)
-    Zs = [orc.linear_fwd(X, W) for X in Xs]
-    fwd = orc.gat_fwd(blocks, Zdst, Zs, a_l, a_r, w.slope)
-    bwd = orc.gat_bwd(blocks, Zdst, Zs, G, a_l, a_r, w.slope, fwd)
-    orc.linear_bwd(Xp, bwd.dZdst, W)
-    dt = time.perf_counter() - t0
+    # the oracle's loops are single-threaded C; hold the matrix products (numpy's BLAS) to one
+    # thread as well, so that `cores` is what ran
+    from threadpoolctl import threadpool_limits
+    Zs = [orc.linear_fwd(X, W) for X in Xs]      # the fetched blocks' rows: given, as in the GPU step
+    with threadpool_limits(limits=1):
+        t0 = time.perf_counter()
+        Zdst = orc.linear_fwd(Xp, W)
+        fwd = orc.gat_fwd(blocks, Zdst, Zs, a_l, a_r, w.slope)
+        bwd = orc.gat_bwd(blocks, Zdst, Zs, G, a_l, a_r, w.slope, fwd)
+        orc.linear_bwd(Xp, bwd.dZdst, W)
+        dt = time.perf_counter() - t0
     edges = sum(b.nnz for b in blocks)
     return {"value": edges / dt, "unit": "edges/s", "cores": 1, "kind": "oracle",
             "sample": "%d of %d source blocks of the same workload (%d edges), forward+backward, fp64, %.1f s"
