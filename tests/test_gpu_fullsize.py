@@ -212,6 +212,14 @@ def test_cfg5_full_size_sampled():
     check_gat("cfg5", 40, 6)
 
 
+@pytest.mark.parametrize("heads", [2, 4])
+def test_head_sweep_full_size_sampled(heads):
+    """The head-count sweep of Sec. 4.1 at its real size: the whole 2.45M-node graph as one block
+    (121.8M edges), heads of width 100 (the padded lane geometry; 4 heads = 2 launches of 2)."""
+    check_gat("fak%d" % heads, 100, 12)
+    torch.cuda.empty_cache()
+
+
 def test_cfg2_full_size_sampled():
     """GraphSage mean aggregation, F = 256 fp32, 15.2M in-edges over 8 blocks."""
     w = synth.make_workload("cfg2", device="cuda")
