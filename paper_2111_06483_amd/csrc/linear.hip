@@ -369,7 +369,6 @@ struct SkinnyArgs {
     int stage_off;
 };
 
-constexpr int kStageBytes = 32 * 32 * 2;   // per wavefront
 
 template <typename TA, typename TC, int NT, bool SC>
 __global__ __launch_bounds__(kSkinnyThreads) void k_gemm_skinny(SkinnyArgs g)
@@ -385,7 +384,7 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_gemm_skinny(SkinnyArgs g)
     uint4* frag = reinterpret_cast<uint4*>(skinny_lds);
 
     const int units = g.chunks * NA * kFragsPerTile * 64;
-    for (int u = tid; u < units; u += kSkinnyThreads) {
+    auto make_frag = [&](int u) -> uint4 {
         const int l = u & 63;
         int f = u >> 6, half = 0;
         if (BF) {
@@ -415,7 +414,16 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_gemm_skinny(SkinnyArgs g)
                 w[j] = part[0] | (part[1] << 16);
             }
         }
-        frag[u] = make_uint4(w[0], w[1], w[2], w[3]);
+        return make_uint4(w[0], w[1], w[2], w[3]);
+    };
+    // four fragments per thread and round, so that their 16 loads travel together
+    for (int u0 = tid; u0 < units; u0 += 4 * kSkinnyThreads) {
+        uint4 val[4];
+#pragma unroll
+        for (int x = 0; x < 4; ++x) val[x] = make_frag(min(u0 + x * kSkinnyThreads, units - 1));
+#pragma unroll
+        for (int x = 0; x < 4; ++x)
+            if (u0 + x * kSkinnyThreads < units) frag[u0 + x * kSkinnyThreads] = val[x];
     }
     if (SC) {
         // (W a)[k][h] = sum_d W[k][h*D + d] a[h][d]: z_h . a_h = x . (W_h a_h), so the scores
@@ -426,12 +434,22 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_gemm_skinny(SkinnyArgs g)
             const int k = p / cols, col = p % cols;
             const int h = col < g.H ? col : col - g.H;
             const float* av = col < g.H ? g.a1 : g.a2;
+            const int t = k / kChunk, gk = (k / (kChunk / 2)) & 1, e = k % (kChunk / 2);
             float v = 0.f;
             if (av) {
-                const float* wrow = g.B + (int64_t)k * g.sbk + (int64_t)h * g.D * g.sbn;
-                for (int d = 0; d < g.D; ++d) v = fmaf(wrow[d * g.sbn], av[h * g.D + d], v);
+                if (!BF && gridDim.y == 1) {
+                    // row k of W is in LDS already (exact fp32 values, fragment order): 64 strided
+                    // reads of global memory per product would cost more than the whole staging
+                    const float* wk = reinterpret_cast<const float*>(frag) + ((size_t)t * NA * 64 + gk * 32) * 4 + e;
+                    for (int d = 0; d < g.D; ++d) {
+                        const int n = h * g.D + d;
+                        v = fmaf(wk[((n >> 5) * 64 + (n & 31)) * 4], av[n], v);
+                    }
+                } else {
+                    const float* wrow = g.B + (int64_t)k * g.sbk + (int64_t)h * g.D * g.sbn;
+                    for (int d = 0; d < g.D; ++d) v = fmaf(wrow[d * g.sbn], av[h * g.D + d], v);
+                }
             }
-            const int t = k / kChunk, gk = (k / (kChunk / 2)) & 1, e = k % (kChunk / 2);
             if (!BF) {
                 reinterpret_cast<float*>(frag)[(((size_t)t * NA + NT) * 64 + gk * 32 + col) * 4 + e] = v;
             } else {
@@ -556,29 +574,31 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_gemm_skinny(SkinnyArgs g)
         }
         // lane holds column c; register r holds row 8*(r/4) + 4*(lane/32) + r%4
         TC* C = static_cast<TC*>(g.C);
-        if (sizeof(TC) == 2 && g.stage_off) {
-            // A lane's 16 values of a tile are 16 different rows: stored directly they are 2-byte
-            // scattered writes.  The tile is turned through the wavefront's own 2 KB of LDS
-            // instead and leaves as 16-byte pieces, 64 contiguous bytes per row.
-            uint16_t* stg = reinterpret_cast<uint16_t*>(skinny_lds + g.stage_off + wave * kStageBytes);
+        if (g.stage_off) {
+            // A lane's 16 values of a tile are 16 different rows: stored directly they are 2- or
+            // 4-byte writes, 128 store instructions per 32 x 256 outputs and more of them than a
+            // wavefront may have in flight.  The tile is turned through the wavefront's own
+            // 2 or 4 KB of LDS instead and leaves as 16-byte pieces, whole 64- or 128-byte rows.
+            constexpr int kPer = 16 / (int)sizeof(TC);        // values per piece
+            constexpr int kPieces = 32 / kPer;                // pieces per tile row
+            constexpr int kRows = 64 / kPieces;               // tile rows per store instruction
+            TC* stg = reinterpret_cast<TC*>(skinny_lds + g.stage_off + wave * (32 * 32 * (int)sizeof(TC)));
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
-                    stg[(8 * (r / 4) + 4 * gq + (r % 4)) * 32 + c] = (uint16_t)f32_to_bf16_rne(acc[nt][r]);
+                    stg[(8 * (r / 4) + 4 * gq + (r % 4)) * 32 + c] = from_f32<TC>(acc[nt][r]);
                 __builtin_amdgcn_wave_barrier();
 #pragma unroll
-                for (int half = 0; half < 2; ++half) {
-                    const int row = half * 16 + (lane >> 2), piece = lane & 3;
-                    const uint4 v = *reinterpret_cast<const uint4*>(stg + row * 32 + piece * 8);
-                    const int64_t i = row0 + row, n = n0 + nt * 32 + piece * 8;
+                for (int pass = 0; pass < 32 / kRows; ++pass) {
+                    const int row = pass * kRows + lane / kPieces, piece = lane % kPieces;
+                    const TC* from = stg + row * 32 + piece * kPer;
+                    const int64_t i = row0 + row, n = n0 + nt * 32 + piece * kPer;
                     if (i < g.M) {
-                        if (n + 8 <= g.N) {
-                            *reinterpret_cast<uint4*>(C + i * g.ldc + n) = v;
+                        if (n + kPer <= g.N) {
+                            *reinterpret_cast<uint4*>(C + i * g.ldc + n) = *reinterpret_cast<const uint4*>(from);
                         } else {
-                            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-                            for (int e = 0; e < 8 && n + e < g.N; ++e)
-                                reinterpret_cast<uint16_t*>(C)[i * g.ldc + n + e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+                            for (int e = 0; e < kPer && n + e < g.N; ++e) C[i * g.ldc + n + e] = from[e];
                         }
                     }
                 }
@@ -631,10 +651,23 @@ bool plan_skinny(const void* A, int64_t lda, const void* C, int64_t ldc, int K, 
     const int need = (N + 31) / 32;
     int nt = 1;
     while (nt < need && nt < 8) nt *= 2;
-    // 2-byte outputs go through staging tiles when their 16-byte pieces are aligned
-    const bool stage = dtype != SAR_F32 && reinterpret_cast<uintptr_t>(C) % 16 == 0 && (ldc * elem) % 16 == 0;
-    const size_t stage_bytes = stage ? (size_t)kSkinnyWaves * kStageBytes : 0;
-    while (nt >= 1 && (size_t)p->chunks * (nt + extra_tiles) * unit + stage_bytes > kSkinnyMaxLds) nt /= 2;
+    // Outputs go through staging tiles when their 16-byte pieces are aligned: always for 2-byte
+    // outputs (stored directly they are scattered 2-byte writes), for 4-byte outputs when the
+    // tiles fit beside the small operand without narrowing the slab
+    bool stage = reinterpret_cast<uintptr_t>(C) % 16 == 0 && (ldc * elem) % 16 == 0;
+    size_t stage_bytes = stage ? (size_t)kSkinnyWaves * 32 * 32 * elem : 0;
+    auto fits = [&](int t, size_t extra) {
+        return (size_t)p->chunks * (t + extra_tiles) * unit + extra <= kSkinnyMaxLds;
+    };
+    if (dtype == SAR_F32) {
+        while (nt >= 1 && !fits(nt, 0)) nt /= 2;
+        if (nt >= 1 && !fits(nt, stage_bytes)) {
+            stage = false;
+            stage_bytes = 0;
+        }
+    } else {
+        while (nt >= 1 && !fits(nt, stage_bytes)) nt /= 2;
+    }
     if (nt < 1) return false;
     p->nt = nt;
     p->slabs = (unsigned)((need + nt - 1) / nt);
