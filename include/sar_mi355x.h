@@ -351,9 +351,11 @@ int sar_probe_gather_write(const void* rows, int64_t n_rows, int row_bytes, cons
 /* ------------------------------------------------ per-kernel timing hooks
  * On rows of 256 values a backward launch (sar_gat_bwd_block / _all) is two
  * kernels: sources with at least 8 edges (bf16 rows) or 4 edges (fp32 rows), one
- * wavefront each, and the others, four per wavefront.  After sar_timing_begin(n) the next n backward launches
- * record HIP events around each of the two on their launch stream.  Not thread
- * safe; allocates n*3 events (sar_timing_begin(0) frees them). */
+ * wavefront each, and the others, four per wavefront, followed by a fill of the
+ * rows of the sources without an edge.  After sar_timing_begin(n) the next n
+ * backward launches record HIP events around the first kernel and around the
+ * rest on their launch stream.  Not thread safe; allocates n*3 events
+ * (sar_timing_begin(0) frees them). */
 int sar_timing_begin(int max_records);
 /* *n = records filled so far. */
 int sar_timing_count(int* n);

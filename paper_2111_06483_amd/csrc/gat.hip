@@ -303,6 +303,9 @@ struct BwdScalars {
     const uint32_t* rows;       // source work list; tagged with the block when ALL
     int64_t n_rows, n_long;
     int64_t n_wide;             // list entries [n_wide, n_rows) have few edges: four sources per wavefront
+    int64_t n_touched;          // list entries [n_touched, n_rows) have no edge at all
+    const int64_t* n_src_host;  // host: rows of every block's dZ_q / dt_q (null: unknown)
+    int n_blocks;
     const void* G;              // [n_dst,H,D]
     const float4* rec;          // [n_dst,H]: (s*log2e, L*log2e, delta, unused)
     const float* a_l;           // [H,D]
@@ -918,6 +921,37 @@ __global__ __launch_bounds__(256) void k_reduce_partials_padded(const float* __r
     if (threadIdx.x == 0) out[h * D + 4 * k + x] += red[0];
 }
 
+// The sources without an edge in their block (the tail of the work list): their rows of dZ_q and
+// dt_q are zero, and nothing has to be read for that but the list entry.
+template <typename T, bool ALL>
+__global__ __launch_bounds__(256) void k_bwd_zero_rows(f256::BwdTabs tabs, const uint32_t* __restrict__ rows,
+                                                       int64_t r_begin, int64_t r_end, int H, int tag_shift)
+{
+    constexpr int kPieces = f256::kF * (int)sizeof(T) / 16;   // 16-byte pieces of a row
+    __shared__ void* s_dZ[SAR_MAX_BLOCKS];
+    __shared__ float* s_dt[SAR_MAX_BLOCKS];
+    if (threadIdx.x < SAR_MAX_BLOCKS) {
+        s_dZ[threadIdx.x] = tabs.dZ[threadIdx.x];
+        s_dt[threadIdx.x] = tabs.dt[threadIdx.x];
+    }
+    __syncthreads();
+    const uint32_t mask = ALL ? ((1u << tag_shift) - 1u) : 0xffffffffu;
+    const int64_t total = (r_end - r_begin) * kPieces;
+    for (int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x; p < total; p += (int64_t)gridDim.x * 256) {
+        const uint32_t id = rows[r_begin + p / kPieces];
+        const int piece = (int)(p % kPieces);
+        const int q = ALL ? (int)(id >> tag_shift) : 0;
+        const int64_t j = (int64_t)(id & mask);
+        reinterpret_cast<uint4*>(static_cast<T*>(s_dZ[q]) + j * f256::kF)[piece] = make_uint4(0u, 0u, 0u, 0u);
+        if (piece < H) s_dt[q][j * H + piece] = 0.f;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_zero_f32(float* __restrict__ p, int64_t n)
+{
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) p[i] = 0.f;
+}
+
 template <typename T, int LPH, bool ALL>
 int launch_bwd_f256(const BwdArgs& tabs, const BwdScalars& a, unsigned* grid_out, hipStream_t st)
 {
@@ -936,7 +970,20 @@ int launch_bwd_f256(const BwdArgs& tabs, const BwdScalars& a, unsigned* grid_out
     p.G = a.G; p.rec = a.rec; p.a_l = a.a_l; p.ds = a.ds; p.partial = a.partial;
     p.H = a.H; p.tag_shift = a.tag_shift; p.slope = a.slope;
     unsigned g_wide = 0, g_narrow = 0;
+    const int64_t n_edged = std::max(a.n_wide, std::min(a.n_rows, a.n_touched));
+    // Where many sources have no edge (a 16-way split leaves 46% of them without one), their 32-byte
+    // rows of dt_q scattered through the array cost more to zero one by one than the whole array
+    // does in one sweep ahead of the kernels that write the other rows.
+    const bool sweep_dt = a.n_src_host != nullptr && (a.n_rows - n_edged) * 4 > a.n_rows;
     timing_mark(0, st);
+    if (sweep_dt) {
+        for (int q = 0; q < a.n_blocks; ++q) {
+            const int64_t n = a.n_src_host[q] * a.H;
+            if (n == 0 || !tabs.dt[q]) continue;
+            k_zero_f32<<<(unsigned)std::min<int64_t>((n + 255) / 256, kMaxPersistentWGs), 256, 0, st>>>(tabs.dt[q], n);
+            SAR_LAUNCH_CHECK();
+        }
+    }
     if (a.n_wide > 0) {
         // sources with at least 8 edges: one wavefront (or workgroup) each
         g_wide = persistent_grid_for(p.n_rows, p.n_long, resident_wide);
@@ -944,11 +991,18 @@ int launch_bwd_f256(const BwdArgs& tabs, const BwdScalars& a, unsigned* grid_out
         SAR_LAUNCH_CHECK();
     }
     timing_mark(1, st);
-    if (a.n_rows > a.n_wide) {
-        // the rest, four per wavefront
-        const int64_t n = a.n_rows - a.n_wide;
+    if (n_edged > a.n_wide) {
+        // the other sources with edges, four per wavefront
+        const int64_t n = n_edged - a.n_wide;
         g_narrow = (unsigned)std::max<int64_t>(1, std::min<int64_t>((n + 15) / 16, resident_narrow));
-        narrow<<<g_narrow, kGatherThreads, 0, st>>>(t, p, a.n_wide, a.n_rows, (int)g_wide);
+        narrow<<<g_narrow, kGatherThreads, 0, st>>>(t, p, a.n_wide, n_edged, (int)g_wide);
+        SAR_LAUNCH_CHECK();
+    }
+    if (a.n_rows > n_edged) {
+        const int64_t pieces = (a.n_rows - n_edged) * (f256::kF * (int64_t)sizeof(T) / 16);
+        const unsigned g_zero = (unsigned)std::min<int64_t>((pieces + 255) / 256, kMaxPersistentWGs);
+        k_bwd_zero_rows<T, ALL><<<g_zero, 256, 0, st>>>(t, a.rows, n_edged, a.n_rows, sweep_dt ? 0 : a.H,
+                                                       a.tag_shift);
         SAR_LAUNCH_CHECK();
     }
     timing_mark(2, st);
@@ -1263,6 +1317,9 @@ extern "C" int sar_gat_bwd_block(const sar_blocks_t* b, int q, const void* Zq, c
         a.n_rows = (b->flags & SAR_BUILD_SKIP_UNTOUCHED) ? k.n_t_rows : k.n_src;
         a.n_long = k.n_t_long;
         a.n_wide = dtype == SAR_F32 ? k.n_t_wide_f32 : k.n_t_wide;
+        a.n_touched = k.n_t_rows;
+        a.n_src_host = &k.n_src;
+        a.n_blocks = 1;
         fill_bwd_group(a, hg, g, H, D, G, rec, a_l, ds, work, slope);
         if (dtype == SAR_F32)
             SAR_TRY((launch_bwd<float, false>(tabs, a, da_l + f0, st)));
@@ -1286,6 +1343,8 @@ extern "C" int sar_gat_bwd_all(const sar_blocks_t* b, const void* const* Zq, con
         SAR_CHECK_ARG(aligned16(Zq[q]) && aligned16(dZq[q]), "Zq[%d] and dZq[%d] must be 16-byte aligned", q, q);
     }
     const HeadGroups hg = head_groups(dtype, H, D);
+    int64_t n_src_all[SAR_MAX_BLOCKS];
+    for (int q = 0; q < b->P; ++q) n_src_all[q] = b->blk[q].n_src;
     for (int g = 0; g < hg.n; ++g) {
         const size_t f0 = (size_t)g * hg.Fg, h0 = (size_t)g * hg.Hg;
         BwdArgs tabs{};
@@ -1305,6 +1364,9 @@ extern "C" int sar_gat_bwd_all(const sar_blocks_t* b, const void* const* Zq, con
         for (int q = 0; q < b->P; ++q) a.n_rows += b->blk[q].n_src;
         if (b->flags & SAR_BUILD_SKIP_UNTOUCHED) a.n_rows = b->n_ft_rows;
         a.n_wide = dtype == SAR_F32 ? b->n_ft_wide_f32 : b->n_ft_wide;
+        a.n_touched = b->n_ft_rows;
+        a.n_src_host = n_src_all;
+        a.n_blocks = b->P;
         a.n_long = b->n_ft_long;
         a.tag_shift = b->tag_shift;
         fill_bwd_group(a, hg, g, H, D, G, rec, a_l, ds, work, slope);
