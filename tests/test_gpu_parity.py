@@ -429,3 +429,24 @@ def test_error_paths():
     b.close()
     with pytest.raises(sar.SarError):
         b.handle
+
+
+@pytest.mark.parametrize("dtype,H,D", [(torch.float32, 4, 64), (torch.bfloat16, 8, 32)])
+@pytest.mark.parametrize("batched", [False, True])
+def test_gat_backward_sources_without_edges(dtype, H, D, batched):
+    """Most sources have no edge in their block (a sparse block of a many-way split): their rows of
+    dZ_q and dt_q must come back as zeros (the buffers start as NaN), the others as usual."""
+    b, want_b, deg, Zdst, Zs, a_l, a_r, G = gat_case(21, 6000, 3000, 3, 1, H, D, dtype, simple=False)
+    empty = [np.diff(w.t_indptr) == 0 for w in want_b]
+    assert all(e.mean() > 0.5 for e in empty)
+    wf = orc.gat_fwd(want_b, f64(Zdst), [f64(z) for z in Zs], f64(a_l), f64(a_r), SLOPE)
+    wb = orc.gat_bwd(want_b, f64(Zdst), [f64(z) for z in Zs], f64(G), f64(a_l), f64(a_r), SLOPE, wf)
+    fw = gu.gat_fwd_all(b, Zdst, Zs, a_l, a_r, SLOPE)
+    g = gu.gat_bwd(b, Zdst, Zs, G, a_l, a_r, SLOPE, fw, batched, fly=True)
+    for q in range(b.P):
+        assert torch.all(g.dZs[q][torch.from_numpy(empty[q]).cuda()] == 0)
+        assert torch.all(g.dts[q][torch.from_numpy(empty[q]).cuda()] == 0)
+        assert rel_err(f64(g.dZs[q]), wb.dZs[q]) < TOL[dtype], q
+        assert rel_err(f64(g.dts[q]), wb.dt[q]) < TOL[dtype], q
+    assert rel_err(f64(g.da_l), wb.da_l) < TOL[dtype]
+    b.close()
