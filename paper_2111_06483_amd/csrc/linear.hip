@@ -364,8 +364,8 @@ struct SkinnyArgs {
     float* s1;         // [M, H] or null
     float* s2;
     int H, D;
-    // 2-byte outputs: byte offset in LDS of the per-wavefront 32 x 32 staging tiles through
-    // which they are stored as whole 64-byte row segments, or 0 to store element-wise
+    // byte offset in LDS of the per-wavefront 32 x 32 staging tiles through which the outputs
+    // are stored as whole 64- or 128-byte row segments, or 0 to store element-wise
     int stage_off;
 };
 
