@@ -260,6 +260,45 @@ def measure_ceilings(torch, sar, row_bytes):
                     "uniform-random over a 2 GiB table" % row_bytes}
 
 
+def measure_transform(layer, reps=20):
+    """The three products of Eq. 1 / Alg. 2 for the worker's own rows, each timed alone with
+    events on the launch stream (after the timed steps): useful flops 2 n K F against the MFMA
+    peak of the row type, operand bytes against the HBM peak."""
+    torch, sar, w = layer.torch, layer.sar, layer.w
+    n, K, F = layer.Xd.shape[0], w.f_in, layer.F
+    fb = 2 if w.dtype == torch.bfloat16 else 4
+    peak = 2500.0 if w.dtype == torch.bfloat16 else 157.3        # dense MFMA TFLOP/s
+    dW = torch.zeros_like(layer.dW)
+    calls = {
+        "Z = X W with both score projections": (
+            lambda: sar.sar_linear_fwd(layer.Xd, layer.W, layer.Zp.reshape(n, F), layer.a_r, layer.s,
+                                       layer.a_l, layer.tp),
+            n * (K + F) * fb + 2 * n * layer.H * 4),
+        "dX = dZ W^T": (lambda: sar.sar_linear_bwd(None, layer.dZdst, layer.W, None, layer.dX_dst, None),
+                        n * (K + F) * fb),
+        "dW += X^T dZ": (lambda: sar.sar_linear_bwd(layer.Xd, layer.dZdst, None, dW, None, layer.lwork),
+                         n * (K + F) * fb),
+    }
+    out = {}
+    for name, (fn, nbytes) in calls.items():
+        fn()
+        fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        tflops = 2.0 * n * K * F / (ms * 1e-3) / 1e12
+        out[name] = {"ms": ms, "useful_TFLOPs": tflops, "frac_of_mfma_peak": tflops / peak,
+                     "operand_GBs": nbytes / (ms * 1e-3) / 1e9, "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 8e12}
+    out["note"] = ("n = %d rows, K = %d, F = %d, %s rows; MFMA peak %.1f TFLOP/s; flop per operand byte %.0f "
+                   "(ridge %.0f at 8 TB/s)" % (n, K, F, "bf16" if fb == 2 else "fp32", peak,
+                                              2.0 * n * K * F / (n * (K + F) * fb), peak * 1e12 / 8e12))
+    return out
+
+
 def cpu_baseline(layer, n_blocks):
     """The oracle, as it stands, on the first n_blocks blocks of the same workload."""
     n_blocks = max(1, min(n_blocks, layer.P))
@@ -534,6 +573,7 @@ def main():
                          d["gather_volume_GBs"] / ceilings["random_row_gather_GBs"],
                      "kernels": per_kernel},
         "ceilings": ceilings,
+        "transform": measure_transform(layer),
     }
     if not args.no_cpu_baseline and not layer.subset:
         res["cpu_baseline"] = cpu_baseline(layer, args.cpu_blocks)
