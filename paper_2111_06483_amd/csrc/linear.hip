@@ -429,6 +429,8 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_gemm_skinny(SkinnyArgs g)
         // (W a)[k][h] = sum_d W[k][h*D + d] a[h][d]: z_h . a_h = x . (W_h a_h), so the scores
         // are 2H more output columns of the same product, taken from the unrounded sums
         __syncthreads();
+        // a head's two score columns belong to the column slab that holds the head's first
+        // column; the other slabs leave them at zero and do not store them
         const int cols = 2 * g.H;
         for (int p = tid; p < g.K * cols; p += kSkinnyThreads) {
             const int k = p / cols, col = p % cols;
@@ -436,14 +438,15 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_gemm_skinny(SkinnyArgs g)
             const float* av = col < g.H ? g.a1 : g.a2;
             const int t = k / kChunk, gk = (k / (kChunk / 2)) & 1, e = k % (kChunk / 2);
             float v = 0.f;
-            if (av) {
-                if (!BF && gridDim.y == 1) {
-                    // row k of W is in LDS already (exact fp32 values, fragment order): 64 strided
-                    // reads of global memory per product would cost more than the whole staging
+            if (av && (h * g.D) / (NT * 32) == (int)blockIdx.y) {
+                if (!BF && (int64_t)(h + 1) * g.D <= n0 + NT * 32) {
+                    // this head's part of row k of W is in LDS already (exact fp32 values, fragment
+                    // order): D strided reads of global memory per product would cost more than
+                    // the whole staging
                     const float* wk = reinterpret_cast<const float*>(frag) + ((size_t)t * NA * 64 + gk * 32) * 4 + e;
                     for (int d = 0; d < g.D; ++d) {
-                        const int n = h * g.D + d;
-                        v = fmaf(wk[((n >> 5) * 64 + (n & 31)) * 4], av[n], v);
+                        const int n = h * g.D + d - (int)n0;
+                        v = fmaf(wk[((n >> 5) * 64 + (n & 31)) * 4], av[h * g.D + d], v);
                     }
                 } else {
                     const float* wrow = g.B + (int64_t)k * g.sbk + (int64_t)h * g.D * g.sbn;
@@ -616,10 +619,10 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_gemm_skinny(SkinnyArgs g)
                 }
             }
         }
-        if (SC && blockIdx.y == 0 && c < 2 * g.H) {
+        if (SC && c < 2 * g.H) {
             float* dst = c < g.H ? g.s1 : g.s2;
             const int h = c < g.H ? c : c - g.H;
-            if (dst) {
+            if (dst && (h * g.D) / (NT * 32) == (int)blockIdx.y) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int64_t i = row0 + 8 * (r / 4) + 4 * gq + (r % 4);

@@ -344,7 +344,9 @@ def test_linear_parity(dtype, n, K, F):
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("n,K,H,D", [(1500, 100, 4, 64), (700, 128, 8, 32), (333, 64, 1, 256), (260, 40, 2, 100),
-                                     (90, 30, 3, 24), (300, 64, 20, 8), (500, 602, 4, 16)])
+                                     (90, 30, 3, 24), (300, 64, 20, 8), (500, 602, 4, 16),
+                                     # two column slabs: heads inside a slab, and a head across the boundary
+                                     (700, 256, 8, 32), (300, 256, 2, 104), (300, 256, 3, 88)])
 def test_linear_scores_parity(dtype, n, K, H, D):
     """The two score projections of Eq. 3 that come out of the transform: s = a1 . z and
     t = a2 . z per head, against the oracle's scores of its own fp64 Z = X W."""
