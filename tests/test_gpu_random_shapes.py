@@ -16,6 +16,7 @@ import torch
 
 from oracle import sar_oracle as orc
 from tests.helpers import rel_err
+from tests.test_gpu_fullsize import kink_rows
 from tests.test_gpu_parity import TOL, SLOPE, check_fwd, f64, feats, make_graph
 
 pytestmark = pytest.mark.gpu
@@ -113,14 +114,19 @@ def test_random_shape(case):
         wf = dataclasses.replace(wf, out=torch.from_numpy(wf.out).to(torch.bfloat16).to(torch.float64).numpy())
     wb = orc.gat_bwd(want_b, f64(Zdst), Z64, f64(G), f64(a_l), f64(a_r), SLOPE, wf)
     g = gu.gat_bwd(b, Zdst, Zs, G, a_l, a_r, SLOPE, fa, o["batched"], fly=o["fly"])
+    # An edge whose LeakyReLU argument is within rounding of zero may take either slope: its
+    # destination's and source's score gradients then differ by a whole term (about one edge in
+    # 10^7 at these sizes); such rows, found from the oracle's values alone, are left out.
+    bad_dst, bad_src = kink_rows(want_b, wf.s, wf.t)
     for q in range(P):
-        t = touched[q]
+        t = touched[q] & ~bad_src[q]
         assert rel_err(f64(g.dZs[q])[t], wb.dZs[q][t]) < tol, q
         assert close(f64(g.dts[q])[t], wb.dt[q][t], tol, np.sqrt(D)), q
     # ds sums alpha (c - delta) du/de over a destination's edges: terms of size ~sqrt(D) that cancel
     # exactly when all its edges sit on one side of the LeakyReLU (always so with one edge).
-    assert close(g.ds, wb.ds, tol, np.sqrt(D))
-    assert close(g.dZdst, wb.dZdst, tol, np.sqrt(D) * bound)
+    ok = ~bad_dst
+    assert close(f64(g.ds)[ok], wb.ds[ok], tol, np.sqrt(D))
+    assert close(f64(g.dZdst)[ok], wb.dZdst[ok], tol, np.sqrt(D) * bound)
     assert close(g.da_r, wb.da_r, tol, np.sqrt(D))
     assert close(g.da_l, wb.da_l, tol, np.sqrt(D))
 
