@@ -29,12 +29,7 @@ constexpr int kPerThread = BM * BK / kGemmThreads / 4;   // 4-element groups eac
 
 typedef float float16_t __attribute__((ext_vector_type(16)));
 
-template <typename T>
-__device__ inline float to_f32(T v);
-template <>
-__device__ inline float to_f32<float>(float v) { return v; }
-template <>
-__device__ inline float to_f32<bf16_t>(bf16_t v) { return __uint_as_float((uint32_t)v.bits << 16); }
+__device__ inline float bf16_to_f32(bf16_t v) { return __uint_as_float((uint32_t)v.bits << 16); }
 
 template <typename T>
 __device__ inline T from_f32(float v);
@@ -68,7 +63,7 @@ __device__ inline void load4<bf16_t>(const bf16_t* p, bool vec, int n_valid, flo
         v[3] = __uint_as_float(x.y & 0xffff0000u);
     } else {
 #pragma unroll
-        for (int k = 0; k < 4; ++k) v[k] = k < n_valid ? to_f32<bf16_t>(p[k]) : 0.f;
+        for (int k = 0; k < 4; ++k) v[k] = k < n_valid ? bf16_to_f32(p[k]) : 0.f;
     }
 }
 
