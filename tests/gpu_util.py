@@ -7,7 +7,7 @@ results back as numpy arrays.
 from __future__ import annotations
 
 from dataclasses import dataclass
-from typing import List, Optional, Sequence
+from typing import List, Sequence
 
 import numpy as np
 import torch
