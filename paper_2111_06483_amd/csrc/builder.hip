@@ -423,20 +423,18 @@ ClassLayout layout_from_hist(const int* hist, int64_t offset)
 // --------------------------------------------------- transpose of a block
 
 // One wavefront per listed destination row.
-__global__ __launch_bounds__(kThreads) void k_t_count(const int32_t* __restrict__ indptr,
-                                                      const int32_t* __restrict__ indices,
-                                                      const uint32_t* __restrict__ rows,
-                                                      int64_t n_rows, int32_t* __restrict__ col_cnt)
+// col_cnt[j] = number of edges of the block whose source is j: one thread per edge
+__global__ __launch_bounds__(kThreads) void k_t_count(const int32_t* __restrict__ indices, int64_t nnz,
+                                                      int32_t* __restrict__ col_cnt)
 {
-    const int lane = threadIdx.x & 63;
-    for (int64_t w = ((int64_t)blockIdx.x * kThreads + threadIdx.x) >> 6; w < n_rows;
-         w += ((int64_t)gridDim.x * kThreads) >> 6) {
-        const int i = (int)rows[w];
-        const int beg = indptr[i], end = indptr[i + 1];
-        for (int e = beg + lane; e < end; e += 64) atomicAdd(&col_cnt[indices[e]], 1);
-    }
+    for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < nnz; e += (int64_t)gridDim.x * kThreads)
+        atomicAdd(&col_cnt[indices[e]], 1);
 }
 
+// Destination i of every edge goes into its source's slot range.  LANES lanes share a row of the
+// launch list: a whole wavefront for the rows of at least 8 edges at the head of the list, 8 lanes
+// for the short rows behind them (most rows of a P-way split have a handful of edges per block).
+template <int LANES>
 __global__ __launch_bounds__(kThreads) void k_t_scatter(const int32_t* __restrict__ indptr,
                                                         const int32_t* __restrict__ indices,
                                                         const uint32_t* __restrict__ rows,
@@ -444,12 +442,12 @@ __global__ __launch_bounds__(kThreads) void k_t_scatter(const int32_t* __restric
                                                         const int32_t* __restrict__ col_off,
                                                         int32_t* __restrict__ t_indices_all)
 {
-    const int lane = threadIdx.x & 63;
-    for (int64_t w = ((int64_t)blockIdx.x * kThreads + threadIdx.x) >> 6; w < n_rows;
-         w += ((int64_t)gridDim.x * kThreads) >> 6) {
+    const int lane = threadIdx.x & (LANES - 1);
+    for (int64_t w = ((int64_t)blockIdx.x * kThreads + threadIdx.x) / LANES; w < n_rows;
+         w += ((int64_t)gridDim.x * kThreads) / LANES) {
         const int i = (int)rows[w];
         const int beg = indptr[i], end = indptr[i + 1];
-        for (int e = beg + lane; e < end; e += 64) {
+        for (int e = beg + lane; e < end; e += LANES) {
             const int j = indices[e];
             const int pos = atomicSub(&col_cnt[j], 1) - 1;
             t_indices_all[(int64_t)col_off[j] + pos] = i;
@@ -502,22 +500,32 @@ __global__ __launch_bounds__(kThreads) void k_total_degree(PtrTable t, int P, in
     }
 }
 
-__global__ __launch_bounds__(kThreads) void k_fused_copy(PtrTable t, int q,
-                                                         const int32_t* __restrict__ indices,
-                                                         const uint32_t* __restrict__ rows,
-                                                         int64_t n_rows,
-                                                         const int32_t* __restrict__ f_indptr,
-                                                         uint32_t tag, uint32_t* __restrict__ f_indices)
+struct IdxTable {
+    const int32_t* indices[SAR_MAX_BLOCKS];
+};
+
+// Row i of the all-blocks index: its sources block after block, tagged with the block.  A
+// wavefront takes a row: lane q reads block q's range of the row, then the blocks are copied
+// in turn (8 lanes per block range when the blocks are many and the ranges short).
+__global__ __launch_bounds__(kThreads) void k_fused_copy(PtrTable t, IdxTable x, int P, int64_t n_dst,
+                                                         const int32_t* __restrict__ f_indptr, int tag_shift,
+                                                         uint32_t* __restrict__ f_indices)
 {
     const int lane = threadIdx.x & 63;
-    for (int64_t w = ((int64_t)blockIdx.x * kThreads + threadIdx.x) >> 6; w < n_rows;
-         w += ((int64_t)gridDim.x * kThreads) >> 6) {
-        const int i = (int)rows[w];
-        int64_t dstpos = f_indptr[i];
-        for (int k = 0; k < q; ++k) dstpos += t.indptr[k][i + 1] - t.indptr[k][i];
-        const int beg = t.indptr[q][i], end = t.indptr[q][i + 1];
-        for (int e = beg + lane; e < end; e += 64)
-            f_indices[dstpos + (e - beg)] = (uint32_t)indices[e] | tag;
+    for (int64_t i = ((int64_t)blockIdx.x * kThreads + threadIdx.x) >> 6; i < n_dst;
+         i += ((int64_t)gridDim.x * kThreads) >> 6) {
+        int beg = 0, len = 0;
+        if (lane < P) {
+            beg = t.indptr[lane][i];
+            len = t.indptr[lane][i + 1] - beg;
+        }
+        int64_t pos = f_indptr[i];
+        for (int q = 0; q < P; ++q) {
+            const int b = __shfl(beg, q), n = __shfl(len, q);
+            for (int e = lane; e < n; e += 64)
+                f_indices[pos + e] = (uint32_t)x.indices[q][b + e] | ((uint32_t)q << tag_shift);
+            pos += n;
+        }
     }
 }
 
@@ -603,6 +611,7 @@ int derive(sar_blocks* h, hipStream_t st)
         ClassLayout L = layout_from_hist(&hist[q * sar::kNumClasses], 0);
         h->blk[q].n_rows = L.n_rows;
         h->blk[q].n_long = L.n_long;
+        h->blk[q].n_rows_wide = L.n_wide;
         memcpy(&cursors[q * sar::kNumClasses], L.start, sizeof(L.start));
         rows_base[q] = rows_total;
         rows_total += L.n_rows;
@@ -627,11 +636,12 @@ int derive(sar_blocks* h, hipStream_t st)
         SAR_TRY(own(h, &h->f_indptr, n_dst + 1));
         SAR_TRY(exclusive_scan(h->deg, h->f_indptr, n_dst + 1, st, tmp));
         SAR_TRY(own(h, &h->f_indices, nnz_total));
-        for (int q = 0; q < P; ++q) {
-            if (h->blk[q].n_rows == 0) continue;
-            k_fused_copy<<<grid_for(h->blk[q].n_rows * 64), kThreads, 0, st>>>(
-                tab, q, h->blk[q].indices, reinterpret_cast<const uint32_t*>(h->blk[q].rows),
-                h->blk[q].n_rows, h->f_indptr, (uint32_t)q << h->tag_shift, h->f_indices);
+        {
+            IdxTable idx;
+            memset(&idx, 0, sizeof(idx));
+            for (int q = 0; q < P; ++q) idx.indices[q] = h->blk[q].indices;
+            k_fused_copy<<<grid_for(n_dst * 64), kThreads, 0, st>>>(tab, idx, P, n_dst, h->f_indptr, h->tag_shift,
+                                                                    h->f_indices);
             SAR_LAUNCH_CHECK();
         }
         int* fh = hist_d + P * sar::kNumClasses;
@@ -667,8 +677,7 @@ int derive(sar_blocks* h, hipStream_t st)
         for (int q = 0; q < P; ++q) {
             const Block& b = h->blk[q];
             if (b.n_rows == 0) continue;
-            k_t_count<<<grid_for(b.n_rows * 64), kThreads, 0, st>>>(
-                b.indptr, b.indices, reinterpret_cast<const uint32_t*>(b.rows), b.n_rows, col_cnt + coff[q]);
+            k_t_count<<<grid_for(b.nnz, kThreads, 1 << 16), kThreads, 0, st>>>(b.indices, b.nnz, col_cnt + coff[q]);
             SAR_LAUNCH_CHECK();
         }
         SAR_TRY(exclusive_scan(col_cnt, col_off, n_src_total + 1, st, tmp));
@@ -676,10 +685,18 @@ int derive(sar_blocks* h, hipStream_t st)
         for (int q = 0; q < P; ++q) {
             const Block& b = h->blk[q];
             if (b.n_rows == 0) continue;
-            k_t_scatter<<<grid_for(b.n_rows * 64), kThreads, 0, st>>>(
-                b.indptr, b.indices, reinterpret_cast<const uint32_t*>(b.rows), b.n_rows, col_cnt + coff[q],
-                col_off + coff[q], t_indices_all);
-            SAR_LAUNCH_CHECK();
+            const uint32_t* rows = reinterpret_cast<const uint32_t*>(b.rows);
+            if (b.n_rows_wide > 0) {
+                k_t_scatter<64><<<grid_for(b.n_rows_wide * 64), kThreads, 0, st>>>(
+                    b.indptr, b.indices, rows, b.n_rows_wide, col_cnt + coff[q], col_off + coff[q], t_indices_all);
+                SAR_LAUNCH_CHECK();
+            }
+            if (b.n_rows > b.n_rows_wide) {
+                k_t_scatter<8><<<grid_for((b.n_rows - b.n_rows_wide) * 8), kThreads, 0, st>>>(
+                    b.indptr, b.indices, rows + b.n_rows_wide, b.n_rows - b.n_rows_wide, col_cnt + coff[q],
+                    col_off + coff[q], t_indices_all);
+                SAR_LAUNCH_CHECK();
+            }
         }
         SAR_TRY(sort_rows(col_off, n_src_total, t_indices_all, nnz_total, st, tmp));
 

@@ -58,6 +58,7 @@ struct Block {
     int32_t* rows = nullptr;
     int64_t n_rows = 0, n_long = 0;
     int32_t* t_rows = nullptr;
+    int64_t n_rows_wide = 0;                             // destination rows with >= 8 edges (head of `rows`)
     int64_t n_t_rows = 0, n_t_long = 0, n_t_wide = 0;   // n_t_wide: sources with >= 8 edges
     int64_t n_t_wide_f32 = 0;                            // sources with >= 4 edges
     int32_t* touched = nullptr;
