@@ -53,6 +53,8 @@ def parse():
                     help="storage type of the feature rows; 'config' keeps what the configuration names "
                          "(the headline, config 3, is fp32); accumulation is fp32 either way")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-transform", action="store_true",
+                    help="skip the separate timing of the three transform products after the timed steps")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this size (to scale rocprofv3's FETCH_SIZE/WRITE_SIZE)")
     ap.add_argument("--cpu-blocks", type=int, default=8,
@@ -573,8 +575,9 @@ def main():
                          d["gather_volume_GBs"] / ceilings["random_row_gather_GBs"],
                      "kernels": per_kernel},
         "ceilings": ceilings,
-        "transform": measure_transform(layer),
     }
+    if not args.no_transform:
+        res["transform"] = measure_transform(layer)
     if not args.no_cpu_baseline and not layer.subset:
         res["cpu_baseline"] = cpu_baseline(layer, args.cpu_blocks)
     print(json.dumps(res))
