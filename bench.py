@@ -569,6 +569,9 @@ def main():
                      "achieved": d["alg_GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": d["alg_GBs"] / HBM_PEAK_GBS,
                      "traffic": d["traffic_bytes"],
+                     # what actually crossed the L2 boundary per second, as a share of the same peak
+                     "traffic_frac": (d["traffic_bytes"] / (d["avg_ms"] / launches * 1e-3) / 1e9 / HBM_PEAK_GBS
+                                      if d["traffic_bytes"] else None),
                      "alg_bytes_per_launch": d["alg_bytes"] / launches, "avg_launch_ms": d["avg_ms"] / launches,
                      "gather_volume_GBs": d["gather_volume_GBs"],
                      "gather_volume_vs_measured_gather_ceiling":
