@@ -398,3 +398,29 @@ def test_step_replays_as_a_hip_graph():
         assert torch.equal(got[0], want[0]) and torch.equal(got[1], want[1])     # the forward is reproducible
         layer.step("all")                      # eager work between the replays
         torch.cuda.synchronize()
+
+
+def test_per_relation_means_chain_through_the_residual():
+    """A relational layer (one mean aggregation per edge type, summed: the R-GCN shape of App. A) needs
+    no kernel of its own: each relation is a handle, and the previous relations' sum enters the next
+    aggregation's epilogue as its residual."""
+    P, p, F, R = 3, 2, 64, 3
+    rng = np.random.default_rng(51)
+    part = None
+    total = None
+    acc = None
+    handles = []
+    for r in range(R):
+        src, dst, part_r, _ = make_graph(60 + r, 2000, 9000, P, hubs=(r == 0))
+        if part is None:
+            part = part_r                       # one partition of the nodes for all relations
+        want_b, deg = orc.build_blocks(src, dst, part, P, p)
+        b = gu.build_blocks(src, dst, part, P, p)
+        handles.append(b)
+        Zs = [feats(rng, w.n_src, F, torch.float32) for w in want_b]      # z = W_r h of this relation
+        want_r = orc.spmm(want_b, [f64(z) for z in Zs], True)
+        total = want_r if total is None else total + want_r
+        acc = gu.spmm_all(b, [z.cuda() for z in Zs], True, residual=acc)
+    assert rel_err(f64(acc), total) < 1e-4
+    for b in handles:
+        b.close()
