@@ -89,7 +89,7 @@ typedef struct sar_blocks sar_blocks_t; /* opaque, library-owned */
  *   rows / t_rows       the n_rows rows (resp. n_t_rows sources) that have at
  *                       least one edge in this block, ordered longest-first by
  *                       degree class: the launch order of the kernels.  The
- *                       first n_long (resp. n_t_long) of them have at least 512
+ *                       first n_long (resp. n_t_long) of them have at least 128
  *                       edges.  The order inside a degree class is unspecified.
  *                       t_rows continues with the n_src - n_t_rows sources that
  *                       have no edge (the backward kernels zero their rows).

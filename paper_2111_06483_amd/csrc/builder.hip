@@ -404,7 +404,7 @@ struct ClassLayout {
     int start[sar::kNumClasses];
 };
 
-ClassLayout layout_from_hist(const int* hist, int64_t offset)
+ClassLayout layout_from_hist(const int* hist, int64_t offset, int long_class)
 {
     ClassLayout L;
     int64_t run = offset;
@@ -412,7 +412,7 @@ ClassLayout layout_from_hist(const int* hist, int64_t offset)
         L.start[c] = (int)run;
         run += hist[c];
         L.n_rows += hist[c];
-        if (c >= sar::kLongClass) L.n_long += hist[c];
+        if (c >= long_class) L.n_long += hist[c];
         if (c > sar::kNarrowMaxClass) L.n_wide += hist[c];
         if (c > sar::kNarrowMaxClassF32) L.n_wide_f32 += hist[c];
     }
@@ -608,7 +608,7 @@ int derive(sar_blocks* h, hipStream_t st)
     int64_t rows_total = 0;
     std::vector<int64_t> rows_base(P);
     for (int q = 0; q < P; ++q) {
-        ClassLayout L = layout_from_hist(&hist[q * sar::kNumClasses], 0);
+        ClassLayout L = layout_from_hist(&hist[q * sar::kNumClasses], 0, sar::kLongClassBlock);
         h->blk[q].n_rows = L.n_rows;
         h->blk[q].n_long = L.n_long;
         h->blk[q].n_rows_wide = L.n_wide;
@@ -651,7 +651,7 @@ int derive(sar_blocks* h, hipStream_t st)
         int fhist[sar::kNumClasses];
         SAR_HIP(hipMemcpyAsync(fhist, fh, sizeof(fhist), hipMemcpyDeviceToHost, st));
         SAR_HIP(hipStreamSynchronize(st));
-        ClassLayout L = layout_from_hist(fhist, 0);
+        ClassLayout L = layout_from_hist(fhist, 0, sar::kLongClass);
         h->n_f_rows = L.n_rows;
         h->n_f_long = L.n_long;
         SAR_TRY(own(h, &h->f_rows, n_dst));
@@ -728,7 +728,7 @@ int derive(sar_blocks* h, hipStream_t st)
         int64_t t_rows_total = 0;
         std::vector<int64_t> t_base(P);
         for (int q = 0; q < P; ++q) {
-            ClassLayout L = layout_from_hist(&hist[q * sar::kNumClasses], 0);
+            ClassLayout L = layout_from_hist(&hist[q * sar::kNumClasses], 0, sar::kLongClassBlock);
             h->blk[q].n_t_rows = L.n_rows;
             h->blk[q].n_t_long = L.n_long;
             h->blk[q].n_t_wide = L.n_wide;
@@ -738,7 +738,7 @@ int derive(sar_blocks* h, hipStream_t st)
             t_rows_total += L.n_rows;
             for (int c = 0; c < sar::kNumClasses; ++c) all_hist[c] += hist[q * sar::kNumClasses + c];
         }
-        ClassLayout LA = layout_from_hist(all_hist, 0);
+        ClassLayout LA = layout_from_hist(all_hist, 0, sar::kLongClass);
         h->n_ft_rows = LA.n_rows;
         h->n_ft_long = LA.n_long;
         h->n_ft_wide = LA.n_wide;

@@ -304,7 +304,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_fwd_f256(FwdP a, Tabs ta
         }
     };
 
-    // rows of at least kLongRow edges: the four wavefronts share the row
+    // the long rows at the head of the list: the four wavefronts share the row
     for (int64_t r = blockIdx.x; r < a.n_long; r += gridDim.x) {
         const int i = (int)a.rows[r];
         FwdState<LPH> st;

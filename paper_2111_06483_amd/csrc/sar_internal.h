@@ -37,8 +37,14 @@ int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
 // Rows (or sources) with at least this many edges in a block are "long": they
 // are handled by a whole workgroup instead of one wavefront.  A power of two
 // so that it coincides with a degree-class boundary.
+// Rows the four wavefronts of a workgroup share: at least 512 edges in the lists of the all-blocks
+// launches, at least 128 in a block's own lists.  A per-block launch is short (a dozen rows per
+// wavefront), and a single 300-edge row at the head of a wavefront's share then decides when the
+// launch ends; the long all-blocks launches absorb that, and splitting their rows costs merges.
 constexpr int kLongRow = 512;
-constexpr int kLongClass = 10;  // 1 + log2(kLongRow)
+constexpr int kLongClass = 10;       // 1 + log2(kLongRow)
+constexpr int kLongRowBlock = 128;
+constexpr int kLongClassBlock = 8;   // 1 + log2(kLongRowBlock)
 constexpr int kNumClasses = 32;
 // Rows of fewer than 8 edges (degree classes 1..3, and the empty class 0) are
 // "narrow": the backward kernels process four of them per wavefront.

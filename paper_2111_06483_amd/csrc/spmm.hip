@@ -5,7 +5,7 @@
 // All kernels are row gathers bound by HBM/L2 bandwidth: one wavefront owns one
 // output row, reads the listed input rows with 16-byte lane accesses (a 1 KiB
 // row is one wave-wide load), keeps several of them in flight, and adds them
-// in fp32 registers.  Rows at least kLongRow long are shared by the four
+// in fp32 registers.  The long rows at the head of a list are shared by the four
 // wavefronts of a workgroup and merged through LDS.  The grid is persistent:
 // workgroups stride over the degree-ordered row list, longest rows first.
 #include <algorithm>

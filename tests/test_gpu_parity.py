@@ -84,11 +84,11 @@ def test_builder_bit_exact(N, E, P, p, simple, idx_dtype):
         assert sorted(v["rows"].tolist()) == np.flatnonzero(deg_q > 0).tolist()
         cls = np.floor(np.log2(np.maximum(deg_q[v["rows"]], 1))).astype(int)
         assert np.all(np.diff(cls) <= 0)
-        assert v["n_long"] == int(np.sum(deg_q >= 512))
+        assert v["n_long"] == int(np.sum(deg_q >= 128))
         tdeg = np.diff(w.t_indptr)
         assert sorted(v["t_rows"].tolist()) == np.flatnonzero(tdeg > 0).tolist()
         assert np.array_equal(v["touched"], np.flatnonzero(tdeg > 0).astype(np.int32))
-        assert v["n_t_long"] == int(np.sum(tdeg >= 512))
+        assert v["n_t_long"] == int(np.sum(tdeg >= 128))
     b.close()
 
 
