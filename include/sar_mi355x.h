@@ -90,7 +90,8 @@ typedef struct sar_blocks sar_blocks_t; /* opaque, library-owned */
  *                       least one edge in this block, ordered longest-first by
  *                       degree class: the launch order of the kernels.  The
  *                       first n_long (resp. n_t_long) of them have at least 128
- *                       edges.  The order inside a degree class is unspecified.
+ *                       edges (256 or 512 where rows that long are more than a
+ *                       sixteenth of the list).  The order inside a degree class is unspecified.
  *                       t_rows continues with the n_src - n_t_rows sources that
  *                       have no edge (the backward kernels zero their rows).
  *   touched             = t_rows sorted ascending: V_{p,q} intersected with V_q,

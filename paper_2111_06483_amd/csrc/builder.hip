@@ -404,8 +404,25 @@ struct ClassLayout {
     int start[sar::kNumClasses];
 };
 
-ClassLayout layout_from_hist(const int* hist, int64_t offset, int long_class)
+// Degree class from which a list's rows are shared by the four wavefronts of a workgroup: the
+// lowest of 128 / 256 / 512 edges (but not below `floor_class`) that leaves them a small minority
+// of the list.  A skewed list then has no single-wavefront row long enough to decide when a
+// launch ends; a list of uniformly long rows keeps one wavefront per row (no merges).
+int pick_long_class(const int* hist, int floor_class)
 {
+    int64_t n_rows = 0;
+    for (int c = 1; c < sar::kNumClasses; ++c) n_rows += hist[c];
+    for (int lc = floor_class; lc < sar::kLongClass; ++lc) {
+        int64_t n_long = 0;
+        for (int c = lc; c < sar::kNumClasses; ++c) n_long += hist[c];
+        if (n_long <= std::max<int64_t>(256, n_rows / 16)) return lc;
+    }
+    return sar::kLongClass;
+}
+
+ClassLayout layout_from_hist(const int* hist, int64_t offset, int floor_class)
+{
+    const int long_class = pick_long_class(hist, floor_class);
     ClassLayout L;
     int64_t run = offset;
     for (int c = sar::kNumClasses - 1; c >= 1; --c) {
@@ -651,7 +668,7 @@ int derive(sar_blocks* h, hipStream_t st)
         int fhist[sar::kNumClasses];
         SAR_HIP(hipMemcpyAsync(fhist, fh, sizeof(fhist), hipMemcpyDeviceToHost, st));
         SAR_HIP(hipStreamSynchronize(st));
-        ClassLayout L = layout_from_hist(fhist, 0, sar::kLongClass);
+        ClassLayout L = layout_from_hist(fhist, 0, sar::kLongClassBlock);
         h->n_f_rows = L.n_rows;
         h->n_f_long = L.n_long;
         SAR_TRY(own(h, &h->f_rows, n_dst));
@@ -738,7 +755,7 @@ int derive(sar_blocks* h, hipStream_t st)
             t_rows_total += L.n_rows;
             for (int c = 0; c < sar::kNumClasses; ++c) all_hist[c] += hist[q * sar::kNumClasses + c];
         }
-        ClassLayout LA = layout_from_hist(all_hist, 0, sar::kLongClass);
+        ClassLayout LA = layout_from_hist(all_hist, 0, sar::kLongClassBlock);
         h->n_ft_rows = LA.n_rows;
         h->n_ft_long = LA.n_long;
         h->n_ft_wide = LA.n_wide;

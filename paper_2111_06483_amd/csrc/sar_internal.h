@@ -37,10 +37,11 @@ int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
 // Rows (or sources) with at least this many edges in a block are "long": they
 // are handled by a whole workgroup instead of one wavefront.  A power of two
 // so that it coincides with a degree-class boundary.
-// Rows the four wavefronts of a workgroup share: at least 512 edges in the lists of the all-blocks
-// launches, at least 128 in a block's own lists.  A per-block launch is short (a dozen rows per
-// wavefront), and a single 300-edge row at the head of a wavefront's share then decides when the
-// launch ends; the long all-blocks launches absorb that, and splitting their rows costs merges.
+// Rows the four wavefronts of a workgroup share: those of at least 128, 256 or 512 edges, the
+// lowest of the three that leaves them a small minority of their list (chosen per list when it
+// is built).  A 300-edge row at the head of one wavefront's share otherwise decides when a
+// launch ends (a per-block launch is a dozen rows per wavefront); where nearly all rows are that
+// long there is nothing to balance, and sharing them would only add merges.
 constexpr int kLongRow = 512;
 constexpr int kLongClass = 10;       // 1 + log2(kLongRow)
 constexpr int kLongRowBlock = 128;
