@@ -218,10 +218,10 @@ class Layer:
 # rocprofv3 counter summary kept under profiles/: 2 x FETCH_SIZE + WRITE_SIZE (KiB), the factor 2
 # being what FETCH_SIZE reads short on a plain 1 GiB copy.
 MEASURED_TRAFFIC = {
-    ("cfg3", "all", "gat_fwd"): (2 * 7.378e6 + 3.161e5) * 1024,
-    ("cfg3", "all", "gat_bwd_wide"): (2 * 6.401e6 + 1.234e6) * 1024,
+    ("cfg3", "all", "gat_fwd"): (2 * 7.376e6 + 3.162e5) * 1024,
+    ("cfg3", "all", "gat_bwd_wide"): (2 * 6.408e6 + 1.235e6) * 1024,
     # the narrow kernel and the fill of the rows of the sources without an edge (timed together)
-    ("cfg3", "all", "gat_bwd_narrow"): (2 * 1.931e6 + 1.432e6 + 2 * 5161 + 3.372e5) * 1024,
+    ("cfg3", "all", "gat_bwd_narrow"): (2 * 1.931e6 + 1.433e6 + 2 * 5161 + 3.372e5) * 1024,
 }
 KERNEL_NAMES = {"gat_fwd": "k_gat_fwd_f256", "gat_bwd_wide": "k_gat_bwd_f256",
                 "gat_bwd_narrow": "k_gat_bwd_narrow + k_bwd_zero_rows"}
