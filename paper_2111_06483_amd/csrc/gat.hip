@@ -1261,7 +1261,9 @@ int bwd_common_checks(const sar_blocks_t* b, int dtype, int H, int D, const void
     SAR_TRY(check_shape(dtype, H, D));
     if (!(b->flags & SAR_BUILD_TRANSPOSE))
         return sar::fail(SAR_ERR_STATE, "handle was built without SAR_BUILD_TRANSPOSE");
-    SAR_CHECK_ARG(G && rec && a_l && ds && da_l, "a tensor argument is null");
+    // with no destination at all the destination-side tensors have no element (and may be null):
+    // the sources still get their zero rows
+    SAR_CHECK_ARG(a_l && da_l && (b->n_dst == 0 || (G && rec && ds)), "a tensor argument is null");
     SAR_CHECK_ARG(aligned16(G) && aligned16(rec) && aligned16(a_l), "G, rec and a_l must be 16-byte aligned");
     SAR_CHECK_ARG(work != nullptr && aligned16(work), "work is null or not 16-byte aligned");
     const size_t need = workspace_bytes(256);

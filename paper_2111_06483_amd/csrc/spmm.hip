@@ -512,7 +512,7 @@ extern "C" int sar_spmm_bwd_block(const sar_blocks_t* b, int q, const void* G, i
     const sar::Block& k = b->blk[q];
     if (!k.t_indptr) return sar::fail(SAR_ERR_STATE, "handle was built without SAR_BUILD_TRANSPOSE");
     if (k.n_src == 0) return SAR_OK;
-    SAR_CHECK_ARG(G && dZq, "G or dZq is null");
+    SAR_CHECK_ARG((G || b->n_dst == 0) && dZq, "G or dZq is null");
     SAR_CHECK_ARG(aligned16(G) && aligned16(dZq), "G and dZq must be 16-byte aligned");
     hipStream_t st = sar::as_stream(stream);
     SpmmArgs a{};
@@ -549,7 +549,7 @@ extern "C" int sar_spmm_bwd_all(const sar_blocks_t* b, const void* G, int mean, 
     int64_t n_src_total = 0;
     for (int q = 0; q < b->P; ++q) n_src_total += b->blk[q].n_src;
     if (n_src_total == 0) return SAR_OK;
-    SAR_CHECK_ARG(G && dZq, "G or dZq is null");
+    SAR_CHECK_ARG((G || b->n_dst == 0) && dZq, "G or dZq is null");
     SAR_CHECK_ARG(aligned16(G), "G must be 16-byte aligned");
     for (int q = 0; q < b->P; ++q) {
         if (b->blk[q].n_src == 0) continue;

@@ -462,3 +462,67 @@ def test_gat_backward_sources_without_edges(dtype, H, D, batched):
         assert rel_err(f64(g.dts[q]), wb.dt[q]) < TOL[dtype], q
     assert rel_err(f64(g.da_l), wb.da_l) < TOL[dtype]
     b.close()
+
+
+DEGENERATE = {
+    "no edges": lambda rng, N, part: ([], [], part, 3, 1),
+    "empty destination partition": lambda rng, N, part: (rng.integers(0, N, 200), rng.integers(0, N, 200),
+                                                         np.where(part == 1, 0, part), 3, 1),
+    "empty source partition": lambda rng, N, part: (rng.integers(0, N, 200), rng.integers(0, N, 200),
+                                                    np.where(part == 1, 0, part), 3, 0),
+    "single node with a self loop": lambda rng, N, part: ([0], [0], [0], 1, 0),
+    "single node without an edge": lambda rng, N, part: ([], [], [0], 1, 0),
+    "all edges into one destination": lambda rng, N, part: (rng.integers(0, N, 3000), np.full(3000, 7),
+                                                            np.zeros(N, np.int32), 1, 0),
+    "all edges out of one source": lambda rng, N, part: (np.full(3000, 7), rng.integers(0, N, 3000),
+                                                         np.zeros(N, np.int32), 1, 0),
+}
+
+
+@pytest.mark.parametrize("case", sorted(DEGENERATE))
+def test_degenerate_inputs(case):
+    """The degenerate cases the method has: nothing to aggregate, nobody to aggregate for, nobody to
+    aggregate from, one node, one row that holds every edge.  Tensors without elements are passed
+    as they are (null pointers); every call succeeds and agrees with the oracle."""
+    rng = np.random.default_rng(3)
+    N, H, D = 50, 4, 64
+    F = H * D
+    part = rng.integers(0, 3, N)
+    part[:3] = [0, 1, 2]
+    src, dst, part, P, p = DEGENERATE[case](rng, N, part)
+    src, dst, part = np.asarray(src, np.int64), np.asarray(dst, np.int64), np.asarray(part, np.int32)
+    want_b, deg = orc.build_blocks(src, dst, part, P, p)
+    b = gu.build_blocks(src, dst, part, P, p)
+    assert b.n_dst == want_b[0].n_dst
+    for q in range(P):
+        v = gu.view_arrays(b, q)
+        assert v["nnz"] == want_b[q].nnz and v["n_src"] == want_b[q].n_src
+    Zs = [feats(rng, w.n_src, F, torch.float32).cuda().reshape(-1, H, D) for w in want_b]
+    Zdst = feats(rng, b.n_dst, F, torch.float32).cuda().reshape(-1, H, D)
+    a_l = torch.from_numpy(rng.uniform(-0.3, 0.3, (H, D)).astype(np.float32)).cuda()
+    a_r = torch.from_numpy(rng.uniform(-0.3, 0.3, (H, D)).astype(np.float32)).cuda()
+    G = feats(rng, b.n_dst, F, torch.float32).cuda().reshape(-1, H, D)
+    Z2, G2 = [z.reshape(-1, F) for z in Zs], G.reshape(-1, F)
+    close = lambda got, want: np.allclose(f64(got), want, rtol=0, atol=1e-4 * max(1.0, np.abs(want).max(initial=0)))
+
+    want = orc.spmm(want_b, [f64(z) for z in Z2], True)
+    assert close(gu.spmm_all(b, Z2, True), want) and close(gu.spmm_stream(b, Z2, True), want)
+    want_d = orc.spmm_bwd(want_b, f64(G2), True)
+    d_all = [torch.full_like(z, float("nan")) for z in Z2]
+    sar.sar_spmm_bwd_all(b, G2, True, d_all)
+    for q in range(P):
+        d_blk = torch.full_like(Z2[q], float("nan"))
+        sar.sar_spmm_bwd_block(b, q, G2, True, d_blk)
+        assert close(d_all[q], want_d[q]) and close(d_blk, want_d[q])
+
+    wf = orc.gat_fwd(want_b, f64(Zdst), [f64(z) for z in Zs], f64(a_l), f64(a_r), SLOPE)
+    wb = orc.gat_bwd(want_b, f64(Zdst), [f64(z) for z in Zs], f64(G), f64(a_l), f64(a_r), SLOPE, wf)
+    for batched in (False, True):
+        fw = (gu.gat_fwd_all if batched else gu.gat_fwd_stream)(b, Zdst, Zs, a_l, a_r, SLOPE, fly=True)
+        assert close(fw.out, wf.out)
+        g = gu.gat_bwd(b, Zdst, Zs, G, a_l, a_r, SLOPE, fw, batched, fly=True)
+        for q in range(P):
+            assert close(g.dZs[q], wb.dZs[q]) and close(g.dts[q], wb.dt[q])
+        assert close(g.dZdst, wb.dZdst) and close(g.ds, wb.ds)
+        assert close(g.da_l, wb.da_l) and close(g.da_r, wb.da_r)
+    b.close()
