@@ -38,6 +38,8 @@
  *     Anything else returns SAR_ERR_UNSUPPORTED.
  *   - A destination with no in-edge at all has out = 0 and L = -inf, and
  *     contributes nothing to any gradient; the mean of an empty set is 0.
+ *     A tensor without elements (n_dst = 0, or a block without sources) may be
+ *     passed as NULL; the backward calls still write the zero rows of dZ_q.
  *   - A repeated edge counts with its multiplicity (one softmax term / one
  *     summand / one unit of degree per copy).
  */
