@@ -123,9 +123,11 @@ class Layer:
         self.dZs = [torch.zeros_like(z) for z in self.Zs]     # zeroed once: skipped rows stay zero
         self.dts = [torch.zeros((z.shape[0], H), **f32) for z in self.Zs]
         self.dZdst = torch.empty((n, H, D), dtype=w.dtype, device=dev)
-        self.da_l = torch.zeros((H, D), **f32)
-        self.da_r = torch.zeros((H, D), **f32)
-        self.dW = torch.zeros_like(self.W)
+        # the parameter gradients accumulate over blocks and calls: one buffer, zeroed by one fill per step
+        self.grads = torch.zeros(2 * H * D + self.W.numel(), **f32)
+        self.da_l = self.grads[:H * D].view(H, D)
+        self.da_r = self.grads[H * D:2 * H * D].view(H, D)
+        self.dW = self.grads[2 * H * D:].view_as(self.W)
         self.dX_dst = torch.empty_like(self.Xd)
         self.dX_src = torch.empty_like(self.X)
         n_src_max = max(v.n_src for v in self.views)
@@ -157,9 +159,7 @@ class Layer:
         mark("fwd1")
         sar.sar_gat_bwd_begin(self.G, self.out, self.s, self.L, self.rec, self.ds, self.act, self.Gact)
         G = self.Gact if self.act else self.G
-        self.da_l.zero_()
-        self.da_r.zero_()
-        self.dW.zero_()
+        self.grads.zero_()
         mark("bwd0")
         if mode == "all":
             sar.sar_gat_bwd_all(self.blocks, Zs, G, None, self.rec, self.a_l, w.slope, self.dZs, self.dts,
