@@ -203,7 +203,7 @@ def check_fwd(got, want, deg, dtype):
 # (heads, head width): every lane mapping of the generic kernels, every head width of the F = 256
 # kernels, non-power-of-two heads, and rows wider than 1 KiB (processed as groups of heads)
 SHAPES = [(4, 16), (1, 4), (4, 64), (8, 32), (2, 100), (3, 12), (1, 256), (2, 128), (16, 16),
-          (8, 100), (8, 64), (3, 200)]
+          (8, 100), (8, 64), (3, 200), (2, 256), (1, 512)]      # the last: the widest head of each row type
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
@@ -211,6 +211,8 @@ SHAPES = [(4, 16), (1, 4), (4, 64), (8, 32), (2, 100), (3, 12), (1, 256), (2, 12
 def test_gat_forward_parity(dtype, H, D):
     if dtype == torch.bfloat16 and D % 8:
         pytest.skip("bf16 rows move 8 values per lane")
+    if D * (4 if dtype == torch.float32 else 2) > 1024:
+        pytest.skip("one head is at most 1024 bytes wide")
     b, want_b, deg, Zdst, Zs, a_l, a_r, G = gat_case(6, 3000, 40000, 3, 0, H, D, dtype, simple=False)
     want = orc.gat_fwd(want_b, f64(Zdst), [f64(z) for z in Zs], f64(a_l), f64(a_r), SLOPE)
     states = []
@@ -236,6 +238,8 @@ def test_gat_forward_parity(dtype, H, D):
 def test_gat_backward_parity(dtype, H, D, batched, fly):
     if dtype == torch.bfloat16 and D % 8:
         pytest.skip("bf16 rows move 8 values per lane")
+    if D * (4 if dtype == torch.float32 else 2) > 1024:
+        pytest.skip("one head is at most 1024 bytes wide")
     b, want_b, deg, Zdst, Zs, a_l, a_r, G = gat_case(7, 3000, 40000, 3, 1, H, D, dtype)
     wf = orc.gat_fwd(want_b, f64(Zdst), [f64(z) for z in Zs], f64(a_l), f64(a_r), SLOPE)
     wb = orc.gat_bwd(want_b, f64(Zdst), [f64(z) for z in Zs], f64(G), f64(a_l), f64(a_r), SLOPE, wf)
