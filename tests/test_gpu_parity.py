@@ -139,8 +139,6 @@ def test_wrap_equals_build():
 @pytest.mark.parametrize("F", [8, 64, 200, 256, 800, 1032])
 @pytest.mark.parametrize("mean", [False, True])
 def test_spmm_parity(dtype, F, mean):
-    if dtype == torch.bfloat16 and F % 8:
-        pytest.skip("bf16 rows move 8 values per lane")
     src, dst, part, rng = make_graph(4, 3000, 40000, 3, simple=False)
     want_b, deg = orc.build_blocks(src, dst, part, 3, 0)
     b = gu.build_blocks(src, dst, part, 3, 0)
@@ -206,13 +204,17 @@ SHAPES = [(4, 16), (1, 4), (4, 64), (8, 32), (2, 100), (3, 12), (1, 256), (2, 12
           (8, 100), (8, 64), (3, 200), (2, 256), (1, 512)]      # the last: the widest head of each row type
 
 
-@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
-@pytest.mark.parametrize("H,D", SHAPES)
+def supported(dtype, D):
+    """Lanes move 16 bytes (4 fp32 or 8 bf16 values); one head is at most 1024 bytes wide."""
+    fb, vec = (4, 4) if dtype == torch.float32 else (2, 8)
+    return D % vec == 0 and D * fb <= 1024
+
+
+CASES = [(dt, H, D) for dt in (torch.float32, torch.bfloat16) for H, D in SHAPES if supported(dt, D)]
+
+
+@pytest.mark.parametrize("dtype,H,D", CASES)
 def test_gat_forward_parity(dtype, H, D):
-    if dtype == torch.bfloat16 and D % 8:
-        pytest.skip("bf16 rows move 8 values per lane")
-    if D * (4 if dtype == torch.float32 else 2) > 1024:
-        pytest.skip("one head is at most 1024 bytes wide")
     b, want_b, deg, Zdst, Zs, a_l, a_r, G = gat_case(6, 3000, 40000, 3, 0, H, D, dtype, simple=False)
     want = orc.gat_fwd(want_b, f64(Zdst), [f64(z) for z in Zs], f64(a_l), f64(a_r), SLOPE)
     states = []
@@ -232,14 +234,9 @@ def test_gat_forward_parity(dtype, H, D):
     b.close()
 
 
-@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
-@pytest.mark.parametrize("H,D", SHAPES)
+@pytest.mark.parametrize("dtype,H,D", CASES)
 @pytest.mark.parametrize("batched,fly", [(False, False), (True, False), (True, True), (False, True)])
 def test_gat_backward_parity(dtype, H, D, batched, fly):
-    if dtype == torch.bfloat16 and D % 8:
-        pytest.skip("bf16 rows move 8 values per lane")
-    if D * (4 if dtype == torch.float32 else 2) > 1024:
-        pytest.skip("one head is at most 1024 bytes wide")
     b, want_b, deg, Zdst, Zs, a_l, a_r, G = gat_case(7, 3000, 40000, 3, 1, H, D, dtype)
     wf = orc.gat_fwd(want_b, f64(Zdst), [f64(z) for z in Zs], f64(a_l), f64(a_r), SLOPE)
     wb = orc.gat_bwd(want_b, f64(Zdst), [f64(z) for z in Zs], f64(G), f64(a_l), f64(a_r), SLOPE, wf)
