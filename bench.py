@@ -222,6 +222,9 @@ MEASURED_TRAFFIC = {
     ("cfg3", "all", "gat_bwd_wide"): (2 * 6.408e6 + 1.235e6) * 1024,
     # the narrow kernel and the fill of the rows of the sources without an edge (timed together)
     ("cfg3", "all", "gat_bwd_narrow"): (2 * 1.931e6 + 1.433e6 + 2 * 5161 + 3.372e5) * 1024,
+    ("cfg4", "all", "gat_fwd"): (2 * 5.181e7 + 3.692e6) * 1024,
+    ("cfg4", "all", "gat_bwd_wide"): (2 * 2.965e7 + 4.711e6) * 1024,
+    ("cfg4", "all", "gat_bwd_narrow"): (2 * 4.931e7 + 3.362e7 + 2 * 5.535e5 + 2.535e7) * 1024,
 }
 KERNEL_NAMES = {"gat_fwd": "k_gat_fwd_f256", "gat_bwd_wide": "k_gat_bwd_f256",
                 "gat_bwd_narrow": "k_gat_bwd_narrow + k_bwd_zero_rows"}
