@@ -543,7 +543,8 @@ def main():
                              "alg_GBs": alg[kname] / (ms * 1e-3) / 1e9,
                              "gather_volume_GBs": gather[kname] / (ms * 1e-3) / 1e9,
                              "traffic_bytes": MEASURED_TRAFFIC.get((args.workload, args.mode, kname))
-                             if args.scale == 1.0 and args.dst_frac == 1.0 else None}
+                             if (args.scale == 1.0 and args.dst_frac == 1.0 and not args.skip_untouched
+                                 and args.storage == "config") else None}
     dom = max(per_kernel, key=lambda k: per_kernel[k]["avg_ms"])
     d = per_kernel[dom]
     # in stream mode the events bracket P launches of the kernel; report per launch
