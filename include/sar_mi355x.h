@@ -307,6 +307,23 @@ int sar_gat_bwd_end(const void* Zdst, const float* ds, const float* a_r, const v
                     void* dZdst, float* da_r, int dtype, int64_t n_dst, int H, int D, void* work,
                     size_t work_bytes, void* stream);
 
+/* sar_gat_bwd_end for callers that cannot allocate device memory or take a workspace
+ * along: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, same kernels and the same results as sar_gat_bwd_end,
+ * but the per-workgroup partial sums of da_r live in a 4 MiB array that is part of the
+ * library's device image (one copy per GPU, held until the process ends) instead of a
+ * caller workspace.  The call allocates nothing and frees nothing.  Limit: a launch
+ * needs (workgroups x values per head group) <= 2048 x 512 partial sums, which every
+ * shape the library supports satisfies; anything beyond returns SAR_ERR_UNSUPPORTED.
+ * All calls on one GPU share that array and it keeps the last call's contents (every
+ * call overwrites the part it reads, nothing has to start at zero): two calls that
+ * overlap in time on the same GPU -- different streams or threads -- race; serialise
+ * them.  The first call on a device looks up the array's device address (no allocation);
+ * make that call outside graph capture. */
+int sar_gat_bwd_end_noalloc(const void* Zdst, const float* ds, const float* a_r, const void* dZadd,
+                            void* dZdst, float* da_r, int dtype, int64_t n_dst, int H, int D,
+                            void* stream);
+
 /* ------------------------------------------------- Eq. 1: Z = X W on MFMA */
 
 /* Z[n,F] = X[n,K] W[K,F]; X, Z of `dtype`, W fp32 row-major.  When a_score is

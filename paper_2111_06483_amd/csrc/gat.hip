@@ -18,6 +18,7 @@
 // (LeakyReLU commutes with a positive scale), so e2 = LeakyReLU(s2 + t2) and
 // exp(e - m) = exp2(e2 - m2).
 #include <algorithm>
+#include <mutex>
 #include <vector>
 
 #include "gather_common.h"
@@ -1380,9 +1381,73 @@ extern "C" int sar_gat_bwd_all(const sar_blocks_t* b, const void* const* Zq, con
     return SAR_OK;
 }
 
-extern "C" int sar_gat_bwd_end(const void* Zdst, const float* ds, const float* a_r, const void* dZadd,
-                               void* dZdst, float* da_r, int dtype, int64_t n_dst, int H, int D, void* work,
-                               size_t work_bytes, void* stream)
+namespace {
+
+// Scratch of the entry point that allocates nothing: one row of partial sums of da_r per
+// workgroup of k_bwd_end (at most kMaxPersistentWGs workgroups, at most 512 values per launch).
+// Host code never uses the array's name as an address: the device address is looked up once
+// per device (scratch_of) and passed to the kernels like any caller workspace.
+constexpr size_t kScratchFloats = (size_t)kMaxPersistentWGs * 512;
+static __device__ __align__(256) float scratch[kScratchFloats];
+
+constexpr int kMaxDevices = 64;
+float* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device (each device holds its own copy).
+int scratch_of(float** out)
+{
+    int dev = -1;
+    SAR_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return sar::fail(SAR_ERR_UNSUPPORTED, "device ordinal %d is beyond %d", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        SAR_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return sar::fail(SAR_ERR_HIP, "hipGetSymbolAddress returned a null address for the scratch array");
+        g_scratch_ptr[dev] = static_cast<float*>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return SAR_OK;
+}
+
+// partial: room for one row of hg.Fg sums per workgroup; partial_floats = its size in values.
+int bwd_end_impl(const void* Zdst, const float* ds, const float* a_r, const void* dZadd, void* dZdst,
+                 float* da_r, int dtype, int64_t n_dst, int H, int D, float* partial, size_t partial_floats,
+                 hipStream_t st)
+{
+    const int F = H * D;
+    const HeadGroups hg = head_groups(dtype, H, D);
+    for (int g = 0; g < hg.n; ++g) {
+        const size_t f0 = (size_t)g * hg.Fg, h0 = (size_t)g * hg.Hg;
+        unsigned grid = 1;
+        const int slots = kWave / lanes_for(hg.Fg, dtype == SAR_F32 ? 4 : 8);
+        grid = nodewise_grid(n_dst, slots);
+        if ((size_t)grid * hg.Fg > partial_floats)
+            return sar::fail(SAR_ERR_UNSUPPORTED, "%u workgroups x %d partial sums exceed the %zu values of scratch",
+                             grid, hg.Fg, partial_floats);
+        if (dtype == SAR_F32) {
+            SAR_DISPATCH_G(float, hg.Fg, (k_bwd_end<float, kG><<<grid, kGatherThreads, 0, st>>>(
+                                              static_cast<const float*>(Zdst) + f0, ds + h0, a_r + f0,
+                                              dZadd ? static_cast<const float*>(dZadd) + f0 : nullptr,
+                                              static_cast<float*>(dZdst) + f0, partial, n_dst, hg.Hg,
+                                              D, hg.Fg, F, H)));
+        } else {
+            SAR_DISPATCH_G(bf16_t, hg.Fg, (k_bwd_end<bf16_t, kG><<<grid, kGatherThreads, 0, st>>>(
+                                               static_cast<const bf16_t*>(Zdst) + f0, ds + h0, a_r + f0,
+                                               dZadd ? static_cast<const bf16_t*>(dZadd) + f0 : nullptr,
+                                               static_cast<bf16_t*>(dZdst) + f0, partial, n_dst,
+                                               hg.Hg, D, hg.Fg, F, H)));
+        }
+        SAR_LAUNCH_CHECK();
+        k_reduce_partials<<<hg.Fg, 256, 0, st>>>(partial, (int)grid, hg.Fg, da_r + f0);
+        SAR_LAUNCH_CHECK();
+    }
+    return SAR_OK;
+}
+
+int bwd_end_checks(const void* Zdst, const float* ds, const float* a_r, const void* dZadd, void* dZdst,
+                   float* da_r, int dtype, int64_t n_dst, int H, int D)
 {
     SAR_TRY(check_shape(dtype, H, D));
     SAR_CHECK_ARG(n_dst >= 0, "n_dst is negative");
@@ -1390,35 +1455,34 @@ extern "C" int sar_gat_bwd_end(const void* Zdst, const float* ds, const float* a
     SAR_CHECK_ARG(Zdst && ds && a_r && dZdst && da_r, "a tensor argument is null");
     SAR_CHECK_ARG(aligned16(Zdst) && aligned16(dZdst) && aligned16(dZadd),
                   "Zdst, dZadd and dZdst must be 16-byte aligned");
+    return SAR_OK;
+}
+
+}  // namespace
+
+extern "C" int sar_gat_bwd_end(const void* Zdst, const float* ds, const float* a_r, const void* dZadd,
+                               void* dZdst, float* da_r, int dtype, int64_t n_dst, int H, int D, void* work,
+                               size_t work_bytes, void* stream)
+{
+    SAR_TRY(bwd_end_checks(Zdst, ds, a_r, dZadd, dZdst, da_r, dtype, n_dst, H, D));
+    if (n_dst == 0) return SAR_OK;
     SAR_CHECK_ARG(work != nullptr && aligned16(work), "work is null or not 16-byte aligned");
-    const int F = H * D;
     const size_t need = workspace_bytes(256);
     SAR_CHECK_ARG(work_bytes >= need, "work_bytes=%zu is below the %zu bytes required", work_bytes, need);
-    hipStream_t st = sar::as_stream(stream);
-    const HeadGroups hg = head_groups(dtype, H, D);
-    for (int g = 0; g < hg.n; ++g) {
-        const size_t f0 = (size_t)g * hg.Fg, h0 = (size_t)g * hg.Hg;
-        unsigned grid = 1;
-        if (dtype == SAR_F32) {
-            SAR_DISPATCH_G(float, hg.Fg, (grid = nodewise_grid(n_dst, kWave / kG),
-                                          k_bwd_end<float, kG><<<grid, kGatherThreads, 0, st>>>(
-                                              static_cast<const float*>(Zdst) + f0, ds + h0, a_r + f0,
-                                              dZadd ? static_cast<const float*>(dZadd) + f0 : nullptr,
-                                              static_cast<float*>(dZdst) + f0, static_cast<float*>(work), n_dst, hg.Hg,
-                                              D, hg.Fg, F, H)));
-        } else {
-            SAR_DISPATCH_G(bf16_t, hg.Fg, (grid = nodewise_grid(n_dst, kWave / kG),
-                                           k_bwd_end<bf16_t, kG><<<grid, kGatherThreads, 0, st>>>(
-                                               static_cast<const bf16_t*>(Zdst) + f0, ds + h0, a_r + f0,
-                                               dZadd ? static_cast<const bf16_t*>(dZadd) + f0 : nullptr,
-                                               static_cast<bf16_t*>(dZdst) + f0, static_cast<float*>(work), n_dst,
-                                               hg.Hg, D, hg.Fg, F, H)));
-        }
-        SAR_LAUNCH_CHECK();
-        k_reduce_partials<<<hg.Fg, 256, 0, st>>>(static_cast<const float*>(work), (int)grid, hg.Fg, da_r + f0);
-        SAR_LAUNCH_CHECK();
-    }
-    return SAR_OK;
+    return bwd_end_impl(Zdst, ds, a_r, dZadd, dZdst, da_r, dtype, n_dst, H, D, static_cast<float*>(work),
+                        work_bytes / sizeof(float), sar::as_stream(stream));
+}
+
+extern "C" int sar_gat_bwd_end_noalloc(const void* Zdst, const float* ds, const float* a_r, const void* dZadd,
+                                       void* dZdst, float* da_r, int dtype, int64_t n_dst, int H, int D,
+                                       void* stream)
+{
+    SAR_TRY(bwd_end_checks(Zdst, ds, a_r, dZadd, dZdst, da_r, dtype, n_dst, H, D));
+    if (n_dst == 0) return SAR_OK;
+    float* partial = nullptr;
+    SAR_TRY(scratch_of(&partial));
+    return bwd_end_impl(Zdst, ds, a_r, dZadd, dZdst, da_r, dtype, n_dst, H, D, partial, kScratchFloats,
+                        sar::as_stream(stream));
 }
 
 extern "C" int sar_timing_begin(int max_records)

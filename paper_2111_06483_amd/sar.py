@@ -76,6 +76,7 @@ EXPORTS = [
     "sar_spmm_block", "sar_spmm_end", "sar_spmm_all", "sar_act_bwd", "sar_spmm_bwd_block", "sar_spmm_bwd_all",
     "sar_gat_scores", "sar_gat_fwd_begin", "sar_gat_fwd_block", "sar_gat_fwd_end", "sar_gat_fwd_all",
     "sar_gat_workspace_bytes", "sar_gat_bwd_begin", "sar_gat_bwd_block", "sar_gat_bwd_all", "sar_gat_bwd_end",
+    "sar_gat_bwd_end_noalloc",
     "sar_linear_fwd", "sar_linear_bwd", "sar_linear_workspace_bytes",
     "sar_probe_stream_read", "sar_probe_copy", "sar_probe_row_gather", "sar_probe_gather_write",
     "sar_timing_begin", "sar_timing_count", "sar_timing_get",
@@ -380,6 +381,14 @@ def sar_gat_bwd_end(Zdst: torch.Tensor, ds: torch.Tensor, a_r: torch.Tensor, dZa
     _check(lib().sar_gat_bwd_end(_ptr(Zdst), _ptr(ds), _ptr(a_r), _ptr(dZadd), _ptr(dZdst), _ptr(da_r),
                                  _c_int(dtype_code(Zdst.dtype)), _c_i64(Zdst.shape[0]), _c_int(H), _c_int(D),
                                  _ptr(work), ctypes.c_size_t(work.numel() * work.element_size()), _stream()))
+
+
+def sar_gat_bwd_end_noalloc(Zdst: torch.Tensor, ds: torch.Tensor, a_r: torch.Tensor,
+                            dZadd: Optional[torch.Tensor], dZdst: torch.Tensor, da_r: torch.Tensor) -> None:
+    H, D = a_r.shape
+    _check(lib().sar_gat_bwd_end_noalloc(_ptr(Zdst), _ptr(ds), _ptr(a_r), _ptr(dZadd), _ptr(dZdst), _ptr(da_r),
+                                         _c_int(dtype_code(Zdst.dtype)), _c_i64(Zdst.shape[0]), _c_int(H),
+                                         _c_int(D), _stream()))
 
 
 # ------------------------------------------------------------------ linear
