@@ -508,31 +508,44 @@ __global__ __launch_bounds__(256) void k_reduce_partials(const float* __restrict
 
 // ---------------------------------------------------------------- node-wise
 
-// score[v,h] = <a[h], Z[v,h]>; one lane group per node.
+// score[v,h] = <a[h], Z[v,h]>; one lane group per node.  A second vector / output pair may ride
+// along (the two halves of the attention score from one pass over Z); avec2 = null: only the first.
 template <typename T, int G>
 __global__ __launch_bounds__(kGatherThreads) void k_scores(const T* __restrict__ Z, int64_t n, int H, int D,
                                                            int F, int ldz, int ldh,
                                                            const float* __restrict__ avec,
-                                                           float* __restrict__ score)
+                                                           float* __restrict__ score,
+                                                           const float* __restrict__ avec2,
+                                                           float* __restrict__ score2)
 {
     constexpr int VEC = Vec<T>::N;
     constexpr int SLOTS = kWave / G;
     const LaneMap<T, G> lm(F, H, D);
     const bool pow2 = is_pow2(lm.lph);
-    float av[VEC];
+    float av[VEC], av2[VEC];
 #pragma unroll
-    for (int x = 0; x < VEC; ++x) av[x] = lm.on ? avec[lm.gl * VEC + x] : 0.f;
+    for (int x = 0; x < VEC; ++x) {
+        av[x] = lm.on ? avec[lm.gl * VEC + x] : 0.f;
+        av2[x] = (lm.on && avec2) ? avec2[lm.gl * VEC + x] : 0.f;
+    }
     const int64_t wave_id = ((int64_t)blockIdx.x * kGatherThreads + threadIdx.x) / kWave;
     const int64_t n_waves = (int64_t)gridDim.x * kWavesPerWG;
     for (int64_t v0 = wave_id * SLOTS; v0 < n; v0 += n_waves * SLOTS) {
         const int64_t v = v0 + lm.slot;
         float z[VEC] = {};
         if (v < n && lm.on) Vec<T>::unpack(Vec<T>::load(Z + v * ldz + lm.gl * VEC), z);
-        float c = 0.f;
+        float c = 0.f, c2 = 0.f;
 #pragma unroll
-        for (int x = 0; x < VEC; ++x) c = fmaf(av[x], z[x], c);
+        for (int x = 0; x < VEC; ++x) {
+            c = fmaf(av[x], z[x], c);
+            c2 = fmaf(av2[x], z[x], c2);
+        }
         c = pow2 ? group_sum_pow2(c, lm.lph) : group_sum_any(c, lm.head_first, lm.lph);
-        if (v < n && lm.on && (lm.gl % lm.lph) == 0) score[v * ldh + lm.h] = c;
+        if (avec2) c2 = pow2 ? group_sum_pow2(c2, lm.lph) : group_sum_any(c2, lm.head_first, lm.lph);
+        if (v < n && lm.on && (lm.gl % lm.lph) == 0) {
+            score[v * ldh + lm.h] = c;
+            if (avec2) score2[v * ldh + lm.h] = c2;
+        }
     }
 }
 
@@ -1049,13 +1062,15 @@ size_t workspace_bytes(int F) { return (size_t)2 * kMaxPersistentWGs * F * sizeo
 
 }  // namespace
 
-extern "C" int sar_gat_scores(const void* Z, int dtype, int64_t n, int H, int D, const float* a,
-                              float* score, void* stream)
+// One pass over Z for one or two score vectors (a2/score2 may be null).
+int sar::gat_scores2(const void* Z, int dtype, int64_t n, int H, int D, const float* a, float* score,
+                     const float* a2, float* score2, void* stream)
 {
     SAR_TRY(check_shape(dtype, H, D));
     SAR_CHECK_ARG(n >= 0, "n is negative");
     if (n == 0) return SAR_OK;
     SAR_CHECK_ARG(Z && a && score, "Z, a or score is null");
+    SAR_CHECK_ARG((a2 == nullptr) == (score2 == nullptr), "the second vector and its output go together");
     SAR_CHECK_ARG(aligned16(Z), "Z must be 16-byte aligned");
     const int F = H * D;
     const HeadGroups hg = head_groups(dtype, H, D);
@@ -1064,16 +1079,24 @@ extern "C" int sar_gat_scores(const void* Z, int dtype, int64_t n, int H, int D,
         const void* Zg = shift(Z, (size_t)g * hg.Fg * hg.fb);
         const float* ag = a + (size_t)g * hg.Fg;
         float* sg = score + (size_t)g * hg.Hg;
+        const float* ag2 = a2 ? a2 + (size_t)g * hg.Fg : nullptr;
+        float* sg2 = score2 ? score2 + (size_t)g * hg.Hg : nullptr;
         if (dtype == SAR_F32) {
             SAR_DISPATCH_G(float, hg.Fg, (k_scores<float, kG><<<nodewise_grid(n, kWave / kG), kGatherThreads, 0, st>>>(
-                                             static_cast<const float*>(Zg), n, hg.Hg, D, hg.Fg, F, H, ag, sg)));
+                                             static_cast<const float*>(Zg), n, hg.Hg, D, hg.Fg, F, H, ag, sg, ag2, sg2)));
         } else {
             SAR_DISPATCH_G(bf16_t, hg.Fg, (k_scores<bf16_t, kG><<<nodewise_grid(n, kWave / kG), kGatherThreads, 0, st>>>(
-                                              static_cast<const bf16_t*>(Zg), n, hg.Hg, D, hg.Fg, F, H, ag, sg)));
+                                              static_cast<const bf16_t*>(Zg), n, hg.Hg, D, hg.Fg, F, H, ag, sg, ag2, sg2)));
         }
         SAR_LAUNCH_CHECK();
     }
     return SAR_OK;
+}
+
+extern "C" int sar_gat_scores(const void* Z, int dtype, int64_t n, int H, int D, const float* a,
+                              float* score, void* stream)
+{
+    return sar::gat_scores2(Z, dtype, n, H, D, a, score, nullptr, nullptr, stream);
 }
 
 extern "C" int sar_gat_fwd_begin(float* m, float* l, float* acc, int64_t n_dst, int H, int D, void* stream)

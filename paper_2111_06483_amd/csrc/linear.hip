@@ -949,13 +949,15 @@ extern "C" int sar_linear_fwd(const void* X, const float* W, void* Z, int dtype,
     g.vec_b = vec_ok(W, F, 4);
     SkinnyPlan plan;
     const bool want_scores = a_score || a_score2;
-    if (want_scores && 2 * H <= 32 && plan_skinny(X, K, Z, F, K, F, dtype, 1, &plan)) {
+    // With fp32 rows the scores are two more columns of the product (z_h . a_h = x . (W_h a_h)),
+    // equal to the scores of the stored rows up to fp32 rounding.  With bf16 rows they are taken
+    // from the STORED (rounded) rows in one pass afterwards: every later step reads those rows,
+    // and a score of the unrounded sums differs from theirs by up to the storage rounding, which
+    // is enough to move LeakyReLU's kink for about one edge in a thousand.
+    if (want_scores && dtype == SAR_F32 && 2 * H <= 32 && plan_skinny(X, K, Z, F, K, F, dtype, 1, &plan)) {
         SkinnyArgs sk{X, K, n, W, F, 1, Z, F, K, F, plan.chunks, a_score, a_score2, score, score2, H, D,
                       plan.stage_off};
-        if (dtype == SAR_F32)
-            SAR_TRY((launch_skinny<float, float, true>(sk, plan, st)));
-        else
-            SAR_TRY((launch_skinny<bf16_t, bf16_t, true>(sk, plan, st)));
+        SAR_TRY((launch_skinny<float, float, true>(sk, plan, st)));
         return SAR_OK;
     }
     if (plan_skinny(X, K, Z, F, K, F, dtype, 0, &plan)) {
@@ -973,6 +975,7 @@ extern "C" int sar_linear_fwd(const void* X, const float* W, void* Z, int dtype,
             k_gemm_bf16<bf16_t, float, bf16_t, true, false, true><<<grid, kGemmThreads, 0, st>>>(g);
         SAR_LAUNCH_CHECK();
     }
+    if (a_score && a_score2) return sar::gat_scores2(Z, dtype, n, H, D, a_score, score, a_score2, score2, stream);
     if (a_score) SAR_TRY(sar_gat_scores(Z, dtype, n, H, D, a_score, score, stream));
     if (a_score2) SAR_TRY(sar_gat_scores(Z, dtype, n, H, D, a_score2, score2, stream));
     return SAR_OK;

@@ -73,6 +73,10 @@ struct Block {
 
 inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
+// score[v,h] = <a[h], Z[v,h]> for one or two vectors a in one pass over Z (gat.hip).
+int gat_scores2(const void* Z, int dtype, int64_t n, int H, int D, const float* a, float* score,
+                const float* a2, float* score2, void* stream);
+
 }  // namespace sar
 
 struct sar_blocks {

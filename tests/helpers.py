@@ -35,3 +35,24 @@ def global_features(rng, part, P, F):
     Z = rng.standard_normal((N, F))
     members = [np.flatnonzero(part == q) for q in range(P)]
     return Z, [Z[m] for m in members], members
+
+
+def row_rel_err(a, b, floor=1e-2) -> float:
+    """Row-scale relative error: max over rows r of max|a_r - b_r| / max(max|b_r|, floor * max|b|).
+
+    rel_err holds every element to the scale of the largest one of the tensor, which lets rows of
+    small magnitude (low-degree sources next to hubs) be wrong by large factors.  Here a row is
+    held to its own scale; `floor` keeps rows that are (nearly) zero from dividing by nothing.
+    Meant for tensors whose rows are sums of like-signed or few terms (aggregates, per-row errors),
+    not for heavily cancelling sums."""
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    assert a.shape == b.shape, (a.shape, b.shape)
+    if b.size == 0:
+        return 0.0
+    a2, b2 = a.reshape(a.shape[0], -1), b.reshape(b.shape[0], -1)
+    scale = np.max(np.abs(b2))
+    if scale == 0:
+        return float(np.max(np.abs(a2)))
+    row = np.maximum(np.max(np.abs(b2), axis=1), floor * scale)
+    return float(np.max(np.max(np.abs(a2 - b2), axis=1) / row))

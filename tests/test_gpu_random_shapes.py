@@ -53,14 +53,25 @@ def draw(case):
     return rng, N, E, P, H, D, dtype, opts
 
 
+FLOOR_USE = {"strict": 0, "floor": 0}
+
+
 def close(got, want, tol, floor):
-    """Relative to the tensor's scale; `floor` is the scale of the terms whose sum the tensor is,
-    for sums that cancel to (nearly) nothing."""
+    """The strict measure max|got - want| <= tol * max|want| wherever the tensor has a scale of its
+    own: more than one row and max|want| >= floor.  Otherwise (a tensor of one node, or a sum whose
+    terms cancel to nearly nothing) the error is held to `floor`, the scale of the terms the
+    tensor's entries are sums of: a cancelling sum is as accurate as its terms, not as its value."""
     want = np.asarray(want)
     if want.size == 0:
         return True
     got = got if isinstance(got, np.ndarray) else f64(got)
-    return np.abs(got - want).max() <= tol * max(np.abs(want).max(), floor)
+    scale = np.abs(want).max()
+    err = np.abs(got - want).max()
+    if want.shape[0] > 1 and scale >= floor:
+        FLOOR_USE["strict"] += 1
+        return err <= tol * scale
+    FLOOR_USE["floor"] += 1
+    return err <= tol * max(scale, floor)
 
 
 def check_fwd_scaled(got, want, deg, dtype, score_floor):
@@ -190,3 +201,12 @@ def test_random_shape(case):
     want_dW, want_dX = orc.linear_bwd(f64(X), f64(dZ), f64(W))
     assert rel_err(f64(dW), want_dW + f64(dW0)) < tol
     assert rel_err(f64(dX), want_dX) < tol
+
+
+def test_the_floor_is_the_exception():
+    """The absolute floor of `close` acts only for the degenerate tensors it is meant for: over the
+    32 cases above the strict relative measure decided the large majority of the comparisons."""
+    total = FLOOR_USE["strict"] + FLOOR_USE["floor"]
+    if total == 0:
+        pytest.skip("runs after test_random_shape in the same process")
+    assert FLOOR_USE["floor"] <= 0.35 * total, FLOOR_USE

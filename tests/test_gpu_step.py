@@ -1,0 +1,240 @@
+"""The step bench.py times, as bench.py composes it, against the oracle: Eq. 1 with the score
+halves out of the transform, Alg. 1 over all blocks (one launch, or one launch per block with the
+running-maximum state of Sec. 3.4 in memory), Alg. 2 with the recomputed coefficients, the worker's
+own error E_{p->p} + ds a_r added in the backward epilogue, and Z_p.backward(E_p) -> dW, dX.
+
+`bench.Layer.step` is called unchanged; the oracle gets the same seeded inputs (blocks from the raw
+edge list by its own builder, features from the shared generator) and computes the whole layer in
+fp64.  fp32: config 3 at its full size.  bf16: config 4's shape at a reduced size, the oracle fed
+the bf16-rounded X and its own fp64 Z = X W rounded to bf16 once (the storage of Z is part of the
+configuration; nothing else is rounded on the oracle's side).
+
+LeakyReLU's derivative is a discrete choice made by the sign of u = s_i + t_j.  For the edges
+whose |u| is below what the two sides' scores may differ by, either branch is a correct result:
+the rows they touch are left out of the element-wise comparisons, and for the parameter
+gradients, which sum over every edge, the test checks that the difference to the oracle is
+explained by SOME choice of branch on exactly those edges (a bounded least-squares fit over one
+unknown in [0,1] per ambiguous edge and head, thousands of equations per head) and by nothing
+else, to the plain tolerance.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import sar_oracle as orc
+from tests.helpers import rel_err, row_rel_err
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    import bench
+    from paper_2111_06483_amd import sar, synth
+
+TOL = {torch.float32: 1e-4, torch.bfloat16: 2e-2}
+# bound on |u_kernel - u_oracle| relative to the largest score: fp32 sums of D products
+KINK_REL = 3e-6
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU in this process")
+    sar.lib()
+
+
+def f64(t):
+    return t.detach().to(torch.float64).cpu().numpy()
+
+
+def round_bf16(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(torch.bfloat16).to(torch.float64).numpy()
+
+
+def near_bf16_tie(z, bound):
+    """Per element: the spacing of bf16 values at z where z lies within `bound` of the midpoint of
+    two neighbouring bf16 values, else 0.  An fp32-accumulated product that differs from the fp64
+    one by up to `bound` may then round to the other neighbour: the stored value, and every score
+    that reads it, may legitimately differ by one spacing between the two sides."""
+    az = np.abs(z)
+    with np.errstate(divide="ignore"):
+        e = np.floor(np.log2(np.where(az > 0, az, 1.0)))
+    spacing = 2.0 ** (e - 7)                      # 8 significant bits
+    frac = az / spacing - np.floor(az / spacing)
+    return np.where(np.abs(frac - 0.5) * spacing < bound, spacing, 0.0)
+
+
+class OracleStep:
+    """What one step has to produce, from the oracle alone."""
+
+    def __init__(self, w):
+        P, p, H, D = w.P, w.p, w.H, w.D
+        dt = w.dtype
+        cpu = lambda t: t.cpu()
+        self.blocks, self.deg = orc.build_blocks(cpu(w.src).numpy(), cpu(w.dst).numpy(), cpu(w.part).numpy(), P, p)
+        members = [w.members(q) for q in range(P)]
+        self.Xs = [f64(synth.normal_rows(2, m, w.f_in, dtype=dt)) for m in members]
+        W, a_l, a_r = synth.gat_params(3, w.f_in, H, D, device="cuda")
+        self.W, self.a_l, self.a_r = f64(W), f64(a_l), f64(a_r)
+        self.G = f64(synth.normal_rows(4, members[p], H * D, dtype=dt)).reshape(-1, H, D)
+        Zs = [orc.linear_fwd(X, self.W) for X in self.Xs]
+        # what a score may differ by between the two sides beyond fp32 rounding (bf16 rows only)
+        self.slack_t = [np.zeros((Z.shape[0], H)) for Z in Zs]
+        self.slack_s = np.zeros((Zs[p].shape[0], H))
+        if dt == torch.bfloat16:
+            for q, (X, Z) in enumerate(zip(self.Xs, Zs)):
+                # fp32 accumulation of exact products plus the part of W below its two bf16 terms
+                near = near_bf16_tie(Z, 2.0 ** -19 * (np.abs(X) @ np.abs(self.W)))
+                self.slack_t[q] = (near.reshape(-1, H, D) * np.abs(self.a_l)[None]).sum(-1)
+                if q == p:
+                    self.slack_s = (near.reshape(-1, H, D) * np.abs(self.a_r)[None]).sum(-1)
+            Zs = [round_bf16(Z) for Z in Zs]
+        self.Zs = [Z.reshape(-1, H, D) for Z in Zs]
+        self.fwd = orc.gat_fwd(self.blocks, self.Zs[p], self.Zs, self.a_l, self.a_r, w.slope)
+        self.bwd = orc.gat_bwd(self.blocks, self.Zs[p], self.Zs, self.G, self.a_l, self.a_r, w.slope, self.fwd)
+        # the worker's own rows receive the error twice: as destinations and as sources of block p
+        self.E_p = self.bwd.dZdst + self.bwd.dZs[p]
+        self.dW, self.dX = orc.linear_bwd(self.Xs[p], self.E_p, self.W)
+        self.p, self.H, self.D, self.slope = p, H, D, w.slope
+
+    def ambiguous(self, margin):
+        """Edges (per head) with |s_i + t_j| < margin: (q, i, j, h, delta_du) where delta_du is
+        what du changes by if the other branch of LeakyReLU' is taken."""
+        out = []
+        fw = self.fwd
+        delta = (self.G * fw.out).sum(-1)
+        for q, b in enumerate(self.blocks):
+            rows = np.repeat(np.arange(b.n_dst), np.diff(b.indptr))
+            u = fw.s[rows] + fw.t[q][b.indices]
+            e_idx, h_idx = np.nonzero(np.abs(u) < margin + self.slack_s[rows] + self.slack_t[q][b.indices])
+            for e, h in zip(e_idx, h_idx):
+                i, j = int(rows[e]), int(b.indices[e])
+                uv = u[e, h]
+                ev = uv if uv > 0 else self.slope * uv
+                alpha = np.exp(ev - fw.L[i, h])
+                c = float(self.G[i, h] @ self.Zs[q][j, h])
+                de = alpha * (c - delta[i, h])
+                own, other = (1.0, self.slope) if uv > 0 else (self.slope, 1.0)
+                out.append((q, i, j, int(h), de * (other - own)))
+        return out
+
+
+def explained_by_branches(o, amb, got, want_dW_rows):
+    """Per head: residual of (got - want) for da_l, da_r and the head's columns of dW after the best
+    choice x in [0,1] per ambiguous edge; each tensor in units of its own largest oracle value."""
+    from scipy.optimize import lsq_linear
+    H, D, p = o.H, o.D, o.p
+    X = o.Xs[p]
+    scale = {"da_l": np.abs(o.bwd.da_l).max(), "da_r": np.abs(o.bwd.da_r).max(), "dW": np.abs(o.dW).max()}
+    worst = {"da_l": 0.0, "da_r": 0.0, "dW": 0.0}
+    n_amb = 0
+    for h in range(H):
+        cols = slice(h * D, (h + 1) * D)
+        rhs = np.concatenate([(got["da_l"][h] - o.bwd.da_l[h]) / scale["da_l"],
+                              (got["da_r"][h] - o.bwd.da_r[h]) / scale["da_r"],
+                              ((got["dW"][:, cols] - o.dW[:, cols]) / scale["dW"]).ravel()])
+        mine = [a for a in amb if a[3] == h]
+        n_amb += len(mine)
+        if mine:
+            A = np.empty((rhs.shape[0], len(mine)))
+            for k, (q, i, j, _, dd) in enumerate(mine):
+                dw = np.outer(X[i], dd * o.a_r[h])
+                if q == p:
+                    dw += np.outer(X[j], dd * o.a_l[h])
+                A[:, k] = np.concatenate([dd * o.Zs[q][j, h] / scale["da_l"], dd * o.Zs[p][i, h] / scale["da_r"],
+                                          dw.ravel() / scale["dW"]])
+            fit = lsq_linear(A, rhs, bounds=(0.0, 1.0))
+            res = A @ fit.x - rhs
+        else:
+            res = -rhs
+        worst["da_l"] = max(worst["da_l"], np.abs(res[:D]).max())
+        worst["da_r"] = max(worst["da_r"], np.abs(res[D:2 * D]).max())
+        worst["dW"] = max(worst["dW"], np.abs(res[2 * D:]).max())
+    return worst, n_amb
+
+
+def check_step(name, scale, modes):
+    w = synth.make_workload(name, device="cuda", scale=scale)
+    dt = w.dtype
+    tol = TOL[dt]
+    P, p, H, D = w.P, w.p, w.H, w.D
+    o = OracleStep(w)
+    n = o.blocks[0].n_dst
+    layer = bench.Layer(w, torch, sar, synth)
+    assert layer.n == n and layer.E == sum(b.nnz for b in o.blocks)
+
+    # rows an ambiguous branch can move (from the oracle's own scores)
+    s_scale = max(np.abs(o.fwd.s).max(), max(np.abs(t).max() for t in o.fwd.t))
+    # (bf16 rows: both sides take the scores of the STORED rows, in fp32 and in fp64, so the margin
+    # is the same; rows whose stored value itself may round either way carry their own slack)
+    margin = KINK_REL * s_scale
+    amb = o.ambiguous(margin)
+    bad_dst = np.zeros((n, H), dtype=bool)
+    bad_src = [np.zeros((b.n_src, H), dtype=bool) for b in o.blocks]
+    for q, i, j, h, _ in amb:
+        bad_dst[i, h] = True
+        bad_src[q][j, h] = True
+    bad_own = bad_dst | bad_src[p]
+    frac = max(bad_dst.mean(), max(b.mean() for b in bad_src))
+    print("%s: %d ambiguous (edge, head) pairs, at most %.2e of the rows of a tensor left out" % (name, len(amb), frac))
+    assert frac < 1e-2
+
+    for mode in modes:
+        for t in (layer.out, layer.L, layer.dZdst, layer.dX_dst, layer.ds, *layer.dZs, *layer.dts):
+            t.fill_(float("nan"))
+        layer.grads.fill_(float("nan"))
+        layer.step(mode)
+        torch.cuda.synchronize()
+        tag = "%s/%s" % (name, mode)
+        # ---- forward
+        # bf16 rows: a stored value that rounds to the other neighbour moves a score by |a| * spacing
+        s_tol = 1e-5 if dt == torch.float32 else 2e-3
+        assert rel_err(f64(layer.s), o.fwd.s) < s_tol, tag
+        assert rel_err(f64(layer.tp), o.fwd.t[p]) < s_tol, tag
+        calm = (o.slack_s == 0)
+        assert rel_err(f64(layer.s)[calm], o.fwd.s[calm]) < 1e-5, tag      # everywhere else: fp32 rounding only
+        assert rel_err(f64(layer.Zp), o.Zs[p]) < tol, tag
+        out = f64(layer.out)
+        assert rel_err(out, o.fwd.out) < tol, tag
+        assert row_rel_err(out, o.fwd.out) < tol, tag
+        L, Lw = f64(layer.L), o.fwd.L
+        fin = np.isfinite(Lw)
+        assert np.array_equal(fin, np.isfinite(L)), tag
+        assert rel_err(L[fin], Lw[fin]) < (1e-4 if dt == torch.float32 else 2e-3), tag
+        assert np.all(out[~fin[:, 0]] == 0), tag
+        # ---- backward, element-wise where no ambiguous branch reaches
+        ds = f64(layer.ds)
+        assert rel_err(ds[~bad_dst], o.bwd.ds[~bad_dst]) < tol, tag
+        for q in range(P):
+            ok = ~bad_src[q]
+            dZ, dZw = f64(layer.dZs[q]), o.bwd.dZs[q]
+            assert rel_err(dZ[ok], dZw[ok]) < tol, (tag, q)
+            assert row_rel_err(np.where(ok[:, :, None], dZ, 0), np.where(ok[:, :, None], dZw, 0)) < tol, (tag, q)
+            assert rel_err(f64(layer.dts[q])[ok], o.bwd.dt[q][ok]) < tol, (tag, q)
+        Ep = f64(layer.dZdst)
+        assert rel_err(Ep[~bad_own], o.E_p[~bad_own]) < tol, tag
+        # (E_p and dX carry ds a_r, a cancelling sum over a row's edges: no row of them has a scale
+        # of its own to be held to, so these two are compared at the tensor's scale only)
+        rows_ok = ~bad_own.any(axis=1)
+        dX = f64(layer.dX_dst)
+        assert rel_err(dX[rows_ok], o.dX[rows_ok]) < tol, tag
+        # ---- parameter gradients: every edge enters
+        got = {"da_l": f64(layer.da_l), "da_r": f64(layer.da_r), "dW": f64(layer.dW)}
+        plain = {"da_l": rel_err(got["da_l"], o.bwd.da_l), "da_r": rel_err(got["da_r"], o.bwd.da_r),
+                 "dW": rel_err(got["dW"], o.dW)}
+        worst, n_amb = explained_by_branches(o, amb, got, None)
+        print("%s: parameter gradients vs oracle, plain %s; after the best branch choice on the %d ambiguous "
+              "edges %s" % (tag, {k: "%.2e" % v for k, v in plain.items()}, n_amb,
+                            {k: "%.2e" % v for k, v in worst.items()}))
+        for k, v in worst.items():
+            assert v < tol, (tag, k, v, plain[k])
+    layer.blocks.close()
+
+
+def test_timed_step_config3_full_size_fp32():
+    """15.2M in-edges, 8 blocks, GAT 4 x 64, fp32: the default bench.py workload, both launch modes."""
+    check_step("cfg3", 1.0, ("all", "stream"))
+
+
+def test_timed_step_config4_shape_bf16():
+    """Config 4's layer (16 blocks, GAT 8 x 32, bf16 rows, fp32 accumulation) on a 3.3M-node graph."""
+    check_step("cfg4", 0.03, ("all", "stream"))
