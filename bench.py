@@ -14,13 +14,19 @@ Inputs are synthetic and already resident in HBM when the timed region starts
 have fetched; they are produced before timing).  The metric is the worker's
 in-edges processed per second of forward+backward.
 
-Prints ONE JSON line.  --gpus above 1 is refused: this build is single-GPU.
+Prints ONE JSON line.  The headline is config 3 (the fp32 GAT layer on the
+products-sized graph); with no --workload the same line also carries, under
+"configs", the steps of configs 2 (GraphSage layer), 4 (papers100M-sized, bf16
+rows) and 5 (dense rows), each timed the same way with its own step count.
+--gpus above 1 is refused: this build is single-GPU.
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
+import re
 import sys
 import time
 
@@ -29,6 +35,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+KERNEL_SOURCES = ("gat.hip", "gat_f256.h", "gather_common.h", "spmm.hip")
 
 
 def parse():
@@ -36,8 +43,10 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "fak"],
-                    help="cfgN: the five benchmark configurations; fak: head-count sweep of the paper's single-host kernel experiment")
+    ap.add_argument("--workload", default=None, choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "fak", "cfg3local"],
+                    help="cfgN: the five benchmark configurations; fak: head-count sweep of the paper's single-host "
+                         "kernel experiment; cfg3local: config 3's sizes on a graph whose neighbourhoods are local. "
+                         "Default: config 3 as the headline plus configs 2, 4, 5 beside it")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the graph (debugging only)")
     ap.add_argument("--mode", default="all", choices=["all", "stream"],
                     help="all: one launch over the P blocks; stream: one launch per block")
@@ -46,15 +55,17 @@ def parse():
     ap.add_argument("--dst-frac", type=float, default=1.0,
                     help="aggregate only into this fraction of the worker's destinations (a seeded random "
                          "subset, as a message flow graph restricts a layer, App. B); sources stay complete")
-    ap.add_argument("--skip-untouched", action="store_true",
-                    help="backward passes do not write the rows of sources without an edge in a block "
-                         "(only the rows V_{p,q} are exchanged, Sec. 3.2); the buffers are zeroed once")
+    ap.add_argument("--errors", default="compact", choices=["compact", "full", "full-skip"],
+                    help="shape of the errors E_{p->q}: compact = one row per source the block touches, the rows "
+                         "a worker exchanges (Sec. 3.2); full = one row per source of the partition, zeros "
+                         "written where no edge; full-skip = full height, rows without an edge not written")
     ap.add_argument("--storage", default="config", choices=["config", "f32", "bf16"],
                     help="storage type of the feature rows; 'config' keeps what the configuration names "
                          "(the headline, config 3, is fp32); accumulation is fp32 either way")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-transform", action="store_true",
                     help="skip the separate timing of the three transform products after the timed steps")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the bandwidth probes")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this size (to scale rocprofv3's FETCH_SIZE/WRITE_SIZE)")
     ap.add_argument("--cpu-blocks", type=int, default=8,
@@ -65,14 +76,18 @@ def parse():
 class Layer:
     """Device state of one worker's GAT layer; methods only call the C ABI."""
 
-    def __init__(self, w, torch, sar, synth, act=0, dst_frac=1.0, skip_untouched=False):
+    def __init__(self, w, torch, sar, synth, act=0, dst_frac=1.0, errors="compact"):
         self.torch, self.sar, self.w, self.act = torch, sar, w, act
         self.subset = dst_frac < 1.0
+        self.errors = errors
+        self.compact = errors == "compact"
         dev = "cuda"
         H, D, P, p = w.H, w.D, w.P, w.p
         self.H, self.D, self.F, self.P, self.p = H, D, H * D, P, p
         t0 = time.perf_counter()
-        flags = sar.SAR_BUILD_TRANSPOSE | sar.SAR_BUILD_FUSED | (sar.SAR_BUILD_SKIP_UNTOUCHED if skip_untouched else 0)
+        flags = sar.SAR_BUILD_TRANSPOSE | sar.SAR_BUILD_FUSED | {"compact": sar.SAR_BUILD_COMPACT,
+                                                                 "full-skip": sar.SAR_BUILD_SKIP_UNTOUCHED,
+                                                                 "full": 0}[errors]
         self.blocks = sar.sar_blocks_build(w.src, w.dst, w.part, P, p, flags)
         torch.cuda.synchronize()
         self.builder_s = time.perf_counter() - t0
@@ -99,13 +114,12 @@ class Layer:
         self.Xd = synth.normal_rows(2, dst_members, w.f_in, dtype=w.dtype) if self.subset else self.X
         self.G = synth.normal_rows(4, dst_members, self.F, dtype=w.dtype).reshape(n, H, D)
         # features of the other partitions, as fetched: Z_q = X_q W produced before timing
-        self.Zs, self.ts = [], []
+        self.Zs = []
         for q in range(P):
             Xq = synth.normal_rows(2, members[q], w.f_in, dtype=w.dtype)
             Zq = torch.empty((Xq.shape[0], self.F), dtype=w.dtype, device=dev)
             sar.sar_linear_fwd(Xq, self.W, Zq)
             self.Zs.append(Zq.reshape(-1, H, D))
-            self.ts.append(torch.empty((Xq.shape[0], H), dtype=torch.float32, device=dev))
             del Xq
         f32 = dict(dtype=torch.float32, device=dev)
         self.Zp = torch.empty((n, H, D), dtype=w.dtype, device=dev)
@@ -120,8 +134,11 @@ class Layer:
         self.rec = torch.empty((n, H, 4), **f32)
         self.Gact = torch.empty_like(self.G) if act else None
         self.ds = torch.empty((n, H), **f32)
-        self.dZs = [torch.zeros_like(z) for z in self.Zs]     # zeroed once: skipped rows stay zero
-        self.dts = [torch.zeros((z.shape[0], H), **f32) for z in self.Zs]
+        # E_{p->q}: one row per touched source (compact) or per source; zeroed once, so that rows a
+        # full-skip handle never writes stay zero
+        err_rows = [int(v.n_t_rows) if self.compact else int(v.n_src) for v in self.views]
+        self.dZs = [torch.zeros((r, H, D), dtype=w.dtype, device=dev) for r in err_rows]
+        self.dts = [torch.zeros((r, H), **f32) for r in err_rows]
         self.dZdst = torch.empty((n, H, D), dtype=w.dtype, device=dev)
         # the parameter gradients accumulate over blocks and calls: one buffer, zeroed by one fill per step
         self.grads = torch.zeros(2 * H * D + self.W.numel(), **f32)
@@ -133,6 +150,10 @@ class Layer:
         n_src_max = max(v.n_src for v in self.views)
         self.work = torch.empty(sar.sar_gat_workspace_bytes(n, n_src_max, H, D) // 4, **f32)
         self.lwork = torch.empty(max(1, sar.sar_linear_workspace_bytes(self.X.shape[0], w.f_in, self.F) // 4), **f32)
+        # with a subset the local block's errors belong to source rows, not to the listed destinations
+        self.own_rank = self.views[p].t_rank if (self.compact and not self.subset) else None
+        self.dZp_full = (torch.empty((self.X.shape[0], H, D), dtype=w.dtype, device=dev)
+                         if (self.compact and self.subset) else None)
         torch.cuda.synchronize()
 
     def step(self, mode, ev=None):
@@ -171,68 +192,78 @@ class Layer:
         mark("bwd1")
         # E_p = E_{p->p} + destination-score term: everything this worker itself produced for its rows
         sar.sar_gat_bwd_end(self.Zp, self.ds, self.a_r, None if self.subset else self.dZs[p], self.dZdst,
-                            self.da_r, self.work)
+                            self.da_r, self.work, dZadd_rank=self.own_rank)
         # Z_p.backward(E_p)
         sar.sar_linear_bwd(self.Xd, self.dZdst, self.W, self.dW, self.dX_dst, self.lwork)
         if self.subset:                      # destination and source roles of the own rows kept apart
-            sar.sar_linear_bwd(self.X, self.dZs[p], self.W, self.dW, self.dX_src, self.lwork)
+            own = self.dZs[p]
+            if self.compact:                 # the received rows placed among the worker's own (Alg. 2)
+                sar.sar_error_add(self.dZs[p], self.views[p].t_rank, False, self.dZp_full)
+                own = self.dZp_full
+            sar.sar_linear_bwd(self.X, own, self.W, self.dW, self.dX_src, self.lwork)
         mark("t1")
 
-    # ---- algorithmic bytes of the gather kernels (what the method must move at least)
+    # ---- algorithmic bytes of the gather calls (what the method must move at least)
     def alg_bytes(self):
-        """Per kernel of the all-blocks launches: forward, backward over sources with at least 4
-        (fp32 rows) or 8 (bf16 rows) edges ("wide"), backward over the other sources ("narrow",
-        four per wavefront)."""
-        torch, sar = self.torch, self.sar
+        """Forward launch and backward call over all blocks.  With U = sum over blocks of the
+        source rows a block touches and n_s = sum of the partition sizes:
+          forward   tagged index 4E, row offsets and launch list 8 n_p, every touched source row
+                    once U F fb, per destination s read, out and L written;
+          backward  transposed index 4E and its offsets 4 n_s, work list and rank 8U, every touched
+                    source row read once (the rematerialisation) U F fb, its error row and dt
+                    written once U (F fb + 4H), per touched destination G and the 16-byte record
+                    read once per head and ds updated.
+        `full_height` adds the zero rows of the sources without an edge that a full-height E_{p->q}
+        also writes ((n_s - U)(F fb + 4H)); the method itself has no such rows (Sec. 3.2)."""
+        torch = self.torch
         fb = 2 if self.w.dtype == torch.bfloat16 else 4
         F, H, n, E = self.F, self.H, self.n, self.E
-        touched = sum(v.n_t_rows for v in self.views)
-        fwd = (4 * E + 4 * (n + 1) + 4 * n            # tagged index, row offsets, launch list
-               + touched * F * fb                     # each touched source row once
-               + n * (H * 4 + F * fb + H * 4))        # s read, out and L written
-        rows = {"wide": 0, "narrow": 0}
-        rows_touched = {"wide": 0, "narrow": 0}
-        edges = {"wide": 0, "narrow": 0}
-        for v in self.views:
-            deg = torch.diff(sar.device_array(v.t_indptr, v.n_src + 1))
-            wide = deg >= (8 if self.w.dtype == torch.bfloat16 else 4)
-            rows["wide"] += int(wide.sum())
-            rows["narrow"] += int((~wide).sum())
-            rows_touched["wide"] += int(wide.sum())
-            rows_touched["narrow"] += int(((~wide) & (deg > 0)).sum())
-            edges["wide"] += int(deg[wide].sum())
-            edges["narrow"] += int(deg[~wide].sum())
-        out = {"gat_fwd": fwd}
-        for part in ("wide", "narrow"):
-            dst_rows = min(edges[part], n)            # distinct G rows this kernel can touch at most
-            out["gat_bwd_" + part] = (
-                4 * edges[part] + 12 * rows[part]     # transposed index, offsets, launch list
-                + rows_touched[part] * F * fb         # z_j read once (the rematerialisation)
-                + rows[part] * (F * fb + H * 4)       # dZ_q, dt_q written once
-                + dst_rows * (F * fb + H * 16 + 2 * H * 4))   # G, record read once; ds read-modify-write
-        self.part_edges = edges
-        return out
+        U = sum(int(v.n_t_rows) for v in self.views)
+        n_s = sum(int(v.n_src) for v in self.views)
+        dst_rows = min(E, n)
+        fwd = 4 * E + 8 * n + U * F * fb + n * (4 * H + F * fb + 4 * H)
+        bwd = (4 * E + 4 * (n_s + self.P) + 8 * U + U * F * fb + U * (F * fb + 4 * H)
+               + dst_rows * (F * fb + 16 * H + 8 * H))
+        return {"gat_fwd": fwd, "gat_bwd": bwd, "gat_bwd_full_height": bwd + (n_s - U) * (F * fb + 4 * H),
+                "touched_source_rows": U, "source_rows": n_s}
 
 
-# HBM-side traffic (bytes per launch) of the gather kernels at the default workload, from the
-# rocprofv3 counter summary kept under profiles/: 2 x FETCH_SIZE + WRITE_SIZE (KiB), the factor 2
-# being what FETCH_SIZE reads short on a plain 1 GiB copy.
-MEASURED_TRAFFIC = {
-    ("cfg3", "all", "gat_fwd"): (2 * 7.376e6 + 3.162e5) * 1024,
-    ("cfg3", "all", "gat_bwd_wide"): (2 * 6.408e6 + 1.235e6) * 1024,
-    # the narrow kernel and the fill of the rows of the sources without an edge (timed together)
-    ("cfg3", "all", "gat_bwd_narrow"): (2 * 1.931e6 + 1.433e6 + 2 * 5161 + 3.372e5) * 1024,
-    ("cfg4", "all", "gat_fwd"): (2 * 5.181e7 + 3.692e6) * 1024,
-    ("cfg4", "all", "gat_bwd_wide"): (2 * 2.965e7 + 4.711e6) * 1024,
-    ("cfg4", "all", "gat_bwd_narrow"): (2 * 4.931e7 + 3.362e7 + 2 * 5.535e5 + 2.535e7) * 1024,
-}
-KERNEL_NAMES = {"gat_fwd": "k_gat_fwd_f256", "gat_bwd_wide": "k_gat_bwd_f256",
-                "gat_bwd_narrow": "k_gat_bwd_narrow + k_bwd_zero_rows"}
+def kernel_source_sha():
+    """Digest of the gather kernels' sources: a counter summary under profiles/ applies to the
+    kernels of this build only if it was taken from the same sources."""
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2111_06483_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
 
 
-def measure_ceilings(torch, sar, row_bytes):
-    """Ceilings of this machine, measured in this run with the library's probe kernels:
+def profile_traffic(workload, kernel):
+    """HBM-side bytes per launch of `kernel` from the committed rocprofv3 counter summary of this
+    workload (two --pmc passes: FETCH_SIZE, WRITE_SIZE, scaled by a plain copy of known size).  The
+    summary carries the digest of the kernel sources it was taken from; for any other sources the
+    figure does not describe the kernel that just ran and None is returned."""
+    path = os.path.join(ROOT, "profiles", "traffic_%s.md" % workload)
+    info = {"file": os.path.relpath(path, ROOT), "measured_in_this_run": False}
+    if not os.path.exists(path):
+        return None, dict(info, note="no counter summary for this workload")
+    text = open(path).read()
+    m = re.search(r"kernel-source-sha:\s*([0-9a-f]+)", text)
+    if not m or m.group(1) != kernel_source_sha():
+        return None, dict(info, note="summary was taken from other kernel sources (%s, now %s)"
+                          % (m.group(1) if m else "none", kernel_source_sha()))
+    for line in text.splitlines():
+        m = re.match(r"\|\s*`?%s`?\s*\|\s*([0-9.e+]+)\s*\|\s*([0-9.e+]+)\s*\|\s*([0-9.e+]+)\s*\|" % re.escape(kernel), line)
+        if m:
+            fetch_kib, write_kib, fetch_scale = (float(x) for x in m.groups())
+            return (fetch_kib * fetch_scale + write_kib) * 1024.0, dict(info, kernel=kernel)
+    return None, dict(info, note="kernel %s not in the summary" % kernel)
+
+
+def measure_ceilings(torch, row_bytes):
+    """Ceilings of this machine, measured in this run with the probe kernels of libsar_bench.so:
     streaming read, copy, and uniform-random whole-row gathers over a 2 GiB table."""
+    from paper_2111_06483_amd import bench_probes as probes
     n_rows = (2 << 30) // row_bytes
     table = torch.zeros((n_rows, row_bytes // 4), dtype=torch.float32, device="cuda")
     g = torch.Generator(device="cuda").manual_seed(7)
@@ -251,17 +282,17 @@ def measure_ceilings(torch, sar, row_bytes):
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / reps * 1e-3
 
-    t_read = timed(lambda: sar.sar_probe_stream_read(table, 2, sink))
-    t_gather = timed(lambda: sar.sar_probe_row_gather(table, idx, sink))
-    t_copy = timed(lambda: sar.sar_probe_copy(table[: dst.numel() // table.shape[1]], dst))
+    t_read = timed(lambda: probes.stream_read(table, 2, sink))
+    t_gather = timed(lambda: probes.row_gather(table, idx, sink))
+    t_copy = timed(lambda: probes.copy(table[: dst.numel() // table.shape[1]], dst))
     # the backward kernels' mix: three rows written for every eight gathered
     out = torch.empty(((idx.numel() // 8) * 3, row_bytes // 4), dtype=torch.float32, device="cuda")
-    t_mix = timed(lambda: sar.sar_probe_gather_write(table, idx, 3, out))
+    t_mix = timed(lambda: probes.gather_write(table, idx, 3, out))
     return {"stream_read_GBs": 2 * (2 << 30) / t_read / 1e9,
             "random_row_gather_GBs": idx.numel() * row_bytes / t_gather / 1e9,
             "copy_read_plus_write_GBs": 2 * (1 << 30) / t_copy / 1e9,
             "gather_8_write_3_GBs": (idx.numel() + (idx.numel() // 8) * 3) * row_bytes / t_mix / 1e9,
-            "note": "probe kernels of the library, timed with HIP events in this run; %d-byte rows, "
+            "note": "probe kernels (libsar_bench.so), timed with HIP events in this run; %d-byte rows, "
                     "uniform-random over a 2 GiB table" % row_bytes}
 
 
@@ -305,7 +336,8 @@ def measure_transform(layer, reps=20):
 
 
 def cpu_baseline(layer, n_blocks):
-    """The oracle, as it stands, on the first n_blocks blocks of the same workload."""
+    """The oracle, as it stands, on the first n_blocks blocks of the same workload: once on one
+    core (its plain serial loops) and once with the same loops spread over all host cores."""
     n_blocks = max(1, min(n_blocks, layer.P))
     import numpy as np
     from oracle import sar_oracle as orc
@@ -320,31 +352,114 @@ def cpu_baseline(layer, n_blocks):
     from paper_2111_06483_amd import synth
     Xs = [f64(synth.normal_rows(2, layer.members[q].cpu(), w.f_in, dtype=w.dtype)) for q in range(n_blocks)]
     a_l, a_r, G = f64(layer.a_l), f64(layer.a_r), f64(layer.G)
-    # the oracle's loops are single-threaded C; hold the matrix products (numpy's BLAS) to one
-    # thread as well, so that `cores` is what ran
     from threadpoolctl import threadpool_limits
     Zs = [orc.linear_fwd(X, W) for X in Xs]      # the fetched blocks' rows: given, as in the GPU step
+    edges = sum(b.nnz for b in blocks)
+    sample = "%d of %d source blocks of the same workload (%d edges), forward+backward, fp64" % (n_blocks, w.P, edges)
+    # one core: the oracle's loops are single-threaded C; the matrix products (numpy's BLAS) are held
+    # to one thread as well, so that `cores` is what ran
     with threadpool_limits(limits=1):
         t0 = time.perf_counter()
         Zdst = orc.linear_fwd(Xp, W)
         fwd = orc.gat_fwd(blocks, Zdst, Zs, a_l, a_r, w.slope)
         bwd = orc.gat_bwd(blocks, Zdst, Zs, G, a_l, a_r, w.slope, fwd)
         orc.linear_bwd(Xp, bwd.dZdst, W)
-        dt = time.perf_counter() - t0
-    edges = sum(b.nnz for b in blocks)
-    return {"value": edges / dt, "unit": "edges/s", "cores": 1, "kind": "oracle",
-            "sample": "%d of %d source blocks of the same workload (%d edges), forward+backward, fp64, %.1f s"
-                      % (n_blocks, w.P, edges, dt)}
+        dt1 = time.perf_counter() - t0
+    del fwd, bwd
+    cores = orc.threads()
+    t0 = time.perf_counter()
+    Zdst = orc.linear_fwd(Xp, W)
+    fwd = orc.gat_fwd_par(blocks, Zdst, Zs, a_l, a_r, w.slope)
+    bwd = orc.gat_bwd_par(blocks, Zdst, Zs, G, a_l, a_r, w.slope, fwd)
+    orc.linear_bwd(Xp, bwd.dZdst, W)
+    dtn = time.perf_counter() - t0
+    one = {"value": edges / dt1, "unit": "edges/s", "cores": 1, "kind": "oracle", "sample": sample + ", %.1f s" % dt1}
+    many = {"value": edges / dtn, "unit": "edges/s", "cores": cores, "kind": "oracle, its loops over all host cores "
+            "(OpenMP over the rows that own the results)", "sample": sample + ", %.1f s" % dtn}
+    return one, many
 
 
-def sage_bench(args, w, torch, sar, synth):
+def time_gat(args, torch, sar, synth, name, steps, warmup, full_report):
+    """Times `steps` steps of workload `name`; returns the result dictionary (and the layer when
+    full_report, for the extras the headline carries)."""
+    w = (synth.make_workload(name, device="cuda", scale=args.scale) if name != "cfg3local"
+         else synth.make_local_workload(device="cuda", scale=args.scale))
+    if args.storage != "config":
+        w.dtype = torch.float32 if args.storage == "f32" else torch.bfloat16
+    layer = Layer(w, torch, sar, synth, act=sar.SAR_ACT_RELU if args.act == "relu" else sar.SAR_ACT_NONE,
+                  dst_frac=args.dst_frac, errors=args.errors)
+    if full_report and args.calib_copy_mib:
+        a = torch.ones(args.calib_copy_mib << 18, dtype=torch.float32, device="cuda")
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        b.copy_(a)          # one kernel that reads and writes exactly calib_copy_mib MiB
+        torch.cuda.synchronize()
+        del a, b
+    for _ in range(warmup):
+        layer.step(args.mode)
+    torch.cuda.synchronize()
+    names = ["t0", "fwd0", "fwd1", "bwd0", "bwd1", "t1"]
+    evs = [{k: torch.cuda.Event(enable_timing=True) for k in names} for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(steps):
+        layer.step(args.mode, evs[k])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_step = wall * 1e3 / steps
+    avg = lambda a, b: sum(e[a].elapsed_time(e[b]) for e in evs) / len(evs)
+    fwd_ms, bwd_ms, all_ms = avg("fwd0", "fwd1"), avg("bwd0", "bwd1"), avg("t0", "t1")
+    fb = 2 if w.dtype == torch.bfloat16 else 4
+    alg = layer.alg_bytes()
+    # in stream mode the events bracket P launches; report per launch
+    launches = 1 if args.mode == "all" else w.P
+    fast = layer.F == 256
+    calls = {
+        "gat_fwd": {"kernel": ("k_gat_fwd_f256" if fast else "k_gat_fwd") + (" (all blocks)" if args.mode == "all" else " (per block)"),
+                    "avg_ms": fwd_ms, "alg_bytes": alg["gat_fwd"]},
+        "gat_bwd": {"kernel": ("k_gat_bwd_f256 + k_gat_bwd_narrow" if fast else "k_gat_bwd")
+                    + ("" if layer.errors != "full" else " + k_bwd_zero_rows"),
+                    "avg_ms": bwd_ms, "alg_bytes": alg["gat_bwd"],
+                    "alg_bytes_full_height": alg["gat_bwd_full_height"]},
+    }
+    for c in calls.values():
+        c["alg_GBs"] = c["alg_bytes"] / (c["avg_ms"] * 1e-3) / 1e9
+        c["frac"] = c["alg_GBs"] / HBM_PEAK_GBS
+        c["gather_volume_GBs"] = layer.E * layer.F * fb / (c["avg_ms"] * 1e-3) / 1e9
+    res = {
+        "ms_per_step": ms_step,
+        "edges_per_s": layer.E / (ms_step * 1e-3),
+        "dtype": "f32" if w.dtype == torch.float32 else "bf16 storage, f32 accumulate",
+        "workload": "%s: one worker's share of a %d-node graph, %d-way split, %d destinations, "
+                    "%d in-edges over %d resident source blocks, GAT %d heads x %d, in_dim %d"
+                    % (name, w.N, w.P, layer.n, layer.E, w.P, w.H, w.D, w.f_in),
+        "steps": steps, "warmup": warmup,
+        "phases_ms": {"step_events": all_ms, "gat_fwd": fwd_ms, "gat_bwd": bwd_ms,
+                      "other (XW fwd+bwd, scores, begin/end)": all_ms - fwd_ms - bwd_ms},
+        "aggregation_only_edges_per_s": layer.E / ((fwd_ms + bwd_ms) * 1e-3),
+        "source_rows": alg["source_rows"], "touched_source_rows": alg["touched_source_rows"],
+        "calls": calls, "launches_per_call": launches,
+        "builder_s": layer.builder_s,
+        **({"subset_builder_s": layer.subset_s} if layer.subset else {}),
+    }
+    return res, layer, w
+
+
+def time_sage(args, torch, sar, synth, steps, warmup):
     """Config 2: one worker's GraphSage layer (Eq. 1 + Eq. 2), forward and backward, over the P
     resident blocks: Z_p = X_p W and R = X_p W_res on MFMA, mean aggregation with the residual and
     ReLU fused into its epilogue, error through ReLU, case-1 backward per block (no features
     needed), dW / dW_res / dX for the worker's own rows."""
+    w = synth.make_workload("cfg2", device="cuda", scale=args.scale)
+    if args.storage != "config":
+        w.dtype = torch.float32 if args.storage == "f32" else torch.bfloat16
     dev = "cuda"
     P, p, F = w.P, w.p, w.H * w.D
-    blocks = sar.sar_blocks_build(w.src, w.dst, w.part, P, p)
+    compact = args.errors == "compact"
+    flags = sar.SAR_BUILD_TRANSPOSE | sar.SAR_BUILD_FUSED | {"compact": sar.SAR_BUILD_COMPACT,
+                                                             "full-skip": sar.SAR_BUILD_SKIP_UNTOUCHED,
+                                                             "full": 0}[args.errors]
+    blocks = sar.sar_blocks_build(w.src, w.dst, w.part, P, p, flags)
     views = [blocks.view(q) for q in range(P)]
     E = sum(v.nnz for v in views)
     n = blocks.n_dst
@@ -365,7 +480,9 @@ def sage_bench(args, w, torch, sar, synth):
     acc = torch.zeros((n, F), **f32)
     h = torch.empty((n, F), dtype=w.dtype, device=dev)
     G = torch.empty((n, F), dtype=w.dtype, device=dev)
-    dZs = [torch.empty_like(z) for z in Zs]
+    dZs = [torch.zeros((int(v.n_t_rows) if compact else int(v.n_src), F), dtype=w.dtype, device=dev) for v in views]
+    # the local block's error for the worker's own rows, full height (what Z_p.backward takes)
+    dZp_full = torch.empty((n, F), dtype=w.dtype, device=dev) if compact else None
     dW, dW_res = torch.zeros_like(W), torch.zeros_like(W_res)
     dX_msg, dX_res = torch.empty_like(X), torch.empty_like(X)
     lwork = torch.empty(max(1, sar.sar_linear_workspace_bytes(n, w.f_in, F) // 4), **f32)
@@ -399,47 +516,56 @@ def sage_bench(args, w, torch, sar, synth):
                 sar.sar_spmm_bwd_block(blocks, q, G, True, dZs[q])
         mark("bwd1")
         sar.sar_linear_bwd(X, G, W_res, dW_res, dX_res, lwork)
-        sar.sar_linear_bwd(X, dZs[p], W, dW, dX_msg, lwork)
+        if compact:                          # the owner adds the received rows to its own (Alg. 2)
+            sar.sar_error_add(dZs[p], views[p].t_rank, False, dZp_full)
+            sar.sar_linear_bwd(X, dZp_full, W, dW, dX_msg, lwork)
+        else:
+            sar.sar_linear_bwd(X, dZs[p], W, dW, dX_msg, lwork)
         mark("t1")
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
     names = ["t0", "fwd0", "fwd1", "bwd0", "bwd1", "t1"]
-    evs = [{k: torch.cuda.Event(enable_timing=True) for k in names} for _ in range(args.steps)]
+    evs = [{k: torch.cuda.Event(enable_timing=True) for k in names} for _ in range(steps)]
     t0 = time.perf_counter()
-    for k in range(args.steps):
+    for k in range(steps):
         step(evs[k])
     torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms = (time.perf_counter() - t0) * 1e3 / steps
     avg = lambda a, b: sum(e[a].elapsed_time(e[b]) for e in evs) / len(evs)
     fwd_ms, bwd_ms, all_ms = avg("fwd0", "fwd1"), avg("bwd0", "bwd1"), avg("t0", "t1")
     fb = 2 if w.dtype == torch.bfloat16 else 4
-    touched = sum(v.n_t_rows for v in views)
-    n_src = sum(v.n_src for v in views)
+    U = sum(int(v.n_t_rows) for v in views)
+    n_src = sum(int(v.n_src) for v in views)
     # forward: index, each touched source row once, residual read, h written
-    alg_fwd = 4 * E + 8 * n + touched * F * fb + 2 * n * F * fb
-    # backward: transposed index, each destination's error row once per block that touches it at
-    # most (counted once per block), every source row of every block written
-    alg_bwd = 4 * E + 12 * n_src + P * 4 * n + min(E, P * n) * F * fb + n_src * F * fb
-    print(json.dumps({
-        "metric": "GraphSage layer fwd+bwd edges/sec per GPU", "value": E / (ms * 1e-3), "unit": "edges/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32" if w.dtype == torch.float32 else "bf16 storage, f32 accumulate", "data": "synthetic",
-        "config": {"workload": "cfg2: one worker's share of a %d-node graph, %d-way split, %d destinations, "
-                               "%d in-edges over %d resident source blocks, GraphSage F=%d, in_dim %d, ReLU"
-                               % (w.N, P, n, E, P, F, w.f_in), "mode": args.mode, "scale": args.scale},
+    alg_fwd = 4 * E + 8 * n + U * F * fb + 2 * n * F * fb
+    # backward: transposed index and offsets, work list and rank, each destination's error row once
+    # (G and its degree), every touched source's error row written once
+    alg_bwd = 4 * E + 4 * (n_src + P) + 8 * U + min(E, n) * (F * fb + 4) + U * F * fb
+    calls = {"spmm_fwd": {"kernel": "k_spmm (all blocks)" if args.mode == "all" else "k_spmm (per block)",
+                          "avg_ms": fwd_ms, "alg_bytes": alg_fwd},
+             "spmm_bwd": {"kernel": "k_spmm_bwd_all" if args.mode == "all" else "k_spmm (backward, per block)",
+                          "avg_ms": bwd_ms, "alg_bytes": alg_bwd,
+                          "alg_bytes_full_height": alg_bwd + (n_src - U) * F * fb}}
+    for c in calls.values():
+        c["alg_GBs"] = c["alg_bytes"] / (c["avg_ms"] * 1e-3) / 1e9
+        c["frac"] = c["alg_GBs"] / HBM_PEAK_GBS
+        c["gather_volume_GBs"] = E * F * fb / (c["avg_ms"] * 1e-3) / 1e9
+    return {
+        "metric": "GraphSage layer fwd+bwd edges/sec per GPU",
+        "ms_per_step": ms, "edges_per_s": E / (ms * 1e-3),
+        "dtype": "f32" if w.dtype == torch.float32 else "bf16 storage, f32 accumulate",
+        "workload": "cfg2: one worker's share of a %d-node graph, %d-way split, %d destinations, "
+                    "%d in-edges over %d resident source blocks, GraphSage F=%d, in_dim %d, ReLU"
+                    % (w.N, P, n, E, P, F, w.f_in),
+        "steps": steps, "warmup": warmup,
         "phases_ms": {"step_events": all_ms, "mean_aggregation_fwd (+residual, ReLU)": fwd_ms,
-                      "aggregation_bwd (%d launches)" % (1 if args.mode == "all" else P): bwd_ms,
+                      "aggregation_bwd": bwd_ms,
                       "other (XW, X W_res fwd+bwd, ReLU bwd)": all_ms - fwd_ms - bwd_ms},
-        "roofline": {"bound": "hbm", "kernel": "k_spmm (all blocks)" if args.mode == "all" else "k_spmm (per block)",
-                     "achieved": alg_fwd / (fwd_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": alg_fwd / (fwd_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
-                     "alg_bytes_per_launch": alg_fwd, "avg_launch_ms": fwd_ms,
-                     "gather_volume_GBs": E * F * fb / (fwd_ms * 1e-3) / 1e9,
-                     "backward": {"alg_bytes": alg_bwd, "ms": bwd_ms, "alg_GBs": alg_bwd / (bwd_ms * 1e-3) / 1e9,
-                                  "gather_volume_GBs": E * F * fb / (bwd_ms * 1e-3) / 1e9}}}))
+        "source_rows": n_src, "touched_source_rows": U,
+        "calls": calls, "launches_per_call": 1 if args.mode == "all" else P,
+    }
 
 
 def fak_sweep(args, torch, sar, synth):
@@ -448,7 +574,7 @@ def fak_sweep(args, torch, sar, synth):
     rows = []
     for H in (2, 4, 8):
         w = synth.make_workload("fak%d" % H, device="cuda", scale=args.scale)
-        layer = Layer(w, torch, sar, synth)
+        layer = Layer(w, torch, sar, synth, errors=args.errors)
         for _ in range(args.warmup):
             layer.step("all")
         names = ["t0", "fwd0", "fwd1", "bwd0", "bwd1", "t1"]
@@ -485,108 +611,83 @@ def main():
     if args.workload == "fak":
         fak_sweep(args, torch, sar, synth)
         return
-    w = synth.make_workload(args.workload, device="cuda", scale=args.scale)
-    if args.storage != "config":
-        w.dtype = torch.float32 if args.storage == "f32" else torch.bfloat16
-    if args.workload == "cfg2":
-        sage_bench(args, w, torch, sar, synth)
+    headline = args.workload or "cfg3"
+    if headline == "cfg2":
+        r = time_sage(args, torch, sar, synth, args.steps, args.warmup)
+        c = r["calls"]["spmm_fwd"]
+        print(json.dumps({
+            "metric": r["metric"], "value": r["edges_per_s"], "unit": "edges/s", "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "ms_per_step": r["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": r["dtype"], "data": "synthetic",
+            "config": {"workload": r["workload"], "mode": args.mode, "scale": args.scale, "errors": args.errors},
+            "phases_ms": r["phases_ms"],
+            "roofline": {"bound": "hbm", "kernel": c["kernel"], "achieved": c["alg_GBs"], "peak": HBM_PEAK_GBS,
+                         "unit": "GB/s", "frac": c["frac"], "traffic": None,
+                         "alg_bytes_per_launch": c["alg_bytes"] / r["launches_per_call"],
+                         "avg_launch_ms": c["avg_ms"] / r["launches_per_call"], "calls": r["calls"]}}))
         return
-    layer = Layer(w, torch, sar, synth, act=sar.SAR_ACT_RELU if args.act == "relu" else sar.SAR_ACT_NONE,
-                  dst_frac=args.dst_frac, skip_untouched=args.skip_untouched)
 
-    if args.calib_copy_mib:
-        a = torch.ones(args.calib_copy_mib << 18, dtype=torch.float32, device="cuda")
-        b = torch.empty_like(a)
-        torch.cuda.synchronize()
-        b.copy_(a)          # one kernel that reads and writes exactly calib_copy_mib MiB
-        torch.cuda.synchronize()
-        del a, b
-    for _ in range(args.warmup):
-        layer.step(args.mode)
-    torch.cuda.synchronize()
-    names = ["t0", "fwd0", "fwd1", "bwd0", "bwd1", "t1"]
-    evs = [{k: torch.cuda.Event(enable_timing=True) for k in names} for _ in range(args.steps)]
-    sar.sar_timing_begin(args.steps * (1 if args.mode == "all" else w.P))
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for k in range(args.steps):
-        layer.step(args.mode, evs[k])
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ms_step = wall * 1e3 / args.steps
-    avg = lambda a, b: sum(e[a].elapsed_time(e[b]) for e in evs) / len(evs)
-    fwd_ms, bwd_ms, all_ms = avg("fwd0", "fwd1"), avg("bwd0", "bwd1"), avg("t0", "t1")
-    recs = [sar.sar_timing_get(k) for k in range(sar.sar_timing_count())]
-    sar.sar_timing_begin(0)
-    wide_ms = sum(r[0] for r in recs) / args.steps if recs else 0.0
-    narrow_ms = sum(r[1] for r in recs) / args.steps if recs else 0.0
-
-    row_bytes = layer.F * (2 if w.dtype == torch.bfloat16 else 4)
-    ceilings = measure_ceilings(torch, sar, 512 if row_bytes == 512 else 1024)   # the probe's two row sizes
-    alg = layer.alg_bytes()
-    fb = 2 if w.dtype == torch.bfloat16 else 4
-    names = dict(KERNEL_NAMES)
-    kern_ms = {"gat_fwd": fwd_ms, "gat_bwd_wide": wide_ms, "gat_bwd_narrow": narrow_ms}
-    gather = {"gat_fwd": layer.E * layer.F * fb, "gat_bwd_wide": layer.part_edges["wide"] * layer.F * fb,
-              "gat_bwd_narrow": layer.part_edges["narrow"] * layer.F * fb}
-    if wide_ms + narrow_ms <= 0:
-        # rows of another width than 256 values take the generic kernels: one backward kernel
-        names.update({"gat_fwd": "k_gat_fwd", "gat_bwd": "k_gat_bwd"})
-        kern_ms = {"gat_fwd": fwd_ms, "gat_bwd": bwd_ms}
-        alg["gat_bwd"] = alg["gat_bwd_wide"] + alg["gat_bwd_narrow"]
-        gather["gat_bwd"] = layer.E * layer.F * fb
-    per_kernel = {}
-    for kname, ms in kern_ms.items():
-        if ms <= 0:
-            continue
-        per_kernel[kname] = {"kernel": names[kname], "avg_ms": ms, "alg_bytes": alg[kname],
-                             "alg_GBs": alg[kname] / (ms * 1e-3) / 1e9,
-                             "gather_volume_GBs": gather[kname] / (ms * 1e-3) / 1e9,
-                             "traffic_bytes": MEASURED_TRAFFIC.get((args.workload, args.mode, kname))
-                             if (args.scale == 1.0 and args.dst_frac == 1.0 and not args.skip_untouched
-                                 and args.storage == "config") else None}
-    dom = max(per_kernel, key=lambda k: per_kernel[k]["avg_ms"])
-    d = per_kernel[dom]
-    # in stream mode the events bracket P launches of the kernel; report per launch
-    launches = 1 if args.mode == "all" else w.P
+    r, layer, w = time_gat(args, torch, sar, synth, headline, args.steps, args.warmup, True)
+    dom = max(r["calls"], key=lambda k: r["calls"][k]["avg_ms"] if k == "gat_fwd" else 0.0)   # one kernel per launch
+    d = r["calls"][dom]
+    launches = r["launches_per_call"]
+    plain = (args.scale == 1.0 and args.dst_frac == 1.0 and args.storage == "config" and args.mode == "all"
+             and args.act == "none")
+    traffic, traffic_src = (profile_traffic(headline, "k_gat_fwd_f256") if plain
+                            else (None, {"note": "no counter summary for these options"}))
     res = {
         "metric": "fused GAT fwd+bwd edges/sec per GPU",
-        "value": layer.E / (ms_step * 1e-3),
+        "value": r["edges_per_s"],
         "unit": "edges/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_step,
+        "ms_per_step": r["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32" if w.dtype == torch.float32 else "bf16 storage, f32 accumulate",
+        "dtype": r["dtype"],
         "data": "synthetic",
-        "config": {"workload": "%s: one worker's share of a %d-node graph, %d-way split, %d destinations, "
-                               "%d in-edges over %d resident source blocks, GAT %d heads x %d, in_dim %d"
-                               % (args.workload, w.N, w.P, layer.n, layer.E, w.P, w.H, w.D, w.f_in),
-                   "mode": args.mode, "scale": args.scale, "act": args.act, "dst_frac": args.dst_frac,
-                   "skip_untouched": args.skip_untouched},
-        "phases_ms": {"step_events": all_ms, "gat_fwd": fwd_ms, "gat_bwd": bwd_ms,
-                      "gat_bwd_kernel_wide": wide_ms, "gat_bwd_kernel_narrow": narrow_ms,
-                      "other (XW fwd+bwd, scores, begin/end)": all_ms - fwd_ms - bwd_ms},
-        "aggregation_only_edges_per_s": layer.E / ((fwd_ms + bwd_ms) * 1e-3),
-        "builder_s": layer.builder_s,
-        **({"subset_builder_s": layer.subset_s} if layer.subset else {}),
+        "config": {"workload": r["workload"], "mode": args.mode, "scale": args.scale, "act": args.act,
+                   "dst_frac": args.dst_frac, "errors": args.errors},
+        "phases_ms": r["phases_ms"],
+        "aggregation_only_edges_per_s": r["aggregation_only_edges_per_s"],
+        "builder_s": r["builder_s"],
+        **({"subset_builder_s": r["subset_builder_s"]} if "subset_builder_s" in r else {}),
         "roofline": {"bound": "hbm", "kernel": d["kernel"],
                      "achieved": d["alg_GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": d["alg_GBs"] / HBM_PEAK_GBS,
-                     "traffic": d["traffic_bytes"],
-                     # what actually crossed the L2 boundary per second, as a share of the same peak
-                     "traffic_frac": (d["traffic_bytes"] / (d["avg_ms"] / launches * 1e-3) / 1e9 / HBM_PEAK_GBS
-                                      if d["traffic_bytes"] else None),
+                     "frac": d["frac"],
+                     # beyond-L2 bytes per launch from the committed rocprofv3 counter summary of this
+                     # workload (not measured in this run; null when the kernel sources have changed since)
+                     "traffic": traffic, "traffic_source": traffic_src,
                      "alg_bytes_per_launch": d["alg_bytes"] / launches, "avg_launch_ms": d["avg_ms"] / launches,
                      "gather_volume_GBs": d["gather_volume_GBs"],
-                     "gather_volume_vs_measured_gather_ceiling":
-                         d["gather_volume_GBs"] / ceilings["random_row_gather_GBs"],
-                     "kernels": per_kernel},
-        "ceilings": ceilings,
+                     "calls": r["calls"],
+                     "note": "the forward launch is one kernel; the backward call is two gather kernels (sources "
+                             "with at least 4 (fp32) / 8 (bf16) edges, and the others); per-kernel durations: "
+                             "profiles/"},
     }
+    if not args.no_ceilings:
+        row_bytes = layer.F * (2 if w.dtype == torch.bfloat16 else 4)
+        res["ceilings"] = measure_ceilings(torch, 512 if row_bytes == 512 else 1024)   # the probe's two row sizes
+        res["roofline"]["gather_volume_vs_measured_gather_ceiling"] = \
+            d["gather_volume_GBs"] / res["ceilings"]["random_row_gather_GBs"]
     if not args.no_transform:
         res["transform"] = measure_transform(layer)
     if not args.no_cpu_baseline and not layer.subset:
-        res["cpu_baseline"] = cpu_baseline(layer, args.cpu_blocks)
+        res["cpu_baseline"], res["cpu_baseline_all_cores"] = cpu_baseline(layer, args.cpu_blocks)
+    layer.blocks.close()
+    del layer, w
+    torch.cuda.empty_cache()
+
+    if args.workload is None and args.scale == 1.0:
+        # the other configurations, one after the other, each with the memory to itself
+        configs = {}
+        configs["cfg2"] = time_sage(args, torch, sar, synth, min(args.steps, 10), min(args.warmup, 2))
+        torch.cuda.empty_cache()
+        for name, steps in (("cfg5", min(args.steps, 10)), ("cfg4", min(args.steps, 5))):
+            rr, ll, ww = time_gat(args, torch, sar, synth, name, steps, min(args.warmup, 2), False)
+            ll.blocks.close()
+            del ll, ww
+            torch.cuda.empty_cache()
+            configs[name] = rr
+        res["configs"] = configs
     print(json.dumps(res))
 
 

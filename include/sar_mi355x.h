@@ -79,6 +79,13 @@ typedef enum { SAR_ACT_NONE = 0, SAR_ACT_RELU = 1 } sar_act;
  * buffers zero them once, the skipped rows never change (the handle's `touched` lists name
  * the others).  Without this flag every row of dZ_q, dt_q is written (zeros where no edge). */
 #define SAR_BUILD_SKIP_UNTOUCHED 4
+/* The error E_{p->q} in the shape it is exchanged in (Alg. 2: worker p sends worker q the errors
+ * of the rows V_{p,q} it fetched, nothing else): every backward call on the handle takes dZ_q
+ * (and dt_q) with n_t_rows rows instead of n_src, row r belonging to source touched[r]
+ * (ascending local id).  Neither zero rows are written nor has a consumer to skip them; the
+ * receiver adds row r to its row touched[r] (t_rank gives the inverse map).  Needs
+ * SAR_BUILD_TRANSPOSE; implies that sources without an edge get nothing written. */
+#define SAR_BUILD_COMPACT 8
 
 typedef struct sar_blocks sar_blocks_t; /* opaque, library-owned */
 
@@ -99,6 +106,10 @@ typedef struct sar_blocks sar_blocks_t; /* opaque, library-owned */
  *   touched             = t_rows sorted ascending: V_{p,q} intersected with V_q,
  *                       the rows of Z_q a remote fetch would have to carry
  *                       (Alg. 1, "Fetch Z_{q->p}")        (NULL without TRANSPOSE)
+ *   t_rank              [n_src+1]: t_rank[j] = number of entries of touched below j, so
+ *                       touched[t_rank[j]] == j exactly when t_rank[j+1] > t_rank[j]: the
+ *                       row of a compact dZ_q that belongs to source j
+ *                                                          (NULL without TRANSPOSE)
  */
 typedef struct {
     int64_t n_dst, n_src, nnz;
@@ -111,13 +122,14 @@ typedef struct {
     const int32_t* t_rows;
     int64_t n_t_rows, n_t_long;
     const int32_t* touched;
+    const int32_t* t_rank;
 } sar_block_view;
 
 /* Text of the last error on this thread ("" if none).  Host pointer, valid until
  * the next failing call on the same thread. */
 const char* sar_last_error(void);
 
-/* ABI version of this header (currently 2). */
+/* ABI version of this header (currently 3). */
 int sar_version(void);
 
 /* ------------------------------------------------------------------ blocks
@@ -205,7 +217,8 @@ int sar_act_bwd(const void* h, const void* dH, int act, void* G, int dtype, int6
 /* Case 1 of Sec. 3.2 (the gradient of a sum does not need the features):
  * dZq[j,:] = sum_{(j->i) in block q} G[i,:] / (mean ? |N(i)| : 1).
  * dZq [n_src_q,F] of `dtype` is OVERWRITTEN (it is the error E_{p->q} of
- * Alg. 2).  G [n_dst,F] of `dtype`.  Needs SAR_BUILD_TRANSPOSE. */
+ * Alg. 2); on a SAR_BUILD_COMPACT handle it has n_t_rows rows, in `touched` order.
+ * G [n_dst,F] of `dtype`.  Needs SAR_BUILD_TRANSPOSE. */
 int sar_spmm_bwd_block(const sar_blocks_t* b, int q, const void* G, int mean, int dtype, int F,
                        void* dZq, void* stream);
 
@@ -213,6 +226,17 @@ int sar_spmm_bwd_block(const sar_blocks_t* b, int q, const void* G, int mean, in
  * sar_spmm_bwd_block calls).  dZq: host array [P] of device pointers. */
 int sar_spmm_bwd_all(const sar_blocks_t* b, const void* G, int mean, int dtype, int F,
                      void* const* dZq, void* stream);
+
+/* The owner's side of Alg. 2's error exchange (E_p = sum over workers q of E_{q->p}) for one
+ * received compact error: Ep[i,:] (+)= Eq[t_rank[i],:] for every row i that has a row in Eq
+ * (t_rank[i+1] > t_rank[i]); the other rows are left alone (accumulate != 0) or set to zero
+ * (accumulate == 0, which turns a compact error into a full-height one).
+ *   Eq      [n_t_rows, F] of `dtype`: dZ_q of a SAR_BUILD_COMPACT handle (may be NULL when no
+ *           row of the block is touched)
+ *   t_rank  device int32 [n+1]: the t_rank of the block the error came from (sar_block_view)
+ *   Ep      [n, F] of `dtype`, n = that block's n_src; must not alias Eq */
+int sar_error_add(const void* Eq, const int32_t* t_rank, int accumulate, void* Ep, int dtype, int64_t n,
+                  int F, void* stream);
 
 /* ------------------------------------------------------ Eq. 3: attention
  * e_{j->i} = LeakyReLU(a^T (z_i || z_j)) = LeakyReLU(s_i + t_j) per head with
@@ -284,7 +308,8 @@ int sar_gat_bwd_begin(const void* G, const void* out, const float* s, const floa
  * source gathers its destinations' G rows, so dZq is written once, without
  * atomics.  rec from sar_gat_bwd_begin; tq may be NULL, then t_j = <a_l, z_j> is
  * formed from the row the wavefront owns; a_l 16-byte aligned; work: scratch of
- * at least sar_gat_workspace_bytes, 16-byte aligned. */
+ * at least sar_gat_workspace_bytes, 16-byte aligned.  On a SAR_BUILD_COMPACT handle dZq and
+ * dtq have n_t_rows rows, row r for source touched[r]; Zq and tq stay full height. */
 int sar_gat_bwd_block(const sar_blocks_t* b, int q, const void* Zq, const void* G, const float* tq,
                       const float* rec, const float* a_l, int dtype, int H, int D, float slope,
                       void* dZq, float* dtq, float* ds, float* da_l, void* work, size_t work_bytes,
@@ -302,10 +327,14 @@ int sar_gat_bwd_all(const sar_blocks_t* b, const void* const* Zq, const void* G,
  * dZdst[i] = ds[i] a_r + dZadd[i] (OVERWRITTEN, `dtype`), da_r += sum_i ds[i] Zdst[i].
  * dZadd may be NULL (= 0); a worker passes its local block's dZq here to get
  * the whole error of its own rows, E_{p->p} plus the destination-score term,
- * in one tensor for Z_p.backward.  dZadd may alias dZdst. */
+ * in one tensor for Z_p.backward.  dZadd may alias dZdst.
+ * dZadd_rank: NULL when dZadd has one row per destination.  For a COMPACT dZadd (the local
+ * block's dZq of a SAR_BUILD_COMPACT handle) pass that block's t_rank (device int32
+ * [n_dst+1]): row i then receives dZadd[dZadd_rank[i]] if dZadd_rank[i+1] > dZadd_rank[i]
+ * and nothing otherwise; such a dZadd must not alias dZdst. */
 int sar_gat_bwd_end(const void* Zdst, const float* ds, const float* a_r, const void* dZadd,
-                    void* dZdst, float* da_r, int dtype, int64_t n_dst, int H, int D, void* work,
-                    size_t work_bytes, void* stream);
+                    const int32_t* dZadd_rank, void* dZdst, float* da_r, int dtype, int64_t n_dst, int H,
+                    int D, void* work, size_t work_bytes, void* stream);
 
 /* sar_gat_bwd_end for callers that cannot allocate device memory or take a workspace
  * along: code under HIP graph capture, tight serving loops, harnesses that forbid
@@ -321,8 +350,8 @@ int sar_gat_bwd_end(const void* Zdst, const float* ds, const float* a_r, const v
  * them.  The first call on a device looks up the array's device address (no allocation);
  * make that call outside graph capture. */
 int sar_gat_bwd_end_noalloc(const void* Zdst, const float* ds, const float* a_r, const void* dZadd,
-                            void* dZdst, float* da_r, int dtype, int64_t n_dst, int H, int D,
-                            void* stream);
+                            const int32_t* dZadd_rank, void* dZdst, float* da_r, int dtype, int64_t n_dst,
+                            int H, int D, void* stream);
 
 /* ------------------------------------------------- Eq. 1: Z = X W on MFMA */
 
@@ -342,45 +371,6 @@ int sar_linear_bwd(const void* X, const void* dZ, const float* W, float* dW, voi
                    int64_t n, int K, int F, void* work, size_t work_bytes, void* stream);
 
 int sar_linear_workspace_bytes(int64_t n, int K, int F, size_t* bytes);
-
-/* ------------------------------------------------------- bandwidth probes
- * Not part of the method: plain kernels that measure the ceilings the gather
- * kernels are held against on the machine at hand (the paper reports its own
- * kernels only relative to DGL, Sec. 4.1; these give the absolute yardstick).
- * The caller times them with events on `stream`.  sink: device float[1]. */
-
-/* Reads `bytes` at buf `reps` times with 16-byte lane accesses, grid-stride. */
-int sar_probe_stream_read(const void* buf, size_t bytes, int reps, float* sink, void* stream);
-
-/* dst[0..bytes) = src[0..bytes). */
-int sar_probe_copy(const void* src, void* dst, size_t bytes, void* stream);
-
-/* For every k < n_idx (in groups of 8 per wavefront) reads the whole row
- * rows[idx[k]] of row_bytes (1024 or 512) bytes; idx values must be in
- * [0, n_rows).  The access shape of the aggregation kernels without their
- * arithmetic. */
-int sar_probe_row_gather(const void* rows, int64_t n_rows, int row_bytes, const int32_t* idx,
-                         int64_t n_idx, float* sink, void* stream);
-
-/* The same gathers with writes mixed in: after every 8 gathered rows, writes_per_8 (0..8) of them
- * are written to consecutive rows of out, which must hold (n_idx / 8) * writes_per_8 rows.  The
- * read/write mix of the backward kernels without their arithmetic. */
-int sar_probe_gather_write(const void* rows, int64_t n_rows, int row_bytes, const int32_t* idx,
-                           int64_t n_idx, int writes_per_8, void* out, void* stream);
-
-/* ------------------------------------------------ per-kernel timing hooks
- * On rows of 256 values a backward launch (sar_gat_bwd_block / _all) is two
- * kernels: sources with at least 8 edges (bf16 rows) or 4 edges (fp32 rows), one
- * wavefront each, and the others, four per wavefront, followed by a fill of the
- * rows of the sources without an edge.  After sar_timing_begin(n) the next n
- * backward launches record HIP events around the first kernel and around the
- * rest on their launch stream.  Not thread safe; allocates n*3 events
- * (sar_timing_begin(0) frees them). */
-int sar_timing_begin(int max_records);
-/* *n = records filled so far. */
-int sar_timing_count(int* n);
-/* Durations of record k in milliseconds; waits for its last event. */
-int sar_timing_get(int k, float* wide_ms, float* narrow_ms);
 
 #ifdef __cplusplus
 }

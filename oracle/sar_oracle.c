@@ -175,3 +175,153 @@ void oracle_gat_online_block(int64_t n_dst, const int64_t* indptr, const int32_t
             }
         }
 }
+
+/* ------------------------------------------- the same loops on all host cores
+ *
+ * For the timed CPU baseline only: the loops above with an OpenMP `parallel
+ * for` over the rows that own the results, so that no two threads write the
+ * same element.  Forward: over destination rows (each owns its M, den, num).
+ * Backward: one loop over destination rows for what a destination owns (ds,
+ * dZdst, its share of da_r) and one over the source rows of the transposed
+ * index for what a source owns (dZq, dt, its share of da_l); the per-edge
+ * coefficient is recomputed in both.  The parameter gradients are summed per
+ * thread and added up in thread order.  tests/test_oracle_gat.py holds these
+ * against the serial loops.  Without OpenMP the pragmas vanish and the loops
+ * run on one core.
+ */
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+int oracle_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void oracle_par_gat_rowmax_block(int64_t n_dst, const int64_t* indptr, const int32_t* indices,
+                                 int64_t H, const double* s, const double* t, double slope,
+                                 double* M)
+{
+#pragma omp parallel for schedule(dynamic, 256)
+    for (int64_t i = 0; i < n_dst; ++i)
+        for (int64_t e = indptr[i]; e < indptr[i + 1]; ++e) {
+            int64_t j = indices[e];
+            for (int64_t h = 0; h < H; ++h) {
+                double ev = leaky(s[i * H + h] + t[j * H + h], slope);
+                if (ev > M[i * H + h]) M[i * H + h] = ev;
+            }
+        }
+}
+
+void oracle_par_gat_sums_block(int64_t n_dst, const int64_t* indptr, const int32_t* indices,
+                               int64_t H, int64_t D, const double* Zq, const double* s,
+                               const double* t, double slope, const double* M, double* den,
+                               double* num)
+{
+#pragma omp parallel for schedule(dynamic, 256)
+    for (int64_t i = 0; i < n_dst; ++i)
+        for (int64_t e = indptr[i]; e < indptr[i + 1]; ++e) {
+            int64_t j = indices[e];
+            for (int64_t h = 0; h < H; ++h) {
+                double ev = leaky(s[i * H + h] + t[j * H + h], slope);
+                double w = exp(ev - M[i * H + h]);
+                den[i * H + h] += w;
+                for (int64_t d = 0; d < D; ++d)
+                    num[(i * H + h) * D + d] += w * Zq[(j * H + h) * D + d];
+            }
+        }
+}
+
+/* du of one edge and head, and alpha through *alpha_out (the body of oracle_gat_bwd_block). */
+static double edge_du(const double* gi, const double* zj, int64_t D, double u, double Lih,
+                      double delta_ih, double slope, double* alpha_out)
+{
+    double alpha = exp(leaky(u, slope) - Lih);
+    double c = 0.0;
+    for (int64_t d = 0; d < D; ++d) c += gi[d] * zj[d];
+    *alpha_out = alpha;
+    return alpha * (c - delta_ih) * (u > 0.0 ? 1.0 : slope);
+}
+
+/* What the destinations own: ds[i] += du, dZdst[i] += du a_r, da_r += du z_i. */
+void oracle_par_gat_bwd_dst_block(int64_t n_dst, const int64_t* indptr, const int32_t* indices,
+                                  int64_t H, int64_t D, const double* Zdst, const double* Zq,
+                                  const double* G, const double* s, const double* t,
+                                  const double* L, const double* delta, const double* a_r,
+                                  double slope, double* dZdst, double* da_r, double* ds)
+{
+    const int nt = oracle_threads();
+    double* part = (double*)calloc((size_t)nt * H * D, sizeof(double));
+#pragma omp parallel
+    {
+#ifdef _OPENMP
+        double* mine = part + (size_t)omp_get_thread_num() * H * D;
+#else
+        double* mine = part;
+#endif
+#pragma omp for schedule(dynamic, 256)
+        for (int64_t i = 0; i < n_dst; ++i)
+            for (int64_t e = indptr[i]; e < indptr[i + 1]; ++e) {
+                int64_t j = indices[e];
+                for (int64_t h = 0; h < H; ++h) {
+                    const double* zi = Zdst + (i * H + h) * D;
+                    double alpha;
+                    double du = edge_du(G + (i * H + h) * D, Zq + (j * H + h) * D, D,
+                                        s[i * H + h] + t[j * H + h], L[i * H + h],
+                                        delta[i * H + h], slope, &alpha);
+                    ds[i * H + h] += du;
+                    for (int64_t d = 0; d < D; ++d) {
+                        dZdst[(i * H + h) * D + d] += du * a_r[h * D + d];
+                        mine[h * D + d] += du * zi[d];
+                    }
+                }
+            }
+    }
+    for (int k = 0; k < nt; ++k)
+        for (int64_t x = 0; x < H * D; ++x) da_r[x] += part[(size_t)k * H * D + x];
+    free(part);
+}
+
+/* What the sources own, over the transposed (source-major) index of the block:
+ * dZq[j] += alpha G_i + du a_l, dt[j] += du, da_l += du z_j. */
+void oracle_par_gat_bwd_src_block(int64_t n_src, const int64_t* t_indptr, const int32_t* t_indices,
+                                  int64_t H, int64_t D, const double* Zq, const double* G,
+                                  const double* s, const double* t, const double* L,
+                                  const double* delta, const double* a_l, double slope,
+                                  double* dZq, double* da_l, double* dt)
+{
+    const int nt = oracle_threads();
+    double* part = (double*)calloc((size_t)nt * H * D, sizeof(double));
+#pragma omp parallel
+    {
+#ifdef _OPENMP
+        double* mine = part + (size_t)omp_get_thread_num() * H * D;
+#else
+        double* mine = part;
+#endif
+#pragma omp for schedule(dynamic, 256)
+        for (int64_t j = 0; j < n_src; ++j)
+            for (int64_t e = t_indptr[j]; e < t_indptr[j + 1]; ++e) {
+                int64_t i = t_indices[e];
+                for (int64_t h = 0; h < H; ++h) {
+                    const double* gi = G + (i * H + h) * D;
+                    const double* zj = Zq + (j * H + h) * D;
+                    double alpha;
+                    double du = edge_du(gi, zj, D, s[i * H + h] + t[j * H + h], L[i * H + h],
+                                        delta[i * H + h], slope, &alpha);
+                    dt[j * H + h] += du;
+                    for (int64_t d = 0; d < D; ++d) {
+                        dZq[(j * H + h) * D + d] += alpha * gi[d] + du * a_l[h * D + d];
+                        mine[h * D + d] += du * zj[d];
+                    }
+                }
+            }
+    }
+    for (int k = 0; k < nt; ++k)
+        for (int64_t x = 0; x < H * D; ++x) da_l[x] += part[(size_t)k * H * D + x];
+    free(part);
+}

@@ -11,6 +11,9 @@ imports it.  The per-edge loops are in ``sar_oracle.c`` (plain C, doubles);
 this file holds the block builder (numpy sorts), the node-wise steps (numpy
 matmul) and the loops over blocks.
 
+The ``*_par`` functions are the same loops spread over all host cores (OpenMP), used only by the
+timed all-cores baseline and held against the serial ones in tests/test_oracle_gat.py.
+
 Parity pins (tests/test_oracle_*.py): brute-force dense masked softmax,
 finite differences, dense autograd (also of the whole layers with the residual
 weights of Eq. 2 and the non-linearity), degree counts, textbook CSR products,
@@ -44,7 +47,11 @@ def build(force: bool = False) -> str:
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         os.makedirs(os.path.dirname(_LIB), exist_ok=True)
         tmp = _LIB + ".%d.tmp" % os.getpid()
-        subprocess.check_call(["gcc", "-O2", "-shared", "-fPIC", "-o", tmp, _SRC, "-lm"])
+        # -fopenmp only serves the *_par_* loops of the timed all-cores baseline; a toolchain
+        # without it still builds everything (those loops then run on one core)
+        if subprocess.call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-o", tmp, _SRC, "-lm"],
+                           stderr=subprocess.DEVNULL) != 0:
+            subprocess.check_call(["gcc", "-O2", "-shared", "-fPIC", "-o", tmp, _SRC, "-lm"])
         os.replace(tmp, _LIB)
     return _LIB
 
@@ -279,6 +286,74 @@ def gat_bwd(blocks: Sequence[Block], Zdst, Zs, G, a_l, a_r, slope: float,
                                   _p(a_l, _f64p), _p(a_r, _f64p), ctypes.c_double(slope),
                                   _p(dZ, _f64p), _p(dZdst, _f64p), _p(da_l, _f64p),
                                   _p(da_r, _f64p), _p(ds, _f64p), _p(dt, _f64p))
+        dZs.append(dZ)
+        dts.append(dt)
+    return GatBackward(dZs, dZdst, da_l, da_r, ds, dts)
+
+
+def threads() -> int:
+    """Host threads the *_par functions below run on."""
+    return int(_c().oracle_threads())
+
+
+def gat_fwd_par(blocks: Sequence[Block], Zdst, Zs, a_l, a_r, slope: float) -> GatForward:
+    """gat_fwd with the per-edge loops spread over all host cores (destination rows in parallel).
+    For the timed baseline; held against gat_fwd in tests/test_oracle_gat.py."""
+    a_l, a_r = _d(a_l), _d(a_r)
+    H, D = a_l.shape
+    n_dst = blocks[0].n_dst
+    Zdst = _d(Zdst).reshape(n_dst, H, D)
+    Zs = [_d(Z).reshape(b.n_src, H, D) for b, Z in zip(blocks, Zs)]
+    s = gat_scores(Zdst, a_r)
+    t = [gat_scores(Z, a_l) for Z in Zs]
+    M = np.full((n_dst, H), -np.inf)
+    for b, tq in zip(blocks, t):
+        _c().oracle_par_gat_rowmax_block(ctypes.c_int64(n_dst), _p(b.indptr, _i64p), _p(b.indices, _i32p),
+                                         ctypes.c_int64(H), _p(s, _f64p), _p(tq, _f64p),
+                                         ctypes.c_double(slope), _p(M, _f64p))
+    den = np.zeros((n_dst, H))
+    num = np.zeros((n_dst, H, D))
+    for b, Z, tq in zip(blocks, Zs, t):
+        _c().oracle_par_gat_sums_block(ctypes.c_int64(n_dst), _p(b.indptr, _i64p), _p(b.indices, _i32p),
+                                       ctypes.c_int64(H), ctypes.c_int64(D), _p(Z, _f64p), _p(s, _f64p),
+                                       _p(tq, _f64p), ctypes.c_double(slope), _p(M, _f64p), _p(den, _f64p),
+                                       _p(num, _f64p))
+    has = den > 0
+    out = np.where(has[:, :, None], num / np.where(has, den, 1.0)[:, :, None], 0.0)
+    with np.errstate(divide="ignore"):
+        L = np.where(has, M + np.log(np.where(has, den, 1.0)), -np.inf)
+    return GatForward(out, L, s, t)
+
+
+def gat_bwd_par(blocks: Sequence[Block], Zdst, Zs, G, a_l, a_r, slope: float, fwd: GatForward) -> GatBackward:
+    """gat_bwd on all host cores: per block one loop over the destination rows (ds, dZdst, da_r)
+    and one over the source rows of the transposed index (dZ_q, dt_q, da_l)."""
+    a_l, a_r = _d(a_l), _d(a_r)
+    H, D = a_l.shape
+    n_dst = blocks[0].n_dst
+    Zdst = _d(Zdst).reshape(n_dst, H, D)
+    Zs = [_d(Z).reshape(b.n_src, H, D) for b, Z in zip(blocks, Zs)]
+    G = _d(G).reshape(n_dst, H, D)
+    delta = np.ascontiguousarray((G * fwd.out).sum(-1))
+    L = np.ascontiguousarray(np.where(np.isfinite(fwd.L), fwd.L, 0.0))
+    dZdst = np.zeros((n_dst, H, D))
+    da_l = np.zeros((H, D))
+    da_r = np.zeros((H, D))
+    ds = np.zeros((n_dst, H))
+    dZs, dts = [], []
+    for b, Z, tq in zip(blocks, Zs, fwd.t):
+        dZ = np.zeros((b.n_src, H, D))
+        dt = np.zeros((b.n_src, H))
+        _c().oracle_par_gat_bwd_dst_block(ctypes.c_int64(n_dst), _p(b.indptr, _i64p), _p(b.indices, _i32p),
+                                          ctypes.c_int64(H), ctypes.c_int64(D), _p(Zdst, _f64p), _p(Z, _f64p),
+                                          _p(G, _f64p), _p(fwd.s, _f64p), _p(tq, _f64p), _p(L, _f64p),
+                                          _p(delta, _f64p), _p(a_r, _f64p), ctypes.c_double(slope),
+                                          _p(dZdst, _f64p), _p(da_r, _f64p), _p(ds, _f64p))
+        _c().oracle_par_gat_bwd_src_block(ctypes.c_int64(b.n_src), _p(b.t_indptr, _i64p), _p(b.t_indices, _i32p),
+                                          ctypes.c_int64(H), ctypes.c_int64(D), _p(Z, _f64p), _p(G, _f64p),
+                                          _p(fwd.s, _f64p), _p(tq, _f64p), _p(L, _f64p), _p(delta, _f64p),
+                                          _p(a_l, _f64p), ctypes.c_double(slope), _p(dZ, _f64p), _p(da_l, _f64p),
+                                          _p(dt, _f64p))
         dZs.append(dZ)
         dts.append(dt)
     return GatBackward(dZs, dZdst, da_l, da_r, ds, dts)

@@ -1,4 +1,5 @@
-"""Build libsar_mi355x.so from csrc/ with hipcc for gfx950 (cross-compiles without a GPU)."""
+"""Build libsar_mi355x.so (the product) and libsar_bench.so (bench.py's bandwidth probes) from
+csrc/ with hipcc for gfx950 (cross-compiles without a GPU)."""
 from __future__ import annotations
 
 import os
@@ -9,7 +10,9 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsar_mi355x.so")
-SOURCES = ["builder.hip", "spmm.hip", "gat.hip", "linear.hip", "probe.hip"]
+SOURCES = ["builder.hip", "spmm.hip", "gat.hip", "linear.hip"]
+BENCH_LIB = os.path.join(HERE, "libsar_bench.so")
+BENCH_SOURCES = ["probe.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics",
@@ -44,14 +47,18 @@ def build(verbose: bool = False) -> str:
             print(err, file=sys.stderr)
         return obj
 
-    with ThreadPoolExecutor(max_workers=4) as pool:
-        objs = list(pool.map(compile_one, SOURCES))
-    tmp = LIB + ".%d.tmp" % os.getpid()
-    res = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs],
-                         capture_output=True, text=True)
-    if res.returncode != 0:
-        raise RuntimeError("link failed:\n" + res.stderr)
-    os.replace(tmp, LIB)
+    def link(objs, lib):
+        tmp = lib + ".%d.tmp" % os.getpid()
+        res = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs],
+                             capture_output=True, text=True)
+        if res.returncode != 0:
+            raise RuntimeError("link failed:\n" + res.stderr)
+        os.replace(tmp, lib)
+
+    with ThreadPoolExecutor(max_workers=5) as pool:
+        objs = list(pool.map(compile_one, SOURCES + BENCH_SOURCES))
+    link(objs[:len(SOURCES)], LIB)
+    link(objs[len(SOURCES):], BENCH_LIB)
     return LIB
 
 

@@ -31,7 +31,7 @@ int fail(int code, const char* fmt, ...)
 }  // namespace sar
 
 extern "C" const char* sar_last_error(void) { return sar::g_err; }
-extern "C" int sar_version(void) { return 2; }
+extern "C" int sar_version(void) { return 3; }
 
 namespace {
 
@@ -587,6 +587,8 @@ int derive(sar_blocks* h, hipStream_t st)
     const int P = h->P;
     const int64_t n_dst = h->n_dst;
     DeviceTemps tmp;
+    if ((h->flags & SAR_BUILD_COMPACT) && !(h->flags & SAR_BUILD_TRANSPOSE))
+        return sar::fail(SAR_ERR_INVALID_ARG, "SAR_BUILD_COMPACT needs SAR_BUILD_TRANSPOSE");
 
     int64_t nnz_total = 0, n_src_total = 0, n_src_max = 0;
     for (auto& b : h->blk) {
@@ -788,8 +790,14 @@ int derive(sar_blocks* h, hipStream_t st)
         SAR_LAUNCH_CHECK();
         SAR_HIP(hipMemsetAsync(pos + n_src_total, 0, sizeof(int32_t), st));
         SAR_TRY(exclusive_scan(pos, pos, n_src_total + 1, st, tmp));
+        // t_rank[j] = number of touched sources below j, per block (the same scan, rebased)
+        int32_t* t_rank_all = nullptr;
+        SAR_TRY(own(h, &t_rank_all, n_src_total + P));
         for (int q = 0; q < P; ++q) {
             Block& b = h->blk[q];
+            b.t_rank = t_rank_all + coff[q] + q;
+            k_rebase<<<grid_for(b.n_src + 1), kThreads, 0, st>>>(pos + coff[q], b.n_src + 1, b.t_rank);
+            SAR_LAUNCH_CHECK();
             if (b.n_t_rows == 0) continue;
             k_compact<<<grid_for(b.n_src), kThreads, 0, st>>>(b.t_indptr, pos + coff[q], b.n_src,
                                                               (int32_t)t_base[q], b.touched);
@@ -943,6 +951,10 @@ void destroy(sar_blocks* h)
 
 }  // namespace
 
+namespace {
+constexpr int kKnownFlags = SAR_BUILD_TRANSPOSE | SAR_BUILD_FUSED | SAR_BUILD_SKIP_UNTOUCHED | SAR_BUILD_COMPACT;
+}
+
 extern "C" int sar_blocks_build(const void* src, const void* dst, int idx_bytes, int64_t E,
                                 const int32_t* part, int64_t N, int P, int p, int flags, void* stream,
                                 sar_blocks_t** out)
@@ -954,7 +966,7 @@ extern "C" int sar_blocks_build(const void* src, const void* dst, int idx_bytes,
     SAR_CHECK_ARG(E == 0 || (src && dst), "src/dst is null");
     SAR_CHECK_ARG(part != nullptr, "part is null");
     SAR_CHECK_ARG(P >= 1 && p >= 0 && p < P, "need 0 <= p < P, got p=%d P=%d", p, P);
-    SAR_CHECK_ARG((flags & ~(SAR_BUILD_TRANSPOSE | SAR_BUILD_FUSED | SAR_BUILD_SKIP_UNTOUCHED)) == 0, "unknown flags 0x%x", flags);
+    SAR_CHECK_ARG((flags & ~kKnownFlags) == 0, "unknown flags 0x%x", flags);
     if (P > SAR_MAX_BLOCKS)
         return sar::fail(SAR_ERR_UNSUPPORTED, "P=%d exceeds SAR_MAX_BLOCKS=%d", P, SAR_MAX_BLOCKS);
     if (E >= ((int64_t)1 << 31) || N >= ((int64_t)1 << 31))
@@ -981,7 +993,7 @@ extern "C" int sar_blocks_wrap(int P, int64_t n_dst, const int64_t* n_src, const
     *out = nullptr;
     SAR_CHECK_ARG(P >= 1 && n_dst >= 0, "need P >= 1 and n_dst >= 0");
     SAR_CHECK_ARG(n_src && indptr && indices, "n_src/indptr/indices is null");
-    SAR_CHECK_ARG((flags & ~(SAR_BUILD_TRANSPOSE | SAR_BUILD_FUSED | SAR_BUILD_SKIP_UNTOUCHED)) == 0, "unknown flags 0x%x", flags);
+    SAR_CHECK_ARG((flags & ~kKnownFlags) == 0, "unknown flags 0x%x", flags);
     if (P > SAR_MAX_BLOCKS)
         return sar::fail(SAR_ERR_UNSUPPORTED, "P=%d exceeds SAR_MAX_BLOCKS=%d", P, SAR_MAX_BLOCKS);
     for (int q = 0; q < P; ++q) {
@@ -1057,6 +1069,7 @@ extern "C" int sar_blocks_get(const sar_blocks_t* b, int q, sar_block_view* v)
     v->n_t_rows = k.n_t_rows;
     v->n_t_long = k.n_t_long;
     v->touched = k.touched;
+    v->t_rank = k.t_rank;
     return SAR_OK;
 }
 
@@ -1081,7 +1094,7 @@ extern "C" int sar_blocks_subset(const sar_blocks_t* b, const int32_t* dst_ids, 
     SAR_CHECK_ARG(b != nullptr, "handle is null");
     SAR_CHECK_ARG(n_sub >= 0 && n_sub < ((int64_t)1 << 31), "n_sub must be in [0, 2^31)");
     SAR_CHECK_ARG(n_sub == 0 || dst_ids != nullptr, "dst_ids is null");
-    SAR_CHECK_ARG((flags & ~(SAR_BUILD_TRANSPOSE | SAR_BUILD_FUSED | SAR_BUILD_SKIP_UNTOUCHED)) == 0, "unknown flags 0x%x", flags);
+    SAR_CHECK_ARG((flags & ~kKnownFlags) == 0, "unknown flags 0x%x", flags);
     hipStream_t st = sar::as_stream(stream);
     sar_blocks* h = new (std::nothrow) sar_blocks();
     if (!h) return sar::fail(SAR_ERR_HIP, "out of host memory");

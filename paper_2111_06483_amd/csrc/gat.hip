@@ -298,6 +298,7 @@ struct BwdArgs {
     const float* t[SAR_MAX_BLOCKS];
     void* dZ[SAR_MAX_BLOCKS];
     float* dt[SAR_MAX_BLOCKS];
+    const int32_t* rank[SAR_MAX_BLOCKS];       // compact outputs: row of dZ / dt of source j (null: j)
 };
 
 struct BwdScalars {
@@ -427,8 +428,9 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd(BwdArgs tabs, BwdSca
             v[x] = fmaf(ac.dt, al[x], ac.dz[x]);
             dal[x] = fmaf(ac.dt, zj[x], dal[x]);
         }
-        Vec<T>::store(static_cast<T*>(tabs.dZ[q]) + (int64_t)j * a.ldz + lm.gl * VEC, v);
-        if ((lm.gl % lm.lph) == 0) tabs.dt[q][(int64_t)j * a.ldh + lm.h] = ac.dt;
+        const int64_t jo = tabs.rank[q] ? tabs.rank[q][j] : j;
+        Vec<T>::store(static_cast<T*>(tabs.dZ[q]) + jo * a.ldz + lm.gl * VEC, v);
+        if ((lm.gl % lm.lph) == 0) tabs.dt[q][jo * a.ldh + lm.h] = ac.dt;
     };
 
     for (int64_t r = blockIdx.x; r < a.n_long; r += gridDim.x) {
@@ -549,6 +551,32 @@ __global__ __launch_bounds__(kGatherThreads) void k_scores(const T* __restrict__
     }
 }
 
+// The same for head widths that do not fill whole 16-byte lane pieces: one thread per
+// (node, head), element-wise reads.  Scores only; the aggregation kernels do not take such rows.
+template <typename T>
+__global__ __launch_bounds__(256) void k_scores_any(const T* __restrict__ Z, int64_t n, int H, int D,
+                                                    const float* __restrict__ avec, float* __restrict__ score,
+                                                    const float* __restrict__ avec2, float* __restrict__ score2)
+{
+    const int64_t total = n * H;
+    for (int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x; k < total; k += (int64_t)gridDim.x * 256) {
+        const int h = (int)(k % H);
+        const T* z = Z + k * D;
+        float c = 0.f, c2 = 0.f;
+        for (int d = 0; d < D; ++d) {
+            float v;
+            if constexpr (sizeof(T) == 2)
+                v = __uint_as_float((uint32_t)z[d].bits << 16);
+            else
+                v = z[d];
+            c = fmaf(avec[h * D + d], v, c);
+            if (avec2) c2 = fmaf(avec2[h * D + d], v, c2);
+        }
+        score[k] = c;
+        if (avec2) score2[k] = c2;
+    }
+}
+
 __global__ __launch_bounds__(256) void k_fwd_begin(float* __restrict__ m, float* __restrict__ l,
                                                    float* __restrict__ acc, int64_t n_h, int64_t n_f)
 {
@@ -636,7 +664,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_bwd_begin(const T* Gr, const
 template <typename T, int G>
 __global__ __launch_bounds__(kGatherThreads) void k_bwd_end(const T* __restrict__ Zdst, const float* __restrict__ ds,
                                                             const float* __restrict__ a_r, const T* dZadd,
-                                                            T* dZdst,
+                                                            const int32_t* __restrict__ add_rank, T* dZdst,
                                                             float* __restrict__ partial, int64_t n, int H, int D,
                                                             int F, int ldz, int ldh)
 {
@@ -659,8 +687,14 @@ __global__ __launch_bounds__(kGatherThreads) void k_bwd_end(const T* __restrict_
         const float d = ds[v * ldh + lm.h];
         float z[VEC], o[VEC];
         Vec<T>::unpack(Vec<T>::load(Zdst + v * ldz + lm.gl * VEC), z);
-        if (dZadd) {
-            Vec<T>::unpack(Vec<T>::load(dZadd + v * ldz + lm.gl * VEC), o);
+        int64_t va = v;
+        bool add = dZadd != nullptr;
+        if (add && add_rank) {
+            va = add_rank[v];
+            add = add_rank[v + 1] > (int32_t)va;
+        }
+        if (add) {
+            Vec<T>::unpack(Vec<T>::load(dZadd + va * ldz + lm.gl * VEC), o);
         } else {
 #pragma unroll
             for (int x = 0; x < VEC; ++x) o[x] = 0.f;
@@ -874,19 +908,6 @@ int launch_fwd(const FwdArgs& a, const PtrTab& zt, const PtrTab& tt, int P, hipS
     return SAR_OK;
 }
 
-// Optional per-kernel timing of the backward launches (two kernels per launch on the
-// F = 256 path): event triples recorded on the launch stream, read back afterwards.
-struct BwdTiming {
-    std::vector<hipEvent_t> ev;   // 3 per record: before wide, between, after narrow
-    int used = 0, capacity = 0;
-};
-BwdTiming g_timing;
-
-void timing_mark(int which, hipStream_t st)
-{
-    if (g_timing.used < g_timing.capacity) (void)hipEventRecord(g_timing.ev[3 * g_timing.used + which], st);
-}
-
 // the padded geometry has no four-sources-per-wavefront kernel: every source takes the wide one
 template <typename T, int LPH, bool ALL>
 int launch_bwd_f256_padded(const BwdArgs& tabs, const BwdScalars& a, unsigned* grid_out, hipStream_t st)
@@ -898,6 +919,7 @@ int launch_bwd_f256_padded(const BwdArgs& tabs, const BwdScalars& a, unsigned* g
     for (int q = 0; q < SAR_MAX_BLOCKS; ++q) {
         t.t_indptr[q] = tabs.t_indptr[q]; t.t_indices[q] = tabs.t_indices[q];
         t.Z[q] = tabs.Z[q]; t.t[q] = tabs.t[q]; t.dZ[q] = tabs.dZ[q]; t.dt[q] = tabs.dt[q];
+        t.rank[q] = tabs.rank[q];
     }
     f256::BwdP p{};
     p.rows = a.rows; p.n_rows = a.n_rows; p.n_long = a.n_long;
@@ -905,12 +927,8 @@ int launch_bwd_f256_padded(const BwdArgs& tabs, const BwdScalars& a, unsigned* g
     p.H = a.H; p.tag_shift = a.tag_shift; p.slope = a.slope;
     p.ld = a.ldz; p.ldh = a.ldh; p.D = a.D;
     const unsigned g = persistent_grid_for(p.n_rows, p.n_long, resident_wide);
-    timing_mark(0, st);
     wide<<<g, kGatherThreads, 0, st>>>(t, p);
     SAR_LAUNCH_CHECK();
-    timing_mark(1, st);
-    timing_mark(2, st);
-    if (g_timing.used < g_timing.capacity) ++g_timing.used;
     *grid_out = g;
     return SAR_OK;
 }
@@ -978,6 +996,7 @@ int launch_bwd_f256(const BwdArgs& tabs, const BwdScalars& a, unsigned* grid_out
     for (int q = 0; q < SAR_MAX_BLOCKS; ++q) {
         t.t_indptr[q] = tabs.t_indptr[q]; t.t_indices[q] = tabs.t_indices[q];
         t.Z[q] = tabs.Z[q]; t.t[q] = tabs.t[q]; t.dZ[q] = tabs.dZ[q]; t.dt[q] = tabs.dt[q];
+        t.rank[q] = tabs.rank[q];
     }
     f256::BwdP p{};
     p.rows = a.rows; p.n_rows = a.n_wide; p.n_long = std::min(a.n_long, a.n_wide);
@@ -989,7 +1008,6 @@ int launch_bwd_f256(const BwdArgs& tabs, const BwdScalars& a, unsigned* grid_out
     // rows of dt_q scattered through the array cost more to zero one by one than the whole array
     // does in one sweep ahead of the kernels that write the other rows.
     const bool sweep_dt = a.n_src_host != nullptr && (a.n_rows - n_edged) * 4 > a.n_rows;
-    timing_mark(0, st);
     if (sweep_dt) {
         for (int q = 0; q < a.n_blocks; ++q) {
             const int64_t n = a.n_src_host[q] * a.H;
@@ -1004,7 +1022,6 @@ int launch_bwd_f256(const BwdArgs& tabs, const BwdScalars& a, unsigned* grid_out
         wide<<<g_wide, kGatherThreads, 0, st>>>(t, p);
         SAR_LAUNCH_CHECK();
     }
-    timing_mark(1, st);
     if (n_edged > a.n_wide) {
         // the other sources with edges, four per wavefront
         const int64_t n = n_edged - a.n_wide;
@@ -1019,8 +1036,6 @@ int launch_bwd_f256(const BwdArgs& tabs, const BwdScalars& a, unsigned* grid_out
                                                        a.tag_shift);
         SAR_LAUNCH_CHECK();
     }
-    timing_mark(2, st);
-    if (g_timing.used < g_timing.capacity) ++g_timing.used;
     *grid_out = g_wide + g_narrow;
     return SAR_OK;
 }
@@ -1066,11 +1081,29 @@ size_t workspace_bytes(int F) { return (size_t)2 * kMaxPersistentWGs * F * sizeo
 int sar::gat_scores2(const void* Z, int dtype, int64_t n, int H, int D, const float* a, float* score,
                      const float* a2, float* score2, void* stream)
 {
+    if (dtype != SAR_F32 && dtype != SAR_BF16)
+        return sar::fail(SAR_ERR_UNSUPPORTED, "dtype %d is neither SAR_F32 nor SAR_BF16", dtype);
+    SAR_CHECK_ARG(H > 0 && D > 0, "H and D must be positive (H=%d, D=%d)", H, D);
+    SAR_CHECK_ARG((a2 == nullptr) == (score2 == nullptr), "the second vector and its output go together");
+    if (a2 && D % (dtype == SAR_F32 ? 4 : 8) != 0) {
+        // (only the transform asks for two vectors at once; any head width is a valid product)
+        SAR_CHECK_ARG(n >= 0, "n is negative");
+        if (n == 0) return SAR_OK;
+        SAR_CHECK_ARG(Z && a && score, "Z, a or score is null");
+        const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>((n * H + 255) / 256, kMaxPersistentWGs * 4));
+        if (dtype == SAR_F32)
+            k_scores_any<float><<<grid, 256, 0, sar::as_stream(stream)>>>(static_cast<const float*>(Z), n, H, D, a,
+                                                                          score, a2, score2);
+        else
+            k_scores_any<bf16_t><<<grid, 256, 0, sar::as_stream(stream)>>>(static_cast<const bf16_t*>(Z), n, H, D, a,
+                                                                           score, a2, score2);
+        SAR_LAUNCH_CHECK();
+        return SAR_OK;
+    }
     SAR_TRY(check_shape(dtype, H, D));
     SAR_CHECK_ARG(n >= 0, "n is negative");
     if (n == 0) return SAR_OK;
     SAR_CHECK_ARG(Z && a && score, "Z, a or score is null");
-    SAR_CHECK_ARG((a2 == nullptr) == (score2 == nullptr), "the second vector and its output go together");
     SAR_CHECK_ARG(aligned16(Z), "Z must be 16-byte aligned");
     const int F = H * D;
     const HeadGroups hg = head_groups(dtype, H, D);
@@ -1323,7 +1356,7 @@ extern "C" int sar_gat_bwd_block(const sar_blocks_t* b, int q, const void* Zq, c
     SAR_TRY(bwd_common_checks(b, dtype, H, D, G, rec, a_l, ds, da_l, work, work_bytes));
     SAR_CHECK_ARG(q >= 0 && q < b->P, "block %d out of range [0,%d)", q, b->P);
     const sar::Block& k = b->blk[q];
-    if (k.n_src == 0) return SAR_OK;
+    if (k.n_src == 0 || (sar::skips_untouched(b->flags) && k.n_t_rows == 0)) return SAR_OK;
     SAR_CHECK_ARG(Zq && dZq && dtq, "a tensor argument is null");
     SAR_CHECK_ARG(aligned16(Zq) && aligned16(dZq), "Zq and dZq must be 16-byte aligned");
     hipStream_t st = sar::as_stream(stream);
@@ -1337,10 +1370,11 @@ extern "C" int sar_gat_bwd_block(const sar_blocks_t* b, int q, const void* Zq, c
         tabs.t[0] = tq ? tq + h0 : nullptr;
         tabs.dZ[0] = shift(dZq, f0 * hg.fb);
         tabs.dt[0] = dtq + h0;
+        tabs.rank[0] = (b->flags & SAR_BUILD_COMPACT) ? k.t_rank : nullptr;
         BwdScalars a{};
         a.rows = reinterpret_cast<const uint32_t*>(k.t_rows);
         // sources without edges come last and get dZ = 0, dt = 0, unless the handle skips them
-        a.n_rows = (b->flags & SAR_BUILD_SKIP_UNTOUCHED) ? k.n_t_rows : k.n_src;
+        a.n_rows = sar::skips_untouched(b->flags) ? k.n_t_rows : k.n_src;
         a.n_long = k.n_t_long;
         a.n_wide = dtype == SAR_F32 ? k.n_t_wide_f32 : k.n_t_wide;
         a.n_touched = k.n_t_rows;
@@ -1364,7 +1398,7 @@ extern "C" int sar_gat_bwd_all(const sar_blocks_t* b, const void* const* Zq, con
     SAR_CHECK_ARG(Zq && dZq && dtq, "a pointer table is null");
     hipStream_t st = sar::as_stream(stream);
     for (int q = 0; q < b->P; ++q) {
-        if (b->blk[q].n_src == 0) continue;
+        if (b->blk[q].n_src == 0 || (sar::skips_untouched(b->flags) && b->blk[q].n_t_rows == 0)) continue;
         SAR_CHECK_ARG(Zq[q] && (!tq || tq[q]) && dZq[q] && dtq[q], "a tensor of block %d is null", q);
         SAR_CHECK_ARG(aligned16(Zq[q]) && aligned16(dZq[q]), "Zq[%d] and dZq[%d] must be 16-byte aligned", q, q);
     }
@@ -1383,12 +1417,13 @@ extern "C" int sar_gat_bwd_all(const sar_blocks_t* b, const void* const* Zq, con
             tabs.t[q] = tq ? tq[q] + h0 : nullptr;
             tabs.dZ[q] = shift(dZq[q], f0 * hg.fb);
             tabs.dt[q] = dtq[q] + h0;
+            tabs.rank[q] = (b->flags & SAR_BUILD_COMPACT) ? k.t_rank : nullptr;
         }
         BwdScalars a{};
         a.rows = b->ft_rows;
         a.n_rows = 0;
         for (int q = 0; q < b->P; ++q) a.n_rows += b->blk[q].n_src;
-        if (b->flags & SAR_BUILD_SKIP_UNTOUCHED) a.n_rows = b->n_ft_rows;
+        if (sar::skips_untouched(b->flags)) a.n_rows = b->n_ft_rows;
         a.n_wide = dtype == SAR_F32 ? b->n_ft_wide_f32 : b->n_ft_wide;
         a.n_touched = b->n_ft_rows;
         a.n_src_host = n_src_all;
@@ -1435,8 +1470,8 @@ int scratch_of(float** out)
 }
 
 // partial: room for one row of hg.Fg sums per workgroup; partial_floats = its size in values.
-int bwd_end_impl(const void* Zdst, const float* ds, const float* a_r, const void* dZadd, void* dZdst,
-                 float* da_r, int dtype, int64_t n_dst, int H, int D, float* partial, size_t partial_floats,
+int bwd_end_impl(const void* Zdst, const float* ds, const float* a_r, const void* dZadd,
+                 const int32_t* dZadd_rank, void* dZdst, float* da_r, int dtype, int64_t n_dst, int H, int D, float* partial, size_t partial_floats,
                  hipStream_t st)
 {
     const int F = H * D;
@@ -1452,13 +1487,13 @@ int bwd_end_impl(const void* Zdst, const float* ds, const float* a_r, const void
         if (dtype == SAR_F32) {
             SAR_DISPATCH_G(float, hg.Fg, (k_bwd_end<float, kG><<<grid, kGatherThreads, 0, st>>>(
                                               static_cast<const float*>(Zdst) + f0, ds + h0, a_r + f0,
-                                              dZadd ? static_cast<const float*>(dZadd) + f0 : nullptr,
+                                              dZadd ? static_cast<const float*>(dZadd) + f0 : nullptr, dZadd_rank,
                                               static_cast<float*>(dZdst) + f0, partial, n_dst, hg.Hg,
                                               D, hg.Fg, F, H)));
         } else {
             SAR_DISPATCH_G(bf16_t, hg.Fg, (k_bwd_end<bf16_t, kG><<<grid, kGatherThreads, 0, st>>>(
                                                static_cast<const bf16_t*>(Zdst) + f0, ds + h0, a_r + f0,
-                                               dZadd ? static_cast<const bf16_t*>(dZadd) + f0 : nullptr,
+                                               dZadd ? static_cast<const bf16_t*>(dZadd) + f0 : nullptr, dZadd_rank,
                                                static_cast<bf16_t*>(dZdst) + f0, partial, n_dst,
                                                hg.Hg, D, hg.Fg, F, H)));
         }
@@ -1469,9 +1504,10 @@ int bwd_end_impl(const void* Zdst, const float* ds, const float* a_r, const void
     return SAR_OK;
 }
 
-int bwd_end_checks(const void* Zdst, const float* ds, const float* a_r, const void* dZadd, void* dZdst,
-                   float* da_r, int dtype, int64_t n_dst, int H, int D)
+int bwd_end_checks(const void* Zdst, const float* ds, const float* a_r, const void* dZadd,
+                   const int32_t* dZadd_rank, void* dZdst, float* da_r, int dtype, int64_t n_dst, int H, int D)
 {
+    SAR_CHECK_ARG(!dZadd_rank || (dZadd && dZadd != dZdst), "dZadd_rank needs a dZadd that is not dZdst");
     SAR_TRY(check_shape(dtype, H, D));
     SAR_CHECK_ARG(n_dst >= 0, "n_dst is negative");
     if (n_dst == 0) return SAR_OK;
@@ -1484,58 +1520,26 @@ int bwd_end_checks(const void* Zdst, const float* ds, const float* a_r, const vo
 }  // namespace
 
 extern "C" int sar_gat_bwd_end(const void* Zdst, const float* ds, const float* a_r, const void* dZadd,
-                               void* dZdst, float* da_r, int dtype, int64_t n_dst, int H, int D, void* work,
-                               size_t work_bytes, void* stream)
+                               const int32_t* dZadd_rank, void* dZdst, float* da_r, int dtype, int64_t n_dst,
+                               int H, int D, void* work, size_t work_bytes, void* stream)
 {
-    SAR_TRY(bwd_end_checks(Zdst, ds, a_r, dZadd, dZdst, da_r, dtype, n_dst, H, D));
+    SAR_TRY(bwd_end_checks(Zdst, ds, a_r, dZadd, dZadd_rank, dZdst, da_r, dtype, n_dst, H, D));
     if (n_dst == 0) return SAR_OK;
     SAR_CHECK_ARG(work != nullptr && aligned16(work), "work is null or not 16-byte aligned");
     const size_t need = workspace_bytes(256);
     SAR_CHECK_ARG(work_bytes >= need, "work_bytes=%zu is below the %zu bytes required", work_bytes, need);
-    return bwd_end_impl(Zdst, ds, a_r, dZadd, dZdst, da_r, dtype, n_dst, H, D, static_cast<float*>(work),
-                        work_bytes / sizeof(float), sar::as_stream(stream));
+    return bwd_end_impl(Zdst, ds, a_r, dZadd, dZadd_rank, dZdst, da_r, dtype, n_dst, H, D,
+                        static_cast<float*>(work), work_bytes / sizeof(float), sar::as_stream(stream));
 }
 
 extern "C" int sar_gat_bwd_end_noalloc(const void* Zdst, const float* ds, const float* a_r, const void* dZadd,
-                                       void* dZdst, float* da_r, int dtype, int64_t n_dst, int H, int D,
-                                       void* stream)
+                                       const int32_t* dZadd_rank, void* dZdst, float* da_r, int dtype,
+                                       int64_t n_dst, int H, int D, void* stream)
 {
-    SAR_TRY(bwd_end_checks(Zdst, ds, a_r, dZadd, dZdst, da_r, dtype, n_dst, H, D));
+    SAR_TRY(bwd_end_checks(Zdst, ds, a_r, dZadd, dZadd_rank, dZdst, da_r, dtype, n_dst, H, D));
     if (n_dst == 0) return SAR_OK;
     float* partial = nullptr;
     SAR_TRY(scratch_of(&partial));
-    return bwd_end_impl(Zdst, ds, a_r, dZadd, dZdst, da_r, dtype, n_dst, H, D, partial, kScratchFloats,
-                        sar::as_stream(stream));
-}
-
-extern "C" int sar_timing_begin(int max_records)
-{
-    SAR_CHECK_ARG(max_records >= 0 && max_records <= 4096, "max_records must be in [0,4096]");
-    for (hipEvent_t e : g_timing.ev) (void)hipEventDestroy(e);
-    g_timing.ev.clear();
-    g_timing.used = g_timing.capacity = 0;
-    for (int k = 0; k < 3 * max_records; ++k) {
-        hipEvent_t e;
-        SAR_HIP(hipEventCreate(&e));
-        g_timing.ev.push_back(e);
-    }
-    g_timing.capacity = max_records;
-    return SAR_OK;
-}
-
-extern "C" int sar_timing_count(int* n)
-{
-    SAR_CHECK_ARG(n != nullptr, "n is null");
-    *n = g_timing.used;
-    return SAR_OK;
-}
-
-extern "C" int sar_timing_get(int k, float* wide_ms, float* narrow_ms)
-{
-    SAR_CHECK_ARG(k >= 0 && k < g_timing.used, "record %d out of range [0,%d)", k, g_timing.used);
-    SAR_CHECK_ARG(wide_ms && narrow_ms, "an output pointer is null");
-    SAR_HIP(hipEventSynchronize(g_timing.ev[3 * k + 2]));
-    SAR_HIP(hipEventElapsedTime(wide_ms, g_timing.ev[3 * k], g_timing.ev[3 * k + 1]));
-    SAR_HIP(hipEventElapsedTime(narrow_ms, g_timing.ev[3 * k + 1], g_timing.ev[3 * k + 2]));
-    return SAR_OK;
+    return bwd_end_impl(Zdst, ds, a_r, dZadd, dZadd_rank, dZdst, da_r, dtype, n_dst, H, D, partial,
+                        kScratchFloats, sar::as_stream(stream));
 }

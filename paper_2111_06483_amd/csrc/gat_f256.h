@@ -353,6 +353,7 @@ struct BwdTabs {
     const float* t[SAR_MAX_BLOCKS];
     void* dZ[SAR_MAX_BLOCKS];
     float* dt[SAR_MAX_BLOCKS];
+    const int32_t* rank[SAR_MAX_BLOCKS];   // compact outputs: row of dZ / dt that source j owns (null: j itself)
 };
 
 struct BwdP {
@@ -467,8 +468,9 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_f256(BwdTabs tabs, B
             v[x] = fmaf(dt, al[x], ac.dz[x]);
             dal[x] = fmaf(dt, zj[x], dal[x]);
         }
-        store_lane<T, PAD>(static_cast<T*>(tabs.dZ[q]) + (int64_t)j * ld, foff, on, v);
-        if (k == 0) tabs.dt[q][(int64_t)j * ldh + h] = dt;
+        const int64_t jo = tabs.rank[q] ? tabs.rank[q][j] : j;
+        store_lane<T, PAD>(static_cast<T*>(tabs.dZ[q]) + jo * ld, foff, on, v);
+        if (k == 0) tabs.dt[q][jo * ldh + h] = dt;
     };
 
     for (int64_t r = blockIdx.x; r < a.n_long; r += gridDim.x) {
@@ -602,6 +604,7 @@ __global__ __launch_bounds__(kGatherThreads, 4) void k_gat_bwd_narrow(BwdTabs ta
     __shared__ float* s_dt[SAR_MAX_BLOCKS];
     __shared__ const int32_t* s_ip[SAR_MAX_BLOCKS];
     __shared__ const int32_t* s_ix[SAR_MAX_BLOCKS];
+    __shared__ const int32_t* s_rank[SAR_MAX_BLOCKS];
     for (int f = threadIdx.x; f < kF; f += kGatherThreads) s_al[f] = a.a_l[f];
     if (threadIdx.x < SAR_MAX_BLOCKS) {
         s_Z[threadIdx.x] = tabs.Z[threadIdx.x];
@@ -610,6 +613,7 @@ __global__ __launch_bounds__(kGatherThreads, 4) void k_gat_bwd_narrow(BwdTabs ta
         s_dt[threadIdx.x] = tabs.dt[threadIdx.x];
         s_ip[threadIdx.x] = tabs.t_indptr[threadIdx.x];
         s_ix[threadIdx.x] = tabs.t_indices[threadIdx.x];
+        s_rank[threadIdx.x] = tabs.rank[threadIdx.x];
     }
     __syncthreads();
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
@@ -630,7 +634,7 @@ __global__ __launch_bounds__(kGatherThreads, 4) void k_gat_bwd_narrow(BwdTabs ta
     // "indices -> G rows" remains as a dependent chain per row.
     struct Meta {
         int q;
-        int64_t j;
+        int64_t j, jo;      // source row, and the row of dZ / dt it owns
         int beg, end;
         typename Row16<T>::Raw z;
     };
@@ -640,6 +644,7 @@ __global__ __launch_bounds__(kGatherThreads, 4) void k_gat_bwd_narrow(BwdTabs ta
         m.j = (int64_t)(id & mask);
         m.beg = s_ip[m.q][m.j];
         m.end = s_ip[m.q][m.j + 1];
+        m.jo = s_rank[m.q] ? (int64_t)s_rank[m.q][m.j] : m.j;
         m.z = Row16<T>::load(static_cast<const T*>(s_Z[m.q]) + m.j * kF + k * 16);
         return m;
     };
@@ -707,8 +712,8 @@ __global__ __launch_bounds__(kGatherThreads, 4) void k_gat_bwd_narrow(BwdTabs ta
             v[x] = fmaf(dt, s_al[k * 16 + x], dz[x]);
             my_dal[x] = fmaf(dt, zj[x], my_dal[x]);
         }
-        Row16<T>::store(static_cast<T*>(s_dZ[q]) + j * kF + k * 16, v);
-        if (head_lead) s_dt[q][j * a.H + h] = dt;
+        Row16<T>::store(static_cast<T*>(s_dZ[q]) + cur.jo * kF + k * 16, v);
+        if (head_lead) s_dt[q][cur.jo * a.H + h] = dt;
     }
 
     // this workgroup's share of da_l

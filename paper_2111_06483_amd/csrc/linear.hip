@@ -975,9 +975,14 @@ extern "C" int sar_linear_fwd(const void* X, const float* W, void* Z, int dtype,
             k_gemm_bf16<bf16_t, float, bf16_t, true, false, true><<<grid, kGemmThreads, 0, st>>>(g);
         SAR_LAUNCH_CHECK();
     }
-    if (a_score && a_score2) return sar::gat_scores2(Z, dtype, n, H, D, a_score, score, a_score2, score2, stream);
-    if (a_score) SAR_TRY(sar_gat_scores(Z, dtype, n, H, D, a_score, score, stream));
-    if (a_score2) SAR_TRY(sar_gat_scores(Z, dtype, n, H, D, a_score2, score2, stream));
+    // (one pass over the stored rows; with one vector the same vector rides along twice)
+    if (a_score || a_score2) {
+        const float* a1 = a_score ? a_score : a_score2;
+        float* s1 = a_score ? score : score2;
+        const float* a2 = a_score2 ? a_score2 : a_score;
+        float* s2 = a_score2 ? score2 : score;
+        return sar::gat_scores2(Z, dtype, n, H, D, a1, s1, a2, s2, stream);
+    }
     return SAR_OK;
 }
 

@@ -3,14 +3,23 @@
 // copy, and random gathers of whole feature rows with the access shape of the
 // aggregation kernels (one wavefront per row, 16 bytes per lane, 8 rows in
 // flight) but no arithmetic to speak of.
-#include <algorithm>
+//
+// Measurement tooling, not part of the method: built into its own shared object
+// (libsar_bench.so, header include/sar_bench_probes.h) that only bench.py loads.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
 
-#include "gather_common.h"
-#include "sar_internal.h"
+#include <algorithm>
+#include <type_traits>
+
+#include "../../include/sar_bench_probes.h"
 
 namespace {
 
-using namespace sar;
+constexpr int kProbeWGs = 256 * 8;   // 256 CUs x 8 resident workgroups
+
+inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+inline int launched() { return hipGetLastError() == hipSuccess ? 0 : -3; }
 
 __global__ __launch_bounds__(256) void k_probe_read(const float4* __restrict__ p, size_t n4, int reps,
                                                     float* __restrict__ sink)
@@ -94,56 +103,50 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 }  // namespace
 
-extern "C" int sar_probe_stream_read(const void* buf, size_t bytes, int reps, float* sink, void* stream)
+extern "C" int sar_bench_stream_read(const void* buf, size_t bytes, int reps, float* sink, void* stream)
 {
-    SAR_CHECK_ARG(buf && sink && aligned16(buf), "buf or sink is null, or buf is not 16-byte aligned");
-    SAR_CHECK_ARG(reps >= 1, "reps must be positive");
-    k_probe_read<<<kMaxPersistentWGs, 256, 0, sar::as_stream(stream)>>>(static_cast<const float4*>(buf), bytes / 16,
+    if (!(buf && sink && aligned16(buf))) return -1;
+    if (!(reps >= 1)) return -1;
+    k_probe_read<<<kProbeWGs, 256, 0, as_stream(stream)>>>(static_cast<const float4*>(buf), bytes / 16,
                                                                          reps, sink);
-    SAR_LAUNCH_CHECK();
-    return SAR_OK;
+    return launched();
 }
 
-extern "C" int sar_probe_copy(const void* src, void* dst, size_t bytes, void* stream)
+extern "C" int sar_bench_copy(const void* src, void* dst, size_t bytes, void* stream)
 {
-    SAR_CHECK_ARG(src && dst && aligned16(src) && aligned16(dst), "src/dst is null or not 16-byte aligned");
-    k_probe_copy<<<kMaxPersistentWGs, 256, 0, sar::as_stream(stream)>>>(static_cast<const float4*>(src),
+    if (!(src && dst && aligned16(src) && aligned16(dst))) return -1;
+    k_probe_copy<<<kProbeWGs, 256, 0, as_stream(stream)>>>(static_cast<const float4*>(src),
                                                                          static_cast<float4*>(dst), bytes / 16);
-    SAR_LAUNCH_CHECK();
-    return SAR_OK;
+    return launched();
 }
 
-extern "C" int sar_probe_row_gather(const void* rows, int64_t n_rows, int row_bytes, const int32_t* idx,
+extern "C" int sar_bench_row_gather(const void* rows, int64_t n_rows, int row_bytes, const int32_t* idx,
                                     int64_t n_idx, float* sink, void* stream)
 {
-    SAR_CHECK_ARG(rows && idx && sink && aligned16(rows), "a pointer is null or rows is not 16-byte aligned");
-    SAR_CHECK_ARG(n_rows > 0 && n_idx >= 0, "need n_rows > 0 and n_idx >= 0");
-    if (row_bytes != 1024 && row_bytes != 512)
-        return sar::fail(SAR_ERR_UNSUPPORTED, "row_bytes must be 1024 or 512, got %d", row_bytes);
-    hipStream_t st = sar::as_stream(stream);
+    if (!(rows && idx && sink && aligned16(rows))) return -1;
+    if (!(n_rows > 0 && n_idx >= 0)) return -1;
+    if (row_bytes != 1024 && row_bytes != 512) return -2;
+    hipStream_t st = as_stream(stream);
     if (row_bytes == 1024)
-        k_probe_gather<16><<<kMaxPersistentWGs, 256, 0, st>>>(static_cast<const char*>(rows), row_bytes, idx, n_idx, sink);
+        k_probe_gather<16><<<kProbeWGs, 256, 0, st>>>(static_cast<const char*>(rows), row_bytes, idx, n_idx, sink);
     else
-        k_probe_gather<8><<<kMaxPersistentWGs, 256, 0, st>>>(static_cast<const char*>(rows), row_bytes, idx, n_idx, sink);
-    SAR_LAUNCH_CHECK();
-    return SAR_OK;
+        k_probe_gather<8><<<kProbeWGs, 256, 0, st>>>(static_cast<const char*>(rows), row_bytes, idx, n_idx, sink);
+    return launched();
 }
 
-extern "C" int sar_probe_gather_write(const void* rows, int64_t n_rows, int row_bytes, const int32_t* idx,
+extern "C" int sar_bench_gather_write(const void* rows, int64_t n_rows, int row_bytes, const int32_t* idx,
                                       int64_t n_idx, int writes_per_8, void* out, void* stream)
 {
-    SAR_CHECK_ARG(rows && idx && out && aligned16(rows) && aligned16(out), "rows/idx/out is null or not 16-byte aligned");
-    SAR_CHECK_ARG(n_rows > 0 && n_idx >= 0, "need n_rows > 0 and n_idx >= 0");
-    SAR_CHECK_ARG(writes_per_8 >= 0 && writes_per_8 <= 8, "writes_per_8 must be in [0,8]");
-    if (row_bytes != 1024 && row_bytes != 512)
-        return sar::fail(SAR_ERR_UNSUPPORTED, "row_bytes must be 1024 or 512, got %d", row_bytes);
-    hipStream_t st = sar::as_stream(stream);
+    if (!(rows && idx && out && aligned16(rows) && aligned16(out))) return -1;
+    if (!(n_rows > 0 && n_idx >= 0)) return -1;
+    if (!(writes_per_8 >= 0 && writes_per_8 <= 8)) return -1;
+    if (row_bytes != 1024 && row_bytes != 512) return -2;
+    hipStream_t st = as_stream(stream);
     if (row_bytes == 1024)
-        k_probe_gather_write<16><<<kMaxPersistentWGs, 256, 0, st>>>(static_cast<const char*>(rows), row_bytes, idx, n_idx,
+        k_probe_gather_write<16><<<kProbeWGs, 256, 0, st>>>(static_cast<const char*>(rows), row_bytes, idx, n_idx,
                                                                     writes_per_8, static_cast<char*>(out));
     else
-        k_probe_gather_write<8><<<kMaxPersistentWGs, 256, 0, st>>>(static_cast<const char*>(rows), row_bytes, idx, n_idx,
+        k_probe_gather_write<8><<<kProbeWGs, 256, 0, st>>>(static_cast<const char*>(rows), row_bytes, idx, n_idx,
                                                                    writes_per_8, static_cast<char*>(out));
-    SAR_LAUNCH_CHECK();
-    return SAR_OK;
+    return launched();
 }

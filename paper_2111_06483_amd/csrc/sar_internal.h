@@ -69,7 +69,11 @@ struct Block {
     int64_t n_t_rows = 0, n_t_long = 0, n_t_wide = 0;   // n_t_wide: sources with >= 8 edges
     int64_t n_t_wide_f32 = 0;                            // sources with >= 4 edges
     int32_t* touched = nullptr;
+    int32_t* t_rank = nullptr;                           // [n_src+1]: touched sources below j
 };
+
+// Rows of dZ_q / dt_q the backward calls write for a handle with these flags.
+inline bool skips_untouched(int flags) { return (flags & (SAR_BUILD_SKIP_UNTOUCHED | SAR_BUILD_COMPACT)) != 0; }
 
 inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 

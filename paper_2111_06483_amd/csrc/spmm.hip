@@ -38,6 +38,7 @@ struct SpmmArgs {
     int mean;
     const void* res;          // batched forward: rows added to the aggregate (Eq. 2's W_res h), or null
     int act;                  //                  SAR_ACT_* applied after that
+    const int32_t* out_rank;  // backward, compact errors: row of `out` that source j owns (null: j)
 };
 
 enum class Mode { kBlock, kAll, kBackward };
@@ -108,7 +109,11 @@ __device__ inline void finish_row(const float (&acc)[Vec<T>::N], const SpmmArgs&
 {
     constexpr int VEC = Vec<T>::N;
     if (lm.slot != 0 || !lm.on) return;
-    const int64_t o = (int64_t)i * a.ld + lm.gl * VEC;
+    int64_t row = i;
+    if constexpr (M == Mode::kBackward) {
+        if (a.out_rank) row = a.out_rank[i];
+    }
+    const int64_t o = row * a.ld + lm.gl * VEC;
     if constexpr (M == Mode::kBlock) {
         float cur[VEC];
         load_f32<VEC>(a.acc + o, cur);
@@ -239,6 +244,7 @@ struct BwdAllTabs {
     const int32_t* t_indptr[SAR_MAX_BLOCKS];
     const uint32_t* t_indices[SAR_MAX_BLOCKS];
     void* dZ[SAR_MAX_BLOCKS];
+    const int32_t* rank[SAR_MAX_BLOCKS];
 };
 
 template <typename T, int G>
@@ -256,6 +262,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_spmm_bwd_all(SpmmArgs a, Bwd
         la.indptr = tabs.t_indptr[q];
         la.indices = tabs.t_indices[q];
         la.out = tabs.dZ[q];
+        la.out_rank = tabs.rank[q];
         return (int)(id & mask);
     };
 
@@ -288,6 +295,34 @@ __global__ __launch_bounds__(kGatherThreads) void k_spmm_bwd_all(SpmmArgs a, Bwd
         add_rows<T, G, M>(acc, la, nullptr, la.indptr[j], la.indptr[j + 1], 0, 1, lm);
         merge_slots<T, G>(acc);
         finish_row<T, G, M>(acc, la, j, lm);
+    }
+}
+
+// Ep[i] (+)= Eq[rank[i]] where source i of the block has a row in the compact error, else (+)= 0
+template <typename T>
+__global__ __launch_bounds__(256) void k_error_add(const T* __restrict__ Eq, const int32_t* __restrict__ rank,
+                                                   int accumulate, T* Ep, int64_t n, int F)
+{
+    constexpr int VEC = Vec<T>::N;
+    const int per_row = F / VEC;
+    const int64_t total = n * per_row;
+    for (int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x; k < total; k += (int64_t)gridDim.x * 256) {
+        const int64_t i = k / per_row;
+        const int c = (int)(k % per_row) * VEC;
+        const int32_t r = rank[i];
+        const bool has = rank[i + 1] > r;
+        if (accumulate && !has) continue;
+        float v[VEC];
+#pragma unroll
+        for (int x = 0; x < VEC; ++x) v[x] = 0.f;
+        if (has) Vec<T>::unpack(Vec<T>::load(Eq + (int64_t)r * F + c), v);
+        if (accumulate) {
+            float e[VEC];
+            Vec<T>::unpack(Vec<T>::load(Ep + i * F + c), e);
+#pragma unroll
+            for (int x = 0; x < VEC; ++x) v[x] += e[x];
+        }
+        Vec<T>::store(Ep + i * F + c, v);
     }
 }
 
@@ -511,7 +546,7 @@ extern "C" int sar_spmm_bwd_block(const sar_blocks_t* b, int q, const void* G, i
     SAR_TRY(check_row_shape(dtype, F));
     const sar::Block& k = b->blk[q];
     if (!k.t_indptr) return sar::fail(SAR_ERR_STATE, "handle was built without SAR_BUILD_TRANSPOSE");
-    if (k.n_src == 0) return SAR_OK;
+    if (k.n_src == 0 || (sar::skips_untouched(b->flags) && k.n_t_rows == 0)) return SAR_OK;
     SAR_CHECK_ARG((G || b->n_dst == 0) && dZq, "G or dZq is null");
     SAR_CHECK_ARG(aligned16(G) && aligned16(dZq), "G and dZq must be 16-byte aligned");
     hipStream_t st = sar::as_stream(stream);
@@ -520,7 +555,8 @@ extern "C" int sar_spmm_bwd_block(const sar_blocks_t* b, int q, const void* G, i
     a.indices = reinterpret_cast<const uint32_t*>(k.t_indices);
     a.rows = reinterpret_cast<const uint32_t*>(k.t_rows);
     // sources without edges come last in the list and get 0, unless the handle skips them
-    a.n_rows = (b->flags & SAR_BUILD_SKIP_UNTOUCHED) ? k.n_t_rows : k.n_src;
+    a.n_rows = sar::skips_untouched(b->flags) ? k.n_t_rows : k.n_src;
+    a.out_rank = (b->flags & SAR_BUILD_COMPACT) ? k.t_rank : nullptr;
     a.n_long = k.n_t_long;
     a.deg = b->deg;
     a.ld = F;
@@ -552,13 +588,13 @@ extern "C" int sar_spmm_bwd_all(const sar_blocks_t* b, const void* G, int mean, 
     SAR_CHECK_ARG((G || b->n_dst == 0) && dZq, "G or dZq is null");
     SAR_CHECK_ARG(aligned16(G), "G must be 16-byte aligned");
     for (int q = 0; q < b->P; ++q) {
-        if (b->blk[q].n_src == 0) continue;
+        if (b->blk[q].n_src == 0 || (sar::skips_untouched(b->flags) && b->blk[q].n_t_rows == 0)) continue;
         SAR_CHECK_ARG(dZq[q] && aligned16(dZq[q]), "dZq[%d] is null or not 16-byte aligned", q);
     }
     hipStream_t st = sar::as_stream(stream);
     SpmmArgs a{};
     a.rows = b->ft_rows;
-    a.n_rows = (b->flags & SAR_BUILD_SKIP_UNTOUCHED) ? b->n_ft_rows : n_src_total;
+    a.n_rows = sar::skips_untouched(b->flags) ? b->n_ft_rows : n_src_total;
     a.n_long = b->n_ft_long;
     a.deg = b->deg;
     a.ld = F;
@@ -574,6 +610,7 @@ extern "C" int sar_spmm_bwd_all(const sar_blocks_t* b, const void* G, int mean, 
             tabs.t_indptr[q] = k.t_indptr;
             tabs.t_indices[q] = reinterpret_cast<const uint32_t*>(k.t_indices);
             tabs.dZ[q] = shift(dZq[q], f0 * cc.fb);
+            tabs.rank[q] = (b->flags & SAR_BUILD_COMPACT) ? k.t_rank : nullptr;
         }
         a.Z = shift(G, f0 * cc.fb);
         a.F = std::min<int>(cc.width, F - (int)f0);
@@ -582,5 +619,27 @@ extern "C" int sar_spmm_bwd_all(const sar_blocks_t* b, const void* G, int mean, 
         else
             SAR_TRY(launch_spmm_bwd_all<bf16_t>(a, tabs, st));
     }
+    return SAR_OK;
+}
+
+extern "C" int sar_error_add(const void* Eq, const int32_t* t_rank, int accumulate, void* Ep, int dtype, int64_t n,
+                             int F, void* stream)
+{
+    SAR_TRY(check_row_shape(dtype, F));
+    SAR_CHECK_ARG(n >= 0, "n is negative");
+    if (n == 0) return SAR_OK;
+    SAR_CHECK_ARG(t_rank && Ep, "t_rank or Ep is null");
+    SAR_CHECK_ARG(aligned16(Eq) && aligned16(Ep), "Eq and Ep must be 16-byte aligned");
+    SAR_CHECK_ARG(Eq != Ep, "Eq and Ep must not alias");
+    const int64_t total = n * (F / (dtype == SAR_F32 ? 4 : 8));
+    const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>((total + 255) / 256, kMaxPersistentWGs * 4));
+    hipStream_t st = sar::as_stream(stream);
+    if (dtype == SAR_F32)
+        k_error_add<float><<<grid, 256, 0, st>>>(static_cast<const float*>(Eq), t_rank, accumulate,
+                                                 static_cast<float*>(Ep), n, F);
+    else
+        k_error_add<bf16_t><<<grid, 256, 0, st>>>(static_cast<const bf16_t*>(Eq), t_rank, accumulate,
+                                                  static_cast<bf16_t*>(Ep), n, F);
+    SAR_LAUNCH_CHECK();
     return SAR_OK;
 }

@@ -29,6 +29,7 @@ SAR_MAX_BLOCKS = 64
 SAR_BUILD_TRANSPOSE = 1
 SAR_BUILD_FUSED = 2
 SAR_BUILD_SKIP_UNTOUCHED = 4
+SAR_BUILD_COMPACT = 8
 
 _c_i64 = ctypes.c_int64
 _c_int = ctypes.c_int
@@ -47,7 +48,7 @@ class BlockView(ctypes.Structure):
         ("indptr", _vp), ("indices", _vp), ("t_indptr", _vp), ("t_indices", _vp),
         ("rows", _vp), ("n_rows", _c_i64), ("n_long", _c_i64),
         ("t_rows", _vp), ("n_t_rows", _c_i64), ("n_t_long", _c_i64),
-        ("touched", _vp),
+        ("touched", _vp), ("t_rank", _vp),
     ]
 
 
@@ -74,12 +75,11 @@ EXPORTS = [
     "sar_blocks_build", "sar_blocks_wrap", "sar_blocks_subset", "sar_blocks_info", "sar_blocks_get", "sar_blocks_degree",
     "sar_blocks_free",
     "sar_spmm_block", "sar_spmm_end", "sar_spmm_all", "sar_act_bwd", "sar_spmm_bwd_block", "sar_spmm_bwd_all",
+    "sar_error_add",
     "sar_gat_scores", "sar_gat_fwd_begin", "sar_gat_fwd_block", "sar_gat_fwd_end", "sar_gat_fwd_all",
     "sar_gat_workspace_bytes", "sar_gat_bwd_begin", "sar_gat_bwd_block", "sar_gat_bwd_all", "sar_gat_bwd_end",
     "sar_gat_bwd_end_noalloc",
     "sar_linear_fwd", "sar_linear_bwd", "sar_linear_workspace_bytes",
-    "sar_probe_stream_read", "sar_probe_copy", "sar_probe_row_gather", "sar_probe_gather_write",
-    "sar_timing_begin", "sar_timing_count", "sar_timing_get",
 ]
 
 
@@ -116,20 +116,36 @@ def dtype_code(dt: torch.dtype) -> int:
     raise SarError(SAR_ERR_UNSUPPORTED, "dtype %s" % dt)
 
 
-def _ptr_array(ts: Sequence[Optional[torch.Tensor]]):
+def _ptr_array(ts: Sequence[Optional[torch.Tensor]], what: str = "tensor", dtype: Optional[torch.dtype] = None,
+               row_values: Optional[int] = None):
+    """Host array of device pointers for the calls that take one tensor per block.  The C side
+    reinterprets the memory, so every entry must be what the call assumes: on the device,
+    contiguous, of `dtype`, and (when given) with `row_values` values per row."""
     arr = (_vp * len(ts))()
     for k, t in enumerate(ts):
-        arr[k] = None if t is None else t.data_ptr()
+        if t is None:
+            arr[k] = None
+            continue
+        if not t.is_cuda or not t.is_contiguous():
+            raise SarError(SAR_ERR_INVALID_ARG, "%s[%d] must be a contiguous device tensor" % (what, k))
+        if dtype is not None and t.dtype != dtype:
+            raise SarError(SAR_ERR_INVALID_ARG, "%s[%d] is %s, the call needs %s" % (what, k, t.dtype, dtype))
+        if row_values is not None and t.numel() != t.shape[0] * row_values:
+            raise SarError(SAR_ERR_INVALID_ARG, "%s[%d] has %d values per row, the call needs %d"
+                           % (what, k, t.numel() // max(t.shape[0], 1), row_values))
+        arr[k] = t.data_ptr()
     return arr
 
 
 class Blocks:
     """Owner of a sar_blocks_t handle (freed on ``close`` / garbage collection)."""
 
-    def __init__(self, handle: _vp, keep=()):
+    def __init__(self, handle: _vp, keep=(), flags: int = 0):
         self._h = handle
         self._keep = keep   # tensors borrowed by a wrapped handle
+        self.flags = flags
         self._n_src = {}
+        self._n_err = {}
         P, n = _c_int(0), _c_i64(0)
         _check(lib().sar_blocks_info(self._h, ctypes.byref(P), ctypes.byref(n)))
         self.P, self.n_dst = P.value, n.value
@@ -156,6 +172,20 @@ class Blocks:
             if t is not None and t.shape[0] != self.n_src(q):
                 raise SarError(SAR_ERR_INVALID_ARG, "block %d has %d sources, tensor has %d rows"
                                % (q, self.n_src(q), t.shape[0]))
+
+    def n_err_rows(self, q: int) -> int:
+        """Rows of block q's dZ_q / dt_q: n_src, or n_t_rows on a SAR_BUILD_COMPACT handle."""
+        if not (self.flags & SAR_BUILD_COMPACT):
+            return self.n_src(q)
+        if q not in self._n_err:
+            self._n_err[q] = int(self.view(q).n_t_rows)
+        return self._n_err[q]
+
+    def check_err_rows(self, q: int, *tensors) -> None:
+        for t in tensors:
+            if t is not None and t.shape[0] != self.n_err_rows(q):
+                raise SarError(SAR_ERR_INVALID_ARG, "block %d's error has %d rows, tensor has %d"
+                               % (q, self.n_err_rows(q), t.shape[0]))
 
     def check_dst(self, *tensors) -> None:
         for t in tensors:
@@ -206,7 +236,7 @@ def sar_blocks_build(src: torch.Tensor, dst: torch.Tensor, part: torch.Tensor, P
     _check(lib().sar_blocks_build(_ptr(src), _ptr(dst), _c_int(src.element_size()), _c_i64(src.numel()),
                                   _ptr(part), _c_i64(part.numel()), _c_int(P), _c_int(p), _c_int(flags),
                                   _stream(), ctypes.byref(h)))
-    return Blocks(h)
+    return Blocks(h, flags=flags)
 
 
 def sar_blocks_wrap(n_dst: int, n_src: Sequence[int], indptr: Sequence[torch.Tensor],
@@ -215,9 +245,10 @@ def sar_blocks_wrap(n_dst: int, n_src: Sequence[int], indptr: Sequence[torch.Ten
     P = len(indptr)
     ns = (_c_i64 * P)(*[int(x) for x in n_src])
     h = _vp(None)
-    _check(lib().sar_blocks_wrap(_c_int(P), _c_i64(n_dst), ns, _ptr_array(indptr), _ptr_array(indices),
-                                 _c_int(flags), _stream(), ctypes.byref(h)))
-    return Blocks(h, keep=(list(indptr), list(indices)))
+    _check(lib().sar_blocks_wrap(_c_int(P), _c_i64(n_dst), ns, _ptr_array(indptr, "indptr", torch.int32),
+                                 _ptr_array(indices, "indices", torch.int32), _c_int(flags), _stream(),
+                                 ctypes.byref(h)))
+    return Blocks(h, keep=(list(indptr), list(indices)), flags=flags)
 
 
 def sar_blocks_subset(b: Blocks, dst_ids: torch.Tensor,
@@ -227,7 +258,7 @@ def sar_blocks_subset(b: Blocks, dst_ids: torch.Tensor,
     h = _vp(None)
     _check(lib().sar_blocks_subset(b.handle, _ptr(dst_ids), _c_i64(dst_ids.numel()), _c_int(flags), _stream(),
                                    ctypes.byref(h)))
-    return Blocks(h)
+    return Blocks(h, flags=flags)
 
 
 def sar_blocks_degree(b: Blocks) -> torch.Tensor:
@@ -259,7 +290,7 @@ def sar_spmm_all(b: Blocks, Zq: Sequence[torch.Tensor], mean: bool, out: torch.T
         b.check_rows(q, Zq[q])
     b.check_dst(out)
     _same_shape(out, residual)
-    _check(lib().sar_spmm_all(b.handle, _ptr_array(Zq), _c_int(dtype_code(out.dtype)),
+    _check(lib().sar_spmm_all(b.handle, _ptr_array(Zq, "Zq", out.dtype, out.shape[-1]), _c_int(dtype_code(out.dtype)),
                               _c_int(out.shape[-1]), _c_int(int(mean)), _ptr(residual), _c_int(act), _ptr(out),
                               _stream()))
 
@@ -272,7 +303,7 @@ def sar_act_bwd(h: torch.Tensor, dH: torch.Tensor, act: int, G: torch.Tensor) ->
 
 
 def sar_spmm_bwd_block(b: Blocks, q: int, G: torch.Tensor, mean: bool, dZq: torch.Tensor) -> None:
-    b.check_rows(q, dZq)
+    b.check_err_rows(q, dZq)
     b.check_dst(G)
     _check(lib().sar_spmm_bwd_block(b.handle, _c_int(q), _ptr(G), _c_int(int(mean)),
                                     _c_int(dtype_code(G.dtype)), _c_int(G.shape[-1]), _ptr(dZq), _stream()))
@@ -280,10 +311,20 @@ def sar_spmm_bwd_block(b: Blocks, q: int, G: torch.Tensor, mean: bool, dZq: torc
 
 def sar_spmm_bwd_all(b: Blocks, G: torch.Tensor, mean: bool, dZq: Sequence[torch.Tensor]) -> None:
     for q in range(b.P):
-        b.check_rows(q, dZq[q])
+        b.check_err_rows(q, dZq[q])
     b.check_dst(G)
     _check(lib().sar_spmm_bwd_all(b.handle, _ptr(G), _c_int(int(mean)), _c_int(dtype_code(G.dtype)),
-                                  _c_int(G.shape[-1]), _ptr_array(dZq), _stream()))
+                                  _c_int(G.shape[-1]), _ptr_array(dZq, "dZq", G.dtype, G.shape[-1]), _stream()))
+
+
+def sar_error_add(Eq: Optional[torch.Tensor], t_rank: int, accumulate: bool, Ep: torch.Tensor) -> None:
+    """t_rank: device address of the block's t_rank array (BlockView.t_rank)."""
+    n = Ep.shape[0]
+    F = Ep.numel() // max(n, 1)
+    if Eq is not None and (Eq.dtype != Ep.dtype or Eq.numel() != Eq.shape[0] * F):
+        raise SarError(SAR_ERR_INVALID_ARG, "Eq and Ep must have the same row width and type")
+    _check(lib().sar_error_add(_ptr(Eq), _vp(t_rank), _c_int(int(accumulate)), _ptr(Ep), _c_int(dtype_code(Ep.dtype)),
+                               _c_i64(n), _c_int(F), _stream()))
 
 
 # --------------------------------------------------------------------- GAT
@@ -324,8 +365,8 @@ def sar_gat_fwd_all(b: Blocks, Zq: Sequence[torch.Tensor], s: torch.Tensor,
     for q in range(b.P):
         b.check_rows(q, Zq[q], None if tq is None else tq[q])
     b.check_dst(s, out, L)
-    _check(lib().sar_gat_fwd_all(b.handle, _ptr_array(Zq), _ptr(s), None if tq is None else _ptr_array(tq),
-                                 _ptr(a_l),
+    _check(lib().sar_gat_fwd_all(b.handle, _ptr_array(Zq, "Zq", out.dtype, H * D), _ptr(s),
+                                 None if tq is None else _ptr_array(tq, "tq", torch.float32, H), _ptr(a_l),
                                  _c_int(dtype_code(out.dtype)), _c_int(H), _c_int(D), ctypes.c_float(slope),
                                  _c_int(act), _ptr(out), _ptr(L), _stream()))
 
@@ -352,7 +393,8 @@ def sar_gat_bwd_block(b: Blocks, q: int, Zq: torch.Tensor, G: torch.Tensor, tq: 
                       rec: torch.Tensor, a_l: torch.Tensor, slope: float, dZq: torch.Tensor,
                       dtq: torch.Tensor, ds: torch.Tensor, da_l: torch.Tensor, work: torch.Tensor) -> None:
     H, D = a_l.shape
-    b.check_rows(q, Zq, tq, dZq, dtq)
+    b.check_rows(q, Zq, tq)
+    b.check_err_rows(q, dZq, dtq)
     b.check_dst(G, rec, ds)
     _check(lib().sar_gat_bwd_block(b.handle, _c_int(q), _ptr(Zq), _ptr(G), _ptr(tq), _ptr(rec), _ptr(a_l),
                                    _c_int(dtype_code(G.dtype)), _c_int(H), _c_int(D), ctypes.c_float(slope),
@@ -366,27 +408,33 @@ def sar_gat_bwd_all(b: Blocks, Zq: Sequence[torch.Tensor], G: torch.Tensor, tq: 
                     work: torch.Tensor) -> None:
     H, D = a_l.shape
     for q in range(b.P):
-        b.check_rows(q, Zq[q], None if tq is None else tq[q], dZq[q], dtq[q])
+        b.check_rows(q, Zq[q], None if tq is None else tq[q])
+        b.check_err_rows(q, dZq[q], dtq[q])
     b.check_dst(G, rec, ds)
-    _check(lib().sar_gat_bwd_all(b.handle, _ptr_array(Zq), _ptr(G), None if tq is None else _ptr_array(tq),
+    _check(lib().sar_gat_bwd_all(b.handle, _ptr_array(Zq, "Zq", G.dtype, H * D), _ptr(G),
+                                 None if tq is None else _ptr_array(tq, "tq", torch.float32, H),
                                  _ptr(rec), _ptr(a_l),
                                  _c_int(dtype_code(G.dtype)), _c_int(H), _c_int(D), ctypes.c_float(slope),
-                                 _ptr_array(dZq), _ptr_array(dtq), _ptr(ds), _ptr(da_l), _ptr(work),
+                                 _ptr_array(dZq, "dZq", G.dtype, H * D), _ptr_array(dtq, "dtq", torch.float32, H),
+                                 _ptr(ds), _ptr(da_l), _ptr(work),
                                  ctypes.c_size_t(work.numel() * work.element_size()), _stream()))
 
 
 def sar_gat_bwd_end(Zdst: torch.Tensor, ds: torch.Tensor, a_r: torch.Tensor, dZadd: Optional[torch.Tensor],
-                    dZdst: torch.Tensor, da_r: torch.Tensor, work: torch.Tensor) -> None:
+                    dZdst: torch.Tensor, da_r: torch.Tensor, work: torch.Tensor,
+                    dZadd_rank: Optional[int] = None) -> None:
+    """dZadd_rank: device address of the local block's t_rank (BlockView.t_rank) when dZadd is compact."""
     H, D = a_r.shape
-    _check(lib().sar_gat_bwd_end(_ptr(Zdst), _ptr(ds), _ptr(a_r), _ptr(dZadd), _ptr(dZdst), _ptr(da_r),
+    _check(lib().sar_gat_bwd_end(_ptr(Zdst), _ptr(ds), _ptr(a_r), _ptr(dZadd), _vp(dZadd_rank), _ptr(dZdst), _ptr(da_r),
                                  _c_int(dtype_code(Zdst.dtype)), _c_i64(Zdst.shape[0]), _c_int(H), _c_int(D),
                                  _ptr(work), ctypes.c_size_t(work.numel() * work.element_size()), _stream()))
 
 
 def sar_gat_bwd_end_noalloc(Zdst: torch.Tensor, ds: torch.Tensor, a_r: torch.Tensor,
-                            dZadd: Optional[torch.Tensor], dZdst: torch.Tensor, da_r: torch.Tensor) -> None:
+                            dZadd: Optional[torch.Tensor], dZdst: torch.Tensor, da_r: torch.Tensor,
+                            dZadd_rank: Optional[int] = None) -> None:
     H, D = a_r.shape
-    _check(lib().sar_gat_bwd_end_noalloc(_ptr(Zdst), _ptr(ds), _ptr(a_r), _ptr(dZadd), _ptr(dZdst), _ptr(da_r),
+    _check(lib().sar_gat_bwd_end_noalloc(_ptr(Zdst), _ptr(ds), _ptr(a_r), _ptr(dZadd), _vp(dZadd_rank), _ptr(dZdst), _ptr(da_r),
                                          _c_int(dtype_code(Zdst.dtype)), _c_i64(Zdst.shape[0]), _c_int(H),
                                          _c_int(D), _stream()))
 
@@ -419,48 +467,3 @@ def sar_linear_bwd(X: Optional[torch.Tensor], dZ: torch.Tensor, W: Optional[torc
     wb = 0 if work is None else work.numel() * work.element_size()
     _check(lib().sar_linear_bwd(_ptr(X), _ptr(dZ), _ptr(W), _ptr(dW), _ptr(dX), _c_int(dtype_code(dZ.dtype)),
                                 _c_i64(n), _c_int(K), _c_int(F), _ptr(work), ctypes.c_size_t(wb), _stream()))
-
-
-# ------------------------------------------------------------------ probes
-
-def sar_probe_stream_read(buf: torch.Tensor, reps: int, sink: torch.Tensor) -> None:
-    _check(lib().sar_probe_stream_read(_ptr(buf), ctypes.c_size_t(buf.numel() * buf.element_size()), _c_int(reps),
-                                       _ptr(sink), _stream()))
-
-
-def sar_probe_copy(src: torch.Tensor, dst: torch.Tensor) -> None:
-    assert src.numel() * src.element_size() == dst.numel() * dst.element_size()
-    _check(lib().sar_probe_copy(_ptr(src), _ptr(dst), ctypes.c_size_t(src.numel() * src.element_size()), _stream()))
-
-
-def sar_probe_row_gather(rows: torch.Tensor, idx: torch.Tensor, sink: torch.Tensor) -> None:
-    assert idx.dtype == torch.int32 and rows.dim() == 2
-    _check(lib().sar_probe_row_gather(_ptr(rows), _c_i64(rows.shape[0]), _c_int(rows.shape[1] * rows.element_size()),
-                                      _ptr(idx), _c_i64(idx.numel()), _ptr(sink), _stream()))
-
-
-def sar_probe_gather_write(rows: torch.Tensor, idx: torch.Tensor, writes_per_8: int, out: torch.Tensor) -> None:
-    assert idx.dtype == torch.int32 and rows.dim() == 2 and out.dim() == 2 and out.shape[1] == rows.shape[1]
-    if out.shape[0] < (idx.numel() // 8) * writes_per_8 or out.dtype != rows.dtype:
-        raise SarError(SAR_ERR_INVALID_ARG, "out needs (n_idx / 8) * writes_per_8 rows of the table's type")
-    _check(lib().sar_probe_gather_write(_ptr(rows), _c_i64(rows.shape[0]), _c_int(rows.shape[1] * rows.element_size()),
-                                        _ptr(idx), _c_i64(idx.numel()), _c_int(writes_per_8), _ptr(out), _stream()))
-
-
-# ------------------------------------------------------------------ timing
-
-def sar_timing_begin(max_records: int) -> None:
-    _check(lib().sar_timing_begin(_c_int(max_records)))
-
-
-def sar_timing_count() -> int:
-    n = _c_int(0)
-    _check(lib().sar_timing_count(ctypes.byref(n)))
-    return n.value
-
-
-def sar_timing_get(k: int):
-    """(wide_ms, narrow_ms) of the k-th recorded backward launch."""
-    a, b = ctypes.c_float(0), ctypes.c_float(0)
-    _check(lib().sar_timing_get(_c_int(k), ctypes.byref(a), ctypes.byref(b)))
-    return a.value, b.value

@@ -304,3 +304,32 @@ def make_workload(name: str, device="cpu", scale: float = 1.0) -> Workload:
         src, dst = chung_lu_worker_share(N, 50, 2.1, part, 0, 0)
         return Workload(name, N, 1, 0, src, dst, part, 100 * H, H, 100, torch.float32)
     raise ValueError(name)
+
+
+def make_local_workload(device="cpu", scale: float = 1.0, window: int = 2048) -> Workload:
+    """Config 3's sizes, partition and destination degrees on a graph with locality: every edge of
+    config 3 keeps its destination and its source's partition, but the source becomes a node of
+    that partition whose local rank lies within `window` ranks of the destination's own local rank
+    (as a partitioner that keeps neighbourhoods together might leave the blocks).  Repeated pairs
+    are dropped.  Used to ask what the aggregation kernels gain from neighbourhoods that overlap.
+    Seed 21 draws the offsets."""
+    w = make_workload("cfg3", device=device, scale=scale)
+    N, P = w.N, w.P
+    part64 = w.part.to(torch.int64)
+    lid = torch.empty(N, dtype=torch.int64, device=device)
+    members, sizes = [], []
+    for q in range(P):
+        m = torch.nonzero(w.part == q).flatten()
+        lid[m] = torch.arange(m.numel(), device=device)
+        members.append(m)
+        sizes.append(m.numel())
+    E = w.src.numel()
+    off = (_lsr(hash_counter(21, 0, torch.arange(E, device=device)), 40) % (2 * window)) - window
+    q_of = part64[w.src]
+    r = lid[w.dst] + off
+    new_src = torch.empty_like(w.src)
+    for q in range(P):
+        sel = q_of == q
+        new_src[sel] = members[q][torch.remainder(r[sel], sizes[q])]
+    dst, src = _dedup_pairs(w.dst, new_src, N)
+    return Workload("cfg3local", N, P, w.p, src, dst, w.part, w.f_in, w.H, w.D, w.dtype)

@@ -44,7 +44,7 @@ def test_binding_covers_the_header():
 def test_validation_errors_need_no_gpu(lib):
     from paper_2111_06483_amd import sar
     i64 = ctypes.c_int64
-    assert lib.sar_version() == 2
+    assert lib.sar_version() == 3
     rc = lib.sar_gat_scores(None, 0, i64(5), 2, 3, None, None, None)
     assert rc == sar.SAR_ERR_UNSUPPORTED and b"multiple of 4" in lib.sar_last_error()
     rc = lib.sar_gat_scores(None, 7, i64(5), 2, 4, None, None, None)
@@ -85,8 +85,19 @@ def test_validation_errors_need_no_gpu(lib):
     part = (ctypes.c_int32 * 1)(0)       # only its being non-null is looked at before the flags
     rc = lib.sar_blocks_build(None, None, 4, i64(0), part, i64(1), 1, 0, 64, None, ctypes.byref(h))
     assert rc == sar.SAR_ERR_INVALID_ARG and b"flags" in lib.sar_last_error()
-    rc = lib.sar_probe_gather_write(None, i64(1), 1024, None, i64(0), 9, None, None)
-    assert rc == sar.SAR_ERR_INVALID_ARG
+    rc = lib.sar_gat_bwd_end(None, None, None, None, part, None, None, 0, i64(4), 2, 4, None, 0, None)
+    assert rc == sar.SAR_ERR_INVALID_ARG and b"dZadd_rank" in lib.sar_last_error()
+
+
+def test_product_library_holds_only_the_method(lib):
+    """Measurement tooling (bandwidth probes, timers) lives in bench.py's own library."""
+    for name in ("sar_probe_row_gather", "sar_timing_begin", "sar_bench_row_gather"):
+        assert not hasattr(lib, name), name
+    from paper_2111_06483_amd import bench_probes
+    probes = bench_probes.lib()
+    for name in ("sar_bench_stream_read", "sar_bench_copy", "sar_bench_row_gather", "sar_bench_gather_write"):
+        assert hasattr(probes, name), name
+    assert probes.sar_bench_row_gather(None, ctypes.c_int64(1), 1024, None, ctypes.c_int64(0), None, None) == -1
 
 
 def test_bench_refuses_more_than_one_gpu():
@@ -106,7 +117,7 @@ C_CALLER = r"""
 int main(void)
 {
     size_t n = 0;
-    if (sar_version() != 2) return 1;
+    if (sar_version() != 3) return 1;
     if (sar_gat_workspace_bytes(10, 10, 4, 64, &n) != SAR_OK || n == 0) return 2;
     if (sar_spmm_block(NULL, 0, NULL, SAR_F32, 16, NULL, NULL) != SAR_ERR_INVALID_ARG) return 3;
     if (strstr(sar_last_error(), "handle") == NULL) return 4;

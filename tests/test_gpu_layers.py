@@ -424,3 +424,81 @@ def test_per_relation_means_chain_through_the_residual():
     assert rel_err(f64(acc), total) < 1e-4
     for b in handles:
         b.close()
+
+
+# ------------------------------------------------------------------ compact errors (Alg. 2: E_{p->q} has only the rows V_{p,q})
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("H,D", [(4, 64), (8, 32), (2, 24), (2, 100)])
+def test_compact_errors_equal_the_touched_rows_of_the_full_ones(dtype, H, D):
+    """A SAR_BUILD_COMPACT handle writes dZ_q / dt_q with one row per touched source, in `touched`
+    order: against the oracle's rows, for the attention backward (per block and all blocks) and
+    the case-1 backward of the mean, and through sar_gat_bwd_end's rank argument."""
+    if dtype == torch.bfloat16 and D % 8:
+        pytest.skip("bf16 rows need D % 8 == 0")
+    tol = TOL[dtype]
+    P, p, F = 4, 1, H * D
+    src, dst, part, rng = make_graph(71, 5000, 12000, P, empty_block=2)
+    want_b, deg = orc.build_blocks(src, dst, part, P, p)
+    flags = sar.SAR_BUILD_TRANSPOSE | sar.SAR_BUILD_FUSED | sar.SAR_BUILD_COMPACT
+    b = gu.build_blocks(src, dst, part, P, p, flags=flags)
+    views = [gu.view_arrays(b, q) for q in range(P)]
+    touched = [np.flatnonzero(np.diff(w.t_indptr) > 0) for w in want_b]
+    for q in range(P):
+        v = b.view(q)
+        assert np.array_equal(views[q]["touched"], touched[q].astype(np.int32))
+        rank = sar.device_array(v.t_rank, v.n_src + 1).cpu().numpy()
+        flags_q = (np.diff(want_b[q].t_indptr) > 0).astype(np.int64)
+        assert np.array_equal(rank, np.concatenate([[0], np.cumsum(flags_q)]).astype(np.int32))
+    assert any(len(t) < w.n_src for t, w in zip(touched, want_b)) and len(touched[2]) == 0
+
+    Zs = [feats(rng, w.n_src, F, dtype).cuda().reshape(-1, H, D) for w in want_b]
+    Zdst = Zs[p]
+    bound = np.sqrt(6.0 / (D + 1))
+    a_l = torch.from_numpy(rng.uniform(-bound, bound, (H, D)).astype(np.float32)).cuda()
+    a_r = torch.from_numpy(rng.uniform(-bound, bound, (H, D)).astype(np.float32)).cuda()
+    G = feats(rng, b.n_dst, F, dtype).cuda().reshape(-1, H, D)
+    Z64 = [f64(z) for z in Zs]
+    wf = orc.gat_fwd(want_b, f64(Zdst), Z64, f64(a_l), f64(a_r), SLOPE)
+    wb = orc.gat_bwd(want_b, f64(Zdst), Z64, f64(G), f64(a_l), f64(a_r), SLOPE, wf)
+    fw = gu.gat_fwd_all(b, Zdst, Zs, a_l, a_r, SLOPE, fly=True)
+    n = b.n_dst
+    work = torch.empty(sar.sar_gat_workspace_bytes(n, 0, H, D) // 4, dtype=torch.float32, device="cuda")
+    for batched in (True, False):
+        rec = torch.empty((n, H, 4), dtype=torch.float32, device="cuda")
+        ds = torch.empty((n, H), dtype=torch.float32, device="cuda")
+        sar.sar_gat_bwd_begin(G, fw.out, fw.s, fw.L, rec, ds)
+        da_l = torch.zeros((H, D), dtype=torch.float32, device="cuda")
+        dZs = [torch.full((len(t), H, D), float("nan"), dtype=dtype, device="cuda") for t in touched]
+        dts = [torch.full((len(t), H), float("nan"), dtype=torch.float32, device="cuda") for t in touched]
+        if batched:
+            sar.sar_gat_bwd_all(b, Zs, G, None, rec, a_l, SLOPE, dZs, dts, ds, da_l, work)
+        else:
+            for q in range(P):
+                sar.sar_gat_bwd_block(b, q, Zs[q], G, None, rec, a_l, SLOPE, dZs[q], dts[q], ds, da_l, work)
+        for q in range(P):
+            assert rel_err(f64(dZs[q]), wb.dZs[q][touched[q]]) < tol, (batched, q)
+            assert rel_err(f64(dts[q]), wb.dt[q][touched[q]]) < tol, (batched, q)
+        assert rel_err(f64(ds), wb.ds) < tol and rel_err(f64(da_l), wb.da_l) < tol
+        # the worker's own error: ds a_r plus the compact local block, placed by rank
+        dZdst = torch.full((n, H, D), float("nan"), dtype=dtype, device="cuda")
+        da_r = torch.zeros((H, D), dtype=torch.float32, device="cuda")
+        sar.sar_gat_bwd_end(Zdst, ds, a_r, dZs[p], dZdst, da_r, work, dZadd_rank=b.view(p).t_rank)
+        assert rel_err(f64(dZdst), wb.dZdst + wb.dZs[p]) < tol
+        assert rel_err(f64(da_r), wb.da_r) < tol
+        with pytest.raises(sar.SarError):          # a full-height tensor is refused on a compact handle
+            sar.sar_gat_bwd_block(b, 0, Zs[0], G, None, rec, a_l, SLOPE, torch.empty_like(Zs[0]), dts[0], ds, da_l, work)
+
+    # case-1 backward of the mean (Eq. 2)
+    G2 = G.reshape(n, F)
+    want_d = orc.spmm_bwd(want_b, f64(G2), True)
+    d_all = [torch.full((len(t), F), float("nan"), dtype=dtype, device="cuda") for t in touched]
+    d_blk = [torch.full((len(t), F), float("nan"), dtype=dtype, device="cuda") for t in touched]
+    sar.sar_spmm_bwd_all(b, G2, True, d_all)
+    for q in range(P):
+        sar.sar_spmm_bwd_block(b, q, G2, True, d_blk[q])
+        assert rel_err(f64(d_all[q]), want_d[q][touched[q]]) < tol, q
+        assert rel_err(f64(d_blk[q]), want_d[q][touched[q]]) < tol, q
+    b.close()
+    with pytest.raises(sar.SarError):
+        gu.build_blocks(src, dst, part, P, p, flags=sar.SAR_BUILD_COMPACT)

@@ -57,19 +57,20 @@ FLOOR_USE = {"strict": 0, "floor": 0}
 
 
 def close(got, want, tol, floor):
-    """The strict measure max|got - want| <= tol * max|want| wherever the tensor has a scale of its
-    own: more than one row and max|want| >= floor.  Otherwise (a tensor of one node, or a sum whose
-    terms cancel to nearly nothing) the error is held to `floor`, the scale of the terms the
-    tensor's entries are sums of: a cancelling sum is as accurate as its terms, not as its value."""
+    """The strict measure first: max|got - want| <= tol * max|want|.  Only a tensor that misses it is
+    held to `floor` instead, the scale of the terms its entries are sums of: a tensor of one node,
+    or a sum whose terms cancel to (nearly) nothing, has no scale of its own, and a cancelling sum
+    is as accurate as its terms, not as its value.  FLOOR_USE counts how each comparison was
+    decided; the floor has to stay the exception (test_the_floor_is_the_exception)."""
     want = np.asarray(want)
     if want.size == 0:
         return True
     got = got if isinstance(got, np.ndarray) else f64(got)
     scale = np.abs(want).max()
     err = np.abs(got - want).max()
-    if want.shape[0] > 1 and scale >= floor:
+    if err <= tol * scale:
         FLOOR_USE["strict"] += 1
-        return err <= tol * scale
+        return True
     FLOOR_USE["floor"] += 1
     return err <= tol * max(scale, floor)
 
@@ -205,8 +206,9 @@ def test_random_shape(case):
 
 def test_the_floor_is_the_exception():
     """The absolute floor of `close` acts only for the degenerate tensors it is meant for: over the
-    32 cases above the strict relative measure decided the large majority of the comparisons."""
+    32 cases above the strict relative measure alone passed nearly all of the comparisons."""
     total = FLOOR_USE["strict"] + FLOOR_USE["floor"]
     if total == 0:
         pytest.skip("runs after test_random_shape in the same process")
-    assert FLOOR_USE["floor"] <= 0.35 * total, FLOOR_USE
+    print("comparisons decided by the strict measure / by the floor:", FLOOR_USE)
+    assert FLOOR_USE["floor"] <= 0.05 * total, FLOOR_USE

@@ -159,8 +159,9 @@ def check_step(name, scale, modes):
     P, p, H, D = w.P, w.p, w.H, w.D
     o = OracleStep(w)
     n = o.blocks[0].n_dst
-    layer = bench.Layer(w, torch, sar, synth)
-    assert layer.n == n and layer.E == sum(b.nnz for b in o.blocks)
+    layer = bench.Layer(w, torch, sar, synth)          # bench.py's defaults: compact errors E_{p->q}
+    assert layer.n == n and layer.E == sum(b.nnz for b in o.blocks) and layer.compact
+    touched = [np.flatnonzero(np.diff(b.t_indptr) > 0) for b in o.blocks]
 
     # rows an ambiguous branch can move (from the oracle's own scores)
     s_scale = max(np.abs(o.fwd.s).max(), max(np.abs(t).max() for t in o.fwd.t))
@@ -205,11 +206,14 @@ def check_step(name, scale, modes):
         ds = f64(layer.ds)
         assert rel_err(ds[~bad_dst], o.bwd.ds[~bad_dst]) < tol, tag
         for q in range(P):
-            ok = ~bad_src[q]
-            dZ, dZw = f64(layer.dZs[q]), o.bwd.dZs[q]
+            # the errors come in the shape they are exchanged in: one row per touched source
+            tq = touched[q]
+            assert layer.dZs[q].shape[0] == tq.shape[0], (tag, q)
+            ok = ~bad_src[q][tq]
+            dZ, dZw = f64(layer.dZs[q]), o.bwd.dZs[q][tq]
             assert rel_err(dZ[ok], dZw[ok]) < tol, (tag, q)
             assert row_rel_err(np.where(ok[:, :, None], dZ, 0), np.where(ok[:, :, None], dZw, 0)) < tol, (tag, q)
-            assert rel_err(f64(layer.dts[q])[ok], o.bwd.dt[q][ok]) < tol, (tag, q)
+            assert rel_err(f64(layer.dts[q])[ok], o.bwd.dt[q][tq][ok]) < tol, (tag, q)
         Ep = f64(layer.dZdst)
         assert rel_err(Ep[~bad_own], o.E_p[~bad_own]) < tol, tag
         # (E_p and dX carry ds a_r, a cancelling sum over a row's edges: no row of them has a scale

@@ -357,3 +357,24 @@ def test_bwd_summed_grads_do_not_depend_on_the_number_of_partitions():
         da_r += bw.da_r
     assert rel_err(tot_dZ, ref_dZ) < 1e-12
     assert rel_err(da_l, ref.da_l) < 1e-12 and rel_err(da_r, ref.da_r) < 1e-12
+
+
+# ---------------------------------------------------------------- all-cores loops
+
+@pytest.mark.parametrize("P,p,H,D", [(1, 0, 2, 3), (3, 1, 4, 5), (5, 4, 1, 8)])
+def test_all_cores_loops_equal_the_serial_ones(P, p, H, D):
+    """The OpenMP loops of the timed baseline against the serial oracle (which the tests above
+    pin): the forward and everything a row owns add their terms in the same order, so they agree
+    to the last bit; the parameter gradients are summed per thread and agree to rounding."""
+    rng, src, dst, part, Z, Zs, members, a_l, a_r, blocks, deg = setup(9, 400, 6000, P, p, H, D, simple=False)
+    G = rng.standard_normal((blocks[0].n_dst, H, D))
+    fw = orc.gat_fwd(blocks, Zs[p], Zs, a_l, a_r, SLOPE)
+    fp = orc.gat_fwd_par(blocks, Zs[p], Zs, a_l, a_r, SLOPE)
+    assert np.array_equal(fp.out, fw.out) and np.array_equal(fp.L, fw.L)
+    bw = orc.gat_bwd(blocks, Zs[p], Zs, G, a_l, a_r, SLOPE, fw)
+    bp = orc.gat_bwd_par(blocks, Zs[p], Zs, G, a_l, a_r, SLOPE, fp)
+    assert np.array_equal(bp.ds, bw.ds) and np.array_equal(bp.dZdst, bw.dZdst)
+    for q in range(P):
+        assert np.array_equal(bp.dZs[q], bw.dZs[q]) and np.array_equal(bp.dt[q], bw.dt[q])
+    assert rel_err(bp.da_l, bw.da_l) < 1e-12 and rel_err(bp.da_r, bw.da_r) < 1e-12
+    assert orc.threads() >= 1
