@@ -141,11 +141,19 @@ int sar_version(void);
  *   src,dst    [E] global node ids of the edges j->i (src = j, dst = i);
  *              idx_bytes = 4 (int32) or 8 (int64).  Edges whose destination is
  *              not in partition p are ignored.  Ids must lie in [0,N).
+ *              E is not limited (the whole graph's list may be passed); the edges
+ *              KEPT for worker p must be fewer than 2^31 (32-bit offsets inside
+ *              the handle), else SAR_ERR_UNSUPPORTED.
  *   part       [N] partition of every node, each in [0,P)
- *   P <= SAR_MAX_BLOCKS, every block must hold fewer than 2^31 edges and every
- *   partition fewer than 2^31 nodes.
- * The result is integer work and bit-exact: it does not depend on thread
- * scheduling.  *out is a new handle the caller frees with sar_blocks_free. */
+ *   P <= SAR_MAX_BLOCKS, N < 2^31.
+ * The CSR arrays, their transposes, the degrees and the touched lists / ranks are
+ * integer work and bit-exact: they do not depend on thread scheduling.  The launch
+ * lists (rows, t_rows) are filled through atomic cursors, so the order of the rows
+ * INSIDE a degree class differs from build to build; that order decides which
+ * workgroup sums which rows into the partial sums of da_l / da_r, whose last bits
+ * are therefore reproducible for one handle, not across handles built from the same
+ * edges (ds is order-dependent through its atomics in any case).
+ * *out is a new handle the caller frees with sar_blocks_free. */
 int sar_blocks_build(const void* src, const void* dst, int idx_bytes, int64_t E,
                      const int32_t* part, int64_t N, int P, int p, int flags, void* stream,
                      sar_blocks_t** out);

@@ -217,8 +217,10 @@ __global__ __launch_bounds__(kThreads) void k_edge_count(const IdxT* __restrict_
                                                          const int32_t* __restrict__ part, int64_t N,
                                                          int p, const int32_t* __restrict__ lid,
                                                          int64_t n_dst, int32_t* __restrict__ row_cnt,
+                                                         unsigned long long* __restrict__ kept,
                                                          int* __restrict__ err)
 {
+    unsigned long long mine = 0;
     for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < E;
          e += (int64_t)gridDim.x * kThreads) {
         const int64_t d = (int64_t)dst[e], s = (int64_t)src[e];
@@ -228,7 +230,11 @@ __global__ __launch_bounds__(kThreads) void k_edge_count(const IdxT* __restrict_
         }
         if (part[d] != p) continue;
         atomicAdd(&row_cnt[(int64_t)part[s] * n_dst + lid[d]], 1);
+        ++mine;
     }
+    // edges kept for this worker, in 64 bits: the 32-bit offsets that follow must not wrap
+    for (int o = 32; o > 0; o >>= 1) mine += __shfl_xor(mine, o);
+    if ((threadIdx.x & 63) == 0 && mine) atomicAdd(kept, mine);
 }
 
 // Uses row_cnt as a countdown cursor: slot order inside a row is arbitrary
@@ -596,6 +602,9 @@ int derive(sar_blocks* h, hipStream_t st)
         n_src_total += b.n_src;
         n_src_max = std::max(n_src_max, b.n_src);
     }
+    if (n_src_total >= ((int64_t)1 << 31))
+        return sar::fail(SAR_ERR_UNSUPPORTED, "the %d source partitions hold %lld nodes in total; a handle's work "
+                         "lists index fewer than 2^31", P, (long long)n_src_total);
     h->tag_shift = std::max(1, bits_for(std::max<int64_t>(n_src_max, 2)));
     if (h->tag_shift + bits_for(P) > 32)
         return sar::fail(SAR_ERR_UNSUPPORTED, "P=%d blocks of up to %lld sources do not fit a 32-bit tagged index",
@@ -863,14 +872,23 @@ int build_from_edges(sar_blocks* h, const void* src, const void* dst, int idx_by
     SAR_HIP(hipMemsetAsync(row_cnt, 0, (n_rows_all + 1) * sizeof(int32_t), st));
     const unsigned ge = grid_for(E, kThreads, 1 << 16);
     if (E > 0) {
+        unsigned long long* kept_d = nullptr;
+        SAR_TRY(tmp.alloc(&kept_d, 1));
+        SAR_HIP(hipMemsetAsync(kept_d, 0, sizeof(unsigned long long), st));
         if (idx_bytes == 4)
             k_edge_count<int32_t><<<ge, kThreads, 0, st>>>((const int32_t*)src, (const int32_t*)dst, E, part,
-                                                           N, p, lid, n_dst, row_cnt, err_d);
+                                                           N, p, lid, n_dst, row_cnt, kept_d, err_d);
         else
             k_edge_count<int64_t><<<ge, kThreads, 0, st>>>((const int64_t*)src, (const int64_t*)dst, E, part,
-                                                           N, p, lid, n_dst, row_cnt, err_d);
+                                                           N, p, lid, n_dst, row_cnt, kept_d, err_d);
         SAR_LAUNCH_CHECK();
         SAR_TRY(check_err_flag(err_d, st));
+        unsigned long long kept = 0;
+        SAR_HIP(hipMemcpyAsync(&kept, kept_d, sizeof(kept), hipMemcpyDeviceToHost, st));
+        SAR_HIP(hipStreamSynchronize(st));
+        if (kept >= (1ull << 31))
+            return sar::fail(SAR_ERR_UNSUPPORTED, "worker %d's share holds %llu in-edges; a handle holds fewer than 2^31",
+                             p, kept);
     }
     SAR_TRY(exclusive_scan(row_cnt, row_off, n_rows_all + 1, st, tmp));
     std::vector<int32_t> block_first(P + 1);
@@ -969,8 +987,8 @@ extern "C" int sar_blocks_build(const void* src, const void* dst, int idx_bytes,
     SAR_CHECK_ARG((flags & ~kKnownFlags) == 0, "unknown flags 0x%x", flags);
     if (P > SAR_MAX_BLOCKS)
         return sar::fail(SAR_ERR_UNSUPPORTED, "P=%d exceeds SAR_MAX_BLOCKS=%d", P, SAR_MAX_BLOCKS);
-    if (E >= ((int64_t)1 << 31) || N >= ((int64_t)1 << 31))
-        return sar::fail(SAR_ERR_UNSUPPORTED, "E and N must be below 2^31 (32-bit offsets)");
+    if (N >= ((int64_t)1 << 31))
+        return sar::fail(SAR_ERR_UNSUPPORTED, "N must be below 2^31 (32-bit node ids inside the handle)");
     sar_blocks* h = new (std::nothrow) sar_blocks();
     if (!h) return sar::fail(SAR_ERR_HIP, "out of host memory");
     h->P = P;

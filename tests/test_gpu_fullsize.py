@@ -212,10 +212,10 @@ def test_cfg5_full_size_sampled():
     check_gat("cfg5", 40, 6)
 
 
-@pytest.mark.parametrize("heads", [2, 4])
+@pytest.mark.parametrize("heads", [2, 4, 8])
 def test_head_sweep_full_size_sampled(heads):
     """The head-count sweep of Sec. 4.1 at its real size: the whole 2.45M-node graph as one block
-    (121.8M edges), heads of width 100 (the padded lane geometry; 4 heads = 2 launches of 2)."""
+    (121.8M edges), heads of width 100 (the padded lane geometry; 4 / 8 heads = 2 / 4 launches of 2)."""
     check_gat("fak%d" % heads, 100, 12)
     torch.cuda.empty_cache()
 
