@@ -32,10 +32,14 @@
  *     all accumulation is fp32.
  *   - a_r multiplies the destination's z_i and a_l the source's z_j: the vector
  *     a of Eq. 3 is [a_r ; a_l] in the order the equation writes z_i || z_j.
- *   - Supported shapes: D (and, for the sum/mean calls, F) a multiple of 4 (fp32)
- *     or 8 (bf16); one head at most 1024 bytes wide.  Rows wider than 1024 bytes
- *     are processed as several launches over groups of heads (or column ranges).
- *     Anything else returns SAR_ERR_UNSUPPORTED.
+ *   - Shapes.  A wavefront covers a head with 64 lanes that each move the largest
+ *     piece of 16, 8, 4 (or, for bf16, 2) bytes that divides the head: any head
+ *     width D that is a multiple of 4 (fp32) / 8 (bf16) up to 1024 bytes is taken
+ *     at full speed, other widths with narrower lane pieces as long as the head
+ *     fits 64 of them (fp32: D <= 128 for even D, D <= 64 for odd D; bf16: D <= 256
+ *     for D % 4 == 0, D <= 128 for even D, D <= 64 for odd D).  A wider head returns
+ *     SAR_ERR_UNSUPPORTED.  Rows of several heads are processed as several launches
+ *     over groups of heads, rows of the sum/mean calls (any F) over column ranges.
  *   - A destination with no in-edge at all has out = 0 and L = -inf, and
  *     contributes nothing to any gradient; the mean of an empty set is 0.
  *     A tensor without elements (n_dst = 0, or a block without sources) may be
@@ -216,8 +220,7 @@ int sar_spmm_all(const sar_blocks_t* b, const void* const* Zq, int dtype, int F,
 
 /* Backward through the non-linearity of Eq. 2 / Eq. 3, with its derivative
  * taken from the output: G = dH * act'(.), for ReLU G = dH where h > 0, else 0.
- * h, dH, G: `count` values of `dtype` (count a multiple of 4 for fp32, 8 for
- * bf16; 16-byte aligned; G may alias dH).  G is then the error of the aggregate
+ * h, dH, G: `count` values of `dtype` (16-byte aligned; G may alias dH).  G is then the error of the aggregate
  * (for sar_spmm_bwd_block) and of the residual rows (for sar_linear_bwd). */
 int sar_act_bwd(const void* h, const void* dH, int act, void* G, int dtype, int64_t count,
                 void* stream);

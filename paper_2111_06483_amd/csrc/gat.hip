@@ -737,21 +737,25 @@ int check_shape(int dtype, int H, int D)
 {
     if (dtype != SAR_F32 && dtype != SAR_BF16)
         return sar::fail(SAR_ERR_UNSUPPORTED, "dtype %d is neither SAR_F32 nor SAR_BF16", dtype);
-    const int vec = dtype == SAR_F32 ? 4 : 8;
     if (H <= 0 || D <= 0) return sar::fail(SAR_ERR_INVALID_ARG, "H and D must be positive (H=%d, D=%d)", H, D);
-    if (D % vec != 0)
-        return sar::fail(SAR_ERR_UNSUPPORTED, "D=%d must be a multiple of %d for this dtype", D, vec);
-    if (D / vec > 64)
-        return sar::fail(SAR_ERR_UNSUPPORTED, "one head of D=%d values is wider than 1024 bytes", D);
+    // a head is covered by lanes that each move the largest piece (16, 8, 4 or 2 bytes) dividing it
+    const int piece = piece_for(dtype == SAR_F32, D);
+    if (D / piece > 64)
+        return sar::fail(SAR_ERR_UNSUPPORTED, "one head of D=%d values in pieces of %d needs more than the 64 lanes "
+                         "of a wavefront", D, piece);
     return SAR_OK;
 }
 
 // Heads are independent in Eq. 3, so a layer whose rows exceed what one wavefront covers
-// (1024 bytes) is processed as several launches over groups of heads, each launch seeing its
-// slice of every row through the row stride.
+// (64 lane pieces: 1024 bytes when the head width is a whole number of 16-byte pieces) is
+// processed as several launches over groups of heads, each launch seeing its slice of every
+// row through the row stride.
 struct HeadGroups {
     int n, Hg, Fg;       // groups, heads per group, values per group
     size_t fb;           // bytes per feature value
+    int piece;           // values per lane of the generic and node-wise kernels (divides D)
+    bool fast;           // the specialised gather kernels take a group (they use the full row type)
+    int full;            // values per lane of the full row type: 4 (fp32) or 8 (bf16)
 };
 
 // Lanes per head of the specialised kernels for head width D: the power of two >= D/4 (4..64), or 0.
@@ -763,11 +767,19 @@ int lanes_per_head(int D)
     return lph;
 }
 
+struct FastGeo {
+    int lph;     // 0: not applicable
+    bool pad;
+};
+FastGeo fast_geo(int H, int D, int ldz);
+
 HeadGroups head_groups(int dtype, int H, int D)
 {
     HeadGroups g;
     g.fb = dtype == SAR_F32 ? 4 : 2;
-    int hg = std::max<int>(1, (int)(1024 / (D * g.fb)));
+    g.full = dtype == SAR_F32 ? 4 : 8;
+    g.piece = piece_for(dtype == SAR_F32, D);
+    int hg = std::max<int>(1, 64 * g.piece / D);
     hg = std::min(hg, H);
     while (H % hg != 0) --hg;
     // groups of 64/LPH heads fill one wavefront of the specialised kernels exactly
@@ -776,6 +788,7 @@ HeadGroups head_groups(int dtype, int H, int D)
     g.Hg = hg;
     g.n = H / hg;
     g.Fg = hg * D;
+    g.fast = fast_geo(hg, D, H * D).lph != 0;
     return g;
 }
 
@@ -832,12 +845,8 @@ unsigned persistent_grid_for(int64_t n_rows, int64_t n_long, int resident)
 
 // Whether the specialised kernels take a launch of H heads of width D in rows of stride ldz, and
 // in which geometry: exact (contiguous rows of 256 values, power-of-two head width) or padded
-// (64/LPH heads of any width up to 4*LPH, any row stride; built for LPH = 16, 32, 64).
-struct FastGeo {
-    int lph;     // 0: not applicable
-    bool pad;
-};
-
+// (64/LPH heads of any width up to 4*LPH that is a multiple of 4, any row stride; built for
+// LPH = 16, 32, 64).  Lanes move 4 values (16 bytes of fp32, 8 bytes of bf16) either way.
 FastGeo fast_geo(int H, int D, int ldz)
 {
     const int lph = lanes_per_head(D);
@@ -873,28 +882,32 @@ template <typename T, bool ALL>
 int launch_fwd(const FwdArgs& a, const PtrTab& zt, const PtrTab& tt, int P, hipStream_t st)
 {
     if (a.n_rows == 0) return SAR_OK;
+    if constexpr (is_full_row<T>::value) {
 #define SAR_FWD_F256(LPH, PAD)                                                             \
     return a.a_l ? launch_fwd_f256<T, LPH, ALL, true, PAD>(a, zt, tt, st)                  \
                  : launch_fwd_f256<T, LPH, ALL, false, PAD>(a, zt, tt, st)
-    const FastGeo geo = fast_geo(a.H, a.D, a.ldz);
-    if (geo.pad) {
-        switch (geo.lph) {
-            case 16: SAR_FWD_F256(16, true);
-            case 32: SAR_FWD_F256(32, true);
-            case 64: SAR_FWD_F256(64, true);
-            default: break;
+        const FastGeo geo = fast_geo(a.H, a.D, a.ldz);
+        if (geo.pad) {
+            switch (geo.lph) {
+                case 16: SAR_FWD_F256(16, true);
+                case 32: SAR_FWD_F256(32, true);
+                case 64: SAR_FWD_F256(64, true);
+                default: break;
+            }
+        } else {
+            switch (geo.lph) {
+                case 4: SAR_FWD_F256(4, false);
+                case 8: SAR_FWD_F256(8, false);
+                case 16: SAR_FWD_F256(16, false);
+                case 32: SAR_FWD_F256(32, false);
+                case 64: SAR_FWD_F256(64, false);
+                default: break;
+            }
         }
-    } else {
-        switch (geo.lph) {
-            case 4: SAR_FWD_F256(4, false);
-            case 8: SAR_FWD_F256(8, false);
-            case 16: SAR_FWD_F256(16, false);
-            case 32: SAR_FWD_F256(32, false);
-            case 64: SAR_FWD_F256(64, false);
-            default: break;
-        }
-    }
 #undef SAR_FWD_F256
+        if (a.D % Vec<T>::N != 0)
+            return sar::fail(SAR_ERR_STATE, "head width %d reached the generic kernel with %d-value pieces", a.D, Vec<T>::N);
+    }
     const unsigned grid = persistent_grid(a.n_rows, a.n_long);
     if constexpr (ALL) {
         if (a.act == SAR_ACT_RELU) {
@@ -1045,27 +1058,34 @@ int launch_bwd(const BwdArgs& tabs, BwdScalars& a, float* da_l, hipStream_t st)
 {
     if (a.n_rows == 0) return SAR_OK;
     unsigned grid = persistent_grid(a.n_rows, a.n_long);
-    const FastGeo geo = fast_geo(a.H, a.D, a.ldz);
-    if (geo.pad) {
-        switch (geo.lph) {
-            case 16: SAR_TRY((launch_bwd_f256_padded<T, 16, ALL>(tabs, a, &grid, st))); break;
-            case 32: SAR_TRY((launch_bwd_f256_padded<T, 32, ALL>(tabs, a, &grid, st))); break;
-            default: SAR_TRY((launch_bwd_f256_padded<T, 64, ALL>(tabs, a, &grid, st))); break;
-        }
-        k_reduce_partials_padded<<<256, 256, 0, st>>>(a.partial, (int)grid, geo.lph, a.D, da_l);
-        SAR_LAUNCH_CHECK();
-        return SAR_OK;
-    }
-    switch (geo.lph) {
-        case 4: SAR_TRY((launch_bwd_f256<T, 4, ALL>(tabs, a, &grid, st))); break;
-        case 8: SAR_TRY((launch_bwd_f256<T, 8, ALL>(tabs, a, &grid, st))); break;
-        case 16: SAR_TRY((launch_bwd_f256<T, 16, ALL>(tabs, a, &grid, st))); break;
-        case 32: SAR_TRY((launch_bwd_f256<T, 32, ALL>(tabs, a, &grid, st))); break;
-        case 64: SAR_TRY((launch_bwd_f256<T, 64, ALL>(tabs, a, &grid, st))); break;
-        default:
-            SAR_DISPATCH_G(T, a.F, (k_gat_bwd<T, kG, ALL><<<grid, kGatherThreads, 0, st>>>(tabs, a)));
+    bool done = false;
+    if constexpr (is_full_row<T>::value) {
+        const FastGeo geo = fast_geo(a.H, a.D, a.ldz);
+        if (geo.pad) {
+            switch (geo.lph) {
+                case 16: SAR_TRY((launch_bwd_f256_padded<T, 16, ALL>(tabs, a, &grid, st))); break;
+                case 32: SAR_TRY((launch_bwd_f256_padded<T, 32, ALL>(tabs, a, &grid, st))); break;
+                default: SAR_TRY((launch_bwd_f256_padded<T, 64, ALL>(tabs, a, &grid, st))); break;
+            }
+            k_reduce_partials_padded<<<256, 256, 0, st>>>(a.partial, (int)grid, geo.lph, a.D, da_l);
             SAR_LAUNCH_CHECK();
-            break;
+            return SAR_OK;
+        }
+        done = true;
+        switch (geo.lph) {
+            case 4: SAR_TRY((launch_bwd_f256<T, 4, ALL>(tabs, a, &grid, st))); break;
+            case 8: SAR_TRY((launch_bwd_f256<T, 8, ALL>(tabs, a, &grid, st))); break;
+            case 16: SAR_TRY((launch_bwd_f256<T, 16, ALL>(tabs, a, &grid, st))); break;
+            case 32: SAR_TRY((launch_bwd_f256<T, 32, ALL>(tabs, a, &grid, st))); break;
+            case 64: SAR_TRY((launch_bwd_f256<T, 64, ALL>(tabs, a, &grid, st))); break;
+            default: done = false; break;
+        }
+        if (!done && a.D % Vec<T>::N != 0)
+            return sar::fail(SAR_ERR_STATE, "head width %d reached the generic kernel with %d-value pieces", a.D, Vec<T>::N);
+    }
+    if (!done) {
+        SAR_DISPATCH_G(T, a.F, (k_gat_bwd<T, kG, ALL><<<grid, kGatherThreads, 0, st>>>(tabs, a)));
+        SAR_LAUNCH_CHECK();
     }
     k_reduce_partials<<<a.F, 256, 0, st>>>(a.partial, (int)grid, a.F, da_l);
     SAR_LAUNCH_CHECK();
@@ -1085,8 +1105,9 @@ int sar::gat_scores2(const void* Z, int dtype, int64_t n, int H, int D, const fl
         return sar::fail(SAR_ERR_UNSUPPORTED, "dtype %d is neither SAR_F32 nor SAR_BF16", dtype);
     SAR_CHECK_ARG(H > 0 && D > 0, "H and D must be positive (H=%d, D=%d)", H, D);
     SAR_CHECK_ARG((a2 == nullptr) == (score2 == nullptr), "the second vector and its output go together");
-    if (a2 && D % (dtype == SAR_F32 ? 4 : 8) != 0) {
-        // (only the transform asks for two vectors at once; any head width is a valid product)
+    if (D / piece_for(dtype == SAR_F32, D) > 64) {
+        // a head that no wavefront covers in lane pieces (an odd width above 64, say): one thread
+        // per (node, head); any width is a valid product of the transform
         SAR_CHECK_ARG(n >= 0, "n is negative");
         if (n == 0) return SAR_OK;
         SAR_CHECK_ARG(Z && a && score, "Z, a or score is null");
@@ -1114,13 +1135,9 @@ int sar::gat_scores2(const void* Z, int dtype, int64_t n, int H, int D, const fl
         float* sg = score + (size_t)g * hg.Hg;
         const float* ag2 = a2 ? a2 + (size_t)g * hg.Fg : nullptr;
         float* sg2 = score2 ? score2 + (size_t)g * hg.Hg : nullptr;
-        if (dtype == SAR_F32) {
-            SAR_DISPATCH_G(float, hg.Fg, (k_scores<float, kG><<<nodewise_grid(n, kWave / kG), kGatherThreads, 0, st>>>(
-                                             static_cast<const float*>(Zg), n, hg.Hg, D, hg.Fg, F, H, ag, sg, ag2, sg2)));
-        } else {
-            SAR_DISPATCH_G(bf16_t, hg.Fg, (k_scores<bf16_t, kG><<<nodewise_grid(n, kWave / kG), kGatherThreads, 0, st>>>(
-                                              static_cast<const bf16_t*>(Zg), n, hg.Hg, D, hg.Fg, F, H, ag, sg, ag2, sg2)));
-        }
+        SAR_DISPATCH_ROW(dtype, hg.piece,
+                         SAR_DISPATCH_G(T, hg.Fg, (k_scores<T, kG><<<nodewise_grid(n, kWave / kG), kGatherThreads, 0, st>>>(
+                                                      static_cast<const T*>(Zg), n, hg.Hg, D, hg.Fg, F, H, ag, sg, ag2, sg2))));
         SAR_LAUNCH_CHECK();
     }
     return SAR_OK;
@@ -1179,10 +1196,8 @@ extern "C" int sar_gat_fwd_block(const sar_blocks_t* b, int q, const void* Zq, c
         a.ldh = H;
         a.slope = slope;
         PtrTab none{};
-        if (dtype == SAR_F32)
-            SAR_TRY((launch_fwd<float, false>(a, none, none, 0, sar::as_stream(stream))));
-        else
-            SAR_TRY((launch_fwd<bf16_t, false>(a, none, none, 0, sar::as_stream(stream))));
+        SAR_DISPATCH_ROW(dtype, hg.fast ? hg.full : hg.piece,
+                         SAR_TRY((launch_fwd<T, false>(a, none, none, 0, sar::as_stream(stream)))));
     }
     return SAR_OK;
 }
@@ -1201,15 +1216,10 @@ extern "C" int sar_gat_fwd_end(const float* m, const float* l, const float* acc,
     hipStream_t st = sar::as_stream(stream);
     for (int g = 0; g < hg.n; ++g) {
         const size_t f0 = (size_t)g * hg.Fg, h0 = (size_t)g * hg.Hg;
-        if (dtype == SAR_F32) {
-            SAR_DISPATCH_G(float, hg.Fg, (k_fwd_end<float, kG><<<nodewise_grid(n_dst, kWave / kG), kGatherThreads, 0, st>>>(
-                                             m + h0, l + h0, acc + f0, static_cast<float*>(out) + f0, L + h0, n_dst,
-                                             hg.Hg, D, hg.Fg, F, H, act)));
-        } else {
-            SAR_DISPATCH_G(bf16_t, hg.Fg, (k_fwd_end<bf16_t, kG><<<nodewise_grid(n_dst, kWave / kG), kGatherThreads, 0, st>>>(
-                                              m + h0, l + h0, acc + f0, static_cast<bf16_t*>(out) + f0, L + h0, n_dst,
-                                              hg.Hg, D, hg.Fg, F, H, act)));
-        }
+        SAR_DISPATCH_ROW(dtype, hg.piece,
+                         SAR_DISPATCH_G(T, hg.Fg, (k_fwd_end<T, kG><<<nodewise_grid(n_dst, kWave / kG), kGatherThreads, 0, st>>>(
+                                                      m + h0, l + h0, acc + f0, static_cast<T*>(out) + f0, L + h0, n_dst,
+                                                      hg.Hg, D, hg.Fg, F, H, act))));
         SAR_LAUNCH_CHECK();
     }
     return SAR_OK;
@@ -1258,10 +1268,7 @@ extern "C" int sar_gat_fwd_all(const sar_blocks_t* b, const void* const* Zq, con
         a.tag_shift = b->tag_shift;
         a.slope = slope;
         a.act = act;
-        if (dtype == SAR_F32)
-            SAR_TRY((launch_fwd<float, true>(a, zt, tt, b->P, st)));
-        else
-            SAR_TRY((launch_fwd<bf16_t, true>(a, zt, tt, b->P, st)));
+        SAR_DISPATCH_ROW(dtype, hg.fast ? hg.full : hg.piece, SAR_TRY((launch_fwd<T, true>(a, zt, tt, b->P, st))));
     }
     return SAR_OK;
 }
@@ -1293,17 +1300,11 @@ extern "C" int sar_gat_bwd_begin(const void* G, const void* out, const float* s,
         const void* Gg = shift(G, f0 * hg.fb);
         const void* og = shift(out, f0 * hg.fb);
         float4* recg = reinterpret_cast<float4*>(rec) + h0;
-        if (dtype == SAR_F32) {
-            SAR_DISPATCH_G(float, hg.Fg, (k_bwd_begin<float, kG><<<nodewise_grid(n_dst, kWave / kG), kGatherThreads, 0, st>>>(
-                                             static_cast<const float*>(Gg), static_cast<const float*>(og), s + h0, L + h0,
-                                             recg, ds + h0, n_dst, hg.Hg, D, hg.Fg, F, H, act,
-                                             static_cast<float*>(shift(Gact, f0 * hg.fb)))));
-        } else {
-            SAR_DISPATCH_G(bf16_t, hg.Fg, (k_bwd_begin<bf16_t, kG><<<nodewise_grid(n_dst, kWave / kG), kGatherThreads, 0, st>>>(
-                                              static_cast<const bf16_t*>(Gg), static_cast<const bf16_t*>(og), s + h0,
-                                              L + h0, recg, ds + h0, n_dst, hg.Hg, D, hg.Fg, F, H, act,
-                                              static_cast<bf16_t*>(shift(Gact, f0 * hg.fb)))));
-        }
+        SAR_DISPATCH_ROW(dtype, hg.piece,
+                         SAR_DISPATCH_G(T, hg.Fg, (k_bwd_begin<T, kG><<<nodewise_grid(n_dst, kWave / kG), kGatherThreads, 0, st>>>(
+                                                      static_cast<const T*>(Gg), static_cast<const T*>(og), s + h0, L + h0,
+                                                      recg, ds + h0, n_dst, hg.Hg, D, hg.Fg, F, H, act,
+                                                      static_cast<T*>(shift(Gact, f0 * hg.fb))))));
         SAR_LAUNCH_CHECK();
     }
     return SAR_OK;
@@ -1381,10 +1382,7 @@ extern "C" int sar_gat_bwd_block(const sar_blocks_t* b, int q, const void* Zq, c
         a.n_src_host = &k.n_src;
         a.n_blocks = 1;
         fill_bwd_group(a, hg, g, H, D, G, rec, a_l, ds, work, slope);
-        if (dtype == SAR_F32)
-            SAR_TRY((launch_bwd<float, false>(tabs, a, da_l + f0, st)));
-        else
-            SAR_TRY((launch_bwd<bf16_t, false>(tabs, a, da_l + f0, st)));
+        SAR_DISPATCH_ROW(dtype, hg.fast ? hg.full : hg.piece, SAR_TRY((launch_bwd<T, false>(tabs, a, da_l + f0, st))));
     }
     return SAR_OK;
 }
@@ -1431,10 +1429,7 @@ extern "C" int sar_gat_bwd_all(const sar_blocks_t* b, const void* const* Zq, con
         a.n_long = b->n_ft_long;
         a.tag_shift = b->tag_shift;
         fill_bwd_group(a, hg, g, H, D, G, rec, a_l, ds, work, slope);
-        if (dtype == SAR_F32)
-            SAR_TRY((launch_bwd<float, true>(tabs, a, da_l + f0, st)));
-        else
-            SAR_TRY((launch_bwd<bf16_t, true>(tabs, a, da_l + f0, st)));
+        SAR_DISPATCH_ROW(dtype, hg.fast ? hg.full : hg.piece, SAR_TRY((launch_bwd<T, true>(tabs, a, da_l + f0, st))));
     }
     return SAR_OK;
 }
@@ -1479,24 +1474,16 @@ int bwd_end_impl(const void* Zdst, const float* ds, const float* a_r, const void
     for (int g = 0; g < hg.n; ++g) {
         const size_t f0 = (size_t)g * hg.Fg, h0 = (size_t)g * hg.Hg;
         unsigned grid = 1;
-        const int slots = kWave / lanes_for(hg.Fg, dtype == SAR_F32 ? 4 : 8);
+        const int slots = kWave / lanes_for(hg.Fg, hg.piece);
         grid = nodewise_grid(n_dst, slots);
         if ((size_t)grid * hg.Fg > partial_floats)
             return sar::fail(SAR_ERR_UNSUPPORTED, "%u workgroups x %d partial sums exceed the %zu values of scratch",
                              grid, hg.Fg, partial_floats);
-        if (dtype == SAR_F32) {
-            SAR_DISPATCH_G(float, hg.Fg, (k_bwd_end<float, kG><<<grid, kGatherThreads, 0, st>>>(
-                                              static_cast<const float*>(Zdst) + f0, ds + h0, a_r + f0,
-                                              dZadd ? static_cast<const float*>(dZadd) + f0 : nullptr, dZadd_rank,
-                                              static_cast<float*>(dZdst) + f0, partial, n_dst, hg.Hg,
-                                              D, hg.Fg, F, H)));
-        } else {
-            SAR_DISPATCH_G(bf16_t, hg.Fg, (k_bwd_end<bf16_t, kG><<<grid, kGatherThreads, 0, st>>>(
-                                               static_cast<const bf16_t*>(Zdst) + f0, ds + h0, a_r + f0,
-                                               dZadd ? static_cast<const bf16_t*>(dZadd) + f0 : nullptr, dZadd_rank,
-                                               static_cast<bf16_t*>(dZdst) + f0, partial, n_dst,
-                                               hg.Hg, D, hg.Fg, F, H)));
-        }
+        SAR_DISPATCH_ROW(dtype, hg.piece,
+                         SAR_DISPATCH_G(T, hg.Fg, (k_bwd_end<T, kG><<<grid, kGatherThreads, 0, st>>>(
+                                                      static_cast<const T*>(Zdst) + f0, ds + h0, a_r + f0,
+                                                      dZadd ? static_cast<const T*>(dZadd) + f0 : nullptr, dZadd_rank,
+                                                      static_cast<T*>(dZdst) + f0, partial, n_dst, hg.Hg, D, hg.Fg, F, H))));
         SAR_LAUNCH_CHECK();
         k_reduce_partials<<<hg.Fg, 256, 0, st>>>(partial, (int)grid, hg.Fg, da_r + f0);
         SAR_LAUNCH_CHECK();

@@ -81,25 +81,148 @@ struct Vec<bf16_t> {
     }
 };
 
-// fp32 rows of VEC values (the accumulator rows), 16 bytes at a time
+// Narrow row types: the same storage moved in lane pieces of fewer than 16 bytes, for head widths
+// (or row widths) that are not a whole number of 16-byte pieces.  sizeof(Piece) is one stored
+// value, so pointer arithmetic on a Piece* counts values like it does on float* / bf16_t*.
+template <typename Base, int N>
+struct Piece {
+    Base v;
+};
+using f32x2_t = Piece<float, 2>;     // fp32 rows, 8 bytes per lane
+using f32x1_t = Piece<float, 1>;     //            4 bytes
+using bf16x4_t = Piece<bf16_t, 4>;   // bf16 rows, 8 bytes per lane
+using bf16x2_t = Piece<bf16_t, 2>;   //            4 bytes
+using bf16x1_t = Piece<bf16_t, 1>;   //            2 bytes
+
+template <int NN>
+struct Vec<Piece<float, NN>> {
+    static constexpr int N = NN;
+    static_assert(N == 1 || N == 2, "fp32 pieces of 4 or 8 bytes");
+    using T = Piece<float, N>;
+    struct Raw {
+        float v[N];
+    };
+    static __device__ inline Raw load(const T* p)
+    {
+        Raw r;
+        if constexpr (N == 2) {
+            const float2 x = *reinterpret_cast<const float2*>(p);
+            r.v[0] = x.x;
+            r.v[1] = x.y;
+        } else {
+            r.v[0] = *reinterpret_cast<const float*>(p);
+        }
+        return r;
+    }
+    static __device__ inline Raw zero()
+    {
+        Raw r;
+#pragma unroll
+        for (int k = 0; k < N; ++k) r.v[k] = 0.f;
+        return r;
+    }
+    static __device__ inline void unpack(const Raw& r, float (&v)[N])
+    {
+#pragma unroll
+        for (int k = 0; k < N; ++k) v[k] = r.v[k];
+    }
+    static __device__ inline void store(T* p, const float (&v)[N])
+    {
+        if constexpr (N == 2)
+            *reinterpret_cast<float2*>(p) = make_float2(v[0], v[1]);
+        else
+            *reinterpret_cast<float*>(p) = v[0];
+    }
+};
+
+template <int NN>
+struct Vec<Piece<bf16_t, NN>> {
+    static constexpr int N = NN;
+    static_assert(N == 1 || N == 2 || N == 4, "bf16 pieces of 2, 4 or 8 bytes");
+    using T = Piece<bf16_t, N>;
+    struct Raw {
+        uint32_t w[N == 4 ? 2 : 1];
+    };
+    static __device__ inline Raw load(const T* p)
+    {
+        Raw r;
+        if constexpr (N == 4) {
+            const uint2 x = *reinterpret_cast<const uint2*>(p);
+            r.w[0] = x.x;
+            r.w[1] = x.y;
+        } else if constexpr (N == 2) {
+            r.w[0] = *reinterpret_cast<const uint32_t*>(p);
+        } else {
+            r.w[0] = *reinterpret_cast<const uint16_t*>(p);
+        }
+        return r;
+    }
+    static __device__ inline Raw zero()
+    {
+        Raw r;
+        r.w[0] = 0u;
+        if constexpr (N == 4) r.w[1] = 0u;
+        return r;
+    }
+    static __device__ inline void unpack(const Raw& r, float (&v)[N])
+    {
+        if constexpr (N == 1) {
+            v[0] = __uint_as_float(r.w[0] << 16);
+        } else {
+#pragma unroll
+            for (int k = 0; k < N / 2; ++k) {
+                v[2 * k] = __uint_as_float(r.w[k] << 16);
+                v[2 * k + 1] = __uint_as_float(r.w[k] & 0xffff0000u);
+            }
+        }
+    }
+    static __device__ inline void store(T* p, const float (&v)[N])
+    {
+        if constexpr (N == 1) {
+            *reinterpret_cast<uint16_t*>(p) = (uint16_t)f32_to_bf16_rne(v[0]);
+        } else if constexpr (N == 2) {
+            *reinterpret_cast<uint32_t*>(p) = f32_to_bf16_rne(v[0]) | (f32_to_bf16_rne(v[1]) << 16);
+        } else {
+            *reinterpret_cast<uint2*>(p) = make_uint2(f32_to_bf16_rne(v[0]) | (f32_to_bf16_rne(v[1]) << 16),
+                                                      f32_to_bf16_rne(v[2]) | (f32_to_bf16_rne(v[3]) << 16));
+        }
+    }
+};
+
+// fp32 rows of N values (the accumulator rows): 16 bytes at a time, or one narrower access
 template <int N>
 __device__ inline void load_f32(const float* p, float (&v)[N])
 {
+    if constexpr (N % 4 == 0) {
 #pragma unroll
-    for (int k = 0; k < N; k += 4) {
-        const float4 x = *reinterpret_cast<const float4*>(p + k);
-        v[k] = x.x;
-        v[k + 1] = x.y;
-        v[k + 2] = x.z;
-        v[k + 3] = x.w;
+        for (int k = 0; k < N; k += 4) {
+            const float4 x = *reinterpret_cast<const float4*>(p + k);
+            v[k] = x.x;
+            v[k + 1] = x.y;
+            v[k + 2] = x.z;
+            v[k + 3] = x.w;
+        }
+    } else if constexpr (N == 2) {
+        const float2 x = *reinterpret_cast<const float2*>(p);
+        v[0] = x.x;
+        v[1] = x.y;
+    } else {
+        static_assert(N == 1, "accumulator pieces of 1, 2 or a multiple of 4 values");
+        v[0] = p[0];
     }
 }
 template <int N>
 __device__ inline void store_f32(float* p, const float (&v)[N])
 {
+    if constexpr (N % 4 == 0) {
 #pragma unroll
-    for (int k = 0; k < N; k += 4)
-        *reinterpret_cast<float4*>(p + k) = make_float4(v[k], v[k + 1], v[k + 2], v[k + 3]);
+        for (int k = 0; k < N; k += 4)
+            *reinterpret_cast<float4*>(p + k) = make_float4(v[k], v[k + 1], v[k + 2], v[k + 3]);
+    } else if constexpr (N == 2) {
+        *reinterpret_cast<float2*>(p) = make_float2(v[0], v[1]);
+    } else {
+        p[0] = v[0];
+    }
 }
 
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -147,6 +270,59 @@ struct LaneMap {
         h = hh < H ? hh : H - 1;
         head_first = slot * G + h * lph;
     }
+};
+
+// Largest lane piece (in values) that divides a head (or row) width w: 4, 2, 1 for fp32 rows,
+// 8, 4, 2, 1 for bf16 rows.
+inline int piece_for(int dtype_is_f32, int w)
+{
+    for (int v = dtype_is_f32 ? 4 : 8; v > 1; v >>= 1)
+        if (w % v == 0) return v;
+    return 1;
+}
+
+// Runs `...` with T bound to the row type of (dtype, piece).
+#define SAR_DISPATCH_ROW(dtype, piece, ...)                  \
+    do {                                                     \
+        if ((dtype) == SAR_F32) {                            \
+            if ((piece) == 4) {                              \
+                using T = float;                             \
+                __VA_ARGS__;                                 \
+            } else if ((piece) == 2) {                       \
+                using T = ::sar::f32x2_t;                    \
+                __VA_ARGS__;                                 \
+            } else {                                         \
+                using T = ::sar::f32x1_t;                    \
+                __VA_ARGS__;                                 \
+            }                                                \
+        } else {                                             \
+            if ((piece) == 8) {                              \
+                using T = ::sar::bf16_t;                     \
+                __VA_ARGS__;                                 \
+            } else if ((piece) == 4) {                       \
+                using T = ::sar::bf16x4_t;                   \
+                __VA_ARGS__;                                 \
+            } else if ((piece) == 2) {                       \
+                using T = ::sar::bf16x2_t;                   \
+                __VA_ARGS__;                                 \
+            } else {                                         \
+                using T = ::sar::bf16x1_t;                   \
+                __VA_ARGS__;                                 \
+            }                                                \
+        }                                                    \
+    } while (0)
+
+template <typename T>
+struct is_full_row {
+    static constexpr bool value = false;
+};
+template <>
+struct is_full_row<float> {
+    static constexpr bool value = true;
+};
+template <>
+struct is_full_row<bf16_t> {
+    static constexpr bool value = true;
 };
 
 inline int lanes_for(int F, int vec)

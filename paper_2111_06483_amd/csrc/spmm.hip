@@ -370,24 +370,25 @@ int check_row_shape(int dtype, int F)
 {
     if (dtype != SAR_F32 && dtype != SAR_BF16)
         return sar::fail(SAR_ERR_UNSUPPORTED, "dtype %d is neither SAR_F32 nor SAR_BF16", dtype);
-    const int vec = dtype == SAR_F32 ? 4 : 8;
-    if (F <= 0 || F % vec != 0)
-        return sar::fail(SAR_ERR_UNSUPPORTED, "F=%d must be a positive multiple of %d for this dtype", F, vec);
+    if (F <= 0) return sar::fail(SAR_ERR_INVALID_ARG, "F=%d must be positive", F);
     return SAR_OK;
 }
 
-// Rows wider than one wavefront covers (1024 bytes) are processed as several launches over
-// column ranges, each seeing its slice of every row through the row stride.
+// A wavefront covers 64 lane pieces of a row (1024 bytes when the row width is a whole number of
+// 16-byte pieces, less when lanes have to move 8, 4 or 2 bytes); wider rows are processed as
+// several launches over column ranges, each seeing its slice of every row through the row stride.
 struct ColumnChunks {
     int n, width;   // launches and values per launch (the last launch may be narrower)
     size_t fb;
+    int piece;      // values per lane: the largest of 16, 8, 4, 2 bytes' worth that divides F
 };
 
 ColumnChunks column_chunks(int dtype, int F)
 {
     ColumnChunks c;
     c.fb = dtype == SAR_F32 ? 4 : 2;
-    c.width = (int)(1024 / c.fb);
+    c.piece = piece_for(dtype == SAR_F32, F);
+    c.width = 64 * c.piece;
     c.n = (F + c.width - 1) / c.width;
     return c;
 }
@@ -426,10 +427,7 @@ extern "C" int sar_spmm_block(const sar_blocks_t* b, int q, const void* Zq, int 
         a.Z = shift(Zq, f0 * cc.fb);
         a.acc = acc + f0;
         a.F = std::min<int>(cc.width, F - (int)f0);
-        if (dtype == SAR_F32)
-            SAR_TRY((launch_spmm<float, Mode::kBlock>(a, tab, 0, sar::as_stream(stream))));
-        else
-            SAR_TRY((launch_spmm<bf16_t, Mode::kBlock>(a, tab, 0, sar::as_stream(stream))));
+        SAR_DISPATCH_ROW(dtype, cc.piece, SAR_TRY((launch_spmm<T, Mode::kBlock>(a, tab, 0, sar::as_stream(stream)))));
     }
     return SAR_OK;
 }
@@ -450,10 +448,9 @@ extern "C" int sar_act_bwd(const void* h, const void* dH, int act, void* G, int 
     if (dtype != SAR_F32 && dtype != SAR_BF16)
         return sar::fail(SAR_ERR_UNSUPPORTED, "dtype %d is neither SAR_F32 nor SAR_BF16", dtype);
     SAR_TRY(check_act(act));
-    const int vec = dtype == SAR_F32 ? 4 : 8;
-    SAR_CHECK_ARG(count >= 0 && count % vec == 0, "count=%lld must be a non-negative multiple of %d",
-                  (long long)count, vec);
+    SAR_CHECK_ARG(count >= 0, "count=%lld is negative", (long long)count);
     if (count == 0) return SAR_OK;
+    const int vec = piece_for(dtype == SAR_F32, (int)(count % 64 == 0 ? 64 : count % 64));
     SAR_CHECK_ARG(h && dH && G, "h, dH or G is null");
     SAR_CHECK_ARG(aligned16(h) && aligned16(dH) && aligned16(G), "h, dH and G must be 16-byte aligned");
     hipStream_t st = sar::as_stream(stream);
@@ -463,12 +460,8 @@ extern "C" int sar_act_bwd(const void* h, const void* dH, int act, void* G, int 
     }
     const int64_t n_vec = count / vec;
     const unsigned grid = (unsigned)std::min<int64_t>((n_vec + 255) / 256, 1 << 20);
-    if (dtype == SAR_F32)
-        k_act_bwd<float><<<grid, 256, 0, st>>>(static_cast<const float*>(h), static_cast<const float*>(dH),
-                                               static_cast<float*>(G), n_vec);
-    else
-        k_act_bwd<bf16_t><<<grid, 256, 0, st>>>(static_cast<const bf16_t*>(h), static_cast<const bf16_t*>(dH),
-                                                static_cast<bf16_t*>(G), n_vec);
+    SAR_DISPATCH_ROW(dtype, vec, (k_act_bwd<T><<<grid, 256, 0, st>>>(static_cast<const T*>(h), static_cast<const T*>(dH),
+                                                                     static_cast<T*>(G), n_vec)));
     SAR_LAUNCH_CHECK();
     return SAR_OK;
 }
@@ -483,14 +476,10 @@ extern "C" int sar_spmm_end(const int32_t* deg, int mean, const float* acc, cons
     if (n_dst == 0) return SAR_OK;
     SAR_CHECK_ARG(acc && out && (!mean || deg), "acc, out or deg is null");
     SAR_CHECK_ARG(aligned16(acc) && aligned16(out), "acc and out must be 16-byte aligned");
-    const int vec = dtype == SAR_F32 ? 4 : 8;
+    const int vec = piece_for(dtype == SAR_F32, F);
     const unsigned grid = (unsigned)std::min<int64_t>((n_dst * (F / vec) + 255) / 256, 1 << 20);
-    if (dtype == SAR_F32)
-        k_spmm_end<float><<<grid, 256, 0, sar::as_stream(stream)>>>(deg, mean, acc, static_cast<const float*>(residual),
-                                                                    act, static_cast<float*>(out), n_dst, F);
-    else
-        k_spmm_end<bf16_t><<<grid, 256, 0, sar::as_stream(stream)>>>(deg, mean, acc, static_cast<const bf16_t*>(residual),
-                                                                     act, static_cast<bf16_t*>(out), n_dst, F);
+    SAR_DISPATCH_ROW(dtype, vec, (k_spmm_end<T><<<grid, 256, 0, sar::as_stream(stream)>>>(
+                                     deg, mean, acc, static_cast<const T*>(residual), act, static_cast<T*>(out), n_dst, F)));
     SAR_LAUNCH_CHECK();
     return SAR_OK;
 }
@@ -530,10 +519,7 @@ extern "C" int sar_spmm_all(const sar_blocks_t* b, const void* const* Zq, int dt
         a.res = residual ? shift(residual, f0 * cc.fb) : nullptr;
         a.act = act;
         a.F = std::min<int>(cc.width, F - (int)f0);
-        if (dtype == SAR_F32)
-            SAR_TRY((launch_spmm<float, Mode::kAll>(a, tab, b->P, st)));
-        else
-            SAR_TRY((launch_spmm<bf16_t, Mode::kAll>(a, tab, b->P, st)));
+        SAR_DISPATCH_ROW(dtype, cc.piece, SAR_TRY((launch_spmm<T, Mode::kAll>(a, tab, b->P, st))));
     }
     return SAR_OK;
 }
@@ -568,10 +554,7 @@ extern "C" int sar_spmm_bwd_block(const sar_blocks_t* b, int q, const void* G, i
         a.Z = shift(G, f0 * cc.fb);
         a.out = shift(dZq, f0 * cc.fb);
         a.F = std::min<int>(cc.width, F - (int)f0);
-        if (dtype == SAR_F32)
-            SAR_TRY((launch_spmm<float, Mode::kBackward>(a, tab, 0, st)));
-        else
-            SAR_TRY((launch_spmm<bf16_t, Mode::kBackward>(a, tab, 0, st)));
+        SAR_DISPATCH_ROW(dtype, cc.piece, SAR_TRY((launch_spmm<T, Mode::kBackward>(a, tab, 0, st))));
     }
     return SAR_OK;
 }
@@ -614,10 +597,7 @@ extern "C" int sar_spmm_bwd_all(const sar_blocks_t* b, const void* G, int mean, 
         }
         a.Z = shift(G, f0 * cc.fb);
         a.F = std::min<int>(cc.width, F - (int)f0);
-        if (dtype == SAR_F32)
-            SAR_TRY(launch_spmm_bwd_all<float>(a, tabs, st));
-        else
-            SAR_TRY(launch_spmm_bwd_all<bf16_t>(a, tabs, st));
+        SAR_DISPATCH_ROW(dtype, cc.piece, SAR_TRY(launch_spmm_bwd_all<T>(a, tabs, st)));
     }
     return SAR_OK;
 }
@@ -631,15 +611,12 @@ extern "C" int sar_error_add(const void* Eq, const int32_t* t_rank, int accumula
     SAR_CHECK_ARG(t_rank && Ep, "t_rank or Ep is null");
     SAR_CHECK_ARG(aligned16(Eq) && aligned16(Ep), "Eq and Ep must be 16-byte aligned");
     SAR_CHECK_ARG(Eq != Ep, "Eq and Ep must not alias");
-    const int64_t total = n * (F / (dtype == SAR_F32 ? 4 : 8));
+    const int vec = piece_for(dtype == SAR_F32, F);
+    const int64_t total = n * (F / vec);
     const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>((total + 255) / 256, kMaxPersistentWGs * 4));
     hipStream_t st = sar::as_stream(stream);
-    if (dtype == SAR_F32)
-        k_error_add<float><<<grid, 256, 0, st>>>(static_cast<const float*>(Eq), t_rank, accumulate,
-                                                 static_cast<float*>(Ep), n, F);
-    else
-        k_error_add<bf16_t><<<grid, 256, 0, st>>>(static_cast<const bf16_t*>(Eq), t_rank, accumulate,
-                                                  static_cast<bf16_t*>(Ep), n, F);
+    SAR_DISPATCH_ROW(dtype, vec, (k_error_add<T><<<grid, 256, 0, st>>>(static_cast<const T*>(Eq), t_rank, accumulate,
+                                                                       static_cast<T*>(Ep), n, F)));
     SAR_LAUNCH_CHECK();
     return SAR_OK;
 }

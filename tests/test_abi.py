@@ -45,14 +45,19 @@ def test_validation_errors_need_no_gpu(lib):
     from paper_2111_06483_amd import sar
     i64 = ctypes.c_int64
     assert lib.sar_version() == 3
-    rc = lib.sar_gat_scores(None, 0, i64(5), 2, 3, None, None, None)
-    assert rc == sar.SAR_ERR_UNSUPPORTED and b"multiple of 4" in lib.sar_last_error()
+    rc = lib.sar_gat_scores(None, 0, i64(5), 2, 3, None, None, None)       # any head width is a valid score
+    assert rc == sar.SAR_ERR_INVALID_ARG and b"null" in lib.sar_last_error()
     rc = lib.sar_gat_scores(None, 7, i64(5), 2, 4, None, None, None)
     assert rc == sar.SAR_ERR_UNSUPPORTED
     rc = lib.sar_gat_scores(None, 0, i64(5), 2, 4, None, None, None)
     assert rc == sar.SAR_ERR_INVALID_ARG and b"null" in lib.sar_last_error()
-    rc = lib.sar_gat_scores(None, 0, i64(5), 1, 512, None, None, None)     # one head wider than 1 KiB
-    assert rc == sar.SAR_ERR_UNSUPPORTED and b"1024" in lib.sar_last_error()
+    # one head wider than the 64 lane pieces of a wavefront: 512 fp32 values (2 KiB), 65 values of odd width
+    rc = lib.sar_gat_fwd_end(None, None, None, 0, None, None, 0, i64(4), 1, 512, None)
+    assert rc == sar.SAR_ERR_UNSUPPORTED and b"64 lanes" in lib.sar_last_error()
+    rc = lib.sar_gat_fwd_end(None, None, None, 0, None, None, 0, i64(4), 2, 65, None)
+    assert rc == sar.SAR_ERR_UNSUPPORTED and b"64 lanes" in lib.sar_last_error()
+    rc = lib.sar_gat_fwd_end(None, None, None, 0, None, None, 0, i64(4), 2, 63, None)     # 63 one-value lanes: fine
+    assert rc == sar.SAR_ERR_INVALID_ARG and b"null" in lib.sar_last_error()
     rc = lib.sar_gat_scores(None, 0, i64(5), 8, 64, None, None, None)      # 2 KiB row of 8 heads: head groups
     assert rc == sar.SAR_ERR_INVALID_ARG and b"null" in lib.sar_last_error()
     h = ctypes.c_void_p()
@@ -70,7 +75,7 @@ def test_validation_errors_need_no_gpu(lib):
     rc = lib.sar_act_bwd(None, None, 9, None, 0, i64(8), None)
     assert rc == sar.SAR_ERR_UNSUPPORTED and b"SAR_ACT" in lib.sar_last_error()
     rc = lib.sar_act_bwd(None, None, sar.SAR_ACT_RELU, None, 0, i64(6), None)
-    assert rc == sar.SAR_ERR_INVALID_ARG and b"multiple of 4" in lib.sar_last_error()
+    assert rc == sar.SAR_ERR_INVALID_ARG and b"null" in lib.sar_last_error()
     assert lib.sar_act_bwd(None, None, sar.SAR_ACT_RELU, None, 1, i64(0), None) == 0       # nothing to do
     rc = lib.sar_spmm_end(None, 0, None, None, 5, None, 0, i64(4), 8, None)
     assert rc == sar.SAR_ERR_UNSUPPORTED

@@ -136,7 +136,7 @@ def test_wrap_equals_build():
 # --------------------------------------------------------------------- spmm
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
-@pytest.mark.parametrize("F", [8, 64, 200, 256, 800, 1032])
+@pytest.mark.parametrize("F", [8, 64, 200, 256, 800, 1032, 50, 7, 130, 33])
 @pytest.mark.parametrize("mean", [False, True])
 def test_spmm_parity(dtype, F, mean):
     src, dst, part, rng = make_graph(4, 3000, 40000, 3, simple=False)
@@ -201,13 +201,17 @@ def check_fwd(got, want, deg, dtype):
 # (heads, head width): every lane mapping of the generic kernels, every head width of the F = 256
 # kernels, non-power-of-two heads, and rows wider than 1 KiB (processed as groups of heads)
 SHAPES = [(4, 16), (1, 4), (4, 64), (8, 32), (2, 100), (3, 12), (1, 256), (2, 128), (16, 16),
-          (8, 100), (8, 64), (3, 200), (2, 256), (1, 512)]      # the last: the widest head of each row type
+          (8, 100), (8, 64), (3, 200), (2, 256), (1, 512),      # the last: the widest head of each row type
+          # head widths that are not whole 16-byte pieces: lanes move 8, 4 or 2 bytes
+          (3, 10), (2, 50), (4, 12), (5, 7), (2, 63), (1, 126), (6, 36)]
 
 
 def supported(dtype, D):
-    """Lanes move 16 bytes (4 fp32 or 8 bf16 values); one head is at most 1024 bytes wide."""
-    fb, vec = (4, 4) if dtype == torch.float32 else (2, 8)
-    return D % vec == 0 and D * fb <= 1024
+    """Lanes move the largest piece of 16, 8, 4 (bf16: 2) bytes that divides the head; a head fits 64 lanes."""
+    piece = 4 if dtype == torch.float32 else 8
+    while D % piece:
+        piece //= 2
+    return D // piece <= 64
 
 
 CASES = [(dt, H, D) for dt in (torch.float32, torch.bfloat16) for H, D in SHAPES if supported(dt, D)]

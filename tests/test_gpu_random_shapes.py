@@ -50,6 +50,9 @@ def draw(case):
                 empty=int(rng.integers(0, P)) if (P > 1 and rng.integers(0, 4) == 0) else None,
                 n_lin=int(rng.choice([1, 31, 33, 257, 1000, 5000])),
                 K=int(rng.choice([4, 8, 24, 40, 64, 100, 128, 200, 256])))
+    # one case in four: a head width that is not a whole number of 16-byte lane pieces
+    if rng.integers(0, 4) == 0:
+        D = max(1, D // vec) * int(rng.choice([1, 2]))
     return rng, N, E, P, H, D, dtype, opts
 
 
