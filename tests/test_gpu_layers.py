@@ -486,6 +486,18 @@ def test_compact_errors_equal_the_touched_rows_of_the_full_ones(dtype, H, D):
         sar.sar_gat_bwd_end(Zdst, ds, a_r, dZs[p], dZdst, da_r, work, dZadd_rank=b.view(p).t_rank)
         assert rel_err(f64(dZdst), wb.dZdst + wb.dZs[p]) < tol
         assert rel_err(f64(da_r), wb.da_r) < tol
+        # the owner's side of the exchange: a received compact error placed among, or added to, its rows
+        for q in (p, 2):                            # block 2 has no touched source: nothing arrives
+            v = b.view(q)
+            full = torch.full((v.n_src, H, D), float("nan"), dtype=dtype, device="cuda")
+            sar.sar_error_add(dZs[q] if len(touched[q]) else None, v.t_rank, False, full)
+            assert rel_err(f64(full), wb.dZs[q]) < tol
+            base = feats(rng, v.n_src, F, dtype).cuda().reshape(-1, H, D)
+            acc2 = base.clone()
+            sar.sar_error_add(dZs[q] if len(touched[q]) else None, v.t_rank, True, acc2)
+            assert rel_err(f64(acc2), f64(base) + wb.dZs[q]) < tol
+            untouched = np.setdiff1d(np.arange(v.n_src), touched[q])
+            assert torch.equal(acc2[untouched], base[untouched])
         with pytest.raises(sar.SarError):          # a full-height tensor is refused on a compact handle
             sar.sar_gat_bwd_block(b, 0, Zs[0], G, None, rec, a_l, SLOPE, torch.empty_like(Zs[0]), dts[0], ds, da_l, work)
 
