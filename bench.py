@@ -417,7 +417,7 @@ def time_gat(args, torch, sar, synth, name, steps, warmup, full_report):
     calls = {
         "gat_fwd": {"kernel": ("k_gat_fwd_f256" if fast else "k_gat_fwd") + (" (all blocks)" if args.mode == "all" else " (per block)"),
                     "avg_ms": fwd_ms, "alg_bytes": alg["gat_fwd"]},
-        "gat_bwd": {"kernel": ("k_gat_bwd_f256 + k_gat_bwd_narrow" if fast else "k_gat_bwd")
+        "gat_bwd": {"kernel": ("k_gat_bwd_f256 + k_gat_bwd_few" if fast else "k_gat_bwd")
                     + ("" if layer.errors != "full" else " + k_bwd_zero_rows"),
                     "avg_ms": bwd_ms, "alg_bytes": alg["gat_bwd"],
                     "alg_bytes_full_height": alg["gat_bwd_full_height"]},

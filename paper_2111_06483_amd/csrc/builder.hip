@@ -406,7 +406,7 @@ __global__ __launch_bounds__(kThreads) void k_class_place(const int32_t* __restr
 }
 
 struct ClassLayout {
-    int64_t n_rows = 0, n_long = 0, n_wide = 0, n_wide_f32 = 0;
+    int64_t n_rows = 0, n_long = 0, n_wide = 0;
     int start[sar::kNumClasses];
 };
 
@@ -437,7 +437,6 @@ ClassLayout layout_from_hist(const int* hist, int64_t offset, int floor_class)
         L.n_rows += hist[c];
         if (c >= long_class) L.n_long += hist[c];
         if (c > sar::kNarrowMaxClass) L.n_wide += hist[c];
-        if (c > sar::kNarrowMaxClassF32) L.n_wide_f32 += hist[c];
     }
     L.start[0] = (int)run;
     return L;
@@ -760,7 +759,6 @@ int derive(sar_blocks* h, hipStream_t st)
             h->blk[q].n_t_rows = L.n_rows;
             h->blk[q].n_t_long = L.n_long;
             h->blk[q].n_t_wide = L.n_wide;
-            h->blk[q].n_t_wide_f32 = L.n_wide_f32;
             memcpy(&cursors[q * sar::kNumClasses], L.start, sizeof(L.start));
             t_base[q] = t_rows_total;
             t_rows_total += L.n_rows;
@@ -770,7 +768,6 @@ int derive(sar_blocks* h, hipStream_t st)
         h->n_ft_rows = LA.n_rows;
         h->n_ft_long = LA.n_long;
         h->n_ft_wide = LA.n_wide;
-        h->n_ft_wide_f32 = LA.n_wide_f32;
         memcpy(&cursors[P * sar::kNumClasses], LA.start, sizeof(LA.start));
         int32_t *t_rows_all = nullptr, *touched_all = nullptr;
         // the launch lists also carry the sources without edges (last), so that the

@@ -304,7 +304,7 @@ struct BwdArgs {
 struct BwdScalars {
     const uint32_t* rows;       // source work list; tagged with the block when ALL
     int64_t n_rows, n_long;
-    int64_t n_wide;             // list entries [n_wide, n_rows) have few edges: four sources per wavefront
+    int64_t n_wide;             // list entries [n_wide, n_rows) have few edges: several sources per wavefront
     int64_t n_touched;          // list entries [n_touched, n_rows) have no edge at all
     const int64_t* n_src_host;  // host: rows of every block's dZ_q / dt_q (null: unknown)
     int n_blocks;
@@ -1002,9 +1002,10 @@ int launch_bwd_f256(const BwdArgs& tabs, const BwdScalars& a, unsigned* grid_out
 {
     constexpr int B = LPH >= 8 ? 8 : 4;
     auto wide = f256::k_gat_bwd_f256<T, LPH, B, ALL, false>;
-    auto narrow = f256::k_gat_bwd_narrow<T, LPH / 4, ALL>;
+    auto few = f256::k_gat_bwd_few<T, LPH, ALL>;
+    constexpr int kPerWave = B / 2;     // sources a wavefront of that kernel takes at once
     static const int resident_wide = resident_workgroups(wide);
-    static const int resident_narrow = resident_workgroups(narrow);
+    static const int resident_few = resident_workgroups(few);
     f256::BwdTabs t{};
     for (int q = 0; q < SAR_MAX_BLOCKS; ++q) {
         t.t_indptr[q] = tabs.t_indptr[q]; t.t_indices[q] = tabs.t_indices[q];
@@ -1015,7 +1016,7 @@ int launch_bwd_f256(const BwdArgs& tabs, const BwdScalars& a, unsigned* grid_out
     p.rows = a.rows; p.n_rows = a.n_wide; p.n_long = std::min(a.n_long, a.n_wide);
     p.G = a.G; p.rec = a.rec; p.a_l = a.a_l; p.ds = a.ds; p.partial = a.partial;
     p.H = a.H; p.tag_shift = a.tag_shift; p.slope = a.slope;
-    unsigned g_wide = 0, g_narrow = 0;
+    unsigned g_wide = 0, g_few = 0;
     const int64_t n_edged = std::max(a.n_wide, std::min(a.n_rows, a.n_touched));
     // Where many sources have no edge (a 16-way split leaves 46% of them without one), their 32-byte
     // rows of dt_q scattered through the array cost more to zero one by one than the whole array
@@ -1036,10 +1037,11 @@ int launch_bwd_f256(const BwdArgs& tabs, const BwdScalars& a, unsigned* grid_out
         SAR_LAUNCH_CHECK();
     }
     if (n_edged > a.n_wide) {
-        // the other sources with edges, four per wavefront
+        // the other sources with edges, several per wavefront
         const int64_t n = n_edged - a.n_wide;
-        g_narrow = (unsigned)std::max<int64_t>(1, std::min<int64_t>((n + 15) / 16, resident_narrow));
-        narrow<<<g_narrow, kGatherThreads, 0, st>>>(t, p, a.n_wide, n_edged, (int)g_wide);
+        const int64_t per_wg = (int64_t)kPerWave * kWavesPerWG;
+        g_few = (unsigned)std::max<int64_t>(1, std::min<int64_t>((n + per_wg - 1) / per_wg, resident_few));
+        few<<<g_few, kGatherThreads, 0, st>>>(t, p, a.n_wide, n_edged, (int)g_wide);
         SAR_LAUNCH_CHECK();
     }
     if (a.n_rows > n_edged) {
@@ -1049,7 +1051,7 @@ int launch_bwd_f256(const BwdArgs& tabs, const BwdScalars& a, unsigned* grid_out
                                                        a.tag_shift);
         SAR_LAUNCH_CHECK();
     }
-    *grid_out = g_wide + g_narrow;
+    *grid_out = g_wide + g_few;
     return SAR_OK;
 }
 
@@ -1377,7 +1379,7 @@ extern "C" int sar_gat_bwd_block(const sar_blocks_t* b, int q, const void* Zq, c
         // sources without edges come last and get dZ = 0, dt = 0, unless the handle skips them
         a.n_rows = sar::skips_untouched(b->flags) ? k.n_t_rows : k.n_src;
         a.n_long = k.n_t_long;
-        a.n_wide = dtype == SAR_F32 ? k.n_t_wide_f32 : k.n_t_wide;
+        a.n_wide = k.n_t_wide;
         a.n_touched = k.n_t_rows;
         a.n_src_host = &k.n_src;
         a.n_blocks = 1;
@@ -1422,7 +1424,7 @@ extern "C" int sar_gat_bwd_all(const sar_blocks_t* b, const void* const* Zq, con
         a.n_rows = 0;
         for (int q = 0; q < b->P; ++q) a.n_rows += b->blk[q].n_src;
         if (sar::skips_untouched(b->flags)) a.n_rows = b->n_ft_rows;
-        a.n_wide = dtype == SAR_F32 ? b->n_ft_wide_f32 : b->n_ft_wide;
+        a.n_wide = b->n_ft_wide;
         a.n_touched = b->n_ft_rows;
         a.n_src_host = n_src_all;
         a.n_blocks = b->P;

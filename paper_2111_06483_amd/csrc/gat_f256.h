@@ -527,77 +527,29 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_f256(BwdTabs tabs, B
 
 // ------------------------------------------- backward, rows of few edges
 //
-// A source with a handful of edges keeps a whole wavefront waiting on a chain
-// of dependent loads (list entry -> offsets -> indices -> G rows) while moving
-// little data; with ~2 edges per source (the papers100M-sized share) the wide
-// kernel is bound by that latency, not by bandwidth.  Here a wavefront works on
-// FOUR sources at once: 16 lanes per source, 16 consecutive features per lane,
-// every lane group walking its own edge list.  Heads are LPH16 = D/16 lanes
-// wide, so the per-edge scalars are recomputed by only D/16 lanes.
-
-template <typename T>
-struct Row16;
-template <>
-struct Row16<float> {
-    struct Raw { float4 a, b, c, d; };
-    static __device__ inline Raw load(const float* p)
-    {
-        const float4* q = reinterpret_cast<const float4*>(p);
-        return Raw{q[0], q[1], q[2], q[3]};
-    }
-    static __device__ inline void unpack(const Raw& r, float (&v)[16])
-    {
-        v[0] = r.a.x; v[1] = r.a.y; v[2] = r.a.z; v[3] = r.a.w;
-        v[4] = r.b.x; v[5] = r.b.y; v[6] = r.b.z; v[7] = r.b.w;
-        v[8] = r.c.x; v[9] = r.c.y; v[10] = r.c.z; v[11] = r.c.w;
-        v[12] = r.d.x; v[13] = r.d.y; v[14] = r.d.z; v[15] = r.d.w;
-    }
-    static __device__ inline void store(float* p, const float (&v)[16])
-    {
-        float4* q = reinterpret_cast<float4*>(p);
-        q[0] = make_float4(v[0], v[1], v[2], v[3]);
-        q[1] = make_float4(v[4], v[5], v[6], v[7]);
-        q[2] = make_float4(v[8], v[9], v[10], v[11]);
-        q[3] = make_float4(v[12], v[13], v[14], v[15]);
-    }
-};
-template <>
-struct Row16<bf16_t> {
-    struct Raw { uint4 a, b; };
-    static __device__ inline Raw load(const bf16_t* p)
-    {
-        const uint4* q = reinterpret_cast<const uint4*>(p);
-        return Raw{q[0], q[1]};
-    }
-    static __device__ inline void unpack(const Raw& r, float (&v)[16])
-    {
-        const uint32_t w[8] = {r.a.x, r.a.y, r.a.z, r.a.w, r.b.x, r.b.y, r.b.z, r.b.w};
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            v[2 * k] = __uint_as_float(w[k] << 16);
-            v[2 * k + 1] = __uint_as_float(w[k] & 0xffff0000u);
-        }
-    }
-    static __device__ inline void store(bf16_t* p, const float (&v)[16])
-    {
-        uint32_t w[8];
-#pragma unroll
-        for (int k = 0; k < 8; ++k) w[k] = f32_to_bf16_rne(v[2 * k]) | (f32_to_bf16_rne(v[2 * k + 1]) << 16);
-        uint4* q = reinterpret_cast<uint4*>(p);
-        q[0] = make_uint4(w[0], w[1], w[2], w[3]);
-        q[1] = make_uint4(w[4], w[5], w[6], w[7]);
-    }
-};
-
-// List entries [r_begin, r_end) of a.rows; partial sums of da_l go to
-// a.partial[(partial_row0 + blockIdx.x) * 256 ...].
-template <typename T, int LPH16, bool ALL>
-__global__ __launch_bounds__(kGatherThreads, 4) void k_gat_bwd_narrow(BwdTabs tabs, BwdP a, int64_t r_begin,
-                                                                   int64_t r_end, int partial_row0)
+// A source of fewer than 8 edges would leave most of a wide-kernel batch empty.  This kernel
+// keeps the lane geometry of the wide kernel -- lane x owns
+// features 4x..4x+3 of every row, so each row -- a source's own row, a gathered G row, the error
+// row written back -- is one fully coalesced wave-wide access.  Independent work comes from
+// taking S sources per wavefront at once: a round gathers B = S*R rows, R edges of each of the
+// S sources, and lane k of every head group speaks for gather slot k (the edge's record,
+// coefficient and score gradient), exactly as it speaks for edge k of a sub-batch in the wide
+// kernel; slot k always belongs to source k / R, so a lane's share of dt needs no indexing.
+//
+// What describes a source is read ahead by the lanes themselves, one register per field:
+// lane u*kAhead + e holds source u's list entry, edge range and output row, and the
+// destination of its edge e.  List entries are read three groups ahead, ranges two, and
+// destinations one, so that a group starts with its row gathers and no dependent chain.
+template <typename T, int LPH, bool ALL>
+__global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_few(BwdTabs tabs, BwdP a, int64_t r_begin, int64_t r_end,
+                                                                int partial_row0)
 {
-    constexpr int kSlots = 4;
-    __shared__ float s_al[kF];
-    __shared__ float s_part[kWavesPerWG * kSlots][kF];
+    constexpr int B = LPH >= 8 ? 8 : 4;   // gather slots per round
+    constexpr int R = 2;                  // slots per source
+    constexpr int S = B / R;              // sources per wavefront and group
+    constexpr int kAhead = 8;             // edges per source whose destinations are read ahead
+    static_assert(S * kAhead <= kWave, "one lane per (source, edge read ahead)");
+    __shared__ float part[kWavesPerWG][kWave][4];
     __shared__ const void* s_Z[SAR_MAX_BLOCKS];
     __shared__ const float* s_t[SAR_MAX_BLOCKS];
     __shared__ void* s_dZ[SAR_MAX_BLOCKS];
@@ -605,7 +557,6 @@ __global__ __launch_bounds__(kGatherThreads, 4) void k_gat_bwd_narrow(BwdTabs ta
     __shared__ const int32_t* s_ip[SAR_MAX_BLOCKS];
     __shared__ const int32_t* s_ix[SAR_MAX_BLOCKS];
     __shared__ const int32_t* s_rank[SAR_MAX_BLOCKS];
-    for (int f = threadIdx.x; f < kF; f += kGatherThreads) s_al[f] = a.a_l[f];
     if (threadIdx.x < SAR_MAX_BLOCKS) {
         s_Z[threadIdx.x] = tabs.Z[threadIdx.x];
         s_t[threadIdx.x] = tabs.t[threadIdx.x];
@@ -616,112 +567,182 @@ __global__ __launch_bounds__(kGatherThreads, 4) void k_gat_bwd_narrow(BwdTabs ta
         s_rank[threadIdx.x] = tabs.rank[threadIdx.x];
     }
     __syncthreads();
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-    const int slot = lane >> 4, k = lane & 15;
-    const int h = k / LPH16;
-    const bool head_lead = (k % LPH16) == 0;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int h = lane / LPH, k = lane % LPH;
+    const int foff = lane * 4;
     const uint32_t mask = ALL ? ((1u << a.tag_shift) - 1u) : 0xffffffffu;
     const T* Gp = static_cast<const T*>(a.G);
-    const int64_t n_slots = (int64_t)gridDim.x * kWavesPerWG * kSlots;
+    auto uni = [](int v) { return __builtin_amdgcn_readfirstlane(v); };
 
-    // this lane's share of da_l lives in LDS (16 private cells), not in registers
-    float* my_dal = &s_part[wave * kSlots + slot][k * 16];
+    float al[4], dal[4];
+    load_f32<4>(a.a_l + foff, al);
 #pragma unroll
-    for (int x = 0; x < 16; ++x) my_dal[x] = 0.f;
+    for (int x = 0; x < 4; ++x) dal[x] = 0.f;
 
-    // Software pipeline over this lane group's rows: the list entry is read two rows
-    // ahead and the row's offsets and own features one row ahead, so that only
-    // "indices -> G rows" remains as a dependent chain per row.
-    struct Meta {
-        int q;
-        int64_t j, jo;      // source row, and the row of dZ / dt it owns
-        int beg, end;
-        typename Row16<T>::Raw z;
-    };
-    auto fetch_meta = [&](uint32_t id) {
-        Meta m;
-        m.q = ALL ? (int)(id >> a.tag_shift) : 0;
-        m.j = (int64_t)(id & mask);
-        m.beg = s_ip[m.q][m.j];
-        m.end = s_ip[m.q][m.j + 1];
-        m.jo = s_rank[m.q] ? (int64_t)s_rank[m.q][m.j] : m.j;
-        m.z = Row16<T>::load(static_cast<const T*>(s_Z[m.q]) + m.j * kF + k * 16);
+    // ---- the lanes' read-ahead of list entries, ranges and destinations
+    const bool meta_lane = lane < S * kAhead;
+    const int mu = lane / kAhead, me = lane % kAhead;
+    const int64_t stride = (int64_t)gridDim.x * kWavesPerWG * S;
+    struct Range { int q, j, beg, end, jo; };
+    auto valid = [&](int64_t g) { return meta_lane && g + mu < r_end; };
+    auto load_id = [&](int64_t g) -> uint32_t { return valid(g) ? a.rows[g + mu] : 0u; };
+    auto load_range = [&](uint32_t id, int64_t g) {
+        Range m{0, 0, 0, 0, 0};
+        if (valid(g)) {
+            m.q = ALL ? (int)(id >> a.tag_shift) : 0;
+            m.j = (int)(id & mask);
+            const int32_t* ip = s_ip[m.q];
+            m.beg = ip[m.j];
+            m.end = ip[m.j + 1];
+            m.jo = s_rank[m.q] ? s_rank[m.q][m.j] : m.j;
+        }
         return m;
     };
-    const int64_t r0 = r_begin + ((int64_t)blockIdx.x * kWavesPerWG + wave) * kSlots + slot;
-    uint32_t id_next = r0 < r_end ? a.rows[r0] : 0u;
-    uint32_t id_next2 = r0 + n_slots < r_end ? a.rows[r0 + n_slots] : 0u;
-    Meta next{};
-    if (r0 < r_end) next = fetch_meta(id_next);
-    for (int64_t r = r0; r < r_end; r += n_slots) {
-        const Meta cur = next;
-        id_next = id_next2;
-        if (r + 2 * n_slots < r_end) id_next2 = a.rows[r + 2 * n_slots];
-        if (r + n_slots < r_end) next = fetch_meta(id_next);
-        const int q = cur.q;
-        const int64_t j = cur.j;
-        float zj[16];
-        Row16<T>::unpack(cur.z, zj);
-        float t2;
-        if (s_t[q]) {
-            t2 = s_t[q][j * a.H + h] * kLog2e;
-        } else {
-            float c = 0.f;
+    auto load_dst = [&](const Range& m, int64_t g) { return (valid(g) && me < m.end - m.beg) ? s_ix[m.q][m.beg + me] : 0; };
+
+    int64_t g0 = r_begin + ((int64_t)blockIdx.x * kWavesPerWG + wave) * S;
+    uint32_t id2 = load_id(g0 + 2 * stride);
+    Range m0 = load_range(load_id(g0), g0), m1 = load_range(load_id(g0 + stride), g0 + stride);
+    int dst0 = load_dst(m0, g0);
+
+    for (; g0 < r_end; g0 += stride) {
+        const int dst1 = load_dst(m1, g0 + stride);
+        const Range m2 = load_range(id2, g0 + 2 * stride);
+        const uint32_t id3 = load_id(g0 + 3 * stride);
+
+        // ---- the S sources of this group: uniform values out of the lanes that hold them
+        bool have[S];
+        int q[S], j[S], beg[S], end[S], jo[S];
+        typename Row4<T>::Raw zr[S];
+        int rounds = 0;
+        static_for<S>([&](auto uu) {
+            constexpr int u = decltype(uu)::value;
+            have[u] = g0 + u < r_end;
+            q[u] = __builtin_amdgcn_readlane(m0.q, u * kAhead);
+            j[u] = __builtin_amdgcn_readlane(m0.j, u * kAhead);
+            beg[u] = __builtin_amdgcn_readlane(m0.beg, u * kAhead);
+            end[u] = __builtin_amdgcn_readlane(m0.end, u * kAhead);
+            jo[u] = __builtin_amdgcn_readlane(m0.jo, u * kAhead);
+            rounds = max(rounds, end[u] - beg[u]);
+            zr[u] = typename Row4<T>::Raw{};
+            if (have[u]) zr[u] = load_lane<T, false>(static_cast<const T*>(s_Z[q[u]]) + (int64_t)j[u] * kF, foff, true);
+        });
+        float t2[S], dz[S][4];
+        static_for<S>([&](auto uu) {
+            constexpr int u = decltype(uu)::value;
 #pragma unroll
-            for (int x = 0; x < 16; ++x) c = fmaf(s_al[k * 16 + x], zj[x], c);
-            t2 = group_all<LPH16, OpSum>(c) * kLog2e;
-        }
-        const int32_t* idx = s_ix[q];
-        const int beg = cur.beg, end = cur.end;
-        float dz[16], dt = 0.f;
+            for (int x = 0; x < 4; ++x) dz[u][x] = 0.f;
+            t2[u] = 0.f;
+            if (have[u]) {
+                if (s_t[q[u]]) {
+                    t2[u] = s_t[q[u]][(int64_t)j[u] * a.H + h] * kLog2e;
+                } else {   // t_j = <a_l, z_j> from the row this wavefront holds
+                    float zj[4];
+                    Row4<T>::unpack(zr[u], zj);
+                    float c = al[0] * zj[0];
 #pragma unroll
-        for (int x = 0; x < 16; ++x) dz[x] = 0.f;
-        for (int e = beg; e < end; e += 2) {
-            const bool two = e + 1 < end;
-            const int64_t i0 = idx[e], i1 = idx[two ? e + 1 : e];
-            const typename Row16<T>::Raw r0 = Row16<T>::load(Gp + i0 * kF + k * 16);
-            const typename Row16<T>::Raw r1 = Row16<T>::load(Gp + i1 * kF + k * 16);
-            const float4 rec0 = a.rec[i0 * a.H + h], rec1 = a.rec[i1 * a.H + h];
-            float g0[16], g1[16];
-            Row16<T>::unpack(r0, g0);
-            Row16<T>::unpack(r1, g1);
-            float c0 = 0.f, c1 = 0.f;
-#pragma unroll
-            for (int x = 0; x < 16; ++x) {
-                c0 = fmaf(g0[x], zj[x], c0);
-                c1 = fmaf(g1[x], zj[x], c1);
+                    for (int x = 1; x < 4; ++x) c = fmaf(al[x], zj[x], c);
+                    t2[u] = group_all<LPH, OpSum>(c) * kLog2e;
+                }
             }
-            c0 = group_all<LPH16, OpSum>(c0);
-            c1 = group_all<LPH16, OpSum>(c1);
-            const float u0 = rec0.x + t2, u1 = rec1.x + t2;
-            const float al0 = fast_exp2(leaky2(u0, a.slope) - rec0.y);
-            const float al1 = two ? fast_exp2(leaky2(u1, a.slope) - rec1.y) : 0.f;
-            const float de0 = al0 * (c0 - rec0.z), de1 = al1 * (c1 - rec1.z);
-            const float du0 = u0 > 0.f ? de0 : a.slope * de0, du1 = u1 > 0.f ? de1 : a.slope * de1;
+        });
+        // the source this lane's slot belongs to
+        float t2_mine = t2[0];
+        static_for<S>([&](auto uu) { t2_mine = (k / R == decltype(uu)::value) ? t2[decltype(uu)::value] : t2_mine; });
+        float dt_mine = 0.f;
+
+        for (int e = 0; e < rounds; e += R) {
+            int dst[B];
+            bool ok[B];
+            typename Row4<T>::Raw raw[B];
+            static_for<B>([&](auto kk) {
+                constexpr int K = decltype(kk)::value, u = K / R, r = K % R;
+                ok[K] = beg[u] + e + r < end[u];
+                dst[K] = 0;
+                raw[K] = typename Row4<T>::Raw{};
+                if (ok[K])
+                    dst[K] = e + r < kAhead ? __builtin_amdgcn_readlane(dst0, u * kAhead + e + r)
+                                            : uni(s_ix[q[u]][beg[u] + e + r]);
+            });
+            static_for<B>([&](auto kk) {
+                constexpr int K = decltype(kk)::value;
+                if (ok[K]) raw[K] = load_lane<T, false>(Gp + (int64_t)dst[K] * kF, foff, true);
+            });
+            // lane k speaks for slot k
+            int my_i = 0;
+            bool my_ok = false;
+            static_for<B>([&](auto kk) {
+                constexpr int K = decltype(kk)::value;
+                my_i = (k == K) ? dst[K] : my_i;
+                my_ok = (k == K) ? ok[K] : my_ok;
+            });
+            float4 rec = make_float4(0.f, INFINITY, 0.f, 0.f);   // L = +inf gives alpha = 0
+            if (my_ok) rec = a.rec[(int64_t)my_i * a.H + h];
+            float c_mine = 0.f;
+            static_for<B>([&](auto kk) {
+                constexpr int K = decltype(kk)::value;
+                float g[4], zj[4];
+                Row4<T>::unpack(raw[K], g);
+                Row4<T>::unpack(zr[K / R], zj);
+                float c = g[0] * zj[0];
 #pragma unroll
-            for (int x = 0; x < 16; ++x) dz[x] = fmaf(al0, g0[x], fmaf(al1, g1[x], dz[x]));
-            dt += du0 + du1;
-            if (head_lead) {
-                unsafeAtomicAdd(a.ds + i0 * a.H + h, du0);
-                if (two) unsafeAtomicAdd(a.ds + i1 * a.H + h, du1);
+                for (int x = 1; x < 4; ++x) c = fmaf(g[x], zj[x], c);
+                c = group_all<LPH, OpSum>(c);
+                c_mine = (k == K) ? c : c_mine;
+            });
+            const float u2 = rec.x + t2_mine;
+            const float alpha = my_ok ? fast_exp2(leaky2(u2, a.slope) - rec.y) : 0.f;
+            const float de = alpha * (c_mine - rec.z);
+            const float du = u2 > 0.f ? de : a.slope * de;
+            dt_mine += du;
+            if (my_ok) unsafeAtomicAdd(a.ds + (int64_t)my_i * a.H + h, du);
+            static_for<B>([&](auto kk) {
+                constexpr int K = decltype(kk)::value;
+                const float ak = group_bcast<LPH, K>(alpha);
+                float g[4];
+                Row4<T>::unpack(raw[K], g);
+#pragma unroll
+                for (int x = 0; x < 4; ++x) dz[K / R][x] = fmaf(ak, g[x], dz[K / R][x]);
+            });
+        }
+
+        // ---- dZ_q[j] = sum alpha G + dt a_l ; dt_q[j] = dt ; da_l += dt z_j
+        static_for<S>([&](auto uu) {
+            constexpr int u = decltype(uu)::value;
+            float dt = 0.f;
+            static_for<R>([&](auto rr) { dt += group_bcast<LPH, u * R + decltype(rr)::value>(dt_mine); });
+            if (have[u]) {
+                float v[4], zj[4];
+                Row4<T>::unpack(zr[u], zj);
+#pragma unroll
+                for (int x = 0; x < 4; ++x) {
+                    v[x] = fmaf(dt, al[x], dz[u][x]);
+                    dal[x] = fmaf(dt, zj[x], dal[x]);
+                }
+                Row4<T>::store(static_cast<T*>(s_dZ[q[u]]) + (int64_t)jo[u] * kF, lane, v);
+                if (k == 0) s_dt[q[u]][(int64_t)jo[u] * a.H + h] = dt;
             }
-        }
-        float v[16];
-#pragma unroll
-        for (int x = 0; x < 16; ++x) {
-            v[x] = fmaf(dt, s_al[k * 16 + x], dz[x]);
-            my_dal[x] = fmaf(dt, zj[x], my_dal[x]);
-        }
-        Row16<T>::store(static_cast<T*>(s_dZ[q]) + cur.jo * kF + k * 16, v);
-        if (head_lead) s_dt[q][cur.jo * a.H + h] = dt;
+        });
+        m0 = m1;
+        dst0 = dst1;
+        m1 = m2;
+        id2 = id3;
     }
 
     // this workgroup's share of da_l
+#pragma unroll
+    for (int x = 0; x < 4; ++x) part[wave][lane][x] = dal[x];
     __syncthreads();
-    for (int f = threadIdx.x; f < kF; f += kGatherThreads) {
-        float s = 0.f;
-        for (int w = 0; w < kWavesPerWG * kSlots; ++w) s += s_part[w][f];
-        a.partial[((int64_t)partial_row0 + blockIdx.x) * kF + f] = s;
+    if (wave == 0) {
+        float v[4];
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            float s = 0.f;
+            for (int w = 0; w < kWavesPerWG; ++w) s += part[w][lane][x];
+            v[x] = s;
+        }
+        store_f32<4>(a.partial + ((int64_t)partial_row0 + blockIdx.x) * kF + lane * 4, v);
     }
 }
 

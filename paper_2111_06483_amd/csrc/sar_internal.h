@@ -48,13 +48,11 @@ constexpr int kLongRowBlock = 128;
 constexpr int kLongClassBlock = 8;   // 1 + log2(kLongRowBlock)
 constexpr int kNumClasses = 32;
 // Rows of fewer than 8 edges (degree classes 1..3, and the empty class 0) are
-// "narrow": the backward kernels process four of them per wavefront.
+// "narrow": the backward kernels process several of them per wavefront.  (Measured on the
+// backward pass of the 8-way products-sized share, fp32: the two kernels together take 3.00 ms
+// with the split at 4 edges, 2.92 at 8 and 2.93 at 16; with bf16 rows on the papers-sized share
+// the split at 8 and at 16 cost the same.)
 constexpr int kNarrowMaxClass = 3;
-// With fp32 rows the split sits lower, at 4 edges (classes 0..2): a whole wavefront gathers the
-// 1 KiB rows of a 4..7-edge source in one batch faster than a quarter wavefront does in two to
-// four dependent rounds.  (Measured: 3.65 -> 3.52 ms for the backward pass of the 8-way products-
-// sized share; with 512-byte bf16 rows the split at 8 is the better one, 53.1 against 54.1 ms.)
-constexpr int kNarrowMaxClassF32 = 2;
 
 struct Block {
     int64_t n_dst = 0, n_src = 0, nnz = 0;
@@ -67,7 +65,6 @@ struct Block {
     int32_t* t_rows = nullptr;
     int64_t n_rows_wide = 0;                             // destination rows with >= 8 edges (head of `rows`)
     int64_t n_t_rows = 0, n_t_long = 0, n_t_wide = 0;   // n_t_wide: sources with >= 8 edges
-    int64_t n_t_wide_f32 = 0;                            // sources with >= 4 edges
     int32_t* touched = nullptr;
     int32_t* t_rank = nullptr;                           // [n_src+1]: touched sources below j
 };
@@ -99,6 +96,6 @@ struct sar_blocks {
     // All-blocks source-side work list: (q << tag_shift) | local source id of
     // every source with an edge, longest class first.
     uint32_t* ft_rows = nullptr;
-    int64_t n_ft_rows = 0, n_ft_long = 0, n_ft_wide = 0, n_ft_wide_f32 = 0;
+    int64_t n_ft_rows = 0, n_ft_long = 0, n_ft_wide = 0;
     std::vector<void*> owned;      // device allocations freed with the handle
 };
