@@ -660,7 +660,7 @@ def main():
                      "gather_volume_GBs": d["gather_volume_GBs"],
                      "calls": r["calls"],
                      "note": "the forward launch is one kernel; the backward call is two gather kernels (sources "
-                             "with at least 4 (fp32) / 8 (bf16) edges, and the others); per-kernel durations: "
+                             "with at least 8 edges one per wavefront, the others several per wavefront); per-kernel durations: "
                              "profiles/"},
     }
     if not args.no_ceilings:
