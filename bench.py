@@ -62,6 +62,9 @@ def parse():
     ap.add_argument("--storage", default="config", choices=["config", "f32", "bf16"],
                     help="storage type of the feature rows; 'config' keeps what the configuration names "
                          "(the headline, config 3, is fp32); accumulation is fp32 either way")
+    ap.add_argument("--graph", action="store_true",
+                    help="also record the step once into a HIP graph and time its replays (reported beside the "
+                         "eager figures as `graph_replay_ms_per_step`; the headline stays the eager step)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-transform", action="store_true",
                     help="skip the separate timing of the three transform products after the timed steps")
@@ -409,6 +412,26 @@ def time_gat(args, torch, sar, synth, name, steps, warmup, full_report):
     ms_step = wall * 1e3 / steps
     avg = lambda a, b: sum(e[a].elapsed_time(e[b]) for e in evs) / len(evs)
     fwd_ms, bwd_ms, all_ms = avg("fwd0", "fwd1"), avg("bwd0", "bwd1"), avg("t0", "t1")
+    graph_ms = None
+    if args.graph:
+        # the library only enqueues work on the stream it is given, so the step can be recorded once
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            layer.step(args.mode)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            layer.step(args.mode)
+        for _ in range(warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) * 1e3 / steps
     fb = 2 if w.dtype == torch.bfloat16 else 4
     alg = layer.alg_bytes()
     # in stream mode the events bracket P launches; report per launch
@@ -441,6 +464,7 @@ def time_gat(args, torch, sar, synth, name, steps, warmup, full_report):
         "calls": calls, "launches_per_call": launches,
         "builder_s": layer.builder_s,
         **({"subset_builder_s": layer.subset_s} if layer.subset else {}),
+        **({"graph_replay_ms_per_step": graph_ms} if graph_ms is not None else {}),
     }
     return res, layer, w
 
@@ -650,6 +674,7 @@ def main():
         "aggregation_only_edges_per_s": r["aggregation_only_edges_per_s"],
         "builder_s": r["builder_s"],
         **({"subset_builder_s": r["subset_builder_s"]} if "subset_builder_s" in r else {}),
+        **({"graph_replay_ms_per_step": r["graph_replay_ms_per_step"]} if "graph_replay_ms_per_step" in r else {}),
         "roofline": {"bound": "hbm", "kernel": d["kernel"],
                      "achieved": d["alg_GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": d["frac"],

@@ -24,6 +24,7 @@
 
 #include "../../include/sar_mi355x.h"
 #include "gather_common.h"
+#include "sar_internal.h"
 
 namespace sar {
 namespace f256 {
@@ -547,8 +548,9 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_few(BwdTabs tabs, Bw
     constexpr int B = LPH >= 8 ? 8 : 4;   // gather slots per round
     constexpr int R = 2;                  // slots per source
     constexpr int S = B / R;              // sources per wavefront and group
-    constexpr int kAhead = 8;             // edges per source whose destinations are read ahead
+    constexpr int kAhead = 8;             // edges per source whose destinations are read ahead: all of them
     static_assert(S * kAhead <= kWave, "one lane per (source, edge read ahead)");
+    static_assert((1 << kNarrowMaxClass) <= kAhead, "this kernel's sources have fewer than kAhead edges");
     __shared__ float part[kWavesPerWG][kWave][4];
     __shared__ const void* s_Z[SAR_MAX_BLOCKS];
     __shared__ const float* s_t[SAR_MAX_BLOCKS];
@@ -573,7 +575,6 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_few(BwdTabs tabs, Bw
     const int foff = lane * 4;
     const uint32_t mask = ALL ? ((1u << a.tag_shift) - 1u) : 0xffffffffu;
     const T* Gp = static_cast<const T*>(a.G);
-    auto uni = [](int v) { return __builtin_amdgcn_readfirstlane(v); };
 
     float al[4], dal[4];
     load_f32<4>(a.a_l + foff, al);
@@ -661,9 +662,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_few(BwdTabs tabs, Bw
                 ok[K] = beg[u] + e + r < end[u];
                 dst[K] = 0;
                 raw[K] = typename Row4<T>::Raw{};
-                if (ok[K])
-                    dst[K] = e + r < kAhead ? __builtin_amdgcn_readlane(dst0, u * kAhead + e + r)
-                                            : uni(s_ix[q[u]][beg[u] + e + r]);
+                if (ok[K]) dst[K] = __builtin_amdgcn_readlane(dst0, u * kAhead + e + r);
             });
             static_for<B>([&](auto kk) {
                 constexpr int K = decltype(kk)::value;
