@@ -260,6 +260,52 @@ def test_gat_backward_parity(dtype, H, D, batched, fly):
     b.close()
 
 
+@pytest.mark.parametrize("dtype,H,D", [(torch.float32, 4, 64), (torch.bfloat16, 8, 32), (torch.float32, 16, 16),
+                                       (torch.bfloat16, 1, 256), (torch.float32, 2, 128)])
+@pytest.mark.parametrize("n_src,degs", [(1, (3,)), (5, (1,)), (6, (7,)), (203, (1, 2, 3, 4, 5, 6, 7)), (66, (2, 7)),
+                                        (1027, (1, 1, 1, 2, 6))])
+def test_backward_sources_of_few_edges(dtype, H, D, n_src, degs):
+    """Sources of 1..7 edges only (the kernel that takes several sources per wavefront): every
+    degree, groups whose sources differ in degree, counts that do not fill the last group, one
+    source alone.  Partition 1 holds the sources, partition 0 the 40 destinations (each of which
+    also cites two others, so the local block has few-edge sources too)."""
+    rng = np.random.default_rng(100 * n_src + len(degs))
+    n_dst = 40
+    src, dst = [], []
+    for j in range(n_src):
+        k = degs[j % len(degs)]
+        src += [n_dst + j] * k
+        dst += rng.choice(n_dst, k, replace=False).tolist()
+    for j in range(n_dst):      # every destination has two local in-edges: no coefficient is exactly 1
+        src += [j, j]
+        dst += [(j + 1) % n_dst, (j + 7) % n_dst]
+    src, dst = np.array(src, dtype=np.int64), np.array(dst, dtype=np.int64)
+    part = np.concatenate([np.zeros(n_dst, np.int32), np.ones(n_src, np.int32)])
+    want_b, deg = orc.build_blocks(src, dst, part, 2, 0)
+    assert max(int(np.diff(w.t_indptr).max()) for w in want_b) < 8
+    b = gu.build_blocks(src, dst, part, 2, 0)
+    F = H * D
+    Zs = [feats(rng, w.n_src, F, dtype).cuda().reshape(-1, H, D) for w in want_b]
+    Zdst = feats(rng, n_dst, F, dtype).cuda().reshape(-1, H, D)
+    bound = np.sqrt(6.0 / (D + 1))
+    a_l = torch.from_numpy(rng.uniform(-bound, bound, (H, D)).astype(np.float32)).cuda()
+    a_r = torch.from_numpy(rng.uniform(-bound, bound, (H, D)).astype(np.float32)).cuda()
+    G = feats(rng, n_dst, F, dtype).cuda().reshape(-1, H, D)
+    wf = orc.gat_fwd(want_b, f64(Zdst), [f64(z) for z in Zs], f64(a_l), f64(a_r), SLOPE)
+    wb = orc.gat_bwd(want_b, f64(Zdst), [f64(z) for z in Zs], f64(G), f64(a_l), f64(a_r), SLOPE, wf)
+    fw = gu.gat_fwd_all(b, Zdst, Zs, a_l, a_r, SLOPE)
+    tol = TOL[dtype]
+    for batched in (False, True):
+        for fly in (False, True):
+            g = gu.gat_bwd(b, Zdst, Zs, G, a_l, a_r, SLOPE, fw, batched, fly=fly)
+            for q in range(2):
+                assert rel_err(f64(g.dZs[q]), wb.dZs[q]) < tol, (batched, fly, q)
+                assert rel_err(f64(g.dts[q]), wb.dt[q]) < tol, (batched, fly, q)
+            assert rel_err(f64(g.ds), wb.ds) < tol
+            assert rel_err(f64(g.da_l), wb.da_l) < tol
+    b.close()
+
+
 def test_gat_edge_cases():
     """Empty block, single block, destinations without edges, block order, big scores."""
     H, D = 4, 16
