@@ -62,6 +62,9 @@ def parse():
     ap.add_argument("--storage", default="config", choices=["config", "f32", "bf16"],
                     help="storage type of the feature rows; 'config' keeps what the configuration names "
                          "(the headline, config 3, is fp32); accumulation is fp32 either way")
+    ap.add_argument("--stored-error", action="store_true",
+                    help="write the worker's own error E_p = E_{p->p} + ds (x) a_r out (sar_gat_bwd_end) before "
+                         "Z_p.backward reads it, instead of forming its rows inside the two products")
     ap.add_argument("--graph", action="store_true",
                     help="also record the step once into a HIP graph and time its replays (reported beside the "
                          "eager figures as `graph_replay_ms_per_step`; the headline stays the eager step)")
@@ -79,8 +82,12 @@ def parse():
 class Layer:
     """Device state of one worker's GAT layer; methods only call the C ABI."""
 
-    def __init__(self, w, torch, sar, synth, act=0, dst_frac=1.0, errors="compact"):
+    def __init__(self, w, torch, sar, synth, act=0, dst_frac=1.0, errors="compact", stored_error=False):
         self.torch, self.sar, self.w, self.act = torch, sar, w, act
+        # False: Z_p.backward(E_p) forms the rows of E_p = E_{p->p} + ds (x) a_r inside its two products
+        # (sar_linear_bwd_rows); True: sar_gat_bwd_end writes E_p out first (`dZdst`)
+        self.stored_error = stored_error
+        self.rows_scratch = None
         self.subset = dst_frac < 1.0
         self.errors = errors
         self.compact = errors == "compact"
@@ -142,7 +149,7 @@ class Layer:
         err_rows = [int(v.n_t_rows) if self.compact else int(v.n_src) for v in self.views]
         self.dZs = [torch.zeros((r, H, D), dtype=w.dtype, device=dev) for r in err_rows]
         self.dts = [torch.zeros((r, H), **f32) for r in err_rows]
-        self.dZdst = torch.empty((n, H, D), dtype=w.dtype, device=dev)
+        self.dZdst = torch.empty((n, H, D), dtype=w.dtype, device=dev) if stored_error else None
         # the parameter gradients accumulate over blocks and calls: one buffer, zeroed by one fill per step
         self.grads = torch.zeros(2 * H * D + self.W.numel(), **f32)
         self.da_l = self.grads[:H * D].view(H, D)
@@ -194,10 +201,27 @@ class Layer:
                                       self.dZs[q], self.dts[q], self.ds, self.da_l, self.work)
         mark("bwd1")
         # E_p = E_{p->p} + destination-score term: everything this worker itself produced for its rows
-        sar.sar_gat_bwd_end(self.Zp, self.ds, self.a_r, None if self.subset else self.dZs[p], self.dZdst,
-                            self.da_r, self.work, dZadd_rank=self.own_rank)
-        # Z_p.backward(E_p)
-        sar.sar_linear_bwd(self.Xd, self.dZdst, self.W, self.dW, self.dX_dst, self.lwork)
+        own = None if self.subset else self.dZs[p]
+        if self.stored_error:
+            if self.dZdst is None:
+                self.dZdst = self.torch.empty((self.n, self.H, self.D), dtype=w.dtype, device="cuda")
+            sar.sar_gat_bwd_end(self.Zp, self.ds, self.a_r, own, self.dZdst, self.da_r, self.work,
+                                dZadd_rank=self.own_rank)
+            # Z_p.backward(E_p)
+            sar.sar_linear_bwd(self.Xd, self.dZdst, self.W, self.dW, self.dX_dst, self.lwork)
+        else:
+            sar.sar_gat_bwd_end(self.Zp, self.ds, self.a_r, None, None, self.da_r, self.work)     # da_r only
+            # Z_p.backward(E_p), the rows of E_p formed where the products read them
+            rows_args = (self.Xd, None if own is None else own.reshape(-1, self.F), self.own_rank, self.ds, self.a_r,
+                         self.H, self.D, self.W, self.dW, self.dX_dst, self.n, w.dtype, self.lwork)
+            try:
+                sar.sar_linear_bwd_rows(*rows_args, rows=self.rows_scratch)
+            except sar.SarError as e:
+                if e.code != sar.SAR_ERR_UNSUPPORTED or self.rows_scratch is not None:
+                    raise
+                # a shape whose rows the products cannot form themselves: give them scratch to be written to
+                self.rows_scratch = self.torch.empty((self.n, self.F), dtype=w.dtype, device="cuda")
+                sar.sar_linear_bwd_rows(*rows_args, rows=self.rows_scratch)
         if self.subset:                      # destination and source roles of the own rows kept apart
             own = self.dZs[p]
             if self.compact:                 # the received rows placed among the worker's own (Alg. 2)
@@ -313,9 +337,10 @@ def measure_transform(layer, reps=20):
             lambda: sar.sar_linear_fwd(layer.Xd, layer.W, layer.Zp.reshape(n, F), layer.a_r, layer.s,
                                        layer.a_l, layer.tp),
             n * (K + F) * fb + 2 * n * layer.H * 4),
-        "dX = dZ W^T": (lambda: sar.sar_linear_bwd(None, layer.dZdst, layer.W, None, layer.dX_dst, None),
+        # (any stored [n,F] operand times the products alone: the upstream error's rows serve)
+        "dX = dZ W^T": (lambda: sar.sar_linear_bwd(None, layer.G.reshape(n, F), layer.W, None, layer.dX_dst, None),
                         n * (K + F) * fb),
-        "dW += X^T dZ": (lambda: sar.sar_linear_bwd(layer.Xd, layer.dZdst, None, dW, None, layer.lwork),
+        "dW += X^T dZ": (lambda: sar.sar_linear_bwd(layer.Xd, layer.G.reshape(n, F), None, dW, None, layer.lwork),
                          n * (K + F) * fb),
     }
     out = {}
@@ -390,7 +415,7 @@ def time_gat(args, torch, sar, synth, name, steps, warmup, full_report):
     if args.storage != "config":
         w.dtype = torch.float32 if args.storage == "f32" else torch.bfloat16
     layer = Layer(w, torch, sar, synth, act=sar.SAR_ACT_RELU if args.act == "relu" else sar.SAR_ACT_NONE,
-                  dst_frac=args.dst_frac, errors=args.errors)
+                  dst_frac=args.dst_frac, errors=args.errors, stored_error=args.stored_error)
     if full_report and args.calib_copy_mib:
         a = torch.ones(args.calib_copy_mib << 18, dtype=torch.float32, device="cuda")
         b = torch.empty_like(a)
@@ -540,7 +565,10 @@ def time_sage(args, torch, sar, synth, steps, warmup):
                 sar.sar_spmm_bwd_block(blocks, q, G, True, dZs[q])
         mark("bwd1")
         sar.sar_linear_bwd(X, G, W_res, dW_res, dX_res, lwork)
-        if compact:                          # the owner adds the received rows to its own (Alg. 2)
+        if compact and not args.stored_error:
+            # the local block's compact error read through its row map inside the two products
+            sar.sar_linear_bwd_rows(X, dZs[p], views[p].t_rank, None, None, 1, F, W, dW, dX_msg, n, w.dtype, lwork)
+        elif compact:                        # the owner places the received rows among its own (Alg. 2)
             sar.sar_error_add(dZs[p], views[p].t_rank, False, dZp_full)
             sar.sar_linear_bwd(X, dZp_full, W, dW, dX_msg, lwork)
         else:

@@ -342,7 +342,9 @@ int sar_gat_bwd_all(const sar_blocks_t* b, const void* const* Zq, const void* G,
  * dZadd_rank: NULL when dZadd has one row per destination.  For a COMPACT dZadd (the local
  * block's dZq of a SAR_BUILD_COMPACT handle) pass that block's t_rank (device int32
  * [n_dst+1]): row i then receives dZadd[dZadd_rank[i]] if dZadd_rank[i+1] > dZadd_rank[i]
- * and nothing otherwise; such a dZadd must not alias dZdst. */
+ * and nothing otherwise; such a dZadd must not alias dZdst.
+ * dZdst may be NULL when the error is not wanted as a tensor (sar_linear_bwd_rows forms it
+ * inside Z_p.backward): then only da_r is produced and dZadd is not read. */
 int sar_gat_bwd_end(const void* Zdst, const float* ds, const float* a_r, const void* dZadd,
                     const int32_t* dZadd_rank, void* dZdst, float* da_r, int dtype, int64_t n_dst, int H,
                     int D, void* work, size_t work_bytes, void* stream);
@@ -380,6 +382,30 @@ int sar_linear_fwd(const void* X, const float* W, void* Z, int dtype, int64_t n,
  * sar_linear_workspace_bytes. */
 int sar_linear_bwd(const void* X, const void* dZ, const float* W, float* dW, void* dX, int dtype,
                    int64_t n, int K, int F, void* work, size_t work_bytes, void* stream);
+
+/* Z_p.backward(E_p) of Alg. 2 (the step "Z.backward(E)" after the errors have been summed)
+ * without E_p ever being stored:  dW += X^T E_p,  dX = E_p W^T  with
+ *     E_p[i,h,:] = E[r(i),h,:] + ds[i,h] a_r[h,:]        (F = H*D values per row),
+ * the rows of E_p formed in fp32 where the two products load them and rounded to `dtype`
+ * as a stored E_p would have been: the results equal, bit for bit, those of
+ * sar_gat_bwd_end (or sar_error_add) into a tensor followed by sar_linear_bwd on it.
+ *   E       [n_E,F] of `dtype`: the stored part; NULL with n_E = 0 when there is none (a
+ *           compact error of a block without edges, or a layer with the score term only).
+ *   E_rank  NULL: E has one row per node (n_E = n).  Otherwise device int32 [n+1], the
+ *           t_rank of a SAR_BUILD_COMPACT handle: node i's row is E[E_rank[i]] if
+ *           E_rank[i+1] > E_rank[i], and zero otherwise (E_{p->p} of the local block).
+ *   ds, a_r [n,H] and [H,D] fp32, both or neither: the destination-score term of the
+ *           attention layer (what sar_gat_bwd_end would add); NULL for a layer without it.
+ *   rows    NULL, or [n,F] values of `dtype` as scratch (not aliasing E or dX).  The rows are
+ *           formed inside the products when K and F are whole 16-byte pieces, D is too,
+ *           F <= 256, H <= 16 (bf16: H <= 8) and the pointers are 16-byte aligned; for any
+ *           other shape they are written to `rows` first (same values), and without
+ *           `rows` such a shape returns SAR_ERR_UNSUPPORTED.  With `rows` given they are
+ *           always written there, so a caller who wants E_p as well passes it.
+ * X [n,K], W [K,F], dW, dX, work as in sar_linear_bwd (F = H*D). */
+int sar_linear_bwd_rows(const void* X, const void* E, const int32_t* E_rank, int64_t n_E, const float* ds,
+                        const float* a_r, int H, int D, const float* W, float* dW, void* dX, int dtype,
+                        int64_t n, int K, void* rows, void* work, size_t work_bytes, void* stream);
 
 int sar_linear_workspace_bytes(int64_t n, int K, int F, size_t* bytes);
 

@@ -688,7 +688,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_bwd_end(const T* __restrict_
         float z[VEC], o[VEC];
         Vec<T>::unpack(Vec<T>::load(Zdst + v * ldz + lm.gl * VEC), z);
         int64_t va = v;
-        bool add = dZadd != nullptr;
+        bool add = dZadd != nullptr && dZdst != nullptr;
         if (add && add_rank) {
             va = add_rank[v];
             add = add_rank[v + 1] > (int32_t)va;
@@ -704,7 +704,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_bwd_end(const T* __restrict_
             o[x] = fmaf(d, ar[x], o[x]);
             dar[x] = fmaf(d, z[x], dar[x]);
         }
-        Vec<T>::store(dZdst + v * ldz + lm.gl * VEC, o);
+        if (dZdst) Vec<T>::store(dZdst + v * ldz + lm.gl * VEC, o);     // null: only da_r is wanted
     }
 #pragma unroll
     for (int x = 0; x < VEC; ++x) part[wave][lm.lane][x] = dar[x];
@@ -1485,7 +1485,8 @@ int bwd_end_impl(const void* Zdst, const float* ds, const float* a_r, const void
                          SAR_DISPATCH_G(T, hg.Fg, (k_bwd_end<T, kG><<<grid, kGatherThreads, 0, st>>>(
                                                       static_cast<const T*>(Zdst) + f0, ds + h0, a_r + f0,
                                                       dZadd ? static_cast<const T*>(dZadd) + f0 : nullptr, dZadd_rank,
-                                                      static_cast<T*>(dZdst) + f0, partial, n_dst, hg.Hg, D, hg.Fg, F, H))));
+                                                      dZdst ? static_cast<T*>(dZdst) + f0 : nullptr, partial, n_dst,
+                                                      hg.Hg, D, hg.Fg, F, H))));
         SAR_LAUNCH_CHECK();
         k_reduce_partials<<<hg.Fg, 256, 0, st>>>(partial, (int)grid, hg.Fg, da_r + f0);
         SAR_LAUNCH_CHECK();
@@ -1500,7 +1501,7 @@ int bwd_end_checks(const void* Zdst, const float* ds, const float* a_r, const vo
     SAR_TRY(check_shape(dtype, H, D));
     SAR_CHECK_ARG(n_dst >= 0, "n_dst is negative");
     if (n_dst == 0) return SAR_OK;
-    SAR_CHECK_ARG(Zdst && ds && a_r && dZdst && da_r, "a tensor argument is null");
+    SAR_CHECK_ARG(Zdst && ds && a_r && da_r, "a tensor argument is null");
     SAR_CHECK_ARG(aligned16(Zdst) && aligned16(dZdst) && aligned16(dZadd),
                   "Zdst, dZadd and dZdst must be 16-byte aligned");
     return SAR_OK;

@@ -125,8 +125,8 @@ struct Row4<bf16_t> {
     static __device__ inline void store(bf16_t* row, int lane, const float (&v)[4])
     {
         uint2 r;
-        r.x = f32_to_bf16_rne(v[0]) | (f32_to_bf16_rne(v[1]) << 16);
-        r.y = f32_to_bf16_rne(v[2]) | (f32_to_bf16_rne(v[3]) << 16);
+        r.x = pack2_bf16(v[0], v[1]);
+        r.y = pack2_bf16(v[2], v[3]);
         reinterpret_cast<uint2*>(row)[lane] = r;
     }
 };

@@ -45,13 +45,17 @@ struct Vec<float> {
     }
 };
 
-__device__ inline uint32_t f32_to_bf16_rne(float f)
+// fp32 -> bf16, round to nearest even, by the hardware's own conversion (V_CVT_PK_BF16_F32 takes
+// two values per instruction): every bf16 value the library stores goes through these two, so
+// a row rounded in one kernel equals the same row rounded in another.
+typedef __bf16 hw_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float hw_f32x2 __attribute__((ext_vector_type(2)));
+__device__ inline uint32_t pack2_bf16(float lo, float hi)     // lo in bits 0..15
 {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;   // keep NaN a NaN
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return u >> 16;
+    const hw_f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, hw_bf16x2));
 }
+__device__ inline uint32_t f32_to_bf16_rne(float f) { return pack2_bf16(f, 0.f) & 0xffffu; }
 
 template <>
 struct Vec<bf16_t> {
@@ -73,10 +77,10 @@ struct Vec<bf16_t> {
     static __device__ inline void store(bf16_t* p, const float (&v)[8])
     {
         uint4 r;
-        r.x = f32_to_bf16_rne(v[0]) | (f32_to_bf16_rne(v[1]) << 16);
-        r.y = f32_to_bf16_rne(v[2]) | (f32_to_bf16_rne(v[3]) << 16);
-        r.z = f32_to_bf16_rne(v[4]) | (f32_to_bf16_rne(v[5]) << 16);
-        r.w = f32_to_bf16_rne(v[6]) | (f32_to_bf16_rne(v[7]) << 16);
+        r.x = pack2_bf16(v[0], v[1]);
+        r.y = pack2_bf16(v[2], v[3]);
+        r.z = pack2_bf16(v[4], v[5]);
+        r.w = pack2_bf16(v[6], v[7]);
         *reinterpret_cast<uint4*>(p) = r;
     }
 };
@@ -181,10 +185,10 @@ struct Vec<Piece<bf16_t, NN>> {
         if constexpr (N == 1) {
             *reinterpret_cast<uint16_t*>(p) = (uint16_t)f32_to_bf16_rne(v[0]);
         } else if constexpr (N == 2) {
-            *reinterpret_cast<uint32_t*>(p) = f32_to_bf16_rne(v[0]) | (f32_to_bf16_rne(v[1]) << 16);
+            *reinterpret_cast<uint32_t*>(p) = pack2_bf16(v[0], v[1]);
         } else {
-            *reinterpret_cast<uint2*>(p) = make_uint2(f32_to_bf16_rne(v[0]) | (f32_to_bf16_rne(v[1]) << 16),
-                                                      f32_to_bf16_rne(v[2]) | (f32_to_bf16_rne(v[3]) << 16));
+            *reinterpret_cast<uint2*>(p) = make_uint2(pack2_bf16(v[0], v[1]),
+                                                      pack2_bf16(v[2], v[3]));
         }
     }
 };

@@ -318,6 +318,47 @@ __global__ __launch_bounds__(kGemmThreads) void k_gemm_bf16(GemmArgs g)
         }
 }
 
+// ---- error rows that are never stored ---------------------------------------
+//
+// Z_p.backward(E_p) of Alg. 2 reads the worker's error E_p twice (dW = X^T E_p, dX = E_p W^T).
+// For the attention layer E_p = E_{p->p} + ds (x) a_r: the local block's error, stored compactly
+// (one row per touched source), plus a rank-one term per head.  Instead of writing that sum out
+// and reading it back twice, the two products can form each 16-byte piece of it where they load
+// the operand: piece(i, f..) = E[row of i][f..] (zero where E has no row for i) + ds[i, f/D] a_r[f..],
+// in fp32 and rounded to the storage type exactly as a stored E_p would have been.
+struct RowsOp {
+    const int32_t* rank;   // [n+1]: node i's row of E is rank[i], present iff rank[i+1] > rank[i]; null: row i
+    const float* ds;       // [n, H] or null (no rank-one term)
+    const float* a_r;      // [H*D]
+    int H, D;
+    int has_E;             // 0: E has no rows at all (or is null)
+};
+
+template <typename T>
+__device__ inline uint4 fuse_piece(const uint4& base, float d, const float* ar);
+template <>
+__device__ inline uint4 fuse_piece<float>(const uint4& base, float d, const float* ar)
+{
+    return make_uint4(__float_as_uint(fmaf(d, ar[0], __uint_as_float(base.x))),
+                      __float_as_uint(fmaf(d, ar[1], __uint_as_float(base.y))),
+                      __float_as_uint(fmaf(d, ar[2], __uint_as_float(base.z))),
+                      __float_as_uint(fmaf(d, ar[3], __uint_as_float(base.w))));
+}
+template <>
+__device__ inline uint4 fuse_piece<bf16_t>(const uint4& base, float d, const float* ar)
+{
+    float v[8];
+    Vec<bf16_t>::unpack(base, v);
+#pragma unroll
+    for (int x = 0; x < 8; ++x) v[x] = fmaf(d, ar[x], v[x]);
+    uint4 r;
+    r.x = pack2_bf16(v[0], v[1]);
+    r.y = pack2_bf16(v[2], v[3]);
+    r.z = pack2_bf16(v[4], v[5]);
+    r.w = pack2_bf16(v[6], v[7]);
+    return r;
+}
+
 // ---- skinny products: the small operand resident in LDS --------------------
 //
 // In Z = X W and dX = dZ W^T the left operand has millions of rows whose
@@ -362,12 +403,20 @@ struct SkinnyArgs {
     // byte offset in LDS of the per-wavefront 32 x 32 staging tiles through which the outputs
     // are stored as whole 64- or 128-byte row segments, or 0 to store element-wise
     int stage_off;
+    RowsOp op;         // FUSE only: how the rows of A are formed
 };
 
 
-template <typename TA, typename TC, int NT, bool SC>
+// FUSE: the rows of A are not stored; each piece is formed where it is multiplied (RowsOp, K <= 256).
+// Between the epilogues a wavefront's staging tile is idle, so it holds what the pieces need: the
+// tile's 32 x H values of ds and the K values of a_r.  The row map and ds of a tile are read one
+// tile ahead (the map two), like the first pieces of its rows.
+constexpr int kDsRegs = 8;   // 32 rows x H <= 16 heads of ds, 64 lanes
+
+template <typename TA, typename TC, int NT, bool SC, bool FUSE = false>
 __global__ __launch_bounds__(kSkinnyThreads) void k_gemm_skinny(SkinnyArgs g)
 {
+    static_assert(!(SC && FUSE), "the fused operand is that of dX = E W^T, which has no score columns");
     constexpr int NA = NT + (SC ? 1 : 0);   // accumulator tiles: NT of the product, one of scores
     extern __shared__ __attribute__((aligned(16))) unsigned char skinny_lds[];
     constexpr bool BF = sizeof(TA) == 2;
@@ -479,6 +528,47 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_gemm_skinny(SkinnyArgs g)
     };
     auto row_ptr = [&](int64_t tl) { return A + std::min<int64_t>(tl * 32 + c, g.M - 1) * g.lda; };
 
+    // FUSE: where this lane's row of the stored part is (row 0, and `has` false, where there is none:
+    // the loads stay unconditional), the tile's ds values on their way to LDS, the lane's four a_r
+    float* dsl = nullptr;
+    float* arl = nullptr;
+    float arreg[4] = {0.f, 0.f, 0.f, 0.f}, dsreg[kDsRegs];
+    int nrk0 = 0, nrk1 = 0;
+    bool has = false;
+    auto rank_of = [&](int64_t tl, int& r0, int& r1) {
+        if (g.op.rank && tl < n_tiles) {
+            const int64_t i = std::min<int64_t>(tl * 32 + c, g.M - 1);
+            r0 = g.op.rank[i];
+            r1 = g.op.rank[i + 1];
+        }
+    };
+    auto row_ptr_fused = [&](int64_t tl, int r0, int r1, bool& present) -> const TA* {
+        if (!g.op.has_E) {
+            present = false;
+            return A;                      // a readable stand-in row
+        }
+        if (g.op.rank) {
+            present = r1 > r0;
+            return A + (int64_t)(present ? r0 : 0) * g.lda;
+        }
+        present = true;
+        return row_ptr(tl);
+    };
+    auto load_ds = [&](int64_t tl) {
+        const int64_t first = tl * 32 * g.op.H, end = g.M * g.op.H;
+#pragma unroll
+        for (int r = 0; r < kDsRegs; ++r) {
+            const int idx = lane + 64 * r;
+            dsreg[r] = (g.op.ds && idx < 32 * g.op.H && first + idx < end) ? g.op.ds[first + idx] : 0.f;
+        }
+    };
+    if constexpr (FUSE) {
+        dsl = reinterpret_cast<float*>(skinny_lds + g.stage_off + wave * (32 * 32 * (int)sizeof(TC)));
+        arl = dsl + 32 * g.op.H;
+#pragma unroll
+        for (int x = 0; x < 4; ++x) arreg[x] = (g.op.ds && lane * 4 + x < g.K) ? g.op.a_r[lane * 4 + x] : 0.f;
+    }
+
     // Two sets of pieces: while the chunks of one set are multiplied, the other set travels.
     // The loads of a set are issued together, ahead of the other set's MFMAs, and are first
     // needed a whole set later.  (The compiler waits for every load in flight, not for the oldest,
@@ -486,7 +576,15 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_gemm_skinny(SkinnyArgs g)
     // chunks per set: about 2000 MFMA cycles of one wavefront either way (two where registers run out)
     constexpr int PS = (BF && !(SC && NT == 8)) ? 4 : 2;
     uint4 a[PS], b[PS];
-    const TA* rowp = row_ptr(tile);
+    const TA* rowp;
+    if constexpr (FUSE) {
+        rank_of(tile, nrk0, nrk1);
+        rowp = row_ptr_fused(tile, nrk0, nrk1, has);
+        load_ds(tile);
+        rank_of(tile + stride, nrk0, nrk1);
+    } else {
+        rowp = row_ptr(tile);
+    }
 #pragma unroll
     for (int u = 0; u < PS; ++u) a[u] = load_piece(rowp, u);
     const int full = g.chunks / (2 * PS) * (2 * PS);
@@ -497,11 +595,32 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_gemm_skinny(SkinnyArgs g)
         for (int nt = 0; nt < NA; ++nt)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[nt][r] = 0.f;
+        if constexpr (FUSE) {
+            // the previous tile's outputs have left the staging tile
+#pragma unroll
+            for (int r = 0; r < kDsRegs; ++r)
+                if (lane + 64 * r < 32 * g.op.H) dsl[lane + 64 * r] = dsreg[r];
+            *reinterpret_cast<float4*>(arl + lane * 4) = make_float4(arreg[0], arreg[1], arreg[2], arreg[3]);
+            __builtin_amdgcn_wave_barrier();
+        }
 
         auto multiply = [&](const uint4& piece, int t) {
-            const bool beyond = t * kChunk + gq * (kChunk / 2) >= g.K;
-            const uint4 av = make_uint4(beyond ? 0u : piece.x, beyond ? 0u : piece.y, beyond ? 0u : piece.z,
-                                        beyond ? 0u : piece.w);
+            const int k_first = t * kChunk + gq * (kChunk / 2);
+            const bool beyond = k_first >= g.K;
+            uint4 av = make_uint4(beyond ? 0u : piece.x, beyond ? 0u : piece.y, beyond ? 0u : piece.z,
+                                  beyond ? 0u : piece.w);
+            if constexpr (FUSE) {
+                if (!has) av = make_uint4(0u, 0u, 0u, 0u);
+                // a_r is zero beyond K, so a piece beyond the row stays zero
+                const float d = dsl[c * g.op.H + min(k_first / g.op.D, g.op.H - 1)];
+                float ar[kChunk / 2];
+#pragma unroll
+                for (int x = 0; x < kChunk / 2; x += 4) {
+                    const float4 v = *reinterpret_cast<const float4*>(arl + k_first + x);
+                    ar[x] = v.x; ar[x + 1] = v.y; ar[x + 2] = v.z; ar[x + 3] = v.w;
+                }
+                av = fuse_piece<TA>(av, d, ar);
+            }
             const uint4* fr = frag + (size_t)t * (NA * kFragsPerTile * 64) + lane;
             if (!BF) {
                 uint4 w[NA];
@@ -566,7 +685,13 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_gemm_skinny(SkinnyArgs g)
         // the next tile's first pieces travel while this one is stored
         const int64_t row0 = tile * 32;
         if (tile + stride < n_tiles) {
-            rowp = row_ptr(tile + stride);
+            if constexpr (FUSE) {
+                rowp = row_ptr_fused(tile + stride, nrk0, nrk1, has);
+                load_ds(tile + stride);
+                rank_of(tile + 2 * stride, nrk0, nrk1);
+            } else {
+                rowp = row_ptr(tile + stride);
+            }
 #pragma unroll
             for (int u = 0; u < PS; ++u) a[u] = load_piece(rowp, u);
         }
@@ -675,14 +800,14 @@ bool plan_skinny(const void* A, int64_t lda, const void* C, int64_t ldc, int K, 
     return p->slabs <= 4;
 }
 
-template <typename TA, typename TC, int NT, bool SC>
+template <typename TA, typename TC, int NT, bool SC, bool FUSE = false>
 int launch_skinny_nt(const SkinnyArgs& g, const SkinnyPlan& p, hipStream_t st)
 {
     int dev = 0;
     SAR_HIP(hipGetDevice(&dev));
     int n_cu = 0;
     SAR_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
-    SAR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_skinny<TA, TC, NT, SC>),
+    SAR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_skinny<TA, TC, NT, SC, FUSE>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.lds));
     const int64_t tiles = (g.M + 31) / 32;
     const int64_t want = (tiles + kSkinnyWaves - 1) / kSkinnyWaves;
@@ -690,20 +815,29 @@ int launch_skinny_nt(const SkinnyArgs& g, const SkinnyPlan& p, hipStream_t st)
     const int per_cu = (NT <= 4 && 2 * p.lds <= 150 * 1024) ? 2 : 1;
     const int64_t resident = std::max<int64_t>(1, (int64_t)n_cu * per_cu / p.slabs);
     dim3 grid((unsigned)std::max<int64_t>(1, std::min(want, resident)), p.slabs, 1);
-    k_gemm_skinny<TA, TC, NT, SC><<<grid, kSkinnyThreads, p.lds, st>>>(g);
+    k_gemm_skinny<TA, TC, NT, SC, FUSE><<<grid, kSkinnyThreads, p.lds, st>>>(g);
     SAR_LAUNCH_CHECK();
     return SAR_OK;
 }
 
-template <typename TA, typename TC, bool SC>
+template <typename TA, typename TC, bool SC, bool FUSE = false>
 int launch_skinny(const SkinnyArgs& g, const SkinnyPlan& p, hipStream_t st)
 {
     switch (p.nt) {
-        case 1: return launch_skinny_nt<TA, TC, 1, SC>(g, p, st);
-        case 2: return launch_skinny_nt<TA, TC, 2, SC>(g, p, st);
-        case 4: return launch_skinny_nt<TA, TC, 4, SC>(g, p, st);
-        default: return launch_skinny_nt<TA, TC, 8, SC>(g, p, st);
+        case 1: return launch_skinny_nt<TA, TC, 1, SC, FUSE>(g, p, st);
+        case 2: return launch_skinny_nt<TA, TC, 2, SC, FUSE>(g, p, st);
+        case 4: return launch_skinny_nt<TA, TC, 4, SC, FUSE>(g, p, st);
+        default: return launch_skinny_nt<TA, TC, 8, SC, FUSE>(g, p, st);
     }
+}
+
+// Whether a plan can also form the rows of A on the fly (k_gemm_skinny's FUSE): the outputs must
+// go through staging tiles, and a tile must hold 32 x H values of ds and 256 of a_r.
+bool plan_takes_rows_op(const SkinnyPlan& p, int K, int H, int dtype)
+{
+    const size_t tile = 32 * 32 * (dtype == SAR_F32 ? 4 : 2);
+    // (with eight accumulator tiles the registers are spoken for)
+    return p.nt <= 4 && p.stage_off != 0 && K <= 256 && H <= 2 * kDsRegs && (size_t)(32 * H + 256) * 4 <= tile;
 }
 
 // ---- dW = X^T dZ: contraction over the rows ---------------------------------
@@ -738,8 +872,8 @@ struct DwShape<bf16_t> {
     static constexpr int kVec = 8;
 };
 
-template <typename T>
-__global__ __launch_bounds__(256) void k_dw(const T* __restrict__ X, const T* __restrict__ dZ,
+template <typename T, bool FUSE>
+__global__ __launch_bounds__(256) void k_dw(const T* __restrict__ X, const T* __restrict__ dZ, RowsOp op,
                                             float* __restrict__ partial, int64_t M, int K, int N,
                                             int64_t rows_per_slab)
 {
@@ -756,6 +890,34 @@ __global__ __launch_bounds__(256) void k_dw(const T* __restrict__ X, const T* __
     const int64_t m_end = std::min<int64_t>(M, m_beg + rows_per_slab);
 
     uint4 gx[kXUnits], gd[kDUnits];
+    // FUSE: the rows of dZ are formed here (see RowsOp).  A thread's units keep their column, so its
+    // pieces of a_r and its heads are fixed; the row map of a chunk is read one chunk ahead of the
+    // rows themselves, which keeps a single level of loads in flight.
+    __shared__ __attribute__((aligned(16))) float ars[FUSE ? kDwN : 4];   // this tile's columns of a_r
+    float dsv[FUSE ? kDUnits : 1];
+    int hq[FUSE ? kDUnits : 1], rk0[FUSE ? kDUnits : 1], rk1[FUSE ? kDUnits : 1];
+    auto fetch_rank = [&](int64_t m0) {
+        if constexpr (FUSE) {
+#pragma unroll
+            for (int q = 0; q < kDUnits; ++q) {
+                const int u = tid + 256 * q, row = u / (kDwN / S::kVec);
+                const bool ok = op.rank != nullptr && m0 + row < m_end;
+                rk0[q] = ok ? op.rank[m0 + row] : 0;
+                rk1[q] = ok ? op.rank[m0 + row + 1] : 0;
+            }
+        }
+    };
+    if constexpr (FUSE) {
+        for (int f = tid; f < kDwN; f += 256) ars[f] = (op.ds && n0 + f < N) ? op.a_r[n0 + f] : 0.f;
+#pragma unroll
+        for (int q = 0; q < kDUnits; ++q) {
+            const int u = tid + 256 * q, col = (u % (kDwN / S::kVec)) * S::kVec;
+            hq[q] = n0 + col < N ? (n0 + col) / op.D : 0;
+            dsv[q] = 0.f;
+        }
+        fetch_rank(m_beg);
+        __syncthreads();
+    }
     auto fetch = [&](int64_t m0) {
 #pragma unroll
         for (int q = 0; q < kXUnits; ++q) {
@@ -767,8 +929,20 @@ __global__ __launch_bounds__(256) void k_dw(const T* __restrict__ X, const T* __
         for (int q = 0; q < kDUnits; ++q) {
             const int u = tid + 256 * q, row = u / (kDwN / S::kVec), col = (u % (kDwN / S::kVec)) * S::kVec;
             const bool ok = m0 + row < m_end && n0 + col < N;
-            gd[q] = ok ? *reinterpret_cast<const uint4*>(dZ + (m0 + row) * N + n0 + col) : make_uint4(0u, 0u, 0u, 0u);
+            if constexpr (FUSE) {
+                int64_t from = m0 + row;
+                bool has = ok && op.has_E;
+                if (op.rank) {
+                    from = rk0[q];
+                    has = has && rk1[q] > rk0[q];
+                }
+                gd[q] = has ? *reinterpret_cast<const uint4*>(dZ + from * N + n0 + col) : make_uint4(0u, 0u, 0u, 0u);
+                dsv[q] = (ok && op.ds) ? op.ds[(m0 + row) * op.H + hq[q]] : 0.f;
+            } else {
+                gd[q] = ok ? *reinterpret_cast<const uint4*>(dZ + (m0 + row) * N + n0 + col) : make_uint4(0u, 0u, 0u, 0u);
+            }
         }
+        fetch_rank(m0 + S::kRows);
     };
     auto commit = [&](int buf) {
 #pragma unroll
@@ -779,7 +953,10 @@ __global__ __launch_bounds__(256) void k_dw(const T* __restrict__ X, const T* __
 #pragma unroll
         for (int q = 0; q < kDUnits; ++q) {
             const int u = tid + 256 * q, row = u / (kDwN / S::kVec), col = (u % (kDwN / S::kVec)) * S::kVec;
-            *reinterpret_cast<uint4*>(&Ds[buf][row][col]) = gd[q];
+            if constexpr (FUSE)
+                *reinterpret_cast<uint4*>(&Ds[buf][row][col]) = fuse_piece<T>(gd[q], dsv[q], ars + col);
+            else
+                *reinterpret_cast<uint4*>(&Ds[buf][row][col]) = gd[q];
         }
     };
 
@@ -986,17 +1163,58 @@ extern "C" int sar_linear_fwd(const void* X, const float* W, void* Z, int dtype,
     return SAR_OK;
 }
 
-extern "C" int sar_linear_bwd(const void* X, const void* dZ, const float* W, float* dW, void* dX, int dtype,
-                              int64_t n, int K, int F, void* work, size_t work_bytes, void* stream)
+namespace {
+
+// Whether both products can form the rows `op` describes while they load them (k_dw and
+// k_gemm_skinny with FUSE): their aligned fast paths, a piece inside one head, the stand-in row
+// readable.  dZ here is the stored part E (or the stand-in when there is none).
+bool rows_op_fusable(const void* X, const void* dZ, const RowsOp& op, void* dX, int dtype, int K, int F)
 {
-    if (dtype != SAR_F32 && dtype != SAR_BF16)
-        return sar::fail(SAR_ERR_UNSUPPORTED, "dtype %d is neither SAR_F32 nor SAR_BF16", dtype);
-    SAR_CHECK_ARG(n >= 0 && K > 0 && F > 0, "need n >= 0, K > 0, F > 0");
-    if (n == 0) return SAR_OK;
-    SAR_CHECK_ARG(dZ != nullptr, "dZ is null");
-    SAR_CHECK_ARG(dW == nullptr || X != nullptr, "dW needs X");
-    SAR_CHECK_ARG(dX == nullptr || W != nullptr, "dX needs W");
-    hipStream_t st = sar::as_stream(stream);
+    const int elem = dtype == SAR_F32 ? 4 : 2, vec = 16 / elem;
+    if (K % vec != 0 || F % vec != 0 || op.D % vec != 0 || op.H * op.D != F) return false;
+    if (reinterpret_cast<uintptr_t>(X) % 16 != 0 || reinterpret_cast<uintptr_t>(dZ) % 16 != 0) return false;
+    if (op.ds && reinterpret_cast<uintptr_t>(op.a_r) % 16 != 0) return false;
+    SkinnyPlan plan;
+    if (dX && !(plan_skinny(dZ, F, dX, K, F, K, dtype, 0, &plan) && plan_takes_rows_op(plan, F, op.H, dtype)))
+        return false;
+    return true;
+}
+
+// The error rows of RowsOp written out (the shapes the two products cannot form on the fly):
+// the same fp32 multiply-add and the same rounding as sar_gat_bwd_end's.
+template <typename T>
+__global__ __launch_bounds__(256) void k_rows_store(const T* __restrict__ E, RowsOp op, T* __restrict__ out,
+                                                    int64_t n, int F)
+{
+    const int64_t total = n * F;
+    for (int64_t at = (int64_t)blockIdx.x * 256 + threadIdx.x; at < total; at += (int64_t)gridDim.x * 256) {
+        const int64_t i = at / F;
+        const int f = (int)(at % F);
+        float o = 0.f;
+        if (op.has_E) {
+            int64_t from = i;
+            bool present = true;
+            if (op.rank) {
+                from = op.rank[i];
+                present = op.rank[i + 1] > (int32_t)from;
+            }
+            if (present) {
+                if constexpr (sizeof(T) == 2)
+                    o = bf16_to_f32(E[from * F + f]);
+                else
+                    o = E[from * F + f];
+            }
+        }
+        if (op.ds) o = fmaf(op.ds[i * op.H + f / op.D], op.a_r[f], o);
+        out[at] = from_f32<T>(o);
+    }
+}
+
+// op == nullptr: dZ is the stored [n,F] operand.  Otherwise dZ is the stored part of the rows
+// `op` describes and both products form the rows as they load them.
+int linear_bwd_impl(const void* X, const void* dZ, const RowsOp* op, const float* W, float* dW, void* dX, int dtype,
+                    int64_t n, int K, int F, void* work, size_t work_bytes, hipStream_t st)
+{
     if (dW) {
         const int slabs = slabs_for(n, K, F);
         const size_t need = (size_t)slabs * K * F * sizeof(float);
@@ -1009,14 +1227,23 @@ extern "C" int sar_linear_bwd(const void* X, const void* dZ, const float* W, flo
             const int chunk = dtype == SAR_F32 ? DwShape<float>::kRows : DwShape<bf16_t>::kRows;
             const int64_t rows_per_slab = ((n + slabs - 1) / slabs + chunk - 1) / chunk * chunk;
             dim3 grid((unsigned)slabs, (unsigned)((F + kDwN - 1) / kDwN), (unsigned)((K + kDwKf - 1) / kDwKf));
-            if (dtype == SAR_F32)
-                k_dw<float><<<grid, 256, 0, st>>>(static_cast<const float*>(X), static_cast<const float*>(dZ),
-                                                  static_cast<float*>(work), n, K, F, rows_per_slab);
+            if (op && dtype == SAR_F32)
+                k_dw<float, true><<<grid, 256, 0, st>>>(static_cast<const float*>(X), static_cast<const float*>(dZ),
+                                                        *op, static_cast<float*>(work), n, K, F, rows_per_slab);
+            else if (op)
+                k_dw<bf16_t, true><<<grid, 256, 0, st>>>(static_cast<const bf16_t*>(X),
+                                                         static_cast<const bf16_t*>(dZ), *op,
+                                                         static_cast<float*>(work), n, K, F, rows_per_slab);
+            else if (dtype == SAR_F32)
+                k_dw<float, false><<<grid, 256, 0, st>>>(static_cast<const float*>(X), static_cast<const float*>(dZ),
+                                                         RowsOp{}, static_cast<float*>(work), n, K, F, rows_per_slab);
             else
-                k_dw<bf16_t><<<grid, 256, 0, st>>>(static_cast<const bf16_t*>(X), static_cast<const bf16_t*>(dZ),
-                                                   static_cast<float*>(work), n, K, F, rows_per_slab);
+                k_dw<bf16_t, false><<<grid, 256, 0, st>>>(static_cast<const bf16_t*>(X),
+                                                          static_cast<const bf16_t*>(dZ), RowsOp{},
+                                                          static_cast<float*>(work), n, K, F, rows_per_slab);
             SAR_LAUNCH_CHECK();
         } else {
+            if (op) return sar::fail(SAR_ERR_STATE, "rows formed on the fly need the aligned dW kernel");
             GemmArgs g{};
             g.A = X;
             g.B = dZ;
@@ -1064,11 +1291,19 @@ extern "C" int sar_linear_bwd(const void* X, const void* dZ, const float* W, flo
             // B(k = f, n = kcol) = W[kcol * F + f]
             SkinnyArgs sk{dZ, F, n, W, 1, F, dX, K, F, K, plan.chunks, nullptr, nullptr, nullptr, nullptr, 0, 0,
                           plan.stage_off};
-            if (dtype == SAR_F32)
+            if (op) {
+                sk.op = *op;
+                if (dtype == SAR_F32)
+                    SAR_TRY((launch_skinny<float, float, false, true>(sk, plan, st)));
+                else
+                    SAR_TRY((launch_skinny<bf16_t, bf16_t, false, true>(sk, plan, st)));
+            } else if (dtype == SAR_F32) {
                 SAR_TRY((launch_skinny<float, float, false>(sk, plan, st)));
-            else
+            } else {
                 SAR_TRY((launch_skinny<bf16_t, bf16_t, false>(sk, plan, st)));
+            }
         } else {
+            if (op) return sar::fail(SAR_ERR_STATE, "rows formed on the fly need the skinny dX kernel");
             dim3 grid((unsigned)((n + BM - 1) / BM), (unsigned)((K + BN - 1) / BN), 1);
             if (dtype == SAR_F32)
                 k_gemm<float, float, float, true, true><<<grid, kGemmThreads, 0, st>>>(g);
@@ -1078,4 +1313,80 @@ extern "C" int sar_linear_bwd(const void* X, const void* dZ, const float* W, flo
         }
     }
     return SAR_OK;
+}
+
+}  // namespace
+
+extern "C" int sar_linear_bwd(const void* X, const void* dZ, const float* W, float* dW, void* dX, int dtype,
+                              int64_t n, int K, int F, void* work, size_t work_bytes, void* stream)
+{
+    if (dtype != SAR_F32 && dtype != SAR_BF16)
+        return sar::fail(SAR_ERR_UNSUPPORTED, "dtype %d is neither SAR_F32 nor SAR_BF16", dtype);
+    SAR_CHECK_ARG(n >= 0 && K > 0 && F > 0, "need n >= 0, K > 0, F > 0");
+    if (n == 0) return SAR_OK;
+    SAR_CHECK_ARG(dZ != nullptr, "dZ is null");
+    SAR_CHECK_ARG(dW == nullptr || X != nullptr, "dW needs X");
+    SAR_CHECK_ARG(dX == nullptr || W != nullptr, "dX needs W");
+    if (dW) {
+        const size_t need = (size_t)slabs_for(n, K, F) * K * F * sizeof(float);
+        SAR_CHECK_ARG(work != nullptr && work_bytes >= need, "work_bytes=%zu is below the %zu bytes required",
+                      work_bytes, need);
+    }
+    return linear_bwd_impl(X, dZ, nullptr, W, dW, dX, dtype, n, K, F, work, work_bytes, sar::as_stream(stream));
+}
+
+extern "C" int sar_linear_bwd_rows(const void* X, const void* E, const int32_t* E_rank, int64_t n_E,
+                                   const float* ds, const float* a_r, int H, int D, const float* W, float* dW,
+                                   void* dX, int dtype, int64_t n, int K, void* rows, void* work,
+                                   size_t work_bytes, void* stream)
+{
+    if (dtype != SAR_F32 && dtype != SAR_BF16)
+        return sar::fail(SAR_ERR_UNSUPPORTED, "dtype %d is neither SAR_F32 nor SAR_BF16", dtype);
+    SAR_CHECK_ARG(H > 0 && D > 0, "need H > 0 and D > 0");
+    const int F = H * D;
+    SAR_CHECK_ARG(n >= 0 && K > 0 && n_E >= 0, "need n >= 0, K > 0, n_E >= 0");
+    if (n == 0) return SAR_OK;
+    SAR_CHECK_ARG(E != nullptr || E_rank != nullptr || ds != nullptr,
+                  "neither stored rows E nor the term ds (x) a_r is given");
+    SAR_CHECK_ARG(E != nullptr || n_E == 0, "E is null but n_E = %lld", (long long)n_E);
+    SAR_CHECK_ARG(E == nullptr || E_rank != nullptr || n_E == n, "without E_rank, E has one row per node: n_E must be n");
+    SAR_CHECK_ARG((ds == nullptr) == (a_r == nullptr), "ds and a_r must be given together");
+    SAR_CHECK_ARG(dW == nullptr || X != nullptr, "dW needs X");
+    SAR_CHECK_ARG(dX == nullptr || W != nullptr, "dX needs W");
+    SAR_CHECK_ARG(rows == nullptr || (rows != E && rows != dX), "rows must not alias E or dX");
+    if (dW) {
+        const size_t need = (size_t)slabs_for(n, K, F) * K * F * sizeof(float);
+        SAR_CHECK_ARG(work != nullptr && work_bytes >= need, "work_bytes=%zu is below the %zu bytes required",
+                      work_bytes, need);
+    }
+    hipStream_t st = sar::as_stream(stream);
+    RowsOp op{E_rank, ds, a_r, H, D, (E != nullptr && n_E > 0) ? 1 : 0};
+    if (!op.has_E && !ds) {
+        // no stored row and no rank-one term: E_p = 0, dW gets nothing and dX is zero
+        if (dX) {
+            const unsigned g0 = (unsigned)std::min<int64_t>((n * K + 255) / 256, 16384);
+            RowsOp none{};
+            if (dtype == SAR_F32)
+                k_rows_store<float><<<g0, 256, 0, st>>>(nullptr, none, static_cast<float*>(dX), n, K);
+            else
+                k_rows_store<bf16_t><<<g0, 256, 0, st>>>(nullptr, none, static_cast<bf16_t*>(dX), n, K);
+            SAR_LAUNCH_CHECK();
+        }
+        return SAR_OK;
+    }
+    // where no row is stored the kernels still need an address they may read a row from
+    const void* stored = op.has_E ? E : static_cast<const void*>(a_r ? a_r : ds);
+    if (!rows && rows_op_fusable(X, stored, op, dX, dtype, K, F))
+        return linear_bwd_impl(X, stored, &op, W, dW, dX, dtype, n, K, F, work, work_bytes, st);
+    if (!rows)
+        return sar::fail(SAR_ERR_UNSUPPORTED,
+                         "this shape (K=%d, H=%d, D=%d) cannot form the error rows inside the products: pass `rows`, "
+                         "[n,F] values of scratch, and they are written out first", K, H, D);
+    const unsigned grid = (unsigned)std::min<int64_t>((n * F + 255) / 256, 16384);
+    if (dtype == SAR_F32)
+        k_rows_store<float><<<grid, 256, 0, st>>>(static_cast<const float*>(E), op, static_cast<float*>(rows), n, F);
+    else
+        k_rows_store<bf16_t><<<grid, 256, 0, st>>>(static_cast<const bf16_t*>(E), op, static_cast<bf16_t*>(rows), n, F);
+    SAR_LAUNCH_CHECK();
+    return linear_bwd_impl(X, rows, nullptr, W, dW, dX, dtype, n, K, F, work, work_bytes, st);
 }

@@ -79,7 +79,7 @@ EXPORTS = [
     "sar_gat_scores", "sar_gat_fwd_begin", "sar_gat_fwd_block", "sar_gat_fwd_end", "sar_gat_fwd_all",
     "sar_gat_workspace_bytes", "sar_gat_bwd_begin", "sar_gat_bwd_block", "sar_gat_bwd_all", "sar_gat_bwd_end",
     "sar_gat_bwd_end_noalloc",
-    "sar_linear_fwd", "sar_linear_bwd", "sar_linear_workspace_bytes",
+    "sar_linear_fwd", "sar_linear_bwd", "sar_linear_bwd_rows", "sar_linear_workspace_bytes",
 ]
 
 
@@ -421,9 +421,10 @@ def sar_gat_bwd_all(b: Blocks, Zq: Sequence[torch.Tensor], G: torch.Tensor, tq: 
 
 
 def sar_gat_bwd_end(Zdst: torch.Tensor, ds: torch.Tensor, a_r: torch.Tensor, dZadd: Optional[torch.Tensor],
-                    dZdst: torch.Tensor, da_r: torch.Tensor, work: torch.Tensor,
+                    dZdst: Optional[torch.Tensor], da_r: torch.Tensor, work: torch.Tensor,
                     dZadd_rank: Optional[int] = None) -> None:
-    """dZadd_rank: device address of the local block's t_rank (BlockView.t_rank) when dZadd is compact."""
+    """dZadd_rank: device address of the local block's t_rank (BlockView.t_rank) when dZadd is compact.
+    dZdst None: only da_r."""
     H, D = a_r.shape
     _check(lib().sar_gat_bwd_end(_ptr(Zdst), _ptr(ds), _ptr(a_r), _ptr(dZadd), _vp(dZadd_rank), _ptr(dZdst), _ptr(da_r),
                                  _c_int(dtype_code(Zdst.dtype)), _c_i64(Zdst.shape[0]), _c_int(H), _c_int(D),
@@ -467,3 +468,17 @@ def sar_linear_bwd(X: Optional[torch.Tensor], dZ: torch.Tensor, W: Optional[torc
     wb = 0 if work is None else work.numel() * work.element_size()
     _check(lib().sar_linear_bwd(_ptr(X), _ptr(dZ), _ptr(W), _ptr(dW), _ptr(dX), _c_int(dtype_code(dZ.dtype)),
                                 _c_i64(n), _c_int(K), _c_int(F), _ptr(work), ctypes.c_size_t(wb), _stream()))
+
+
+def sar_linear_bwd_rows(X: Optional[torch.Tensor], E: Optional[torch.Tensor], E_rank: Optional[int],
+                        ds: Optional[torch.Tensor], a_r: Optional[torch.Tensor], H: int, D: int,
+                        W: Optional[torch.Tensor], dW: Optional[torch.Tensor], dX: Optional[torch.Tensor],
+                        n: int, dtype: torch.dtype, work: Optional[torch.Tensor],
+                        rows: Optional[torch.Tensor] = None) -> None:
+    """E_rank: device address of a t_rank array (BlockView.t_rank) when E is compact."""
+    K = X.shape[1] if X is not None else W.shape[0]
+    n_E = 0 if E is None else E.shape[0]
+    wb = 0 if work is None else work.numel() * work.element_size()
+    _check(lib().sar_linear_bwd_rows(_ptr(X), _ptr(E), _vp(E_rank), _c_i64(n_E), _ptr(ds), _ptr(a_r), _c_int(H),
+                                     _c_int(D), _ptr(W), _ptr(dW), _ptr(dX), _c_int(dtype_code(dtype)), _c_i64(n),
+                                     _c_int(K), _ptr(rows), _ptr(work), ctypes.c_size_t(wb), _stream()))

@@ -362,7 +362,7 @@ def test_step_replays_as_a_hip_graph():
     import bench
     from paper_2111_06483_amd import synth
     w = synth.make_workload("cfg3", device="cuda", scale=0.01)
-    layer = bench.Layer(w, torch, sar, synth, act=sar.SAR_ACT_RELU)
+    layer = bench.Layer(w, torch, sar, synth, act=sar.SAR_ACT_RELU, stored_error=True)
     for _ in range(2):
         layer.step("all")                      # warm-up: one-time queries happen outside the capture
     torch.cuda.synchronize()
