@@ -908,7 +908,12 @@ __global__ __launch_bounds__(256) void k_dw(const T* __restrict__ X, const T* __
         }
     };
     if constexpr (FUSE) {
-        for (int f = tid; f < kDwN; f += 256) ars[f] = (op.ds && n0 + f < N) ? op.a_r[n0 + f] : 0.f;
+        // a piece's values four by four: the first four of every piece, then (8-value pieces) the
+        // last four, so that neighbouring lanes read neighbouring 16 bytes (no bank conflicts)
+        for (int f = tid; f < kDwN; f += 256) {
+            const int piece = f / S::kVec, x = f % S::kVec;
+            ars[(x / 4) * (kDwN / 2) + piece * 4 + (x % 4)] = (op.ds && n0 + f < N) ? op.a_r[n0 + f] : 0.f;
+        }
 #pragma unroll
         for (int q = 0; q < kDUnits; ++q) {
             const int u = tid + 256 * q, col = (u % (kDwN / S::kVec)) * S::kVec;
@@ -953,9 +958,15 @@ __global__ __launch_bounds__(256) void k_dw(const T* __restrict__ X, const T* __
 #pragma unroll
         for (int q = 0; q < kDUnits; ++q) {
             const int u = tid + 256 * q, row = u / (kDwN / S::kVec), col = (u % (kDwN / S::kVec)) * S::kVec;
-            if constexpr (FUSE)
-                *reinterpret_cast<uint4*>(&Ds[buf][row][col]) = fuse_piece<T>(gd[q], dsv[q], ars + col);
-            else
+            if constexpr (FUSE) {
+                float arv[S::kVec];
+#pragma unroll
+                for (int x = 0; x < S::kVec; x += 4) {
+                    const float4 v = *reinterpret_cast<const float4*>(ars + (x / 4) * (kDwN / 2) + (col / S::kVec) * 4);
+                    arv[x] = v.x; arv[x + 1] = v.y; arv[x + 2] = v.z; arv[x + 3] = v.w;
+                }
+                *reinterpret_cast<uint4*>(&Ds[buf][row][col]) = fuse_piece<T>(gd[q], dsv[q], arv);
+            } else
                 *reinterpret_cast<uint4*>(&Ds[buf][row][col]) = gd[q];
         }
     };
@@ -1171,7 +1182,7 @@ namespace {
 bool rows_op_fusable(const void* X, const void* dZ, const RowsOp& op, void* dX, int dtype, int K, int F)
 {
     const int elem = dtype == SAR_F32 ? 4 : 2, vec = 16 / elem;
-    if (K % vec != 0 || F % vec != 0 || op.D % vec != 0 || op.H * op.D != F) return false;
+    if (K % vec != 0 || F % vec != 0 || op.D % vec != 0 || op.H * op.D != F || op.H > 2 * kDsRegs) return false;
     if (reinterpret_cast<uintptr_t>(X) % 16 != 0 || reinterpret_cast<uintptr_t>(dZ) % 16 != 0) return false;
     if (op.ds && reinterpret_cast<uintptr_t>(op.a_r) % 16 != 0) return false;
     SkinnyPlan plan;
