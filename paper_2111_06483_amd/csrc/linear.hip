@@ -535,6 +535,7 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_gemm_skinny(SkinnyArgs g)
     float arreg[4] = {0.f, 0.f, 0.f, 0.f}, dsreg[kDsRegs];
     int nrk0 = 0, nrk1 = 0;
     bool has = false;
+    const float inv_D = FUSE ? 1.f / (float)g.op.D : 0.f;
     auto rank_of = [&](int64_t tl, int& r0, int& r1) {
         if (g.op.rank && tl < n_tiles) {
             const int64_t i = std::min<int64_t>(tl * 32 + c, g.M - 1);
@@ -597,9 +598,12 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_gemm_skinny(SkinnyArgs g)
             for (int r = 0; r < 16; ++r) acc[nt][r] = 0.f;
         if constexpr (FUSE) {
             // the previous tile's outputs have left the staging tile
+            // kept head-major, [H][32 rows]: the 32 rows of a head sit in 32 different banks
 #pragma unroll
-            for (int r = 0; r < kDsRegs; ++r)
-                if (lane + 64 * r < 32 * g.op.H) dsl[lane + 64 * r] = dsreg[r];
+            for (int r = 0; r < kDsRegs; ++r) {
+                const int idx = lane + 64 * r;
+                if (idx < 32 * g.op.H) dsl[(idx % g.op.H) * 32 + idx / g.op.H] = dsreg[r];
+            }
             *reinterpret_cast<float4*>(arl + lane * 4) = make_float4(arreg[0], arreg[1], arreg[2], arreg[3]);
             __builtin_amdgcn_wave_barrier();
         }
@@ -612,7 +616,9 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_gemm_skinny(SkinnyArgs g)
             if constexpr (FUSE) {
                 if (!has) av = make_uint4(0u, 0u, 0u, 0u);
                 // a_r is zero beyond K, so a piece beyond the row stays zero
-                const float d = dsl[c * g.op.H + min(k_first / g.op.D, g.op.H - 1)];
+                // head of the piece: k_first / D for 0 <= k_first < 512, without an integer division
+                const int head = min((int)(((float)k_first + 0.5f) * inv_D), g.op.H - 1);
+                const float d = dsl[head * 32 + c];
                 float ar[kChunk / 2];
 #pragma unroll
                 for (int x = 0; x < kChunk / 2; x += 4) {
