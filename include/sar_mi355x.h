@@ -71,8 +71,12 @@ typedef enum { SAR_F32 = 0, SAR_BF16 = 1 } sar_dtype;
  * the one offered, its derivative being a function of the output alone. */
 typedef enum { SAR_ACT_NONE = 0, SAR_ACT_RELU = 1 } sar_act;
 
-/* Most blocks one batched (..._all) call or one handle can hold. */
+/* Most blocks one batched (..._all) call can take, hence most partitions of a handle built with
+ * SAR_BUILD_FUSED; and most partitions of any handle.  A handle of more than SAR_MAX_BLOCKS
+ * partitions (the paper's runs go up to 128 workers) is built without SAR_BUILD_FUSED and used
+ * block by block, which is the streaming form of Alg. 1 / Alg. 2 anyway. */
 #define SAR_MAX_BLOCKS 64
+#define SAR_MAX_PARTS 256
 
 /* flags of sar_blocks_build / sar_blocks_wrap */
 #define SAR_BUILD_TRANSPOSE 1 /* also build the source-major index (needed by every *_bwd_*) */
@@ -149,7 +153,7 @@ int sar_version(void);
  *              KEPT for worker p must be fewer than 2^31 (32-bit offsets inside
  *              the handle), else SAR_ERR_UNSUPPORTED.
  *   part       [N] partition of every node, each in [0,P)
- *   P <= SAR_MAX_BLOCKS, N < 2^31.
+ *   P <= SAR_MAX_PARTS (<= SAR_MAX_BLOCKS with SAR_BUILD_FUSED), N < 2^31.
  * The CSR arrays, their transposes, the degrees and the touched lists / ranks are
  * integer work and bit-exact: they do not depend on thread scheduling.  The launch
  * lists (rows, t_rows) are filled through atomic cursors, so the order of the rows

@@ -142,8 +142,9 @@ __global__ __launch_bounds__(kThreads) void k_part_tile_count(const int32_t* __r
                                                               int32_t* __restrict__ tile_counts,
                                                               int* __restrict__ err)
 {
-    __shared__ int hist[SAR_MAX_BLOCKS];
-    if (threadIdx.x < SAR_MAX_BLOCKS) hist[threadIdx.x] = 0;
+    static_assert(SAR_MAX_PARTS <= kThreads, "one thread per partition");
+    __shared__ int hist[SAR_MAX_PARTS];
+    if (threadIdx.x < SAR_MAX_PARTS) hist[threadIdx.x] = 0;
     __syncthreads();
     for (int r = 0; r < kPartTile / kThreads; ++r) {
         const int64_t v = (int64_t)blockIdx.x * kPartTile + r * kThreads + threadIdx.x;
@@ -167,8 +168,8 @@ __global__ __launch_bounds__(kThreads) void k_local_ids(const int32_t* __restric
 {
     constexpr int kRounds = kPartTile / kThreads;
     constexpr int kChunks = kPartTile / 64;
-    __shared__ int cnt[kChunks][SAR_MAX_BLOCKS];
-    for (int k = threadIdx.x; k < kChunks * SAR_MAX_BLOCKS; k += kThreads) (&cnt[0][0])[k] = 0;
+    __shared__ int cnt[kChunks][SAR_MAX_PARTS];
+    for (int k = threadIdx.x; k < kChunks * SAR_MAX_PARTS; k += kThreads) (&cnt[0][0])[k] = 0;
     __syncthreads();
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int pv[kRounds], rank[kRounds];
@@ -507,7 +508,7 @@ __global__ __launch_bounds__(kThreads) void k_compact(const int32_t* __restrict_
 // ------------------------------------------------- all-blocks (fused) index
 
 struct PtrTable {
-    const int32_t* indptr[SAR_MAX_BLOCKS];
+    const int32_t* indptr[SAR_MAX_PARTS];     // every handle's blocks (the degree pass), 2 KB of kernel arguments
 };
 
 __global__ __launch_bounds__(kThreads) void k_total_degree(PtrTable t, int P, int64_t n_dst,
@@ -982,8 +983,12 @@ extern "C" int sar_blocks_build(const void* src, const void* dst, int idx_bytes,
     SAR_CHECK_ARG(part != nullptr, "part is null");
     SAR_CHECK_ARG(P >= 1 && p >= 0 && p < P, "need 0 <= p < P, got p=%d P=%d", p, P);
     SAR_CHECK_ARG((flags & ~kKnownFlags) == 0, "unknown flags 0x%x", flags);
-    if (P > SAR_MAX_BLOCKS)
-        return sar::fail(SAR_ERR_UNSUPPORTED, "P=%d exceeds SAR_MAX_BLOCKS=%d", P, SAR_MAX_BLOCKS);
+    if (P > SAR_MAX_PARTS)
+        return sar::fail(SAR_ERR_UNSUPPORTED, "P=%d exceeds SAR_MAX_PARTS=%d", P, SAR_MAX_PARTS);
+    if (P > SAR_MAX_BLOCKS && (flags & SAR_BUILD_FUSED))
+        return sar::fail(SAR_ERR_UNSUPPORTED,
+                         "P=%d exceeds SAR_MAX_BLOCKS=%d, the most an all-blocks call takes: build without "
+                         "SAR_BUILD_FUSED and use the per-block calls", P, SAR_MAX_BLOCKS);
     if (N >= ((int64_t)1 << 31))
         return sar::fail(SAR_ERR_UNSUPPORTED, "N must be below 2^31 (32-bit node ids inside the handle)");
     sar_blocks* h = new (std::nothrow) sar_blocks();
@@ -1009,8 +1014,12 @@ extern "C" int sar_blocks_wrap(int P, int64_t n_dst, const int64_t* n_src, const
     SAR_CHECK_ARG(P >= 1 && n_dst >= 0, "need P >= 1 and n_dst >= 0");
     SAR_CHECK_ARG(n_src && indptr && indices, "n_src/indptr/indices is null");
     SAR_CHECK_ARG((flags & ~kKnownFlags) == 0, "unknown flags 0x%x", flags);
-    if (P > SAR_MAX_BLOCKS)
-        return sar::fail(SAR_ERR_UNSUPPORTED, "P=%d exceeds SAR_MAX_BLOCKS=%d", P, SAR_MAX_BLOCKS);
+    if (P > SAR_MAX_PARTS)
+        return sar::fail(SAR_ERR_UNSUPPORTED, "P=%d exceeds SAR_MAX_PARTS=%d", P, SAR_MAX_PARTS);
+    if (P > SAR_MAX_BLOCKS && (flags & SAR_BUILD_FUSED))
+        return sar::fail(SAR_ERR_UNSUPPORTED,
+                         "P=%d exceeds SAR_MAX_BLOCKS=%d, the most an all-blocks call takes: build without "
+                         "SAR_BUILD_FUSED and use the per-block calls", P, SAR_MAX_BLOCKS);
     for (int q = 0; q < P; ++q) {
         SAR_CHECK_ARG(indptr[q] != nullptr, "indptr[%d] is null", q);
         SAR_CHECK_ARG(n_src[q] >= 0 && n_src[q] < ((int64_t)1 << 31), "n_src[%d] out of range", q);

@@ -1396,6 +1396,9 @@ extern "C" int sar_gat_bwd_all(const sar_blocks_t* b, const void* const* Zq, con
 {
     SAR_TRY(bwd_common_checks(b, dtype, H, D, G, rec, a_l, ds, da_l, work, work_bytes));
     SAR_CHECK_ARG(Zq && dZq && dtq, "a pointer table is null");
+    if (b->P > SAR_MAX_BLOCKS)
+        return sar::fail(SAR_ERR_UNSUPPORTED, "an all-blocks call takes at most %d blocks, the handle has %d: use the "
+                         "per-block calls", SAR_MAX_BLOCKS, b->P);
     hipStream_t st = sar::as_stream(stream);
     for (int q = 0; q < b->P; ++q) {
         if (b->blk[q].n_src == 0 || (sar::skips_untouched(b->flags) && b->blk[q].n_t_rows == 0)) continue;

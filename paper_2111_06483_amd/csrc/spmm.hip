@@ -565,6 +565,9 @@ extern "C" int sar_spmm_bwd_all(const sar_blocks_t* b, const void* G, int mean, 
     SAR_CHECK_ARG(b != nullptr, "handle is null");
     SAR_TRY(check_row_shape(dtype, F));
     if (!b->ft_rows) return sar::fail(SAR_ERR_STATE, "handle was built without SAR_BUILD_TRANSPOSE");
+    if (b->P > SAR_MAX_BLOCKS)
+        return sar::fail(SAR_ERR_UNSUPPORTED, "an all-blocks call takes at most %d blocks, the handle has %d: use the "
+                         "per-block calls", SAR_MAX_BLOCKS, b->P);
     int64_t n_src_total = 0;
     for (int q = 0; q < b->P; ++q) n_src_total += b->blk[q].n_src;
     if (n_src_total == 0) return SAR_OK;

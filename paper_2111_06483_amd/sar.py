@@ -25,7 +25,8 @@ SAR_F32 = 0
 SAR_BF16 = 1
 SAR_ACT_NONE = 0
 SAR_ACT_RELU = 1
-SAR_MAX_BLOCKS = 64
+SAR_MAX_BLOCKS = 64      # blocks of an all-blocks call (handles built with SAR_BUILD_FUSED)
+SAR_MAX_PARTS = 256      # partitions of any handle
 SAR_BUILD_TRANSPOSE = 1
 SAR_BUILD_FUSED = 2
 SAR_BUILD_SKIP_UNTOUCHED = 4

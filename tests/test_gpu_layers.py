@@ -349,8 +349,54 @@ def test_max_blocks(H, D):
     b.close()
     part65 = (np.arange(len(part)) % 65).astype(np.int32)
     with pytest.raises(sar.SarError) as e:
-        gu.build_blocks(src, dst, part65, 65, 0)
-    assert e.value.code == sar.SAR_ERR_UNSUPPORTED
+        gu.build_blocks(src, dst, part65, 65, 0)        # with the all-blocks index
+    assert e.value.code == sar.SAR_ERR_UNSUPPORTED and "SAR_BUILD_FUSED" in str(e.value)
+
+
+@pytest.mark.parametrize("dtype,H,D", [(torch.float32, 4, 64), (torch.bfloat16, 8, 32), (torch.float32, 2, 50)])
+def test_128_partitions_block_by_block(dtype, H, D):
+    """The paper's largest runs use 128 workers: a handle of 128 partitions, built without the
+    all-blocks index, serves the streaming form of Alg. 1 / Alg. 2 (one call per block); the
+    all-blocks calls refuse it, and more than SAR_MAX_PARTS partitions are refused outright."""
+    P, p, F = 128, 77, H * D
+    src, dst, part, rng = make_graph(45, 9000, 90000, P, simple=False)
+    want_b, deg = orc.build_blocks(src, dst, part, P, p)
+    flags = sar.SAR_BUILD_TRANSPOSE
+    b = gu.build_blocks(src, dst, part, P, p, flags=flags)
+    assert b.P == P
+    assert np.array_equal(sar.sar_blocks_degree(b).cpu().numpy(), deg)
+    for q in (0, 64, 77, 127):
+        v = gu.view_arrays(b, q)
+        assert np.array_equal(v["indptr"], want_b[q].indptr.astype(np.int32))
+        assert np.array_equal(v["indices"], want_b[q].indices)
+        assert np.array_equal(v["t_indptr"], want_b[q].t_indptr.astype(np.int32))
+        assert np.array_equal(v["t_indices"], want_b[q].t_indices)
+    tol = TOL[dtype]
+    Zs = [feats(rng, w.n_src, F, dtype).cuda() for w in want_b]
+    want = orc.spmm(want_b, [f64(z) for z in Zs], True)
+    assert rel_err(f64(gu.spmm_stream(b, Zs, True)), want) < tol
+    Z3 = [z.reshape(-1, H, D) for z in Zs]
+    Zdst = Z3[p]
+    bound = np.sqrt(6.0 / (D + 1))
+    a_l = torch.from_numpy(rng.uniform(-bound, bound, (H, D)).astype(np.float32)).cuda()
+    a_r = torch.from_numpy(rng.uniform(-bound, bound, (H, D)).astype(np.float32)).cuda()
+    G = feats(rng, b.n_dst, F, dtype).cuda().reshape(-1, H, D)
+    wf = orc.gat_fwd(want_b, f64(Zdst), [f64(z) for z in Z3], f64(a_l), f64(a_r), SLOPE)
+    wb = orc.gat_bwd(want_b, f64(Zdst), [f64(z) for z in Z3], f64(G), f64(a_l), f64(a_r), SLOPE, wf)
+    fw = gu.gat_fwd_stream(b, Zdst, Z3, a_l, a_r, SLOPE, fly=True)
+    assert rel_err(f64(fw.out), wf.out) < tol
+    g = gu.gat_bwd(b, Zdst, Z3, G, a_l, a_r, SLOPE, fw, False, fly=True)
+    for q in range(P):
+        assert rel_err(f64(g.dZs[q]), wb.dZs[q]) < tol, q
+    assert rel_err(f64(g.ds), wb.ds) < tol
+    assert rel_err(f64(g.da_l), wb.da_l) < tol and rel_err(f64(g.da_r), wb.da_r) < tol
+    with pytest.raises(sar.SarError):                       # no all-blocks index in this handle
+        gu.gat_fwd_all(b, Zdst, Z3, a_l, a_r, SLOPE, fly=True)
+    b.close()
+    part257 = (np.arange(len(part)) % 257).astype(np.int32)
+    with pytest.raises(sar.SarError) as e:
+        gu.build_blocks(src, dst, part257, 257, 0, flags=flags)
+    assert e.value.code == sar.SAR_ERR_UNSUPPORTED and "SAR_MAX_PARTS" in str(e.value)
 
 
 # ------------------------------------------------------------------ HIP graph replay
