@@ -697,7 +697,8 @@ def main():
         "dtype": r["dtype"],
         "data": "synthetic",
         "config": {"workload": r["workload"], "mode": args.mode, "scale": args.scale, "act": args.act,
-                   "dst_frac": args.dst_frac, "errors": args.errors},
+                   "dst_frac": args.dst_frac, "errors": args.errors,
+                   "own_error_rows": "stored before Z_p.backward" if args.stored_error else "formed inside Z_p.backward"},
         "phases_ms": r["phases_ms"],
         "aggregation_only_edges_per_s": r["aggregation_only_edges_per_s"],
         "builder_s": r["builder_s"],
