@@ -137,7 +137,7 @@ typedef struct {
  * the next failing call on the same thread. */
 const char* sar_last_error(void);
 
-/* ABI version of this header (currently 3). */
+/* ABI version of this header (currently 4). */
 int sar_version(void);
 
 /* ------------------------------------------------------------------ blocks

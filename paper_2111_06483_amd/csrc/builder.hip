@@ -31,7 +31,7 @@ int fail(int code, const char* fmt, ...)
 }  // namespace sar
 
 extern "C" const char* sar_last_error(void) { return sar::g_err; }
-extern "C" int sar_version(void) { return 3; }
+extern "C" int sar_version(void) { return 4; }
 
 namespace {
 
