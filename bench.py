@@ -62,6 +62,10 @@ def parse():
     ap.add_argument("--storage", default="config", choices=["config", "f32", "bf16"],
                     help="storage type of the feature rows; 'config' keeps what the configuration names "
                          "(the headline, config 3, is fp32); accumulation is fp32 either way")
+    ap.add_argument("--heads", type=int, default=0, help="override the workload's head count (with --head-dim)")
+    ap.add_argument("--head-dim", type=int, default=0,
+                    help="override the workload's head width: the same graph and in_dim with another layer shape, "
+                         "e.g. 4 x 32 (not a BASELINE configuration)")
     ap.add_argument("--stored-error", action="store_true",
                     help="write the worker's own error E_p = E_{p->p} + ds (x) a_r out (sar_gat_bwd_end) before "
                          "Z_p.backward reads it, instead of forming its rows inside the two products")
@@ -414,6 +418,8 @@ def time_gat(args, torch, sar, synth, name, steps, warmup, full_report):
          else synth.make_local_workload(device="cuda", scale=args.scale))
     if args.storage != "config":
         w.dtype = torch.float32 if args.storage == "f32" else torch.bfloat16
+    if args.heads and args.head_dim:
+        w.H, w.D = args.heads, args.head_dim
     layer = Layer(w, torch, sar, synth, act=sar.SAR_ACT_RELU if args.act == "relu" else sar.SAR_ACT_NONE,
                   dst_frac=args.dst_frac, errors=args.errors, stored_error=args.stored_error)
     if full_report and args.calib_copy_mib:
@@ -463,9 +469,11 @@ def time_gat(args, torch, sar, synth, name, steps, warmup, full_report):
     launches = 1 if args.mode == "all" else w.P
     fast = layer.F == 256
     calls = {
-        "gat_fwd": {"kernel": ("k_gat_fwd_f256" if fast else "k_gat_fwd") + (" (all blocks)" if args.mode == "all" else " (per block)"),
+        "gat_fwd": {"kernel": ("k_gat_fwd_f256" if fast else "k_gat_fwd_f256 in its padded geometry, or k_gat_fwd, by shape")
+                    + (" (all blocks)" if args.mode == "all" else " (per block)"),
                     "avg_ms": fwd_ms, "alg_bytes": alg["gat_fwd"]},
-        "gat_bwd": {"kernel": ("k_gat_bwd_f256 + k_gat_bwd_few" if fast else "k_gat_bwd")
+        "gat_bwd": {"kernel": ("k_gat_bwd_f256 + k_gat_bwd_few" if fast
+                               else "k_gat_bwd_f256 + k_gat_bwd_few in their padded geometry, or k_gat_bwd, by shape")
                     + ("" if layer.errors != "full" else " + k_bwd_zero_rows"),
                     "avg_ms": bwd_ms, "alg_bytes": alg["gat_bwd"],
                     "alg_bytes_full_height": alg["gat_bwd_full_height"]},

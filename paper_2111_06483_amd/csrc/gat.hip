@@ -767,6 +767,14 @@ int lanes_per_head(int D)
     return lph;
 }
 
+// Whether heads of width D may run with twice the lanes they need (8..32 lanes needed, and at
+// least 3/8 of the doubled lanes carrying values: widths 32, 64, 128, 100, ...).
+bool half_filled_ok(int D)
+{
+    const int lph = lanes_per_head(D);
+    return lph >= 8 && lph <= 32 && D * 2 >= 3 * lph;
+}
+
 struct FastGeo {
     int lph;     // 0: not applicable
     bool pad;
@@ -782,9 +790,14 @@ HeadGroups head_groups(int dtype, int H, int D)
     int hg = std::max<int>(1, 64 * g.piece / D);
     hg = std::min(hg, H);
     while (H % hg != 0) --hg;
-    // groups of 64/LPH heads fill one wavefront of the specialised kernels exactly
+    // groups of 64/LPH heads fill one wavefront of the specialised kernels exactly; where the heads
+    // do not come in such groups, groups of half as many heads with twice the lanes each (the
+    // padded geometry leaves the surplus lanes idle) still beat the generic kernels
     const int lph = lanes_per_head(D);
-    if (lph >= 16 && H % (64 / lph) == 0) hg = 64 / lph;
+    if (lph >= 16 && H % (64 / lph) == 0)
+        hg = 64 / lph;
+    else if (half_filled_ok(D) && H % (32 / lph) == 0 && !(H % (64 / lph) == 0 && H * D == f256::kF))
+        hg = 32 / lph;
     g.Hg = hg;
     g.n = H / hg;
     g.Fg = hg * D;
@@ -850,10 +863,14 @@ unsigned persistent_grid_for(int64_t n_rows, int64_t n_long, int resident)
 FastGeo fast_geo(int H, int D, int ldz)
 {
     const int lph = lanes_per_head(D);
-    if (lph == 0 || H * lph != 64) return FastGeo{0, false};
-    const bool exact = D == 4 * lph && ldz == f256::kF;
-    if (!exact && lph < 16) return FastGeo{0, false};
-    return FastGeo{lph, !exact};
+    if (lph == 0) return FastGeo{0, false};
+    if (H * lph == 64) {
+        const bool exact = D == 4 * lph && ldz == f256::kF;
+        if (exact || lph >= 16) return FastGeo{lph, !exact};
+    }
+    // half as many heads as would fill the lanes: every head gets 2 lph lanes, half of them idle
+    if (H * lph == 32 && half_filled_ok(D)) return FastGeo{2 * lph, true};
+    return FastGeo{0, false};
 }
 
 template <typename T, int LPH, bool ALL, bool FLY, bool PAD>
@@ -921,13 +938,16 @@ int launch_fwd(const FwdArgs& a, const PtrTab& zt, const PtrTab& tt, int P, hipS
     return SAR_OK;
 }
 
-// the padded geometry has no four-sources-per-wavefront kernel: every source takes the wide one
+// The same pair of kernels in the padded geometry.  The few-edges kernel also takes the sources
+// without an edge at the end of the list (it writes their zero rows).
 template <typename T, int LPH, bool ALL>
 int launch_bwd_f256_padded(const BwdArgs& tabs, const BwdScalars& a, unsigned* grid_out, hipStream_t st)
 {
     constexpr int B = 8;
     auto wide = f256::k_gat_bwd_f256<T, LPH, B, ALL, true>;
+    auto few = f256::k_gat_bwd_few<T, LPH, ALL, true>;
     static const int resident_wide = resident_workgroups(wide);
+    static const int resident_few = resident_workgroups(few);
     f256::BwdTabs t{};
     for (int q = 0; q < SAR_MAX_BLOCKS; ++q) {
         t.t_indptr[q] = tabs.t_indptr[q]; t.t_indices[q] = tabs.t_indices[q];
@@ -935,14 +955,24 @@ int launch_bwd_f256_padded(const BwdArgs& tabs, const BwdScalars& a, unsigned* g
         t.rank[q] = tabs.rank[q];
     }
     f256::BwdP p{};
-    p.rows = a.rows; p.n_rows = a.n_rows; p.n_long = a.n_long;
+    p.rows = a.rows; p.n_rows = a.n_wide; p.n_long = std::min(a.n_long, a.n_wide);
     p.G = a.G; p.rec = a.rec; p.a_l = a.a_l; p.ds = a.ds; p.partial = a.partial;
     p.H = a.H; p.tag_shift = a.tag_shift; p.slope = a.slope;
     p.ld = a.ldz; p.ldh = a.ldh; p.D = a.D;
-    const unsigned g = persistent_grid_for(p.n_rows, p.n_long, resident_wide);
-    wide<<<g, kGatherThreads, 0, st>>>(t, p);
-    SAR_LAUNCH_CHECK();
-    *grid_out = g;
+    unsigned g_wide = 0, g_few = 0;
+    if (a.n_wide > 0) {
+        g_wide = persistent_grid_for(p.n_rows, p.n_long, resident_wide);
+        wide<<<g_wide, kGatherThreads, 0, st>>>(t, p);
+        SAR_LAUNCH_CHECK();
+    }
+    if (a.n_rows > a.n_wide) {
+        const int64_t n = a.n_rows - a.n_wide;
+        const int64_t per_wg = (int64_t)(B / 2) * kWavesPerWG;
+        g_few = (unsigned)std::max<int64_t>(1, std::min<int64_t>((n + per_wg - 1) / per_wg, resident_few));
+        few<<<g_few, kGatherThreads, 0, st>>>(t, p, a.n_wide, a.n_rows, (int)g_wide);
+        SAR_LAUNCH_CHECK();
+    }
+    *grid_out = g_wide + g_few;
     return SAR_OK;
 }
 
@@ -1002,7 +1032,7 @@ int launch_bwd_f256(const BwdArgs& tabs, const BwdScalars& a, unsigned* grid_out
 {
     constexpr int B = LPH >= 8 ? 8 : 4;
     auto wide = f256::k_gat_bwd_f256<T, LPH, B, ALL, false>;
-    auto few = f256::k_gat_bwd_few<T, LPH, ALL>;
+    auto few = f256::k_gat_bwd_few<T, LPH, ALL, false>;
     constexpr int kPerWave = B / 2;     // sources a wavefront of that kernel takes at once
     static const int resident_wide = resident_workgroups(wide);
     static const int resident_few = resident_workgroups(few);

@@ -541,7 +541,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_f256(BwdTabs tabs, B
 // lane u*kAhead + e holds source u's list entry, edge range and output row, and the
 // destination of its edge e.  List entries are read three groups ahead, ranges two, and
 // destinations one, so that a group starts with its row gathers and no dependent chain.
-template <typename T, int LPH, bool ALL>
+template <typename T, int LPH, bool ALL, bool PAD>
 __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_few(BwdTabs tabs, BwdP a, int64_t r_begin, int64_t r_end,
                                                                 int partial_row0)
 {
@@ -572,12 +572,15 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_few(BwdTabs tabs, Bw
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int h = lane / LPH, k = lane % LPH;
-    const int foff = lane * 4;
+    // exact geometry: rows of 256 values; padded: heads of any width D <= 4 LPH inside rows of stride ld
+    const int ld = PAD ? a.ld : kF, ldh = PAD ? a.ldh : a.H;
+    const int foff = PAD ? h * a.D + 4 * k : lane * 4;
+    const bool on = PAD ? 4 * k < a.D : true;
     const uint32_t mask = ALL ? ((1u << a.tag_shift) - 1u) : 0xffffffffu;
     const T* Gp = static_cast<const T*>(a.G);
 
-    float al[4], dal[4];
-    load_f32<4>(a.a_l + foff, al);
+    float al[4] = {0.f, 0.f, 0.f, 0.f}, dal[4];
+    if (on) load_f32<4>(a.a_l + foff, al);
 #pragma unroll
     for (int x = 0; x < 4; ++x) dal[x] = 0.f;
 
@@ -627,7 +630,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_few(BwdTabs tabs, Bw
             jo[u] = __builtin_amdgcn_readlane(m0.jo, u * kAhead);
             rounds = max(rounds, end[u] - beg[u]);
             zr[u] = typename Row4<T>::Raw{};
-            if (have[u]) zr[u] = load_lane<T, false>(static_cast<const T*>(s_Z[q[u]]) + (int64_t)j[u] * kF, foff, true);
+            if (have[u]) zr[u] = load_lane<T, PAD>(static_cast<const T*>(s_Z[q[u]]) + (int64_t)j[u] * ld, foff, on);
         });
         float t2[S], dz[S][4];
         static_for<S>([&](auto uu) {
@@ -637,7 +640,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_few(BwdTabs tabs, Bw
             t2[u] = 0.f;
             if (have[u]) {
                 if (s_t[q[u]]) {
-                    t2[u] = s_t[q[u]][(int64_t)j[u] * a.H + h] * kLog2e;
+                    t2[u] = s_t[q[u]][(int64_t)j[u] * ldh + h] * kLog2e;
                 } else {   // t_j = <a_l, z_j> from the row this wavefront holds
                     float zj[4];
                     Row4<T>::unpack(zr[u], zj);
@@ -666,7 +669,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_few(BwdTabs tabs, Bw
             });
             static_for<B>([&](auto kk) {
                 constexpr int K = decltype(kk)::value;
-                if (ok[K]) raw[K] = load_lane<T, false>(Gp + (int64_t)dst[K] * kF, foff, true);
+                if (ok[K]) raw[K] = load_lane<T, PAD>(Gp + (int64_t)dst[K] * ld, foff, on);
             });
             // lane k speaks for slot k
             int my_i = 0;
@@ -677,7 +680,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_few(BwdTabs tabs, Bw
                 my_ok = (k == K) ? ok[K] : my_ok;
             });
             float4 rec = make_float4(0.f, INFINITY, 0.f, 0.f);   // L = +inf gives alpha = 0
-            if (my_ok) rec = a.rec[(int64_t)my_i * a.H + h];
+            if (my_ok) rec = a.rec[(int64_t)my_i * ldh + h];
             float c_mine = 0.f;
             static_for<B>([&](auto kk) {
                 constexpr int K = decltype(kk)::value;
@@ -695,7 +698,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_few(BwdTabs tabs, Bw
             const float de = alpha * (c_mine - rec.z);
             const float du = u2 > 0.f ? de : a.slope * de;
             dt_mine += du;
-            if (my_ok) unsafeAtomicAdd(a.ds + (int64_t)my_i * a.H + h, du);
+            if (my_ok) unsafeAtomicAdd(a.ds + (int64_t)my_i * ldh + h, du);
             static_for<B>([&](auto kk) {
                 constexpr int K = decltype(kk)::value;
                 const float ak = group_bcast<LPH, K>(alpha);
@@ -719,8 +722,8 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_few(BwdTabs tabs, Bw
                     v[x] = fmaf(dt, al[x], dz[u][x]);
                     dal[x] = fmaf(dt, zj[x], dal[x]);
                 }
-                Row4<T>::store(static_cast<T*>(s_dZ[q[u]]) + (int64_t)jo[u] * kF, lane, v);
-                if (k == 0) s_dt[q[u]][(int64_t)jo[u] * a.H + h] = dt;
+                store_lane<T, PAD>(static_cast<T*>(s_dZ[q[u]]) + (int64_t)jo[u] * ld, foff, on, v);
+                if (k == 0) s_dt[q[u]][(int64_t)jo[u] * ldh + h] = dt;
             }
         });
         m0 = m1;

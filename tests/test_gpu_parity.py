@@ -202,6 +202,8 @@ def check_fwd(got, want, deg, dtype):
 # kernels, non-power-of-two heads, and rows wider than 1 KiB (processed as groups of heads)
 SHAPES = [(4, 16), (1, 4), (4, 64), (8, 32), (2, 100), (3, 12), (1, 256), (2, 128), (16, 16),
           (8, 100), (8, 64), (3, 200), (2, 256), (1, 512),      # the last: the widest head of each row type
+          # groups of half as many heads as fill a wavefront (padded geometry, half the lanes idle)
+          (4, 32), (2, 64), (1, 128), (16, 32), (1, 100), (6, 36),
           # head widths that are not whole 16-byte pieces: lanes move 8, 4 or 2 bytes
           (3, 10), (2, 50), (4, 12), (5, 7), (2, 63), (1, 126), (6, 36)]
 
