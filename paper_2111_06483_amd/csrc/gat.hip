@@ -420,7 +420,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd(BwdArgs tabs, BwdSca
         }
     };
     // dZ_q[j] = sum alpha G + dt a_l ; dt_q[j] = dt ; da_l += dt z_j
-    auto row_outputs = [&](const BwdAcc<VEC>& ac, int q, int j, const float (&zj)[VEC]) {
+    auto row_outputs = [&](const BwdAcc<VEC>& ac, int q, int j, const float (&zj)[VEC], int64_t jo) {
         if (lm.slot != 0 || !lm.on) return;
         float v[VEC];
 #pragma unroll
@@ -428,7 +428,6 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd(BwdArgs tabs, BwdSca
             v[x] = fmaf(ac.dt, al[x], ac.dz[x]);
             dal[x] = fmaf(ac.dt, zj[x], dal[x]);
         }
-        const int64_t jo = tabs.rank[q] ? tabs.rank[q][j] : j;
         Vec<T>::store(static_cast<T*>(tabs.dZ[q]) + jo * a.ldz + lm.gl * VEC, v);
         if ((lm.gl % lm.lph) == 0) tabs.dt[q][jo * a.ldh + lm.h] = ac.dt;
     };
@@ -457,20 +456,45 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd(BwdArgs tabs, BwdSca
                 else
                     ac.dt = s;
             }
-            row_outputs(ac, q, j, zj);
+            row_outputs(ac, q, j, zj, tabs.rank[q] ? (int64_t)tabs.rank[q][j] : (int64_t)j);
         }
         __syncthreads();
     }
+    // One source per wavefront.  Most sources of a partitioned graph have a handful of edges, so
+    // what a wavefront spends its time on is the chain list entry -> edge range -> indices -> rows;
+    // the first two links (and the output row) of the NEXT source are read while this one is
+    // processed, the list entry of the one after that as well.
     const int64_t n_waves = (int64_t)gridDim.x * kWavesPerWG;
-    for (int64_t r = a.n_long + (int64_t)blockIdx.x * kWavesPerWG + wave; r < a.n_rows; r += n_waves) {
+    int64_t r = a.n_long + (int64_t)blockIdx.x * kWavesPerWG + wave;
+    struct Ahead {
+        uint32_t id;
+        int beg, end;
+        int64_t jo;
+    };
+    auto look_up = [&](uint32_t id) {
+        Ahead m;
+        m.id = id;
+        const int q = ALL ? (int)(id >> a.tag_shift) : 0, j = (int)(id & mask);
+        m.beg = tabs.t_indptr[q][j];
+        m.end = tabs.t_indptr[q][j + 1];
+        m.jo = tabs.rank[q] ? (int64_t)tabs.rank[q][j] : (int64_t)j;
+        return m;
+    };
+    Ahead next{};
+    uint32_t id_after = 0;
+    if (r < a.n_rows) next = look_up(a.rows[r]);
+    if (r + n_waves < a.n_rows) id_after = a.rows[r + n_waves];
+    for (; r < a.n_rows; r += n_waves) {
+        const Ahead cur = next;
+        if (r + n_waves < a.n_rows) next = look_up(id_after);
+        if (r + 2 * n_waves < a.n_rows) id_after = a.rows[r + 2 * n_waves];
         int q, j;
         float zj[VEC], t2;
-        row_inputs(a.rows[r], q, j, zj, t2);
+        row_inputs(cur.id, q, j, zj, t2);
         BwdAcc<VEC> ac = {};
-        bwd_edges<T, G>(ac, a, tabs.t_indices[q], tabs.t_indptr[q][j], tabs.t_indptr[q][j + 1], 0, 1, lm,
-                        zj, t2, pow2);
+        bwd_edges<T, G>(ac, a, tabs.t_indices[q], cur.beg, cur.end, 0, 1, lm, zj, t2, pow2);
         bwd_merge_slots<T, G>(ac);
-        row_outputs(ac, q, j, zj);
+        row_outputs(ac, q, j, zj, cur.jo);
     }
 
     // this workgroup's share of da_l = sum_j dt_j z_j
@@ -754,7 +778,8 @@ struct HeadGroups {
     int n, Hg, Fg;       // groups, heads per group, values per group
     size_t fb;           // bytes per feature value
     int piece;           // values per lane of the generic and node-wise kernels (divides D)
-    bool fast;           // the specialised gather kernels take a group (they use the full row type)
+    bool fast_fwd;       // the specialised forward / backward gather kernels take a group (they use the
+    bool fast_bwd;       // full row type)
     int full;            // values per lane of the full row type: 4 (fp32) or 8 (bf16)
 };
 
@@ -767,17 +792,32 @@ int lanes_per_head(int D)
     return lph;
 }
 
-// Whether heads of width D may run with twice the lanes they need (8..32 lanes needed, and at
-// least 3/8 of the doubled lanes carrying values: widths 32, 64, 128, 100, ...).
-bool half_filled_ok(int D)
+// The specialised kernels give every head LPH lanes of 4 values and a launch takes 64/LPH heads.
+// Exact geometry: contiguous rows of 256 values, LPH = D/4 (4..64).  Padded geometry (built for
+// LPH = 8, 16, 32, 64): heads of any width that is a multiple of 4 up to 4 LPH, rows of any stride,
+// the lanes a head does not need staying idle; a layer of more heads runs as several launches over
+// groups of heads.  The gathers are bound by memory, not by lanes, so idle lanes cost little:
+//   at least 3/8 of the lanes busy: faster than the generic kernels in both passes, also over
+//     several launches (4 x 32 on 16 lanes per head, 5.96 -> 3.78 ms per step of the products-sized
+//     share; 16 x 32 in rows of 512, 19.2 -> 14.9 ms; 1 x 100 on 64 lanes, 11.5 -> 5.3 ms);
+//   fewer ("sparse"): only the backward pass gains, and only when the whole layer is ONE launch
+//     (the generic backward gives every source a wavefront however few its edges: 4 x 16,
+//     3.43 -> 1.83 ms; its forward stays ahead, 0.69 against 0.94 ms; over several launches the
+//     repeated index traffic costs more than it saves: 8 x 8 on 16 lanes, 3 x 64 on 64).
+// Lanes per head for a launch of Hg heads of width D, or 0 if the padded geometry cannot take it.
+int padded_lanes(int Hg, int D)
 {
-    const int lph = lanes_per_head(D);
-    return lph >= 8 && lph <= 32 && D * 2 >= 3 * lph;
+    const int need = lanes_per_head(D);
+    if (need == 0 || Hg < 1 || Hg > 8 || 64 % Hg != 0) return 0;
+    const int lanes = 64 / Hg;
+    return lanes >= need ? lanes : 0;
 }
+bool sparse_lanes(int lanes, int D) { return (D / 4) * 8 < 3 * lanes; }
 
 struct FastGeo {
     int lph;     // 0: not applicable
     bool pad;
+    bool sparse; // fewer than 3/8 of the lanes carry values: backward pass only
 };
 FastGeo fast_geo(int H, int D, int ldz);
 
@@ -790,18 +830,23 @@ HeadGroups head_groups(int dtype, int H, int D)
     int hg = std::max<int>(1, 64 * g.piece / D);
     hg = std::min(hg, H);
     while (H % hg != 0) --hg;
-    // groups of 64/LPH heads fill one wavefront of the specialised kernels exactly; where the heads
-    // do not come in such groups, groups of half as many heads with twice the lanes each (the
-    // padded geometry leaves the surplus lanes idle) still beat the generic kernels
+    // heads per launch of the specialised kernels, where they apply (see padded_lanes)
     const int lph = lanes_per_head(D);
-    if (lph >= 16 && H % (64 / lph) == 0)
-        hg = 64 / lph;
-    else if (half_filled_ok(D) && H % (32 / lph) == 0 && !(H % (64 / lph) == 0 && H * D == f256::kF))
-        hg = 32 / lph;
+    if (lph > 0 && H * lph == 64 && H * D == f256::kF) {
+        hg = H;                                   // the exact geometry: all heads in one launch
+    } else if (lph > 0) {
+        for (int cand = 8; cand >= 1; cand /= 2) {   // most heads per launch first: most lanes busy
+            if (H % cand != 0 || padded_lanes(cand, D) == 0) continue;
+            if (!sparse_lanes(64 / cand, D) || cand == H) hg = cand;
+            break;
+        }
+    }
     g.Hg = hg;
     g.n = H / hg;
     g.Fg = hg * D;
-    g.fast = fast_geo(hg, D, H * D).lph != 0;
+    const FastGeo geo = fast_geo(hg, D, H * D);
+    g.fast_bwd = geo.lph != 0;
+    g.fast_fwd = geo.lph != 0 && !geo.sparse;
     return g;
 }
 
@@ -859,18 +904,17 @@ unsigned persistent_grid_for(int64_t n_rows, int64_t n_long, int resident)
 // Whether the specialised kernels take a launch of H heads of width D in rows of stride ldz, and
 // in which geometry: exact (contiguous rows of 256 values, power-of-two head width) or padded
 // (64/LPH heads of any width up to 4*LPH that is a multiple of 4, any row stride; built for
-// LPH = 16, 32, 64).  Lanes move 4 values (16 bytes of fp32, 8 bytes of bf16) either way.
+// LPH = 8, 16, 32, 64).  Lanes move 4 values (16 bytes of fp32, 8 bytes of bf16) either way.
 FastGeo fast_geo(int H, int D, int ldz)
 {
     const int lph = lanes_per_head(D);
-    if (lph == 0) return FastGeo{0, false};
-    if (H * lph == 64) {
-        const bool exact = D == 4 * lph && ldz == f256::kF;
-        if (exact || lph >= 16) return FastGeo{lph, !exact};
-    }
-    // half as many heads as would fill the lanes: every head gets 2 lph lanes, half of them idle
-    if (H * lph == 32 && half_filled_ok(D)) return FastGeo{2 * lph, true};
-    return FastGeo{0, false};
+    if (lph == 0) return FastGeo{0, false, false};
+    if (H * lph == 64 && D == 4 * lph && ldz == f256::kF) return FastGeo{lph, false, false};
+    const int lanes = padded_lanes(H, D);
+    if (lanes < 8) return FastGeo{0, false, false};
+    const bool sparse = sparse_lanes(lanes, D);
+    if (sparse && H * D != ldz) return FastGeo{0, false, false};   // sparse groups pay in one launch only
+    return FastGeo{lanes, true, sparse};
 }
 
 template <typename T, int LPH, bool ALL, bool FLY, bool PAD>
@@ -904,8 +948,11 @@ int launch_fwd(const FwdArgs& a, const PtrTab& zt, const PtrTab& tt, int P, hipS
     return a.a_l ? launch_fwd_f256<T, LPH, ALL, true, PAD>(a, zt, tt, st)                  \
                  : launch_fwd_f256<T, LPH, ALL, false, PAD>(a, zt, tt, st)
         const FastGeo geo = fast_geo(a.H, a.D, a.ldz);
-        if (geo.pad) {
+        if (geo.sparse) {
+            // the generic forward kernel is the faster one here
+        } else if (geo.pad) {
             switch (geo.lph) {
+                case 8: SAR_FWD_F256(8, true);
                 case 16: SAR_FWD_F256(16, true);
                 case 32: SAR_FWD_F256(32, true);
                 case 64: SAR_FWD_F256(64, true);
@@ -1095,6 +1142,7 @@ int launch_bwd(const BwdArgs& tabs, BwdScalars& a, float* da_l, hipStream_t st)
         const FastGeo geo = fast_geo(a.H, a.D, a.ldz);
         if (geo.pad) {
             switch (geo.lph) {
+                case 8: SAR_TRY((launch_bwd_f256_padded<T, 8, ALL>(tabs, a, &grid, st))); break;
                 case 16: SAR_TRY((launch_bwd_f256_padded<T, 16, ALL>(tabs, a, &grid, st))); break;
                 case 32: SAR_TRY((launch_bwd_f256_padded<T, 32, ALL>(tabs, a, &grid, st))); break;
                 default: SAR_TRY((launch_bwd_f256_padded<T, 64, ALL>(tabs, a, &grid, st))); break;
@@ -1228,7 +1276,7 @@ extern "C" int sar_gat_fwd_block(const sar_blocks_t* b, int q, const void* Zq, c
         a.ldh = H;
         a.slope = slope;
         PtrTab none{};
-        SAR_DISPATCH_ROW(dtype, hg.fast ? hg.full : hg.piece,
+        SAR_DISPATCH_ROW(dtype, hg.fast_fwd ? hg.full : hg.piece,
                          SAR_TRY((launch_fwd<T, false>(a, none, none, 0, sar::as_stream(stream)))));
     }
     return SAR_OK;
@@ -1300,7 +1348,7 @@ extern "C" int sar_gat_fwd_all(const sar_blocks_t* b, const void* const* Zq, con
         a.tag_shift = b->tag_shift;
         a.slope = slope;
         a.act = act;
-        SAR_DISPATCH_ROW(dtype, hg.fast ? hg.full : hg.piece, SAR_TRY((launch_fwd<T, true>(a, zt, tt, b->P, st))));
+        SAR_DISPATCH_ROW(dtype, hg.fast_fwd ? hg.full : hg.piece, SAR_TRY((launch_fwd<T, true>(a, zt, tt, b->P, st))));
     }
     return SAR_OK;
 }
@@ -1414,7 +1462,7 @@ extern "C" int sar_gat_bwd_block(const sar_blocks_t* b, int q, const void* Zq, c
         a.n_src_host = &k.n_src;
         a.n_blocks = 1;
         fill_bwd_group(a, hg, g, H, D, G, rec, a_l, ds, work, slope);
-        SAR_DISPATCH_ROW(dtype, hg.fast ? hg.full : hg.piece, SAR_TRY((launch_bwd<T, false>(tabs, a, da_l + f0, st))));
+        SAR_DISPATCH_ROW(dtype, hg.fast_bwd ? hg.full : hg.piece, SAR_TRY((launch_bwd<T, false>(tabs, a, da_l + f0, st))));
     }
     return SAR_OK;
 }
@@ -1464,7 +1512,7 @@ extern "C" int sar_gat_bwd_all(const sar_blocks_t* b, const void* const* Zq, con
         a.n_long = b->n_ft_long;
         a.tag_shift = b->tag_shift;
         fill_bwd_group(a, hg, g, H, D, G, rec, a_l, ds, work, slope);
-        SAR_DISPATCH_ROW(dtype, hg.fast ? hg.full : hg.piece, SAR_TRY((launch_bwd<T, true>(tabs, a, da_l + f0, st))));
+        SAR_DISPATCH_ROW(dtype, hg.fast_bwd ? hg.full : hg.piece, SAR_TRY((launch_bwd<T, true>(tabs, a, da_l + f0, st))));
     }
     return SAR_OK;
 }

@@ -202,8 +202,10 @@ def check_fwd(got, want, deg, dtype):
 # kernels, non-power-of-two heads, and rows wider than 1 KiB (processed as groups of heads)
 SHAPES = [(4, 16), (1, 4), (4, 64), (8, 32), (2, 100), (3, 12), (1, 256), (2, 128), (16, 16),
           (8, 100), (8, 64), (3, 200), (2, 256), (1, 512),      # the last: the widest head of each row type
-          # groups of half as many heads as fill a wavefront (padded geometry, half the lanes idle)
-          (4, 32), (2, 64), (1, 128), (16, 32), (1, 100), (6, 36),
+          # padded geometry with idle lanes: half-filled head groups, 8 lanes per head, and the sparse
+          # single-launch layers whose backward pass alone takes the specialised kernels
+          (4, 32), (2, 64), (1, 128), (16, 32), (1, 100), (6, 36), (8, 16), (8, 8), (2, 32), (1, 64), (2, 16),
+          (8, 20), (12, 16),
           # head widths that are not whole 16-byte pieces: lanes move 8, 4 or 2 bytes
           (3, 10), (2, 50), (4, 12), (5, 7), (2, 63), (1, 126), (6, 36)]
 
