@@ -33,13 +33,15 @@
  *   - a_r multiplies the destination's z_i and a_l the source's z_j: the vector
  *     a of Eq. 3 is [a_r ; a_l] in the order the equation writes z_i || z_j.
  *   - Shapes.  A wavefront covers a head with 64 lanes that each move the largest
- *     piece of 16, 8, 4 (or, for bf16, 2) bytes that divides the head: any head
- *     width D that is a multiple of 4 (fp32) / 8 (bf16) up to 1024 bytes is taken
- *     at full speed, other widths with narrower lane pieces as long as the head
- *     fits 64 of them (fp32: D <= 128 for even D, D <= 64 for odd D; bf16: D <= 256
- *     for D % 4 == 0, D <= 128 for even D, D <= 64 for odd D).  A wider head returns
+ *     piece of 16, 8, 4 (or, for bf16, 2) bytes that divides the head: every head
+ *     width is accepted as long as the head fits 64 such lanes (any D up to 256 that
+ *     is a multiple of 4; else fp32: D <= 128 for even D, D <= 64 for odd D; bf16:
+ *     D <= 128 for even D, D <= 64 for odd D).  A wider head returns
  *     SAR_ERR_UNSUPPORTED.  Rows of several heads are processed as several launches
  *     over groups of heads, rows of the sum/mean calls (any F) over column ranges.
+ *     The fastest kernels take head widths that are a multiple of 4 in layers of
+ *     1, 2, 4, 8 heads or a multiple thereof (4 x 64, 8 x 32, 4 x 32, 2 x 100, ...);
+ *     the results do not depend on which kernel a shape takes.
  *   - A destination with no in-edge at all has out = 0 and L = -inf, and
  *     contributes nothing to any gradient; the mean of an empty set is 0.
  *     A tensor without elements (n_dst = 0, or a block without sources) may be
