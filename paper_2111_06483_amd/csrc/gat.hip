@@ -792,27 +792,27 @@ int lanes_per_head(int D)
     return lph;
 }
 
-// The specialised kernels give every head LPH lanes of 4 values and a launch takes 64/LPH heads.
-// Exact geometry: contiguous rows of 256 values, LPH = D/4 (4..64).  Padded geometry (built for
-// LPH = 8, 16, 32, 64): heads of any width that is a multiple of 4 up to 4 LPH, rows of any stride,
-// the lanes a head does not need staying idle; a layer of more heads runs as several launches over
-// groups of heads.  The gathers are bound by memory, not by lanes, so idle lanes cost little:
-//   at least 3/8 of the lanes busy: faster than the generic kernels in both passes, also over
-//     several launches (4 x 32 on 16 lanes per head, 5.96 -> 3.78 ms per step of the products-sized
-//     share; 16 x 32 in rows of 512, 19.2 -> 14.9 ms; 1 x 100 on 64 lanes, 11.5 -> 5.3 ms);
+// The specialised kernels give every head LPH lanes of 4 values.  Exact geometry: contiguous rows
+// of 256 values, LPH = D/4 (4..64), 64/LPH heads.  Padded geometry (built for LPH = 8, 16, 32, 64):
+// heads of any width that is a multiple of 4 up to 4 LPH, rows of any stride, up to 64/LPH heads per
+// launch; lanes a head does not need, and head groups the launch has no head for, stay idle, and a
+// layer of more heads runs as several launches over groups of heads.  The gathers are bound by
+// memory, not by lanes, so idle lanes cost little:
+//   at least 3/8 of the 64 lanes busy: faster than the generic kernels in both passes, also over
+//     several launches (4 x 32, 5.96 -> 3.8 ms per step of the products-sized share; 16 x 32 in
+//     rows of 512, 19.2 -> 14.9 ms; 1 x 100, 11.5 -> 5.3 ms; 3 x 64 and 6 x 32 on 48 lanes);
 //   fewer ("sparse"): only the backward pass gains, and only when the whole layer is ONE launch
 //     (the generic backward gives every source a wavefront however few its edges: 4 x 16,
 //     3.43 -> 1.83 ms; its forward stays ahead, 0.69 against 0.94 ms; over several launches the
-//     repeated index traffic costs more than it saves: 8 x 8 on 16 lanes, 3 x 64 on 64).
-// Lanes per head for a launch of Hg heads of width D, or 0 if the padded geometry cannot take it.
-int padded_lanes(int Hg, int D)
+//     repeated index traffic costs more than it saves).
+// Lanes per head of the padded geometry for head width D, or 0.
+int padded_lanes(int D)
 {
     const int need = lanes_per_head(D);
-    if (need == 0 || Hg < 1 || Hg > 8 || 64 % Hg != 0) return 0;
-    const int lanes = 64 / Hg;
-    return lanes >= need ? lanes : 0;
+    return need == 0 ? 0 : std::max(8, need);
 }
-bool sparse_lanes(int lanes, int D) { return (D / 4) * 8 < 3 * lanes; }
+// Whether a launch of Hg heads of width D would leave more than 5/8 of the lanes idle.
+bool sparse_launch(int Hg, int D) { return Hg * (D / 4) * 8 < 3 * 64; }
 
 struct FastGeo {
     int lph;     // 0: not applicable
@@ -830,14 +830,15 @@ HeadGroups head_groups(int dtype, int H, int D)
     int hg = std::max<int>(1, 64 * g.piece / D);
     hg = std::min(hg, H);
     while (H % hg != 0) --hg;
-    // heads per launch of the specialised kernels, where they apply (see padded_lanes)
+    // heads per launch of the specialised kernels, where they apply (see padded_lanes): the largest
+    // divisor of H that fits a wavefront
     const int lph = lanes_per_head(D);
     if (lph > 0 && H * lph == 64 && H * D == f256::kF) {
         hg = H;                                   // the exact geometry: all heads in one launch
     } else if (lph > 0) {
-        for (int cand = 8; cand >= 1; cand /= 2) {   // most heads per launch first: most lanes busy
-            if (H % cand != 0 || padded_lanes(cand, D) == 0) continue;
-            if (!sparse_lanes(64 / cand, D) || cand == H) hg = cand;
+        for (int cand = std::min(H, 64 / padded_lanes(D)); cand >= 1; --cand) {
+            if (H % cand != 0) continue;
+            if (!sparse_launch(cand, D) || cand == H) hg = cand;
             break;
         }
     }
@@ -910,10 +911,10 @@ FastGeo fast_geo(int H, int D, int ldz)
     const int lph = lanes_per_head(D);
     if (lph == 0) return FastGeo{0, false, false};
     if (H * lph == 64 && D == 4 * lph && ldz == f256::kF) return FastGeo{lph, false, false};
-    const int lanes = padded_lanes(H, D);
-    if (lanes < 8) return FastGeo{0, false, false};
-    const bool sparse = sparse_lanes(lanes, D);
-    if (sparse && H * D != ldz) return FastGeo{0, false, false};   // sparse groups pay in one launch only
+    const int lanes = padded_lanes(D);
+    if (H < 1 || H * lanes > 64) return FastGeo{0, false, false};
+    const bool sparse = sparse_launch(H, D);
+    if (sparse && H * D != ldz) return FastGeo{0, false, false};   // sparse launches pay only as the single one
     return FastGeo{lanes, true, sparse};
 }
 
@@ -1026,12 +1027,12 @@ int launch_bwd_f256_padded(const BwdArgs& tabs, const BwdScalars& a, unsigned* g
 // da_l[h*D + 4k + x] += sum_w partial[w][(h*LPH + k)*4 + x]: the padded kernels leave their
 // partial sums in lane order (256 slots per workgroup)
 __global__ __launch_bounds__(256) void k_reduce_partials_padded(const float* __restrict__ partial, int n_part,
-                                                                int lph, int D, float* __restrict__ out)
+                                                                int lph, int H, int D, float* __restrict__ out)
 {
     __shared__ float red[256];
     const int slot = blockIdx.x, lane = slot >> 2, x = slot & 3;
     const int h = lane / lph, k = lane % lph;
-    if (4 * k >= D) return;
+    if (h >= H || 4 * k >= D) return;
     float s = 0.f;
     for (int w = threadIdx.x; w < n_part; w += 256) s += partial[(int64_t)w * 256 + slot];
     red[threadIdx.x] = s;
@@ -1147,7 +1148,7 @@ int launch_bwd(const BwdArgs& tabs, BwdScalars& a, float* da_l, hipStream_t st)
                 case 32: SAR_TRY((launch_bwd_f256_padded<T, 32, ALL>(tabs, a, &grid, st))); break;
                 default: SAR_TRY((launch_bwd_f256_padded<T, 64, ALL>(tabs, a, &grid, st))); break;
             }
-            k_reduce_partials_padded<<<256, 256, 0, st>>>(a.partial, (int)grid, geo.lph, a.D, da_l);
+            k_reduce_partials_padded<<<256, 256, 0, st>>>(a.partial, (int)grid, geo.lph, a.H, a.D, da_l);
             SAR_LAUNCH_CHECK();
             return SAR_OK;
         }

@@ -252,10 +252,15 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_fwd_f256(FwdP a, Tabs ta
     __shared__ float part[kWavesPerWG][kWave][6];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int h = lane / LPH, k = lane % LPH;
+    // Padded geometry: a launch of fewer than 64/LPH heads leaves whole head groups without a head.
+    // Such a group reads what the last head reads (valid memory), speaks for no edge and owns no
+    // output: its lanes' `k` matches no slot, so every weight it forms is zero.
+    const int h_pos = lane / LPH, k_pos = lane % LPH;
+    const bool head_ok = !PAD || h_pos < a.H;
+    const int h = head_ok ? h_pos : a.H - 1, k = head_ok ? k_pos : kWave;
     const int ld = PAD ? a.ld : kF, ldh = PAD ? a.ldh : a.H;
-    const int foff = PAD ? h * a.D + 4 * k : lane * 4;
-    const bool on = PAD ? 4 * k < a.D : true;
+    const int foff = PAD ? h * a.D + 4 * k_pos : lane * 4;
+    const bool on = PAD ? head_ok && 4 * k_pos < a.D : true;
     T* outp = static_cast<T*>(a.out);
     float al[4] = {0.f, 0.f, 0.f, 0.f};
     if constexpr (FLY) {
@@ -427,10 +432,15 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_f256(BwdTabs tabs, B
     __shared__ float part[kWavesPerWG][kWave][5];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int h = lane / LPH, k = lane % LPH;
+    // Padded geometry: a launch of fewer than 64/LPH heads leaves whole head groups without a head.
+    // Such a group reads what the last head reads (valid memory), speaks for no edge and owns no
+    // output: its lanes' `k` matches no slot, so every weight it forms is zero.
+    const int h_pos = lane / LPH, k_pos = lane % LPH;
+    const bool head_ok = !PAD || h_pos < a.H;
+    const int h = head_ok ? h_pos : a.H - 1, k = head_ok ? k_pos : kWave;
     const int ld = PAD ? a.ld : kF, ldh = PAD ? a.ldh : a.H;
-    const int foff = PAD ? h * a.D + 4 * k : lane * 4;
-    const bool on = PAD ? 4 * k < a.D : true;
+    const int foff = PAD ? h * a.D + 4 * k_pos : lane * 4;
+    const bool on = PAD ? head_ok && 4 * k_pos < a.D : true;
     const uint32_t mask = ALL ? ((1u << a.tag_shift) - 1u) : 0xffffffffu;
 
     float al[4] = {0.f, 0.f, 0.f, 0.f}, dal[4];
@@ -571,11 +581,14 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_few(BwdTabs tabs, Bw
     __syncthreads();
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int h = lane / LPH, k = lane % LPH;
-    // exact geometry: rows of 256 values; padded: heads of any width D <= 4 LPH inside rows of stride ld
+    // exact geometry: rows of 256 values; padded: heads of any width D <= 4 LPH inside rows of stride
+    // ld, head groups beyond the launch's heads idle (see k_gat_fwd_f256)
+    const int h_pos = lane / LPH, k_pos = lane % LPH;
+    const bool head_ok = !PAD || h_pos < a.H;
+    const int h = head_ok ? h_pos : a.H - 1, k = head_ok ? k_pos : kWave;
     const int ld = PAD ? a.ld : kF, ldh = PAD ? a.ldh : a.H;
-    const int foff = PAD ? h * a.D + 4 * k : lane * 4;
-    const bool on = PAD ? 4 * k < a.D : true;
+    const int foff = PAD ? h * a.D + 4 * k_pos : lane * 4;
+    const bool on = PAD ? head_ok && 4 * k_pos < a.D : true;
     const uint32_t mask = ALL ? ((1u << a.tag_shift) - 1u) : 0xffffffffu;
     const T* Gp = static_cast<const T*>(a.G);
 

@@ -206,6 +206,8 @@ SHAPES = [(4, 16), (1, 4), (4, 64), (8, 32), (2, 100), (3, 12), (1, 256), (2, 12
           # single-launch layers whose backward pass alone takes the specialised kernels
           (4, 32), (2, 64), (1, 128), (16, 32), (1, 100), (6, 36), (8, 16), (8, 8), (2, 32), (1, 64), (2, 16),
           (8, 20), (12, 16),
+          # head counts that leave whole head groups of the padded geometry without a head
+          (3, 64), (6, 32), (5, 8), (7, 8), (3, 32), (5, 40),
           # head widths that are not whole 16-byte pieces: lanes move 8, 4 or 2 bytes
           (3, 10), (2, 50), (4, 12), (5, 7), (2, 63), (1, 126), (6, 36)]
 
