@@ -246,5 +246,5 @@ def test_timed_step_config3_full_size_fp32():
 
 
 def test_timed_step_config4_shape_bf16():
-    """Config 4's layer (16 blocks, GAT 8 x 32, bf16 rows, fp32 accumulation) on a 3.3M-node graph."""
-    check_step("cfg4", 0.03, ("all", "stream"))
+    """Config 4's layer (16 blocks, GAT 8 x 32, bf16 rows, fp32 accumulation) on a 2.2M-node graph."""
+    check_step("cfg4", 0.02, ("all", "stream"))
