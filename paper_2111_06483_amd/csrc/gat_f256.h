@@ -85,6 +85,42 @@ __device__ inline float group_bcast(float v)
     }
 }
 
+// Sums of 8 per-lane values over each group of LPH consecutive lanes, one sum per lane: the lane
+// at position k of its group (k % 8 for LPH > 8) returns the group's sum of c[k % 8].  Eight
+// separate all-reductions would move every value through every step; here the lanes first split
+// the eight values between them while they add (pairs, quads, eights: 4 + 2 + 1 exchanges), and
+// only one value per lane takes the remaining log2(LPH / 8) steps.
+// Measured: a gain from LPH = 32 on, where each all-reduction takes steps through the LDS crossbar
+// (bf16 4 x 128 and 2 x 256: 3 to 10% per pass); within 16 lanes the eight independent DPP chains
+// of the separate all-reductions are as fast or faster.
+constexpr int kScatterSumsFrom = 32;
+constexpr int kQuadReverse = 0x1B;     // quad_perm [3,2,1,0]
+template <int LPH>
+__device__ inline float group_sums8(const float (&c)[8])
+{
+    static_assert(LPH >= 8, "eight lanes share eight sums");
+    const int k = threadIdx.x;           // groups start at multiples of 8: the low bits are the position
+    const bool b0 = k & 1, b1 = k & 2, b2 = k & 4;
+    float v1[4], v2[2];
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {        // the partner (lane ^ 1) takes the values of the other parity
+        const float mine = b0 ? c[2 * m + 1] : c[2 * m], send = b0 ? c[2 * m] : c[2 * m + 1];
+        v1[m] = mine + dpp<kQuadXor1>(send);
+    }
+#pragma unroll
+    for (int n = 0; n < 2; ++n) {        // lane ^ 2
+        const float mine = b1 ? v1[2 * n + 1] : v1[2 * n], send = b1 ? v1[2 * n] : v1[2 * n + 1];
+        v2[n] = mine + dpp<kQuadXor2>(send);
+    }
+    const float mine = b2 ? v2[1] : v2[0], send = b2 ? v2[0] : v2[1];
+    // lane ^ 4 = the mirror image within 8 lanes (lane ^ 7) of the quad's reverse (lane ^ 3)
+    float v = mine + dpp<kQuadReverse>(dpp<kRowHalfMirror>(send));
+    if constexpr (LPH >= 16) v += dpp<kRowRor8>(v);
+    if constexpr (LPH >= 32) v += swizzle<0x401F>(v);   // xor 16
+    if constexpr (LPH >= 64) v += __shfl_xor(v, 32);
+    return v;
+}
+
 template <int N, typename Fn>
 __device__ inline void static_for(Fn&& fn)
 {
@@ -209,15 +245,23 @@ __device__ inline void fwd_chunk(FwdState<LPH>& st, const FwdP& a, const Tabs& t
         float tv = 0.f;
         if constexpr (FLY) {
             // t_j = <a_l, z_j> from the row just gathered; lane k keeps edge k's value
+            float cs[B];
             static_for<B>([&](auto kk) {
                 float v[4];
                 Row4<T>::unpack(raw[decltype(kk)::value], v);
                 float c = al[0] * v[0];
 #pragma unroll
                 for (int x = 1; x < 4; ++x) c = fmaf(al[x], v[x], c);
-                c = group_all<LPH, OpSum>(c);
-                tv = (k == decltype(kk)::value) ? c : tv;
+                cs[decltype(kk)::value] = c;
             });
+            if constexpr (B == 8 && LPH >= kScatterSumsFrom) {
+                tv = group_sums8<LPH>(cs);
+            } else {
+                static_for<B>([&](auto kk) {
+                    const float c = group_all<LPH, OpSum>(cs[decltype(kk)::value]);
+                    tv = (k == decltype(kk)::value) ? c : tv;
+                });
+            }
         } else {
             const uint32_t my = (uint32_t)__shfl((int)mine, k0 + (valid ? k : 0));
             const float* tb = ALL ? tabs.t[my >> a.tag_shift] : a.t;
@@ -400,15 +444,23 @@ __device__ inline void bwd_chunk(BwdAcc4& ac, const BwdP& a, int mine, int cnt, 
         const float4 rec = a.rec[(int64_t)my_i * ldh + h];
         // c_k = <G_i, z_j> per head, reduced over the head's lanes; lane k keeps edge k's value
         float c_mine = 0.f;
+        float cs[B];
         static_for<B>([&](auto kk) {
             float g[4];
             Row4<T>::unpack(raw[decltype(kk)::value], g);
             float c = g[0] * zj[0];
 #pragma unroll
             for (int x = 1; x < 4; ++x) c = fmaf(g[x], zj[x], c);
-            c = group_all<LPH, OpSum>(c);
-            c_mine = (k == decltype(kk)::value) ? c : c_mine;
+            cs[decltype(kk)::value] = c;
         });
+        if constexpr (B == 8 && LPH >= kScatterSumsFrom) {
+            c_mine = group_sums8<LPH>(cs);
+        } else {
+            static_for<B>([&](auto kk) {
+                const float c = group_all<LPH, OpSum>(cs[decltype(kk)::value]);
+                c_mine = (k == decltype(kk)::value) ? c : c_mine;
+            });
+        }
         const float u2 = rec.x + t2;
         const float alpha = valid ? fast_exp2(leaky2(u2, a.slope) - rec.y) : 0.f;
         const float de = alpha * (c_mine - rec.z);
@@ -695,6 +747,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_few(BwdTabs tabs, Bw
             float4 rec = make_float4(0.f, INFINITY, 0.f, 0.f);   // L = +inf gives alpha = 0
             if (my_ok) rec = a.rec[(int64_t)my_i * ldh + h];
             float c_mine = 0.f;
+            float cs[B];
             static_for<B>([&](auto kk) {
                 constexpr int K = decltype(kk)::value;
                 float g[4], zj[4];
@@ -703,9 +756,17 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_few(BwdTabs tabs, Bw
                 float c = g[0] * zj[0];
 #pragma unroll
                 for (int x = 1; x < 4; ++x) c = fmaf(g[x], zj[x], c);
-                c = group_all<LPH, OpSum>(c);
-                c_mine = (k == K) ? c : c_mine;
+                cs[K] = c;
             });
+            if constexpr (B == 8 && LPH >= kScatterSumsFrom) {
+                c_mine = group_sums8<LPH>(cs);
+            } else {
+                static_for<B>([&](auto kk) {
+                    constexpr int K = decltype(kk)::value;
+                    const float c = group_all<LPH, OpSum>(cs[K]);
+                    c_mine = (k == K) ? c : c_mine;
+                });
+            }
             const float u2 = rec.x + t2_mine;
             const float alpha = my_ok ? fast_exp2(leaky2(u2, a.slope) - rec.y) : 0.f;
             const float de = alpha * (c_mine - rec.z);
