@@ -59,6 +59,10 @@ def parse():
                     help="shape of the errors E_{p->q}: compact = one row per source the block touches, the rows "
                          "a worker exchanges (Sec. 3.2); full = one row per source of the partition, zeros "
                          "written where no edge; full-skip = full height, rows without an edge not written")
+    ap.add_argument("--singles", default="auto", choices=["auto", "on", "off"],
+                    help="sources with one edge in their block: walked from the destination's side in the "
+                         "all-blocks backward pass (on), source-major like the others (off), or by the library's "
+                         "rule: listed where they carry at least an eighth of the edges (auto)")
     ap.add_argument("--storage", default="config", choices=["config", "f32", "bf16"],
                     help="storage type of the feature rows; 'config' keeps what the configuration names "
                          "(the headline, config 3, is fp32); accumulation is fp32 either way")
@@ -86,7 +90,8 @@ def parse():
 class Layer:
     """Device state of one worker's GAT layer; methods only call the C ABI."""
 
-    def __init__(self, w, torch, sar, synth, act=0, dst_frac=1.0, errors="compact", stored_error=False):
+    def __init__(self, w, torch, sar, synth, act=0, dst_frac=1.0, errors="compact", stored_error=False,
+                 singles="auto"):
         self.torch, self.sar, self.w, self.act = torch, sar, w, act
         # False: Z_p.backward(E_p) forms the rows of E_p = E_{p->p} + ds (x) a_r inside its two products
         # (sar_linear_bwd_rows); True: sar_gat_bwd_end writes E_p out first (`dZdst`)
@@ -102,6 +107,9 @@ class Layer:
         flags = sar.SAR_BUILD_TRANSPOSE | sar.SAR_BUILD_FUSED | {"compact": sar.SAR_BUILD_COMPACT,
                                                                  "full-skip": sar.SAR_BUILD_SKIP_UNTOUCHED,
                                                                  "full": 0}[errors]
+        # sources of one edge in their block walked from the destination's side: the library's rule
+        # (an eighth of the edges), always, or never
+        flags |= {"auto": 0, "on": sar.SAR_BUILD_SINGLES, "off": sar.SAR_BUILD_NO_SINGLES}[singles]
         self.blocks = sar.sar_blocks_build(w.src, w.dst, w.part, P, p, flags)
         torch.cuda.synchronize()
         self.builder_s = time.perf_counter() - t0
@@ -434,7 +442,7 @@ def time_gat(args, torch, sar, synth, name, steps, warmup, full_report):
     if args.heads and args.head_dim:
         w.H, w.D = args.heads, args.head_dim
     layer = Layer(w, torch, sar, synth, act=sar.SAR_ACT_RELU if args.act == "relu" else sar.SAR_ACT_NONE,
-                  dst_frac=args.dst_frac, errors=args.errors, stored_error=args.stored_error)
+                  dst_frac=args.dst_frac, errors=args.errors, stored_error=args.stored_error, singles=args.singles)
     if full_report:
         calibration_copy(args, torch)
     for _ in range(warmup):
@@ -476,13 +484,17 @@ def time_gat(args, torch, sar, synth, name, steps, warmup, full_report):
     # in stream mode the events bracket P launches; report per launch
     launches = 1 if args.mode == "all" else w.P
     fast = layer.F == 256
+    # sources of one edge in their block that the backward call takes destination-major (exact geometry only)
+    n_singles = sar.sar_blocks_n_singles(layer.blocks) if (fast and args.mode == "all") else 0
     calls = {
         "gat_fwd": {"kernel": ("k_gat_fwd_f256" if fast else "k_gat_fwd_f256 in its padded geometry, or k_gat_fwd, by shape")
                     + (" (all blocks)" if args.mode == "all" else " (per block)"),
                     "avg_ms": fwd_ms, "alg_bytes": alg["gat_fwd"]},
         "gat_bwd": {"kernel": ("k_gat_bwd_f256 + k_gat_bwd_few" if fast
                                else "k_gat_bwd_f256 + k_gat_bwd_few in their padded geometry, or k_gat_bwd, by shape")
+                    + (" + k_gat_bwd_single" if n_singles else "")
                     + ("" if layer.errors != "full" else " + k_bwd_zero_rows"),
+                    "single_edge_sources_destination_major": n_singles,
                     "avg_ms": bwd_ms, "alg_bytes": alg["gat_bwd"],
                     "alg_bytes_full_height": alg["gat_bwd_full_height"]},
     }
@@ -732,8 +744,8 @@ def main():
                      "gather_volume_GBs": d["gather_volume_GBs"],
                      "calls": r["calls"],
                      "note": "the forward launch is one kernel; the backward call is two gather kernels (sources "
-                             "with at least 8 edges one per wavefront, the others several per wavefront); per-kernel durations: "
-                             "profiles/"},
+                             "with at least 8 edges one per wavefront, the others several per wavefront), three where "
+                             "the sources of one edge are taken destination-major; per-kernel durations: profiles/"},
     }
     if not args.no_ceilings:
         row_bytes = layer.F * (2 if w.dtype == torch.bfloat16 else 4)

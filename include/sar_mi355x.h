@@ -96,6 +96,16 @@ typedef enum { SAR_ACT_NONE = 0, SAR_ACT_RELU = 1 } sar_act;
  * receiver adds row r to its row touched[r] (t_rank gives the inverse map).  Needs
  * SAR_BUILD_TRANSPOSE; implies that sources without an edge get nothing written. */
 #define SAR_BUILD_COMPACT 8
+/* Sources that have ONE edge in their block.  The backward pass of Alg. 2 walks a block from its
+ * sources' side; a source of one edge then costs its own row, its error row and a gathered row of
+ * the upstream error with that destination's record.  Walked from the destination's side the same
+ * edge costs the source's row and one write of its error row, and nobody else writes that row.
+ * A handle with TRANSPOSE and FUSED lists those sources destination-major (sar_blocks_singles)
+ * when they carry at least an eighth of the worker's edges, always with SAR_BUILD_SINGLES, never
+ * with SAR_BUILD_NO_SINGLES; sar_gat_bwd_all takes them from that list where it exists.  Results
+ * are the same either way up to the order of fp32 sums. */
+#define SAR_BUILD_SINGLES 16
+#define SAR_BUILD_NO_SINGLES 32
 
 typedef struct sar_blocks sar_blocks_t; /* opaque, library-owned */
 
@@ -139,7 +149,7 @@ typedef struct {
  * the next failing call on the same thread. */
 const char* sar_last_error(void);
 
-/* ABI version of this header (currently 4). */
+/* ABI version of this header (currently 5). */
 int sar_version(void);
 
 /* ------------------------------------------------------------------ blocks
@@ -193,6 +203,17 @@ int sar_blocks_info(const sar_blocks_t* b, int* P, int64_t* n_dst);
 
 /* Fill *v (host struct) with block q's device pointers and sizes. */
 int sar_blocks_get(const sar_blocks_t* b, int q, sar_block_view* v);
+
+/* The handle's destination-major list of the sources that have one edge in their block (Alg. 2
+ * walked from the destination for them; see SAR_BUILD_SINGLES): *n entries, entry e being the edge
+ * into destination dst[e] from source src[e] = (q << *tag_shift) | j, whose row in block q's error
+ * E_{p->q} is row[e] (its rank among the touched sources with SAR_BUILD_COMPACT, else j).  The
+ * order is that of the all-blocks index: ascending destination, inside a destination ascending
+ * block, inside a block ascending source (integer work, bit-exact like the other index arrays).
+ * *n = 0 and null arrays where the list was not built.  Device pointers borrowed from the
+ * handle; any of dst, src, row, tag_shift may be NULL. */
+int sar_blocks_singles(const sar_blocks_t* b, int64_t* n, const int32_t** dst, const uint32_t** src,
+                       const int32_t** row, int* tag_shift);
 
 /* *deg = device int32 [n_dst]: total in-degree |N(i)| over all blocks (Eq. 2). */
 int sar_blocks_degree(const sar_blocks_t* b, const int32_t** deg);

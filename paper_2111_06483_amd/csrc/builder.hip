@@ -31,7 +31,7 @@ int fail(int code, const char* fmt, ...)
 }  // namespace sar
 
 extern "C" const char* sar_last_error(void) { return sar::g_err; }
-extern "C" int sar_version(void) { return 4; }
+extern "C" int sar_version(void) { return 5; }
 
 namespace {
 
@@ -443,6 +443,61 @@ ClassLayout layout_from_hist(const int* hist, int64_t offset, int floor_class)
     return L;
 }
 
+// ------------------------------------- sources of one edge, destination-major
+
+struct SingleTabs {
+    const int32_t* t_indptr[SAR_MAX_BLOCKS];
+    const int32_t* t_rank[SAR_MAX_BLOCKS];   // null: the source's own id is its row
+};
+
+// The entries of the all-blocks index whose source has no other edge in its block, in the order
+// of the index (ascending destination, block after block inside a destination): (destination,
+// tagged source, row of the source in its block's error).  One wavefront per destination row,
+// twice: FILL = false counts a row's entries into cnt[r], FILL = true writes them from off[r] on.
+template <bool FILL>
+__global__ __launch_bounds__(kThreads) void k_single_list(SingleTabs tabs, const int32_t* __restrict__ f_indptr,
+                                                          const uint32_t* __restrict__ f_indices, int64_t n_dst,
+                                                          int tag_shift, int32_t* __restrict__ cnt,
+                                                          const int32_t* __restrict__ off,
+                                                          int32_t* __restrict__ s_dst, uint32_t* __restrict__ s_src,
+                                                          int32_t* __restrict__ s_row)
+{
+    __shared__ const int32_t* ip[SAR_MAX_BLOCKS];
+    __shared__ const int32_t* rk[SAR_MAX_BLOCKS];
+    if (threadIdx.x < SAR_MAX_BLOCKS) {
+        ip[threadIdx.x] = tabs.t_indptr[threadIdx.x];
+        rk[threadIdx.x] = tabs.t_rank[threadIdx.x];
+    }
+    __syncthreads();
+    const int lane = threadIdx.x & 63;
+    const uint32_t mask = (1u << tag_shift) - 1u;
+    const int64_t n_waves = (int64_t)gridDim.x * (kThreads / 64);
+    for (int64_t r = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6); r < n_dst; r += n_waves) {
+        const int beg = f_indptr[r], end = f_indptr[r + 1];
+        int at = FILL ? off[r] : 0;
+        for (int c = beg; c < end; c += 64) {
+            uint32_t id = 0;
+            int q = 0, j = 0;
+            bool single = false;
+            if (c + lane < end) {
+                id = f_indices[c + lane];
+                q = (int)(id >> tag_shift);
+                j = (int)(id & mask);
+                single = ip[q][j + 1] - ip[q][j] == 1;
+            }
+            const unsigned long long votes = __ballot(single);
+            if (FILL && single) {
+                const int mine = at + __popcll(votes & ((1ull << lane) - 1ull));
+                s_dst[mine] = (int32_t)r;
+                s_src[mine] = id;
+                s_row[mine] = rk[q] ? rk[q][j] : j;
+            }
+            at += __popcll(votes);
+        }
+        if (!FILL && lane == 0) cnt[r] = at;
+    }
+}
+
 // --------------------------------------------------- transpose of a block
 
 // One wavefront per listed destination row.
@@ -811,6 +866,42 @@ int derive(sar_blocks* h, hipStream_t st)
             SAR_LAUNCH_CHECK();
         }
         SAR_HIP(hipStreamSynchronize(st));
+
+        // ---- the sources of one edge, listed from their destinations' side (all-blocks backward):
+        // built where they carry at least an eighth of the edges, or on request
+        const int64_t n_single = all_hist[1];
+        const bool want_singles = (h->flags & SAR_BUILD_SINGLES) ||
+                                  (!(h->flags & SAR_BUILD_NO_SINGLES) && n_single * 8 >= nnz_total);
+        if ((h->flags & SAR_BUILD_FUSED) && want_singles && n_single > 0) {
+            SAR_TRY(own(h, &h->s_dst, n_single));
+            SAR_TRY(own(h, &h->s_src, n_single));
+            SAR_TRY(own(h, &h->s_row, n_single));
+            SingleTabs stabs;
+            memset(&stabs, 0, sizeof(stabs));
+            for (int q = 0; q < P; ++q) {
+                stabs.t_indptr[q] = h->blk[q].t_indptr;
+                stabs.t_rank[q] = (h->flags & SAR_BUILD_COMPACT) ? h->blk[q].t_rank : nullptr;
+            }
+            int32_t *s_cnt = nullptr, *s_off = nullptr;
+            SAR_TRY(tmp.alloc(&s_cnt, n_dst + 1));
+            SAR_TRY(tmp.alloc(&s_off, n_dst + 1));
+            SAR_HIP(hipMemsetAsync(s_cnt + n_dst, 0, sizeof(int32_t), st));
+            const unsigned g_list = grid_for(n_dst * 64, kThreads, 1 << 16);
+            k_single_list<false><<<g_list, kThreads, 0, st>>>(stabs, h->f_indptr, h->f_indices, n_dst, h->tag_shift,
+                                                              s_cnt, nullptr, nullptr, nullptr, nullptr);
+            SAR_LAUNCH_CHECK();
+            SAR_TRY(exclusive_scan(s_cnt, s_off, n_dst + 1, st, tmp));
+            int32_t placed = 0;
+            SAR_HIP(hipMemcpyAsync(&placed, s_off + n_dst, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+            SAR_HIP(hipStreamSynchronize(st));
+            if (placed != n_single)
+                return sar::fail(SAR_ERR_STATE, "the all-blocks index lists %d sources of one edge, the transposes %lld",
+                                 placed, (long long)n_single);
+            k_single_list<true><<<g_list, kThreads, 0, st>>>(stabs, h->f_indptr, h->f_indices, n_dst, h->tag_shift,
+                                                             nullptr, s_off, h->s_dst, h->s_src, h->s_row);
+            SAR_LAUNCH_CHECK();
+            h->n_single = n_single;
+        }
     }
     SAR_HIP(hipStreamSynchronize(st));
     return SAR_OK;
@@ -968,7 +1059,8 @@ void destroy(sar_blocks* h)
 }  // namespace
 
 namespace {
-constexpr int kKnownFlags = SAR_BUILD_TRANSPOSE | SAR_BUILD_FUSED | SAR_BUILD_SKIP_UNTOUCHED | SAR_BUILD_COMPACT;
+constexpr int kKnownFlags = SAR_BUILD_TRANSPOSE | SAR_BUILD_FUSED | SAR_BUILD_SKIP_UNTOUCHED | SAR_BUILD_COMPACT |
+                            SAR_BUILD_SINGLES | SAR_BUILD_NO_SINGLES;
 }
 
 extern "C" int sar_blocks_build(const void* src, const void* dst, int idx_bytes, int64_t E,
@@ -1071,6 +1163,18 @@ extern "C" int sar_blocks_info(const sar_blocks_t* b, int* P, int64_t* n_dst)
     SAR_CHECK_ARG(b != nullptr, "handle is null");
     if (P) *P = b->P;
     if (n_dst) *n_dst = b->n_dst;
+    return SAR_OK;
+}
+
+extern "C" int sar_blocks_singles(const sar_blocks_t* b, int64_t* n, const int32_t** dst, const uint32_t** src,
+                                  const int32_t** row, int* tag_shift)
+{
+    SAR_CHECK_ARG(b != nullptr && n != nullptr, "handle or n is null");
+    *n = b->n_single;
+    if (dst) *dst = b->s_dst;
+    if (src) *src = b->s_src;
+    if (row) *row = b->s_row;
+    if (tag_shift) *tag_shift = b->tag_shift;
     return SAR_OK;
 }
 

@@ -306,6 +306,12 @@ struct BwdScalars {
     int64_t n_rows, n_long;
     int64_t n_wide;             // list entries [n_wide, n_rows) have few edges: several sources per wavefront
     int64_t n_touched;          // list entries [n_touched, n_rows) have no edge at all
+    // all-blocks calls on a handle that lists them: the n_single list entries before n_touched are
+    // the sources of ONE edge, also listed destination-major (destination, tagged source, error row)
+    int64_t n_single;
+    const int32_t* s_dst;
+    const uint32_t* s_src;
+    const int32_t* s_row;
     const int64_t* n_src_host;  // host: rows of every block's dZ_q / dt_q (null: unknown)
     int n_blocks;
     const void* G;              // [n_dst,H,D]
@@ -1081,9 +1087,11 @@ int launch_bwd_f256(const BwdArgs& tabs, const BwdScalars& a, unsigned* grid_out
     constexpr int B = LPH >= 8 ? 8 : 4;
     auto wide = f256::k_gat_bwd_f256<T, LPH, B, ALL, false>;
     auto few = f256::k_gat_bwd_few<T, LPH, ALL, false>;
+    auto single = f256::k_gat_bwd_single<T, LPH>;
     constexpr int kPerWave = B / 2;     // sources a wavefront of that kernel takes at once
     static const int resident_wide = resident_workgroups(wide);
     static const int resident_few = resident_workgroups(few);
+    static const int resident_single = resident_workgroups(single);
     f256::BwdTabs t{};
     for (int q = 0; q < SAR_MAX_BLOCKS; ++q) {
         t.t_indptr[q] = tabs.t_indptr[q]; t.t_indices[q] = tabs.t_indices[q];
@@ -1094,8 +1102,12 @@ int launch_bwd_f256(const BwdArgs& tabs, const BwdScalars& a, unsigned* grid_out
     p.rows = a.rows; p.n_rows = a.n_wide; p.n_long = std::min(a.n_long, a.n_wide);
     p.G = a.G; p.rec = a.rec; p.a_l = a.a_l; p.ds = a.ds; p.partial = a.partial;
     p.H = a.H; p.tag_shift = a.tag_shift; p.slope = a.slope;
-    unsigned g_wide = 0, g_few = 0;
+    unsigned g_wide = 0, g_few = 0, g_single = 0;
     const int64_t n_edged = std::max(a.n_wide, std::min(a.n_rows, a.n_touched));
+    // the sources of one edge (the end of the edged part of the list) go destination-major where
+    // the handle lists them that way
+    const int64_t n_pulled = (ALL && a.s_dst && a.n_single <= n_edged - a.n_wide) ? a.n_single : 0;
+    const int64_t n_few_end = n_edged - n_pulled;
     // Where many sources have no edge (a 16-way split leaves 46% of them without one), their 32-byte
     // rows of dt_q scattered through the array cost more to zero one by one than the whole array
     // does in one sweep ahead of the kernels that write the other rows.
@@ -1114,12 +1126,19 @@ int launch_bwd_f256(const BwdArgs& tabs, const BwdScalars& a, unsigned* grid_out
         wide<<<g_wide, kGatherThreads, 0, st>>>(t, p);
         SAR_LAUNCH_CHECK();
     }
-    if (n_edged > a.n_wide) {
+    if (n_few_end > a.n_wide) {
         // the other sources with edges, several per wavefront
-        const int64_t n = n_edged - a.n_wide;
+        const int64_t n = n_few_end - a.n_wide;
         const int64_t per_wg = (int64_t)kPerWave * kWavesPerWG;
         g_few = (unsigned)std::max<int64_t>(1, std::min<int64_t>((n + per_wg - 1) / per_wg, resident_few));
-        few<<<g_few, kGatherThreads, 0, st>>>(t, p, a.n_wide, n_edged, (int)g_wide);
+        few<<<g_few, kGatherThreads, 0, st>>>(t, p, a.n_wide, n_few_end, (int)g_wide);
+        SAR_LAUNCH_CHECK();
+    }
+    if (n_pulled > 0) {
+        const f256::SingleP sp{a.s_dst, a.s_src, a.s_row, n_pulled};
+        const int64_t per_wg = (int64_t)kWave * kWavesPerWG;
+        g_single = (unsigned)std::max<int64_t>(1, std::min<int64_t>((n_pulled + per_wg - 1) / per_wg, resident_single));
+        single<<<g_single, kGatherThreads, 0, st>>>(t, p, sp, (int)(g_wide + g_few));
         SAR_LAUNCH_CHECK();
     }
     if (a.n_rows > n_edged) {
@@ -1129,7 +1148,7 @@ int launch_bwd_f256(const BwdArgs& tabs, const BwdScalars& a, unsigned* grid_out
                                                        a.tag_shift);
         SAR_LAUNCH_CHECK();
     }
-    *grid_out = g_wide + g_few;
+    *grid_out = g_wide + g_few + g_single;
     return SAR_OK;
 }
 
@@ -1173,8 +1192,8 @@ int launch_bwd(const BwdArgs& tabs, BwdScalars& a, float* da_l, hipStream_t st)
     return SAR_OK;
 }
 
-// room for one row of 256 partial sums per workgroup of the two backward kernels of a launch
-size_t workspace_bytes(int F) { return (size_t)2 * kMaxPersistentWGs * F * sizeof(float); }
+// room for one row of 256 partial sums per workgroup of the (up to) three backward kernels of a launch
+size_t workspace_bytes(int F) { return (size_t)3 * kMaxPersistentWGs * F * sizeof(float); }
 
 }  // namespace
 
@@ -1508,6 +1527,10 @@ extern "C" int sar_gat_bwd_all(const sar_blocks_t* b, const void* const* Zq, con
         if (sar::skips_untouched(b->flags)) a.n_rows = b->n_ft_rows;
         a.n_wide = b->n_ft_wide;
         a.n_touched = b->n_ft_rows;
+        a.n_single = b->n_single;
+        a.s_dst = b->s_dst;
+        a.s_src = b->s_src;
+        a.s_row = b->s_row;
         a.n_src_host = n_src_all;
         a.n_blocks = b->P;
         a.n_long = b->n_ft_long;

@@ -38,6 +38,13 @@ __device__ inline float dpp(float v)
 {
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
 }
+template <int CTRL>
+__device__ inline int dpp_i(int v)
+{
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, false);
+}
+constexpr int kRowShr = 0x110;         // + n: lane r of a row of 16 reads lane r - n (0 where there is none)
+constexpr int kRowShl = 0x100;         // + n: lane r reads lane r + n
 constexpr int kQuadXor1 = 0xB1;        // quad_perm [1,0,3,2]
 constexpr int kQuadXor2 = 0x4E;        // quad_perm [2,3,0,1]
 constexpr int kRowHalfMirror = 0x141;
@@ -817,6 +824,174 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_few(BwdTabs tabs, Bw
             float s = 0.f;
             for (int w = 0; w < kWavesPerWG; ++w) s += part[w][lane][x];
             v[x] = s;
+        }
+        store_f32<4>(a.partial + ((int64_t)partial_row0 + blockIdx.x) * kF + lane * 4, v);
+    }
+}
+
+// ------------------------------------------- backward, sources of one edge
+//
+// A source with ONE edge in its block gains nothing from being walked source-major: its own row,
+// its error row, and a gathered row of G with that destination's record, for one edge.  This
+// kernel takes such edges in the order of their DESTINATIONS (a list the builder derives from the
+// all-blocks index): the entries of a destination follow each other, so its row of G and its
+// record come from the caches after the first of them, and what is left per edge is the source's
+// row and one write of its error row -- which nobody else writes, so dZ_q[j] = alpha G_i + du a_l
+// and dt_q[j] = du are plain stores.  Lane geometry and the sub-batch of B gather slots are those
+// of the wide kernel; slot k here is an (edge, source) of its own and lane k of every head group
+// speaks for it.
+struct SingleP {
+    const int32_t* dst;    // [n] destination of the entry's edge
+    const uint32_t* src;   // [n] its source, tagged with the block
+    const int32_t* row;    // [n] row of the source in its block's dZ_q / dt_q
+    int64_t n;
+};
+
+template <typename T, int LPH>
+__global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_single(BwdTabs tabs, BwdP a, SingleP s, int partial_row0)
+{
+    constexpr int B = LPH >= 8 ? 8 : 4;
+    static_assert(B <= LPH, "a sub-batch must fit a head group");
+    __shared__ float part[kWavesPerWG][kWave][4];
+    __shared__ const void* s_Z[SAR_MAX_BLOCKS];
+    __shared__ const float* s_t[SAR_MAX_BLOCKS];
+    __shared__ void* s_dZ[SAR_MAX_BLOCKS];
+    __shared__ float* s_dt[SAR_MAX_BLOCKS];
+    if (threadIdx.x < SAR_MAX_BLOCKS) {
+        s_Z[threadIdx.x] = tabs.Z[threadIdx.x];
+        s_t[threadIdx.x] = tabs.t[threadIdx.x];
+        s_dZ[threadIdx.x] = tabs.dZ[threadIdx.x];
+        s_dt[threadIdx.x] = tabs.dt[threadIdx.x];
+    }
+    __syncthreads();
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int h = lane / LPH, k = lane % LPH, foff = lane * 4;
+    const uint32_t mask = (1u << a.tag_shift) - 1u;
+    const T* Gp = static_cast<const T*>(a.G);
+
+    float al[4], dal[4];
+    load_f32<4>(a.a_l + foff, al);
+#pragma unroll
+    for (int x = 0; x < 4; ++x) dal[x] = 0.f;
+
+    // a wavefront takes 64 entries at a time, one per lane; the next 64 travel meanwhile
+    const int64_t n_chunks = (s.n + kWave - 1) / kWave;
+    const int64_t stride = (int64_t)gridDim.x * kWavesPerWG;
+    struct Entry { int i; uint32_t id; int row; };
+    auto load_entries = [&](int64_t c) {
+        Entry e{0, 0u, 0};
+        const int64_t at = c * kWave + lane;
+        if (c < n_chunks && at < s.n) e = Entry{s.dst[at], s.src[at], s.row[at]};
+        return e;
+    };
+    int64_t c = (int64_t)blockIdx.x * kWavesPerWG + wave;
+    Entry cur = load_entries(c);
+    for (; c < n_chunks; c += stride) {
+        const Entry nxt = load_entries(c + stride);
+        const int cnt = (int)min((int64_t)kWave, s.n - c * kWave);
+        for (int k0 = 0; k0 < cnt; k0 += B) {
+            const int nb = min(B, cnt - k0);
+            int q[B], row[B];
+            typename Row4<T>::Raw rg[B], rz[B];
+            static_for<B>([&](auto kk) {
+                constexpr int K = decltype(kk)::value;
+                const int e = k0 + min(K, nb - 1);
+                const int i = __builtin_amdgcn_readlane(cur.i, e);
+                const uint32_t id = (uint32_t)__builtin_amdgcn_readlane((int)cur.id, e);
+                q[K] = (int)(id >> a.tag_shift);
+                row[K] = __builtin_amdgcn_readlane(cur.row, e);
+                rg[K] = load_lane<T, false>(Gp + (int64_t)i * kF, foff, true);
+                rz[K] = load_lane<T, false>(static_cast<const T*>(s_Z[q[K]]) + (int64_t)(id & mask) * kF, foff, true);
+            });
+            // lane k speaks for slot k
+            const bool valid = k < nb;
+            const int sel = k0 + (valid ? k : 0);
+            const int my_i = __shfl(cur.i, sel);
+            const uint32_t my_id = (uint32_t)__shfl((int)cur.id, sel);
+            const int my_row = __shfl(cur.row, sel);
+            const int my_q = (int)(my_id >> a.tag_shift);
+            const float4 rec = a.rec[(int64_t)my_i * a.H + h];
+            float cs[B], ts[B];
+            static_for<B>([&](auto kk) {
+                constexpr int K = decltype(kk)::value;
+                float g[4], z[4];
+                Row4<T>::unpack(rg[K], g);
+                Row4<T>::unpack(rz[K], z);
+                float cg = g[0] * z[0], ct = al[0] * z[0];
+#pragma unroll
+                for (int x = 1; x < 4; ++x) {
+                    cg = fmaf(g[x], z[x], cg);
+                    ct = fmaf(al[x], z[x], ct);
+                }
+                cs[K] = cg;
+                ts[K] = ct;
+            });
+            float c_mine = 0.f, t_mine = 0.f;
+            if constexpr (B == 8 && LPH >= kScatterSumsFrom) {
+                c_mine = group_sums8<LPH>(cs);
+                t_mine = group_sums8<LPH>(ts);
+            } else {
+                static_for<B>([&](auto kk) {
+                    constexpr int K = decltype(kk)::value;
+                    const float cg = group_all<LPH, OpSum>(cs[K]);
+                    const float ct = group_all<LPH, OpSum>(ts[K]);
+                    c_mine = (k == K) ? cg : c_mine;
+                    t_mine = (k == K) ? ct : t_mine;
+                });
+            }
+            if (valid && s_t[my_q]) t_mine = s_t[my_q][(int64_t)(my_id & mask) * a.H + h];
+            const float u2 = rec.x + t_mine * kLog2e;
+            const float alpha = valid ? fast_exp2(leaky2(u2, a.slope) - rec.y) : 0.f;
+            const float de = alpha * (c_mine - rec.z);
+            const float du = u2 > 0.f ? de : a.slope * de;
+            if (valid) s_dt[my_q][(int64_t)my_row * a.H + h] = du;
+            // ds_i += du: the entries of a destination follow each other, and a frequent destination
+            // fills whole sub-batches: one atomic per run of slots that share the destination
+            // (a running sum along the run, added by its last slot), not one per slot on one address
+            {
+                const int seg = valid ? my_i : -1 - k;
+                float run = du;
+                static_for<3>([&](auto ss) {
+                    constexpr int sh = 1 << decltype(ss)::value;
+                    if constexpr (sh < B) {
+                        const float r_s = dpp<kRowShr + sh>(run);
+                        const int i_s = dpp_i<kRowShr + sh>(seg);
+                        if (k >= sh && i_s == seg) run += r_s;
+                    }
+                });
+                const int next = dpp_i<kRowShl + 1>(seg);
+                if (valid && (k == B - 1 || next != seg)) unsafeAtomicAdd(a.ds + (int64_t)my_i * a.H + h, run);
+            }
+            static_for<B>([&](auto kk) {
+                constexpr int K = decltype(kk)::value;
+                const float ak = group_bcast<LPH, K>(alpha);
+                const float dk = group_bcast<LPH, K>(du);
+                float g[4], z[4], v[4];
+                Row4<T>::unpack(rg[K], g);
+                Row4<T>::unpack(rz[K], z);
+#pragma unroll
+                for (int x = 0; x < 4; ++x) {
+                    v[x] = fmaf(dk, al[x], ak * g[x]);
+                    dal[x] = fmaf(dk, z[x], dal[x]);
+                }
+                if (K < nb) store_lane<T, false>(static_cast<T*>(s_dZ[q[K]]) + (int64_t)row[K] * kF, foff, true, v);
+            });
+        }
+        cur = nxt;
+    }
+
+    // this workgroup's share of da_l
+#pragma unroll
+    for (int x = 0; x < 4; ++x) part[wave][lane][x] = dal[x];
+    __syncthreads();
+    if (wave == 0) {
+        float v[4];
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            float sum = 0.f;
+            for (int w = 0; w < kWavesPerWG; ++w) sum += part[w][lane][x];
+            v[x] = sum;
         }
         store_f32<4>(a.partial + ((int64_t)partial_row0 + blockIdx.x) * kF + lane * 4, v);
     }

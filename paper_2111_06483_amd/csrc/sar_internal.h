@@ -97,5 +97,12 @@ struct sar_blocks {
     // every source with an edge, longest class first.
     uint32_t* ft_rows = nullptr;
     int64_t n_ft_rows = 0, n_ft_long = 0, n_ft_wide = 0;
+    // The sources that have ONE edge in their block (the last n_single entries of ft_rows that
+    // have an edge), listed in the order of that edge's destination: destination, tagged source,
+    // row of the source in its block's error.  Null / 0 where the list was not built.
+    int32_t* s_dst = nullptr;
+    uint32_t* s_src = nullptr;
+    int32_t* s_row = nullptr;
+    int64_t n_single = 0;
     std::vector<void*> owned;      // device allocations freed with the handle
 };

@@ -31,6 +31,8 @@ SAR_BUILD_TRANSPOSE = 1
 SAR_BUILD_FUSED = 2
 SAR_BUILD_SKIP_UNTOUCHED = 4
 SAR_BUILD_COMPACT = 8
+SAR_BUILD_SINGLES = 16
+SAR_BUILD_NO_SINGLES = 32
 
 _c_i64 = ctypes.c_int64
 _c_int = ctypes.c_int
@@ -73,8 +75,8 @@ def lib() -> ctypes.CDLL:
 
 EXPORTS = [
     "sar_last_error", "sar_version",
-    "sar_blocks_build", "sar_blocks_wrap", "sar_blocks_subset", "sar_blocks_info", "sar_blocks_get", "sar_blocks_degree",
-    "sar_blocks_free",
+    "sar_blocks_build", "sar_blocks_wrap", "sar_blocks_subset", "sar_blocks_info", "sar_blocks_get", "sar_blocks_singles",
+    "sar_blocks_degree", "sar_blocks_free",
     "sar_spmm_block", "sar_spmm_end", "sar_spmm_all", "sar_act_bwd", "sar_spmm_bwd_block", "sar_spmm_bwd_all",
     "sar_error_add",
     "sar_gat_scores", "sar_gat_fwd_begin", "sar_gat_fwd_block", "sar_gat_fwd_end", "sar_gat_fwd_all",
@@ -260,6 +262,24 @@ def sar_blocks_subset(b: Blocks, dst_ids: torch.Tensor,
     _check(lib().sar_blocks_subset(b.handle, _ptr(dst_ids), _c_i64(dst_ids.numel()), _c_int(flags), _stream(),
                                    ctypes.byref(h)))
     return Blocks(h, flags=flags)
+
+
+def sar_blocks_n_singles(b: Blocks) -> int:
+    """Length of the handle's list of single-edge sources (0: not built)."""
+    n = _c_i64(0)
+    _check(lib().sar_blocks_singles(b.handle, ctypes.byref(n), None, None, None, None))
+    return int(n.value)
+
+
+def sar_blocks_singles(b: Blocks):
+    """(dst, src, row, tag_shift) of the handle's destination-major list of the sources that have one
+    edge in their block (copies, for inspection); three empty tensors where the list was not built."""
+    n, ts = _c_i64(0), _c_int(0)
+    pd, ps, pr = _vp(None), _vp(None), _vp(None)
+    _check(lib().sar_blocks_singles(b.handle, ctypes.byref(n), ctypes.byref(pd), ctypes.byref(ps), ctypes.byref(pr),
+                                    ctypes.byref(ts)))
+    return (device_array(pd.value, n.value), device_array(ps.value, n.value), device_array(pr.value, n.value),
+            ts.value)
 
 
 def sar_blocks_degree(b: Blocks) -> torch.Tensor:

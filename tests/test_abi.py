@@ -44,7 +44,7 @@ def test_binding_covers_the_header():
 def test_validation_errors_need_no_gpu(lib):
     from paper_2111_06483_amd import sar
     i64 = ctypes.c_int64
-    assert lib.sar_version() == 4
+    assert lib.sar_version() == 5
     rc = lib.sar_gat_scores(None, 0, i64(5), 2, 3, None, None, None)       # any head width is a valid score
     assert rc == sar.SAR_ERR_INVALID_ARG and b"null" in lib.sar_last_error()
     rc = lib.sar_gat_scores(None, 7, i64(5), 2, 4, None, None, None)
@@ -122,7 +122,7 @@ C_CALLER = r"""
 int main(void)
 {
     size_t n = 0;
-    if (sar_version() != 4) return 1;
+    if (sar_version() != 5) return 1;
     if (sar_gat_workspace_bytes(10, 10, 4, 64, &n) != SAR_OK || n == 0) return 2;
     if (sar_spmm_block(NULL, 0, NULL, SAR_F32, 16, NULL, NULL) != SAR_ERR_INVALID_ARG) return 3;
     if (strstr(sar_last_error(), "handle") == NULL) return 4;

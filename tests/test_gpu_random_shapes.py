@@ -99,6 +99,8 @@ def test_random_shape(case):
                                     empty_block=o["empty"])
     want_b, deg = orc.build_blocks(src, dst, part, P, p)
     flags = sar.SAR_BUILD_TRANSPOSE | sar.SAR_BUILD_FUSED | (sar.SAR_BUILD_SKIP_UNTOUCHED if o["skip"] else 0)
+    # sources of one edge in their block: listed destination-major by the library's rule, always, never
+    flags |= (0, sar.SAR_BUILD_SINGLES, sar.SAR_BUILD_NO_SINGLES)[case % 3]
     b = gu.build_blocks(src, dst, part, P, p, flags=flags)
     touched = [np.diff(w.t_indptr) > 0 if o["skip"] else np.ones(w.n_src, bool) for w in want_b]
     for q in range(P):

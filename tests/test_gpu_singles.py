@@ -1,0 +1,192 @@
+"""Sources that have ONE edge in their block, walked from the destination's side (Alg. 2's per-block
+backward for them; SAR_BUILD_SINGLES): the builder's list against the oracle's transposes, bit for
+bit, and the all-blocks attention backward that takes them from that list against the
+oracle, in every shape of the errors (full height, untouched rows skipped, compact).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import sar_oracle as orc
+from tests.helpers import rel_err
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    from paper_2111_06483_amd import sar
+    from tests import gpu_util as gu
+
+TOL = {torch.float32: 1e-4, torch.bfloat16: 2e-2}
+SLOPE = 0.2
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU in this process")
+    sar.lib()
+
+
+def sparse_graph(seed, n_dst, n_src_per_block, P, mean_edges, hub=True):
+    """Partition 0 holds the destinations; every other partition holds sources whose edge counts are
+    Poisson(mean_edges): at 1.0 about a third of them have exactly one edge.  Destinations cite two
+    local nodes each, so no coefficient is exactly 1, and (hub) one destination collects many
+    single-edge sources (its entries fill more than one run of 64)."""
+    rng = np.random.default_rng(seed)
+    src, dst = [], []
+    node = n_dst
+    for q in range(1, P):
+        k = rng.poisson(mean_edges, n_src_per_block)
+        for j in range(n_src_per_block):
+            if k[j]:
+                src += [node + j] * int(k[j])
+                dst += rng.choice(n_dst, int(k[j]), replace=False).tolist()
+        node += n_src_per_block
+    if hub:
+        extra = min(200, n_src_per_block)
+        free = [node - 1 - j for j in range(extra)]
+        have = set(src)
+        free = [v for v in free if v not in have]
+        src += free
+        dst += [3] * len(free)
+    for i in range(n_dst):
+        src += [i, i]
+        dst += [(i + 1) % n_dst, (i + 5) % n_dst]
+    part = np.concatenate([np.zeros(n_dst, np.int32)] + [np.full(n_src_per_block, q, np.int32) for q in range(1, P)])
+    return np.array(src, np.int64), np.array(dst, np.int64), part, rng
+
+
+def expected_singles(blocks, compact):
+    """(destination, block, source, error row) of every source with one edge in its block."""
+    out = []
+    for q, w in enumerate(blocks):
+        tdeg = np.diff(w.t_indptr)
+        rank = np.concatenate([[0], np.cumsum(tdeg > 0)])
+        for j in np.flatnonzero(tdeg == 1):
+            out.append((int(w.t_indices[w.t_indptr[j]]), q, int(j), int(rank[j]) if compact else int(j)))
+    return sorted(out)
+
+
+def listed_singles(b):
+    dst, src, row, shift = sar.sar_blocks_singles(b)
+    src = src.cpu().numpy().astype(np.int64) & 0xffffffff
+    dst, row = dst.cpu().numpy(), row.cpu().numpy()
+    got = [(int(d), int(s >> shift), int(s & ((1 << shift) - 1)), int(r)) for d, s, r in zip(dst, src, row)]
+    return got
+
+
+BASE = 3  # TRANSPOSE | FUSED
+
+
+@pytest.mark.parametrize("extra", [0, 4, 8])    # full height, untouched rows skipped, compact
+def test_list_of_single_edge_sources(extra):
+    src, dst, part, _ = sparse_graph(5, 300, 2500, 4, 1.0)
+    want_b, _ = orc.build_blocks(src, dst, part, 4, 0)
+    want = expected_singles(want_b, compact=bool(extra & sar.SAR_BUILD_COMPACT))
+    assert len(want) > 2000
+    b = gu.build_blocks(src, dst, part, 4, 0, flags=BASE | extra | sar.SAR_BUILD_SINGLES)
+    assert listed_singles(b) == want      # in the order of the all-blocks index: destination, block, source
+    b.close()
+
+
+def test_list_is_built_by_share_of_the_edges():
+    # mean 1.0: about 37% of the sources' edges belong to single-edge sources -> listed unasked
+    src, dst, part, _ = sparse_graph(6, 200, 1500, 3, 1.0, hub=False)
+    want_b, _ = orc.build_blocks(src, dst, part, 3, 0)
+    n_single = len(expected_singles(want_b, False))
+    nnz = sum(w.nnz for w in want_b)
+    assert n_single * 8 >= nnz
+    b = gu.build_blocks(src, dst, part, 3, 0)
+    assert len(listed_singles(b)) == n_single
+    b.close()
+    b = gu.build_blocks(src, dst, part, 3, 0, flags=BASE | sar.SAR_BUILD_NO_SINGLES)
+    assert len(listed_singles(b)) == 0
+    b.close()
+    # mean 5: three sources in a hundred have one edge -> not listed unless asked for
+    src, dst, part, _ = sparse_graph(7, 200, 300, 3, 5.0, hub=False)
+    want_b, _ = orc.build_blocks(src, dst, part, 3, 0)
+    n_single = len(expected_singles(want_b, False))
+    assert 0 < n_single and n_single * 8 < sum(w.nnz for w in want_b)
+    b = gu.build_blocks(src, dst, part, 3, 0)
+    assert len(listed_singles(b)) == 0
+    b.close()
+    b = gu.build_blocks(src, dst, part, 3, 0, flags=BASE | sar.SAR_BUILD_SINGLES)
+    assert len(listed_singles(b)) == n_single
+    b.close()
+    # without the all-blocks index there is nothing to list them from
+    b = gu.build_blocks(src, dst, part, 3, 0, flags=sar.SAR_BUILD_TRANSPOSE | sar.SAR_BUILD_SINGLES)
+    assert len(listed_singles(b)) == 0
+    b.close()
+
+
+# the shapes of the exact 256-wide geometry (4, 8, 16, 32, 64 lanes per head) and two that the list is
+# not used for (padded geometry, generic kernels): the result must be the oracle's either way
+SHAPES = [(torch.float32, 4, 64), (torch.bfloat16, 8, 32), (torch.float32, 16, 16), (torch.bfloat16, 2, 128),
+          (torch.float32, 1, 256), (torch.bfloat16, 4, 64), (torch.float32, 8, 32), (torch.float32, 4, 32),
+          (torch.bfloat16, 3, 10)]
+
+
+@pytest.mark.parametrize("dtype,H,D", SHAPES)
+@pytest.mark.parametrize("extra", [0, 4, 8])
+@pytest.mark.parametrize("mean_edges", [0.7, 2.5])
+def test_backward_takes_single_edge_sources_from_the_list(dtype, H, D, extra, mean_edges):
+    P, F = 4, H * D
+    src, dst, part, rng = sparse_graph(11, 150, 1300, P, mean_edges)
+    want_b, deg = orc.build_blocks(src, dst, part, P, 0)
+    compact = bool(extra & sar.SAR_BUILD_COMPACT)
+    skips = extra != 0
+    b = gu.build_blocks(src, dst, part, P, 0, flags=BASE | extra | sar.SAR_BUILD_SINGLES)
+    n_listed = len(listed_singles(b))
+    assert n_listed == len(expected_singles(want_b, compact)) and n_listed > 300
+    touched = [np.flatnonzero(np.diff(w.t_indptr) > 0) for w in want_b]
+    rows = [t if compact else np.arange(w.n_src) for t, w in zip(touched, want_b)]
+
+    Zs = [torch.from_numpy(rng.standard_normal((w.n_src, H, D)).astype(np.float32)).to(dtype).cuda() for w in want_b]
+    Zdst = Zs[0]
+    bound = np.sqrt(6.0 / (D + 1))
+    a_l = torch.from_numpy(rng.uniform(-bound, bound, (H, D)).astype(np.float32)).cuda()
+    a_r = torch.from_numpy(rng.uniform(-bound, bound, (H, D)).astype(np.float32)).cuda()
+    G = torch.from_numpy(rng.standard_normal((b.n_dst, H, D)).astype(np.float32)).to(dtype).cuda()
+    f64 = lambda t: t.to(torch.float64).cpu().numpy()
+    Z64 = [f64(z) for z in Zs]
+    wf = orc.gat_fwd(want_b, f64(Zdst), Z64, f64(a_l), f64(a_r), SLOPE)
+    wb = orc.gat_bwd(want_b, f64(Zdst), Z64, f64(G), f64(a_l), f64(a_r), SLOPE, wf)
+    fw = gu.gat_fwd_all(b, Zdst, Zs, a_l, a_r, SLOPE)
+    n = b.n_dst
+    work = torch.empty(sar.sar_gat_workspace_bytes(n, 0, H, D) // 4, dtype=torch.float32, device="cuda")
+    tol = TOL[dtype]
+    for fly in (True, False):
+        rec = torch.empty((n, H, 4), dtype=torch.float32, device="cuda")
+        ds = torch.empty((n, H), dtype=torch.float32, device="cuda")
+        sar.sar_gat_bwd_begin(G, fw.out, fw.s, fw.L, rec, ds)
+        da_l = torch.zeros((H, D), dtype=torch.float32, device="cuda")
+        dZs = [torch.full((len(r), H, D), float("nan"), dtype=dtype, device="cuda") for r in rows]
+        dts = [torch.full((len(r), H), float("nan"), dtype=torch.float32, device="cuda") for r in rows]
+        sar.sar_gat_bwd_all(b, Zs, G, None if fly else fw.t, rec, a_l, SLOPE, dZs, dts, ds, da_l, work)
+        for q in range(P):
+            got_z, got_t = f64(dZs[q]), f64(dts[q])
+            if skips and not compact:       # rows of untouched sources are left alone: compare the others
+                got_z, got_t = got_z[touched[q]], got_t[touched[q]]
+                want_z, want_t = wb.dZs[q][touched[q]], wb.dt[q][touched[q]]
+            else:
+                want_z, want_t = wb.dZs[q][rows[q]], wb.dt[q][rows[q]]
+            assert not np.isnan(got_z).any() and not np.isnan(got_t).any(), (fly, q)
+            assert rel_err(got_z, want_z) < tol, (fly, q)
+            assert rel_err(got_t, want_t) < tol, (fly, q)
+        assert rel_err(f64(ds), wb.ds) < tol, fly
+        assert rel_err(f64(da_l), wb.da_l) < tol, fly
+    b.close()
+
+
+def test_restricted_handle_lists_its_own_single_edge_sources():
+    """A handle restricted to some destinations has other single-edge sources than the full one."""
+    src, dst, part, rng = sparse_graph(13, 200, 1500, 3, 2.0)
+    want_full, _ = orc.build_blocks(src, dst, part, 3, 0)
+    ids = np.sort(rng.choice(200, 90, replace=False)).astype(np.int32)
+    want_sub, _ = orc.subset_blocks(want_full, ids)
+    b = gu.build_blocks(src, dst, part, 3, 0, flags=BASE | sar.SAR_BUILD_SINGLES)
+    sub = sar.sar_blocks_subset(b, torch.from_numpy(ids).cuda(), flags=BASE | sar.SAR_BUILD_COMPACT | sar.SAR_BUILD_SINGLES)
+    assert listed_singles(sub) == expected_singles(want_sub, True)
+    assert listed_singles(b) == expected_singles(want_full, False)
+    sub.close()
+    b.close()
