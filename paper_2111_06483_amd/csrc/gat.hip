@@ -1000,8 +1000,10 @@ int launch_bwd_f256_padded(const BwdArgs& tabs, const BwdScalars& a, unsigned* g
     constexpr int B = 8;
     auto wide = f256::k_gat_bwd_f256<T, LPH, B, ALL, true>;
     auto few = f256::k_gat_bwd_few<T, LPH, ALL, true>;
+    auto single = f256::k_gat_bwd_single<T, LPH, true>;
     static const int resident_wide = resident_workgroups(wide);
     static const int resident_few = resident_workgroups(few);
+    static const int resident_single = resident_workgroups(single);
     f256::BwdTabs t{};
     for (int q = 0; q < SAR_MAX_BLOCKS; ++q) {
         t.t_indptr[q] = tabs.t_indptr[q]; t.t_indices[q] = tabs.t_indices[q];
@@ -1013,20 +1015,35 @@ int launch_bwd_f256_padded(const BwdArgs& tabs, const BwdScalars& a, unsigned* g
     p.G = a.G; p.rec = a.rec; p.a_l = a.a_l; p.ds = a.ds; p.partial = a.partial;
     p.H = a.H; p.tag_shift = a.tag_shift; p.slope = a.slope;
     p.ld = a.ldz; p.ldh = a.ldh; p.D = a.D;
-    unsigned g_wide = 0, g_few = 0;
+    unsigned g_wide = 0, g_few = 0, g_single = 0;
     if (a.n_wide > 0) {
         g_wide = persistent_grid_for(p.n_rows, p.n_long, resident_wide);
         wide<<<g_wide, kGatherThreads, 0, st>>>(t, p);
         SAR_LAUNCH_CHECK();
     }
-    if (a.n_rows > a.n_wide) {
-        const int64_t n = a.n_rows - a.n_wide;
-        const int64_t per_wg = (int64_t)(B / 2) * kWavesPerWG;
-        g_few = (unsigned)std::max<int64_t>(1, std::min<int64_t>((n + per_wg - 1) / per_wg, resident_few));
-        few<<<g_few, kGatherThreads, 0, st>>>(t, p, a.n_wide, a.n_rows, (int)g_wide);
+    // The sources of one edge go destination-major where the handle lists them that way.  In the
+    // work list they sit between the other few-edge sources and the ones without an edge, so the
+    // few-edges kernel takes the list in two pieces around them.
+    const int64_t n_edged = std::max(a.n_wide, std::min(a.n_rows, a.n_touched));
+    const int64_t n_pulled = (ALL && a.s_dst && a.n_single <= n_edged - a.n_wide) ? a.n_single : 0;
+    const int64_t per_wg = (int64_t)(B / 2) * kWavesPerWG;
+    const int64_t piece[2][2] = {{a.n_wide, n_pulled ? n_edged - n_pulled : a.n_rows}, {n_edged, n_pulled ? a.n_rows : n_edged}};
+    for (int k = 0; k < 2; ++k) {
+        const int64_t n = piece[k][1] - piece[k][0];
+        if (n <= 0) continue;
+        const unsigned g = (unsigned)std::max<int64_t>(1, std::min<int64_t>((n + per_wg - 1) / per_wg, resident_few));
+        few<<<g, kGatherThreads, 0, st>>>(t, p, piece[k][0], piece[k][1], (int)(g_wide + g_few));
+        SAR_LAUNCH_CHECK();
+        g_few += g;
+    }
+    if (n_pulled > 0) {
+        const f256::SingleP sp{a.s_dst, a.s_src, a.s_row, n_pulled};
+        const int64_t per_wg_s = (int64_t)kWave * kWavesPerWG;
+        g_single = (unsigned)std::max<int64_t>(1, std::min<int64_t>((n_pulled + per_wg_s - 1) / per_wg_s, resident_single));
+        single<<<g_single, kGatherThreads, 0, st>>>(t, p, sp, (int)(g_wide + g_few));
         SAR_LAUNCH_CHECK();
     }
-    *grid_out = g_wide + g_few;
+    *grid_out = g_wide + g_few + g_single;
     return SAR_OK;
 }
 
@@ -1087,7 +1104,7 @@ int launch_bwd_f256(const BwdArgs& tabs, const BwdScalars& a, unsigned* grid_out
     constexpr int B = LPH >= 8 ? 8 : 4;
     auto wide = f256::k_gat_bwd_f256<T, LPH, B, ALL, false>;
     auto few = f256::k_gat_bwd_few<T, LPH, ALL, false>;
-    auto single = f256::k_gat_bwd_single<T, LPH>;
+    auto single = f256::k_gat_bwd_single<T, LPH, false>;
     constexpr int kPerWave = B / 2;     // sources a wavefront of that kernel takes at once
     static const int resident_wide = resident_workgroups(wide);
     static const int resident_few = resident_workgroups(few);
@@ -1192,8 +1209,8 @@ int launch_bwd(const BwdArgs& tabs, BwdScalars& a, float* da_l, hipStream_t st)
     return SAR_OK;
 }
 
-// room for one row of 256 partial sums per workgroup of the (up to) three backward kernels of a launch
-size_t workspace_bytes(int F) { return (size_t)3 * kMaxPersistentWGs * F * sizeof(float); }
+// room for one row of 256 partial sums per workgroup of the (up to) four backward launches of a call
+size_t workspace_bytes(int F) { return (size_t)4 * kMaxPersistentWGs * F * sizeof(float); }
 
 }  // namespace
 

@@ -847,7 +847,7 @@ struct SingleP {
     int64_t n;
 };
 
-template <typename T, int LPH>
+template <typename T, int LPH, bool PAD>
 __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_single(BwdTabs tabs, BwdP a, SingleP s, int partial_row0)
 {
     constexpr int B = LPH >= 8 ? 8 : 4;
@@ -866,12 +866,19 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_single(BwdTabs tabs,
     __syncthreads();
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int h = lane / LPH, k = lane % LPH, foff = lane * 4;
+    // exact geometry: rows of 256 values; padded: heads of any width D <= 4 LPH inside rows of stride
+    // ld, head groups beyond the launch's heads idle (see k_gat_fwd_f256)
+    const int h_pos = lane / LPH, k_pos = lane % LPH;
+    const bool head_ok = !PAD || h_pos < a.H;
+    const int h = head_ok ? h_pos : a.H - 1, k = head_ok ? k_pos : kWave;
+    const int ld = PAD ? a.ld : kF, ldh = PAD ? a.ldh : a.H;
+    const int foff = PAD ? h * a.D + 4 * k_pos : lane * 4;
+    const bool on = PAD ? head_ok && 4 * k_pos < a.D : true;
     const uint32_t mask = (1u << a.tag_shift) - 1u;
     const T* Gp = static_cast<const T*>(a.G);
 
-    float al[4], dal[4];
-    load_f32<4>(a.a_l + foff, al);
+    float al[4] = {0.f, 0.f, 0.f, 0.f}, dal[4];
+    if (on) load_f32<4>(a.a_l + foff, al);
 #pragma unroll
     for (int x = 0; x < 4; ++x) dal[x] = 0.f;
 
@@ -901,8 +908,8 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_single(BwdTabs tabs,
                 const uint32_t id = (uint32_t)__builtin_amdgcn_readlane((int)cur.id, e);
                 q[K] = (int)(id >> a.tag_shift);
                 row[K] = __builtin_amdgcn_readlane(cur.row, e);
-                rg[K] = load_lane<T, false>(Gp + (int64_t)i * kF, foff, true);
-                rz[K] = load_lane<T, false>(static_cast<const T*>(s_Z[q[K]]) + (int64_t)(id & mask) * kF, foff, true);
+                rg[K] = load_lane<T, PAD>(Gp + (int64_t)i * ld, foff, on);
+                rz[K] = load_lane<T, PAD>(static_cast<const T*>(s_Z[q[K]]) + (int64_t)(id & mask) * ld, foff, on);
             });
             // lane k speaks for slot k
             const bool valid = k < nb;
@@ -911,7 +918,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_single(BwdTabs tabs,
             const uint32_t my_id = (uint32_t)__shfl((int)cur.id, sel);
             const int my_row = __shfl(cur.row, sel);
             const int my_q = (int)(my_id >> a.tag_shift);
-            const float4 rec = a.rec[(int64_t)my_i * a.H + h];
+            const float4 rec = a.rec[(int64_t)my_i * ldh + h];
             float cs[B], ts[B];
             static_for<B>([&](auto kk) {
                 constexpr int K = decltype(kk)::value;
@@ -940,12 +947,12 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_single(BwdTabs tabs,
                     t_mine = (k == K) ? ct : t_mine;
                 });
             }
-            if (valid && s_t[my_q]) t_mine = s_t[my_q][(int64_t)(my_id & mask) * a.H + h];
+            if (valid && s_t[my_q]) t_mine = s_t[my_q][(int64_t)(my_id & mask) * ldh + h];
             const float u2 = rec.x + t_mine * kLog2e;
             const float alpha = valid ? fast_exp2(leaky2(u2, a.slope) - rec.y) : 0.f;
             const float de = alpha * (c_mine - rec.z);
             const float du = u2 > 0.f ? de : a.slope * de;
-            if (valid) s_dt[my_q][(int64_t)my_row * a.H + h] = du;
+            if (valid) s_dt[my_q][(int64_t)my_row * ldh + h] = du;
             // ds_i += du: the entries of a destination follow each other, and a frequent destination
             // fills whole sub-batches: one atomic per run of slots that share the destination
             // (a running sum along the run, added by its last slot), not one per slot on one address
@@ -961,7 +968,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_single(BwdTabs tabs,
                     }
                 });
                 const int next = dpp_i<kRowShl + 1>(seg);
-                if (valid && (k == B - 1 || next != seg)) unsafeAtomicAdd(a.ds + (int64_t)my_i * a.H + h, run);
+                if (valid && (k == B - 1 || next != seg)) unsafeAtomicAdd(a.ds + (int64_t)my_i * ldh + h, run);
             }
             static_for<B>([&](auto kk) {
                 constexpr int K = decltype(kk)::value;
@@ -975,7 +982,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_single(BwdTabs tabs,
                     v[x] = fmaf(dk, al[x], ak * g[x]);
                     dal[x] = fmaf(dk, z[x], dal[x]);
                 }
-                if (K < nb) store_lane<T, false>(static_cast<T*>(s_dZ[q[K]]) + (int64_t)row[K] * kF, foff, true, v);
+                if (K < nb) store_lane<T, PAD>(static_cast<T*>(s_dZ[q[K]]) + (int64_t)row[K] * ld, foff, on, v);
             });
         }
         cur = nxt;

@@ -119,10 +119,13 @@ def test_list_is_built_by_share_of_the_edges():
     b.close()
 
 
-# the shapes of the exact 256-wide geometry (4, 8, 16, 32, 64 lanes per head) and two that the list is
-# not used for (padded geometry, generic kernels): the result must be the oracle's either way
+# the shapes of the exact 256-wide geometry (4, 8, 16, 32, 64 lanes per head), shapes of the padded one
+# (idle lanes, several launches, head groups without a head), and one the list is not used for (generic
+# kernels): the result must be the oracle's either way
 SHAPES = [(torch.float32, 4, 64), (torch.bfloat16, 8, 32), (torch.float32, 16, 16), (torch.bfloat16, 2, 128),
-          (torch.float32, 1, 256), (torch.bfloat16, 4, 64), (torch.float32, 8, 32), (torch.float32, 4, 32),
+          (torch.float32, 1, 256), (torch.bfloat16, 4, 64), (torch.float32, 8, 32),
+          (torch.float32, 4, 32), (torch.bfloat16, 2, 100), (torch.float32, 8, 64), (torch.bfloat16, 3, 64),
+          (torch.float32, 1, 100), (torch.bfloat16, 8, 16),
           (torch.bfloat16, 3, 10)]
 
 
