@@ -133,7 +133,7 @@ SHAPES = [(torch.float32, 4, 64), (torch.bfloat16, 8, 32), (torch.float32, 16, 1
 @pytest.mark.parametrize("extra", [0, 4, 8])
 @pytest.mark.parametrize("mean_edges", [0.7, 2.5])
 def test_backward_takes_single_edge_sources_from_the_list(dtype, H, D, extra, mean_edges):
-    P, F = 4, H * D
+    P = 4
     src, dst, part, rng = sparse_graph(11, 150, 1300, P, mean_edges)
     want_b, deg = orc.build_blocks(src, dst, part, P, 0)
     compact = bool(extra & sar.SAR_BUILD_COMPACT)
