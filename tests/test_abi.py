@@ -87,6 +87,9 @@ def test_validation_errors_need_no_gpu(lib):
     assert rc == sar.SAR_ERR_INVALID_ARG and b"handle" in lib.sar_last_error()
     rc = lib.sar_blocks_subset(None, None, i64(0), 0, None, ctypes.byref(h))
     assert rc == sar.SAR_ERR_INVALID_ARG and b"handle" in lib.sar_last_error()
+    cnt = i64(7)
+    rc = lib.sar_blocks_singles(None, ctypes.byref(cnt), None, None, None, None)
+    assert rc == sar.SAR_ERR_INVALID_ARG and b"handle" in lib.sar_last_error()
     part = (ctypes.c_int32 * 1)(0)       # only its being non-null is looked at before the flags
     rc = lib.sar_blocks_build(None, None, 4, i64(0), part, i64(1), 1, 0, 64, None, ctypes.byref(h))
     assert rc == sar.SAR_ERR_INVALID_ARG and b"flags" in lib.sar_last_error()
