@@ -59,6 +59,9 @@ def parse():
                     help="shape of the errors E_{p->q}: compact = one row per source the block touches, the rows "
                          "a worker exchanges (Sec. 3.2); full = one row per source of the partition, zeros "
                          "written where no edge; full-skip = full height, rows without an edge not written")
+    ap.add_argument("--store-dt", action="store_true",
+                    help="also write the per-source score gradients dt_q (an intermediate of the backward kernels "
+                         "that nothing downstream reads; 32 scattered bytes per source row at 8 heads)")
     ap.add_argument("--singles", default="auto", choices=["auto", "on", "off"],
                     help="sources with one edge in their block: walked from the destination's side in the "
                          "all-blocks backward pass (on), source-major like the others (off), or by the library's "
@@ -91,7 +94,7 @@ class Layer:
     """Device state of one worker's GAT layer; methods only call the C ABI."""
 
     def __init__(self, w, torch, sar, synth, act=0, dst_frac=1.0, errors="compact", stored_error=False,
-                 singles="auto"):
+                 singles="auto", store_dt=False):
         self.torch, self.sar, self.w, self.act = torch, sar, w, act
         # False: Z_p.backward(E_p) forms the rows of E_p = E_{p->p} + ds (x) a_r inside its two products
         # (sar_linear_bwd_rows); True: sar_gat_bwd_end writes E_p out first (`dZdst`)
@@ -160,7 +163,9 @@ class Layer:
         # full-skip handle never writes stay zero
         err_rows = [int(v.n_t_rows) if self.compact else int(v.n_src) for v in self.views]
         self.dZs = [torch.zeros((r, H, D), dtype=w.dtype, device=dev) for r in err_rows]
-        self.dts = [torch.zeros((r, H), **f32) for r in err_rows]
+        # dt_q[j] = sum_i du is an intermediate of the backward kernels (dt_q[j] a_l goes into dZ_q, the sum
+        # of dt_q[j] z_j into da_l inside them); it is written out only on request
+        self.dts = [torch.zeros((r, H), **f32) for r in err_rows] if store_dt else None
         self.dZdst = torch.empty((n, H, D), dtype=w.dtype, device=dev) if stored_error else None
         # the parameter gradients accumulate over blocks and calls: one buffer, zeroed by one fill per step
         self.grads = torch.zeros(2 * H * D + self.W.numel(), **f32)
@@ -205,12 +210,13 @@ class Layer:
         self.grads.zero_()
         mark("bwd0")
         if mode == "all":
-            sar.sar_gat_bwd_all(self.blocks, Zs, G, None, self.rec, self.a_l, w.slope, self.dZs, self.dts,
+            sar.sar_gat_bwd_all(self.blocks, Zs, G, None, self.rec, self.a_l, w.slope, self.dZs,
+                                self.dts,
                                 self.ds, self.da_l, self.work)
         else:
             for q in range(P):
                 sar.sar_gat_bwd_block(self.blocks, q, Zs[q], G, None, self.rec, self.a_l, w.slope,
-                                      self.dZs[q], self.dts[q], self.ds, self.da_l, self.work)
+                                      self.dZs[q], self.dts[q] if self.dts else None, self.ds, self.da_l, self.work)
         mark("bwd1")
         # E_p = E_{p->p} + destination-score term: everything this worker itself produced for its rows
         own = None if self.subset else self.dZs[p]
@@ -249,11 +255,11 @@ class Layer:
           forward   tagged index 4E, row offsets and launch list 8 n_p, every touched source row
                     once U F fb, per destination s read, out and L written;
           backward  transposed index 4E and its offsets 4 n_s, work list and rank 8U, every touched
-                    source row read once (the rematerialisation) U F fb, its error row and dt
-                    written once U (F fb + 4H), per touched destination G and the 16-byte record
-                    read once per head and ds updated.
+                    source row read once (the rematerialisation) U F fb, its error row written once
+                    U F fb (and U 4H for dt where it is written out), per touched destination G and
+                    the 16-byte record read once per head and ds updated.
         `full_height` adds the zero rows of the sources without an edge that a full-height E_{p->q}
-        also writes ((n_s - U)(F fb + 4H)); the method itself has no such rows (Sec. 3.2)."""
+        also writes ((n_s - U) F fb, and 4H each for dt); the method itself has no such rows (Sec. 3.2)."""
         torch = self.torch
         fb = 2 if self.w.dtype == torch.bfloat16 else 4
         F, H, n, E = self.F, self.H, self.n, self.E
@@ -261,9 +267,10 @@ class Layer:
         n_s = sum(int(v.n_src) for v in self.views)
         dst_rows = min(E, n)
         fwd = 4 * E + 8 * n + U * F * fb + n * (4 * H + F * fb + 4 * H)
-        bwd = (4 * E + 4 * (n_s + self.P) + 8 * U + U * F * fb + U * (F * fb + 4 * H)
+        dt_b = 4 * H if self.dts is not None else 0
+        bwd = (4 * E + 4 * (n_s + self.P) + 8 * U + U * F * fb + U * (F * fb + dt_b)
                + dst_rows * (F * fb + 16 * H + 8 * H))
-        return {"gat_fwd": fwd, "gat_bwd": bwd, "gat_bwd_full_height": bwd + (n_s - U) * (F * fb + 4 * H),
+        return {"gat_fwd": fwd, "gat_bwd": bwd, "gat_bwd_full_height": bwd + (n_s - U) * (F * fb + dt_b),
                 "touched_source_rows": U, "source_rows": n_s}
 
 
@@ -442,7 +449,8 @@ def time_gat(args, torch, sar, synth, name, steps, warmup, full_report):
     if args.heads and args.head_dim:
         w.H, w.D = args.heads, args.head_dim
     layer = Layer(w, torch, sar, synth, act=sar.SAR_ACT_RELU if args.act == "relu" else sar.SAR_ACT_NONE,
-                  dst_frac=args.dst_frac, errors=args.errors, stored_error=args.stored_error, singles=args.singles)
+                  dst_frac=args.dst_frac, errors=args.errors, stored_error=args.stored_error, singles=args.singles,
+                  store_dt=args.store_dt)
     if full_report:
         calibration_copy(args, torch)
     for _ in range(warmup):
@@ -728,7 +736,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": r["workload"], "mode": args.mode, "scale": args.scale, "act": args.act,
                    "dst_frac": args.dst_frac, "errors": args.errors,
-                   "own_error_rows": "stored before Z_p.backward" if args.stored_error else "formed inside Z_p.backward"},
+                   "own_error_rows": "stored before Z_p.backward" if args.stored_error else "formed inside Z_p.backward",
+                   "dt_q": "written out" if args.store_dt else "not stored (an intermediate of the fused backward kernels)"},
         "phases_ms": r["phases_ms"],
         "aggregation_only_edges_per_s": r["aggregation_only_edges_per_s"],
         "builder_s": r["builder_s"],

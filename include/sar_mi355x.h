@@ -347,7 +347,9 @@ int sar_gat_bwd_begin(const void* G, const void* out, const float* s, const floa
  * atomics.  rec from sar_gat_bwd_begin; tq may be NULL, then t_j = <a_l, z_j> is
  * formed from the row the wavefront owns; a_l 16-byte aligned; work: scratch of
  * at least sar_gat_workspace_bytes, 16-byte aligned.  On a SAR_BUILD_COMPACT handle dZq and
- * dtq have n_t_rows rows, row r for source touched[r]; Zq and tq stay full height. */
+ * dtq have n_t_rows rows, row r for source touched[r]; Zq and tq stay full height.
+ * dtq may be NULL: the per-source sums are an intermediate (both of their uses, dtq[j] a_l in
+ * dZq and the sum into da_l, happen inside the kernel) and are then not written. */
 int sar_gat_bwd_block(const sar_blocks_t* b, int q, const void* Zq, const void* G, const float* tq,
                       const float* rec, const float* a_l, int dtype, int H, int D, float slope,
                       void* dZq, float* dtq, float* ds, float* da_l, void* work, size_t work_bytes,
@@ -355,7 +357,7 @@ int sar_gat_bwd_block(const sar_blocks_t* b, int q, const void* Zq, const void* 
 
 /* All P blocks of Alg. 2's loop in one launch (same results as P
  * sar_gat_bwd_block calls).  Zq, tq, dZq, dtq: host arrays [P] of device
- * pointers.  Needs SAR_BUILD_TRANSPOSE. */
+ * pointers; dtq may be NULL as a whole (see sar_gat_bwd_block).  Needs SAR_BUILD_TRANSPOSE. */
 int sar_gat_bwd_all(const sar_blocks_t* b, const void* const* Zq, const void* G,
                     const float* const* tq, const float* rec, const float* a_l, int dtype, int H,
                     int D, float slope, void* const* dZq, float* const* dtq, float* ds, float* da_l,

@@ -435,7 +435,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd(BwdArgs tabs, BwdSca
             dal[x] = fmaf(ac.dt, zj[x], dal[x]);
         }
         Vec<T>::store(static_cast<T*>(tabs.dZ[q]) + jo * a.ldz + lm.gl * VEC, v);
-        if ((lm.gl % lm.lph) == 0) tabs.dt[q][jo * a.ldh + lm.h] = ac.dt;
+        if ((lm.gl % lm.lph) == 0 && tabs.dt[q]) tabs.dt[q][jo * a.ldh + lm.h] = ac.dt;
     };
 
     for (int64_t r = blockIdx.x; r < a.n_long; r += gridDim.x) {
@@ -1089,7 +1089,7 @@ __global__ __launch_bounds__(256) void k_bwd_zero_rows(f256::BwdTabs tabs, const
         const int q = ALL ? (int)(id >> tag_shift) : 0;
         const int64_t j = (int64_t)(id & mask);
         reinterpret_cast<uint4*>(static_cast<T*>(s_dZ[q]) + j * f256::kF)[piece] = make_uint4(0u, 0u, 0u, 0u);
-        if (piece < H) s_dt[q][j * H + piece] = 0.f;
+        if (piece < H && s_dt[q]) s_dt[q][j * H + piece] = 0.f;
     }
 }
 
@@ -1475,7 +1475,7 @@ extern "C" int sar_gat_bwd_block(const sar_blocks_t* b, int q, const void* Zq, c
     SAR_CHECK_ARG(q >= 0 && q < b->P, "block %d out of range [0,%d)", q, b->P);
     const sar::Block& k = b->blk[q];
     if (k.n_src == 0 || (sar::skips_untouched(b->flags) && k.n_t_rows == 0)) return SAR_OK;
-    SAR_CHECK_ARG(Zq && dZq && dtq, "a tensor argument is null");
+    SAR_CHECK_ARG(Zq && dZq, "a tensor argument is null");
     SAR_CHECK_ARG(aligned16(Zq) && aligned16(dZq), "Zq and dZq must be 16-byte aligned");
     hipStream_t st = sar::as_stream(stream);
     const HeadGroups hg = head_groups(dtype, H, D);
@@ -1487,7 +1487,7 @@ extern "C" int sar_gat_bwd_block(const sar_blocks_t* b, int q, const void* Zq, c
         tabs.Z[0] = shift(Zq, f0 * hg.fb);
         tabs.t[0] = tq ? tq + h0 : nullptr;
         tabs.dZ[0] = shift(dZq, f0 * hg.fb);
-        tabs.dt[0] = dtq + h0;
+        tabs.dt[0] = dtq ? dtq + h0 : nullptr;
         tabs.rank[0] = (b->flags & SAR_BUILD_COMPACT) ? k.t_rank : nullptr;
         BwdScalars a{};
         a.rows = reinterpret_cast<const uint32_t*>(k.t_rows);
@@ -1510,14 +1510,14 @@ extern "C" int sar_gat_bwd_all(const sar_blocks_t* b, const void* const* Zq, con
                                void* work, size_t work_bytes, void* stream)
 {
     SAR_TRY(bwd_common_checks(b, dtype, H, D, G, rec, a_l, ds, da_l, work, work_bytes));
-    SAR_CHECK_ARG(Zq && dZq && dtq, "a pointer table is null");
+    SAR_CHECK_ARG(Zq && dZq, "a pointer table is null");
     if (b->P > SAR_MAX_BLOCKS)
         return sar::fail(SAR_ERR_UNSUPPORTED, "an all-blocks call takes at most %d blocks, the handle has %d: use the "
                          "per-block calls", SAR_MAX_BLOCKS, b->P);
     hipStream_t st = sar::as_stream(stream);
     for (int q = 0; q < b->P; ++q) {
         if (b->blk[q].n_src == 0 || (sar::skips_untouched(b->flags) && b->blk[q].n_t_rows == 0)) continue;
-        SAR_CHECK_ARG(Zq[q] && (!tq || tq[q]) && dZq[q] && dtq[q], "a tensor of block %d is null", q);
+        SAR_CHECK_ARG(Zq[q] && (!tq || tq[q]) && dZq[q] && (!dtq || dtq[q]), "a tensor of block %d is null", q);
         SAR_CHECK_ARG(aligned16(Zq[q]) && aligned16(dZq[q]), "Zq[%d] and dZq[%d] must be 16-byte aligned", q, q);
     }
     const HeadGroups hg = head_groups(dtype, H, D);
@@ -1534,7 +1534,7 @@ extern "C" int sar_gat_bwd_all(const sar_blocks_t* b, const void* const* Zq, con
             tabs.Z[q] = shift(Zq[q], f0 * hg.fb);
             tabs.t[q] = tq ? tq[q] + h0 : nullptr;
             tabs.dZ[q] = shift(dZq[q], f0 * hg.fb);
-            tabs.dt[q] = dtq[q] + h0;
+            tabs.dt[q] = dtq ? dtq[q] + h0 : nullptr;
             tabs.rank[q] = (b->flags & SAR_BUILD_COMPACT) ? k.t_rank : nullptr;
         }
         BwdScalars a{};

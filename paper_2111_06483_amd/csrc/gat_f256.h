@@ -540,7 +540,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_f256(BwdTabs tabs, B
         }
         const int64_t jo = tabs.rank[q] ? tabs.rank[q][j] : j;
         store_lane<T, PAD>(static_cast<T*>(tabs.dZ[q]) + jo * ld, foff, on, v);
-        if (k == 0) tabs.dt[q][jo * ldh + h] = dt;
+        if (k == 0 && tabs.dt[q]) tabs.dt[q][jo * ldh + h] = dt;
     };
 
     for (int64_t r = blockIdx.x; r < a.n_long; r += gridDim.x) {
@@ -804,7 +804,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_few(BwdTabs tabs, Bw
                     dal[x] = fmaf(dt, zj[x], dal[x]);
                 }
                 store_lane<T, PAD>(static_cast<T*>(s_dZ[q[u]]) + (int64_t)jo[u] * ld, foff, on, v);
-                if (k == 0) s_dt[q[u]][(int64_t)jo[u] * ldh + h] = dt;
+                if (k == 0 && s_dt[q[u]]) s_dt[q[u]][(int64_t)jo[u] * ldh + h] = dt;
             }
         });
         m0 = m1;
@@ -952,7 +952,7 @@ __global__ __launch_bounds__(kGatherThreads) void k_gat_bwd_single(BwdTabs tabs,
             const float alpha = valid ? fast_exp2(leaky2(u2, a.slope) - rec.y) : 0.f;
             const float de = alpha * (c_mine - rec.z);
             const float du = u2 > 0.f ? de : a.slope * de;
-            if (valid) s_dt[my_q][(int64_t)my_row * ldh + h] = du;
+            if (valid && s_dt[my_q]) s_dt[my_q][(int64_t)my_row * ldh + h] = du;
             // ds_i += du: the entries of a destination follow each other, and a frequent destination
             // fills whole sub-batches: one atomic per run of slots that share the destination
             // (a running sum along the run, added by its last slot), not one per slot on one address

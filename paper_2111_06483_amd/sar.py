@@ -412,7 +412,8 @@ def sar_gat_bwd_begin(G: torch.Tensor, out: torch.Tensor, s: torch.Tensor, L: to
 
 def sar_gat_bwd_block(b: Blocks, q: int, Zq: torch.Tensor, G: torch.Tensor, tq: torch.Tensor,
                       rec: torch.Tensor, a_l: torch.Tensor, slope: float, dZq: torch.Tensor,
-                      dtq: torch.Tensor, ds: torch.Tensor, da_l: torch.Tensor, work: torch.Tensor) -> None:
+                      dtq: Optional[torch.Tensor], ds: torch.Tensor, da_l: torch.Tensor, work: torch.Tensor) -> None:
+    """dtq None: the per-source sums dt_q are not written (dZq and da_l contain them already)."""
     H, D = a_l.shape
     b.check_rows(q, Zq, tq)
     b.check_err_rows(q, dZq, dtq)
@@ -425,18 +426,20 @@ def sar_gat_bwd_block(b: Blocks, q: int, Zq: torch.Tensor, G: torch.Tensor, tq: 
 
 def sar_gat_bwd_all(b: Blocks, Zq: Sequence[torch.Tensor], G: torch.Tensor, tq: Sequence[torch.Tensor],
                     rec: torch.Tensor, a_l: torch.Tensor, slope: float, dZq: Sequence[torch.Tensor],
-                    dtq: Sequence[torch.Tensor], ds: torch.Tensor, da_l: torch.Tensor,
+                    dtq: Optional[Sequence[torch.Tensor]], ds: torch.Tensor, da_l: torch.Tensor,
                     work: torch.Tensor) -> None:
+    """dtq None: the per-source sums dt_q are not written (dZq and da_l contain them already)."""
     H, D = a_l.shape
     for q in range(b.P):
         b.check_rows(q, Zq[q], None if tq is None else tq[q])
-        b.check_err_rows(q, dZq[q], dtq[q])
+        b.check_err_rows(q, dZq[q], None if dtq is None else dtq[q])
     b.check_dst(G, rec, ds)
     _check(lib().sar_gat_bwd_all(b.handle, _ptr_array(Zq, "Zq", G.dtype, H * D), _ptr(G),
                                  None if tq is None else _ptr_array(tq, "tq", torch.float32, H),
                                  _ptr(rec), _ptr(a_l),
                                  _c_int(dtype_code(G.dtype)), _c_int(H), _c_int(D), ctypes.c_float(slope),
-                                 _ptr_array(dZq, "dZq", G.dtype, H * D), _ptr_array(dtq, "dtq", torch.float32, H),
+                                 _ptr_array(dZq, "dZq", G.dtype, H * D),
+                                 None if dtq is None else _ptr_array(dtq, "dtq", torch.float32, H),
                                  _ptr(ds), _ptr(da_l), _ptr(work),
                                  ctypes.c_size_t(work.numel() * work.element_size()), _stream()))
 

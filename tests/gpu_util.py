@@ -158,8 +158,9 @@ class GatGrads:
 
 
 def gat_bwd(b: sar.Blocks, Zdst, Zs, G, a_l, a_r, slope, fw: GatOut, batched: bool, fly=False,
-            dZadd=None, act=sar.SAR_ACT_NONE) -> GatGrads:
-    """With a non-linearity fw.out is h = act(aggregate) and G the error of h."""
+            dZadd=None, act=sar.SAR_ACT_NONE, store_dt=True) -> GatGrads:
+    """With a non-linearity fw.out is h = act(aggregate) and G the error of h.  store_dt False: the
+    calls are told not to write dt_q (GatGrads.dts is None)."""
     H, D = a_l.shape
     n = b.n_dst
     rec = torch.empty((n, H, 4), dtype=torch.float32, device=DEV)
@@ -175,13 +176,13 @@ def gat_bwd(b: sar.Blocks, Zdst, Zs, G, a_l, a_r, slope, fw: GatOut, batched: bo
     da_l = torch.zeros((H, D), dtype=torch.float32, device=DEV)
     da_r = torch.zeros((H, D), dtype=torch.float32, device=DEV)
     dZs = [torch.full(Z.shape, float("nan"), dtype=Z.dtype, device=DEV) for Z in Zs]
-    dts = [torch.full((Z.shape[0], H), float("nan"), dtype=torch.float32, device=DEV) for Z in Zs]
+    dts = [torch.full((Z.shape[0], H), float("nan"), dtype=torch.float32, device=DEV) for Z in Zs] if store_dt else None
     if batched:
         sar.sar_gat_bwd_all(b, Zs, G, None if fly else fw.t, rec, a_l, slope, dZs, dts, ds, da_l, work)
     else:
         for q in range(b.P):
-            sar.sar_gat_bwd_block(b, q, Zs[q], G, None if fly else fw.t[q], rec, a_l, slope, dZs[q], dts[q], ds,
-                                  da_l, work)
+            sar.sar_gat_bwd_block(b, q, Zs[q], G, None if fly else fw.t[q], rec, a_l, slope, dZs[q],
+                                  dts[q] if store_dt else None, ds, da_l, work)
     dZdst = torch.full(Zdst.shape, float("nan"), dtype=Zdst.dtype, device=DEV)
     sar.sar_gat_bwd_end(Zdst, ds, a_r, dZadd, dZdst, da_r, work)
     return GatGrads(dZs, dts, ds, dZdst, da_l, da_r)

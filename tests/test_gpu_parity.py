@@ -266,6 +266,53 @@ def test_gat_backward_parity(dtype, H, D, batched, fly):
     b.close()
 
 
+@pytest.mark.parametrize("dtype,H,D", [(torch.float32, 4, 64), (torch.bfloat16, 8, 32), (torch.float32, 2, 100),
+                                       (torch.bfloat16, 4, 32), (torch.float32, 3, 10), (torch.bfloat16, 5, 40)])
+@pytest.mark.parametrize("batched", [False, True])
+@pytest.mark.parametrize("full_height", [False, True])
+def test_backward_without_the_dt_output(dtype, H, D, batched, full_height):
+    """dt_q is an intermediate of the backward kernels; a call that does not ask for it (dtq NULL) gives
+    the same dZ_q and da_l bit for bit (neither involves an atomic) and the same ds up to the order
+    of its atomic sums.  Full-height handles also write the zero rows of the sources without an edge."""
+    src, dst, part, rng = make_graph(23, 3000, 9000, 3, empty_block=None)
+    flags = sar.SAR_BUILD_TRANSPOSE | sar.SAR_BUILD_FUSED | (0 if full_height else sar.SAR_BUILD_COMPACT)
+    want_b, _ = orc.build_blocks(src, dst, part, 3, 1)
+    b = gu.build_blocks(src, dst, part, 3, 1, flags=flags)
+    rows = [w.n_src if full_height else int(np.count_nonzero(np.diff(w.t_indptr))) for w in want_b]
+    F = H * D
+    Zs = [feats(rng, w.n_src, F, dtype).cuda().reshape(-1, H, D) for w in want_b]
+    Zdst = Zs[1]
+    bound = np.sqrt(6.0 / (D + 1))
+    a_l = torch.from_numpy(rng.uniform(-bound, bound, (H, D)).astype(np.float32)).cuda()
+    a_r = torch.from_numpy(rng.uniform(-bound, bound, (H, D)).astype(np.float32)).cuda()
+    G = feats(rng, b.n_dst, F, dtype).cuda().reshape(-1, H, D)
+    fw = gu.gat_fwd_all(b, Zdst, Zs, a_l, a_r, SLOPE, fly=True)
+    n = b.n_dst
+    work = torch.empty(sar.sar_gat_workspace_bytes(n, 0, H, D) // 4, dtype=torch.float32, device="cuda")
+    res = []
+    for store_dt in (True, False):
+        rec = torch.empty((n, H, 4), dtype=torch.float32, device="cuda")
+        ds = torch.empty((n, H), dtype=torch.float32, device="cuda")
+        sar.sar_gat_bwd_begin(G, fw.out, fw.s, fw.L, rec, ds)
+        da_l = torch.zeros((H, D), dtype=torch.float32, device="cuda")
+        dZs = [torch.full((r, H, D), float("nan"), dtype=dtype, device="cuda") for r in rows]
+        dts = [torch.full((r, H), float("nan"), dtype=torch.float32, device="cuda") for r in rows] if store_dt else None
+        if batched:
+            sar.sar_gat_bwd_all(b, Zs, G, None, rec, a_l, SLOPE, dZs, dts, ds, da_l, work)
+        else:
+            for q in range(3):
+                sar.sar_gat_bwd_block(b, q, Zs[q], G, None, rec, a_l, SLOPE, dZs[q], dts[q] if store_dt else None,
+                                      ds, da_l, work)
+        res.append((dZs, dts, ds, da_l))
+    (dZ1, dt1, ds1, da1), (dZ0, _, ds0, da0) = res
+    for q in range(3):
+        assert not torch.isnan(dZ0[q].float()).any() and not torch.isnan(dt1[q]).any()
+        assert torch.equal(dZ0[q], dZ1[q]), q
+    assert torch.equal(da0, da1)
+    assert rel_err(f64(ds0), f64(ds1)) < 1e-5
+    b.close()
+
+
 @pytest.mark.parametrize("dtype,H,D", [(torch.float32, 4, 64), (torch.bfloat16, 8, 32), (torch.float32, 16, 16),
                                        (torch.bfloat16, 1, 256), (torch.float32, 2, 128)])
 @pytest.mark.parametrize("n_src,degs", [(1, (3,)), (5, (1,)), (6, (7,)), (203, (1, 2, 3, 4, 5, 6, 7)), (66, (2, 7)),

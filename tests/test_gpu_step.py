@@ -159,7 +159,8 @@ def check_step(name, scale, modes):
     P, p, H, D = w.P, w.p, w.H, w.D
     o = OracleStep(w)
     n = o.blocks[0].n_dst
-    layer = bench.Layer(w, torch, sar, synth)          # bench.py's defaults: compact errors E_{p->q}
+    layer = bench.Layer(w, torch, sar, synth, store_dt=True)   # bench.py's defaults: compact errors E_{p->q}
+    all_dts = layer.dts
     assert layer.n == n and layer.E == sum(b.nnz for b in o.blocks) and layer.compact
     touched = [np.flatnonzero(np.diff(b.t_indptr) > 0) for b in o.blocks]
 
@@ -183,7 +184,9 @@ def check_step(name, scale, modes):
         # bench.py's default forms the rows of E_p inside Z_p.backward's two products; its
         # --stored-error writes E_p out first.  One launch mode takes each, so both are held here.
         layer.stored_error = mode == "stream"
-        for t in (layer.out, layer.L, layer.dX_dst, layer.ds, *layer.dZs, *layer.dts):
+        # likewise dt_q: bench.py's default leaves this intermediate unwritten, --store-dt writes it
+        layer.dts = all_dts if mode == "stream" else None
+        for t in (layer.out, layer.L, layer.dX_dst, layer.ds, *layer.dZs, *all_dts):
             t.fill_(float("nan"))
         if layer.dZdst is not None:
             layer.dZdst.fill_(float("nan"))
@@ -218,7 +221,10 @@ def check_step(name, scale, modes):
             dZ, dZw = f64(layer.dZs[q]), o.bwd.dZs[q][tq]
             assert rel_err(dZ[ok], dZw[ok]) < tol, (tag, q)
             assert row_rel_err(np.where(ok[:, :, None], dZ, 0), np.where(ok[:, :, None], dZw, 0)) < tol, (tag, q)
-            assert rel_err(f64(layer.dts[q])[ok], o.bwd.dt[q][tq][ok]) < tol, (tag, q)
+            if layer.dts is not None:
+                assert rel_err(f64(layer.dts[q])[ok], o.bwd.dt[q][tq][ok]) < tol, (tag, q)
+            else:
+                assert torch.isnan(all_dts[q]).all(), (tag, q)      # not asked for, not touched
         if layer.stored_error:
             Ep = f64(layer.dZdst)
             assert rel_err(Ep[~bad_own], o.E_p[~bad_own]) < tol, tag
