@@ -467,6 +467,19 @@ def time_gat(args, torch, sar, synth, name, steps, warmup, full_report):
     ms_step = wall * 1e3 / steps
     avg = lambda a, b: sum(e[a].elapsed_time(e[b]) for e in evs) / len(evs)
     fwd_ms, bwd_ms, all_ms = avg("fwd0", "fwd1"), avg("bwd0", "bwd1"), avg("t0", "t1")
+    # the same step with the intermediate dt_q written out as well (for comparison; not the headline)
+    with_dt_ms = None
+    if layer.dts is None:
+        f32 = dict(dtype=torch.float32, device="cuda")
+        layer.dts = [torch.zeros((dz.shape[0], layer.H), **f32) for dz in layer.dZs]
+        layer.step(args.mode)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            layer.step(args.mode)
+        torch.cuda.synchronize()
+        with_dt_ms = (time.perf_counter() - t0) * 1e3 / steps
+        layer.dts = None
     graph_ms = None
     if args.graph:
         # the library only enqueues work on the stream it is given, so the step can be recorded once
@@ -526,6 +539,7 @@ def time_gat(args, torch, sar, synth, name, steps, warmup, full_report):
         "builder_s": layer.builder_s,
         **({"subset_builder_s": layer.subset_s} if layer.subset else {}),
         **({"graph_replay_ms_per_step": graph_ms} if graph_ms is not None else {}),
+        **({"ms_per_step_with_dt_q_written": with_dt_ms} if with_dt_ms is not None else {}),
     }
     return res, layer, w
 
@@ -743,6 +757,8 @@ def main():
         "builder_s": r["builder_s"],
         **({"subset_builder_s": r["subset_builder_s"]} if "subset_builder_s" in r else {}),
         **({"graph_replay_ms_per_step": r["graph_replay_ms_per_step"]} if "graph_replay_ms_per_step" in r else {}),
+        **({"ms_per_step_with_dt_q_written": r["ms_per_step_with_dt_q_written"]}
+           if "ms_per_step_with_dt_q_written" in r else {}),
         "roofline": {"bound": "hbm", "kernel": d["kernel"],
                      "achieved": d["alg_GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": d["frac"],
